@@ -1,0 +1,146 @@
+"""fp64 CPU oracle for the diagonal linear-recurrence scan -- TEST INFRASTRUCTURE ONLY.
+
+This package wraps ``lrnnx_oracle.c`` (plain sequential C, fp64) with ctypes and
+numpy.  It states what the paper's Eq. 2 (Sec. 2.2) computes for a diagonal
+state matrix under the discretisations named in Sec. 3; see the C file's header
+for the formulas, the layouts and the list of pins.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import it.  It imports nothing from the HIP package and the
+HIP package imports nothing from here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lrnnx_oracle.c")
+_LIB = os.path.join(_HERE, "liblrnnx_oracle.so")
+
+DISC = {"zoh_s6": 0, "zoh": 1, "bilinear": 2, "dirac": 3}
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (-O2, OpenMP, no fast-math). Returns the .so path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.lrnnx_oracle_softplus.restype = ctypes.c_double
+        _lib.lrnnx_oracle_softplus.argtypes = [ctypes.c_double]
+        _lib.lrnnx_oracle_disc.restype = None
+        _lib.lrnnx_oracle_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a):
+    """double* of a contiguous float64 array, or NULL."""
+    if a is None:
+        return ctypes.c_void_p(0)
+    assert a.dtype == np.float64 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f64(a):
+    return None if a is None else np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def _c128(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.complex128))
+
+
+def num_threads() -> int:
+    return int(_load().lrnnx_oracle_num_threads())
+
+
+def softplus(s: float) -> float:
+    return float(_load().lrnnx_oracle_softplus(float(s)))
+
+
+def disc_terms(disc, dt: float, A: float):
+    """(a, g, da/ddt, da/dA, dg/ddt, dg/dA) of one discretisation at (dt, A)."""
+    out = (ctypes.c_double * 6)()
+    _load().lrnnx_oracle_disc(ctypes.c_int(_disc(disc)), ctypes.c_double(dt), ctypes.c_double(A), out)
+    return tuple(out)
+
+
+def _disc(disc) -> int:
+    return DISC[disc] if isinstance(disc, str) else int(disc)
+
+
+def selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, x0=None,
+                       disc="zoh_s6", delta_softplus=True, return_states=False):
+    """y [B,D,L], x_last [B,D,N] (and every state [B,D,L,N] if asked) of Eq. 2 with diagonal A(k)."""
+    u, delta, A, Bm, Cm = map(_f64, (u, delta, A, Bm, Cm))
+    Dskip, delta_bias, z, x0 = map(_f64, (Dskip, delta_bias, z, x0))
+    Bsz, D, L = u.shape
+    N = A.shape[1]
+    assert delta.shape == (Bsz, D, L) and A.shape == (D, N)
+    assert Bm.shape == (Bsz, L, N) and Cm.shape == (Bsz, L, N)
+    y = np.empty((Bsz, D, L))
+    x_last = np.empty((Bsz, D, N))
+    xs = np.empty((Bsz, D, L, N)) if return_states else None
+    rc = _load().lrnnx_oracle_selective_scan_fwd(
+        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_long(L),
+        ctypes.c_int(_disc(disc)), ctypes.c_int(int(bool(delta_softplus))),
+        _p(u), _p(delta), _p(A), _p(Bm), _p(Cm), _p(Dskip), _p(delta_bias), _p(z), _p(x0),
+        _p(y), _p(x_last), _p(xs))
+    if rc != 0:
+        raise ValueError(f"oracle fwd: bad arguments (rc={rc})")
+    return (y, x_last, xs) if return_states else (y, x_last)
+
+
+def selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,
+                       disc="zoh_s6", delta_softplus=True):
+    """Gradients of sum(dy * y) w.r.t. every input, as a dict of float64 arrays."""
+    u, delta, A, Bm, Cm, dy = map(_f64, (u, delta, A, Bm, Cm, dy))
+    Dskip, delta_bias, z, x0 = map(_f64, (Dskip, delta_bias, z, x0))
+    Bsz, D, L = u.shape
+    N = A.shape[1]
+    out = {
+        "du": np.empty((Bsz, D, L)), "ddelta": np.empty((Bsz, D, L)),
+        "dA": np.empty((D, N)), "dBm": np.empty((Bsz, L, N)), "dCm": np.empty((Bsz, L, N)),
+        "dD": np.empty(D) if Dskip is not None else None,
+        "dbias": np.empty(D) if delta_bias is not None else None,
+        "dz": np.empty((Bsz, D, L)) if z is not None else None,
+        "dx0": np.empty((Bsz, D, N)),
+    }
+    rc = _load().lrnnx_oracle_selective_scan_bwd(
+        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_long(L),
+        ctypes.c_int(_disc(disc)), ctypes.c_int(int(bool(delta_softplus))),
+        _p(u), _p(delta), _p(A), _p(Bm), _p(Cm), _p(Dskip), _p(delta_bias), _p(z), _p(x0), _p(dy),
+        _p(out["du"]), _p(out["ddelta"]), _p(out["dA"]), _p(out["dBm"]), _p(out["dCm"]),
+        _p(out["dD"]), _p(out["dbias"]), _p(out["dz"]), _p(out["dx0"]))
+    if rc != 0:
+        raise ValueError(f"oracle bwd: bad arguments (rc={rc})")
+    return out
+
+
+def lti_diag_scan(lam, v, x0=None):
+    """x [B,L,P] complex128 of x_k = lam * x_{k-1} + v_k (S5/LRU recurrence, Sec. 2.2.1)."""
+    lam, v = _c128(lam), _c128(v)
+    Bsz, L, P = v.shape
+    assert lam.shape == (P,)
+    x0c = None if x0 is None else _c128(x0)
+    x = np.empty((Bsz, L, P), dtype=np.complex128)
+    rc = _load().lrnnx_oracle_lti_diag_scan(
+        ctypes.c_int(Bsz), ctypes.c_long(L), ctypes.c_int(P),
+        lam.ctypes.data_as(ctypes.c_void_p), v.ctypes.data_as(ctypes.c_void_p),
+        ctypes.c_void_p(0) if x0c is None else x0c.ctypes.data_as(ctypes.c_void_p),
+        x.ctypes.data_as(ctypes.c_void_p))
+    if rc != 0:
+        raise ValueError(f"oracle lti: bad arguments (rc={rc})")
+    return x

@@ -1,0 +1,269 @@
+/*
+ * lrnnx_oracle.c -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+ *
+ * Plain sequential fp64 CPU statement of the diagonal linear recurrence of the
+ * lrnnx paper (Sec. 2.2 "Linear RNNs", Eq. 2):
+ *
+ *     x_k = A(k) x_{k-1} + B(k) u_k
+ *     y_k = C(k) x_k     + D(k) u_k
+ *
+ * specialised to a diagonal A(k), as used by the time-varying S6 layer and the
+ * time-invariant complex-diagonal S5/LRU layers the paper lists (Sec. 2.2.1,
+ * 2.2.2, Table 1).  The paper names the discretisation schemes (Sec. 3:
+ * "ZOH, bilinear, dirac") without printing their formulas; the standard
+ * diagonal forms are written out in disc_eval() below.
+ *
+ * Only tests/, __graft_entry__.smoke() and the cpu_baseline leg of bench.py
+ * may use this file.  It shares no code with the HIP library and is never on
+ * the product path.  Rows (b,d) are independent recurrences, so the outer row
+ * loop carries an OpenMP pragma; nothing else is blocked, fused or reordered.
+ *
+ * Parity pins (tests/test_oracle_pins.py): brute-force unrolled sum, LTI
+ * convolution closed form, impulse response, scipy.signal.lfilter and
+ * cont2discrete, exact-ZOH step response, central finite differences, adjoint
+ * dot test, linearity / causality / chaining invariants.
+ * Parity unpinned: which of the two "ZOH" input maps (disc 0 or 1) the
+ * paper's own "zoh" string selects; the paper's asynchronous scheme is read
+ * as "the caller supplies Delta per step" (delta_softplus = 0).
+ *
+ * Layouts (all contiguous, all double):
+ *   u, delta, z, y, dy, du, ddelta, dz : [B, D, L]
+ *   A, dA                               : [D, N]
+ *   Bm, Cm, dBm, dCm                    : [B, L, N]   (shared by all channels)
+ *   Dskip, delta_bias, dD, dbias        : [D]
+ *   x0, x_last, dx0                     : [B, D, N]
+ *   xs (optional dump of every state)   : [B, D, L, N]
+ *   LTI: lambda [P], v, x [B, L, P], x0 [B, P] -- complex, (re, im) pairs
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { DISC_ZOH_S6 = 0, DISC_ZOH = 1, DISC_BILINEAR = 2, DISC_DIRAC = 3 };
+
+/* Discretisation of the scalar continuous system x' = A x + B u with step dt
+ * (Sec. 3 names the schemes).  Returns the state multiplier a and the input
+ * gain g (so that Bbar = g * B), and their partial derivatives.
+ *   ZOH_S6   : a = exp(dt A), g = dt            (S6 simplification of ZOH)
+ *   ZOH      : a = exp(dt A), g = (a - 1) / A   (exact zero-order hold)
+ *   BILINEAR : a = (1 + dt A/2)/(1 - dt A/2), g = dt/(1 - dt A/2)
+ *   DIRAC    : a = exp(dt A), g = 1             (impulse input, B unchanged)
+ */
+static void disc_eval(int disc, double dt, double A, double *a, double *g,
+                      double *da_ddt, double *da_dA, double *dg_ddt, double *dg_dA)
+{
+    double aa, gg, a_t, a_A, g_t, g_A;
+    if (disc == DISC_BILINEAR) {
+        double q = 1.0 / (1.0 - 0.5 * dt * A);
+        aa = (1.0 + 0.5 * dt * A) * q;
+        gg = dt * q;
+        a_t = A * q * q;
+        a_A = dt * q * q;
+        g_t = q * q;
+        g_A = 0.5 * dt * dt * q * q;
+    } else {
+        aa = exp(dt * A);
+        a_t = A * aa;
+        a_A = dt * aa;
+        if (disc == DISC_ZOH_S6) {
+            gg = dt; g_t = 1.0; g_A = 0.0;
+        } else if (disc == DISC_ZOH) {
+            double em1 = expm1(dt * A);
+            if (A == 0.0) { gg = dt; g_t = 1.0; g_A = 0.5 * dt * dt; }
+            else {
+                gg = em1 / A;
+                g_t = aa;
+                g_A = (dt * A * aa - em1) / (A * A);
+            }
+        } else { /* DISC_DIRAC */
+            gg = 1.0; g_t = 0.0; g_A = 0.0;
+        }
+    }
+    *a = aa; *g = gg;
+    if (da_ddt) { *da_ddt = a_t; *da_dA = a_A; *dg_ddt = g_t; *dg_dA = g_A; }
+}
+
+/* softplus(s) = log(1 + e^s), written so that neither branch overflows. */
+static double softplus(double s) { return fmax(s, 0.0) + log1p(exp(-fabs(s))); }
+static double sigmoid(double s)  { return s >= 0 ? 1.0 / (1.0 + exp(-s)) : exp(s) / (1.0 + exp(s)); }
+
+int lrnnx_oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Expose the scalar pieces so the tests can pin them one by one. */
+void lrnnx_oracle_disc(int disc, double dt, double A, double *out6)
+{
+    disc_eval(disc, dt, A, &out6[0], &out6[1], &out6[2], &out6[3], &out6[4], &out6[5]);
+}
+double lrnnx_oracle_softplus(double s) { return softplus(s); }
+
+/* Forward selective scan (Eq. 2 with diagonal, input-dependent A(k), B(k), C(k)).
+ * Optional pointers may be NULL: Dskip, delta_bias, z, x0, x_last, xs.        */
+int lrnnx_oracle_selective_scan_fwd(
+    int B, int D, int N, long L, int disc, int delta_softplus,
+    const double *u, const double *delta, const double *A,
+    const double *Bm, const double *Cm, const double *Dskip,
+    const double *delta_bias, const double *z, const double *x0,
+    double *y, double *x_last, double *xs)
+{
+    if (B < 0 || D < 0 || N < 1 || L < 0 || disc < 0 || disc > 3) return 1;
+    long rows = (long)B * D;
+#pragma omp parallel for schedule(static)
+    for (long row = 0; row < rows; ++row) {
+        int b = (int)(row / D), d = (int)(row % D);
+        double *x = (double *)malloc(sizeof(double) * N);
+        for (int n = 0; n < N; ++n) x[n] = x0 ? x0[row * N + n] : 0.0;
+        for (long l = 0; l < L; ++l) {
+            double s = delta[row * L + l] + (delta_bias ? delta_bias[d] : 0.0);
+            double dt = delta_softplus ? softplus(s) : s;
+            double uu = u[row * L + l];
+            double acc = 0.0;
+            for (int n = 0; n < N; ++n) {
+                double a, g;
+                disc_eval(disc, dt, A[(long)d * N + n], &a, &g, 0, 0, 0, 0);
+                x[n] = a * x[n] + g * Bm[((long)b * L + l) * N + n] * uu;   /* Eq. 2, line 1 */
+                acc += Cm[((long)b * L + l) * N + n] * x[n];                /* Eq. 2, line 2 */
+                if (xs) xs[(row * L + l) * N + n] = x[n];
+            }
+            double ypre = acc + (Dskip ? Dskip[d] * uu : 0.0);
+            if (z) { double zz = z[row * L + l]; ypre *= zz * sigmoid(zz); }
+            y[row * L + l] = ypre;
+        }
+        if (x_last) for (int n = 0; n < N; ++n) x_last[row * N + n] = x[n];
+        free(x);
+    }
+    return 0;
+}
+
+/* Reverse-mode derivative of the forward above for a given upstream dy.
+ * Every state of a row is kept (L*N doubles) -- the oracle stores what the
+ * GPU path recomputes.  Outputs dA, dD, dbias, dBm, dCm are overwritten.
+ * Optional (may be NULL): Dskip, delta_bias, z, x0, dD, dbias, dz, dx0.       */
+int lrnnx_oracle_selective_scan_bwd(
+    int B, int D, int N, long L, int disc, int delta_softplus,
+    const double *u, const double *delta, const double *A,
+    const double *Bm, const double *Cm, const double *Dskip,
+    const double *delta_bias, const double *z, const double *x0,
+    const double *dy,
+    double *du, double *ddelta, double *dA, double *dBm, double *dCm,
+    double *dD, double *dbias, double *dz, double *dx0)
+{
+    if (B < 0 || D < 0 || N < 1 || L < 0 || disc < 0 || disc > 3) return 1;
+    long nBC = (long)B * L * N;
+    memset(dA, 0, sizeof(double) * (size_t)D * N);
+    memset(dBm, 0, sizeof(double) * (size_t)nBC);
+    memset(dCm, 0, sizeof(double) * (size_t)nBC);
+    if (dD) memset(dD, 0, sizeof(double) * (size_t)D);
+    if (dbias) memset(dbias, 0, sizeof(double) * (size_t)D);
+
+    int nthreads = lrnnx_oracle_num_threads();
+    /* dBm, dCm sum over channels: one private copy per thread, added up at the end. */
+    double *privB = (double *)calloc((size_t)nthreads * nBC, sizeof(double));
+    double *privC = (double *)calloc((size_t)nthreads * nBC, sizeof(double));
+    if (!privB || !privC) { free(privB); free(privC); return 2; }
+
+#pragma omp parallel for schedule(static)
+    for (int d = 0; d < D; ++d) {           /* dA, dD, dbias are per channel: no race */
+#ifdef _OPENMP
+        int tid = omp_get_thread_num();
+#else
+        int tid = 0;
+#endif
+        double *pB = privB + (size_t)tid * nBC, *pC = privC + (size_t)tid * nBC;
+        double *xs = (double *)malloc(sizeof(double) * (size_t)(L + 1) * N); /* xs[(l+1)*N+n] = x_l, xs[n] = x_{-1} */
+        double *h = (double *)malloc(sizeof(double) * N);
+        for (int b = 0; b < B; ++b) {
+            long row = (long)b * D + d;
+            for (int n = 0; n < N; ++n) xs[n] = x0 ? x0[row * N + n] : 0.0;
+            for (long l = 0; l < L; ++l) {                      /* forward sweep, states kept */
+                double s = delta[row * L + l] + (delta_bias ? delta_bias[d] : 0.0);
+                double dt = delta_softplus ? softplus(s) : s;
+                double uu = u[row * L + l];
+                for (int n = 0; n < N; ++n) {
+                    double a, g;
+                    disc_eval(disc, dt, A[(long)d * N + n], &a, &g, 0, 0, 0, 0);
+                    xs[(l + 1) * N + n] = a * xs[l * N + n] + g * Bm[((long)b * L + l) * N + n] * uu;
+                }
+            }
+            for (int n = 0; n < N; ++n) h[n] = 0.0;            /* h[n] = a_{l+1} * (dLoss/dx_{l+1}), zero past the end */
+            for (long l = L - 1; l >= 0; --l) {                 /* reverse sweep */
+                double s = delta[row * L + l] + (delta_bias ? delta_bias[d] : 0.0);
+                double dt = delta_softplus ? softplus(s) : s;
+                double uu = u[row * L + l];
+                double acc = 0.0;
+                for (int n = 0; n < N; ++n) acc += Cm[((long)b * L + l) * N + n] * xs[(l + 1) * N + n];
+                double ypre = acc + (Dskip ? Dskip[d] * uu : 0.0);
+                double dypre = dy[row * L + l];
+                if (z) {
+                    double zz = z[row * L + l], sg = sigmoid(zz);
+                    if (dz) dz[row * L + l] = dypre * ypre * sg * (1.0 + zz * (1.0 - sg));
+                    dypre *= zz * sg;
+                }
+                if (dD && Dskip) dD[d] += dypre * uu;
+                double du_l = Dskip ? dypre * Dskip[d] : 0.0;
+                double ddt = 0.0;
+                for (int n = 0; n < N; ++n) {
+                    long bc = ((long)b * L + l) * N + n;
+                    double a, g, a_t, a_A, g_t, g_A;
+                    disc_eval(disc, dt, A[(long)d * N + n], &a, &g, &a_t, &a_A, &g_t, &g_A);
+                    double hx = Cm[bc] * dypre + h[n];           /* dLoss/dx_l */
+                    pC[bc] += dypre * xs[(l + 1) * N + n];
+                    double da = hx * xs[l * N + n];              /* x_l = a x_{l-1} + g Bm u */
+                    double dg = hx * Bm[bc] * uu;
+                    pB[bc] += hx * g * uu;
+                    du_l += hx * g * Bm[bc];
+                    ddt += da * a_t + dg * g_t;
+                    dA[(long)d * N + n] += da * a_A + dg * g_A;
+                    h[n] = a * hx;
+                }
+                double ds = delta_softplus ? ddt * sigmoid(s) : ddt;   /* d softplus / ds = sigmoid */
+                ddelta[row * L + l] = ds;
+                if (dbias && delta_bias) dbias[d] += ds;
+                du[row * L + l] = du_l;
+            }
+            if (dx0) for (int n = 0; n < N; ++n) dx0[row * N + n] = h[n];
+        }
+        free(xs); free(h);
+    }
+    for (int t = 0; t < nthreads; ++t)
+        for (long i = 0; i < nBC; ++i) {
+            dBm[i] += privB[(size_t)t * nBC + i];
+            dCm[i] += privC[(size_t)t * nBC + i];
+        }
+    free(privB); free(privC);
+    return 0;
+}
+
+/* Time-invariant complex-diagonal recurrence (S5 / LRU, Sec. 2.2.1):
+ *     x_k = lambda (.) x_{k-1} + v_k,   v_k = Bbar u_k supplied by the caller.
+ * Complex numbers are (re, im) pairs of doubles.  x0 may be NULL (zero).      */
+int lrnnx_oracle_lti_diag_scan(int B, long L, int P,
+                               const double *lambda, const double *v,
+                               const double *x0, double *x)
+{
+    if (B < 0 || L < 0 || P < 0) return 1;
+    long rows = (long)B * P;
+#pragma omp parallel for schedule(static)
+    for (long row = 0; row < rows; ++row) {
+        int b = (int)(row / P), p = (int)(row % P);
+        double lr = lambda[2 * p], li = lambda[2 * p + 1];
+        double xr = x0 ? x0[2 * row] : 0.0, xi = x0 ? x0[2 * row + 1] : 0.0;
+        for (long k = 0; k < L; ++k) {
+            long idx = 2 * (((long)b * L + k) * P + p);
+            double nr = lr * xr - li * xi + v[idx];
+            double ni = lr * xi + li * xr + v[idx + 1];
+            xr = nr; xi = ni;
+            x[idx] = xr; x[idx + 1] = xi;
+        }
+    }
+    return 0;
+}

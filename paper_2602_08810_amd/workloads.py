@@ -1,0 +1,96 @@
+"""Seeded synthetic inputs for the five benchmark configurations.
+
+This module holds no scan arithmetic: it only draws random tensors with the
+shapes and distributions of the Mamba / LRU-shaped workloads (the paper
+benchmarks on random tensors, Sec. 4.2) and rounds them once to the I/O dtype,
+so that the CPU oracle and the HIP library consume identical bits.  It is the
+only module both sides import.
+
+All arrays are numpy.  Values of a bf16 configuration are returned as float32
+arrays that are exactly representable in bf16 (round-to-nearest-even applied
+here), so ``torch.from_numpy(a).to(torch.bfloat16)`` is lossless.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# name -> description of BASELINE configs 0..4
+CONFIGS = {
+    "c0": dict(kind="selective", B=1, D=16, N=4, L=256, io="f32", gate=False,
+               bias=("const", -2.0), seed=0),
+    "c1": dict(kind="lti", B=4, P=256, L=4096, seed=1),
+    "c2": dict(kind="selective", B=8, D=1536, N=16, L=2048, io="bf16", gate=True,
+               bias=("uniform", -4.0, -2.0), seed=2),
+    "c3": dict(kind="selective", B=1, D=2048, N=16, L=65536, io="bf16", gate=False,
+               bias=("uniform", -4.0, -2.0), seed=3),
+    "c4": dict(kind="selective", B=16, D=2560, N=16, L=4096, io="bf16", gate=True,
+               bias=("uniform", -4.0, -2.0), seed=4),
+}
+
+
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """float32 -> nearest bf16 (ties to even), returned as float32."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    bits = x.view(np.uint32)
+    rounded = (bits + (((bits >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF))) & np.uint32(0xFFFF0000)
+    return rounded.view(np.float32)
+
+
+def _io_round(x: np.ndarray, io: str) -> np.ndarray:
+    return round_to_bf16(x) if io == "bf16" else np.ascontiguousarray(x, dtype=np.float32)
+
+
+def make_selective(B, D, N, L, io="f32", gate=False, bias=("const", -2.0), seed=0,
+                   with_dy=True, with_x0=False, **_unused):
+    """Inputs of the selective scan.
+
+    A[d,n] = -exp(U(-1,1)); delta ~ N(0,1) (raw, pre-bias, pre-softplus);
+    delta_bias constant or U(lo,hi) per channel; Bm, Cm ~ N(0,1) [B,L,N] shared
+    by all channels; u, Dskip, z, dy ~ N(0,1).
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    f32 = np.float32
+    out = {}
+    out["A"] = (-np.exp(rng.uniform(-1.0, 1.0, size=(D, N)))).astype(f32)
+    out["Dskip"] = rng.standard_normal(D, dtype=f32)
+    if bias is None:
+        out["delta_bias"] = None
+    elif bias[0] == "const":
+        out["delta_bias"] = np.full(D, bias[1], dtype=f32)
+    else:
+        out["delta_bias"] = rng.uniform(bias[1], bias[2], size=D).astype(f32)
+    out["Bm"] = _io_round(rng.standard_normal((B, L, N), dtype=f32), io)
+    out["Cm"] = _io_round(rng.standard_normal((B, L, N), dtype=f32), io)
+    out["u"] = _io_round(rng.standard_normal((B, D, L), dtype=f32), io)
+    out["delta"] = _io_round(rng.standard_normal((B, D, L), dtype=f32), io)
+    out["z"] = _io_round(rng.standard_normal((B, D, L), dtype=f32), io) if gate else None
+    out["dy"] = _io_round(rng.standard_normal((B, D, L), dtype=f32), io) if with_dy else None
+    out["x0"] = rng.standard_normal((B, D, N), dtype=f32) if with_x0 else None
+    return out
+
+
+def make_lti(B, P, L, seed=1, with_x0=False, **_unused):
+    """Inputs of the LTI complex-diagonal scan.
+
+    lambda = r e^{i theta}, r ~ U(0.9, 0.999), theta ~ U(0, 2 pi);
+    v = (N(0,1) + i N(0,1)) / sqrt(2), complex64 [B,L,P].
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    r = rng.uniform(0.9, 0.999, size=P)
+    th = rng.uniform(0.0, 2.0 * np.pi, size=P)
+    lam = (r * np.exp(1j * th)).astype(np.complex64)
+    v = np.empty((B, L, P), dtype=np.complex64)
+    s = np.float32(1.0 / np.sqrt(2.0))
+    v.real = rng.standard_normal((B, L, P), dtype=np.float32) * s
+    v.imag = rng.standard_normal((B, L, P), dtype=np.float32) * s
+    x0 = None
+    if with_x0:
+        x0 = (rng.standard_normal((B, P)) + 1j * rng.standard_normal((B, P))).astype(np.complex64)
+    return {"lam": lam, "v": v, "x0": x0}
+
+
+def make(name: str, **overrides):
+    """Inputs of BASELINE configuration ``name`` ("c0".."c4"), optionally with fields overridden."""
+    cfg = dict(CONFIGS[name])
+    cfg.update(overrides)
+    return (make_lti if cfg["kind"] == "lti" else make_selective)(**cfg), cfg

@@ -1,0 +1,281 @@
+"""Pins for the fp64 CPU oracle: it is checked against things other than itself.
+
+The paper prints no worked numeric example (its results are figures), so the
+oracle is pinned to what the mathematics of Eq. 2 (Sec. 2.2) and of the
+discretisations named in Sec. 3 fixes: brute-force unrolled sums, the LTI
+convolution closed form, impulse responses, SciPy's lfilter and cont2discrete,
+the textbook exactness of zero-order hold on a step input, central finite
+differences, the adjoint dot test, and structural invariants.
+"""
+import numpy as np
+import pytest
+import scipy.signal
+
+DISCS = ["zoh_s6", "zoh", "bilinear", "dirac"]
+
+
+def _rand_problem(rng, B=2, D=3, N=4, L=9, gate=True, bias=True, x0=True, skip=True):
+    p = dict(
+        u=rng.standard_normal((B, D, L)),
+        delta=rng.standard_normal((B, D, L)),
+        A=-np.exp(rng.uniform(-1, 1, (D, N))),
+        Bm=rng.standard_normal((B, L, N)),
+        Cm=rng.standard_normal((B, L, N)),
+        Dskip=rng.standard_normal(D) if skip else None,
+        delta_bias=rng.uniform(-2, 0, D) if bias else None,
+        z=rng.standard_normal((B, D, L)) if gate else None,
+        x0=rng.standard_normal((B, D, N)) if x0 else None,
+    )
+    return p
+
+
+def _disc_py(disc, dt, A):
+    """Independent restatement of the four schemes with numpy scalars (pinned itself by cont2discrete below)."""
+    if disc == "bilinear":
+        return (1 + dt * A / 2) / (1 - dt * A / 2), dt / (1 - dt * A / 2)
+    a = np.exp(dt * A)
+    return a, {"zoh_s6": dt, "zoh": (a - 1) / A, "dirac": 1.0}[disc]
+
+
+# ----------------------------------------------------------------------------- scalar pieces
+
+@pytest.mark.parametrize("s", [-40.0, -6.0, -1.0, 0.0, 0.3, 5.0, 30.0, 800.0])
+def test_softplus_matches_logaddexp(oracle, s):
+    assert oracle.softplus(s) == pytest.approx(np.logaddexp(0.0, s), rel=1e-14, abs=1e-300)
+
+
+@pytest.mark.parametrize("dt,A", [(0.05, -1.3), (0.7, -0.4), (1e-3, -2.5)])
+def test_zoh_and_bilinear_match_scipy_cont2discrete(oracle, dt, A):
+    """Ad, Bd of the scalar system x' = A x + 1*u from SciPy equal (a, g) of the oracle (Sec. 3 schemes)."""
+    sys_c = (np.array([[A]]), np.array([[1.0]]), np.array([[1.0]]), np.array([[0.0]]))
+    Ad, Bd, *_ = scipy.signal.cont2discrete(sys_c, dt, method="zoh")
+    a, g, *_ = oracle.disc_terms("zoh", dt, A)
+    assert a == pytest.approx(Ad[0, 0], rel=1e-13) and g == pytest.approx(Bd[0, 0], rel=1e-12)
+    Ad, Bd, *_ = scipy.signal.cont2discrete(sys_c, dt, method="bilinear")
+    a, g, *_ = oracle.disc_terms("bilinear", dt, A)
+    assert a == pytest.approx(Ad[0, 0], rel=1e-13) and g == pytest.approx(Bd[0, 0], rel=1e-12)
+
+
+def test_zoh_identity_and_other_input_gains(oracle):
+    """Abar = exp(dt A) for the three exponential schemes; S6 gain is dt, dirac gain is 1."""
+    for dt, A in [(0.2, -0.9), (1.1, -2.0)]:
+        for disc in ["zoh_s6", "zoh", "dirac"]:
+            assert oracle.disc_terms(disc, dt, A)[0] == pytest.approx(np.exp(dt * A), rel=1e-15)
+        assert oracle.disc_terms("zoh_s6", dt, A)[1] == dt
+        assert oracle.disc_terms("dirac", dt, A)[1] == 1.0
+
+
+def test_bilinear_stability_and_order(oracle):
+    """|a| < 1 iff A < 0, and a = exp(dt A) + O(dt^3)."""
+    for A in [-3.0, -0.1]:
+        for dt in [0.01, 1.0, 50.0]:
+            assert abs(oracle.disc_terms("bilinear", dt, A)[0]) < 1
+    assert abs(oracle.disc_terms("bilinear", 0.5, 0.7)[0]) > 1
+    e1 = abs(oracle.disc_terms("bilinear", 1e-2, -1.0)[0] - np.exp(-1e-2))
+    e2 = abs(oracle.disc_terms("bilinear", 5e-3, -1.0)[0] - np.exp(-5e-3))
+    assert e1 / e2 == pytest.approx(8.0, rel=0.05)
+
+
+@pytest.mark.parametrize("disc", DISCS)
+def test_disc_partials_by_finite_differences(oracle, disc):
+    dt, A, h = 0.37, -1.2, 1e-6
+    a, g, a_t, a_A, g_t, g_A = oracle.disc_terms(disc, dt, A)
+    ap, gp, *_ = oracle.disc_terms(disc, dt + h, A)
+    am, gm, *_ = oracle.disc_terms(disc, dt - h, A)
+    assert a_t == pytest.approx((ap - am) / (2 * h), rel=1e-7, abs=1e-9)
+    assert g_t == pytest.approx((gp - gm) / (2 * h), rel=1e-7, abs=1e-9)
+    ap, gp, *_ = oracle.disc_terms(disc, dt, A + h)
+    am, gm, *_ = oracle.disc_terms(disc, dt, A - h)
+    assert a_A == pytest.approx((ap - am) / (2 * h), rel=1e-7, abs=1e-9)
+    assert g_A == pytest.approx((gp - gm) / (2 * h), rel=1e-7, abs=1e-9)
+
+
+# ----------------------------------------------------------------------------- forward recurrence
+
+@pytest.mark.parametrize("disc", DISCS)
+@pytest.mark.parametrize("softplus", [True, False])
+def test_fwd_matches_bruteforce_unrolled_sum(oracle, disc, softplus):
+    """x_k = sum_{j<=k} (prod_{i=j+1..k} a_i) b_j + (prod_{i<=k} a_i) x0, written as an O(L^2) double sum."""
+    rng = np.random.default_rng(11)
+    p = _rand_problem(rng, B=2, D=2, N=3, L=7)
+    if not softplus:
+        p["delta"] = np.abs(p["delta"]) + 0.1
+        p["delta_bias"] = None
+    y, x_last, xs = oracle.selective_scan_fwd(**p, disc=disc, delta_softplus=softplus, return_states=True)
+    B, D, L = p["u"].shape
+    N = p["A"].shape[1]
+    for b in range(B):
+        for d in range(D):
+            s = p["delta"][b, d] + (p["delta_bias"][d] if p["delta_bias"] is not None else 0.0)
+            dt = np.logaddexp(0, s) if softplus else s
+            for n in range(N):
+                a = np.empty(L); bb = np.empty(L)
+                for l in range(L):
+                    a[l], g = _disc_py(disc, dt[l], p["A"][d, n])
+                    bb[l] = g * p["Bm"][b, l, n] * p["u"][b, d, l]
+                for k in range(L):
+                    tot = np.prod(a[: k + 1]) * p["x0"][b, d, n]
+                    for j in range(k + 1):
+                        tot += np.prod(a[j + 1: k + 1]) * bb[j]
+                    assert xs[b, d, k, n] == pytest.approx(tot, rel=1e-11, abs=1e-12)
+            for k in range(L):
+                ypre = np.dot(p["Cm"][b, k], xs[b, d, k]) + p["Dskip"][d] * p["u"][b, d, k]
+                zz = p["z"][b, d, k]
+                assert y[b, d, k] == pytest.approx(ypre * zz / (1 + np.exp(-zz)), rel=1e-11, abs=1e-12)
+            np.testing.assert_allclose(x_last[b, d], xs[b, d, L - 1], rtol=0, atol=0)
+
+
+@pytest.mark.parametrize("disc", DISCS)
+def test_lti_special_case_is_a_convolution(oracle, disc):
+    """Constant delta, B, C  =>  y = K * u with K_k = C Abar^k Bbar (+ D at k = 0)."""
+    rng = np.random.default_rng(5)
+    Bsz, D, N, L = 1, 2, 3, 24
+    A = -np.exp(rng.uniform(-1, 1, (D, N)))
+    dt = np.array([0.3, 0.8])
+    Bv, Cv = rng.standard_normal(N), rng.standard_normal(N)
+    Dskip = rng.standard_normal(D)
+    u = rng.standard_normal((Bsz, D, L))
+    delta = np.broadcast_to(dt[None, :, None], (Bsz, D, L)).copy()
+    Bm = np.broadcast_to(Bv, (Bsz, L, N)).copy()
+    Cm = np.broadcast_to(Cv, (Bsz, L, N)).copy()
+    y, _ = oracle.selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=Dskip, disc=disc, delta_softplus=False)
+    for d in range(D):
+        K = np.zeros(L)
+        for n in range(N):
+            a, g = _disc_py(disc, dt[d], A[d, n])
+            K += Cv[n] * a ** np.arange(L) * g * Bv[n]
+        K[0] += Dskip[d]
+        np.testing.assert_allclose(y[0, d], np.convolve(u[0, d], K)[:L], rtol=1e-11, atol=1e-12)
+    # impulse input => y_k = K_k
+    u_imp = np.zeros((Bsz, D, L)); u_imp[:, :, 0] = 1.0
+    y_imp, _ = oracle.selective_scan_fwd(u_imp, delta, A, Bm, Cm, Dskip=Dskip, disc=disc, delta_softplus=False)
+    for d in range(D):
+        K = sum(Cv[n] * _disc_py(disc, dt[d], A[d, n])[0] ** np.arange(L) * _disc_py(disc, dt[d], A[d, n])[1] * Bv[n]
+                for n in range(N))
+        K[0] += Dskip[d]
+        np.testing.assert_allclose(y_imp[0, d], K, rtol=1e-11, atol=1e-13)
+
+
+def test_exact_zoh_step_response_is_the_continuous_solution(oracle):
+    """u = 1 held constant: exact ZOH reproduces x(t) = (e^{tA} - 1)/A * B at t = k*dt; the S6 form is off by dt*A/(e^{dt A}-1)."""
+    A, dt, L, Bc = -0.7, 0.25, 40, 1.3
+    u = np.ones((1, 1, L)); delta = np.full((1, 1, L), dt)
+    Bm = np.full((1, L, 1), Bc); Cm = np.ones((1, L, 1))
+    y, _ = oracle.selective_scan_fwd(u, delta, np.array([[A]]), Bm, Cm, disc="zoh", delta_softplus=False)
+    t = dt * np.arange(1, L + 1)
+    np.testing.assert_allclose(y[0, 0], np.expm1(t * A) / A * Bc, rtol=1e-12)
+    y6, _ = oracle.selective_scan_fwd(u, delta, np.array([[A]]), Bm, Cm, disc="zoh_s6", delta_softplus=False)
+    np.testing.assert_allclose(y6[0, 0] / y[0, 0], dt * A / np.expm1(dt * A), rtol=1e-12)
+
+
+def test_linearity_causality_gate_and_chaining(oracle):
+    rng = np.random.default_rng(3)
+    p = _rand_problem(rng, B=2, D=3, N=4, L=20, gate=False, x0=False)
+    y1, _ = oracle.selective_scan_fwd(**p)
+    u2 = rng.standard_normal(p["u"].shape)
+    y2, _ = oracle.selective_scan_fwd(**{**p, "u": u2})
+    y12, _ = oracle.selective_scan_fwd(**{**p, "u": 2.0 * p["u"] - 3.0 * u2})
+    np.testing.assert_allclose(y12, 2.0 * y1 - 3.0 * y2, rtol=1e-11, atol=1e-12)       # superposition in u
+    pc = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in p.items()}
+    pc["u"][:, :, 12:] += 5.0; pc["delta"][:, :, 12:] -= 1.0; pc["Bm"][:, 12:] *= 2; pc["Cm"][:, 12:] *= -1
+    yc, _ = oracle.selective_scan_fwd(**pc)
+    np.testing.assert_array_equal(yc[:, :, :12], y1[:, :, :12])                          # causality
+    z = rng.standard_normal(p["u"].shape)
+    yg, _ = oracle.selective_scan_fwd(**{**p, "z": z})
+    np.testing.assert_allclose(yg, y1 * z / (1 + np.exp(-z)), rtol=1e-13)                # gate identity
+    # scan(L1+L2) == scan(L1) then scan(L2, x0 = x_last)
+    L1 = 7
+    ya, xa = oracle.selective_scan_fwd(p["u"][:, :, :L1], p["delta"][:, :, :L1], p["A"], p["Bm"][:, :L1],
+                                       p["Cm"][:, :L1], Dskip=p["Dskip"], delta_bias=p["delta_bias"])
+    yb, xb = oracle.selective_scan_fwd(p["u"][:, :, L1:], p["delta"][:, :, L1:], p["A"], p["Bm"][:, L1:],
+                                       p["Cm"][:, L1:], Dskip=p["Dskip"], delta_bias=p["delta_bias"], x0=xa)
+    yfull, xfull = oracle.selective_scan_fwd(**p)
+    np.testing.assert_allclose(np.concatenate([ya, yb], axis=2), yfull, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(xb, xfull, rtol=1e-12, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- backward
+
+def _loss(oracle, p, dy, disc, softplus):
+    y, _ = oracle.selective_scan_fwd(**p, disc=disc, delta_softplus=softplus)
+    return float(np.sum(dy * y))
+
+
+@pytest.mark.parametrize("disc", DISCS)
+@pytest.mark.parametrize("softplus,gate", [(True, True), (False, False)])
+def test_bwd_matches_central_finite_differences(oracle, disc, softplus, gate):
+    rng = np.random.default_rng(7)
+    p = _rand_problem(rng, B=2, D=2, N=3, L=6, gate=gate)
+    if not softplus:                      # caller-supplied positive step sizes; bias still added
+        p["delta"] = np.abs(p["delta"]) + 2.2
+    dy = rng.standard_normal(p["u"].shape)
+    g = oracle.selective_scan_bwd(**p, dy=dy, disc=disc, delta_softplus=softplus)
+    names = {"u": "du", "delta": "ddelta", "A": "dA", "Bm": "dBm", "Cm": "dCm", "Dskip": "dD",
+             "delta_bias": "dbias", "z": "dz", "x0": "dx0"}
+    h = 1e-6
+    for key, gname in names.items():
+        if p[key] is None:
+            continue
+        base = p[key]
+        num = np.zeros_like(base)
+        it = np.nditer(base, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            pp = dict(p); arr = base.copy(); arr[idx] += h; pp[key] = arr
+            pm = dict(p); arr2 = base.copy(); arr2[idx] -= h; pm[key] = arr2
+            num[idx] = (_loss(oracle, pp, dy, disc, softplus) - _loss(oracle, pm, dy, disc, softplus)) / (2 * h)
+        scale = max(1.0, np.abs(num).max())
+        np.testing.assert_allclose(g[gname], num, rtol=0, atol=2e-7 * scale, err_msg=f"{gname} ({disc})")
+
+
+def test_bwd_adjoint_dot_test(oracle):
+    """y is linear in u for fixed delta, B, C, z:  <dy, J du> == <J^T dy, du>."""
+    rng = np.random.default_rng(9)
+    p = _rand_problem(rng, B=2, D=3, N=4, L=33, x0=False)
+    dy = rng.standard_normal(p["u"].shape)
+    v = rng.standard_normal(p["u"].shape)
+    Jv, _ = oracle.selective_scan_fwd(**{**p, "u": v})
+    g = oracle.selective_scan_bwd(**p, dy=dy)
+    assert np.sum(dy * Jv) == pytest.approx(np.sum(g["du"] * v), rel=1e-11)
+
+
+def test_bwd_optional_outputs_absent(oracle):
+    rng = np.random.default_rng(2)
+    p = _rand_problem(rng, gate=False, bias=False, x0=False, skip=False)
+    g = oracle.selective_scan_bwd(**p, dy=rng.standard_normal(p["u"].shape))
+    assert g["dz"] is None and g["dD"] is None and g["dbias"] is None
+    assert np.all(np.isfinite(g["du"])) and np.all(np.isfinite(g["dBm"]))
+
+
+# ----------------------------------------------------------------------------- LTI complex-diagonal scan
+
+def test_lti_scan_matches_scipy_lfilter_and_powers(oracle):
+    rng = np.random.default_rng(4)
+    Bsz, L, P = 2, 50, 5
+    lam = rng.uniform(0.9, 0.999, P) * np.exp(1j * rng.uniform(0, 2 * np.pi, P))
+    v = (rng.standard_normal((Bsz, L, P)) + 1j * rng.standard_normal((Bsz, L, P))) / np.sqrt(2)
+    x = oracle.lti_diag_scan(lam, v)
+    for b in range(Bsz):
+        for p_ in range(P):
+            ref = scipy.signal.lfilter([1.0], [1.0, -lam[p_]], v[b, :, p_])
+            np.testing.assert_allclose(x[b, :, p_], ref, rtol=1e-12, atol=1e-13)
+    imp = np.zeros((1, L, P), dtype=complex); imp[0, 0] = 1.0
+    xi = oracle.lti_diag_scan(lam, imp)
+    np.testing.assert_allclose(xi[0], lam[None, :] ** np.arange(L)[:, None], rtol=1e-12)   # impulse => lambda^k
+    x0 = rng.standard_normal((Bsz, P)) + 1j * rng.standard_normal((Bsz, P))
+    xz = oracle.lti_diag_scan(lam, np.zeros_like(v), x0=x0)
+    np.testing.assert_allclose(xz, x0[:, None, :] * lam[None, None, :] ** np.arange(1, L + 1)[None, :, None], rtol=1e-12)
+
+
+def test_lti_scan_agrees_with_selective_scan_on_a_real_pole(oracle):
+    """A real lambda with dirac input map is the same recurrence through both oracle entry points."""
+    rng = np.random.default_rng(8)
+    L = 30
+    A, dt = -0.5, 0.3
+    lam = np.array([np.exp(A * dt) + 0j])
+    vv = rng.standard_normal(L)
+    x = oracle.lti_diag_scan(lam, vv[None, :, None] + 0j)
+    y, _ = oracle.selective_scan_fwd(vv[None, None, :], np.full((1, 1, L), dt), np.array([[A]]),
+                                     np.ones((1, L, 1)), np.ones((1, L, 1)), disc="dirac", delta_softplus=False)
+    np.testing.assert_allclose(x[0, :, 0].real, y[0, 0], rtol=1e-13)
+    assert np.all(x.imag == 0)
