@@ -1,0 +1,188 @@
+/*
+ * lrnnx.h -- C ABI of the MI355X (gfx950) diagonal linear-recurrence scan library.
+ *
+ * The library computes the linear RNN recurrence of the lrnnx paper (Sec. 2.2, Eq. 2)
+ *
+ *     x_k = A(k) x_{k-1} + B(k) u_k,        y_k = C(k) x_k + D(k) u_k
+ *
+ * for a diagonal state matrix, in two forms:
+ *   - time-varying, input-dependent ("selective", the S6 row of Table 1; Sec. 2.2.2),
+ *     with the discretisation fused into the scan (Sec. 3: ZOH, bilinear, dirac; the
+ *     asynchronous / event-driven scheme is served by delta_softplus = 0 with the
+ *     caller's own per-step Delta) and with the output projection fused in;
+ *   - time-invariant complex-diagonal (the S5 / LRU rows of Table 1; Sec. 2.2.1).
+ * The hidden state x[B,D,L,N] is never written to memory (Sec. 3, the stated
+ * advantage of the fused kernels); the backward pass recomputes it.
+ *
+ * General rules for every entry point
+ *   - Every pointer is a DEVICE pointer unless stated otherwise.  The caller owns all
+ *     buffers; the library allocates nothing, frees nothing and never synchronises.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream) and the call returns at once.
+ *   - The return value is an lrnnx_status.  On any status other than LRNNX_OK nothing
+ *     has been launched and no output has been touched.  No C++ exception crosses the
+ *     ABI and the library never aborts.
+ *   - `struct_size` must be set to sizeof(the struct); a smaller value is rejected.
+ *   - Tensors named [B,D,L] have the time axis contiguous (stride 1) and explicit
+ *     batch / channel strides counted in ELEMENTS; a channel stride of 0 broadcasts
+ *     one row over all channels (inputs only).  Tensors [B,L,N], [D,N], [D], [B,D,N]
+ *     are contiguous.  io_dtype selects the element type of u, delta, z, Bm, Cm, y, dy,
+ *     du, ddelta, dz (float or bfloat16); the state, all accumulation, A, Dskip,
+ *     delta_bias, x0, x_last, checkpoints and the reduced gradients are float.
+ *   - Supported: N in {1,2,4,8,16}; any B, D >= 1; any L >= 1 (B*D*L must fit int64).
+ */
+#ifndef LRNNX_H
+#define LRNNX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LRNNX_OK = 0,
+    LRNNX_ERR_INVALID_ARG = 1,   /* NULL required pointer, bad size, bad enum, bad stride */
+    LRNNX_ERR_UNSUPPORTED = 2,   /* valid request the library has no kernel for (e.g. N = 3) */
+    LRNNX_ERR_WORKSPACE = 3,     /* workspace missing or smaller than lrnnx_workspace_bytes() */
+    LRNNX_ERR_LAUNCH = 4         /* the HIP runtime refused a launch; hipGetLastError has details */
+} lrnnx_status;
+
+typedef enum { LRNNX_F32 = 0, LRNNX_BF16 = 1 } lrnnx_dtype;
+
+/* Discretisation of x' = A x + B u with step Delta (schemes named in Sec. 3).
+ * a is the state multiplier, g the input gain (Bbar = g * B).                */
+typedef enum {
+    LRNNX_DISC_ZOH_S6 = 0,    /* a = exp(Delta A), g = Delta               (S6's simplified ZOH) */
+    LRNNX_DISC_ZOH = 1,       /* a = exp(Delta A), g = (a - 1) / A         (exact zero-order hold) */
+    LRNNX_DISC_BILINEAR = 2,  /* a = (1 + Delta A/2)/(1 - Delta A/2), g = Delta/(1 - Delta A/2) */
+    LRNNX_DISC_DIRAC = 3      /* a = exp(Delta A), g = 1 */
+} lrnnx_disc;
+
+/* How the forward pass covers the time axis. */
+typedef enum {
+    LRNNX_PATH_AUTO = 0,         /* library chooses from B*D and L */
+    LRNNX_PATH_SINGLE_PASS = 1,  /* one launch; each row walks its tiles in order, carrying the state */
+    LRNNX_PATH_CHUNK_CARRY = 2   /* three launches: per-chunk aggregates, carry over chunks, apply; needs workspace */
+} lrnnx_path;
+
+/* State checkpoints: ckpt[b,d,c,n] (float, [B,D,ceil(L/interval),N]) is the state
+ * x entering time step c*interval, i.e. x_{c*interval-1} (x0 or 0 for c = 0).
+ * The forward pass can write them; the backward pass restarts its recomputation
+ * from them.  The interval is a constant of the build.                        */
+int64_t lrnnx_ckpt_interval(void);
+
+/* ------------------------------------------------------------------ selective scan, forward
+ * For every row (b,d), with s_l = delta[b,d,l] + delta_bias[d],
+ * Delta_l = softplus(s_l) if delta_softplus else s_l, and (a,g) from `disc`:
+ *     x_{l,n} = a(Delta_l, A[d,n]) x_{l-1,n} + g(Delta_l, A[d,n]) Bm[b,l,n] u[b,d,l]     (Eq. 2, line 1)
+ *     ypre_l  = sum_n Cm[b,l,n] x_{l,n} + Dskip[d] u[b,d,l]                            (Eq. 2, line 2)
+ *     y[b,d,l] = ypre_l * z[b,d,l] * sigmoid(z[b,d,l])   if z != NULL, else ypre_l
+ * x_{-1} = x0[b,d,:] or 0.  Optional (NULL allowed): Dskip, delta_bias, z, x0, x_last, ckpt.
+ * workspace is needed only by LRNNX_PATH_CHUNK_CARRY (AUTO falls back to the single
+ * pass when it is missing or too small).                                              */
+typedef struct lrnnx_ss_fwd_args {
+    size_t struct_size;
+    int32_t B, D, N;
+    int64_t L;
+    int32_t io_dtype;        /* lrnnx_dtype */
+    int32_t disc;            /* lrnnx_disc */
+    int32_t delta_softplus;  /* 0 or 1 */
+    int32_t path;            /* lrnnx_path */
+    const void *u;      int64_t u_stride_b, u_stride_d;            /* [B,D,L] io */
+    const void *delta;  int64_t delta_stride_b, delta_stride_d;    /* [B,D,L] io, raw (pre-bias, pre-softplus) */
+    const float *A;                                                /* [D,N] */
+    const void *Bm;                                                /* [B,L,N] io */
+    const void *Cm;                                                /* [B,L,N] io */
+    const float *Dskip;                                            /* [D] or NULL */
+    const float *delta_bias;                                       /* [D] or NULL */
+    const void *z;      int64_t z_stride_b, z_stride_d;            /* [B,D,L] io or NULL */
+    const float *x0;                                               /* [B,D,N] or NULL */
+    void *y;            int64_t y_stride_b, y_stride_d;            /* [B,D,L] io, out */
+    float *x_last;                                                 /* [B,D,N] out or NULL: x_{L-1} */
+    float *ckpt;                                                   /* [B,D,ceil(L/interval),N] out or NULL */
+    void *workspace;    size_t workspace_bytes;
+    void *stream;
+} lrnnx_ss_fwd_args;
+
+int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *args);
+
+/* ------------------------------------------------------------------ selective scan, backward
+ * Reverse-mode derivative of the forward above for an upstream gradient dy[B,D,L]:
+ * the gradients of sum(dy * y) with respect to u, the raw delta, A, Bm, Cm, Dskip,
+ * delta_bias, z and x0.  The state is recomputed tile by tile from checkpoints and
+ * never stored per step (Sec. 3).  `ckpt` is the array a forward call wrote for the
+ * same inputs; if NULL the library first runs a state-only forward sweep into
+ * `workspace` (size from lrnnx_workspace_bytes(LRNNX_WS_BWD, ...)).
+ * Outputs du, ddelta, dz: io_dtype, written once each.  dA[D,N], dBm, dCm[B,L,N],
+ * dD[D], dbias[D]: float, OVERWRITTEN (the library clears them on the stream, then
+ * accumulates with atomics: their last bits may differ from run to run).
+ * dx0[B,D,N] float.  Optional (NULL allowed): Dskip, delta_bias, z, x0, ckpt, dD,
+ * dbias, dz, dx0.  dD requires Dskip, dbias requires delta_bias, dz requires z.    */
+typedef struct lrnnx_ss_bwd_args {
+    size_t struct_size;
+    int32_t B, D, N;
+    int64_t L;
+    int32_t io_dtype, disc, delta_softplus, reserved;
+    const void *u;      int64_t u_stride_b, u_stride_d;
+    const void *delta;  int64_t delta_stride_b, delta_stride_d;
+    const float *A;
+    const void *Bm;
+    const void *Cm;
+    const float *Dskip;
+    const float *delta_bias;
+    const void *z;      int64_t z_stride_b, z_stride_d;
+    const float *x0;
+    const void *dy;     int64_t dy_stride_b, dy_stride_d;          /* [B,D,L] io */
+    const float *ckpt;                                             /* from the forward call, or NULL */
+    void *du;           int64_t du_stride_b, du_stride_d;          /* [B,D,L] io, out */
+    void *ddelta;       int64_t ddelta_stride_b, ddelta_stride_d;  /* [B,D,L] io, out */
+    void *dz;           int64_t dz_stride_b, dz_stride_d;          /* [B,D,L] io, out or NULL */
+    float *dA;                                                     /* [D,N] out */
+    float *dBm;                                                    /* [B,L,N] out */
+    float *dCm;                                                    /* [B,L,N] out */
+    float *dD;                                                     /* [D] out or NULL */
+    float *dbias;                                                  /* [D] out or NULL */
+    float *dx0;                                                    /* [B,D,N] out or NULL */
+    void *workspace;    size_t workspace_bytes;
+    void *stream;
+} lrnnx_ss_bwd_args;
+
+int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *args);
+
+/* ------------------------------------------------------------------ LTI complex-diagonal scan
+ *     x[b,k,p] = lambda[p] * x[b,k-1,p] + v[b,k,p]        (Eq. 2 with constant diagonal A; Sec. 2.2.1)
+ * for complex numbers stored as interleaved (re, im) float pairs.  v_k = Bbar u_k is
+ * the caller's (a dense projection); the call returns the state at every step.
+ * lambda[P], v and x [B,L,P] (P contiguous), x0 and x_last [B,P] (optional, NULL
+ * allowed).  x may alias v.  workspace: lrnnx_workspace_bytes(LRNNX_WS_LTI, B, P, 0, L, 0). */
+typedef struct lrnnx_lti_args {
+    size_t struct_size;
+    int32_t B, P;
+    int64_t L;
+    const void *lambda;
+    const void *v;
+    const void *x0;
+    void *x;
+    void *x_last;
+    void *workspace;    size_t workspace_bytes;
+    void *stream;
+} lrnnx_lti_args;
+
+int lrnnx_lti_diag_scan(const lrnnx_lti_args *args);
+
+/* ------------------------------------------------------------------ queries (host only, no GPU needed) */
+typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2 } lrnnx_ws_kind;
+
+/* Bytes of device scratch the call may need (the largest over its paths).
+ * For LRNNX_WS_LTI pass P as D and 0 for N.  Returns 0 for invalid sizes.   */
+size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t L, int io_dtype);
+
+const char *lrnnx_status_string(int status);
+int lrnnx_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LRNNX_H */
