@@ -1,0 +1,281 @@
+"""Thin ctypes binding of liblrnnx.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (include/lrnnx.h) and
+does nothing but check tensor dtypes/devices, allocate the outputs and the workspace
+with torch, fill the args struct with data pointers, strides and the current HIP
+stream, and call into the library.  There is no CPU or PyTorch fallback: if the
+library has not been built, importing the entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblrnnx.so")
+
+F32, BF16 = 0, 1
+DISC = {"zoh_s6": 0, "zoh": 1, "bilinear": 2, "dirac": 3}
+PATH = {"auto": 0, "single_pass": 1, "chunk_carry": 2}
+WS_FWD, WS_BWD, WS_LTI = 0, 1, 2
+STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported", 3: "workspace", 4: "launch"}
+
+_vp, _i32, _i64, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+
+
+class FwdArgs(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32), ("L", _i64),
+        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32), ("path", _i32),
+        ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
+        ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
+        ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
+        ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
+        ("x0", _vp),
+        ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
+        ("x_last", _vp), ("ckpt", _vp),
+        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
+    ]
+
+
+class BwdArgs(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32), ("L", _i64),
+        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32), ("reserved", _i32),
+        ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
+        ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
+        ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
+        ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
+        ("x0", _vp),
+        ("dy", _vp), ("dy_stride_b", _i64), ("dy_stride_d", _i64),
+        ("ckpt", _vp),
+        ("du", _vp), ("du_stride_b", _i64), ("du_stride_d", _i64),
+        ("ddelta", _vp), ("ddelta_stride_b", _i64), ("ddelta_stride_d", _i64),
+        ("dz", _vp), ("dz_stride_b", _i64), ("dz_stride_d", _i64),
+        ("dA", _vp), ("dBm", _vp), ("dCm", _vp), ("dD", _vp), ("dbias", _vp), ("dx0", _vp),
+        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
+    ]
+
+
+class LtiArgs(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", _sz), ("B", _i32), ("P", _i32), ("L", _i64),
+        ("lambda_", _vp), ("v", _vp), ("x0", _vp), ("x", _vp), ("x_last", _vp),
+        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
+    ]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library.  Raises if it was not built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2602_08810_amd.build` "
+                               "(the scan has no CPU or PyTorch fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        L.lrnnx_selective_scan_fwd.argtypes = [ctypes.POINTER(FwdArgs)]
+        L.lrnnx_selective_scan_bwd.argtypes = [ctypes.POINTER(BwdArgs)]
+        L.lrnnx_lti_diag_scan.argtypes = [ctypes.POINTER(LtiArgs)]
+        for f in (L.lrnnx_selective_scan_fwd, L.lrnnx_selective_scan_bwd, L.lrnnx_lti_diag_scan, L.lrnnx_version):
+            f.restype = ctypes.c_int
+        L.lrnnx_workspace_bytes.argtypes = [ctypes.c_int, _i64, _i64, _i64, _i64, ctypes.c_int]
+        L.lrnnx_workspace_bytes.restype = _sz
+        L.lrnnx_ckpt_interval.restype = _i64
+        L.lrnnx_status_string.argtypes = [ctypes.c_int]
+        L.lrnnx_status_string.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+class LrnnxError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        super().__init__(f"lrnnx status {code}: {lib().lrnnx_status_string(code).decode()}")
+
+
+def _check(code):
+    if code != 0:
+        raise LrnnxError(code)
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _io_dtype(t):
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"I/O dtype must be float32 or bfloat16, got {t.dtype}")
+
+
+def _bdl(t, name, io=None):
+    """(ptr, stride_b, stride_d) of a [B,D,L] tensor whose last axis is contiguous."""
+    if t is None:
+        return None, 0, 0
+    if t.dim() != 3 or (t.shape[2] > 1 and t.stride(2) != 1):
+        raise ValueError(f"{name}: expected [B,D,L] with contiguous time axis")
+    if io is not None and t.dtype != io:
+        raise TypeError(f"{name}: dtype {t.dtype} differs from the I/O dtype {io}")
+    return t.data_ptr(), t.stride(0), t.stride(1)
+
+
+def _f32c(t, name, shape=None):
+    if t is None:
+        return None
+    if t.dtype != torch.float32 or not t.is_contiguous():
+        raise TypeError(f"{name}: expected a contiguous float32 tensor")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    return t
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def lrnnx_ckpt_interval() -> int:
+    return int(lib().lrnnx_ckpt_interval())
+
+
+def lrnnx_workspace_bytes(which, B, D, N, L, io_dtype) -> int:
+    return int(lib().lrnnx_workspace_bytes(which, B, D, N, L, io_dtype))
+
+
+def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, x0=None,
+                             disc="zoh_s6", delta_softplus=True, path="auto",
+                             return_last_state=False, return_ckpt=False, out=None, workspace=None):
+    """y (and optionally x_last, ckpt) of the forward selective scan; see lrnnx_ss_fwd_args."""
+    io = u.dtype
+    Bsz, D, L = u.shape
+    N = A.shape[1]
+    a = FwdArgs()
+    a.struct_size = ctypes.sizeof(FwdArgs)
+    a.B, a.D, a.N, a.L = Bsz, D, N, L
+    a.io_dtype = _io_dtype(u)
+    a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
+    a.delta_softplus = int(bool(delta_softplus))
+    a.path = PATH[path] if isinstance(path, str) else int(path)
+    a.u, a.u_stride_b, a.u_stride_d = _bdl(u, "u", io)
+    a.delta, a.delta_stride_b, a.delta_stride_d = _bdl(delta, "delta", io)
+    a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io)
+    a.A = _ptr(_f32c(A, "A", (D, N)))
+    for name, t in (("Bm", Bm), ("Cm", Cm)):
+        if t.dtype != io or not t.is_contiguous() or tuple(t.shape) != (Bsz, L, N):
+            raise ValueError(f"{name}: expected contiguous [B,L,N] of dtype {io}")
+    a.Bm, a.Cm = Bm.data_ptr(), Cm.data_ptr()
+    a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
+    a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
+    a.x0 = _ptr(_f32c(x0, "x0", (Bsz, D, N)))
+    y = out if out is not None else torch.empty((Bsz, D, L), dtype=io, device=u.device)
+    a.y, a.y_stride_b, a.y_stride_d = _bdl(y, "y", io)
+    x_last = torch.empty((Bsz, D, N), dtype=torch.float32, device=u.device) if return_last_state else None
+    a.x_last = _ptr(x_last)
+    ckpt = None
+    if return_ckpt:
+        I = lrnnx_ckpt_interval()
+        ckpt = torch.empty((Bsz, D, (L + I - 1) // I, N), dtype=torch.float32, device=u.device)
+    a.ckpt = _ptr(ckpt)
+    if workspace is None:
+        nbytes = lrnnx_workspace_bytes(WS_FWD, Bsz, D, N, L, a.io_dtype)
+        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=u.device)
+    a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    a.stream = _stream()
+    _check(lib().lrnnx_selective_scan_fwd(ctypes.byref(a)))
+    res = (y,)
+    if return_last_state:
+        res += (x_last,)
+    if return_ckpt:
+        res += (ckpt,)
+    return res[0] if len(res) == 1 else res
+
+
+def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,
+                             ckpt=None, disc="zoh_s6", delta_softplus=True, want_dx0=False,
+                             outs=None, workspace=None):
+    """Gradients of sum(dy*y) as a dict; see lrnnx_ss_bwd_args.  `outs` may supply preallocated outputs."""
+    io = u.dtype
+    Bsz, D, L = u.shape
+    N = A.shape[1]
+    dev = u.device
+    outs = dict(outs or {})
+
+    def new(name, shape, dtype):
+        if name not in outs:
+            outs[name] = torch.empty(shape, dtype=dtype, device=dev)
+        return outs[name]
+
+    a = BwdArgs()
+    a.struct_size = ctypes.sizeof(BwdArgs)
+    a.B, a.D, a.N, a.L = Bsz, D, N, L
+    a.io_dtype = _io_dtype(u)
+    a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
+    a.delta_softplus = int(bool(delta_softplus))
+    a.u, a.u_stride_b, a.u_stride_d = _bdl(u, "u", io)
+    a.delta, a.delta_stride_b, a.delta_stride_d = _bdl(delta, "delta", io)
+    a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io)
+    a.dy, a.dy_stride_b, a.dy_stride_d = _bdl(dy, "dy", io)
+    a.A = _ptr(_f32c(A, "A", (D, N)))
+    for name, t in (("Bm", Bm), ("Cm", Cm)):
+        if t.dtype != io or not t.is_contiguous() or tuple(t.shape) != (Bsz, L, N):
+            raise ValueError(f"{name}: expected contiguous [B,L,N] of dtype {io}")
+    a.Bm, a.Cm = Bm.data_ptr(), Cm.data_ptr()
+    a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
+    a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
+    a.x0 = _ptr(_f32c(x0, "x0", (Bsz, D, N)))
+    a.ckpt = _ptr(_f32c(ckpt, "ckpt"))
+    a.du, a.du_stride_b, a.du_stride_d = _bdl(new("du", (Bsz, D, L), io), "du", io)
+    a.ddelta, a.ddelta_stride_b, a.ddelta_stride_d = _bdl(new("ddelta", (Bsz, D, L), io), "ddelta", io)
+    if z is not None:
+        a.dz, a.dz_stride_b, a.dz_stride_d = _bdl(new("dz", (Bsz, D, L), io), "dz", io)
+    a.dA = new("dA", (D, N), torch.float32).data_ptr()
+    a.dBm = new("dBm", (Bsz, L, N), torch.float32).data_ptr()
+    a.dCm = new("dCm", (Bsz, L, N), torch.float32).data_ptr()
+    if Dskip is not None:
+        a.dD = new("dD", (D,), torch.float32).data_ptr()
+    if delta_bias is not None:
+        a.dbias = new("dbias", (D,), torch.float32).data_ptr()
+    if want_dx0:
+        a.dx0 = new("dx0", (Bsz, D, N), torch.float32).data_ptr()
+    if workspace is None and ckpt is None:
+        nbytes = lrnnx_workspace_bytes(WS_BWD, Bsz, D, N, L, a.io_dtype)
+        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
+    if workspace is not None:
+        a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    a.stream = _stream()
+    _check(lib().lrnnx_selective_scan_bwd(ctypes.byref(a)))
+    return outs
+
+
+def lrnnx_lti_diag_scan(lam, v, x0=None, return_last_state=False, out=None, workspace=None):
+    """x [B,L,P] complex64 of x_k = lam * x_{k-1} + v_k; see lrnnx_lti_args."""
+    if v.dtype != torch.complex64 or lam.dtype != torch.complex64:
+        raise TypeError("lam and v must be complex64")
+    if not v.is_contiguous() or not lam.is_contiguous():
+        raise ValueError("lam and v must be contiguous")
+    Bsz, L, P = v.shape
+    a = LtiArgs()
+    a.struct_size = ctypes.sizeof(LtiArgs)
+    a.B, a.P, a.L = Bsz, P, L
+    a.lambda_, a.v = lam.data_ptr(), v.data_ptr()
+    if x0 is not None:
+        if x0.dtype != torch.complex64 or not x0.is_contiguous() or tuple(x0.shape) != (Bsz, P):
+            raise ValueError("x0: expected contiguous complex64 [B,P]")
+        a.x0 = x0.data_ptr()
+    x = out if out is not None else torch.empty_like(v)
+    a.x = x.data_ptr()
+    x_last = torch.empty((Bsz, P), dtype=torch.complex64, device=v.device) if return_last_state else None
+    a.x_last = _ptr(x_last)
+    if workspace is None:
+        nbytes = lrnnx_workspace_bytes(WS_LTI, Bsz, P, 0, L, 0)
+        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=v.device)
+    a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    a.stream = _stream()
+    _check(lib().lrnnx_lti_diag_scan(ctypes.byref(a)))
+    return (x, x_last) if return_last_state else x

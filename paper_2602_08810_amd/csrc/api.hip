@@ -1,0 +1,232 @@
+// C ABI of the scan library: argument checks, choice of path, workspace layout, launches.
+// Nothing here allocates, frees or synchronises; see include/lrnnx.h for the contract.
+#include "../../include/lrnnx.h"
+#include "kernels.hpp"
+
+using namespace lrnnx;
+
+namespace {
+
+constexpr int kNumCU = 256;              // MI355X
+constexpr int kFwdWaves = 8;             // channels (wavefronts) per forward workgroup
+
+inline bool supported_n(int n) { return n == 1 || n == 2 || n == 4 || n == 8 || n == 16; }
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t elem_size(int io) { return io == LRNNX_BF16 ? 2 : 4; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// 16-byte vector access to a [B,D,L] tensor is possible when every row start is 16-byte aligned.
+inline bool row_vec_ok(const void *p, int64_t sb, int64_t sd, size_t es) {
+    return aligned16(p) && (sb * (int64_t)es) % 16 == 0 && (sd * (int64_t)es) % 16 == 0;
+}
+
+// Number of time chunks of the chunk-carry forward path.
+int fwd_chunks(int64_t B, int64_t D, int64_t L, int io, bool forced) {
+    const int64_t wgs = B * cdiv(D, kFwdWaves);
+    const int64_t ntiles = cdiv(L, fwd_tile_steps(io));
+    int64_t n = cdiv(forced ? 8 * kNumCU : 2 * kNumCU, wgs);
+    if (forced && n < 2) n = 2;
+    if (n > ntiles) n = ntiles;
+    if (n < 1) n = 1;
+    return (int)n;
+}
+
+int lti_chunks(int64_t B, int64_t P, int64_t L) {
+    const int64_t waves_per_chunk = B * cdiv(P, 256) * 4;
+    int64_t n = cdiv(8 * kNumCU, waves_per_chunk);
+    const int64_t max_n = cdiv(L, 16);                 // at least 16 steps per chunk
+    if (n > max_n) n = max_n;
+    if (n > 65535) n = 65535;
+    if (n < 1) n = 1;
+    return (int)n;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t lrnnx_ckpt_interval(void) { return kCkptInterval; }
+int lrnnx_version(void) { return 100; }
+
+const char *lrnnx_status_string(int status) {
+    switch (status) {
+        case LRNNX_OK: return "ok";
+        case LRNNX_ERR_INVALID_ARG: return "invalid argument";
+        case LRNNX_ERR_UNSUPPORTED: return "unsupported configuration";
+        case LRNNX_ERR_WORKSPACE: return "workspace missing or too small";
+        case LRNNX_ERR_LAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t L, int io_dtype) {
+    if (B < 1 || D < 1 || L < 1) return 0;
+    if (which == LRNNX_WS_FWD) {
+        if (!supported_n((int)N)) return 0;
+        const int nch = fwd_chunks(B, D, L, io_dtype, true);
+        return (size_t)2 * B * D * nch * N * sizeof(float);
+    }
+    if (which == LRNNX_WS_BWD) {
+        if (!supported_n((int)N)) return 0;
+        return (size_t)B * D * cdiv(L, kCkptInterval) * N * sizeof(float);
+    }
+    if (which == LRNNX_WS_LTI) {
+        const int nch = lti_chunks(B, D, L);
+        return nch > 1 ? (size_t)B * nch * D * 2 * sizeof(float) : 0;
+    }
+    return 0;
+}
+
+int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *a) {
+    if (!a || a->struct_size < sizeof(lrnnx_ss_fwd_args)) return LRNNX_ERR_INVALID_ARG;
+    if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
+    if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
+    if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
+    if (a->path < LRNNX_PATH_AUTO || a->path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
+    if (!a->u || !a->delta || !a->A || !a->Bm || !a->Cm || !a->y) return LRNNX_ERR_INVALID_ARG;
+    if (a->u_stride_b < 0 || a->u_stride_d < 0 || a->delta_stride_b < 0 || a->delta_stride_d < 0 ||
+        a->y_stride_b < 0 || a->y_stride_d < a->L || (a->z && (a->z_stride_b < 0 || a->z_stride_d < 0)))
+        return LRNNX_ERR_INVALID_ARG;
+    if (!supported_n(a->N)) return LRNNX_ERR_UNSUPPORTED;
+    if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
+    const size_t es = elem_size(a->io_dtype);
+    if (!aligned16(a->Bm) || !aligned16(a->Cm)) return LRNNX_ERR_INVALID_ARG;
+
+    FwdParams p{};
+    p.B = a->B; p.D = a->D; p.N = a->N; p.L = a->L;
+    p.softplus = a->delta_softplus ? 1 : 0;
+    p.u = a->u; p.delta = a->delta; p.z = a->z; p.y = a->y;
+    p.u_sb = a->u_stride_b; p.u_sd = a->u_stride_d;
+    p.dl_sb = a->delta_stride_b; p.dl_sd = a->delta_stride_d;
+    p.z_sb = a->z_stride_b; p.z_sd = a->z_stride_d;
+    p.y_sb = a->y_stride_b; p.y_sd = a->y_stride_d;
+    p.A = a->A; p.Dskip = a->Dskip; p.bias = a->delta_bias; p.x0 = a->x0;
+    p.Bm = a->Bm; p.Cm = a->Cm; p.x_last = a->x_last; p.ckpt = a->ckpt;
+    p.vec = row_vec_ok(a->u, p.u_sb, p.u_sd, es) && row_vec_ok(a->delta, p.dl_sb, p.dl_sd, es) &&
+            row_vec_ok(a->y, p.y_sb, p.y_sd, es) && (!a->z || row_vec_ok(a->z, p.z_sb, p.z_sd, es));
+
+    const int64_t ntiles = cdiv(a->L, fwd_tile_steps(a->io_dtype));
+    const int64_t wgs = (int64_t)a->B * cdiv(a->D, kFwdWaves);
+    bool chunked = false;
+    int nch = 1;
+    if (a->path == LRNNX_PATH_CHUNK_CARRY) {
+        nch = fwd_chunks(a->B, a->D, a->L, a->io_dtype, true);
+        const size_t need = (size_t)2 * a->B * a->D * nch * a->N * sizeof(float);
+        if (!a->workspace || a->workspace_bytes < need) return LRNNX_ERR_WORKSPACE;
+        chunked = true;
+    } else if (a->path == LRNNX_PATH_AUTO && wgs < kNumCU / 2 && ntiles >= 4) {
+        nch = fwd_chunks(a->B, a->D, a->L, a->io_dtype, false);
+        const size_t need = (size_t)2 * a->B * a->D * nch * a->N * sizeof(float);
+        chunked = nch > 1 && a->workspace && a->workspace_bytes >= need;
+        if (!chunked) nch = 1;
+    }
+    hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
+    if (!chunked) {
+        p.mode = MODE_FULL; p.nchunks = 1; p.tiles_per_chunk = ntiles;
+        return launch_ss_fwd(p, a->io_dtype, a->disc, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+    }
+    p.nchunks = nch;
+    p.tiles_per_chunk = cdiv(ntiles, nch);
+    p.nchunks = (int)cdiv(ntiles, p.tiles_per_chunk);      // no empty trailing chunk
+    p.ws_P = reinterpret_cast<float *>(a->workspace);
+    p.ws_S = p.ws_P + (size_t)a->B * a->D * p.nchunks * a->N;
+    FwdParams pa = p;
+    pa.mode = MODE_AGG; pa.ckpt = nullptr; pa.x_last = nullptr;
+    if (launch_ss_fwd(pa, a->io_dtype, a->disc, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    if (launch_ss_carry(p, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    p.mode = MODE_APPLY;
+    return launch_ss_fwd(p, a->io_dtype, a->disc, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+}
+
+int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
+    if (!a || a->struct_size < sizeof(lrnnx_ss_bwd_args)) return LRNNX_ERR_INVALID_ARG;
+    if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
+    if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
+    if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
+    if (!a->u || !a->delta || !a->A || !a->Bm || !a->Cm || !a->dy) return LRNNX_ERR_INVALID_ARG;
+    if (!a->du || !a->ddelta || !a->dA || !a->dBm || !a->dCm) return LRNNX_ERR_INVALID_ARG;
+    if ((a->dz && !a->z) || (a->dD && !a->Dskip) || (a->dbias && !a->delta_bias)) return LRNNX_ERR_INVALID_ARG;
+    if (a->u_stride_b < 0 || a->u_stride_d < 0 || a->delta_stride_b < 0 || a->delta_stride_d < 0 ||
+        a->dy_stride_b < 0 || a->dy_stride_d < 0 || (a->z && (a->z_stride_b < 0 || a->z_stride_d < 0)) ||
+        a->du_stride_b < 0 || a->du_stride_d < a->L || a->ddelta_stride_b < 0 || a->ddelta_stride_d < a->L ||
+        (a->dz && (a->dz_stride_b < 0 || a->dz_stride_d < a->L)))
+        return LRNNX_ERR_INVALID_ARG;
+    if (!supported_n(a->N)) return LRNNX_ERR_UNSUPPORTED;
+    if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
+    if (!aligned16(a->Bm) || !aligned16(a->Cm) || !aligned16(a->dBm) || !aligned16(a->dCm)) return LRNNX_ERR_INVALID_ARG;
+    const size_t es = elem_size(a->io_dtype);
+    const int64_t nck = cdiv(a->L, kCkptInterval);
+    const size_t ck_bytes = (size_t)a->B * a->D * nck * a->N * sizeof(float);
+    if (!a->ckpt && (!a->workspace || a->workspace_bytes < ck_bytes)) return LRNNX_ERR_WORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
+
+    const float *ckpt = a->ckpt;
+    if (!ckpt) {                                   // state-only forward sweep: writes the checkpoints
+        FwdParams f{};
+        f.B = a->B; f.D = a->D; f.N = a->N; f.L = a->L;
+        f.softplus = a->delta_softplus ? 1 : 0;
+        f.u = a->u; f.delta = a->delta;
+        f.u_sb = a->u_stride_b; f.u_sd = a->u_stride_d; f.dl_sb = a->delta_stride_b; f.dl_sd = a->delta_stride_d;
+        f.A = a->A; f.bias = a->delta_bias; f.x0 = a->x0; f.Bm = a->Bm; f.Cm = a->Cm;
+        f.ckpt = reinterpret_cast<float *>(a->workspace);
+        f.vec = row_vec_ok(a->u, f.u_sb, f.u_sd, es) && row_vec_ok(a->delta, f.dl_sb, f.dl_sd, es);
+        f.mode = MODE_CKPT_ONLY; f.nchunks = 1; f.tiles_per_chunk = cdiv(a->L, fwd_tile_steps(a->io_dtype));
+        if (launch_ss_fwd(f, a->io_dtype, a->disc, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+        ckpt = f.ckpt;
+    }
+
+    BwdParams p{};
+    p.B = a->B; p.D = a->D; p.N = a->N; p.L = a->L;
+    p.softplus = a->delta_softplus ? 1 : 0;
+    p.u = a->u; p.delta = a->delta; p.z = a->z; p.dy = a->dy;
+    p.du = a->du; p.ddelta = a->ddelta; p.dz = a->dz;
+    p.u_sb = a->u_stride_b; p.u_sd = a->u_stride_d; p.dl_sb = a->delta_stride_b; p.dl_sd = a->delta_stride_d;
+    p.z_sb = a->z_stride_b; p.z_sd = a->z_stride_d; p.dy_sb = a->dy_stride_b; p.dy_sd = a->dy_stride_d;
+    p.du_sb = a->du_stride_b; p.du_sd = a->du_stride_d; p.dd_sb = a->ddelta_stride_b; p.dd_sd = a->ddelta_stride_d;
+    p.dz_sb = a->dz_stride_b; p.dz_sd = a->dz_stride_d;
+    p.A = a->A; p.Dskip = a->Dskip; p.bias = a->delta_bias; p.x0 = a->x0; p.ckpt = ckpt;
+    p.Bm = a->Bm; p.Cm = a->Cm;
+    p.dA = a->dA; p.dBm = a->dBm; p.dCm = a->dCm; p.dD = a->dD; p.dbias = a->dbias; p.dx0 = a->dx0;
+    p.vec = row_vec_ok(a->u, p.u_sb, p.u_sd, es) && row_vec_ok(a->delta, p.dl_sb, p.dl_sd, es) &&
+            row_vec_ok(a->dy, p.dy_sb, p.dy_sd, es) && (!a->z || row_vec_ok(a->z, p.z_sb, p.z_sd, es)) &&
+            row_vec_ok(a->du, p.du_sb, p.du_sd, es) && row_vec_ok(a->ddelta, p.dd_sb, p.dd_sd, es) &&
+            (!a->dz || row_vec_ok(a->dz, p.dz_sb, p.dz_sd, es));
+    p.G = bwd_channels_per_group(a->B, a->D, a->N, a->L);
+
+    // reduced outputs are accumulated with atomics: clear them on the stream first
+    const int64_t nbc = (int64_t)a->B * a->L * a->N;
+    if (launch_fill_zero(a->dA, (int64_t)a->D * a->N, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    if (launch_fill_zero(a->dBm, nbc, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    if (launch_fill_zero(a->dCm, nbc, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    if (a->dD && launch_fill_zero(a->dD, a->D, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    if (a->dbias && launch_fill_zero(a->dbias, a->D, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    return launch_ss_bwd(p, a->io_dtype, a->disc, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+}
+
+int lrnnx_lti_diag_scan(const lrnnx_lti_args *a) {
+    if (!a || a->struct_size < sizeof(lrnnx_lti_args)) return LRNNX_ERR_INVALID_ARG;
+    if (a->B < 1 || a->P < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
+    if (!a->lambda || !a->v || !a->x) return LRNNX_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(a->v) & 7u) || (reinterpret_cast<uintptr_t>(a->x) & 7u) ||
+        (reinterpret_cast<uintptr_t>(a->lambda) & 7u))
+        return LRNNX_ERR_INVALID_ARG;
+    if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
+    LtiParams p{};
+    p.B = a->B; p.P = a->P; p.L = a->L;
+    p.lambda = reinterpret_cast<const float2 *>(a->lambda);
+    p.v = reinterpret_cast<const float2 *>(a->v);
+    p.x0 = reinterpret_cast<const float2 *>(a->x0);
+    p.x = reinterpret_cast<float2 *>(a->x);
+    p.x_last = reinterpret_cast<float2 *>(a->x_last);
+    int nch = lti_chunks(a->B, a->P, a->L);
+    p.chunk = cdiv(a->L, nch);
+    p.nchunks = (int)cdiv(a->L, p.chunk);
+    if (p.nchunks > 1) {
+        const size_t need = (size_t)a->B * p.nchunks * a->P * 2 * sizeof(float);
+        if (!a->workspace || a->workspace_bytes < need) return LRNNX_ERR_WORKSPACE;
+        p.ws_S = reinterpret_cast<float2 *>(a->workspace);
+    }
+    return launch_lti(p, reinterpret_cast<hipStream_t>(a->stream)) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,61 @@
+// Host-visible parameter blocks and launcher declarations of the scan kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lrnnx {
+
+constexpr int64_t kCkptInterval = 256;   // steps between state checkpoints (public: lrnnx_ckpt_interval)
+
+enum : int { MODE_FULL = 0, MODE_AGG = 1, MODE_APPLY = 2, MODE_CKPT_ONLY = 3 };
+
+struct FwdParams {
+    int B, D, N;
+    int64_t L;
+    int softplus, mode, vec;
+    int nchunks;
+    int64_t tiles_per_chunk;
+    const void *u, *delta, *z;
+    void *y;
+    int64_t u_sb, u_sd, dl_sb, dl_sd, z_sb, z_sd, y_sb, y_sd;
+    const float *A, *Dskip, *bias, *x0;
+    const void *Bm, *Cm;
+    float *x_last, *ckpt;
+    float *ws_P, *ws_S;      // [B,D,nchunks,N] chunk aggregates; ws_S is overwritten with the chunk carry-in
+};
+
+struct BwdParams {
+    int B, D, N;
+    int64_t L;
+    int softplus, vec;
+    int G;                   // channels per workgroup
+    const void *u, *delta, *z, *dy;
+    void *du, *ddelta, *dz;
+    int64_t u_sb, u_sd, dl_sb, dl_sd, z_sb, z_sd, dy_sb, dy_sd, du_sb, du_sd, dd_sb, dd_sd, dz_sb, dz_sd;
+    const float *A, *Dskip, *bias, *x0, *ckpt;
+    const void *Bm, *Cm;
+    float *dA, *dBm, *dCm, *dD, *dbias, *dx0;
+};
+
+struct LtiParams {
+    int B, P;
+    int64_t L;
+    int nchunks;
+    int64_t chunk;           // time steps per chunk
+    const float2 *lambda, *v, *x0;
+    float2 *x, *x_last;
+    float2 *ws_S;            // [B,nchunks,P] chunk end states, overwritten with chunk carry-ins
+};
+
+// Each launcher returns hipSuccess or the launch error; it validates nothing.
+hipError_t launch_ss_fwd(const FwdParams &p, int io_dtype, int disc, hipStream_t s);
+hipError_t launch_ss_carry(const FwdParams &p, hipStream_t s);
+hipError_t launch_ss_bwd(const BwdParams &p, int io_dtype, int disc, hipStream_t s);
+hipError_t launch_lti(const LtiParams &p, hipStream_t s);
+hipError_t launch_fill_zero(float *ptr, int64_t count, hipStream_t s);
+
+// Tile geometry the host needs for grids, workspaces and the choice of path.
+int fwd_tile_steps(int io_dtype);            // time steps one workgroup covers per tile
+int bwd_channels_per_group(int B, int D, int N, int64_t L);
+
+}  // namespace lrnnx

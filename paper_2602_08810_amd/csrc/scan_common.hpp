@@ -1,0 +1,255 @@
+// Device-side building blocks shared by the gfx950 scan kernels: I/O element access,
+// transcendental helpers, the fused discretisations (schemes named in Sec. 3 of the
+// paper) and the wavefront scans over affine pairs.
+//
+// The recurrence x_k = a_k x_{k-1} + b_k (Eq. 2, line 1, diagonal A) is the
+// composition of affine maps (a, b): x -> a x + b.  Two maps compose as
+//     (a2, b2) o (a1, b1) = (a2 a1, a2 b1 + b2),
+// which is associative, so a wavefront can take an inclusive prefix over its 64
+// lanes in six cross-lane steps.  Out-of-range lanes hold the identity (1, 0).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lrnnx {
+
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct bf16_t { unsigned short v; };
+
+// ---------------------------------------------------------------- bit casts and cross-lane moves
+__device__ __forceinline__ int f2i(float x) { return __builtin_bit_cast(int, x); }
+__device__ __forceinline__ float i2f(int x) { return __builtin_bit_cast(float, x); }
+
+// DPP move: lanes whose source lane does not exist (or whose row is masked off) keep `old`.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp(float old, float src) {
+    return i2f(__builtin_amdgcn_update_dpp(f2i(old), f2i(src), CTRL, ROW_MASK, 0xF, false));
+}
+constexpr int DPP_ROW_SHL1 = 0x101, DPP_ROW_SHR1 = 0x111;
+constexpr int DPP_WAVE_SHL1 = 0x130, DPP_WAVE_SHR1 = 0x138;
+constexpr int DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
+
+__device__ __forceinline__ float readlane(float x, int lane) { return i2f(__builtin_amdgcn_readlane(f2i(x), lane)); }
+__device__ __forceinline__ float bpermute(int src_lane, float x) { return i2f(__builtin_amdgcn_ds_bpermute(src_lane << 2, f2i(x))); }
+
+// ---------------------------------------------------------------- transcendentals (fp32, ~1 ulp hardware ops)
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32
+__device__ __forceinline__ float log2_fast(float x) { return __builtin_amdgcn_logf(x); }    // v_log_f32
+__device__ __forceinline__ float rcp_fast(float x) { return __builtin_amdgcn_rcpf(x); }     // v_rcp_f32
+
+// softplus(s) = log(1 + e^s) and its derivative sigmoid(s) = e^s / (1 + e^s).
+// For s > 20 both saturate (softplus = s to 2e-9); for small e^s the logarithm is taken
+// by its series so that the result keeps full relative accuracy.
+__device__ __forceinline__ void softplus_sigmoid(float s, float &sp, float &sg) {
+    float w = exp2_fast(fminf(s, 20.0f) * kLog2e);
+    float r = rcp_fast(1.0f + w);
+    float series = w * (1.0f - w * (0.5f - w * (0.33333334f - w * 0.25f)));
+    float lg = log2_fast(1.0f + w) * kLn2;
+    float v = w < 0.015625f ? series : lg;
+    sp = s > 20.0f ? s : v;
+    sg = s > 20.0f ? 1.0f : w * r;
+}
+__device__ __forceinline__ float sigmoid_fast(float zz) { return rcp_fast(1.0f + exp2_fast(-zz * kLog2e)); }
+
+// e^x - 1 with full relative accuracy near 0 (needed by the exact zero-order hold).
+__device__ __forceinline__ float expm1_acc(float x, float ex) {
+    float p = x * (1.0f + x * (0.5f + x * (0.16666667f + x * (0.041666668f + x * 0.008333334f))));
+    return fabsf(x) < 0.125f ? p : ex - 1.0f;
+}
+
+// ---------------------------------------------------------------- fused discretisation (Sec. 3 schemes)
+enum : int { DISC_ZOH_S6 = 0, DISC_ZOH = 1, DISC_BILINEAR = 2, DISC_DIRAC = 3 };
+
+// Per-(d,n) constants derived once from A[d,n].
+struct ACoef {
+    float A;      // A[d,n]
+    float A2;     // A * log2(e), so that exp(dt*A) = exp2(dt*A2)
+    float rA;     // 1/A (exact ZOH only; A == 0 handled by the caller's formula below)
+};
+__device__ __forceinline__ ACoef make_acoef(float A) {
+    ACoef c; c.A = A; c.A2 = A * kLog2e; c.rA = (A != 0.0f) ? 1.0f / A : 0.0f; return c;
+}
+
+// State multiplier a and input gain g of one step.
+template <int DISC>
+__device__ __forceinline__ void disc_ag(float dt, const ACoef &c, float &a, float &g) {
+    if constexpr (DISC == DISC_BILINEAR) {
+        float h = 0.5f * dt * c.A;
+        float q = rcp_fast(1.0f - h);
+        q = q * (2.0f - (1.0f - h) * q);              // one Newton step on the reciprocal
+        a = (1.0f + h) * q;
+        g = dt * q;
+    } else {
+        a = exp2_fast(dt * c.A2);
+        if constexpr (DISC == DISC_ZOH_S6) g = dt;
+        else if constexpr (DISC == DISC_DIRAC) g = 1.0f;
+        else g = (c.A != 0.0f) ? expm1_acc(dt * c.A, a) * c.rA : dt;
+    }
+}
+
+// Partials (da/ddt, da/dA, dg/ddt, dg/dA) given a, g of the same step.
+template <int DISC>
+__device__ __forceinline__ void disc_partials(float dt, const ACoef &c, float a, float g,
+                                              float &a_t, float &a_A, float &g_t, float &g_A) {
+    if constexpr (DISC == DISC_BILINEAR) {
+        float q = (dt != 0.0f) ? g / dt : 1.0f;       // q = 1/(1 - dt A/2)
+        float q2 = q * q;
+        a_t = c.A * q2; a_A = dt * q2; g_t = q2; g_A = 0.5f * dt * dt * q2;
+    } else {
+        a_t = c.A * a; a_A = dt * a;
+        if constexpr (DISC == DISC_ZOH_S6) { g_t = 1.0f; g_A = 0.0f; }
+        else if constexpr (DISC == DISC_DIRAC) { g_t = 0.0f; g_A = 0.0f; }
+        else {
+            g_t = a;
+            // (dt A a - (a - 1)) / A^2 = (dt a - g) / A ; near A dt -> 0 it tends to dt^2/2
+            float x = dt * c.A;
+            float small = dt * dt * (0.5f + x * (0.33333334f + x * (0.125f + x * 0.033333335f)));
+            g_A = (fabsf(x) < 0.125f) ? small : (dt * a - g) * c.rA;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- wavefront scans over affine pairs
+// One Hillis-Steele step on the pair held in (P,S): the pair of the lane named by the DPP
+// control is composed in from the earlier side.  Both updates are single VALU instructions
+// with a DPP source operand; a lane whose source lane does not exist, or whose row is
+// masked off, is left unchanged (= composed with the identity).  The leading s_nop covers
+// the two wait states a DPP read needs after a VALU write of the same register.
+#define LRNNX_PAIR_STEP(P, S, CTRL)                                                   \
+    asm("s_nop 1\n\t"                                                                 \
+        "v_fmac_f32_dpp %0, %0, %1 " CTRL "\n\t"                                      \
+        "v_mul_f32_dpp %1, %1, %1 " CTRL                                              \
+        : "+v"(S), "+v"(P))
+
+// Inclusive prefix over the 64 lanes, lane 0 first:  (P,S)_i <- (P,S)_i o ... o (P,S)_0.
+__device__ __forceinline__ void wave_scan_fwd(float &P, float &S) {
+    LRNNX_PAIR_STEP(P, S, "row_shr:1 row_mask:0xf bank_mask:0xf");
+    LRNNX_PAIR_STEP(P, S, "row_shr:2 row_mask:0xf bank_mask:0xf");
+    LRNNX_PAIR_STEP(P, S, "row_shr:4 row_mask:0xf bank_mask:0xf");
+    LRNNX_PAIR_STEP(P, S, "row_shr:8 row_mask:0xf bank_mask:0xf");
+    LRNNX_PAIR_STEP(P, S, "row_bcast:15 row_mask:0xa bank_mask:0xf");   // lane 15 of rows 0,2 -> rows 1,3
+    LRNNX_PAIR_STEP(P, S, "row_bcast:31 row_mask:0xc bank_mask:0xf");   // lane 31 -> rows 2,3
+}
+
+// Inclusive suffix over the 64 lanes, lane 63 first (time runs right to left):
+//   (P,S)_i <- (P,S)_i o (P,S)_{i+1} o ... o (P,S)_63.
+__device__ __forceinline__ void wave_scan_rev(float &P, float &S, int lane) {
+    LRNNX_PAIR_STEP(P, S, "row_shl:1 row_mask:0xf bank_mask:0xf");
+    LRNNX_PAIR_STEP(P, S, "row_shl:2 row_mask:0xf bank_mask:0xf");
+    LRNNX_PAIR_STEP(P, S, "row_shl:4 row_mask:0xf bank_mask:0xf");
+    LRNNX_PAIR_STEP(P, S, "row_shl:8 row_mask:0xf bank_mask:0xf");
+    {   // rows 0 and 2 take the suffix held by the first lane of the next row
+        const int src = ((lane & 0x30) + 16) & 63;
+        float Pp = bpermute(src, P), Sp = bpermute(src, S);
+        const bool take = ((lane >> 4) & 1) == 0;
+        Pp = take ? Pp : 1.0f; Sp = take ? Sp : 0.0f;
+        S = __builtin_fmaf(P, Sp, S); P = P * Pp;
+    }
+    {   // rows 0 and 1 take the suffix held by lane 32
+        float Pp = bpermute(32, P), Sp = bpermute(32, S);
+        const bool take = lane < 32;
+        Pp = take ? Pp : 1.0f; Sp = take ? Sp : 0.0f;
+        S = __builtin_fmaf(P, Sp, S); P = P * Pp;
+    }
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+    v += dpp<0x111>(0.0f, v);
+    v += dpp<0x112>(0.0f, v);
+    v += dpp<0x114>(0.0f, v);
+    v += dpp<0x118>(0.0f, v);
+    v += dpp<DPP_ROW_BCAST15, 0xA>(0.0f, v);
+    v += dpp<DPP_ROW_BCAST31, 0xC>(0.0f, v);
+    return readlane(v, 63);
+}
+
+// ---------------------------------------------------------------- I/O element access
+template <typename IO> struct io_traits;
+template <> struct io_traits<float> {
+    static constexpr int EPC = 4;                                  // elements per 16-byte chunk
+    __device__ static __forceinline__ float get(const float *p, int64_t i) { return p[i]; }
+    __device__ static __forceinline__ void put(float *p, int64_t i, float v) { p[i] = v; }
+    __device__ static __forceinline__ void unpack(const uint4 &r, float *o) {
+        o[0] = i2f(r.x); o[1] = i2f(r.y); o[2] = i2f(r.z); o[3] = i2f(r.w);
+    }
+    __device__ static __forceinline__ uint4 pack(const float *v) {
+        return make_uint4(f2i(v[0]), f2i(v[1]), f2i(v[2]), f2i(v[3]));
+    }
+};
+typedef __bf16 bf16x2_native __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {   // round to nearest even
+    floatx2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_native));
+}
+template <> struct io_traits<bf16_t> {
+    static constexpr int EPC = 8;
+    __device__ static __forceinline__ float get(const bf16_t *p, int64_t i) { return i2f((int)p[i].v << 16); }
+    __device__ static __forceinline__ void put(bf16_t *p, int64_t i, float v) {
+        p[i].v = (unsigned short)(pack_bf16x2(v, 0.0f) & 0xFFFFu);
+    }
+    __device__ static __forceinline__ void unpack(const uint4 &r, float *o) {
+        o[0] = i2f(r.x << 16); o[1] = i2f(r.x & 0xFFFF0000u);
+        o[2] = i2f(r.y << 16); o[3] = i2f(r.y & 0xFFFF0000u);
+        o[4] = i2f(r.z << 16); o[5] = i2f(r.z & 0xFFFF0000u);
+        o[6] = i2f(r.w << 16); o[7] = i2f(r.w & 0xFFFF0000u);
+    }
+    __device__ static __forceinline__ uint4 pack(const float *v) {
+        return make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
+                          pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+    }
+};
+
+// A lane's CNT consecutive elements row[l .. l+CNT), zero where l+i >= L.  `vec` says that
+// row + l is 16-byte aligned whenever l is a multiple of EPC (checked on the host).
+template <typename IO, int CNT>
+__device__ __forceinline__ void load_seg(const IO *row, int64_t l, int64_t L, bool vec, float *out) {
+    constexpr int EPC = io_traits<IO>::EPC;
+    static_assert(CNT % EPC == 0, "segment must be whole 16-byte chunks");
+#pragma unroll
+    for (int c = 0; c < CNT / EPC; ++c) {
+        int64_t lc = l + c * EPC;
+        if (vec && lc + EPC <= L) {
+            uint4 r = *reinterpret_cast<const uint4 *>(row + lc);
+            io_traits<IO>::unpack(r, out + c * EPC);
+        } else {
+#pragma unroll
+            for (int i = 0; i < EPC; ++i) out[c * EPC + i] = (lc + i < L) ? io_traits<IO>::get(row, lc + i) : 0.0f;
+        }
+    }
+}
+template <typename IO, int CNT>
+__device__ __forceinline__ void store_seg(IO *row, int64_t l, int64_t L, bool vec, const float *v) {
+    constexpr int EPC = io_traits<IO>::EPC;
+#pragma unroll
+    for (int c = 0; c < CNT / EPC; ++c) {
+        int64_t lc = l + c * EPC;
+        if (vec && lc + EPC <= L) {
+            *reinterpret_cast<uint4 *>(row + lc) = io_traits<IO>::pack(v + c * EPC);
+        } else {
+#pragma unroll
+            for (int i = 0; i < EPC; ++i) if (lc + i < L) io_traits<IO>::put(row, lc + i, v[c * EPC + i]);
+        }
+    }
+}
+
+// CNT contiguous elements starting at p (p aligned to min(16, CNT*sizeof(IO)) bytes), as floats.
+template <typename IO, int CNT>
+__device__ __forceinline__ void load_row(const IO *p, float *out) {
+    constexpr int EPC = io_traits<IO>::EPC;
+    if constexpr (CNT % EPC == 0) {
+#pragma unroll
+        for (int c = 0; c < CNT / EPC; ++c) {
+            uint4 r = reinterpret_cast<const uint4 *>(p)[c];
+            io_traits<IO>::unpack(r, out + c * EPC);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < CNT; ++i) out[i] = io_traits<IO>::get(p, i);
+    }
+}
+
+}  // namespace lrnnx

@@ -1,0 +1,253 @@
+// Forward selective scan for gfx950 (Eq. 2 of the paper with diagonal, input-dependent
+// A(k), B(k), C(k); S6 row of Table 1; discretisation fused in, Sec. 3).
+//
+// Mapping.  Time runs along the lanes: lane i of a wavefront owns T consecutive steps
+// of one (b,d) row, so the [B,D,L] tensors are read and written with 16-byte accesses
+// that are contiguous across the wavefront.  One wavefront = one channel; the W
+// wavefronts of a workgroup are W channels of the same batch entry walking the same
+// time tile (64*T steps), so the tile of Bm/Cm (shared by all channels) is staged once
+// per workgroup into LDS as fp32, in an order that makes every later read a
+// conflict-free ds_read_b128.  States never leave registers (Sec. 3: no hidden-state
+// materialisation): for each n the lane folds its T steps into one affine pair, the
+// wavefront takes an inclusive prefix over the 64 pairs with DPP moves, and the lane
+// replays its steps from the carried-in state, accumulating y = sum_n C x on the fly.
+// The state after the tile is lane 63's, broadcast through a scalar register to the
+// next tile of the same row.
+//
+// The same kernel serves the three launches of the chunk-carry path for long L / few
+// rows (blockIdx.z = chunk): MODE_AGG returns each chunk's affine aggregate,
+// k_ss_carry chains them, MODE_APPLY reruns the chunk from its true carry-in.
+#include "kernels.hpp"
+#include "scan_common.hpp"
+
+namespace lrnnx {
+
+template <typename IO, int N, int T, int W, int DISC, bool WANT_Y>
+__global__ __launch_bounds__(W * 64) void k_ss_fwd(const FwdParams p) {
+    constexpr int TQ = T / 4;
+    constexpr int QS = 256 + (TQ > 1 ? 32 / TQ : 0);   // floats per quarter-plane, padded against bank conflicts on staging
+    constexpr int PLANE = TQ * QS;                     // floats per state index n
+    constexpr int TILE = 64 * T;
+    __shared__ __attribute__((aligned(16))) float sB[N * PLANE];
+    __shared__ __attribute__((aligned(16))) float sC[N * PLANE];
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int b = blockIdx.y;
+    const int d_raw = blockIdx.x * W + w;
+    const bool active = d_raw < p.D;
+    const int d = active ? d_raw : p.D - 1;
+    const int chunk = blockIdx.z;
+    const int64_t L = p.L;
+    const int64_t ntiles = (L + TILE - 1) / TILE;
+    const int64_t tile0 = (int64_t)chunk * p.tiles_per_chunk;
+    const int64_t tile1 = (tile0 + p.tiles_per_chunk < ntiles) ? tile0 + p.tiles_per_chunk : ntiles;
+    const int64_t row = (int64_t)b * p.D + d;
+    const bool vec = p.vec != 0;
+    const int mode = p.mode;
+
+    const IO *urow = reinterpret_cast<const IO *>(p.u) + b * p.u_sb + d * p.u_sd;
+    const IO *drow = reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd;
+    const IO *zrow = p.z ? reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd : nullptr;
+    IO *yrow = p.y ? reinterpret_cast<IO *>(p.y) + b * p.y_sb + d * p.y_sd : nullptr;
+    const IO *Bm = reinterpret_cast<const IO *>(p.Bm) + (int64_t)b * L * N;
+    const IO *Cm = reinterpret_cast<const IO *>(p.Cm) + (int64_t)b * L * N;
+
+    ACoef ac[N];
+    float xc[N], Pc[N];
+#pragma unroll
+    for (int n = 0; n < N; ++n) {
+        ac[n] = make_acoef(p.A[d * N + n]);
+        Pc[n] = 1.0f;
+        if (mode == MODE_APPLY) xc[n] = p.ws_S[(row * p.nchunks + chunk) * N + n];
+        else if (mode == MODE_AGG) xc[n] = 0.0f;
+        else xc[n] = p.x0 ? p.x0[row * N + n] : 0.0f;
+    }
+    const float Dsk = p.Dskip ? p.Dskip[d] : 0.0f;
+    const float bias = p.bias ? p.bias[d] : 0.0f;
+    const int64_t nck = (L + kCkptInterval - 1) / kCkptInterval;
+
+    for (int64_t tile = tile0; tile < tile1; ++tile) {
+        const int64_t l0 = tile * TILE;
+        const int64_t ll = l0 + lane * T;
+
+        // ---- stage the Bm/Cm tile (all wavefronts), fp32, layout [n][t/4][lane][t%4]
+        __syncthreads();
+        for (int r = threadIdx.x; r < TILE; r += W * 64) {
+            float bv[N], cv[N];
+            const int64_t l = l0 + r;
+            if (l < L) {
+                load_row<IO, N>(Bm + l * N, bv);
+                load_row<IO, N>(Cm + l * N, cv);
+            } else {
+#pragma unroll
+                for (int k = 0; k < N; ++k) { bv[k] = 0.0f; cv[k] = 0.0f; }
+            }
+            const int off = ((r % T) / 4) * QS + (r / T) * 4 + (r % 4);
+#pragma unroll
+            for (int k = 0; k < N; ++k) { sB[k * PLANE + off] = bv[k]; sC[k * PLANE + off] = cv[k]; }
+        }
+        __syncthreads();
+        if (!active) continue;
+
+        // ---- this lane's T steps of u and Delta
+        float uv[T], dl[T], du[T], yv[T];
+        load_seg<IO, T>(urow, ll, L, vec, uv);
+        load_seg<IO, T>(drow, ll, L, vec, dl);
+        float sum_dl = 0.0f;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            float s = dl[t] + bias, sp, sg;
+            if (p.softplus) softplus_sigmoid(s, sp, sg); else sp = s;
+            dl[t] = (ll + t < L) ? sp : 0.0f;         // steps past the end are the identity map (a = 1, b = 0)
+            sum_dl += dl[t];
+            du[t] = dl[t] * uv[t];
+            yv[t] = Dsk * uv[t];
+        }
+
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            float Bv[T], Cv[T], a[T], bb[T];
+#pragma unroll
+            for (int q = 0; q < TQ; ++q) {
+                float4 vb = *reinterpret_cast<const float4 *>(&sB[n * PLANE + q * QS + lane * 4]);
+                float4 vc = *reinterpret_cast<const float4 *>(&sC[n * PLANE + q * QS + lane * 4]);
+                Bv[4 * q] = vb.x; Bv[4 * q + 1] = vb.y; Bv[4 * q + 2] = vb.z; Bv[4 * q + 3] = vb.w;
+                Cv[4 * q] = vc.x; Cv[4 * q + 1] = vc.y; Cv[4 * q + 2] = vc.z; Cv[4 * q + 3] = vc.w;
+            }
+            float P = 1.0f, S = 0.0f;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                float g;
+                disc_ag<DISC>(dl[t], ac[n], a[t], g);
+                if constexpr (DISC == DISC_ZOH_S6) bb[t] = du[t] * Bv[t];
+                else if constexpr (DISC == DISC_DIRAC) bb[t] = uv[t] * Bv[t];
+                else bb[t] = g * uv[t] * Bv[t];
+                S = __builtin_fmaf(a[t], S, bb[t]);
+                if constexpr (DISC == DISC_BILINEAR) P *= a[t];
+            }
+            if constexpr (DISC != DISC_BILINEAR) P = exp2_fast(sum_dl * ac[n].A2);   // product of the T multipliers
+            wave_scan_fwd(P, S);
+            const float Pex = dpp<DPP_WAVE_SHR1>(1.0f, P);
+            const float Sex = dpp<DPP_WAVE_SHR1>(0.0f, S);
+            float x = __builtin_fmaf(Pex, xc[n], Sex);               // state entering this lane's first step
+            if (p.ckpt && (ll % kCkptInterval) == 0 && ll < L)
+                p.ckpt[(row * nck + ll / kCkptInterval) * N + n] = x;
+            const float xe = __builtin_fmaf(P, xc[n], S);            // state after this lane's last step
+            xc[n] = readlane(xe, 63);
+            if constexpr (!WANT_Y) Pc[n] *= readlane(P, 63);
+            if constexpr (WANT_Y) {
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    x = __builtin_fmaf(a[t], x, bb[t]);
+                    yv[t] = __builtin_fmaf(Cv[t], x, yv[t]);
+                }
+            }
+        }
+
+        if constexpr (WANT_Y) {
+            if (zrow) {
+                float zv[T];
+                load_seg<IO, T>(zrow, ll, L, vec, zv);
+#pragma unroll
+                for (int t = 0; t < T; ++t) yv[t] *= zv[t] * sigmoid_fast(zv[t]);
+            }
+            store_seg<IO, T>(yrow, ll, L, vec, yv);
+        }
+    }
+
+    if (active && lane == 0) {
+        if (mode == MODE_AGG) {
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                p.ws_P[(row * p.nchunks + chunk) * N + n] = Pc[n];
+                p.ws_S[(row * p.nchunks + chunk) * N + n] = xc[n];
+            }
+        } else if (p.x_last && tile1 == ntiles) {
+#pragma unroll
+            for (int n = 0; n < N; ++n) p.x_last[row * N + n] = xc[n];
+        }
+    }
+}
+
+// Chains the chunk aggregates of one (b,d,n): carry-in of chunk c+1 = P_c * carry-in of chunk c + S_c.
+// ws_S[c] is replaced by the carry-in of chunk c.
+__global__ void k_ss_carry(const FwdParams p) {
+    const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    const int64_t total = (int64_t)p.B * p.D * p.N;
+    if (i >= total) return;
+    const int64_t row = i / p.N;
+    const int n = (int)(i % p.N);
+    float x = p.x0 ? p.x0[i] : 0.0f;
+    for (int c = 0; c < p.nchunks; ++c) {
+        const int64_t j = (row * p.nchunks + c) * p.N + n;
+        const float P = p.ws_P[j], S = p.ws_S[j];
+        p.ws_S[j] = x;
+        x = __builtin_fmaf(P, x, S);
+    }
+}
+
+__global__ void k_fill_zero(float *ptr, int64_t count) {
+    int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) ptr[i] = 0.0f;
+}
+
+// ---------------------------------------------------------------- launchers
+constexpr int kFwdT = 8;
+constexpr int kFwdW = 8;
+
+int fwd_tile_steps(int) { return 64 * kFwdT; }
+
+template <typename IO, int N, int DISC>
+static hipError_t launch_fwd_n(const FwdParams &p, hipStream_t s) {
+    dim3 grid((p.D + kFwdW - 1) / kFwdW, p.B, p.nchunks);
+    if (p.mode == MODE_FULL || p.mode == MODE_APPLY)
+        hipLaunchKernelGGL((k_ss_fwd<IO, N, kFwdT, kFwdW, DISC, true>), grid, dim3(kFwdW * 64), 0, s, p);
+    else
+        hipLaunchKernelGGL((k_ss_fwd<IO, N, kFwdT, kFwdW, DISC, false>), grid, dim3(kFwdW * 64), 0, s, p);
+    return hipGetLastError();
+}
+
+template <typename IO, int DISC>
+static hipError_t launch_fwd_disc(const FwdParams &p, hipStream_t s) {
+    switch (p.N) {
+        case 1: return launch_fwd_n<IO, 1, DISC>(p, s);
+        case 2: return launch_fwd_n<IO, 2, DISC>(p, s);
+        case 4: return launch_fwd_n<IO, 4, DISC>(p, s);
+        case 8: return launch_fwd_n<IO, 8, DISC>(p, s);
+        case 16: return launch_fwd_n<IO, 16, DISC>(p, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+template <typename IO>
+static hipError_t launch_fwd_io(const FwdParams &p, int disc, hipStream_t s) {
+    switch (disc) {
+        case DISC_ZOH_S6: return launch_fwd_disc<IO, DISC_ZOH_S6>(p, s);
+        case DISC_ZOH: return launch_fwd_disc<IO, DISC_ZOH>(p, s);
+        case DISC_BILINEAR: return launch_fwd_disc<IO, DISC_BILINEAR>(p, s);
+        case DISC_DIRAC: return launch_fwd_disc<IO, DISC_DIRAC>(p, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_ss_fwd(const FwdParams &p, int io_dtype, int disc, hipStream_t s) {
+    return io_dtype == 1 ? launch_fwd_io<bf16_t>(p, disc, s) : launch_fwd_io<float>(p, disc, s);
+}
+
+hipError_t launch_ss_carry(const FwdParams &p, hipStream_t s) {
+    const int64_t total = (int64_t)p.B * p.D * p.N;
+    hipLaunchKernelGGL(k_ss_carry, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(float *ptr, int64_t count, hipStream_t s) {
+    if (count <= 0) return hipSuccess;
+    int64_t blocks = (count + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)blocks), dim3(256), 0, s, ptr, count);
+    return hipGetLastError();
+}
+
+}  // namespace lrnnx

@@ -1,0 +1,57 @@
+"""CPU check: the built C-ABI library loads and exports every symbol include/lrnnx.h declares; host-only queries work."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2602_08810_amd", "liblrnnx.so")
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "lrnnx.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lrnnx_[a-z_0-9]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        pytest.skip("liblrnnx.so not built (run python -m paper_2602_08810_amd.build)")
+    return ctypes.CDLL(LIB)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert {"lrnnx_selective_scan_fwd", "lrnnx_selective_scan_bwd", "lrnnx_lti_diag_scan"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in lrnnx.h but not exported"
+
+
+def test_host_queries(lib):
+    lib.lrnnx_workspace_bytes.argtypes = [ctypes.c_int] + [ctypes.c_int64] * 4 + [ctypes.c_int]
+    lib.lrnnx_workspace_bytes.restype = ctypes.c_size_t
+    lib.lrnnx_ckpt_interval.restype = ctypes.c_int64
+    lib.lrnnx_status_string.restype = ctypes.c_char_p
+    I = lib.lrnnx_ckpt_interval()
+    assert I > 0
+    assert lib.lrnnx_workspace_bytes(1, 2, 3, 16, 1000, 1) == 2 * 3 * ((1000 + I - 1) // I) * 16 * 4
+    assert lib.lrnnx_workspace_bytes(0, 1, 2048, 16, 65536, 1) > 0
+    assert lib.lrnnx_workspace_bytes(0, 1, 8, 3, 64, 1) == 0          # unsupported N
+    assert lib.lrnnx_workspace_bytes(2, 4, 256, 0, 4096, 0) > 0
+    assert lib.lrnnx_status_string(0) == b"ok" and lib.lrnnx_status_string(3).startswith(b"workspace")
+    assert lib.lrnnx_version() >= 100
+
+
+def test_null_and_bad_struct_are_rejected_without_a_gpu(lib):
+    """Argument errors are detected on the host before anything touches the device."""
+    lib.lrnnx_selective_scan_fwd.argtypes = [ctypes.c_void_p]
+    lib.lrnnx_selective_scan_bwd.argtypes = [ctypes.c_void_p]
+    lib.lrnnx_lti_diag_scan.argtypes = [ctypes.c_void_p]
+    assert lib.lrnnx_selective_scan_fwd(None) == 1
+    assert lib.lrnnx_selective_scan_bwd(None) == 1
+    assert lib.lrnnx_lti_diag_scan(None) == 1
+    buf = (ctypes.c_char * 512)()                                       # struct_size = 0
+    assert lib.lrnnx_selective_scan_fwd(ctypes.addressof(buf)) == 1
+    assert lib.lrnnx_lti_diag_scan(ctypes.addressof(buf)) == 1
