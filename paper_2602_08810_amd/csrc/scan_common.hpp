@@ -33,6 +33,10 @@ constexpr int DPP_WAVE_SHL1 = 0x130, DPP_WAVE_SHR1 = 0x138;
 constexpr int DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
 
 __device__ __forceinline__ float readlane(float x, int lane) { return i2f(__builtin_amdgcn_readlane(f2i(x), lane)); }
+// copy of `old` with lane `lane` replaced by the (wave-uniform) value v
+__device__ __forceinline__ float writelane(float old, float v, int lane) {
+    return ((int)(threadIdx.x & 63) == lane) ? v : old;
+}
 __device__ __forceinline__ float bpermute(int src_lane, float x) { return i2f(__builtin_amdgcn_ds_bpermute(src_lane << 2, f2i(x))); }
 
 // ---------------------------------------------------------------- transcendentals (fp32, ~1 ulp hardware ops)
@@ -69,8 +73,11 @@ struct ACoef {
     float A2;     // A * log2(e), so that exp(dt*A) = exp2(dt*A2)
     float rA;     // 1/A (exact ZOH only; A == 0 handled by the caller's formula below)
 };
+template <int DISC>
 __device__ __forceinline__ ACoef make_acoef(float A) {
-    ACoef c; c.A = A; c.A2 = A * kLog2e; c.rA = (A != 0.0f) ? 1.0f / A : 0.0f; return c;
+    ACoef c; c.A = A; c.A2 = A * kLog2e;
+    if constexpr (DISC == 1) c.rA = (A != 0.0f) ? 1.0f / A : 0.0f; else c.rA = 0.0f;
+    return c;
 }
 
 // State multiplier a and input gain g of one step.
@@ -236,19 +243,65 @@ __device__ __forceinline__ void store_seg(IO *row, int64_t l, int64_t L, bool ve
     }
 }
 
-// CNT contiguous elements starting at p (p aligned to min(16, CNT*sizeof(IO)) bytes), as floats.
+// CNT contiguous elements starting at p, as floats.  p must be aligned to min(16, CNT*sizeof(IO)) bytes
+// (CNT*sizeof(IO) is a power of two in every use).
 template <typename IO, int CNT>
 __device__ __forceinline__ void load_row(const IO *p, float *out) {
     constexpr int EPC = io_traits<IO>::EPC;
-    if constexpr (CNT % EPC == 0) {
+    constexpr int BYTES = CNT * (16 / EPC);
+    if constexpr (BYTES % 16 == 0) {
 #pragma unroll
         for (int c = 0; c < CNT / EPC; ++c) {
             uint4 r = reinterpret_cast<const uint4 *>(p)[c];
             io_traits<IO>::unpack(r, out + c * EPC);
         }
+    } else if constexpr (BYTES == 8) {
+        uint2 r = *reinterpret_cast<const uint2 *>(p);
+        float tmp[EPC];
+        io_traits<IO>::unpack(make_uint4(r.x, r.y, 0u, 0u), tmp);
+#pragma unroll
+        for (int i = 0; i < CNT; ++i) out[i] = tmp[i];
+    } else if constexpr (BYTES == 4) {
+        uint32_t r = *reinterpret_cast<const uint32_t *>(p);
+        float tmp[EPC];
+        io_traits<IO>::unpack(make_uint4(r, 0u, 0u, 0u), tmp);
+#pragma unroll
+        for (int i = 0; i < CNT; ++i) out[i] = tmp[i];
     } else {
 #pragma unroll
         for (int i = 0; i < CNT; ++i) out[i] = io_traits<IO>::get(p, i);
+    }
+}
+
+// CNT (1, 2, 4 or 8) consecutive elements row[l .. l+CNT) with zero fill past L; `vec` as in load_seg
+// (then row + l is aligned to CNT*sizeof(IO) bytes whenever l is a multiple of CNT).
+template <typename IO, int CNT>
+__device__ __forceinline__ void load_few(const IO *row, int64_t l, int64_t L, bool vec, float *out) {
+    if (vec && l + CNT <= L) {
+        load_row<IO, CNT>(row + l, out);
+    } else {
+#pragma unroll
+        for (int i = 0; i < CNT; ++i) out[i] = (l + i < L) ? io_traits<IO>::get(row, l + i) : 0.0f;
+    }
+}
+template <typename IO, int CNT>
+__device__ __forceinline__ void store_few(IO *row, int64_t l, int64_t L, bool vec, const float *v) {
+    constexpr int EPC = io_traits<IO>::EPC;
+    constexpr int BYTES = CNT * (16 / EPC);
+    if (vec && l + CNT <= L && BYTES % 16 == 0) {
+#pragma unroll
+        for (int c = 0; c < BYTES / 16; ++c)
+            reinterpret_cast<uint4 *>(row + l)[c] = io_traits<IO>::pack(v + c * EPC);
+    } else if (vec && l + CNT <= L && (BYTES == 8 || BYTES == 4)) {
+        float tmp[EPC];
+#pragma unroll
+        for (int i = 0; i < EPC; ++i) tmp[i] = i < CNT ? v[i] : 0.0f;
+        uint4 r = io_traits<IO>::pack(tmp);
+        if constexpr (BYTES == 8) *reinterpret_cast<uint2 *>(row + l) = make_uint2(r.x, r.y);
+        else *reinterpret_cast<uint32_t *>(row + l) = r.x;
+    } else {
+#pragma unroll
+        for (int i = 0; i < CNT; ++i) if (l + i < L) io_traits<IO>::put(row, l + i, v[i]);
     }
 }
 

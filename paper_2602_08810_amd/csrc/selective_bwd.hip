@@ -1,6 +1,349 @@
-// placeholder until the backward kernel lands
+// Backward selective scan for gfx950: reverse-mode derivative of Eq. 2 of the paper (diagonal,
+// input-dependent A(k), B(k), C(k)) with the fused discretisations of Sec. 3.  The state is never
+// stored per step (Sec. 3): every time tile is recomputed from the checkpoint the forward wrote.
+//
+// For one (b,d) row and one state n, with H_l = dLoss/dx_l:
+//     H_l      = Cm_{l,n} dypre_l + a_{l+1} H_{l+1}                 (same affine scan, time reversed)
+//     dCm_{l,n} += dypre_l x_l          dBm_{l,n} += H_l g_l u_l
+//     du_l     += H_l g_l Bm_{l,n}      da_l = H_l x_{l-1}          dg_l = H_l Bm_{l,n} u_l
+//     dDelta_l += da_l da/dDelta + dg_l dg/dDelta                    dA_n += da_l da/dA + dg_l dg/dA
+//
+// Mapping.  Time runs along the lanes as in the forward kernel (lane i owns T consecutive steps of
+// the tile), but the N states are split over the W = N/NK wavefronts of the workgroup, which all
+// work on the same channel at the same time.  A wavefront therefore keeps its NK columns of Bm/Cm
+// for the tile, and the running sums of dBm/dCm over channels, in registers while the workgroup
+// loops over G channels: the reduction of dBm/dCm over channels costs no memory traffic and no
+// atomics inside the loop (LDS float atomics are very slow on this chip).  What is summed over n
+// (du, dDelta, ypre for dz) is exchanged through LDS once per (channel, tile): each wavefront
+// writes its partial sums, and after a barrier the threads share the epilogue of the 64*T steps
+// in flat order, so u/delta/dy/z are each read once and du/ddelta/dz written once, coalesced.
+// At the end of a tile the dBm/dCm sums are transposed through LDS and added to global memory
+// with fully coalesced float atomics (other workgroups hold other channel groups).
 #include "kernels.hpp"
+#include "scan_common.hpp"
+
 namespace lrnnx {
-int bwd_channels_per_group(int, int, int, int64_t) { return 16; }
-hipError_t launch_ss_bwd(const BwdParams &, int, int, hipStream_t) { return hipErrorNotSupported; }
+
+constexpr int kMaxG = 128;
+
+template <typename IO, int N, int NK, int T, int DISC>
+__global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) {
+    constexpr int W = N / NK;
+    constexpr int NT = W * 64;
+    constexpr int TILE = 64 * T;
+    constexpr int TPW = TILE / NT;                   // flat steps per thread in prologue / epilogue
+    constexpr int TQ = T / 4;
+    constexpr int CK_PER_TILE = TILE / (int)kCkptInterval;
+    static_assert(T % 4 == 0 && T % W == 0 && TPW >= 1 && TPW <= 8, "tile shape");
+    static_assert(TILE % kCkptInterval == 0, "tiles must start on checkpoints");
+    static_assert(W * 3 * TILE >= 2 * 16 * T * N, "flush buffer must fit in the partials area");
+
+    __shared__ __attribute__((aligned(16))) float sIn[3 * TILE];          // delta, u, dypre   [q][lane][4]
+    __shared__ __attribute__((aligned(16))) float sPart[W * 3 * TILE];    // per wave: ypre, du, ddelta partials
+    __shared__ float sH[kMaxG * N];       // a_{l0} H_{l0} carried to the earlier tile, per (channel, n)
+    __shared__ float sdA[kMaxG * N];
+    __shared__ float sdD[W * kMaxG];
+    __shared__ float sdb[W * kMaxG];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int b = blockIdx.y;
+    const int d0 = blockIdx.x * p.G;
+    const int Gact = (p.D - d0 < p.G) ? p.D - d0 : p.G;
+    const int64_t L = p.L;
+    const int64_t ntiles = (L + TILE - 1) / TILE;
+    const int64_t nck = (L + kCkptInterval - 1) / kCkptInterval;
+    const bool vec = p.vec != 0;
+    const bool has_z = p.z != nullptr;
+
+    for (int i = tid; i < kMaxG * N; i += NT) { sH[i] = 0.0f; sdA[i] = 0.0f; }
+    for (int i = tid; i < W * kMaxG; i += NT) { sdD[i] = 0.0f; sdb[i] = 0.0f; }
+
+    const IO *Bm = reinterpret_cast<const IO *>(p.Bm) + (int64_t)b * L * N;
+    const IO *Cm = reinterpret_cast<const IO *>(p.Cm) + (int64_t)b * L * N;
+
+    // flat position of this thread in prologue / epilogue, and its slot in the [q][lane][4] layout
+    const int f0 = tid * TPW;
+    auto fslot = [](int f) { return (((f % T) / 4) * 64 + f / T) * 4 + (f % 4); };
+
+    for (int64_t tile = ntiles - 1; tile >= 0; --tile) {
+        const int64_t l0 = tile * TILE;
+        const int64_t ll = l0 + lane * T;
+
+        // ---- this wavefront's NK columns of Bm/Cm for the tile, and zeroed dBm/dCm sums
+        float Bv[NK][T], Cv[NK][T], dBacc[NK][T], dCacc[NK][T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            float tb[NK], tc[NK];
+            if (ll + t < L) {
+                load_row<IO, NK>(Bm + (ll + t) * N + w * NK, tb);
+                load_row<IO, NK>(Cm + (ll + t) * N + w * NK, tc);
+            } else {
+#pragma unroll
+                for (int k = 0; k < NK; ++k) { tb[k] = 0.0f; tc[k] = 0.0f; }
+            }
+#pragma unroll
+            for (int k = 0; k < NK; ++k) { Bv[k][t] = tb[k]; Cv[k][t] = tc[k]; dBacc[k][t] = 0.0f; dCacc[k][t] = 0.0f; }
+        }
+
+        for (int g = 0; g < Gact; ++g) {
+            const int d = d0 + g;
+            const int64_t row = (int64_t)b * p.D + d;
+            const float Dsk = p.Dskip ? p.Dskip[d] : 0.0f;
+            const float bias = p.bias ? p.bias[d] : 0.0f;
+
+            // ---- prologue: each thread prepares TPW flat steps for everybody
+            float e_dl[TPW], e_u[TPW], e_sg[TPW], e_dyp[TPW], e_dy[TPW], e_z[TPW], e_sz[TPW];
+            {
+                const int64_t lf = l0 + f0;
+                float r_dl[TPW];
+                load_few<IO, TPW>(reinterpret_cast<const IO *>(p.u) + b * p.u_sb + d * p.u_sd, lf, L, vec, e_u);
+                load_few<IO, TPW>(reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd, lf, L, vec, r_dl);
+                load_few<IO, TPW>(reinterpret_cast<const IO *>(p.dy) + b * p.dy_sb + d * p.dy_sd, lf, L, vec, e_dy);
+                if (has_z) load_few<IO, TPW>(reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd, lf, L, vec, e_z);
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) {
+                    float s = r_dl[i] + bias, sp, sg;
+                    if (p.softplus) softplus_sigmoid(s, sp, sg); else { sp = s; sg = 1.0f; }
+                    e_dl[i] = (lf + i < L) ? sp : 0.0f;
+                    e_sg[i] = sg;
+                    if (has_z) { e_sz[i] = sigmoid_fast(e_z[i]); e_dyp[i] = e_dy[i] * e_z[i] * e_sz[i]; }
+                    else { e_z[i] = 0.0f; e_sz[i] = 0.0f; e_dyp[i] = e_dy[i]; }
+                    sIn[0 * TILE + fslot(f0 + i)] = e_dl[i];
+                    sIn[1 * TILE + fslot(f0 + i)] = e_u[i];
+                    sIn[2 * TILE + fslot(f0 + i)] = e_dyp[i];
+                }
+            }
+            __syncthreads();
+
+            // ---- main: this lane's T steps, this wavefront's NK states
+            float dl[T], uv[T], dyp[T], dlu[T], ypre[T], pdu[T], pdd[T];
+#pragma unroll
+            for (int q = 0; q < TQ; ++q) {
+                const float4 v0 = *reinterpret_cast<const float4 *>(&sIn[0 * TILE + (q * 64 + lane) * 4]);
+                const float4 v1 = *reinterpret_cast<const float4 *>(&sIn[1 * TILE + (q * 64 + lane) * 4]);
+                const float4 v2 = *reinterpret_cast<const float4 *>(&sIn[2 * TILE + (q * 64 + lane) * 4]);
+                dl[4 * q] = v0.x; dl[4 * q + 1] = v0.y; dl[4 * q + 2] = v0.z; dl[4 * q + 3] = v0.w;
+                uv[4 * q] = v1.x; uv[4 * q + 1] = v1.y; uv[4 * q + 2] = v1.z; uv[4 * q + 3] = v1.w;
+                dyp[4 * q] = v2.x; dyp[4 * q + 1] = v2.y; dyp[4 * q + 2] = v2.z; dyp[4 * q + 3] = v2.w;
+            }
+            float sum_dl = 0.0f;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                sum_dl += dl[t];
+                dlu[t] = dl[t] * uv[t];
+                ypre[t] = 0.0f; pdu[t] = 0.0f; pdd[t] = 0.0f;
+            }
+            const float dl_next0 = dpp<DPP_WAVE_SHL1>(0.0f, dl[0]);        // first Delta of the next lane (0 past lane 63)
+            const float sum_shift = sum_dl - dl[0] + dl_next0;
+
+#pragma unroll
+            for (int k = 0; k < NK; ++k) {
+                const int n = w * NK + k;
+                const ACoef ac = make_acoef<DISC>(p.A[d * N + n]);
+                const float xck = p.ckpt[(row * nck + tile * CK_PER_TILE) * N + n];
+                const float hc = sH[g * N + n];
+
+                // forward recompute of the states of this tile
+                float a[T + 1], gg[T], x[T];
+                float P = 1.0f, S = 0.0f;
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    disc_ag<DISC>(dl[t], ac, a[t], gg[t]);
+                    if constexpr (DISC == DISC_ZOH_S6) x[t] = dlu[t] * Bv[k][t];
+                    else if constexpr (DISC == DISC_DIRAC) x[t] = uv[t] * Bv[k][t];
+                    else x[t] = gg[t] * uv[t] * Bv[k][t];
+                    S = __builtin_fmaf(a[t], S, x[t]);
+                    if constexpr (DISC == DISC_BILINEAR) P *= a[t];
+                }
+                if constexpr (DISC != DISC_BILINEAR) P = exp2_fast(sum_dl * ac.A2);
+                wave_scan_fwd(P, S);
+                const float Pex = dpp<DPP_WAVE_SHR1>(1.0f, P);
+                const float Sex = dpp<DPP_WAVE_SHR1>(0.0f, S);
+                const float xin = __builtin_fmaf(Pex, xck, Sex);            // x entering this lane's first step
+                {
+                    float xp = xin;
+#pragma unroll
+                    for (int t = 0; t < T; ++t) { xp = __builtin_fmaf(a[t], xp, x[t]); x[t] = xp; }
+                }
+
+                // reverse scan of H_l = c_l + a_{l+1} H_{l+1}; the multiplier of the tile's last step is 1
+                // because the carried value is already a_{l1} H_{l1}
+                a[T] = dpp<DPP_WAVE_SHL1>(1.0f, a[0]);
+                float c[T];
+                float Pr = 1.0f, Sr = 0.0f;
+#pragma unroll
+                for (int t = T - 1; t >= 0; --t) {
+                    c[t] = Cv[k][t] * dyp[t];
+                    Sr = __builtin_fmaf(a[t + 1], Sr, c[t]);
+                    if constexpr (DISC == DISC_BILINEAR) Pr *= a[t + 1];
+                }
+                if constexpr (DISC != DISC_BILINEAR) Pr = exp2_fast(sum_shift * ac.A2);
+                wave_scan_rev(Pr, Sr, lane);
+                const float Pn = dpp<DPP_WAVE_SHL1>(1.0f, Pr);
+                const float Sn = dpp<DPP_WAVE_SHL1>(0.0f, Sr);
+                float R = __builtin_fmaf(Pn, hc, Sn);                       // H of the next lane's first step (the carry itself past lane 63)
+                const float H0 = __builtin_fmaf(Pr, hc, Sr);               // H of this lane's first step
+                const float hc_new = readlane(a[0] * H0, 0);
+                if (lane == 0) sH[g * N + n] = hc_new;
+
+                float dA_part = 0.0f;
+#pragma unroll
+                for (int t = T - 1; t >= 0; --t) {
+                    R = __builtin_fmaf(a[t + 1], R, c[t]);                   // H_t
+                    const float xprev = (t > 0) ? x[t - 1] : xin;
+                    dCacc[k][t] = __builtin_fmaf(dyp[t], x[t], dCacc[k][t]);
+                    ypre[t] = __builtin_fmaf(Cv[k][t], x[t], ypre[t]);
+                    if constexpr (DISC == DISC_ZOH_S6) {
+                        pdu[t] = __builtin_fmaf(R, Bv[k][t], pdu[t]);       // sum_n H B; scaled by Delta / u after the loop
+                        dBacc[k][t] = __builtin_fmaf(R, dlu[t], dBacc[k][t]);
+                        const float q = R * xprev * a[t];
+                        pdd[t] = __builtin_fmaf(q, ac.A, pdd[t]);
+                        dA_part = __builtin_fmaf(q, dl[t], dA_part);
+                    } else {
+                        float a_t, a_A, g_t, g_A;
+                        disc_partials<DISC>(dl[t], ac, a[t], gg[t], a_t, a_A, g_t, g_A);
+                        const float da = R * xprev;
+                        const float hb = R * Bv[k][t];
+                        const float dg = hb * uv[t];
+                        pdu[t] = __builtin_fmaf(hb, gg[t], pdu[t]);
+                        dBacc[k][t] = __builtin_fmaf(R * gg[t], uv[t], dBacc[k][t]);
+                        pdd[t] = __builtin_fmaf(da, a_t, __builtin_fmaf(dg, g_t, pdd[t]));
+                        dA_part = __builtin_fmaf(da, a_A, __builtin_fmaf(dg, g_A, dA_part));
+                    }
+                }
+                const float dA_tot = wave_sum(dA_part);
+                if (lane == 0) sdA[g * N + n] += dA_tot;
+                __builtin_amdgcn_sched_barrier(0);       // keep the NK state passes from being interleaved (register pressure)
+            }
+            if constexpr (DISC == DISC_ZOH_S6) {
+#pragma unroll
+                for (int t = 0; t < T; ++t) { pdd[t] = __builtin_fmaf(uv[t], pdu[t], pdd[t]); pdu[t] *= dl[t]; }
+            }
+#pragma unroll
+            for (int q = 0; q < TQ; ++q) {
+                float *base = &sPart[(w * 3) * TILE + (q * 64 + lane) * 4];
+                *reinterpret_cast<float4 *>(base) = make_float4(ypre[4 * q], ypre[4 * q + 1], ypre[4 * q + 2], ypre[4 * q + 3]);
+                *reinterpret_cast<float4 *>(base + TILE) = make_float4(pdu[4 * q], pdu[4 * q + 1], pdu[4 * q + 2], pdu[4 * q + 3]);
+                *reinterpret_cast<float4 *>(base + 2 * TILE) = make_float4(pdd[4 * q], pdd[4 * q + 1], pdd[4 * q + 2], pdd[4 * q + 3]);
+            }
+            __syncthreads();
+
+            // ---- epilogue: the threads share the tile in flat order
+            {
+                const int64_t lf = l0 + f0;
+                float o_du[TPW], o_dd[TPW], o_dz[TPW];
+                float dD_part = 0.0f, db_part = 0.0f;
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) {
+                    float yp = Dsk * e_u[i], s_du = 0.0f, s_dd = 0.0f;
+#pragma unroll
+                    for (int ww = 0; ww < W; ++ww) {
+                        yp += sPart[(ww * 3 + 0) * TILE + fslot(f0 + i)];
+                        s_du += sPart[(ww * 3 + 1) * TILE + fslot(f0 + i)];
+                        s_dd += sPart[(ww * 3 + 2) * TILE + fslot(f0 + i)];
+                    }
+                    o_du[i] = __builtin_fmaf(e_dyp[i], Dsk, s_du);
+                    o_dd[i] = s_dd * e_sg[i];
+                    o_dz[i] = e_dy[i] * yp * e_sz[i] * (1.0f + e_z[i] * (1.0f - e_sz[i]));
+                    dD_part = __builtin_fmaf(e_dyp[i], e_u[i], dD_part);
+                    db_part += (lf + i < L) ? o_dd[i] : 0.0f;
+                }
+                store_few<IO, TPW>(reinterpret_cast<IO *>(p.du) + b * p.du_sb + d * p.du_sd, lf, L, vec, o_du);
+                store_few<IO, TPW>(reinterpret_cast<IO *>(p.ddelta) + b * p.dd_sb + d * p.dd_sd, lf, L, vec, o_dd);
+                if (p.dz) store_few<IO, TPW>(reinterpret_cast<IO *>(p.dz) + b * p.dz_sb + d * p.dz_sd, lf, L, vec, o_dz);
+                const float dD_tot = wave_sum(dD_part), db_tot = wave_sum(db_part);
+                if (lane == 0) { sdD[w * kMaxG + g] += dD_tot; sdb[w * kMaxG + g] += db_tot; }
+            }
+        }
+
+        // ---- add this tile's dBm/dCm sums (over the G channels) to global memory, transposed through LDS
+        // so that consecutive threads hit consecutive addresses
+        float *fbB = sPart, *fbC = sPart + 16 * T * N;
+        for (int j = 0; j < 4; ++j) {
+            __syncthreads();
+            if ((lane >> 4) == j) {
+#pragma unroll
+                for (int t = 0; t < T; ++t)
+#pragma unroll
+                    for (int k = 0; k < NK; ++k) {
+                        fbB[((lane & 15) * T + t) * N + w * NK + k] = dBacc[k][t];
+                        fbC[((lane & 15) * T + t) * N + w * NK + k] = dCacc[k][t];
+                    }
+            }
+            __syncthreads();
+            const int64_t step0 = l0 + j * 16 * T;
+            for (int idx = tid; idx < 16 * T * N; idx += NT) {
+                if (step0 + idx / N < L) {
+                    const int64_t o = ((int64_t)b * L + step0) * N + idx;
+                    unsafeAtomicAdd(p.dBm + o, fbB[idx]);
+                    unsafeAtomicAdd(p.dCm + o, fbC[idx]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- per-channel results of this workgroup
+    for (int i = tid; i < Gact * N; i += NT) {
+        const int g = i / N, n = i % N;
+        unsafeAtomicAdd(p.dA + (int64_t)(d0 + g) * N + n, sdA[g * N + n]);
+        if (p.dx0) p.dx0[((int64_t)b * p.D + d0 + g) * N + n] = sH[g * N + n];
+    }
+    for (int g = tid; g < Gact; g += NT) {
+        float sD = 0.0f, sb = 0.0f;
+#pragma unroll
+        for (int ww = 0; ww < W; ++ww) { sD += sdD[ww * kMaxG + g]; sb += sdb[ww * kMaxG + g]; }
+        if (p.dD) unsafeAtomicAdd(p.dD + d0 + g, sD);
+        if (p.dbias) unsafeAtomicAdd(p.dbias + d0 + g, sb);
+    }
 }
+
+// ---------------------------------------------------------------- launchers
+int bwd_channels_per_group(int B, int D, int, int64_t) {
+    int64_t G = ((int64_t)B * D) / 512;               // aim at >= 512 workgroups (two per CU)
+    if (G < 8) G = 8;
+    if (G > kMaxG) G = kMaxG;
+    if (G > D) G = D;
+    const int64_t groups = (D + G - 1) / G;
+    G = (D + groups - 1) / groups;                     // even split
+    return (int)G;
+}
+
+template <typename IO, int N, int NK, int DISC>
+static hipError_t launch_bwd_n(const BwdParams &p, hipStream_t s) {
+    constexpr int T = 8;
+    dim3 grid((p.D + p.G - 1) / p.G, p.B);
+    hipLaunchKernelGGL((k_ss_bwd<IO, N, NK, T, DISC>), grid, dim3((N / NK) * 64), 0, s, p);
+    return hipGetLastError();
+}
+
+template <typename IO, int DISC>
+static hipError_t launch_bwd_disc(const BwdParams &p, hipStream_t s) {
+    switch (p.N) {
+        case 1: return launch_bwd_n<IO, 1, 1, DISC>(p, s);
+        case 2: return launch_bwd_n<IO, 2, 2, DISC>(p, s);
+        case 4: return launch_bwd_n<IO, 4, 4, DISC>(p, s);
+        case 8: return launch_bwd_n<IO, 8, 4, DISC>(p, s);
+        case 16: return launch_bwd_n<IO, 16, 4, DISC>(p, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+template <typename IO>
+static hipError_t launch_bwd_io(const BwdParams &p, int disc, hipStream_t s) {
+    switch (disc) {
+        case DISC_ZOH_S6: return launch_bwd_disc<IO, DISC_ZOH_S6>(p, s);
+        case DISC_ZOH: return launch_bwd_disc<IO, DISC_ZOH>(p, s);
+        case DISC_BILINEAR: return launch_bwd_disc<IO, DISC_BILINEAR>(p, s);
+        case DISC_DIRAC: return launch_bwd_disc<IO, DISC_DIRAC>(p, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_ss_bwd(const BwdParams &p, int io_dtype, int disc, hipStream_t s) {
+    return io_dtype == 1 ? launch_bwd_io<bf16_t>(p, disc, s) : launch_bwd_io<float>(p, disc, s);
+}
+
+}  // namespace lrnnx

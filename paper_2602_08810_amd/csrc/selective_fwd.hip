@@ -22,8 +22,8 @@
 
 namespace lrnnx {
 
-template <typename IO, int N, int T, int W, int DISC, bool WANT_Y>
-__global__ __launch_bounds__(W * 64) void k_ss_fwd(const FwdParams p) {
+template <typename IO, int N, int T, int W, int DISC, bool WANT_Y, bool CKPT>
+__global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
     constexpr int TQ = T / 4;
     constexpr int QS = 256 + (TQ > 1 ? 32 / TQ : 0);   // floats per quarter-plane, padded against bank conflicts on staging
     constexpr int PLANE = TQ * QS;                     // floats per state index n
@@ -53,16 +53,14 @@ __global__ __launch_bounds__(W * 64) void k_ss_fwd(const FwdParams p) {
     const IO *Bm = reinterpret_cast<const IO *>(p.Bm) + (int64_t)b * L * N;
     const IO *Cm = reinterpret_cast<const IO *>(p.Cm) + (int64_t)b * L * N;
 
-    ACoef ac[N];
-    float xc[N], Pc[N];
-#pragma unroll
-    for (int n = 0; n < N; ++n) {
-        ac[n] = make_acoef(p.A[d * N + n]);
-        Pc[n] = 1.0f;
-        if (mode == MODE_APPLY) xc[n] = p.ws_S[(row * p.nchunks + chunk) * N + n];
-        else if (mode == MODE_AGG) xc[n] = 0.0f;
-        else xc[n] = p.x0 ? p.x0[row * N + n] : 0.0f;
+    // Per-state uniform values live one per lane (lane n holds state n) and are read with
+    // v_readlane, so the loop over n stays rolled and nothing is indexed dynamically.
+    float xcv = 0.0f, pcv = 1.0f;
+    if (lane < N) {
+        if (mode == MODE_APPLY) xcv = p.ws_S[(row * p.nchunks + chunk) * N + lane];
+        else if (mode != MODE_AGG && p.x0) xcv = p.x0[row * N + lane];
     }
+    const float Av = (lane < N) ? p.A[d * N + lane] : 0.0f;
     const float Dsk = p.Dskip ? p.Dskip[d] : 0.0f;
     const float bias = p.bias ? p.bias[d] : 0.0f;
     const int64_t nck = (L + kCkptInterval - 1) / kCkptInterval;
@@ -105,37 +103,51 @@ __global__ __launch_bounds__(W * 64) void k_ss_fwd(const FwdParams p) {
             yv[t] = Dsk * uv[t];
         }
 
+        float4 Bq[TQ], Cq[TQ];
 #pragma unroll
+        for (int q = 0; q < TQ; ++q) {
+            Bq[q] = *reinterpret_cast<const float4 *>(&sB[q * QS + lane * 4]);
+            Cq[q] = *reinterpret_cast<const float4 *>(&sC[q * QS + lane * 4]);
+        }
+#pragma unroll 1
         for (int n = 0; n < N; ++n) {
             float Bv[T], Cv[T], a[T], bb[T];
 #pragma unroll
             for (int q = 0; q < TQ; ++q) {
-                float4 vb = *reinterpret_cast<const float4 *>(&sB[n * PLANE + q * QS + lane * 4]);
-                float4 vc = *reinterpret_cast<const float4 *>(&sC[n * PLANE + q * QS + lane * 4]);
-                Bv[4 * q] = vb.x; Bv[4 * q + 1] = vb.y; Bv[4 * q + 2] = vb.z; Bv[4 * q + 3] = vb.w;
-                Cv[4 * q] = vc.x; Cv[4 * q + 1] = vc.y; Cv[4 * q + 2] = vc.z; Cv[4 * q + 3] = vc.w;
+                Bv[4 * q] = Bq[q].x; Bv[4 * q + 1] = Bq[q].y; Bv[4 * q + 2] = Bq[q].z; Bv[4 * q + 3] = Bq[q].w;
+                Cv[4 * q] = Cq[q].x; Cv[4 * q + 1] = Cq[q].y; Cv[4 * q + 2] = Cq[q].z; Cv[4 * q + 3] = Cq[q].w;
             }
+            if (n + 1 < N) {                                   // next state's Bm/Cm while this one computes
+#pragma unroll
+                for (int q = 0; q < TQ; ++q) {
+                    Bq[q] = *reinterpret_cast<const float4 *>(&sB[(n + 1) * PLANE + q * QS + lane * 4]);
+                    Cq[q] = *reinterpret_cast<const float4 *>(&sC[(n + 1) * PLANE + q * QS + lane * 4]);
+                }
+            }
+            const ACoef ac = make_acoef<DISC>(readlane(Av, n));
+            const float xc = readlane(xcv, n);
             float P = 1.0f, S = 0.0f;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 float g;
-                disc_ag<DISC>(dl[t], ac[n], a[t], g);
+                disc_ag<DISC>(dl[t], ac, a[t], g);
                 if constexpr (DISC == DISC_ZOH_S6) bb[t] = du[t] * Bv[t];
                 else if constexpr (DISC == DISC_DIRAC) bb[t] = uv[t] * Bv[t];
                 else bb[t] = g * uv[t] * Bv[t];
                 S = __builtin_fmaf(a[t], S, bb[t]);
                 if constexpr (DISC == DISC_BILINEAR) P *= a[t];
             }
-            if constexpr (DISC != DISC_BILINEAR) P = exp2_fast(sum_dl * ac[n].A2);   // product of the T multipliers
+            if constexpr (DISC != DISC_BILINEAR) P = exp2_fast(sum_dl * ac.A2);   // product of the T multipliers
             wave_scan_fwd(P, S);
             const float Pex = dpp<DPP_WAVE_SHR1>(1.0f, P);
             const float Sex = dpp<DPP_WAVE_SHR1>(0.0f, S);
-            float x = __builtin_fmaf(Pex, xc[n], Sex);               // state entering this lane's first step
-            if (p.ckpt && (ll % kCkptInterval) == 0 && ll < L)
-                p.ckpt[(row * nck + ll / kCkptInterval) * N + n] = x;
-            const float xe = __builtin_fmaf(P, xc[n], S);            // state after this lane's last step
-            xc[n] = readlane(xe, 63);
-            if constexpr (!WANT_Y) Pc[n] *= readlane(P, 63);
+            float x = __builtin_fmaf(Pex, xc, Sex);                  // state entering this lane's first step
+            if constexpr (CKPT) {
+                if ((ll % kCkptInterval) == 0 && ll < L) p.ckpt[(row * nck + ll / kCkptInterval) * N + n] = x;
+            }
+            const float xe = __builtin_fmaf(P, xc, S);               // state after this lane's last step
+            xcv = writelane(xcv, readlane(xe, 63), n);
+            if constexpr (!WANT_Y) pcv = writelane(pcv, readlane(pcv, n) * readlane(P, 63), n);
             if constexpr (WANT_Y) {
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
@@ -156,16 +168,12 @@ __global__ __launch_bounds__(W * 64) void k_ss_fwd(const FwdParams p) {
         }
     }
 
-    if (active && lane == 0) {
+    if (active && lane < N) {
         if (mode == MODE_AGG) {
-#pragma unroll
-            for (int n = 0; n < N; ++n) {
-                p.ws_P[(row * p.nchunks + chunk) * N + n] = Pc[n];
-                p.ws_S[(row * p.nchunks + chunk) * N + n] = xc[n];
-            }
+            p.ws_P[(row * p.nchunks + chunk) * N + lane] = pcv;
+            p.ws_S[(row * p.nchunks + chunk) * N + lane] = xcv;
         } else if (p.x_last && tile1 == ntiles) {
-#pragma unroll
-            for (int n = 0; n < N; ++n) p.x_last[row * N + n] = xc[n];
+            p.x_last[row * N + lane] = xcv;
         }
     }
 }
@@ -202,10 +210,12 @@ int fwd_tile_steps(int) { return 64 * kFwdT; }
 template <typename IO, int N, int DISC>
 static hipError_t launch_fwd_n(const FwdParams &p, hipStream_t s) {
     dim3 grid((p.D + kFwdW - 1) / kFwdW, p.B, p.nchunks);
-    if (p.mode == MODE_FULL || p.mode == MODE_APPLY)
-        hipLaunchKernelGGL((k_ss_fwd<IO, N, kFwdT, kFwdW, DISC, true>), grid, dim3(kFwdW * 64), 0, s, p);
-    else
-        hipLaunchKernelGGL((k_ss_fwd<IO, N, kFwdT, kFwdW, DISC, false>), grid, dim3(kFwdW * 64), 0, s, p);
+    const bool want_y = (p.mode == MODE_FULL || p.mode == MODE_APPLY);
+    const dim3 block(kFwdW * 64);
+    if (want_y && p.ckpt) hipLaunchKernelGGL((k_ss_fwd<IO, N, kFwdT, kFwdW, DISC, true, true>), grid, block, 0, s, p);
+    else if (want_y) hipLaunchKernelGGL((k_ss_fwd<IO, N, kFwdT, kFwdW, DISC, true, false>), grid, block, 0, s, p);
+    else if (p.ckpt) hipLaunchKernelGGL((k_ss_fwd<IO, N, kFwdT, kFwdW, DISC, false, true>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((k_ss_fwd<IO, N, kFwdT, kFwdW, DISC, false, false>), grid, block, 0, s, p);
     return hipGetLastError();
 }
 

@@ -1,0 +1,104 @@
+"""GPU parity: lrnnx_selective_scan_bwd (through the C ABI) against the fp64 oracle's analytic gradients."""
+import numpy as np
+import pytest
+
+from paper_2602_08810_amd import workloads
+from _util import TOL, dev, host, rel_err, sel_inputs_dev
+
+pytestmark = pytest.mark.gpu
+
+# gradients reduced over many terms in fp32 (dA, dBm, dCm, dD, dbias) are held to the fp32-I/O bar even when the
+# I/O tensors are bf16: their inputs are bf16 but every product and sum is fp32
+GRAD_TOL_F32 = 1e-4
+
+
+@pytest.fixture(scope="module")
+def api():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2602_08810_amd import api as _api
+    _api.lib()
+    return _api
+
+
+def _check(api, oracle, io, disc, softplus, use_fwd_ckpt, **shape):
+    p = workloads.make_selective(io=io, with_dy=True, **shape)
+    if not softplus:
+        p["delta"] = workloads._io_round(np.abs(p["delta"]) * 0.1 + 0.01, io)
+        p["delta_bias"] = None
+    t = sel_inputs_dev(p, io)
+    dy = dev(p["dy"], io)
+    ckpt = None
+    if use_fwd_ckpt:
+        _, ckpt = api.lrnnx_selective_scan_fwd(**t, disc=disc, delta_softplus=softplus, return_ckpt=True)
+    g = api.lrnnx_selective_scan_bwd(**t, dy=dy, ckpt=ckpt, disc=disc, delta_softplus=softplus, want_dx0=True)
+    r = oracle.selective_scan_bwd(p["u"], p["delta"], p["A"], p["Bm"], p["Cm"], p["dy"], Dskip=p["Dskip"],
+                                  delta_bias=p["delta_bias"], z=p["z"], x0=p["x0"], disc=disc,
+                                  delta_softplus=softplus)
+    tol_io = TOL[io]
+    errs = {}
+    for name in ("du", "ddelta", "dz"):
+        if r[name] is not None:
+            errs[name] = (rel_err(host(g[name]), r[name]), tol_io)
+    for name in ("dA", "dBm", "dCm", "dD", "dbias", "dx0"):
+        if r[name] is not None:
+            errs[name] = (rel_err(host(g[name]), r[name]), GRAD_TOL_F32)
+    bad = {k: v for k, v in errs.items() if not v[0] <= v[1]}
+    assert not bad, f"rel errors over tolerance: {bad}  (all: {errs})"
+
+
+def test_config0_shape_fp32(api, oracle):
+    """BASELINE config 0 shape (B=1, D=16, N=4, L=256, fp32), gradients of every input."""
+    _check(api, oracle, "f32", "zoh_s6", True, True, B=1, D=16, N=4, L=256, gate=False, seed=0, bias=("const", -2.0))
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("N", [1, 2, 4, 8, 16])
+def test_state_sizes_multi_tile_ragged(api, oracle, io, N):
+    _check(api, oracle, io, "zoh_s6", True, True, B=2, D=11, N=N, L=1300, gate=True, with_x0=True, seed=60 + N,
+           bias=("uniform", -4.0, -2.0))
+
+
+@pytest.mark.parametrize("disc", ["zoh_s6", "zoh", "bilinear", "dirac"])
+@pytest.mark.parametrize("softplus", [True, False])
+def test_discretisations(api, oracle, disc, softplus):
+    _check(api, oracle, "f32", disc, softplus, True, B=2, D=5, N=16, L=777, gate=False, seed=71)
+    _check(api, oracle, "bf16", disc, softplus, True, B=1, D=9, N=8, L=520, gate=True, seed=72)
+
+
+@pytest.mark.parametrize("L", [1, 7, 8, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1024])
+def test_lengths_around_lane_and_tile_edges(api, oracle, L):
+    _check(api, oracle, "f32", "zoh_s6", True, True, B=1, D=3, N=4, L=L, gate=True, with_x0=True, seed=L)
+    _check(api, oracle, "bf16", "zoh_s6", True, True, B=1, D=3, N=16, L=L, gate=False, seed=L + 1)
+
+
+def test_without_forward_checkpoints(api, oracle):
+    """ckpt = NULL: the library runs its own state-only forward sweep into the workspace."""
+    _check(api, oracle, "bf16", "zoh_s6", True, False, B=2, D=20, N=16, L=1500, gate=True, with_x0=True, seed=80)
+    _check(api, oracle, "f32", "bilinear", True, False, B=1, D=4, N=8, L=600, gate=False, seed=81)
+
+
+def test_many_channels_per_group_and_groups(api, oracle):
+    """More channels than one workgroup takes: several channel groups add into dBm/dCm."""
+    _check(api, oracle, "bf16", "zoh_s6", True, True, B=2, D=300, N=16, L=640, gate=True, seed=82)
+
+
+def test_non_reduced_outputs_are_deterministic(api):
+    import torch
+    p = workloads.make_selective(B=2, D=24, N=16, L=1100, io="bf16", gate=True, seed=83)
+    t = sel_inputs_dev(p, "bf16")
+    dy = dev(p["dy"], "bf16")
+    g1 = api.lrnnx_selective_scan_bwd(**t, dy=dy)
+    g2 = api.lrnnx_selective_scan_bwd(**t, dy=dy)
+    for k in ("du", "ddelta", "dz"):
+        assert torch.equal(g1[k], g2[k]), k
+
+
+def test_error_codes(api):
+    import torch
+    p = workloads.make_selective(B=1, D=4, N=4, L=64, io="f32")
+    t = sel_inputs_dev(p, "f32")
+    dy = dev(p["dy"])
+    with pytest.raises(api.LrnnxError) as e:
+        api.lrnnx_selective_scan_bwd(**t, dy=dy, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == 3                                   # no ckpt and workspace too small
