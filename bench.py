@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X diagonal linear-recurrence scan (one GPU).
+
+A step is one forward + one backward selective scan on BASELINE config 2 (Mamba-block
+shape: B=8, D=1536, N=16, L=2048, bf16 I/O, fp32 state, SiLU gate), inputs resident in
+HBM.  The metric is scan elements/s, elements = B*L*D*N per pass (2 passes per step).
+The same run also times the other single-kernel workloads (config 1 LTI scan, config 3
+long-sequence forward on both paths, config 4 backward) and reports them under
+"other_configs"; they are not part of `value`.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--quick]
+
+Prints ONE JSON line.  `roofline` is for the dominant kernel of the step (the backward
+kernel): algorithmic HBM bytes per launch / average launch time measured with HIP
+events on the launch stream, against the 8 TB/s HBM peak.  `roofline_alu` prices the
+same launch against the plain (non-packed) fp32 VALU issue rate, which is the tighter
+bound for this path (N exponentials per loaded element).  `cpu_baseline` is the fp64
+oracle timed on the host cores on the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# 256 CUs x 4 SIMDs x 2.4 GHz x 32 lanes/clk: the vendor's 157.3 TFLOP/s fp32 vector peak counts an FMA as two
+# flops, i.e. 78.6e12 lane-instructions/s for plain (non-packed) fp32 VALU work
+VALU_PEAK_TLANEOPS = 78.6
+
+# measured HBM traffic of the backward kernel on config 2 (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
+# copy kernel of known size); filled from profiles/ when a counter run exists, else null
+BWD_TRAFFIC_BYTES = None
+
+
+def _selective_bytes(B, D, N, L, es, gate, bwd):
+    """Algorithmic HBM bytes: every I/O tensor once, Bm/Cm once, reduced grads once, no state traffic."""
+    per = B * D * L * es
+    bc = 2 * B * L * N * es
+    if not bwd:
+        return per * (3 + (1 if gate else 0)) + bc
+    return per * (5 + (2 if gate else 0)) + bc + 2 * B * L * N * 4
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=90)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--repeats", type=int, default=1, help="experiments of --steps steps (mean/std over their means)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--quick", action="store_true", help="skip the other configs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(rows (b,d) are independent, see DESIGN.md for how the path would shard)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_08810_amd import api, workloads
+    api.lib()                                   # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    # ------------------------------------------------------------------ headline workload: config 2, fwd + bwd
+    p, cfg = workloads.make("c2")
+    B, D, N, L = cfg["B"], cfg["D"], cfg["N"], cfg["L"]
+    io = torch.bfloat16
+
+    def up(a, dt=None):
+        t = torch.from_numpy(a).to(dev)
+        return t.to(dt) if dt is not None else t
+
+    t = dict(u=up(p["u"], io), delta=up(p["delta"], io), A=up(p["A"]), Bm=up(p["Bm"], io), Cm=up(p["Cm"], io),
+             Dskip=up(p["Dskip"]), delta_bias=up(p["delta_bias"]), z=up(p["z"], io))
+    dy = up(p["dy"], io)
+    I = api.lrnnx_ckpt_interval()
+    y = torch.empty_like(t["u"])
+    ckpt = torch.empty((B, D, (L + I - 1) // I, N), dtype=torch.float32, device=dev)
+    outs = {k: torch.empty_like(t["u"]) for k in ("du", "ddelta", "dz")}
+    outs.update(dA=torch.empty((D, N), device=dev), dBm=torch.empty((B, L, N), device=dev),
+                dCm=torch.empty((B, L, N), device=dev), dD=torch.empty(D, device=dev), dbias=torch.empty(D, device=dev))
+    ws = torch.empty(max(api.lrnnx_workspace_bytes(api.WS_FWD, B, D, N, L, api.BF16), 16), dtype=torch.uint8, device=dev)
+
+    def fwd():
+        api.lrnnx_selective_scan_fwd(**t, out=y, ckpt_out=ckpt, workspace=ws)
+
+    def bwd():
+        api.lrnnx_selective_scan_bwd(**t, dy=dy, ckpt=ckpt, outs=outs)
+
+    def step():
+        fwd()
+        bwd()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps; per-kernel HIP events (torch events on the current stream, which is the
+    # stream handed to the library) bracket the forward and the backward launches inside it
+    K = args.steps
+    exp_means = []
+    fwd_ms, bwd_ms = [], []
+    for _rep in range(max(1, args.repeats)):
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(K):
+            ev[k][0].record()
+            fwd()
+            ev[k][1].record()
+            bwd()
+            ev[k][2].record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        exp_means.append((t1 - t0) * 1e3 / K)
+        fwd_ms += [ev[k][0].elapsed_time(ev[k][1]) for k in range(K)]
+        bwd_ms += [ev[k][1].elapsed_time(ev[k][2]) for k in range(K)]
+    ms_per_step = float(np.mean(exp_means))
+    elements = B * L * D * N
+    value = 2 * elements / (ms_per_step * 1e-3)
+    fwd_t, bwd_t = float(np.mean(fwd_ms)) * 1e-3, float(np.mean(bwd_ms)) * 1e-3
+
+    fwd_bytes = _selective_bytes(B, D, N, L, 2, True, False) + ckpt.numel() * 4
+    bwd_bytes = _selective_bytes(B, D, N, L, 2, True, True) + ckpt.numel() * 4
+    roofline = {"bound": "hbm", "kernel": "k_ss_bwd<bf16,N=16> (config 2 backward)",
+                "achieved": bwd_bytes / bwd_t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": bwd_bytes / bwd_t / 1e9 / HBM_PEAK_GBS, "traffic": BWD_TRAFFIC_BYTES,
+                "algorithmic_bytes": bwd_bytes, "avg_launch_us": bwd_t * 1e6}
+    # algorithmic VALU work of the backward pass: per element 2 exponentials' worth of transcendental issue
+    # is not counted; 18 fp32 lane-instructions + 1 exponential per element
+    bwd_ops = elements * 19.0
+    roofline_alu = {"bound": "alu", "kernel": roofline["kernel"], "achieved": bwd_ops / bwd_t / 1e12,
+                    "peak": VALU_PEAK_TLANEOPS, "unit": "T lane-instr/s",
+                    "frac": bwd_ops / bwd_t / 1e12 / VALU_PEAK_TLANEOPS, "ops_per_element": 19.0}
+
+    result = {
+        "metric": "scan elements/s (B*L*D*N) fwd & bwd", "value": value, "unit": "elements/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "config 2: selective scan fwd+bwd, B=8 D=1536 N=16 L=2048, bf16 I/O, fp32 state, SiLU gate",
+                   "io_dtype": "bf16", "disc": "zoh_s6", "elements_per_pass": elements},
+        "ms_per_step_std": float(np.std(exp_means)), "experiments": len(exp_means),
+        "fwd": {"us": fwd_t * 1e6, "elements_per_s": elements / fwd_t, "hbm_GBs": fwd_bytes / fwd_t / 1e9,
+                "hbm_frac": fwd_bytes / fwd_t / 1e9 / HBM_PEAK_GBS},
+        "bwd": {"us": bwd_t * 1e6, "elements_per_s": elements / bwd_t, "hbm_GBs": bwd_bytes / bwd_t / 1e9,
+                "hbm_frac": bwd_bytes / bwd_t / 1e9 / HBM_PEAK_GBS},
+        "roofline": roofline, "roofline_alu": roofline_alu,
+    }
+
+    # ------------------------------------------------------------------ the other configs (context, not `value`)
+    if not args.quick:
+        result["other_configs"] = _other_configs(api, torch, dev)
+
+    # ------------------------------------------------------------------ CPU baseline: the oracle as it stands
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        t0 = time.perf_counter()
+        oracle.selective_scan_fwd(p["u"], p["delta"], p["A"], p["Bm"], p["Cm"], Dskip=p["Dskip"],
+                                  delta_bias=p["delta_bias"], z=p["z"])
+        t1 = time.perf_counter()
+        oracle.selective_scan_bwd(p["u"], p["delta"], p["A"], p["Bm"], p["Cm"], p["dy"], Dskip=p["Dskip"],
+                                  delta_bias=p["delta_bias"], z=p["z"])
+        t2 = time.perf_counter()
+        result["cpu_baseline"] = {
+            "value": 2 * elements / (t2 - t0), "unit": "elements/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "the whole config-2 workload, one fwd + one bwd pass of the fp64 C oracle (OpenMP over rows), "
+                      "including its float64 input conversion",
+            "fwd_s": t1 - t0, "bwd_s": t2 - t1}
+    print(json.dumps(result))
+
+
+def _time(torch, fn, reps, warm=3):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / reps
+
+
+def _other_configs(api, torch, dev):
+    """Configs 1, 3, 4 with seeded on-device random inputs of the stated distributions (timing only)."""
+    out = {}
+    g = torch.Generator(device=dev).manual_seed(1234)
+    bf = torch.bfloat16
+
+    def sel(B, D, N, L, gate):
+        r = lambda *s: torch.randn(*s, device=dev, generator=g)
+        return dict(u=r(B, D, L).to(bf), delta=r(B, D, L).to(bf),
+                    A=-torch.exp(torch.rand(D, N, device=dev, generator=g) * 2 - 1),
+                    Bm=r(B, L, N).to(bf), Cm=r(B, L, N).to(bf), Dskip=r(D),
+                    delta_bias=torch.rand(D, device=dev, generator=g) * 2 - 4,
+                    z=r(B, D, L).to(bf) if gate else None)
+
+    # config 1: LTI complex-diagonal scan
+    Bq, P, Lq = 4, 256, 4096
+    lam = torch.polar(torch.rand(P, device=dev, generator=g) * 0.099 + 0.9,
+                      torch.rand(P, device=dev, generator=g) * 6.2831853)
+    v = torch.randn(Bq, Lq, P, dtype=torch.complex64, device=dev, generator=g) * 0.70710678
+    x = torch.empty_like(v)
+    ws = torch.empty(max(api.lrnnx_workspace_bytes(api.WS_LTI, Bq, P, 0, Lq, 0), 16), dtype=torch.uint8, device=dev)
+    tt = _time(torch, lambda: api.lrnnx_lti_diag_scan(lam, v, out=x, workspace=ws), 50)
+    nb = 2 * Bq * Lq * P * 8
+    out["c1_lti"] = {"us": tt * 1e6, "elements_per_s": Bq * Lq * P / tt, "hbm_GBs": nb / tt / 1e9,
+                     "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
+
+    # config 3: long-sequence forward, both paths
+    B3, D3, N3, L3 = 1, 2048, 16, 65536
+    t3 = sel(B3, D3, N3, L3, False)
+    y3 = torch.empty_like(t3["u"])
+    ws3 = torch.empty(max(api.lrnnx_workspace_bytes(api.WS_FWD, B3, D3, N3, L3, api.BF16), 16), dtype=torch.uint8, device=dev)
+    nb = _selective_bytes(B3, D3, N3, L3, 2, False, False)
+    for path in ("single_pass", "chunk_carry"):
+        tt = _time(torch, lambda: api.lrnnx_selective_scan_fwd(**t3, path=path, out=y3, workspace=ws3), 5)
+        out[f"c3_fwd_{path}"] = {"us": tt * 1e6, "elements_per_s": B3 * D3 * N3 * L3 / tt, "hbm_GBs": nb / tt / 1e9,
+                                 "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
+    del t3, y3, ws3
+
+    # config 4: backward only (checkpoints from one untimed forward)
+    B4, D4, N4, L4 = 16, 2560, 16, 4096
+    t4 = sel(B4, D4, N4, L4, True)
+    dy4 = torch.randn(B4, D4, L4, device=dev, generator=g).to(bf)
+    _, ck4 = api.lrnnx_selective_scan_fwd(**t4, return_ckpt=True)
+    outs = {k: torch.empty_like(t4["u"]) for k in ("du", "ddelta", "dz")}
+    outs.update(dA=torch.empty((D4, N4), device=dev), dBm=torch.empty((B4, L4, N4), device=dev),
+                dCm=torch.empty((B4, L4, N4), device=dev), dD=torch.empty(D4, device=dev),
+                dbias=torch.empty(D4, device=dev))
+    tt = _time(torch, lambda: api.lrnnx_selective_scan_bwd(**t4, dy=dy4, ckpt=ck4, outs=outs), 5)
+    nb = _selective_bytes(B4, D4, N4, L4, 2, True, True) + ck4.numel() * 4
+    out["c4_bwd"] = {"us": tt * 1e6, "elements_per_s": B4 * D4 * N4 * L4 / tt, "hbm_GBs": nb / tt / 1e9,
+                     "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
+    y4 = torch.empty_like(t4["u"])
+    tt = _time(torch, lambda: api.lrnnx_selective_scan_fwd(**t4, out=y4), 5)
+    nb = _selective_bytes(B4, D4, N4, L4, 2, True, False)
+    out["c4_fwd"] = {"us": tt * 1e6, "elements_per_s": B4 * D4 * N4 * L4 / tt, "hbm_GBs": nb / tt / 1e9,
+                     "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
+    return out
+
+
+if __name__ == "__main__":
+    main()

@@ -150,8 +150,10 @@ def lrnnx_workspace_bytes(which, B, D, N, L, io_dtype) -> int:
 
 def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, x0=None,
                              disc="zoh_s6", delta_softplus=True, path="auto",
-                             return_last_state=False, return_ckpt=False, out=None, workspace=None):
-    """y (and optionally x_last, ckpt) of the forward selective scan; see lrnnx_ss_fwd_args."""
+                             return_last_state=False, return_ckpt=False, out=None, ckpt_out=None, workspace=None):
+    """y (and optionally x_last, ckpt) of the forward selective scan; see lrnnx_ss_fwd_args.
+
+    `out`, `ckpt_out` and `workspace` may supply preallocated buffers (ckpt_out implies return_ckpt)."""
     io = u.dtype
     Bsz, D, L = u.shape
     N = A.shape[1]
@@ -177,10 +179,13 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
     a.y, a.y_stride_b, a.y_stride_d = _bdl(y, "y", io)
     x_last = torch.empty((Bsz, D, N), dtype=torch.float32, device=u.device) if return_last_state else None
     a.x_last = _ptr(x_last)
-    ckpt = None
+    ckpt = ckpt_out
+    return_ckpt = return_ckpt or ckpt_out is not None
     if return_ckpt:
         I = lrnnx_ckpt_interval()
-        ckpt = torch.empty((Bsz, D, (L + I - 1) // I, N), dtype=torch.float32, device=u.device)
+        if ckpt is None:
+            ckpt = torch.empty((Bsz, D, (L + I - 1) // I, N), dtype=torch.float32, device=u.device)
+        _f32c(ckpt, "ckpt_out", (Bsz, D, (L + I - 1) // I, N))
     a.ckpt = _ptr(ckpt)
     if workspace is None:
         nbytes = lrnnx_workspace_bytes(WS_FWD, Bsz, D, N, L, a.io_dtype)
