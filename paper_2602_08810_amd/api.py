@@ -14,7 +14,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblrnnx.so")
+LIB_PATH = os.environ.get("LRNNX_LIB", os.path.join(_HERE, "liblrnnx.so"))   # LRNNX_LIB: alternative build of the same library
 
 F32, BF16 = 0, 1
 DISC = {"zoh_s6": 0, "zoh": 1, "bilinear": 2, "dirac": 3}

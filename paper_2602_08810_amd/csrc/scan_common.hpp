@@ -284,8 +284,8 @@ __device__ __forceinline__ void load_few(const IO *row, int64_t l, int64_t L, bo
         for (int i = 0; i < CNT; ++i) out[i] = (l + i < L) ? io_traits<IO>::get(row, l + i) : 0.0f;
     }
 }
-template <typename IO, int CNT>
-__device__ __forceinline__ void store_few(IO *row, int64_t l, int64_t L, bool vec, const float *v) {
+template <typename IO, int CNT, typename IDX>
+__device__ __forceinline__ void store_few(IO *row, IDX l, IDX L, bool vec, const float *v) {
     constexpr int EPC = io_traits<IO>::EPC;
     constexpr int BYTES = CNT * (16 / EPC);
     if (vec && l + CNT <= L && BYTES % 16 == 0) {
@@ -302,6 +302,53 @@ __device__ __forceinline__ void store_few(IO *row, int64_t l, int64_t L, bool ve
     } else {
 #pragma unroll
         for (int i = 0; i < CNT; ++i) if (l + i < L) io_traits<IO>::put(row, l + i, v[i]);
+    }
+}
+
+// The same few elements as untouched 32-bit words, so that a load can be issued long before its
+// data is needed (unpacking is a separate step and nothing waits on the load until then).
+template <typename IO, int CNT>
+struct RawFew {
+    static constexpr int WORDS = (CNT * (16 / io_traits<IO>::EPC) + 3) / 4;
+    uint32_t w[WORDS];
+};
+template <typename IO, int CNT, typename IDX>
+__device__ __forceinline__ void load_few_raw(const IO *row, IDX l, IDX L, bool vec, RawFew<IO, CNT> &r) {
+    constexpr int BYTES = CNT * (16 / io_traits<IO>::EPC);
+    constexpr int WORDS = RawFew<IO, CNT>::WORDS;
+    if (vec && l + CNT <= L) {
+        if constexpr (BYTES % 16 == 0) {
+#pragma unroll
+            for (int c = 0; c < BYTES / 16; ++c) {
+                const uint4 v = reinterpret_cast<const uint4 *>(row + l)[c];
+                r.w[4 * c] = v.x; r.w[4 * c + 1] = v.y; r.w[4 * c + 2] = v.z; r.w[4 * c + 3] = v.w;
+            }
+        } else if constexpr (BYTES == 8) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(row + l);
+            r.w[0] = v.x; r.w[1] = v.y;
+        } else if constexpr (BYTES == 4) {
+            r.w[0] = *reinterpret_cast<const uint32_t *>(row + l);
+        } else {
+            r.w[0] = *reinterpret_cast<const unsigned short *>(row + l);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < WORDS; ++i) r.w[i] = 0u;
+#pragma unroll
+        for (int i = 0; i < CNT; ++i) {
+            if (l + i < L) {
+                if constexpr (sizeof(IO) == 4) r.w[i] = *reinterpret_cast<const uint32_t *>(row + l + i);
+                else r.w[i / 2] |= (uint32_t)(*reinterpret_cast<const unsigned short *>(row + l + i)) << (16 * (i % 2));
+            }
+        }
+    }
+}
+template <typename IO, int CNT>
+__device__ __forceinline__ void unpack_few(const RawFew<IO, CNT> &r, float *out) {
+#pragma unroll
+    for (int i = 0; i < CNT; ++i) {
+        if constexpr (sizeof(IO) == 4) out[i] = i2f((int)r.w[i]);
+        else out[i] = (i % 2) ? i2f((int)(r.w[i / 2] & 0xFFFF0000u)) : i2f((int)(r.w[i / 2] << 16));
     }
 }
 

@@ -25,6 +25,12 @@
 namespace lrnnx {
 
 constexpr int kMaxG = 128;
+#ifndef LRNNX_BWD_NK16
+#define LRNNX_BWD_NK16 4
+#endif
+#ifndef LRNNX_BWD_T16
+#define LRNNX_BWD_T16 4
+#endif
 
 template <typename IO, int N, int NK, int T, int DISC>
 __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) {
@@ -40,6 +46,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
 
     __shared__ __attribute__((aligned(16))) float sIn[3 * TILE];          // delta, u, dypre   [q][lane][4]
     __shared__ __attribute__((aligned(16))) float sPart[W * 3 * TILE];    // per wave: ypre, du, ddelta partials
+    __shared__ __attribute__((aligned(16))) float sBt[N * TILE];          // Bm columns of the tile, fp32: [n][q][lane][4], wave-private slices
     __shared__ float sH[kMaxG * N];       // a_{l0} H_{l0} carried to the earlier tile, per (channel, n)
     __shared__ float sdA[kMaxG * N];
     __shared__ float sdD[W * kMaxG];
@@ -69,16 +76,22 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
 
     for (int64_t tile = ntiles - 1; tile >= 0; --tile) {
         const int64_t l0 = tile * TILE;
-        const int64_t ll = l0 + lane * T;
+        const int rem = (L - l0 < TILE) ? (int)(L - l0) : TILE;      // valid steps of this tile
+        // all global addresses below are a wave-uniform base plus a small unsigned per-lane offset, so that
+        // they need one 32-bit register per lane instead of a 64-bit induction variable each
+        const IO *BmT = Bm + l0 * N + w * NK, *CmT = Cm + l0 * N + w * NK;
 
-        // ---- this wavefront's NK columns of Bm/Cm for the tile, and zeroed dBm/dCm sums
-        float Bv[NK][T], Cv[NK][T], dBacc[NK][T], dCacc[NK][T];
+        // ---- this wavefront's NK columns of Bm/Cm for the tile, and zeroed dBm/dCm sums.  Cm and both sums stay in
+        // registers; the Bm columns go to this wavefront's own slice of LDS (read back as ds_read_b128 in each pass)
+        float Cv[NK][T], dBacc[NK][T], dCacc[NK][T];
+        {
+        float Bv[NK][T];
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             float tb[NK], tc[NK];
-            if (ll + t < L) {
-                load_row<IO, NK>(Bm + (ll + t) * N + w * NK, tb);
-                load_row<IO, NK>(Cm + (ll + t) * N + w * NK, tc);
+            if (lane * T + t < rem) {
+                load_row<IO, NK>(BmT + (unsigned)((lane * T + t) * N), tb);
+                load_row<IO, NK>(CmT + (unsigned)((lane * T + t) * N), tc);
             } else {
 #pragma unroll
                 for (int k = 0; k < NK; ++k) { tb[k] = 0.0f; tc[k] = 0.0f; }
@@ -86,53 +99,80 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
 #pragma unroll
             for (int k = 0; k < NK; ++k) { Bv[k][t] = tb[k]; Cv[k][t] = tc[k]; dBacc[k][t] = 0.0f; dCacc[k][t] = 0.0f; }
         }
+#pragma unroll
+        for (int k = 0; k < NK; ++k)
+#pragma unroll
+            for (int q = 0; q < TQ; ++q)
+                *reinterpret_cast<float4 *>(&sBt[(((w * NK + k) * TQ + q) * 64 + lane) * 4]) =
+                    make_float4(Bv[k][4 * q], Bv[k][4 * q + 1], Bv[k][4 * q + 2], Bv[k][4 * q + 3]);
+        }
+
+        // per-channel inputs are fetched one channel ahead, so their latency hides behind the main pass
+        RawFew<IO, TPW> r_u, r_dl, r_dy, r_z;
+        float pA[NK], pck[NK], pDsk, pbias;
+        auto prefetch = [&](int g) {
+            const int d = d0 + g;
+            const int64_t row = (int64_t)b * p.D + d;
+            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.u) + b * p.u_sb + d * p.u_sd + l0, f0, rem, vec, r_u);
+            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd + l0, f0, rem, vec, r_dl);
+            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.dy) + b * p.dy_sb + d * p.dy_sd + l0, f0, rem, vec, r_dy);
+            if (has_z) load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd + l0, f0, rem, vec, r_z);
+#pragma unroll
+            for (int k = 0; k < NK; ++k) {
+                pA[k] = p.A[d * N + w * NK + k];
+                pck[k] = p.ckpt[(row * nck + tile * CK_PER_TILE) * N + w * NK + k];
+            }
+            pDsk = p.Dskip ? p.Dskip[d] : 0.0f;
+            pbias = p.bias ? p.bias[d] : 0.0f;
+        };
+        prefetch(0);
 
         for (int g = 0; g < Gact; ++g) {
             const int d = d0 + g;
-            const int64_t row = (int64_t)b * p.D + d;
-            const float Dsk = p.Dskip ? p.Dskip[d] : 0.0f;
-            const float bias = p.bias ? p.bias[d] : 0.0f;
+            const float Dsk = pDsk, bias = pbias;
+            float cA[NK], cck[NK];
+#pragma unroll
+            for (int k = 0; k < NK; ++k) { cA[k] = pA[k]; cck[k] = pck[k]; }
 
             // ---- prologue: each thread prepares TPW flat steps for everybody
-            float e_dl[TPW], e_u[TPW], e_sg[TPW], e_dyp[TPW], e_dy[TPW], e_z[TPW], e_sz[TPW];
+            float e_sg[TPW], e_dy[TPW], e_z[TPW], e_sz[TPW];
             {
-                const int64_t lf = l0 + f0;
-                float r_dl[TPW];
-                load_few<IO, TPW>(reinterpret_cast<const IO *>(p.u) + b * p.u_sb + d * p.u_sd, lf, L, vec, e_u);
-                load_few<IO, TPW>(reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd, lf, L, vec, r_dl);
-                load_few<IO, TPW>(reinterpret_cast<const IO *>(p.dy) + b * p.dy_sb + d * p.dy_sd, lf, L, vec, e_dy);
-                if (has_z) load_few<IO, TPW>(reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd, lf, L, vec, e_z);
+                float e_u[TPW], r_d[TPW];
+                unpack_few<IO, TPW>(r_u, e_u);
+                unpack_few<IO, TPW>(r_dl, r_d);
+                unpack_few<IO, TPW>(r_dy, e_dy);
+                if (has_z) unpack_few<IO, TPW>(r_z, e_z);
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) {
-                    float s = r_dl[i] + bias, sp, sg;
+                    float s = r_d[i] + bias, sp, sg, dyp;
                     if (p.softplus) softplus_sigmoid(s, sp, sg); else { sp = s; sg = 1.0f; }
-                    e_dl[i] = (lf + i < L) ? sp : 0.0f;
                     e_sg[i] = sg;
-                    if (has_z) { e_sz[i] = sigmoid_fast(e_z[i]); e_dyp[i] = e_dy[i] * e_z[i] * e_sz[i]; }
-                    else { e_z[i] = 0.0f; e_sz[i] = 0.0f; e_dyp[i] = e_dy[i]; }
-                    sIn[0 * TILE + fslot(f0 + i)] = e_dl[i];
+                    if (has_z) { e_sz[i] = sigmoid_fast(e_z[i]); dyp = e_dy[i] * e_z[i] * e_sz[i]; }
+                    else { e_z[i] = 0.0f; e_sz[i] = 0.0f; dyp = e_dy[i]; }
+                    sIn[0 * TILE + fslot(f0 + i)] = (f0 + i < rem) ? sp : 0.0f;
                     sIn[1 * TILE + fslot(f0 + i)] = e_u[i];
-                    sIn[2 * TILE + fslot(f0 + i)] = e_dyp[i];
+                    sIn[2 * TILE + fslot(f0 + i)] = dyp;
                 }
             }
             __syncthreads();
+            if (g + 1 < Gact) prefetch(g + 1);
 
             // ---- main: this lane's T steps, this wavefront's NK states
-            float dl[T], uv[T], dyp[T], dlu[T], ypre[T], pdu[T], pdd[T];
+            float dl[T], dyp[T], dlu[T], ypre[T], pdu[T], pdd[T];
 #pragma unroll
             for (int q = 0; q < TQ; ++q) {
                 const float4 v0 = *reinterpret_cast<const float4 *>(&sIn[0 * TILE + (q * 64 + lane) * 4]);
                 const float4 v1 = *reinterpret_cast<const float4 *>(&sIn[1 * TILE + (q * 64 + lane) * 4]);
                 const float4 v2 = *reinterpret_cast<const float4 *>(&sIn[2 * TILE + (q * 64 + lane) * 4]);
                 dl[4 * q] = v0.x; dl[4 * q + 1] = v0.y; dl[4 * q + 2] = v0.z; dl[4 * q + 3] = v0.w;
-                uv[4 * q] = v1.x; uv[4 * q + 1] = v1.y; uv[4 * q + 2] = v1.z; uv[4 * q + 3] = v1.w;
+                dlu[4 * q] = v1.x; dlu[4 * q + 1] = v1.y; dlu[4 * q + 2] = v1.z; dlu[4 * q + 3] = v1.w;   // u for now
                 dyp[4 * q] = v2.x; dyp[4 * q + 1] = v2.y; dyp[4 * q + 2] = v2.z; dyp[4 * q + 3] = v2.w;
             }
             float sum_dl = 0.0f;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 sum_dl += dl[t];
-                dlu[t] = dl[t] * uv[t];
+                if constexpr (DISC == DISC_ZOH_S6) dlu[t] *= dl[t];   // S6 only ever needs Delta*u; the others keep u
                 ypre[t] = 0.0f; pdu[t] = 0.0f; pdd[t] = 0.0f;
             }
             const float dl_next0 = dpp<DPP_WAVE_SHL1>(0.0f, dl[0]);        // first Delta of the next lane (0 past lane 63)
@@ -141,9 +181,15 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
 #pragma unroll
             for (int k = 0; k < NK; ++k) {
                 const int n = w * NK + k;
-                const ACoef ac = make_acoef<DISC>(p.A[d * N + n]);
-                const float xck = p.ckpt[(row * nck + tile * CK_PER_TILE) * N + n];
+                const ACoef ac = make_acoef<DISC>(cA[k]);
+                const float xck = cck[k];
                 const float hc = sH[g * N + n];
+                float Bk[T];
+#pragma unroll
+                for (int q = 0; q < TQ; ++q) {
+                    const float4 vb = *reinterpret_cast<const float4 *>(&sBt[((n * TQ + q) * 64 + lane) * 4]);
+                    Bk[4 * q] = vb.x; Bk[4 * q + 1] = vb.y; Bk[4 * q + 2] = vb.z; Bk[4 * q + 3] = vb.w;
+                }
 
                 // forward recompute of the states of this tile
                 float a[T + 1], gg[T], x[T];
@@ -151,9 +197,9 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
                     disc_ag<DISC>(dl[t], ac, a[t], gg[t]);
-                    if constexpr (DISC == DISC_ZOH_S6) x[t] = dlu[t] * Bv[k][t];
-                    else if constexpr (DISC == DISC_DIRAC) x[t] = uv[t] * Bv[k][t];
-                    else x[t] = gg[t] * uv[t] * Bv[k][t];
+                    if constexpr (DISC == DISC_ZOH_S6) x[t] = dlu[t] * Bk[t];
+                    else if constexpr (DISC == DISC_DIRAC) x[t] = dlu[t] * Bk[t];
+                    else x[t] = gg[t] * dlu[t] * Bk[t];
                     S = __builtin_fmaf(a[t], S, x[t]);
                     if constexpr (DISC == DISC_BILINEAR) P *= a[t];
                 }
@@ -171,12 +217,10 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 // reverse scan of H_l = c_l + a_{l+1} H_{l+1}; the multiplier of the tile's last step is 1
                 // because the carried value is already a_{l1} H_{l1}
                 a[T] = dpp<DPP_WAVE_SHL1>(1.0f, a[0]);
-                float c[T];
                 float Pr = 1.0f, Sr = 0.0f;
 #pragma unroll
                 for (int t = T - 1; t >= 0; --t) {
-                    c[t] = Cv[k][t] * dyp[t];
-                    Sr = __builtin_fmaf(a[t + 1], Sr, c[t]);
+                    Sr = __builtin_fmaf(a[t + 1], Sr, Cv[k][t] * dyp[t]);
                     if constexpr (DISC == DISC_BILINEAR) Pr *= a[t + 1];
                 }
                 if constexpr (DISC != DISC_BILINEAR) Pr = exp2_fast(sum_shift * ac.A2);
@@ -191,12 +235,12 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 float dA_part = 0.0f;
 #pragma unroll
                 for (int t = T - 1; t >= 0; --t) {
-                    R = __builtin_fmaf(a[t + 1], R, c[t]);                   // H_t
+                    R = __builtin_fmaf(a[t + 1], R, Cv[k][t] * dyp[t]);       // H_t (the product is recomputed: registers are scarcer than VALU slots here)
                     const float xprev = (t > 0) ? x[t - 1] : xin;
                     dCacc[k][t] = __builtin_fmaf(dyp[t], x[t], dCacc[k][t]);
                     ypre[t] = __builtin_fmaf(Cv[k][t], x[t], ypre[t]);
                     if constexpr (DISC == DISC_ZOH_S6) {
-                        pdu[t] = __builtin_fmaf(R, Bv[k][t], pdu[t]);       // sum_n H B; scaled by Delta / u after the loop
+                        pdu[t] = __builtin_fmaf(R, Bk[t], pdu[t]);       // sum_n H B; scaled by Delta / u after the loop
                         dBacc[k][t] = __builtin_fmaf(R, dlu[t], dBacc[k][t]);
                         const float q = R * xprev * a[t];
                         pdd[t] = __builtin_fmaf(q, ac.A, pdd[t]);
@@ -205,10 +249,10 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                         float a_t, a_A, g_t, g_A;
                         disc_partials<DISC>(dl[t], ac, a[t], gg[t], a_t, a_A, g_t, g_A);
                         const float da = R * xprev;
-                        const float hb = R * Bv[k][t];
-                        const float dg = hb * uv[t];
+                        const float hb = R * Bk[t];
+                        const float dg = hb * dlu[t];
                         pdu[t] = __builtin_fmaf(hb, gg[t], pdu[t]);
-                        dBacc[k][t] = __builtin_fmaf(R * gg[t], uv[t], dBacc[k][t]);
+                        dBacc[k][t] = __builtin_fmaf(R * gg[t], dlu[t], dBacc[k][t]);
                         pdd[t] = __builtin_fmaf(da, a_t, __builtin_fmaf(dg, g_t, pdd[t]));
                         dA_part = __builtin_fmaf(da, a_A, __builtin_fmaf(dg, g_A, dA_part));
                     }
@@ -217,9 +261,17 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 if (lane == 0) sdA[g * N + n] += dA_tot;
                 __builtin_amdgcn_sched_barrier(0);       // keep the NK state passes from being interleaved (register pressure)
             }
-            if constexpr (DISC == DISC_ZOH_S6) {
+            if constexpr (DISC == DISC_ZOH_S6) {     // dDelta += u sum_n H B ;  du = Delta sum_n H B
 #pragma unroll
-                for (int t = 0; t < T; ++t) { pdd[t] = __builtin_fmaf(uv[t], pdu[t], pdd[t]); pdu[t] *= dl[t]; }
+                for (int q = 0; q < TQ; ++q) {
+                    const float4 v1 = *reinterpret_cast<const float4 *>(&sIn[1 * TILE + (q * 64 + lane) * 4]);
+                    const float uu[4] = {v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        pdd[4 * q + r] = __builtin_fmaf(uu[r], pdu[4 * q + r], pdd[4 * q + r]);
+                        pdu[4 * q + r] *= dl[4 * q + r];
+                    }
+                }
             }
 #pragma unroll
             for (int q = 0; q < TQ; ++q) {
@@ -232,27 +284,27 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
 
             // ---- epilogue: the threads share the tile in flat order
             {
-                const int64_t lf = l0 + f0;
                 float o_du[TPW], o_dd[TPW], o_dz[TPW];
                 float dD_part = 0.0f, db_part = 0.0f;
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) {
-                    float yp = Dsk * e_u[i], s_du = 0.0f, s_dd = 0.0f;
+                    const float e_u = sIn[1 * TILE + fslot(f0 + i)], e_dyp = sIn[2 * TILE + fslot(f0 + i)];
+                    float yp = Dsk * e_u, s_du = 0.0f, s_dd = 0.0f;
 #pragma unroll
                     for (int ww = 0; ww < W; ++ww) {
                         yp += sPart[(ww * 3 + 0) * TILE + fslot(f0 + i)];
                         s_du += sPart[(ww * 3 + 1) * TILE + fslot(f0 + i)];
                         s_dd += sPart[(ww * 3 + 2) * TILE + fslot(f0 + i)];
                     }
-                    o_du[i] = __builtin_fmaf(e_dyp[i], Dsk, s_du);
+                    o_du[i] = __builtin_fmaf(e_dyp, Dsk, s_du);
                     o_dd[i] = s_dd * e_sg[i];
                     o_dz[i] = e_dy[i] * yp * e_sz[i] * (1.0f + e_z[i] * (1.0f - e_sz[i]));
-                    dD_part = __builtin_fmaf(e_dyp[i], e_u[i], dD_part);
-                    db_part += (lf + i < L) ? o_dd[i] : 0.0f;
+                    dD_part = __builtin_fmaf(e_dyp, e_u, dD_part);
+                    db_part += (f0 + i < rem) ? o_dd[i] : 0.0f;
                 }
-                store_few<IO, TPW>(reinterpret_cast<IO *>(p.du) + b * p.du_sb + d * p.du_sd, lf, L, vec, o_du);
-                store_few<IO, TPW>(reinterpret_cast<IO *>(p.ddelta) + b * p.dd_sb + d * p.dd_sd, lf, L, vec, o_dd);
-                if (p.dz) store_few<IO, TPW>(reinterpret_cast<IO *>(p.dz) + b * p.dz_sb + d * p.dz_sd, lf, L, vec, o_dz);
+                store_few<IO, TPW>(reinterpret_cast<IO *>(p.du) + b * p.du_sb + d * p.du_sd + l0, f0, rem, vec, o_du);
+                store_few<IO, TPW>(reinterpret_cast<IO *>(p.ddelta) + b * p.dd_sb + d * p.dd_sd + l0, f0, rem, vec, o_dd);
+                if (p.dz) store_few<IO, TPW>(reinterpret_cast<IO *>(p.dz) + b * p.dz_sb + d * p.dz_sd + l0, f0, rem, vec, o_dz);
                 const float dD_tot = wave_sum(dD_part), db_tot = wave_sum(db_part);
                 if (lane == 0) { sdD[w * kMaxG + g] += dD_tot; sdb[w * kMaxG + g] += db_tot; }
             }
@@ -273,12 +325,12 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                     }
             }
             __syncthreads();
-            const int64_t step0 = l0 + j * 16 * T;
+            const int step0 = j * 16 * T;                                // within the tile
+            float *gB = p.dBm + ((int64_t)b * L + l0 + step0) * N, *gC = p.dCm + ((int64_t)b * L + l0 + step0) * N;
             for (int idx = tid; idx < 16 * T * N; idx += NT) {
-                if (step0 + idx / N < L) {
-                    const int64_t o = ((int64_t)b * L + step0) * N + idx;
-                    unsafeAtomicAdd(p.dBm + o, fbB[idx]);
-                    unsafeAtomicAdd(p.dCm + o, fbC[idx]);
+                if (step0 + idx / N < rem) {
+                    unsafeAtomicAdd(gB + (unsigned)idx, fbB[idx]);
+                    unsafeAtomicAdd(gC + (unsigned)idx, fbC[idx]);
                 }
             }
         }
@@ -300,6 +352,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     }
 }
 
+#ifndef LRNNX_KERNEL_ONLY
 // ---------------------------------------------------------------- launchers
 int bwd_channels_per_group(int B, int D, int, int64_t) {
     int64_t G = ((int64_t)B * D) / 512;               // aim at >= 512 workgroups (two per CU)
@@ -311,9 +364,8 @@ int bwd_channels_per_group(int B, int D, int, int64_t) {
     return (int)G;
 }
 
-template <typename IO, int N, int NK, int DISC>
+template <typename IO, int N, int NK, int DISC, int T = 8>
 static hipError_t launch_bwd_n(const BwdParams &p, hipStream_t s) {
-    constexpr int T = 8;
     dim3 grid((p.D + p.G - 1) / p.G, p.B);
     hipLaunchKernelGGL((k_ss_bwd<IO, N, NK, T, DISC>), grid, dim3((N / NK) * 64), 0, s, p);
     return hipGetLastError();
@@ -322,11 +374,13 @@ static hipError_t launch_bwd_n(const BwdParams &p, hipStream_t s) {
 template <typename IO, int DISC>
 static hipError_t launch_bwd_disc(const BwdParams &p, hipStream_t s) {
     switch (p.N) {
-        case 1: return launch_bwd_n<IO, 1, 1, DISC>(p, s);
-        case 2: return launch_bwd_n<IO, 2, 2, DISC>(p, s);
-        case 4: return launch_bwd_n<IO, 4, 4, DISC>(p, s);
-        case 8: return launch_bwd_n<IO, 8, 4, DISC>(p, s);
-        case 16: return launch_bwd_n<IO, 16, 4, DISC>(p, s);
+        // T = 4 steps per lane: with T = 8 the compiler spills to scratch, which costs far more than the
+        // longer scans (measured 2.4x slower on the Mamba-block shape)
+        case 1: return launch_bwd_n<IO, 1, 1, DISC, 4>(p, s);
+        case 2: return launch_bwd_n<IO, 2, 2, DISC, 4>(p, s);
+        case 4: return launch_bwd_n<IO, 4, 4, DISC, 4>(p, s);
+        case 8: return launch_bwd_n<IO, 8, 4, DISC, 4>(p, s);
+        case 16: return launch_bwd_n<IO, 16, LRNNX_BWD_NK16, DISC, LRNNX_BWD_T16>(p, s);
     }
     return hipErrorInvalidValue;
 }
@@ -345,5 +399,6 @@ static hipError_t launch_bwd_io(const BwdParams &p, int disc, hipStream_t s) {
 hipError_t launch_ss_bwd(const BwdParams &p, int io_dtype, int disc, hipStream_t s) {
     return io_dtype == 1 ? launch_bwd_io<bf16_t>(p, disc, s) : launch_bwd_io<float>(p, disc, s);
 }
+#endif  // LRNNX_KERNEL_ONLY
 
 }  // namespace lrnnx

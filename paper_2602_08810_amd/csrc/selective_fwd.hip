@@ -103,26 +103,21 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
             yv[t] = Dsk * uv[t];
         }
 
-        float4 Bq[TQ], Cq[TQ];
+        // One state: fold the lane's T steps, wavefront prefix, replay.  (Bc,Cc) hold this state's Bm/Cm
+        // for the lane; (Bn,Cn) receive the next state's while this one computes (ping-pong, no copies).
+        auto one_state = [&](int n, const float4 (&Bc)[TQ], const float4 (&Cc)[TQ], float4 (&Bn)[TQ], float4 (&Cn)[TQ]) {
+            if (n + 1 < N) {
 #pragma unroll
-        for (int q = 0; q < TQ; ++q) {
-            Bq[q] = *reinterpret_cast<const float4 *>(&sB[q * QS + lane * 4]);
-            Cq[q] = *reinterpret_cast<const float4 *>(&sC[q * QS + lane * 4]);
-        }
-#pragma unroll 1
-        for (int n = 0; n < N; ++n) {
+                for (int q = 0; q < TQ; ++q) {
+                    Bn[q] = *reinterpret_cast<const float4 *>(&sB[(n + 1) * PLANE + q * QS + lane * 4]);
+                    Cn[q] = *reinterpret_cast<const float4 *>(&sC[(n + 1) * PLANE + q * QS + lane * 4]);
+                }
+            }
             float Bv[T], Cv[T], a[T], bb[T];
 #pragma unroll
             for (int q = 0; q < TQ; ++q) {
-                Bv[4 * q] = Bq[q].x; Bv[4 * q + 1] = Bq[q].y; Bv[4 * q + 2] = Bq[q].z; Bv[4 * q + 3] = Bq[q].w;
-                Cv[4 * q] = Cq[q].x; Cv[4 * q + 1] = Cq[q].y; Cv[4 * q + 2] = Cq[q].z; Cv[4 * q + 3] = Cq[q].w;
-            }
-            if (n + 1 < N) {                                   // next state's Bm/Cm while this one computes
-#pragma unroll
-                for (int q = 0; q < TQ; ++q) {
-                    Bq[q] = *reinterpret_cast<const float4 *>(&sB[(n + 1) * PLANE + q * QS + lane * 4]);
-                    Cq[q] = *reinterpret_cast<const float4 *>(&sC[(n + 1) * PLANE + q * QS + lane * 4]);
-                }
+                Bv[4 * q] = Bc[q].x; Bv[4 * q + 1] = Bc[q].y; Bv[4 * q + 2] = Bc[q].z; Bv[4 * q + 3] = Bc[q].w;
+                Cv[4 * q] = Cc[q].x; Cv[4 * q + 1] = Cc[q].y; Cv[4 * q + 2] = Cc[q].z; Cv[4 * q + 3] = Cc[q].w;
             }
             const ACoef ac = make_acoef<DISC>(readlane(Av, n));
             const float xc = readlane(xcv, n);
@@ -145,16 +140,29 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
             if constexpr (CKPT) {
                 if ((ll % kCkptInterval) == 0 && ll < L) p.ckpt[(row * nck + ll / kCkptInterval) * N + n] = x;
             }
-            const float xe = __builtin_fmaf(P, xc, S);               // state after this lane's last step
-            xcv = writelane(xcv, readlane(xe, 63), n);
-            if constexpr (!WANT_Y) pcv = writelane(pcv, readlane(pcv, n) * readlane(P, 63), n);
-            if constexpr (WANT_Y) {
+            if constexpr (!WANT_Y) {
+                const float xe = __builtin_fmaf(P, xc, S);           // state after this lane's last step
+                xcv = writelane(xcv, readlane(xe, 63), n);
+                pcv = writelane(pcv, readlane(pcv, n) * readlane(P, 63), n);
+            } else {
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
                     x = __builtin_fmaf(a[t], x, bb[t]);
                     yv[t] = __builtin_fmaf(Cv[t], x, yv[t]);
                 }
+                xcv = writelane(xcv, readlane(x, 63), n);            // lane 63 ends on the tile's last step
             }
+        };
+        float4 Bq0[TQ], Cq0[TQ], Bq1[TQ], Cq1[TQ];
+#pragma unroll
+        for (int q = 0; q < TQ; ++q) {
+            Bq0[q] = *reinterpret_cast<const float4 *>(&sB[q * QS + lane * 4]);
+            Cq0[q] = *reinterpret_cast<const float4 *>(&sC[q * QS + lane * 4]);
+        }
+#pragma unroll 1
+        for (int n = 0; n < N; n += 2) {
+            one_state(n, Bq0, Cq0, Bq1, Cq1);
+            if (n + 1 < N) one_state(n + 1, Bq1, Cq1, Bq0, Cq0);
         }
 
         if constexpr (WANT_Y) {
