@@ -36,7 +36,7 @@ int lti_chunks(int64_t B, int64_t P, int64_t L) {
     int64_t n = cdiv(8 * kNumCU, waves_per_chunk);
     const int64_t max_n = cdiv(L, 16);                 // at least 16 steps per chunk
     if (n > max_n) n = max_n;
-    if (n > 65535) n = 65535;
+    if (n > 1024) n = 1024;                             // each workgroup walks the end states of the chunks before it
     if (n < 1) n = 1;
     return (int)n;
 }

@@ -44,7 +44,7 @@ struct LtiParams {
     int64_t chunk;           // time steps per chunk
     const float2 *lambda, *v, *x0;
     float2 *x, *x_last;
-    float2 *ws_S;            // [B,nchunks,P] chunk end states, overwritten with chunk carry-ins
+    float2 *ws_S;            // [B,nchunks,P] end state of each chunk started from zero
 };
 
 // Each launcher returns hipSuccess or the launch error; it validates nothing.

@@ -4,15 +4,25 @@
 // v and x are [B,L,P] with P contiguous, so the lanes run along P (coalesced 8-byte
 // complex elements) and the time axis is cut into chunks that different workgroups take.
 // Because lambda is constant the affine aggregate of a chunk is (lambda^len, end state
-// from zero): only the end state is stored.  Three launches: chunk end states, a short
-// carry over the chunks of each (b,p), and the rescan of every chunk from its true
-// carry-in (the second read of v is served by the L2 / Infinity Cache at these sizes).
+// from zero): only the end state is stored.  Two launches: the end state of every chunk, then
+// the rescan of every chunk from its true carry-in, which each workgroup first rebuilds for
+// itself from the end states of the chunks before it (Horner in lambda^len over an L2-resident
+// array; the second read of v is served by the L2 / Infinity Cache at these sizes).
 #include "kernels.hpp"
 
 namespace lrnnx {
 
 __device__ __forceinline__ float2 cmul(float2 a, float2 b) {
     return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
+}
+__device__ __forceinline__ float2 cpow(float2 a, int64_t e) {            // a^e by repeated squaring
+    float2 r = make_float2(1.0f, 0.0f);
+    while (e > 0) {
+        if (e & 1) r = cmul(r, a);
+        a = cmul(a, a);
+        e >>= 1;
+    }
+    return r;
 }
 __device__ __forceinline__ float2 cfma(float2 a, float2 b, float2 c) {   // a*b + c
     return make_float2(__builtin_fmaf(a.x, b.x, __builtin_fmaf(-a.y, b.y, c.x)),
@@ -22,7 +32,8 @@ __device__ __forceinline__ float2 cfma(float2 a, float2 b, float2 c) {   // a*b 
 constexpr int kLtiThreads = 256;
 
 // APPLY = false: end state of each chunk started from zero -> ws_S[b,c,p].
-// APPLY = true : rescan from the carry-in (ws_S[b,c,p], or x0 when there is one chunk) and store x.
+// APPLY = true : carry-in = x0 pushed through the chunks before this one (from their end states), then
+//                rescan and store x.
 template <bool APPLY>
 __global__ __launch_bounds__(kLtiThreads) void k_lti_chunk(const LtiParams p) {
     const int pp = blockIdx.x * kLtiThreads + threadIdx.x;
@@ -33,8 +44,18 @@ __global__ __launch_bounds__(kLtiThreads) void k_lti_chunk(const LtiParams p) {
     const float2 lam = p.lambda[pp];
     float2 x = make_float2(0.0f, 0.0f);
     if (APPLY) {
-        if (p.nchunks > 1) x = p.ws_S[((int64_t)b * p.nchunks + c) * p.P + pp];
-        else if (p.x0) x = p.x0[(int64_t)b * p.P + pp];
+        if (p.x0) x = p.x0[(int64_t)b * p.P + pp];
+        if (c > 0) {                                  // in_{j+1} = lambda^chunk in_j + S_j  (every chunk before c is full)
+            const float2 lp = cpow(lam, p.chunk);
+            const float2 *S = p.ws_S + (int64_t)b * p.nchunks * p.P + pp;
+            int j = 0;
+            for (; j + 4 <= c; j += 4) {
+                const float2 s0 = S[(int64_t)j * p.P], s1 = S[(int64_t)(j + 1) * p.P];
+                const float2 s2 = S[(int64_t)(j + 2) * p.P], s3 = S[(int64_t)(j + 3) * p.P];
+                x = cfma(lp, x, s0); x = cfma(lp, x, s1); x = cfma(lp, x, s2); x = cfma(lp, x, s3);
+            }
+            for (; j < c; ++j) x = cfma(lp, x, S[(int64_t)j * p.P]);
+        }
     }
     const float2 *v = p.v + ((int64_t)b * p.L + k0) * p.P + pp;
     float2 *xo = p.x + ((int64_t)b * p.L + k0) * p.P + pp;
@@ -56,29 +77,10 @@ __global__ __launch_bounds__(kLtiThreads) void k_lti_chunk(const LtiParams p) {
     else if (p.x_last && k1 == p.L) p.x_last[(int64_t)b * p.P + pp] = x;
 }
 
-// Carry over the chunks of one (b,p):  in_{c+1} = lambda^chunk * in_c + S_c ; ws_S[c] <- in_c.
-__global__ void k_lti_carry(const LtiParams p) {
-    const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-    if (i >= (int64_t)p.B * p.P) return;
-    const int b = (int)(i / p.P), pp = (int)(i % p.P);
-    const float2 lam = p.lambda[pp];
-    float2 lp = make_float2(1.0f, 0.0f);
-    for (int64_t k = 0; k < p.chunk; ++k) lp = cmul(lp, lam);     // lambda^chunk (every chunk but the last is full)
-    float2 x = p.x0 ? p.x0[i] : make_float2(0.0f, 0.0f);
-    for (int c = 0; c < p.nchunks; ++c) {
-        const int64_t j = ((int64_t)b * p.nchunks + c) * p.P + pp;
-        const float2 S = p.ws_S[j];
-        p.ws_S[j] = x;
-        x = cfma(lp, x, S);
-    }
-}
-
 hipError_t launch_lti(const LtiParams &p, hipStream_t s) {
     dim3 grid((p.P + kLtiThreads - 1) / kLtiThreads, p.nchunks, p.B);
     if (p.nchunks > 1) {
         hipLaunchKernelGGL(k_lti_chunk<false>, grid, dim3(kLtiThreads), 0, s, p);
-        const int64_t rows = (int64_t)p.B * p.P;
-        hipLaunchKernelGGL(k_lti_carry, dim3((unsigned)((rows + 63) / 64)), dim3(64), 0, s, p);
     }
     hipLaunchKernelGGL(k_lti_chunk<true>, grid, dim3(kLtiThreads), 0, s, p);
     return hipGetLastError();

@@ -35,7 +35,8 @@ def test_config1(api, oracle):
     _run(api, oracle, 4, 256, 4096, False, 1)
 
 
-@pytest.mark.parametrize("B,P,L", [(1, 1, 1), (2, 5, 17), (3, 300, 1000), (1, 64, 33), (2, 257, 4099), (1, 2048, 64)])
+@pytest.mark.parametrize("B,P,L", [(1, 1, 1), (2, 5, 17), (3, 300, 1000), (1, 64, 33), (2, 257, 4099), (1, 2048, 64),
+                                   (1, 64, 8192), (1, 70, 5000)])
 @pytest.mark.parametrize("with_x0", [False, True])
 def test_shapes(api, oracle, B, P, L, with_x0):
     _run(api, oracle, B, P, L, with_x0, seed=B * 1000 + P + L)
