@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--repeats", type=int, default=1, help="experiments of --steps steps (mean/std over their means)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quick", action="store_true", help="skip the other configs")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain device copy of 256 MiB (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -99,6 +101,13 @@ def main():
     def step():
         fwd()
         bwd()
+
+    if args.copy_calibration:
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device=dev)      # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
