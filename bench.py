@@ -31,9 +31,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# 256 CUs x 4 SIMDs x 2.4 GHz x 32 lanes/clk: the vendor's 157.3 TFLOP/s fp32 vector peak counts an FMA as two
-# flops, i.e. 78.6e12 lane-instructions/s for plain (non-packed) fp32 VALU work
-VALU_PEAK_TLANEOPS = 78.6
+# 256 CUs x 4 SIMD16 x 2.4 GHz = 39.3e12 plain (non-packed) fp32 lane-instructions/s; the vendor's 157.3 TFLOP/s
+# fp32 vector peak counts an FMA as two flops and a packed instruction as two more
+VALU_PEAK_TLANEOPS = 39.3
 
 # measured HBM traffic of the backward kernel on config 2 (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # copy kernel of known size); filled from profiles/ when a counter run exists, else null
@@ -144,12 +144,12 @@ def main():
                 "achieved": bwd_bytes / bwd_t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": bwd_bytes / bwd_t / 1e9 / HBM_PEAK_GBS, "traffic": BWD_TRAFFIC_BYTES,
                 "algorithmic_bytes": bwd_bytes, "avg_launch_us": bwd_t * 1e6}
-    # algorithmic VALU work of the backward pass: per element 2 exponentials' worth of transcendental issue
-    # is not counted; 18 fp32 lane-instructions + 1 exponential per element
-    bwd_ops = elements * 19.0
+    # algorithmic VALU work of the backward pass per element: state recompute (3 fp32 + 1 exponential = 2 issue
+    # slots), adjoint recurrence (2), gradient terms (8) = 15 issue slots; scans, softplus and gate not counted
+    bwd_ops = elements * 15.0
     roofline_alu = {"bound": "alu", "kernel": roofline["kernel"], "achieved": bwd_ops / bwd_t / 1e12,
                     "peak": VALU_PEAK_TLANEOPS, "unit": "T lane-instr/s",
-                    "frac": bwd_ops / bwd_t / 1e12 / VALU_PEAK_TLANEOPS, "ops_per_element": 19.0}
+                    "frac": bwd_ops / bwd_t / 1e12 / VALU_PEAK_TLANEOPS, "ops_per_element": 15.0}
 
     result = {
         "metric": "scan elements/s (B*L*D*N) fwd & bwd", "value": value, "unit": "elements/s",
