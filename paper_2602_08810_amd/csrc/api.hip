@@ -9,6 +9,7 @@ namespace {
 
 constexpr int kNumCU = 256;              // MI355X
 constexpr int kFwdWaves = 8;             // channels (wavefronts) per forward workgroup
+constexpr int kLtiGroup = 4;             // chunks (wavefronts) per LTI workgroup; must match lti_scan.hip
 
 inline bool supported_n(int n) { return n == 1 || n == 2 || n == 4 || n == 8 || n == 16; }
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -32,11 +33,11 @@ int fwd_chunks(int64_t B, int64_t D, int64_t L, int io, bool forced) {
 }
 
 int lti_chunks(int64_t B, int64_t P, int64_t L) {
-    const int64_t waves_per_chunk = B * cdiv(P, 256) * 4;
+    const int64_t waves_per_chunk = B * cdiv(P, 64);
     int64_t n = cdiv(8 * kNumCU, waves_per_chunk);
     const int64_t max_n = cdiv(L, 16);                 // at least 16 steps per chunk
     if (n > max_n) n = max_n;
-    if (n > 1024) n = 1024;                             // each workgroup walks the end states of the chunks before it
+    if (n > 512) n = 512;                               // each workgroup walks the end states of the groups before it
     if (n < 1) n = 1;
     return (int)n;
 }
@@ -72,7 +73,7 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
     }
     if (which == LRNNX_WS_LTI) {
         const int nch = lti_chunks(B, D, L);
-        return nch > 1 ? (size_t)B * nch * D * 2 * sizeof(float) : 0;
+        return nch > 1 ? (size_t)B * (nch + cdiv(nch, kLtiGroup)) * D * 2 * sizeof(float) : 0;
     }
     return 0;
 }
@@ -195,11 +196,13 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
 
     // reduced outputs are accumulated with atomics: clear them on the stream first
     const int64_t nbc = (int64_t)a->B * a->L * a->N;
-    if (launch_fill_zero(a->dA, (int64_t)a->D * a->N, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
-    if (launch_fill_zero(a->dBm, nbc, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
-    if (launch_fill_zero(a->dCm, nbc, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
-    if (a->dD && launch_fill_zero(a->dD, a->D, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
-    if (a->dbias && launch_fill_zero(a->dbias, a->D, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    ZeroList z{};
+    z.ptr[0] = a->dBm; z.count[0] = nbc;
+    z.ptr[1] = a->dCm; z.count[1] = nbc;
+    z.ptr[2] = a->dA; z.count[2] = (int64_t)a->D * a->N;
+    z.ptr[3] = a->dD; z.count[3] = a->D;
+    z.ptr[4] = a->dbias; z.count[4] = a->D;
+    if (launch_fill_zero(z, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
     return launch_ss_bwd(p, a->io_dtype, a->disc, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }
 
@@ -221,10 +224,13 @@ int lrnnx_lti_diag_scan(const lrnnx_lti_args *a) {
     int nch = lti_chunks(a->B, a->P, a->L);
     p.chunk = cdiv(a->L, nch);
     p.nchunks = (int)cdiv(a->L, p.chunk);
+    p.ngroups = (int)cdiv(p.nchunks, kLtiGroup);
+    if (p.ngroups > 65535) return LRNNX_ERR_UNSUPPORTED;
     if (p.nchunks > 1) {
-        const size_t need = (size_t)a->B * p.nchunks * a->P * 2 * sizeof(float);
+        const size_t need = (size_t)a->B * (p.nchunks + p.ngroups) * a->P * 2 * sizeof(float);
         if (!a->workspace || a->workspace_bytes < need) return LRNNX_ERR_WORKSPACE;
         p.ws_S = reinterpret_cast<float2 *>(a->workspace);
+        p.ws_G = p.ws_S + (size_t)a->B * p.nchunks * a->P;
     }
     return launch_lti(p, reinterpret_cast<hipStream_t>(a->stream)) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }

@@ -40,11 +40,12 @@ struct BwdParams {
 struct LtiParams {
     int B, P;
     int64_t L;
-    int nchunks;
+    int nchunks, ngroups;    // chunks, and groups of 4 consecutive chunks
     int64_t chunk;           // time steps per chunk
     const float2 *lambda, *v, *x0;
     float2 *x, *x_last;
-    float2 *ws_S;            // [B,nchunks,P] end state of each chunk started from zero
+    float2 *ws_S;            // [B,nchunks,P] state entering each chunk if its group had started from zero
+    float2 *ws_G;            // [B,ngroups,P] end state of each group started from zero
 };
 
 // Each launcher returns hipSuccess or the launch error; it validates nothing.
@@ -52,7 +53,12 @@ hipError_t launch_ss_fwd(const FwdParams &p, int io_dtype, int disc, hipStream_t
 hipError_t launch_ss_carry(const FwdParams &p, hipStream_t s);
 hipError_t launch_ss_bwd(const BwdParams &p, int io_dtype, int disc, hipStream_t s);
 hipError_t launch_lti(const LtiParams &p, hipStream_t s);
-hipError_t launch_fill_zero(float *ptr, int64_t count, hipStream_t s);
+struct ZeroList {
+    static constexpr int kMax = 5;
+    float *ptr[kMax];
+    int64_t count[kMax];
+};
+hipError_t launch_fill_zero(const ZeroList &z, hipStream_t s);
 
 // Tile geometry the host needs for grids, workspaces and the choice of path.
 int fwd_tile_steps(int io_dtype);            // time steps one workgroup covers per tile

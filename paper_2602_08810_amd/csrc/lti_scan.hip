@@ -4,10 +4,11 @@
 // v and x are [B,L,P] with P contiguous, so the lanes run along P (coalesced 8-byte
 // complex elements) and the time axis is cut into chunks that different workgroups take.
 // Because lambda is constant the affine aggregate of a chunk is (lambda^len, end state
-// from zero): only the end state is stored.  Two launches: the end state of every chunk, then
-// the rescan of every chunk from its true carry-in, which each workgroup first rebuilds for
-// itself from the end states of the chunks before it (Horner in lambda^len over an L2-resident
-// array; the second read of v is served by the L2 / Infinity Cache at these sizes).
+// from zero): only end states are stored.  Two launches.  The first scans every chunk from zero
+// and, inside each workgroup (4 consecutive chunks), chains the end states through LDS.  The
+// second rebuilds each chunk's true carry-in from the end states of the groups before it and its in-group
+// prefix, rescans the chunk and writes x (the second read of v is served by the L2 / Infinity
+// Cache at these sizes, so v comes from HBM once and x is written once).
 #include "kernels.hpp"
 
 namespace lrnnx {
@@ -29,59 +30,71 @@ __device__ __forceinline__ float2 cfma(float2 a, float2 b, float2 c) {   // a*b 
                        __builtin_fmaf(a.x, b.y, __builtin_fmaf(a.y, b.x, c.y)));
 }
 
-constexpr int kLtiThreads = 256;
+constexpr int kLtiWaves = 4;                  // wavefronts per workgroup = consecutive chunks of one group
+constexpr int kLtiThreads = kLtiWaves * 64;
 
-// APPLY = false: end state of each chunk started from zero -> ws_S[b,c,p].
-// APPLY = true : carry-in = x0 pushed through the chunks before this one (from their end states), then
-//                rescan and store x.
+// Lanes run along p (64 complex values = 512 contiguous bytes per time step); wavefront w of a workgroup takes
+// chunk 4*group + w of the same (b, p-slab).
+// APPLY = false: scan each chunk from zero; through LDS, the state entering each chunk if its group had started
+//                from zero -> ws_S[b,c,p], and the group's end state -> ws_G[b,group,p].
+// APPLY = true : carry-in = (x0 pushed through the groups before, Horner over the group end states) pushed
+//                through the w chunks before this one in its group, plus ws_S; then rescan and store x.
 template <bool APPLY>
 __global__ __launch_bounds__(kLtiThreads) void k_lti_chunk(const LtiParams p) {
-    const int pp = blockIdx.x * kLtiThreads + threadIdx.x;
-    if (pp >= p.P) return;
-    const int c = blockIdx.y, b = blockIdx.z;
+    __shared__ float2 sS[kLtiWaves][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int pp = blockIdx.x * 64 + lane;
+    const bool okp = pp < p.P;
+    const int grp = blockIdx.y, b = blockIdx.z;
+    const int c = grp * kLtiWaves + w;
+    const bool okc = c < p.nchunks;
     const int64_t k0 = (int64_t)c * p.chunk;
     const int64_t k1 = (k0 + p.chunk < p.L) ? k0 + p.chunk : p.L;
-    const float2 lam = p.lambda[pp];
+    const float2 lam = okp ? p.lambda[pp] : make_float2(0.0f, 0.0f);
+    const float2 lp = cpow(lam, p.chunk);                        // every chunk but the very last is full
     float2 x = make_float2(0.0f, 0.0f);
-    if (APPLY) {
+    if (APPLY && okp && okc) {
         if (p.x0) x = p.x0[(int64_t)b * p.P + pp];
-        if (c > 0) {                                  // in_{j+1} = lambda^chunk in_j + S_j  (every chunk before c is full)
-            const float2 lp = cpow(lam, p.chunk);
-            const float2 *S = p.ws_S + (int64_t)b * p.nchunks * p.P + pp;
-            int j = 0;
-            for (; j + 4 <= c; j += 4) {
-                const float2 s0 = S[(int64_t)j * p.P], s1 = S[(int64_t)(j + 1) * p.P];
-                const float2 s2 = S[(int64_t)(j + 2) * p.P], s3 = S[(int64_t)(j + 3) * p.P];
-                x = cfma(lp, x, s0); x = cfma(lp, x, s1); x = cfma(lp, x, s2); x = cfma(lp, x, s3);
-            }
-            for (; j < c; ++j) x = cfma(lp, x, S[(int64_t)j * p.P]);
+        if (p.nchunks > 1) {
+            const float2 lg = cpow(lp, kLtiWaves);
+            const float2 *G = p.ws_G + (int64_t)b * p.ngroups * p.P + pp;
+            for (int g = 0; g < grp; ++g) x = cfma(lg, x, G[(int64_t)g * p.P]);
+            x = cfma(cpow(lp, w), x, p.ws_S[((int64_t)b * p.nchunks + c) * p.P + pp]);
         }
     }
-    const float2 *v = p.v + ((int64_t)b * p.L + k0) * p.P + pp;
-    float2 *xo = p.x + ((int64_t)b * p.L + k0) * p.P + pp;
-    int64_t k = k0;
-    for (; k + 4 <= k1; k += 4) {          // four loads in flight per lane
-        float2 v0 = v[0], v1 = v[p.P], v2 = v[2 * (int64_t)p.P], v3 = v[3 * (int64_t)p.P];
-        v += 4 * (int64_t)p.P;
-        x = cfma(lam, x, v0); if (APPLY) xo[0] = x;
-        x = cfma(lam, x, v1); if (APPLY) xo[p.P] = x;
-        x = cfma(lam, x, v2); if (APPLY) xo[2 * (int64_t)p.P] = x;
-        x = cfma(lam, x, v3); if (APPLY) xo[3 * (int64_t)p.P] = x;
-        if (APPLY) xo += 4 * (int64_t)p.P;
+    if (okp && okc) {
+        const float2 *v = p.v + ((int64_t)b * p.L + k0) * p.P + pp;
+        float2 *xo = p.x + ((int64_t)b * p.L + k0) * p.P + pp;
+        const int64_t P = p.P;
+        int64_t k = k0;
+        for (; k + 8 <= k1; k += 8) {          // eight loads in flight per lane
+            float2 vv[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) vv[i] = v[i * P];
+            v += 8 * P;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { x = cfma(lam, x, vv[i]); if (APPLY) xo[i * P] = x; }
+            if (APPLY) xo += 8 * P;
+        }
+        for (; k < k1; ++k) {
+            x = cfma(lam, x, v[0]); v += P;
+            if (APPLY) { xo[0] = x; xo += P; }
+        }
+        if (APPLY && p.x_last && k1 == p.L) p.x_last[(int64_t)b * p.P + pp] = x;
     }
-    for (; k < k1; ++k) {
-        x = cfma(lam, x, v[0]); v += p.P;
-        if (APPLY) { xo[0] = x; xo += p.P; }
+    if (!APPLY) {
+        sS[w][lane] = (okp && okc) ? x : make_float2(0.0f, 0.0f);
+        __syncthreads();
+        float2 e = make_float2(0.0f, 0.0f);
+        for (int ww = 0; ww < w; ++ww) e = cfma(lp, e, sS[ww][lane]);
+        if (okp && okc) p.ws_S[((int64_t)b * p.nchunks + c) * p.P + pp] = e;
+        if (okp && w == kLtiWaves - 1) p.ws_G[((int64_t)b * p.ngroups + grp) * p.P + pp] = cfma(lp, e, sS[w][lane]);
     }
-    if (!APPLY) p.ws_S[((int64_t)b * p.nchunks + c) * p.P + pp] = x;
-    else if (p.x_last && k1 == p.L) p.x_last[(int64_t)b * p.P + pp] = x;
 }
 
 hipError_t launch_lti(const LtiParams &p, hipStream_t s) {
-    dim3 grid((p.P + kLtiThreads - 1) / kLtiThreads, p.nchunks, p.B);
-    if (p.nchunks > 1) {
-        hipLaunchKernelGGL(k_lti_chunk<false>, grid, dim3(kLtiThreads), 0, s, p);
-    }
+    dim3 grid((p.P + 63) / 64, p.ngroups, p.B);
+    if (p.nchunks > 1) hipLaunchKernelGGL(k_lti_chunk<false>, grid, dim3(kLtiThreads), 0, s, p);
     hipLaunchKernelGGL(k_lti_chunk<true>, grid, dim3(kLtiThreads), 0, s, p);
     return hipGetLastError();
 }

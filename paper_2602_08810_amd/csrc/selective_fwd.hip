@@ -203,10 +203,16 @@ __global__ void k_ss_carry(const FwdParams p) {
     }
 }
 
-__global__ void k_fill_zero(float *ptr, int64_t count) {
-    int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+// Clears up to five float buffers in one launch (a fill kernel rather than hipMemsetAsync, so that a caller
+// may capture the library call in a HIP graph).
+__global__ void k_fill_zero(const ZeroList z) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (; i < count; i += stride) ptr[i] = 0.0f;
+#pragma unroll
+    for (int k = 0; k < ZeroList::kMax; ++k) {
+        float *ptr = z.ptr[k];
+        if (!ptr) continue;
+        for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < z.count[k]; i += stride) ptr[i] = 0.0f;
+    }
 }
 
 // ---------------------------------------------------------------- launchers
@@ -260,11 +266,13 @@ hipError_t launch_ss_carry(const FwdParams &p, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_fill_zero(float *ptr, int64_t count, hipStream_t s) {
-    if (count <= 0) return hipSuccess;
-    int64_t blocks = (count + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)blocks), dim3(256), 0, s, ptr, count);
+hipError_t launch_fill_zero(const ZeroList &z, hipStream_t s) {
+    int64_t most = 0;
+    for (int k = 0; k < ZeroList::kMax; ++k) if (z.ptr[k] && z.count[k] > most) most = z.count[k];
+    if (most <= 0) return hipSuccess;
+    int64_t blocks = (most + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)blocks), dim3(256), 0, s, z);
     return hipGetLastError();
 }
 
