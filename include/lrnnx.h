@@ -156,7 +156,8 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *args);
  * for complex numbers stored as interleaved (re, im) float pairs.  v_k = Bbar u_k is
  * the caller's (a dense projection); the call returns the state at every step.
  * lambda[P], v and x [B,L,P] (P contiguous), x0 and x_last [B,P] (optional, NULL
- * allowed).  x may alias v.  workspace: lrnnx_workspace_bytes(LRNNX_WS_LTI, B, P, 0, L, 0). */
+ * allowed).  x may alias v.  workspace: lrnnx_workspace_bytes(LRNNX_WS_LTI, B, P, 0, L, 0); its contents on entry
+ * do not matter (the library clears what it uses on the stream).                      */
 typedef struct lrnnx_lti_args {
     size_t struct_size;
     int32_t B, P;
@@ -168,6 +169,9 @@ typedef struct lrnnx_lti_args {
     void *x_last;
     void *workspace;    size_t workspace_bytes;
     void *stream;
+    int32_t path;            /* lrnnx_path: AUTO / SINGLE_PASS = one launch with look-back between time groups;
+                                CHUNK_CARRY = two launches.  Callers built against the shorter struct get AUTO. */
+    int32_t reserved;
 } lrnnx_lti_args;
 
 int lrnnx_lti_diag_scan(const lrnnx_lti_args *args);

@@ -64,6 +64,7 @@ class LtiArgs(ctypes.Structure):
         ("struct_size", _sz), ("B", _i32), ("P", _i32), ("L", _i64),
         ("lambda_", _vp), ("v", _vp), ("x0", _vp), ("x", _vp), ("x_last", _vp),
         ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
+        ("path", _i32), ("reserved", _i32),
     ]
 
 
@@ -258,7 +259,7 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
     return outs
 
 
-def lrnnx_lti_diag_scan(lam, v, x0=None, return_last_state=False, out=None, workspace=None):
+def lrnnx_lti_diag_scan(lam, v, x0=None, return_last_state=False, out=None, workspace=None, path="auto"):
     """x [B,L,P] complex64 of x_k = lam * x_{k-1} + v_k; see lrnnx_lti_args."""
     if v.dtype != torch.complex64 or lam.dtype != torch.complex64:
         raise TypeError("lam and v must be complex64")
@@ -268,6 +269,7 @@ def lrnnx_lti_diag_scan(lam, v, x0=None, return_last_state=False, out=None, work
     a = LtiArgs()
     a.struct_size = ctypes.sizeof(LtiArgs)
     a.B, a.P, a.L = Bsz, P, L
+    a.path = PATH[path] if isinstance(path, str) else int(path)
     a.lambda_, a.v = lam.data_ptr(), v.data_ptr()
     if x0 is not None:
         if x0.dtype != torch.complex64 or not x0.is_contiguous() or tuple(x0.shape) != (Bsz, P):

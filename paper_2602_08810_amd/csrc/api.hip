@@ -2,6 +2,7 @@
 // Nothing here allocates, frees or synchronises; see include/lrnnx.h for the contract.
 #include "../../include/lrnnx.h"
 #include "kernels.hpp"
+#include <cstddef>
 
 using namespace lrnnx;
 
@@ -42,6 +43,12 @@ int lti_chunks(int64_t B, int64_t P, int64_t L) {
     return (int)n;
 }
 
+// single-pass LTI workspace: T and X [B,ngroups,P] complex, flags [B,ceil(P/64),ngroups] + error word (ints)
+size_t lti_onepass_bytes(int64_t B, int64_t P, int64_t L) {
+    const int64_t ng = cdiv(L, lti_onepass_group_steps());
+    return (size_t)(2 * B * ng * P * 2 * sizeof(float)) + (size_t)(B * cdiv(P, 64) * ng + 64) * sizeof(int);
+}
+
 }  // namespace
 
 extern "C" {
@@ -73,7 +80,9 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
     }
     if (which == LRNNX_WS_LTI) {
         const int nch = lti_chunks(B, D, L);
-        return nch > 1 ? (size_t)B * (nch + cdiv(nch, kLtiGroup)) * D * 2 * sizeof(float) : 0;
+        const size_t two = nch > 1 ? (size_t)B * (nch + cdiv(nch, kLtiGroup)) * D * 2 * sizeof(float) : 0;
+        const size_t one = lti_onepass_bytes(B, D, L);
+        return two > one ? two : one;
     }
     return 0;
 }
@@ -207,13 +216,17 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
 }
 
 int lrnnx_lti_diag_scan(const lrnnx_lti_args *a) {
-    if (!a || a->struct_size < sizeof(lrnnx_lti_args)) return LRNNX_ERR_INVALID_ARG;
+    constexpr size_t kOldSize = offsetof(lrnnx_lti_args, path);          // struct before `path` was appended
+    if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
+    const int path = a->struct_size >= sizeof(lrnnx_lti_args) ? a->path : LRNNX_PATH_AUTO;
+    if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->P < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (!a->lambda || !a->v || !a->x) return LRNNX_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(a->v) & 7u) || (reinterpret_cast<uintptr_t>(a->x) & 7u) ||
         (reinterpret_cast<uintptr_t>(a->lambda) & 7u))
         return LRNNX_ERR_INVALID_ARG;
     if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
+    hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
     LtiParams p{};
     p.B = a->B; p.P = a->P; p.L = a->L;
     p.lambda = reinterpret_cast<const float2 *>(a->lambda);
@@ -221,6 +234,25 @@ int lrnnx_lti_diag_scan(const lrnnx_lti_args *a) {
     p.x0 = reinterpret_cast<const float2 *>(a->x0);
     p.x = reinterpret_cast<float2 *>(a->x);
     p.x_last = reinterpret_cast<float2 *>(a->x_last);
+
+    if (path != LRNNX_PATH_CHUNK_CARRY) {
+        const int64_t ng = cdiv(a->L, lti_onepass_group_steps());
+        const int64_t wgx = (int64_t)a->B * cdiv(a->P, 64);
+        if (ng > 65535 || wgx > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;
+        if (!a->workspace || a->workspace_bytes < lti_onepass_bytes(a->B, a->P, a->L) ||
+            (reinterpret_cast<uintptr_t>(a->workspace) & 7u))
+            return LRNNX_ERR_WORKSPACE;
+        p.ngroups = (int)ng;
+        p.ws_T = reinterpret_cast<float2 *>(a->workspace);
+        p.ws_X = p.ws_T + (size_t)a->B * ng * a->P;
+        p.flags = reinterpret_cast<int *>(p.ws_X + (size_t)a->B * ng * a->P);
+        p.err = p.flags + (size_t)wgx * ng;
+        ZeroList z{};                                   // flags and the error word start at zero (bit pattern of 0.0f)
+        z.ptr[0] = reinterpret_cast<float *>(p.flags); z.count[0] = wgx * ng + 1;
+        if (launch_fill_zero(z, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+        return launch_lti_onepass(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+    }
+
     int nch = lti_chunks(a->B, a->P, a->L);
     p.chunk = cdiv(a->L, nch);
     p.nchunks = (int)cdiv(a->L, p.chunk);
@@ -232,7 +264,7 @@ int lrnnx_lti_diag_scan(const lrnnx_lti_args *a) {
         p.ws_S = reinterpret_cast<float2 *>(a->workspace);
         p.ws_G = p.ws_S + (size_t)a->B * p.nchunks * a->P;
     }
-    return launch_lti(p, reinterpret_cast<hipStream_t>(a->stream)) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+    return launch_lti(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }
 
 }  // extern "C"

@@ -46,6 +46,10 @@ struct LtiParams {
     float2 *x, *x_last;
     float2 *ws_S;            // [B,nchunks,P] state entering each chunk if its group had started from zero
     float2 *ws_G;            // [B,ngroups,P] end state of each group started from zero
+    // single-pass path
+    float2 *ws_T, *ws_X;     // [B,ngroups,P] group end state from zero / true group end state
+    int *flags;              // [B,ceil(P/64),ngroups] 0 = nothing, 1 = ws_T written, 2 = ws_X written
+    int *err;                // set to 1 if a bounded wait ran out
 };
 
 // Each launcher returns hipSuccess or the launch error; it validates nothing.
@@ -53,6 +57,8 @@ hipError_t launch_ss_fwd(const FwdParams &p, int io_dtype, int disc, hipStream_t
 hipError_t launch_ss_carry(const FwdParams &p, hipStream_t s);
 hipError_t launch_ss_bwd(const BwdParams &p, int io_dtype, int disc, hipStream_t s);
 hipError_t launch_lti(const LtiParams &p, hipStream_t s);
+hipError_t launch_lti_onepass(const LtiParams &p, hipStream_t s);
+int lti_onepass_group_steps();
 struct ZeroList {
     static constexpr int kMax = 5;
     float *ptr[kMax];

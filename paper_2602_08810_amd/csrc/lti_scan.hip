@@ -92,6 +92,120 @@ __global__ __launch_bounds__(kLtiThreads) void k_lti_chunk(const LtiParams p) {
     }
 }
 
+// ---------------------------------------------------------------- single pass
+// One launch, v read once and x written once.  A wavefront keeps its 32 steps of v in registers, scans them from
+// zero, the 8 wavefronts of a workgroup (one group = 256 consecutive steps of 64 values of p) chain their end
+// states through LDS, and the groups of one (b, p-slab) are chained through global memory: every group publishes
+// its end-state-from-zero T_g (flag 1) as soon as it has it, then rebuilds its carry-in from the T_j of the groups
+// before it, back to the last "anchor" group, whose true end state X (flag 2) it takes.  Every T_g is available
+// after one load phase, so only anchors wait on a chain (one hop per 16 groups).  Workgroups are ordered so that a
+// group is dispatched after the groups it looks back on (blockIdx.y = group), and every wait is bounded: after
+// kSpinLimit polls a wavefront gives up, raises *err and finishes with a wrong carry rather than hang.
+constexpr int kOneCS = 32;
+constexpr int kOneGW = 8;
+constexpr int kSpinLimit = 1 << 22;
+constexpr int kAnchor = 16;                  // every 16th group publishes its true end state
+
+__global__ __launch_bounds__(kOneGW * 64) void k_lti_onepass(const LtiParams p) {
+    __shared__ float2 sS[kOneGW][64];
+    __shared__ float2 sCarry[64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int npslab = (p.P + 63) / 64;
+    const int pslab = blockIdx.x % npslab, b = blockIdx.x / npslab;
+    const int g = blockIdx.y;
+    const int pp = pslab * 64 + lane;
+    const bool okp = pp < p.P;
+    const int64_t P = p.P;
+    const int64_t k0 = ((int64_t)g * kOneGW + w) * kOneCS;
+    const float2 lam = okp ? p.lambda[pp] : make_float2(0.0f, 0.0f);
+    const float2 lp = cpow(lam, kOneCS), lg = cpow(lp, kOneGW);
+
+    // ---- this wavefront's 32 steps, all loads in flight at once
+    float2 v[kOneCS];
+    const float2 *vp = p.v + ((int64_t)b * p.L + k0) * P + pp;
+#pragma unroll
+    for (int i = 0; i < kOneCS; ++i)
+        v[i] = (okp && k0 + i < p.L) ? vp[i * P] : make_float2(0.0f, 0.0f);
+    float2 x = make_float2(0.0f, 0.0f);
+#pragma unroll
+    for (int i = 0; i < kOneCS; ++i) x = cfma(lam, x, v[i]);
+    sS[w][lane] = x;
+    __syncthreads();
+    float2 e = make_float2(0.0f, 0.0f);                       // state entering this chunk if the group started from zero
+    for (int ww = 0; ww < w; ++ww) e = cfma(lp, e, sS[ww][lane]);
+
+    if (w == 0) {
+        float2 T = make_float2(0.0f, 0.0f);                   // end state of the group started from zero
+#pragma unroll
+        for (int ww = 0; ww < kOneGW; ++ww) T = cfma(lp, T, sS[ww][lane]);
+        int *flags = p.flags + ((int64_t)b * npslab + pslab) * p.ngroups;
+        const int64_t gi = ((int64_t)b * p.ngroups) * P + pp;
+        if (okp) p.ws_T[gi + (int64_t)g * P] = T;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        if (lane == 0) __hip_atomic_store(flags + g, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+        // Carry-in of this group, always by the same arithmetic (so x is bitwise reproducible): start from the true
+        // end state X_m of the last "anchor" group before g (every 16th group publishes one; x0 before the first)
+        // and push it through the end-states-from-zero of the groups in between, oldest first.
+        const int m = (g / kAnchor) * kAnchor - 1;
+        const int need = g - 1 - m;                            // groups m+1 .. g-1 contribute their T (at most 15)
+        // one poll covers every flag this group depends on: lane i < need watches group m+1+i (needs >= 1),
+        // lane `need` watches the anchor m (needs 2)
+        bool failed = false;
+        {
+            const bool watch = lane < need || (lane == need && m >= 0);
+            const int idx = lane < need ? m + 1 + lane : m;
+            const int want = lane < need ? 1 : 2;
+            int spins = 0;
+            bool ok;
+            do {
+                const int f = watch ? __hip_atomic_load(flags + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : want;
+                ok = __builtin_amdgcn_ballot_w64(f < want) == 0;
+            } while (!ok && ++spins < kSpinLimit);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            failed = !ok;
+        }
+        float2 acc = make_float2(0.0f, 0.0f);
+        if (m >= 0) { if (okp) acc = p.ws_X[gi + (int64_t)m * P]; }
+        else if (p.x0 && okp) acc = p.x0[(int64_t)b * P + pp];
+        float2 Tj[kAnchor - 1];
+#pragma unroll
+        for (int i = 0; i < kAnchor - 1; ++i)                  // all loads in flight before the Horner chain
+            Tj[i] = (i < need && okp) ? p.ws_T[gi + (int64_t)(m + 1 + i) * P] : make_float2(0.0f, 0.0f);
+#pragma unroll
+        for (int i = 0; i < kAnchor - 1; ++i)
+            if (i < need) acc = cfma(lg, acc, Tj[i]);
+        if (failed && lane == 0) *p.err = 1;
+        if (g % kAnchor == kAnchor - 1) {
+            if (okp) p.ws_X[gi + (int64_t)g * P] = cfma(lg, acc, T);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            if (lane == 0) __hip_atomic_store(flags + g, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        sCarry[lane] = acc;
+    }
+    __syncthreads();
+
+    // ---- replay from the true carry-in, out of registers
+    x = cfma(cpow(lp, w), sCarry[lane], e);
+    float2 *xo = p.x + ((int64_t)b * p.L + k0) * P + pp;
+#pragma unroll
+    for (int i = 0; i < kOneCS; ++i) {
+        x = cfma(lam, x, v[i]);
+        if (okp && k0 + i < p.L) {
+            xo[i * P] = x;
+            if (p.x_last && k0 + i == p.L - 1) p.x_last[(int64_t)b * P + pp] = x;
+        }
+    }
+}
+
+hipError_t launch_lti_onepass(const LtiParams &p, hipStream_t s) {
+    const int npslab = (p.P + 63) / 64;
+    dim3 grid((unsigned)(npslab * p.B), p.ngroups);
+    hipLaunchKernelGGL(k_lti_onepass, grid, dim3(kOneGW * 64), 0, s, p);
+    return hipGetLastError();
+}
+int lti_onepass_group_steps() { return kOneCS * kOneGW; }
+
 hipError_t launch_lti(const LtiParams &p, hipStream_t s) {
     dim3 grid((p.P + 63) / 64, p.ngroups, p.B);
     if (p.nchunks > 1) hipLaunchKernelGGL(k_lti_chunk<false>, grid, dim3(kLtiThreads), 0, s, p);

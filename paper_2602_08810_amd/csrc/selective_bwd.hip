@@ -259,7 +259,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 }
                 const float dA_tot = wave_sum(dA_part);
                 if (lane == 0) sdA[g * N + n] += dA_tot;
-                __builtin_amdgcn_sched_barrier(0);       // keep the NK state passes from being interleaved (register pressure)
+
             }
             if constexpr (DISC == DISC_ZOH_S6) {     // dDelta += u sum_n H B ;  du = Delta sum_n H B
 #pragma unroll
@@ -351,6 +351,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
         if (p.dbias) unsafeAtomicAdd(p.dbias + d0 + g, sb);
     }
 }
+
 
 #ifndef LRNNX_KERNEL_ONLY
 // ---------------------------------------------------------------- launchers

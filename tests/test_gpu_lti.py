@@ -17,12 +17,12 @@ def api():
     return _api
 
 
-def _run(api, oracle, B, P, L, with_x0, seed, inplace=False):
+def _run(api, oracle, B, P, L, with_x0, seed, inplace=False, path="auto"):
     import torch
     q = workloads.make_lti(B=B, P=P, L=L, seed=seed, with_x0=with_x0)
     lam, v = torch.from_numpy(q["lam"]).cuda(), torch.from_numpy(q["v"]).cuda()
     x0 = torch.from_numpy(q["x0"]).cuda() if with_x0 else None
-    x, x_last = api.lrnnx_lti_diag_scan(lam, v, x0=x0, return_last_state=True, out=v if inplace else None)
+    x, x_last = api.lrnnx_lti_diag_scan(lam, v, x0=x0, return_last_state=True, out=v if inplace else None, path=path)
     ref = oracle.lti_diag_scan(q["lam"], q["v"], x0=q["x0"])
     got = x.cpu().numpy()
     assert rel_err(got.real, ref.real) <= 1e-4 and rel_err(got.imag, ref.imag) <= 1e-4
@@ -30,16 +30,24 @@ def _run(api, oracle, B, P, L, with_x0, seed, inplace=False):
     return got, ref
 
 
-def test_config1(api, oracle):
-    """BASELINE config 1: B=4, P=256, L=4096, complex64."""
-    _run(api, oracle, 4, 256, 4096, False, 1)
+@pytest.mark.parametrize("path", ["single_pass", "chunk_carry"])
+def test_config1(api, oracle, path):
+    """BASELINE config 1: B=4, P=256, L=4096, complex64; one-launch look-back path and two-launch path."""
+    _run(api, oracle, 4, 256, 4096, False, 1, path=path)
 
 
 @pytest.mark.parametrize("B,P,L", [(1, 1, 1), (2, 5, 17), (3, 300, 1000), (1, 64, 33), (2, 257, 4099), (1, 2048, 64),
                                    (1, 64, 8192), (1, 70, 5000)])
 @pytest.mark.parametrize("with_x0", [False, True])
-def test_shapes(api, oracle, B, P, L, with_x0):
-    _run(api, oracle, B, P, L, with_x0, seed=B * 1000 + P + L)
+@pytest.mark.parametrize("path", ["single_pass", "chunk_carry"])
+def test_shapes(api, oracle, B, P, L, with_x0, path):
+    _run(api, oracle, B, P, L, with_x0, seed=B * 1000 + P + L, path=path)
+
+
+def test_long_sequence_many_groups(api, oracle):
+    """L = 65536: 256 time groups chained by look-back in the single-pass kernel."""
+    _run(api, oracle, 1, 96, 65536, True, seed=9, path="single_pass")
+    _run(api, oracle, 1, 96, 65536, True, seed=9, path="chunk_carry")
 
 
 def test_in_place_and_deterministic(api, oracle):
