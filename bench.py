@@ -37,7 +37,7 @@ VALU_PEAK_TLANEOPS = 39.3
 
 # measured HBM traffic of the backward kernel on config 2 (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # copy kernel of known size); filled from profiles/ when a counter run exists, else null
-BWD_TRAFFIC_BYTES = None
+BWD_TRAFFIC_BYTES = 508.1e6   # 222.0 MB read + 286.1 MB written (profiles/config2_fwd_bwd_hbm_traffic.md)
 
 
 def _selective_bytes(B, D, N, L, es, gate, bwd):
@@ -223,10 +223,11 @@ def _other_configs(api, torch, dev):
     v = torch.randn(Bq, Lq, P, dtype=torch.complex64, device=dev, generator=g) * 0.70710678
     x = torch.empty_like(v)
     ws = torch.empty(max(api.lrnnx_workspace_bytes(api.WS_LTI, Bq, P, 0, Lq, 0), 16), dtype=torch.uint8, device=dev)
-    tt = _time(torch, lambda: api.lrnnx_lti_diag_scan(lam, v, out=x, workspace=ws), 50)
     nb = 2 * Bq * Lq * P * 8
-    out["c1_lti"] = {"us": tt * 1e6, "elements_per_s": Bq * Lq * P / tt, "hbm_GBs": nb / tt / 1e9,
-                     "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
+    for path in ("single_pass", "chunk_carry"):
+        tt = _time(torch, lambda: api.lrnnx_lti_diag_scan(lam, v, out=x, workspace=ws, path=path), 50)
+        out[f"c1_lti_{path}"] = {"us": tt * 1e6, "elements_per_s": Bq * Lq * P / tt, "hbm_GBs": nb / tt / 1e9,
+                                 "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
 
     # config 3: long-sequence forward, both paths
     B3, D3, N3, L3 = 1, 2048, 16, 65536
