@@ -144,3 +144,32 @@ def lti_diag_scan(lam, v, x0=None):
     if rc != 0:
         raise ValueError(f"oracle lti: bad arguments (rc={rc})")
     return x
+
+
+def selective_step(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, disc="zoh_s6", delta_softplus=True):
+    """One token: returns (y [B,D], new state [B,D,N]); the input state is not modified."""
+    x = np.array(_f64(x), copy=True)
+    u, delta, A, Bm, Cm = map(_f64, (u, delta, A, Bm, Cm))
+    Dskip, delta_bias, z = map(_f64, (Dskip, delta_bias, z))
+    Bsz, D, N = x.shape
+    assert u.shape == (Bsz, D) and delta.shape == (Bsz, D) and Bm.shape == (Bsz, N) and Cm.shape == (Bsz, N)
+    y = np.empty((Bsz, D))
+    rc = _load().lrnnx_oracle_selective_step(
+        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_int(_disc(disc)),
+        ctypes.c_int(int(bool(delta_softplus))), _p(x), _p(u), _p(delta), _p(A), _p(Bm), _p(Cm),
+        _p(Dskip), _p(delta_bias), _p(z), _p(y))
+    if rc != 0:
+        raise ValueError(f"oracle step: bad arguments (rc={rc})")
+    return y, x
+
+
+def lti_step(lam, x, v):
+    """One token of x <- lam * x + v for complex [B,P] arrays; returns the new state."""
+    lam, v = _c128(lam), _c128(v)
+    x = np.array(_c128(x), copy=True)
+    Bsz, P = x.shape
+    rc = _load().lrnnx_oracle_lti_step(ctypes.c_int(Bsz), ctypes.c_int(P), lam.ctypes.data_as(ctypes.c_void_p),
+                                       x.ctypes.data_as(ctypes.c_void_p), v.ctypes.data_as(ctypes.c_void_p))
+    if rc != 0:
+        raise ValueError(f"oracle lti step: bad arguments (rc={rc})")
+    return x

@@ -279,3 +279,41 @@ def test_lti_scan_agrees_with_selective_scan_on_a_real_pole(oracle):
                                      np.ones((1, L, 1)), np.ones((1, L, 1)), disc="dirac", delta_softplus=False)
     np.testing.assert_allclose(x[0, :, 0].real, y[0, 0], rtol=1e-13)
     assert np.all(x.imag == 0)
+
+
+# ----------------------------------------------------------------------------- single-token step
+
+@pytest.mark.parametrize("disc", DISCS)
+def test_step_by_step_equals_the_scan(oracle, disc):
+    """Mode equivalence (Sec. 3): L calls of the step update reproduce the scan, state and output, and a single
+    step matches Eq. 2 written out by hand."""
+    rng = np.random.default_rng(12)
+    p = _rand_problem(rng, B=2, D=3, N=4, L=11)
+    y_scan, x_last = oracle.selective_scan_fwd(**p, disc=disc)
+    x = p["x0"].copy()
+    for l in range(11):
+        y, x = oracle.selective_step(x, p["u"][:, :, l], p["delta"][:, :, l], p["A"], p["Bm"][:, l], p["Cm"][:, l],
+                                     Dskip=p["Dskip"], delta_bias=p["delta_bias"], z=p["z"][:, :, l], disc=disc)
+        np.testing.assert_allclose(y, y_scan[:, :, l], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(x, x_last, rtol=1e-12, atol=1e-13)
+    # one step by hand for (b, d, n) = (1, 2, 3)
+    b, d, n = 1, 2, 3
+    dt = np.logaddexp(0, p["delta"][b, d, 0] + p["delta_bias"][d])
+    a, g = _disc_py(disc, dt, p["A"][d, n])
+    _, x1 = oracle.selective_step(p["x0"], p["u"][:, :, 0], p["delta"][:, :, 0], p["A"], p["Bm"][:, 0], p["Cm"][:, 0],
+                                  delta_bias=p["delta_bias"], disc=disc)
+    assert x1[b, d, n] == pytest.approx(a * p["x0"][b, d, n] + g * p["Bm"][b, 0, n] * p["u"][b, d, 0], rel=1e-13)
+
+
+def test_lti_step_equals_the_scan(oracle):
+    rng = np.random.default_rng(13)
+    Bsz, L, P = 2, 9, 5
+    lam = rng.uniform(0.9, 0.999, P) * np.exp(1j * rng.uniform(0, 2 * np.pi, P))
+    v = rng.standard_normal((Bsz, L, P)) + 1j * rng.standard_normal((Bsz, L, P))
+    x0 = rng.standard_normal((Bsz, P)) + 1j * rng.standard_normal((Bsz, P))
+    xs = oracle.lti_diag_scan(lam, v, x0=x0)
+    x = x0
+    for k in range(L):
+        x = oracle.lti_step(lam, x, v[:, k])
+        np.testing.assert_allclose(x, xs[:, k], rtol=1e-13)
+    np.testing.assert_allclose(oracle.lti_step(lam, x0, v[:, 0]), lam[None, :] * x0 + v[:, 0], rtol=1e-15)
