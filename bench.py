@@ -229,6 +229,20 @@ def _other_configs(api, torch, dev):
         out[f"c1_lti_{path}"] = {"us": tt * 1e6, "elements_per_s": Bq * Lq * P / tt, "hbm_GBs": nb / tt / 1e9,
                                  "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
 
+    # single-token step (generation): state [B,D,N] read and written once per token
+    Bs, Ds, Ns = 64, 1536, 16
+    ts = sel(Bs, Ds, Ns, 1, True)
+    xs = torch.randn(Bs, Ds, Ns, device=dev, generator=g)
+    ys = torch.empty((Bs, Ds), dtype=bf, device=dev)
+    us, ds_, zs = ts["u"][:, :, 0], ts["delta"][:, :, 0], ts["z"][:, :, 0]
+    Bs1, Cs1 = ts["Bm"][:, 0].contiguous(), ts["Cm"][:, 0].contiguous()
+    tt = _time(torch, lambda: api.lrnnx_selective_step(xs, us, ds_, ts["A"], Bs1, Cs1, Dskip=ts["Dskip"],
+                                                       delta_bias=ts["delta_bias"], z=zs, out=ys), 200)
+    nb = 2 * Bs * Ds * Ns * 4 + 4 * Bs * Ds * 2
+    out["step_B64_D1536_N16"] = {"us": tt * 1e6, "elements_per_s": Bs * Ds * Ns / tt, "hbm_GBs": nb / tt / 1e9,
+                                 "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS,
+                                 "note": "includes the Python call overhead of one launch per token"}
+
     # config 3: long-sequence forward, both paths
     B3, D3, N3, L3 = 1, 2048, 16, 65536
     t3 = sel(B3, D3, N3, L3, False)

@@ -176,6 +176,46 @@ typedef struct lrnnx_lti_args {
 
 int lrnnx_lti_diag_scan(const lrnnx_lti_args *args);
 
+/* ------------------------------------------------------------------ single-token updates
+ * The `step` method of the paper's layers (Sec. 3, "Library Design": every layer implements a step for
+ * autoregressive generation): one application of Eq. 2 to a carried state.
+ *
+ * lrnnx_selective_step: x[B,D,N] (float, updated IN PLACE) <- a (.) x + g Bm[b,:] u[b,d], and
+ * y[b,d] = Cm[b,:] . x[b,d,:] + Dskip[d] u[b,d], times z sigmoid(z) if z != NULL; same Delta transform and
+ * discretisations as the scan.  u, delta, z, y are [B,D] in io_dtype with element strides (so a time slice
+ * of a [B,D,L] tensor can be passed); Bm, Cm are contiguous [B,N] in io_dtype.  L calls reproduce
+ * lrnnx_selective_scan_fwd on L steps up to fp32 rounding.  Optional: Dskip, delta_bias, z.        */
+typedef struct lrnnx_ss_step_args {
+    size_t struct_size;
+    int32_t B, D, N;
+    int32_t io_dtype, disc, delta_softplus;
+    float *x;
+    const void *u;      int64_t u_stride_b, u_stride_d;
+    const void *delta;  int64_t delta_stride_b, delta_stride_d;
+    const float *A;
+    const void *Bm;
+    const void *Cm;
+    const float *Dskip;
+    const float *delta_bias;
+    const void *z;      int64_t z_stride_b, z_stride_d;
+    void *y;            int64_t y_stride_b, y_stride_d;
+    void *stream;
+} lrnnx_ss_step_args;
+
+int lrnnx_selective_step(const lrnnx_ss_step_args *args);
+
+/* lrnnx_lti_step: x[B,P] (complex64, IN PLACE) <- lambda[P] (.) x + v[B,P]. */
+typedef struct lrnnx_lti_step_args {
+    size_t struct_size;
+    int32_t B, P;
+    const void *lambda;
+    void *x;
+    const void *v;
+    void *stream;
+} lrnnx_lti_step_args;
+
+int lrnnx_lti_step(const lrnnx_lti_step_args *args);
+
 /* ------------------------------------------------------------------ queries (host only, no GPU needed) */
 typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2 } lrnnx_ws_kind;
 

@@ -68,6 +68,24 @@ class LtiArgs(ctypes.Structure):
     ]
 
 
+class StepArgs(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32),
+        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32),
+        ("x", _vp),
+        ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
+        ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
+        ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
+        ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
+        ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
+        ("stream", _vp),
+    ]
+
+
+class LtiStepArgs(ctypes.Structure):
+    _fields_ = [("struct_size", _sz), ("B", _i32), ("P", _i32), ("lambda_", _vp), ("x", _vp), ("v", _vp), ("stream", _vp)]
+
+
 _lib = None
 
 
@@ -82,6 +100,10 @@ def lib():
         L.lrnnx_selective_scan_fwd.argtypes = [ctypes.POINTER(FwdArgs)]
         L.lrnnx_selective_scan_bwd.argtypes = [ctypes.POINTER(BwdArgs)]
         L.lrnnx_lti_diag_scan.argtypes = [ctypes.POINTER(LtiArgs)]
+        L.lrnnx_selective_step.argtypes = [ctypes.POINTER(StepArgs)]
+        L.lrnnx_lti_step.argtypes = [ctypes.POINTER(LtiStepArgs)]
+        L.lrnnx_selective_step.restype = ctypes.c_int
+        L.lrnnx_lti_step.restype = ctypes.c_int
         for f in (L.lrnnx_selective_scan_fwd, L.lrnnx_selective_scan_bwd, L.lrnnx_lti_diag_scan, L.lrnnx_version):
             f.restype = ctypes.c_int
         L.lrnnx_workspace_bytes.argtypes = [ctypes.c_int, _i64, _i64, _i64, _i64, ctypes.c_int]
@@ -286,3 +308,57 @@ def lrnnx_lti_diag_scan(lam, v, x0=None, return_last_state=False, out=None, work
     a.stream = _stream()
     _check(lib().lrnnx_lti_diag_scan(ctypes.byref(a)))
     return (x, x_last) if return_last_state else x
+
+
+def _bd(t, name, io):
+    """(ptr, stride_b, stride_d) of a [B,D] tensor (any strides)."""
+    if t is None:
+        return None, 0, 0
+    if t.dim() != 2 or t.dtype != io:
+        raise ValueError(f"{name}: expected a [B,D] tensor of dtype {io}")
+    return t.data_ptr(), t.stride(0), t.stride(1)
+
+
+def lrnnx_selective_step(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None,
+                         disc="zoh_s6", delta_softplus=True, out=None):
+    """One token: updates the state x [B,D,N] in place and returns y [B,D]; see lrnnx_ss_step_args."""
+    io = u.dtype
+    Bsz, D, N = x.shape
+    _f32c(x, "x", (Bsz, D, N))
+    a = StepArgs()
+    a.struct_size = ctypes.sizeof(StepArgs)
+    a.B, a.D, a.N = Bsz, D, N
+    a.io_dtype = _io_dtype(u)
+    a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
+    a.delta_softplus = int(bool(delta_softplus))
+    a.x = x.data_ptr()
+    a.u, a.u_stride_b, a.u_stride_d = _bd(u, "u", io)
+    a.delta, a.delta_stride_b, a.delta_stride_d = _bd(delta, "delta", io)
+    a.z, a.z_stride_b, a.z_stride_d = _bd(z, "z", io)
+    a.A = _ptr(_f32c(A, "A", (D, N)))
+    for name, t in (("Bm", Bm), ("Cm", Cm)):
+        if t.dtype != io or not t.is_contiguous() or tuple(t.shape) != (Bsz, N):
+            raise ValueError(f"{name}: expected contiguous [B,N] of dtype {io}")
+    a.Bm, a.Cm = Bm.data_ptr(), Cm.data_ptr()
+    a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
+    a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
+    y = out if out is not None else torch.empty((Bsz, D), dtype=io, device=u.device)
+    a.y, a.y_stride_b, a.y_stride_d = _bd(y, "y", io)
+    a.stream = _stream()
+    _check(lib().lrnnx_selective_step(ctypes.byref(a)))
+    return y
+
+
+def lrnnx_lti_step(lam, x, v):
+    """One token of the LTI recurrence: x [B,P] complex64 is updated in place and returned."""
+    for name, t in (("lam", lam), ("x", x), ("v", v)):
+        if t.dtype != torch.complex64 or not t.is_contiguous():
+            raise TypeError(f"{name}: expected contiguous complex64")
+    Bsz, P = x.shape
+    a = LtiStepArgs()
+    a.struct_size = ctypes.sizeof(LtiStepArgs)
+    a.B, a.P = Bsz, P
+    a.lambda_, a.x, a.v = lam.data_ptr(), x.data_ptr(), v.data_ptr()
+    a.stream = _stream()
+    _check(lib().lrnnx_lti_step(ctypes.byref(a)))
+    return x

@@ -267,4 +267,34 @@ int lrnnx_lti_diag_scan(const lrnnx_lti_args *a) {
     return launch_lti(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }
 
+int lrnnx_selective_step(const lrnnx_ss_step_args *a) {
+    if (!a || a->struct_size < sizeof(lrnnx_ss_step_args)) return LRNNX_ERR_INVALID_ARG;
+    if (a->B < 1 || a->D < 1 || a->N < 1) return LRNNX_ERR_INVALID_ARG;
+    if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
+    if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
+    if (!a->x || !a->u || !a->delta || !a->A || !a->Bm || !a->Cm || !a->y) return LRNNX_ERR_INVALID_ARG;
+    if (!supported_n(a->N)) return LRNNX_ERR_UNSUPPORTED;
+    if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
+    if (!aligned16(a->x) || !aligned16(a->A) || !aligned16(a->Bm) || !aligned16(a->Cm)) return LRNNX_ERR_INVALID_ARG;
+    StepParams p{};
+    p.B = a->B; p.D = a->D; p.N = a->N; p.softplus = a->delta_softplus ? 1 : 0;
+    p.x = a->x; p.u = a->u; p.delta = a->delta; p.z = a->z; p.Bm = a->Bm; p.Cm = a->Cm; p.y = a->y;
+    p.u_sb = a->u_stride_b; p.u_sd = a->u_stride_d; p.dl_sb = a->delta_stride_b; p.dl_sd = a->delta_stride_d;
+    p.z_sb = a->z_stride_b; p.z_sd = a->z_stride_d; p.y_sb = a->y_stride_b; p.y_sd = a->y_stride_d;
+    p.A = a->A; p.Dskip = a->Dskip; p.bias = a->delta_bias;
+    return launch_ss_step(p, a->io_dtype, a->disc, reinterpret_cast<hipStream_t>(a->stream)) == hipSuccess
+               ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+}
+
+int lrnnx_lti_step(const lrnnx_lti_step_args *a) {
+    if (!a || a->struct_size < sizeof(lrnnx_lti_step_args)) return LRNNX_ERR_INVALID_ARG;
+    if (a->B < 1 || a->P < 1 || !a->lambda || !a->x || !a->v) return LRNNX_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(a->v) & 7u) || (reinterpret_cast<uintptr_t>(a->x) & 7u) ||
+        (reinterpret_cast<uintptr_t>(a->lambda) & 7u))
+        return LRNNX_ERR_INVALID_ARG;
+    return launch_lti_step(a->B, a->P, reinterpret_cast<const float2 *>(a->lambda), reinterpret_cast<float2 *>(a->x),
+                           reinterpret_cast<const float2 *>(a->v), reinterpret_cast<hipStream_t>(a->stream)) == hipSuccess
+               ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+}
+
 }  // extern "C"
