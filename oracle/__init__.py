@@ -146,6 +146,23 @@ def lti_diag_scan(lam, v, x0=None):
     return x
 
 
+def lti_diag_scan_bwd(lam, v, gx, x0=None):
+    """Gradients (dv [B,L,P], dlam [P], dx0 [B,P]) of a real loss with dLoss/dRe(x) + i dLoss/dIm(x) = gx."""
+    lam, v, gx = _c128(lam), _c128(v), _c128(gx)
+    Bsz, L, P = v.shape
+    assert lam.shape == (P,) and gx.shape == v.shape
+    x0c = None if x0 is None else _c128(x0)
+    dv = np.empty((Bsz, L, P), dtype=np.complex128)
+    dlam = np.empty(P, dtype=np.complex128)
+    dx0 = np.empty((Bsz, P), dtype=np.complex128)
+    cp = lambda a: ctypes.c_void_p(0) if a is None else a.ctypes.data_as(ctypes.c_void_p)
+    rc = _load().lrnnx_oracle_lti_diag_scan_bwd(
+        ctypes.c_int(Bsz), ctypes.c_long(L), ctypes.c_int(P), cp(lam), cp(v), cp(x0c), cp(gx), cp(dv), cp(dlam), cp(dx0))
+    if rc != 0:
+        raise ValueError(f"oracle lti bwd: bad arguments (rc={rc})")
+    return dv, dlam, dx0
+
+
 def selective_step(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, disc="zoh_s6", delta_softplus=True):
     """One token: returns (y [B,D], new state [B,D,N]); the input state is not modified."""
     x = np.array(_f64(x), copy=True)

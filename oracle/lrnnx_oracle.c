@@ -21,7 +21,8 @@
  * Parity pins (tests/test_oracle_pins.py): brute-force unrolled sum, LTI
  * convolution closed form, impulse response, scipy.signal.lfilter and
  * cont2discrete, exact-ZOH step response, central finite differences, adjoint
- * dot test, linearity / causality / chaining invariants.
+ * dot test, linearity / causality / chaining invariants; for the LTI backward: finite differences of a real
+ * loss over real and imaginary parts, the L = 1 closed form, the reversed-forward-scan identity.
  * Parity unpinned: which of the two "ZOH" input maps (disc 0 or 1) the
  * paper's own "zoh" string selects; the paper's asynchronous scheme is read
  * as "the caller supplies Delta per step" (delta_softplus = 0).
@@ -264,6 +265,57 @@ int lrnnx_oracle_lti_diag_scan(int B, long L, int P,
             xr = nr; xi = ni;
             x[idx] = xr; x[idx + 1] = xi;
         }
+    }
+    return 0;
+}
+
+/* Backward of the time-invariant complex-diagonal recurrence (the adjoint recurrence of Sec. 2.2.1's
+ * x_k = lambda x_{k-1} + v_k).  A real loss depends on x through gx_k = dLoss/dRe(x_k) + i dLoss/dIm(x_k);
+ * gradients of complex quantities follow the same convention.  Because x_k is holomorphic in x_{k-1}, v_k and
+ * lambda, the chain rule multiplies by the CONJUGATE of the holomorphic derivative:
+ *     g_k   = gx_k + conj(lambda) g_{k+1},  g_{L+1} = 0     (total gradient reaching x_k)
+ *     dv_k  = g_k
+ *     dx0   = conj(lambda) g_1
+ *     dlam  = sum_b sum_k conj(x_{k-1}) g_k
+ * The states are recomputed here from (lambda, v, x0); xs is a scratch row of L+1 complex numbers per thread.  */
+int lrnnx_oracle_lti_diag_scan_bwd(int B, long L, int P,
+                                   const double *lambda, const double *v, const double *x0,
+                                   const double *gx, double *dv, double *dlambda, double *dx0)
+{
+    if (B < 0 || L < 0 || P < 0) return 1;
+#pragma omp parallel
+    {
+        double *xs = (double *)malloc(sizeof(double) * 2 * (size_t)(L + 1));
+#pragma omp for schedule(static)
+        for (int p = 0; p < P; ++p) {
+            double lr = lambda[2 * p], li = lambda[2 * p + 1];
+            double dlr = 0.0, dli = 0.0;
+            for (int b = 0; b < B; ++b) {
+                long row = (long)b * P + p;
+                xs[0] = x0 ? x0[2 * row] : 0.0;
+                xs[1] = x0 ? x0[2 * row + 1] : 0.0;
+                for (long k = 0; k < L; ++k) {                      /* x_{k+1} in slot k+1 */
+                    long idx = 2 * (((long)b * L + k) * P + p);
+                    xs[2 * (k + 1)]     = lr * xs[2 * k] - li * xs[2 * k + 1] + v[idx];
+                    xs[2 * (k + 1) + 1] = lr * xs[2 * k + 1] + li * xs[2 * k] + v[idx + 1];
+                }
+                double gr = 0.0, gi = 0.0;                          /* conj(lambda) g_{k+1}, carried backwards */
+                for (long k = L - 1; k >= 0; --k) {
+                    long idx = 2 * (((long)b * L + k) * P + p);
+                    double tr = gx[idx] + gr, ti = gx[idx + 1] + gi;   /* g_k */
+                    dv[idx] = tr; dv[idx + 1] = ti;
+                    /* conj(x_{k-1}) g_k : (xr - i xi)(tr + i ti) */
+                    dlr += xs[2 * k] * tr + xs[2 * k + 1] * ti;
+                    dli += xs[2 * k] * ti - xs[2 * k + 1] * tr;
+                    /* conj(lambda) g_k : (lr - i li)(tr + i ti) */
+                    gr = lr * tr + li * ti;
+                    gi = lr * ti - li * tr;
+                }
+                if (dx0) { dx0[2 * row] = gr; dx0[2 * row + 1] = gi; }
+            }
+            dlambda[2 * p] = dlr; dlambda[2 * p + 1] = dli;
+        }
+        free(xs);
     }
     return 0;
 }

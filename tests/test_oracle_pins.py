@@ -317,3 +317,78 @@ def test_lti_step_equals_the_scan(oracle):
         x = oracle.lti_step(lam, x, v[:, k])
         np.testing.assert_allclose(x, xs[:, k], rtol=1e-13)
     np.testing.assert_allclose(oracle.lti_step(lam, x0, v[:, 0]), lam[None, :] * x0 + v[:, 0], rtol=1e-15)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# LTI backward (adjoint of x_k = lam x_{k-1} + v_k, Sec. 2.2.1).  Convention: grad_z = dLoss/dRe z + i dLoss/dIm z.
+# ---------------------------------------------------------------------------------------------------------------
+def _lti_case(seed, B=2, L=9, P=3):
+    rng = np.random.default_rng(seed)
+    lam = (0.6 + 0.35 * rng.random(P)) * np.exp(1j * rng.uniform(-1.0, 1.0, P))
+    c = lambda *s: rng.standard_normal(s) + 1j * rng.standard_normal(s)
+    return lam, c(B, L, P), c(B, P), c(B, L, P)
+
+
+def test_lti_bwd_finite_differences_real_and_imaginary(oracle):
+    """Loss = sum Re(conj(w) x) has gx = w; every real and imaginary part of v, lam, x0 is perturbed."""
+    lam, v, x0, w = _lti_case(21)
+    dv, dlam, dx0 = oracle.lti_diag_scan_bwd(lam, v, w, x0=x0)
+    loss = lambda lam_, v_, x0_: float(np.sum((np.conj(w) * oracle.lti_diag_scan(lam_, v_, x0=x0_)).real))
+    h = 1e-6
+
+    def fd(which, idx, unit):
+        args = [lam.copy(), v.copy(), x0.copy()]
+        args[which][idx] += h * unit
+        up = loss(*args)
+        args[which][idx] -= 2 * h * unit
+        return (up - loss(*args)) / (2 * h)
+
+    for which, grad in ((0, dlam), (1, dv), (2, dx0)):
+        for idx in np.ndindex(grad.shape):
+            num = fd(which, idx, 1.0) + 1j * fd(which, idx, 1j)
+            assert abs(num - grad[idx]) <= 1e-7 * (1 + abs(grad[idx])), (which, idx, num, grad[idx])
+
+
+def test_lti_bwd_single_step_closed_form(oracle):
+    lam, v, x0, w = _lti_case(22, B=3, L=1, P=4)
+    dv, dlam, dx0 = oracle.lti_diag_scan_bwd(lam, v, w, x0=x0)
+    np.testing.assert_allclose(dv, w, rtol=1e-15)
+    np.testing.assert_allclose(dx0, np.conj(lam)[None, :] * w[:, 0], rtol=1e-14)
+    np.testing.assert_allclose(dlam, (np.conj(x0) * w[:, 0]).sum(0), rtol=1e-13)
+
+
+def test_lti_bwd_dv_is_the_time_reversed_scan_with_conjugate_pole(oracle):
+    """dv reversed in time obeys the forward recurrence with conj(lam) driven by the reversed gx; and with x0 = 0,
+    a one-step sequence dlam vanishes (x_0 = 0 is the only state multiplied by lam)."""
+    lam, v, x0, w = _lti_case(23, B=2, L=40, P=5)
+    dv, dlam, dx0 = oracle.lti_diag_scan_bwd(lam, v, w, x0=x0)
+    rev = oracle.lti_diag_scan(np.conj(lam), w[:, ::-1])[:, ::-1]
+    np.testing.assert_allclose(dv, rev, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(dx0, np.conj(lam)[None, :] * dv[:, 0], rtol=1e-13)
+    # dlam by the explicit double sum over pairs (j < k): x_{k-1} = lam^{k-1} x0 + sum_{j<k} lam^{k-1-j} v_j
+    B, L, P = v.shape
+    ref = np.zeros(P, dtype=complex)
+    for b in range(B):
+        for k in range(1, L + 1):                  # 1-based step k, state x_{k-1}
+            xprev = lam ** (k - 1) * x0[b] + sum(lam ** (k - 1 - j) * v[b, j - 1] for j in range(1, k))
+            ref += np.conj(xprev) * dv[b, k - 1]
+    np.testing.assert_allclose(dlam, ref, rtol=1e-11)
+    _, dl1, _ = oracle.lti_diag_scan_bwd(lam, v[:, :1], w[:, :1])
+    assert np.all(dl1 == 0)
+
+
+def test_lti_bwd_matches_library_autograd(oracle):
+    """torch's complex autograd on a plain Python loop of the recurrence (its grad convention is the same)."""
+    import torch
+    lam, v, x0, w = _lti_case(24, B=2, L=12, P=3)
+    tl, tv, tx0 = (torch.tensor(a, dtype=torch.complex128, requires_grad=True) for a in (lam, v, x0))
+    x, xs = tx0, []
+    for k in range(v.shape[1]):
+        x = tl * x + tv[:, k]
+        xs.append(x)
+    loss = (torch.conj(torch.tensor(w)) * torch.stack(xs, 1)).real.sum()
+    loss.backward()
+    dv, dlam, dx0 = oracle.lti_diag_scan_bwd(lam, v, w, x0=x0)
+    np.testing.assert_allclose(dv, tv.grad.numpy(), rtol=1e-12)
+    np.testing.assert_allclose(dlam, tl.grad.numpy(), rtol=1e-12)
+    np.testing.assert_allclose(dx0, tx0.grad.numpy(), rtol=1e-12)
