@@ -157,7 +157,9 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *args);
  * the caller's (a dense projection); the call returns the state at every step.
  * lambda[P], v and x [B,L,P] (P contiguous), x0 and x_last [B,P] (optional, NULL
  * allowed).  x may alias v.  workspace: lrnnx_workspace_bytes(LRNNX_WS_LTI, B, P, 0, L, 0); its contents on entry
- * do not matter (the library clears what it uses on the stream).                      */
+ * do not matter (the library clears what it uses on the stream).  The single-launch path chains workgroups
+ * through flags in global memory with bounded waits; should a wait ever run out, the states from that point of
+ * that sequence on are written as NaN rather than left plausible.                     */
 typedef struct lrnnx_lti_args {
     size_t struct_size;
     int32_t B, P;
@@ -175,6 +177,34 @@ typedef struct lrnnx_lti_args {
 } lrnnx_lti_args;
 
 int lrnnx_lti_diag_scan(const lrnnx_lti_args *args);
+
+/* ------------------------------------------------------------------ backward of the LTI scan
+ * Adjoint of the recurrence above (Sec. 2.2.1; the paper trains these layers through the same scan).  For a real
+ * loss, the gradient of a complex quantity q is dLoss/dRe(q) + i dLoss/dIm(q) (the convention of complex
+ * autograd).  With gx[b,k,p] the gradient reaching x[b,k,p] from the layers above:
+ *     g_k  = gx_k + conj(lambda) g_{k+1}  (g beyond the last step is 0),   dv_k = g_k,
+ *     dx0  = conj(lambda) g_first,        dlambda[p] = sum_b sum_k conj(x[b,k-1,p]) g[b,k,p]   (x[b,-1] = x0).
+ * x is the array the forward call wrote (states are not recomputed), x0 the forward call's (NULL = zero).
+ * gx and dv [B,L,P], dv may alias gx; dlambda[P] is OVERWRITTEN (cleared on the stream, then accumulated with
+ * float atomics: its last bits may differ from run to run; dv and dx0 are bitwise reproducible); dx0 [B,P] or NULL.
+ * All arrays device memory, 8-byte aligned, contiguous.  workspace:
+ * lrnnx_workspace_bytes(LRNNX_WS_LTI_BWD, B, P, 0, L, 0), contents on entry irrelevant.                          */
+typedef struct lrnnx_lti_bwd_args {
+    size_t struct_size;
+    int32_t B, P;
+    int64_t L;
+    const void *lambda;     /* [P] */
+    const void *x;          /* [B,L,P] forward states */
+    const void *x0;         /* [B,P] or NULL */
+    const void *gx;         /* [B,L,P] */
+    void *dv;               /* [B,L,P] out */
+    void *dlambda;          /* [P] out */
+    void *dx0;              /* [B,P] out or NULL */
+    void *workspace;    size_t workspace_bytes;
+    void *stream;
+} lrnnx_lti_bwd_args;
+
+int lrnnx_lti_diag_scan_bwd(const lrnnx_lti_bwd_args *args);
 
 /* ------------------------------------------------------------------ single-token updates
  * The `step` method of the paper's layers (Sec. 3, "Library Design": every layer implements a step for
@@ -217,10 +247,10 @@ typedef struct lrnnx_lti_step_args {
 int lrnnx_lti_step(const lrnnx_lti_step_args *args);
 
 /* ------------------------------------------------------------------ queries (host only, no GPU needed) */
-typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2 } lrnnx_ws_kind;
+typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2, LRNNX_WS_LTI_BWD = 3 } lrnnx_ws_kind;
 
 /* Bytes of device scratch the call may need (the largest over its paths).
- * For LRNNX_WS_LTI pass P as D and 0 for N.  Returns 0 for invalid sizes.   */
+ * For LRNNX_WS_LTI and LRNNX_WS_LTI_BWD pass P as D and 0 for N.  Returns 0 for invalid sizes.   */
 size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t L, int io_dtype);
 
 const char *lrnnx_status_string(int status);

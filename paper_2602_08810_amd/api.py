@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("LRNNX_LIB", os.path.join(_HERE, "liblrnnx.so"))   # L
 F32, BF16 = 0, 1
 DISC = {"zoh_s6": 0, "zoh": 1, "bilinear": 2, "dirac": 3}
 PATH = {"auto": 0, "single_pass": 1, "chunk_carry": 2}
-WS_FWD, WS_BWD, WS_LTI = 0, 1, 2
+WS_FWD, WS_BWD, WS_LTI, WS_LTI_BWD = 0, 1, 2, 3
 STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported", 3: "workspace", 4: "launch"}
 
 _vp, _i32, _i64, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
@@ -68,6 +68,14 @@ class LtiArgs(ctypes.Structure):
     ]
 
 
+class LtiBwdArgs(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", _sz), ("B", _i32), ("P", _i32), ("L", _i64),
+        ("lambda_", _vp), ("x", _vp), ("x0", _vp), ("gx", _vp), ("dv", _vp), ("dlambda", _vp), ("dx0", _vp),
+        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
+    ]
+
+
 class StepArgs(ctypes.Structure):
     _fields_ = [
         ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32),
@@ -100,6 +108,8 @@ def lib():
         L.lrnnx_selective_scan_fwd.argtypes = [ctypes.POINTER(FwdArgs)]
         L.lrnnx_selective_scan_bwd.argtypes = [ctypes.POINTER(BwdArgs)]
         L.lrnnx_lti_diag_scan.argtypes = [ctypes.POINTER(LtiArgs)]
+        L.lrnnx_lti_diag_scan_bwd.argtypes = [ctypes.POINTER(LtiBwdArgs)]
+        L.lrnnx_lti_diag_scan_bwd.restype = ctypes.c_int
         L.lrnnx_selective_step.argtypes = [ctypes.POINTER(StepArgs)]
         L.lrnnx_lti_step.argtypes = [ctypes.POINTER(LtiStepArgs)]
         L.lrnnx_selective_step.restype = ctypes.c_int
@@ -308,6 +318,36 @@ def lrnnx_lti_diag_scan(lam, v, x0=None, return_last_state=False, out=None, work
     a.stream = _stream()
     _check(lib().lrnnx_lti_diag_scan(ctypes.byref(a)))
     return (x, x_last) if return_last_state else x
+
+
+def lrnnx_lti_diag_scan_bwd(lam, x, gx, x0=None, want_dx0=True, out=None, workspace=None):
+    """(dv [B,L,P], dlam [P], dx0 [B,P] or None) from the saved states x and the incoming gradient gx;
+    see lrnnx_lti_bwd_args."""
+    for t, name in ((lam, "lam"), (x, "x"), (gx, "gx")):
+        if t.dtype != torch.complex64 or not t.is_contiguous():
+            raise ValueError(f"{name}: expected contiguous complex64")
+    Bsz, L, P = x.shape
+    if tuple(gx.shape) != (Bsz, L, P) or tuple(lam.shape) != (P,):
+        raise ValueError("shape mismatch between lam [P], x and gx [B,L,P]")
+    a = LtiBwdArgs()
+    a.struct_size = ctypes.sizeof(LtiBwdArgs)
+    a.B, a.P, a.L = Bsz, P, L
+    a.lambda_, a.x, a.gx = lam.data_ptr(), x.data_ptr(), gx.data_ptr()
+    if x0 is not None:
+        if x0.dtype != torch.complex64 or not x0.is_contiguous() or tuple(x0.shape) != (Bsz, P):
+            raise ValueError("x0: expected contiguous complex64 [B,P]")
+        a.x0 = x0.data_ptr()
+    dv = out if out is not None else torch.empty_like(gx)
+    dlam = torch.empty(P, dtype=torch.complex64, device=x.device)
+    dx0 = torch.empty((Bsz, P), dtype=torch.complex64, device=x.device) if want_dx0 else None
+    a.dv, a.dlambda, a.dx0 = dv.data_ptr(), dlam.data_ptr(), _ptr(dx0)
+    if workspace is None:
+        nbytes = lrnnx_workspace_bytes(WS_LTI_BWD, Bsz, P, 0, L, 0)
+        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
+    a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    a.stream = _stream()
+    _check(lib().lrnnx_lti_diag_scan_bwd(ctypes.byref(a)))
+    return dv, dlam, dx0
 
 
 def _bd(t, name, io):

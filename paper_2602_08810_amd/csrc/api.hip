@@ -49,6 +49,11 @@ size_t lti_onepass_bytes(int64_t B, int64_t P, int64_t L) {
     return (size_t)(2 * B * ng * P * 2 * sizeof(float)) + (size_t)(B * cdiv(P, 64) * ng + 64) * sizeof(int);
 }
 
+size_t lti_onepass_bwd_bytes(int64_t B, int64_t P, int64_t L) {
+    const int64_t ng = cdiv(L, lti_onepass_bwd_group_steps());
+    return (size_t)(2 * B * ng * P * 2 * sizeof(float)) + (size_t)(B * cdiv(P, 64) * ng + 64) * sizeof(int);
+}
+
 }  // namespace
 
 extern "C" {
@@ -84,6 +89,7 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
         const size_t one = lti_onepass_bytes(B, D, L);
         return two > one ? two : one;
     }
+    if (which == LRNNX_WS_LTI_BWD) return lti_onepass_bwd_bytes(B, D, L);
     return 0;
 }
 
@@ -265,6 +271,41 @@ int lrnnx_lti_diag_scan(const lrnnx_lti_args *a) {
         p.ws_G = p.ws_S + (size_t)a->B * p.nchunks * a->P;
     }
     return launch_lti(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+}
+
+int lrnnx_lti_diag_scan_bwd(const lrnnx_lti_bwd_args *a) {
+    if (!a || a->struct_size < sizeof(lrnnx_lti_bwd_args)) return LRNNX_ERR_INVALID_ARG;
+    if (a->B < 1 || a->P < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
+    if (!a->lambda || !a->x || !a->gx || !a->dv || !a->dlambda) return LRNNX_ERR_INVALID_ARG;
+    for (const void *q : {a->lambda, a->x, a->x0, a->gx, (const void *)a->dv, (const void *)a->dlambda,
+                          (const void *)a->dx0})
+        if (reinterpret_cast<uintptr_t>(q) & 7u) return LRNNX_ERR_INVALID_ARG;
+    const int64_t ng = cdiv(a->L, lti_onepass_bwd_group_steps());
+    const int64_t wgx = (int64_t)a->B * cdiv(a->P, 64);
+    if (ng > 65535 || wgx > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;
+    if (!a->workspace || a->workspace_bytes < lti_onepass_bwd_bytes(a->B, a->P, a->L) ||
+        (reinterpret_cast<uintptr_t>(a->workspace) & 7u))
+        return LRNNX_ERR_WORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
+    LtiParams p{};
+    p.B = a->B; p.P = a->P; p.L = a->L;
+    p.lambda = reinterpret_cast<const float2 *>(a->lambda);
+    p.v = reinterpret_cast<const float2 *>(a->gx);
+    p.xs = reinterpret_cast<const float2 *>(a->x);
+    p.x0 = reinterpret_cast<const float2 *>(a->x0);
+    p.x = reinterpret_cast<float2 *>(a->dv);
+    p.x_last = reinterpret_cast<float2 *>(a->dx0);
+    p.dlambda = reinterpret_cast<float *>(a->dlambda);
+    p.ngroups = (int)ng;
+    p.ws_T = reinterpret_cast<float2 *>(a->workspace);
+    p.ws_X = p.ws_T + (size_t)a->B * ng * a->P;
+    p.flags = reinterpret_cast<int *>(p.ws_X + (size_t)a->B * ng * a->P);
+    p.err = p.flags + (size_t)wgx * ng;
+    ZeroList z{};
+    z.ptr[0] = reinterpret_cast<float *>(p.flags); z.count[0] = wgx * ng + 1;
+    z.ptr[1] = p.dlambda;                          z.count[1] = 2 * (int64_t)a->P;
+    if (launch_fill_zero(z, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    return launch_lti_onepass_bwd(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }
 
 int lrnnx_selective_step(const lrnnx_ss_step_args *a) {

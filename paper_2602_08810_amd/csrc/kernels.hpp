@@ -50,6 +50,9 @@ struct LtiParams {
     float2 *ws_T, *ws_X;     // [B,ngroups,P] group end state from zero / true group end state
     int *flags;              // [B,ceil(P/64),ngroups] 0 = nothing, 1 = ws_T written, 2 = ws_X written
     int *err;                // set to 1 if a bounded wait ran out
+    // adjoint (single-pass only): v = gx, x = dv, x_last = dx0, x0 = the forward pass's x0
+    const float2 *xs;        // [B,L,P] states saved by the forward scan
+    float *dlambda;          // [P] complex as float pairs, accumulated with atomics (zero it first)
 };
 
 struct StepParams {
@@ -71,6 +74,8 @@ hipError_t launch_ss_bwd(const BwdParams &p, int io_dtype, int disc, hipStream_t
 hipError_t launch_lti(const LtiParams &p, hipStream_t s);
 hipError_t launch_lti_onepass(const LtiParams &p, hipStream_t s);
 int lti_onepass_group_steps();
+hipError_t launch_lti_onepass_bwd(const LtiParams &p, hipStream_t s);
+int lti_onepass_bwd_group_steps();
 struct ZeroList {
     static constexpr int kMax = 5;
     float *ptr[kMax];

@@ -100,12 +100,19 @@ __global__ __launch_bounds__(kLtiThreads) void k_lti_chunk(const LtiParams p) {
 // before it, back to the last "anchor" group, whose true end state X (flag 2) it takes.  Every T_g is available
 // after one load phase, so only anchors wait on a chain (one hop per 16 groups).  Workgroups are ordered so that a
 // group is dispatched after the groups it looks back on (blockIdx.y = group), and every wait is bounded: after
-// kSpinLimit polls a wavefront gives up, raises *err and finishes with a wrong carry rather than hang.
+// kSpinLimit polls a wavefront gives up, raises *err and finishes with a NaN carry rather than hang.
 constexpr int kOneCS = 32;
+constexpr int kOneBwdCS = 16;               // the adjoint also holds the saved states of its steps in registers
 constexpr int kOneGW = 8;
 constexpr int kSpinLimit = 1 << 22;
 constexpr int kAnchor = 16;                  // every 16th group publishes its true end state
 
+// BWD = false: the scan itself.  BWD = true: its adjoint (Sec. 2.2.1's recurrence differentiated): the same chain
+// run over reversed time with the conjugate pole, g_k = gx_k + conj(lambda) g_{k+1}, reading gx through p.v and
+// writing dv = g through p.x; each wavefront also loads the saved forward state before each of its steps and
+// accumulates dlambda += conj(x_{k-1}) g_k, reduced over the workgroup in LDS and added to p.dlambda with one
+// atomic pair per lane.  The scan position j maps to time k = j (forward) or k = L-1-j (adjoint).
+template <int CS, bool BWD>
 __global__ __launch_bounds__(kOneGW * 64) void k_lti_onepass(const LtiParams p) {
     __shared__ float2 sS[kOneGW][64];
     __shared__ float2 sCarry[64];
@@ -116,19 +123,34 @@ __global__ __launch_bounds__(kOneGW * 64) void k_lti_onepass(const LtiParams p) 
     const int pp = pslab * 64 + lane;
     const bool okp = pp < p.P;
     const int64_t P = p.P;
-    const int64_t k0 = ((int64_t)g * kOneGW + w) * kOneCS;
-    const float2 lam = okp ? p.lambda[pp] : make_float2(0.0f, 0.0f);
-    const float2 lp = cpow(lam, kOneCS), lg = cpow(lp, kOneGW);
+    const int64_t k0 = ((int64_t)g * kOneGW + w) * CS;
+    float2 lam = okp ? p.lambda[pp] : make_float2(0.0f, 0.0f);
+    if (BWD) lam.y = -lam.y;
+    const float2 lp = cpow(lam, CS), lg = cpow(lp, kOneGW);
+    const int64_t tstep = BWD ? -P : P;                        // element stride between consecutive scan positions
+    const int64_t first = ((int64_t)b * p.L + (BWD ? p.L - 1 - k0 : k0)) * P + pp;
 
-    // ---- this wavefront's 32 steps, all loads in flight at once
-    float2 v[kOneCS];
-    const float2 *vp = p.v + ((int64_t)b * p.L + k0) * P + pp;
+    // ---- this wavefront's steps, all loads in flight at once
+    float2 v[CS];
+    const float2 *vp = p.v + first;
 #pragma unroll
-    for (int i = 0; i < kOneCS; ++i)
-        v[i] = (okp && k0 + i < p.L) ? vp[i * P] : make_float2(0.0f, 0.0f);
+    for (int i = 0; i < CS; ++i)
+        v[i] = (okp && k0 + i < p.L) ? vp[i * tstep] : make_float2(0.0f, 0.0f);
+    float2 xprev[BWD ? CS : 1];
+    if constexpr (BWD) {
+        // state before time step k = L-1-(k0+i): the saved x at k-1, or x0 (zero if absent) for k = 0
+        const float2 *xp = p.xs + first - P;
+#pragma unroll
+        for (int i = 0; i < CS; ++i) {
+            const int64_t k = p.L - 1 - (k0 + i);
+            xprev[i] = make_float2(0.0f, 0.0f);
+            if (okp && k > 0) xprev[i] = xp[i * tstep];
+            else if (okp && k == 0 && p.x0) xprev[i] = p.x0[(int64_t)b * P + pp];
+        }
+    }
     float2 x = make_float2(0.0f, 0.0f);
 #pragma unroll
-    for (int i = 0; i < kOneCS; ++i) x = cfma(lam, x, v[i]);
+    for (int i = 0; i < CS; ++i) x = cfma(lam, x, v[i]);
     sS[w][lane] = x;
     __syncthreads();
     float2 e = make_float2(0.0f, 0.0f);                       // state entering this chunk if the group started from zero
@@ -167,7 +189,7 @@ __global__ __launch_bounds__(kOneGW * 64) void k_lti_onepass(const LtiParams p) 
         }
         float2 acc = make_float2(0.0f, 0.0f);
         if (m >= 0) { if (okp) acc = p.ws_X[gi + (int64_t)m * P]; }
-        else if (p.x0 && okp) acc = p.x0[(int64_t)b * P + pp];
+        else if (!BWD && p.x0 && okp) acc = p.x0[(int64_t)b * P + pp];   // the adjoint starts from g_{L+1} = 0
         float2 Tj[kAnchor - 1];
 #pragma unroll
         for (int i = 0; i < kAnchor - 1; ++i)                  // all loads in flight before the Horner chain
@@ -175,7 +197,10 @@ __global__ __launch_bounds__(kOneGW * 64) void k_lti_onepass(const LtiParams p) 
 #pragma unroll
         for (int i = 0; i < kAnchor - 1; ++i)
             if (i < need) acc = cfma(lg, acc, Tj[i]);
-        if (failed && lane == 0) *p.err = 1;
+        if (failed) {                                          // never hand back a plausible but wrong state
+            if (lane == 0) *p.err = 1;
+            acc = make_float2(__builtin_nanf(""), __builtin_nanf(""));
+        }
         if (g % kAnchor == kAnchor - 1) {
             if (okp) p.ws_X[gi + (int64_t)g * P] = cfma(lg, acc, T);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
@@ -187,13 +212,29 @@ __global__ __launch_bounds__(kOneGW * 64) void k_lti_onepass(const LtiParams p) 
 
     // ---- replay from the true carry-in, out of registers
     x = cfma(cpow(lp, w), sCarry[lane], e);
-    float2 *xo = p.x + ((int64_t)b * p.L + k0) * P + pp;
+    float2 *xo = p.x + first;
+    float2 dl = make_float2(0.0f, 0.0f);
 #pragma unroll
-    for (int i = 0; i < kOneCS; ++i) {
+    for (int i = 0; i < CS; ++i) {
         x = cfma(lam, x, v[i]);
         if (okp && k0 + i < p.L) {
-            xo[i * P] = x;
-            if (p.x_last && k0 + i == p.L - 1) p.x_last[(int64_t)b * P + pp] = x;
+            xo[i * tstep] = x;
+            if constexpr (BWD) {                               // conj(xprev) * g
+                dl.x = __builtin_fmaf(xprev[i].x, x.x, __builtin_fmaf(xprev[i].y, x.y, dl.x));
+                dl.y = __builtin_fmaf(xprev[i].x, x.y, __builtin_fmaf(-xprev[i].y, x.x, dl.y));
+            }
+            if (p.x_last && k0 + i == p.L - 1) p.x_last[(int64_t)b * P + pp] = BWD ? cmul(lam, x) : x;
+        }
+    }
+    if constexpr (BWD) {
+        __syncthreads();                                       // sS is free again: every wavefront has read its prefix
+        sS[w][lane] = dl;
+        __syncthreads();
+        if (w == 0 && okp) {
+#pragma unroll
+            for (int ww = 1; ww < kOneGW; ++ww) { dl.x += sS[ww][lane].x; dl.y += sS[ww][lane].y; }
+            atomicAdd(p.dlambda + 2 * pp, dl.x);
+            atomicAdd(p.dlambda + 2 * pp + 1, dl.y);
         }
     }
 }
@@ -201,10 +242,18 @@ __global__ __launch_bounds__(kOneGW * 64) void k_lti_onepass(const LtiParams p) 
 hipError_t launch_lti_onepass(const LtiParams &p, hipStream_t s) {
     const int npslab = (p.P + 63) / 64;
     dim3 grid((unsigned)(npslab * p.B), p.ngroups);
-    hipLaunchKernelGGL(k_lti_onepass, grid, dim3(kOneGW * 64), 0, s, p);
+    hipLaunchKernelGGL((k_lti_onepass<kOneCS, false>), grid, dim3(kOneGW * 64), 0, s, p);
     return hipGetLastError();
 }
 int lti_onepass_group_steps() { return kOneCS * kOneGW; }
+
+hipError_t launch_lti_onepass_bwd(const LtiParams &p, hipStream_t s) {
+    const int npslab = (p.P + 63) / 64;
+    dim3 grid((unsigned)(npslab * p.B), p.ngroups);
+    hipLaunchKernelGGL((k_lti_onepass<kOneBwdCS, true>), grid, dim3(kOneGW * 64), 0, s, p);
+    return hipGetLastError();
+}
+int lti_onepass_bwd_group_steps() { return kOneBwdCS * kOneGW; }
 
 hipError_t launch_lti(const LtiParams &p, hipStream_t s) {
     dim3 grid((p.P + 63) / 64, p.ngroups, p.B);

@@ -69,11 +69,12 @@ def make_selective(B, D, N, L, io="f32", gate=False, bias=("const", -2.0), seed=
     return out
 
 
-def make_lti(B, P, L, seed=1, with_x0=False, **_unused):
+def make_lti(B, P, L, seed=1, with_x0=False, with_gx=False, **_unused):
     """Inputs of the LTI complex-diagonal scan.
 
     lambda = r e^{i theta}, r ~ U(0.9, 0.999), theta ~ U(0, 2 pi);
-    v = (N(0,1) + i N(0,1)) / sqrt(2), complex64 [B,L,P].
+    v = (N(0,1) + i N(0,1)) / sqrt(2), complex64 [B,L,P]; gx (the gradient reaching the states, for the
+    backward pass) is drawn like v, after everything else.
     """
     rng = np.random.Generator(np.random.PCG64(seed))
     r = rng.uniform(0.9, 0.999, size=P)
@@ -86,7 +87,12 @@ def make_lti(B, P, L, seed=1, with_x0=False, **_unused):
     x0 = None
     if with_x0:
         x0 = (rng.standard_normal((B, P)) + 1j * rng.standard_normal((B, P))).astype(np.complex64)
-    return {"lam": lam, "v": v, "x0": x0}
+    gx = None
+    if with_gx:
+        gx = np.empty((B, L, P), dtype=np.complex64)
+        gx.real = rng.standard_normal((B, L, P), dtype=np.float32) * s
+        gx.imag = rng.standard_normal((B, L, P), dtype=np.float32) * s
+    return {"lam": lam, "v": v, "x0": x0, "gx": gx}
 
 
 def make(name: str, **overrides):
