@@ -229,6 +229,36 @@ def _other_configs(api, torch, dev):
         out[f"c1_lti_{path}"] = {"us": tt * 1e6, "elements_per_s": Bq * Lq * P / tt, "hbm_GBs": nb / tt / 1e9,
                                  "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
 
+    # backward of the LTI scan at config 1's shape: reads gx and the saved states, writes dv
+    gx = torch.randn(Bq, Lq, P, dtype=torch.complex64, device=dev, generator=g) * 0.70710678
+    api.lrnnx_lti_diag_scan(lam, v, out=x, workspace=ws)
+    dvq = torch.empty_like(v)
+    wsb = torch.empty(max(api.lrnnx_workspace_bytes(api.WS_LTI_BWD, Bq, P, 0, Lq, 0), 16), dtype=torch.uint8, device=dev)
+    tt = _time(torch, lambda: api.lrnnx_lti_diag_scan_bwd(lam, x, gx, out=dvq, workspace=wsb), 50)
+    nb = 3 * Bq * Lq * P * 8
+    out["c1_lti_bwd"] = {"us": tt * 1e6, "elements_per_s": Bq * Lq * P / tt, "hbm_GBs": nb / tt / 1e9,
+                         "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
+    del gx, dvq, wsb
+
+    # the same two calls on tensors well beyond the 256 MB Infinity Cache (B=8, P=1024, L=8192: 512 MiB each)
+    Bl, Pl, Ll = 8, 1024, 8192
+    laml = torch.polar(torch.rand(Pl, device=dev, generator=g) * 0.099 + 0.9,
+                       torch.rand(Pl, device=dev, generator=g) * 6.2831853)
+    vl = torch.randn(Bl, Ll, Pl, dtype=torch.complex64, device=dev, generator=g) * 0.70710678
+    xl = torch.empty_like(vl)
+    wsl = torch.empty(max(api.lrnnx_workspace_bytes(api.WS_LTI, Bl, Pl, 0, Ll, 0),
+                          api.lrnnx_workspace_bytes(api.WS_LTI_BWD, Bl, Pl, 0, Ll, 0), 16), dtype=torch.uint8, device=dev)
+    tt = _time(torch, lambda: api.lrnnx_lti_diag_scan(laml, vl, out=xl, workspace=wsl), 10)
+    nb = 2 * Bl * Ll * Pl * 8
+    out["lti_B8_P1024_L8192_fwd"] = {"us": tt * 1e6, "elements_per_s": Bl * Ll * Pl / tt, "hbm_GBs": nb / tt / 1e9,
+                                     "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
+    gl = torch.randn(Bl, Ll, Pl, dtype=torch.complex64, device=dev, generator=g) * 0.70710678
+    tt = _time(torch, lambda: api.lrnnx_lti_diag_scan_bwd(laml, xl, gl, out=gl, workspace=wsl), 10)
+    nb = 3 * Bl * Ll * Pl * 8
+    out["lti_B8_P1024_L8192_bwd"] = {"us": tt * 1e6, "elements_per_s": Bl * Ll * Pl / tt, "hbm_GBs": nb / tt / 1e9,
+                                     "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
+    del vl, xl, gl, wsl
+
     # single-token step (generation): state [B,D,N] read and written once per token
     Bs, Ds, Ns = 64, 1536, 16
     ts = sel(Bs, Ds, Ns, 1, True)

@@ -43,15 +43,28 @@ int lti_chunks(int64_t B, int64_t P, int64_t L) {
     return (int)n;
 }
 
-// single-pass LTI workspace: T and X [B,ngroups,P] complex, flags [B,ceil(P/64),ngroups] + error word (ints)
-size_t lti_onepass_bytes(int64_t B, int64_t P, int64_t L) {
-    const int64_t ng = cdiv(L, lti_onepass_group_steps());
-    return (size_t)(2 * B * ng * P * 2 * sizeof(float)) + (size_t)(B * cdiv(P, 64) * ng + 64) * sizeof(int);
+// single-pass LTI workspace: T [B,ngroups,P] and X [B,ngroups/16+1,P] complex, then the error word
+constexpr int kLtiAnchor = 16;            // must match lti_scan.hip
+size_t onepass_bytes(int64_t B, int64_t P, int64_t ng) {
+    return (size_t)(B * (ng + ng / kLtiAnchor + 1) * P * 2 * sizeof(float)) + 64 * sizeof(int);
 }
-
+size_t lti_onepass_bytes(int64_t B, int64_t P, int64_t L) { return onepass_bytes(B, P, cdiv(L, lti_onepass_min_group_steps())); }
 size_t lti_onepass_bwd_bytes(int64_t B, int64_t P, int64_t L) {
-    const int64_t ng = cdiv(L, lti_onepass_bwd_group_steps());
-    return (size_t)(2 * B * ng * P * 2 * sizeof(float)) + (size_t)(B * cdiv(P, 64) * ng + 64) * sizeof(int);
+    return onepass_bytes(B, P, cdiv(L, lti_onepass_bwd_group_steps()));
+}
+void set_onepass_workspace(LtiParams &p, void *ws) {
+    p.ws_T = reinterpret_cast<float2 *>(ws);
+    p.ws_X = p.ws_T + (size_t)p.B * p.ngroups * p.P;
+    p.err = reinterpret_cast<int *>(p.ws_X + (size_t)p.B * (p.ngroups / kLtiAnchor + 1) * p.P);
+}
+// every slot starts as "not published" (all-ones words), the error word as zero
+FillList onepass_fill(const LtiParams &p) {
+    FillList z{};
+    z.ptr[0] = reinterpret_cast<float *>(p.ws_T);
+    z.count[0] = 2 * (int64_t)p.B * (p.ngroups + p.ngroups / kLtiAnchor + 1) * p.P;
+    z.bits[0] = 0xffffffffu;
+    z.ptr[1] = reinterpret_cast<float *>(p.err); z.count[1] = 1;
+    return z;
 }
 
 }  // namespace
@@ -211,13 +224,13 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
 
     // reduced outputs are accumulated with atomics: clear them on the stream first
     const int64_t nbc = (int64_t)a->B * a->L * a->N;
-    ZeroList z{};
+    FillList z{};
     z.ptr[0] = a->dBm; z.count[0] = nbc;
     z.ptr[1] = a->dCm; z.count[1] = nbc;
     z.ptr[2] = a->dA; z.count[2] = (int64_t)a->D * a->N;
     z.ptr[3] = a->dD; z.count[3] = a->D;
     z.ptr[4] = a->dbias; z.count[4] = a->D;
-    if (launch_fill_zero(z, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    if (launch_fill(z, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
     return launch_ss_bwd(p, a->io_dtype, a->disc, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }
 
@@ -242,20 +255,15 @@ int lrnnx_lti_diag_scan(const lrnnx_lti_args *a) {
     p.x_last = reinterpret_cast<float2 *>(a->x_last);
 
     if (path != LRNNX_PATH_CHUNK_CARRY) {
-        const int64_t ng = cdiv(a->L, lti_onepass_group_steps());
+        const int64_t ng = cdiv(a->L, lti_onepass_group_steps(a->B, a->P));
         const int64_t wgx = (int64_t)a->B * cdiv(a->P, 64);
         if (ng > 65535 || wgx > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;
         if (!a->workspace || a->workspace_bytes < lti_onepass_bytes(a->B, a->P, a->L) ||
             (reinterpret_cast<uintptr_t>(a->workspace) & 7u))
             return LRNNX_ERR_WORKSPACE;
         p.ngroups = (int)ng;
-        p.ws_T = reinterpret_cast<float2 *>(a->workspace);
-        p.ws_X = p.ws_T + (size_t)a->B * ng * a->P;
-        p.flags = reinterpret_cast<int *>(p.ws_X + (size_t)a->B * ng * a->P);
-        p.err = p.flags + (size_t)wgx * ng;
-        ZeroList z{};                                   // flags and the error word start at zero (bit pattern of 0.0f)
-        z.ptr[0] = reinterpret_cast<float *>(p.flags); z.count[0] = wgx * ng + 1;
-        if (launch_fill_zero(z, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+        set_onepass_workspace(p, a->workspace);
+        if (launch_fill(onepass_fill(p), s) != hipSuccess) return LRNNX_ERR_LAUNCH;
         return launch_lti_onepass(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
     }
 
@@ -297,14 +305,10 @@ int lrnnx_lti_diag_scan_bwd(const lrnnx_lti_bwd_args *a) {
     p.x_last = reinterpret_cast<float2 *>(a->dx0);
     p.dlambda = reinterpret_cast<float *>(a->dlambda);
     p.ngroups = (int)ng;
-    p.ws_T = reinterpret_cast<float2 *>(a->workspace);
-    p.ws_X = p.ws_T + (size_t)a->B * ng * a->P;
-    p.flags = reinterpret_cast<int *>(p.ws_X + (size_t)a->B * ng * a->P);
-    p.err = p.flags + (size_t)wgx * ng;
-    ZeroList z{};
-    z.ptr[0] = reinterpret_cast<float *>(p.flags); z.count[0] = wgx * ng + 1;
-    z.ptr[1] = p.dlambda;                          z.count[1] = 2 * (int64_t)a->P;
-    if (launch_fill_zero(z, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    set_onepass_workspace(p, a->workspace);
+    FillList z = onepass_fill(p);
+    z.ptr[2] = p.dlambda; z.count[2] = 2 * (int64_t)a->P;
+    if (launch_fill(z, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
     return launch_lti_onepass_bwd(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }
 

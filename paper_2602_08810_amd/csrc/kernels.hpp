@@ -47,8 +47,8 @@ struct LtiParams {
     float2 *ws_S;            // [B,nchunks,P] state entering each chunk if its group had started from zero
     float2 *ws_G;            // [B,ngroups,P] end state of each group started from zero
     // single-pass path
-    float2 *ws_T, *ws_X;     // [B,ngroups,P] group end state from zero / true group end state
-    int *flags;              // [B,ceil(P/64),ngroups] 0 = nothing, 1 = ws_T written, 2 = ws_X written
+    float2 *ws_T;            // [B,ngroups,P] group end state from zero; all-ones words = not published yet
+    float2 *ws_X;            // [B,ngroups/16+1,P] true end state of every 16th group; all-ones = not published
     int *err;                // set to 1 if a bounded wait ran out
     // adjoint (single-pass only): v = gx, x = dv, x_last = dx0, x0 = the forward pass's x0
     const float2 *xs;        // [B,L,P] states saved by the forward scan
@@ -73,15 +73,17 @@ hipError_t launch_ss_carry(const FwdParams &p, hipStream_t s);
 hipError_t launch_ss_bwd(const BwdParams &p, int io_dtype, int disc, hipStream_t s);
 hipError_t launch_lti(const LtiParams &p, hipStream_t s);
 hipError_t launch_lti_onepass(const LtiParams &p, hipStream_t s);
-int lti_onepass_group_steps();
+int lti_onepass_group_steps(int64_t B, int64_t P);   // time steps per chained group for this shape
+int lti_onepass_min_group_steps();                   // the smallest it can be (sizes the workspace)
 hipError_t launch_lti_onepass_bwd(const LtiParams &p, hipStream_t s);
 int lti_onepass_bwd_group_steps();
-struct ZeroList {
+struct FillList {
     static constexpr int kMax = 5;
     float *ptr[kMax];
-    int64_t count[kMax];
+    int64_t count[kMax];     // 32-bit words
+    uint32_t bits[kMax];     // the word written (0 = 0.0f)
 };
-hipError_t launch_fill_zero(const ZeroList &z, hipStream_t s);
+hipError_t launch_fill(const FillList &z, hipStream_t s);
 
 // Tile geometry the host needs for grids, workspaces and the choice of path.
 int fwd_tile_steps(int io_dtype);            // time steps one workgroup covers per tile

@@ -94,58 +94,107 @@ __global__ __launch_bounds__(kLtiThreads) void k_lti_chunk(const LtiParams p) {
 
 // ---------------------------------------------------------------- single pass
 // One launch, v read once and x written once.  A wavefront keeps its 32 steps of v in registers, scans them from
-// zero, the 8 wavefronts of a workgroup (one group = 256 consecutive steps of 64 values of p) chain their end
+// zero, the 4 or 8 wavefronts of a workgroup (one group = 128 or 256 consecutive steps of 64 values of p) chain their end
 // states through LDS, and the groups of one (b, p-slab) are chained through global memory: every group publishes
-// its end-state-from-zero T_g (flag 1) as soon as it has it, then rebuilds its carry-in from the T_j of the groups
-// before it, back to the last "anchor" group, whose true end state X (flag 2) it takes.  Every T_g is available
-// after one load phase, so only anchors wait on a chain (one hop per 16 groups).  Workgroups are ordered so that a
-// group is dispatched after the groups it looks back on (blockIdx.y = group), and every wait is bounded: after
-// kSpinLimit polls a wavefront gives up, raises *err and finishes with a NaN carry rather than hang.
-constexpr int kOneCS = 32;
-constexpr int kOneBwdCS = 16;               // the adjoint also holds the saved states of its steps in registers
-constexpr int kOneGW = 8;
+// its end-state-from-zero T_g as soon as it has it, then rebuilds its carry-in from the T_j of the groups
+// before it, back to the last "anchor" group, whose true end state X it takes.  Every T_g is available
+// after one load phase, so only anchors wait on a chain (one hop per 16 groups).  A published value is its own
+// ready flag (see publish() below), so a hop costs one store and one load round trip and needs no fence.
+// Workgroups are ordered so that a group is dispatched after the groups it looks back on (blockIdx.y = group),
+// and every wait is bounded: after kSpinLimit polls a wavefront gives up, raises *err and finishes with a NaN
+// carry rather than hang.
+constexpr int kOneCS = 32;                   // steps a wavefront keeps in registers
+constexpr int kOneGWSmall = 4, kOneGWLarge = 8;   // wavefronts per group: see lti_onepass_group_steps()
+constexpr int kOneBwdCS = 32, kOneBwdGW = 4;      // the adjoint also holds the saved states of its steps
 constexpr int kSpinLimit = 1 << 22;
 constexpr int kAnchor = 16;                  // every 16th group publishes its true end state
+
+// element of a wave-uniform row at a lane's 32-bit byte offset (scalar base + vector offset addressing)
+__device__ __forceinline__ const float2 &at(const float2 *row, unsigned byte_off) {
+    return *reinterpret_cast<const float2 *>(reinterpret_cast<const char *>(row) + byte_off);
+}
+__device__ __forceinline__ float2 &at(float2 *row, unsigned byte_off) {
+    return *reinterpret_cast<float2 *>(reinterpret_cast<char *>(row) + byte_off);
+}
+
+// A published slot is an 8-byte complex value written by one relaxed atomic store at agent scope; kNotReady
+// (all ones, a NaN pattern that arithmetic does not produce from other inputs) marks an empty slot, and a
+// value that happens to equal it is stored as the canonical NaN instead.
+constexpr unsigned long long kNotReady = ~0ull;
+__device__ __forceinline__ void publish(float2 *slot, float2 val) {
+    unsigned long long bits = ((unsigned long long)__float_as_uint(val.y) << 32) | __float_as_uint(val.x);
+    if (bits == kNotReady) bits = 0x7fc000007fc00000ull;
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(slot), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long peek(const float2 *slot) {
+    return __hip_atomic_load(reinterpret_cast<const unsigned long long *>(slot), __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 from_bits(unsigned long long bits) {
+    return make_float2(__uint_as_float((unsigned)bits), __uint_as_float((unsigned)(bits >> 32)));
+}
 
 // BWD = false: the scan itself.  BWD = true: its adjoint (Sec. 2.2.1's recurrence differentiated): the same chain
 // run over reversed time with the conjugate pole, g_k = gx_k + conj(lambda) g_{k+1}, reading gx through p.v and
 // writing dv = g through p.x; each wavefront also loads the saved forward state before each of its steps and
 // accumulates dlambda += conj(x_{k-1}) g_k, reduced over the workgroup in LDS and added to p.dlambda with one
 // atomic pair per lane.  The scan position j maps to time k = j (forward) or k = L-1-j (adjoint).
-template <int CS, bool BWD>
+template <int CS, int kOneGW, bool BWD>
 __global__ __launch_bounds__(kOneGW * 64) void k_lti_onepass(const LtiParams p) {
     __shared__ float2 sS[kOneGW][64];
     __shared__ float2 sCarry[64];
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int npslab = (p.P + 63) / 64;
     const int pslab = blockIdx.x % npslab, b = blockIdx.x / npslab;
     const int g = blockIdx.y;
     const int pp = pslab * 64 + lane;
+    const unsigned boff = (unsigned)pp * 8u;                   // the lane's byte offset within a row of P values
     const bool okp = pp < p.P;
     const int64_t P = p.P;
     const int64_t k0 = ((int64_t)g * kOneGW + w) * CS;
     float2 lam = okp ? p.lambda[pp] : make_float2(0.0f, 0.0f);
     if (BWD) lam.y = -lam.y;
     const float2 lp = cpow(lam, CS), lg = cpow(lp, kOneGW);
+    // Row pointers are wave-uniform (scalar registers) and the lane adds only its p, so a whole chunk needs one
+    // vector offset register; scan position k0+i is time k0+i (forward) or L-1-(k0+i) (adjoint).
     const int64_t tstep = BWD ? -P : P;                        // element stride between consecutive scan positions
-    const int64_t first = ((int64_t)b * p.L + (BWD ? p.L - 1 - k0 : k0)) * P + pp;
+    const int64_t row0 = ((int64_t)b * p.L + (BWD ? p.L - 1 - k0 : k0)) * P;
+    const bool full = k0 + CS <= p.L;                          // no step of this chunk is beyond the sequence
 
     // ---- this wavefront's steps, all loads in flight at once
     float2 v[CS];
-    const float2 *vp = p.v + first;
 #pragma unroll
-    for (int i = 0; i < CS; ++i)
-        v[i] = (okp && k0 + i < p.L) ? vp[i * tstep] : make_float2(0.0f, 0.0f);
+    for (int i = 0; i < CS; ++i) v[i] = make_float2(0.0f, 0.0f);
+    const float2 *vrow = p.v + row0;
+    if (full) {
+        if (okp) {
+#pragma unroll
+            for (int i = 0; i < CS; ++i) v[i] = at(vrow + i * tstep, boff);
+        }
+    } else if (okp) {
+#pragma unroll
+        for (int i = 0; i < CS; ++i)
+            if (k0 + i < p.L) v[i] = at(vrow + i * tstep, boff);
+    }
     float2 xprev[BWD ? CS : 1];
     if constexpr (BWD) {
         // state before time step k = L-1-(k0+i): the saved x at k-1, or x0 (zero if absent) for k = 0
-        const float2 *xp = p.xs + first - P;
 #pragma unroll
-        for (int i = 0; i < CS; ++i) {
-            const int64_t k = p.L - 1 - (k0 + i);
-            xprev[i] = make_float2(0.0f, 0.0f);
-            if (okp && k > 0) xprev[i] = xp[i * tstep];
-            else if (okp && k == 0 && p.x0) xprev[i] = p.x0[(int64_t)b * P + pp];
+        for (int i = 0; i < CS; ++i) xprev[i] = make_float2(0.0f, 0.0f);
+        const float2 *xrow = p.xs + row0 - P;
+        if (k0 + CS < p.L) {                                   // every k of this chunk is at least 1
+            if (okp) {
+#pragma unroll
+                for (int i = 0; i < CS; ++i) xprev[i] = at(xrow + i * tstep, boff);
+            }
+        } else if (okp) {
+#pragma unroll
+            for (int i = 0; i < CS; ++i) {
+                const int64_t k = p.L - 1 - (k0 + i);
+                if (k > 0) xprev[i] = at(xrow + i * tstep, boff);
+                else if (k == 0 && p.x0) xprev[i] = p.x0[(int64_t)b * P + pp];
+            }
         }
     }
     float2 x = make_float2(0.0f, 0.0f);
@@ -160,72 +209,75 @@ __global__ __launch_bounds__(kOneGW * 64) void k_lti_onepass(const LtiParams p) 
         float2 T = make_float2(0.0f, 0.0f);                   // end state of the group started from zero
 #pragma unroll
         for (int ww = 0; ww < kOneGW; ++ww) T = cfma(lp, T, sS[ww][lane]);
-        int *flags = p.flags + ((int64_t)b * npslab + pslab) * p.ngroups;
-        const int64_t gi = ((int64_t)b * p.ngroups) * P + pp;
-        if (okp) p.ws_T[gi + (int64_t)g * P] = T;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        if (lane == 0) __hip_atomic_store(flags + g, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int nanch = p.ngroups / kAnchor + 1;
+        float2 *wsT = p.ws_T + ((int64_t)b * p.ngroups) * P + pp;
+        float2 *wsX = p.ws_X + ((int64_t)b * nanch) * P + pp;
+        if (okp) publish(wsT + (int64_t)g * P, T);
 
         // Carry-in of this group, always by the same arithmetic (so x is bitwise reproducible): start from the true
         // end state X_m of the last "anchor" group before g (every 16th group publishes one; x0 before the first)
         // and push it through the end-states-from-zero of the groups in between, oldest first.
         const int m = (g / kAnchor) * kAnchor - 1;
         const int need = g - 1 - m;                            // groups m+1 .. g-1 contribute their T (at most 15)
-        // one poll covers every flag this group depends on: lane i < need watches group m+1+i (needs >= 1),
-        // lane `need` watches the anchor m (needs 2)
-        bool failed = false;
-        {
-            const bool watch = lane < need || (lane == need && m >= 0);
-            const int idx = lane < need ? m + 1 + lane : m;
-            const int want = lane < need ? 1 : 2;
-            int spins = 0;
-            bool ok;
-            do {
-                const int f = watch ? __hip_atomic_load(flags + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : want;
-                ok = __builtin_amdgcn_ballot_w64(f < want) == 0;
-            } while (!ok && ++spins < kSpinLimit);
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            failed = !ok;
-        }
-        float2 acc = make_float2(0.0f, 0.0f);
-        if (m >= 0) { if (okp) acc = p.ws_X[gi + (int64_t)m * P]; }
-        else if (!BWD && p.x0 && okp) acc = p.x0[(int64_t)b * P + pp];   // the adjoint starts from g_{L+1} = 0
-        float2 Tj[kAnchor - 1];
+        // Every lane polls the slots of its own p: all loads of one round are in flight together, and a slot is
+        // its own ready flag (it holds kNotReady until its 8-byte value is stored), so no fence is involved.
+        unsigned long long tb[kAnchor - 1] = {}, xb = 0;
+        int spins = 0;
+        bool ok;
+        do {
+            bool mine = true;
 #pragma unroll
-        for (int i = 0; i < kAnchor - 1; ++i)                  // all loads in flight before the Horner chain
-            Tj[i] = (i < need && okp) ? p.ws_T[gi + (int64_t)(m + 1 + i) * P] : make_float2(0.0f, 0.0f);
+            for (int i = 0; i < kAnchor - 1; ++i)
+                if (i < need && okp) { tb[i] = peek(wsT + (int64_t)(m + 1 + i) * P); mine &= tb[i] != kNotReady; }
+            if (m >= 0 && okp) { xb = peek(wsX + (int64_t)(m / kAnchor) * P); mine &= xb != kNotReady; }
+            ok = __builtin_amdgcn_ballot_w64(!mine) == 0;
+        } while (!ok && ++spins < kSpinLimit);
+        float2 acc = make_float2(0.0f, 0.0f);
+        if (m >= 0) acc = from_bits(xb);
+        else if (!BWD && p.x0 && okp) acc = p.x0[(int64_t)b * P + pp];   // the adjoint starts from g_{L+1} = 0
 #pragma unroll
         for (int i = 0; i < kAnchor - 1; ++i)
-            if (i < need) acc = cfma(lg, acc, Tj[i]);
-        if (failed) {                                          // never hand back a plausible but wrong state
+            if (i < need) acc = cfma(lg, acc, from_bits(tb[i]));
+        if (!ok) {                                             // never hand back a plausible but wrong state
             if (lane == 0) *p.err = 1;
             acc = make_float2(__builtin_nanf(""), __builtin_nanf(""));
         }
-        if (g % kAnchor == kAnchor - 1) {
-            if (okp) p.ws_X[gi + (int64_t)g * P] = cfma(lg, acc, T);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-            if (lane == 0) __hip_atomic_store(flags + g, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        if (g % kAnchor == kAnchor - 1 && okp) publish(wsX + (int64_t)(g / kAnchor) * P, cfma(lg, acc, T));
         sCarry[lane] = acc;
     }
     __syncthreads();
 
     // ---- replay from the true carry-in, out of registers
     x = cfma(cpow(lp, w), sCarry[lane], e);
-    float2 *xo = p.x + first;
+    float2 *xrow_out = p.x + row0;
     float2 dl = make_float2(0.0f, 0.0f);
+    float2 xl = x;                                             // state at the last scan position of the sequence
+    auto dlam_term = [&](int i) {                              // dl += conj(xprev) * g
+        dl.x = __builtin_fmaf(xprev[BWD ? i : 0].x, x.x, __builtin_fmaf(xprev[BWD ? i : 0].y, x.y, dl.x));
+        dl.y = __builtin_fmaf(xprev[BWD ? i : 0].x, x.y, __builtin_fmaf(-xprev[BWD ? i : 0].y, x.x, dl.y));
+    };
+    if (full) {
+        if (okp) {
 #pragma unroll
-    for (int i = 0; i < CS; ++i) {
-        x = cfma(lam, x, v[i]);
-        if (okp && k0 + i < p.L) {
-            xo[i * tstep] = x;
-            if constexpr (BWD) {                               // conj(xprev) * g
-                dl.x = __builtin_fmaf(xprev[i].x, x.x, __builtin_fmaf(xprev[i].y, x.y, dl.x));
-                dl.y = __builtin_fmaf(xprev[i].x, x.y, __builtin_fmaf(-xprev[i].y, x.x, dl.y));
+            for (int i = 0; i < CS; ++i) {
+                x = cfma(lam, x, v[i]);
+                at(xrow_out + i * tstep, boff) = x;
+                if constexpr (BWD) dlam_term(i);
             }
-            if (p.x_last && k0 + i == p.L - 1) p.x_last[(int64_t)b * P + pp] = BWD ? cmul(lam, x) : x;
+        }
+        xl = x;
+    } else if (okp) {
+#pragma unroll
+        for (int i = 0; i < CS; ++i) {
+            x = cfma(lam, x, v[i]);
+            if (k0 + i < p.L) {
+                at(xrow_out + i * tstep, boff) = x;
+                if constexpr (BWD) dlam_term(i);
+                xl = x;
+            }
         }
     }
+    if (p.x_last && okp && k0 < p.L && p.L <= k0 + CS) p.x_last[(int64_t)b * P + pp] = BWD ? cmul(lam, xl) : xl;
     if constexpr (BWD) {
         __syncthreads();                                       // sS is free again: every wavefront has read its prefix
         sS[w][lane] = dl;
@@ -239,21 +291,30 @@ __global__ __launch_bounds__(kOneGW * 64) void k_lti_onepass(const LtiParams p) 
     }
 }
 
+// Wavefronts per group of the forward scan.  With many independent chains (one per batch entry and 64 values of
+// p) the chip is filled by chains alone and small workgroups overlap their load, wait and store phases best
+// (two per compute unit); with few chains the time is the length of a chain, and longer groups halve it.
+static int onepass_gw(int64_t B, int64_t P) { return B * ((P + 63) / 64) >= 64 ? kOneGWSmall : kOneGWLarge; }
+int lti_onepass_group_steps(int64_t B, int64_t P) { return kOneCS * onepass_gw(B, P); }
+int lti_onepass_min_group_steps() { return kOneCS * kOneGWSmall; }
+int lti_onepass_bwd_group_steps() { return kOneBwdCS * kOneBwdGW; }
+
 hipError_t launch_lti_onepass(const LtiParams &p, hipStream_t s) {
     const int npslab = (p.P + 63) / 64;
     dim3 grid((unsigned)(npslab * p.B), p.ngroups);
-    hipLaunchKernelGGL((k_lti_onepass<kOneCS, false>), grid, dim3(kOneGW * 64), 0, s, p);
+    if (onepass_gw(p.B, p.P) == kOneGWSmall)
+        hipLaunchKernelGGL((k_lti_onepass<kOneCS, kOneGWSmall, false>), grid, dim3(kOneGWSmall * 64), 0, s, p);
+    else
+        hipLaunchKernelGGL((k_lti_onepass<kOneCS, kOneGWLarge, false>), grid, dim3(kOneGWLarge * 64), 0, s, p);
     return hipGetLastError();
 }
-int lti_onepass_group_steps() { return kOneCS * kOneGW; }
 
 hipError_t launch_lti_onepass_bwd(const LtiParams &p, hipStream_t s) {
     const int npslab = (p.P + 63) / 64;
     dim3 grid((unsigned)(npslab * p.B), p.ngroups);
-    hipLaunchKernelGGL((k_lti_onepass<kOneBwdCS, true>), grid, dim3(kOneGW * 64), 0, s, p);
+    hipLaunchKernelGGL((k_lti_onepass<kOneBwdCS, kOneBwdGW, true>), grid, dim3(kOneBwdGW * 64), 0, s, p);
     return hipGetLastError();
 }
-int lti_onepass_bwd_group_steps() { return kOneBwdCS * kOneGW; }
 
 hipError_t launch_lti(const LtiParams &p, hipStream_t s) {
     dim3 grid((p.P + 63) / 64, p.ngroups, p.B);

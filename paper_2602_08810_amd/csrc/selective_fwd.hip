@@ -203,15 +203,16 @@ __global__ void k_ss_carry(const FwdParams p) {
     }
 }
 
-// Clears up to five float buffers in one launch (a fill kernel rather than hipMemsetAsync, so that a caller
-// may capture the library call in a HIP graph).
-__global__ void k_fill_zero(const ZeroList z) {
+// Fills up to five buffers of 32-bit words, each with its own word, in one launch (a fill kernel rather than
+// hipMemsetAsync, so that a caller may capture the library call in a HIP graph).
+__global__ void k_fill(const FillList z) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
 #pragma unroll
-    for (int k = 0; k < ZeroList::kMax; ++k) {
-        float *ptr = z.ptr[k];
+    for (int k = 0; k < FillList::kMax; ++k) {
+        uint32_t *ptr = reinterpret_cast<uint32_t *>(z.ptr[k]);
         if (!ptr) continue;
-        for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < z.count[k]; i += stride) ptr[i] = 0.0f;
+        const uint32_t word = z.bits[k];
+        for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < z.count[k]; i += stride) ptr[i] = word;
     }
 }
 
@@ -266,13 +267,13 @@ hipError_t launch_ss_carry(const FwdParams &p, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_fill_zero(const ZeroList &z, hipStream_t s) {
+hipError_t launch_fill(const FillList &z, hipStream_t s) {
     int64_t most = 0;
-    for (int k = 0; k < ZeroList::kMax; ++k) if (z.ptr[k] && z.count[k] > most) most = z.count[k];
+    for (int k = 0; k < FillList::kMax; ++k) if (z.ptr[k] && z.count[k] > most) most = z.count[k];
     if (most <= 0) return hipSuccess;
     int64_t blocks = (most + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)blocks), dim3(256), 0, s, z);
+    hipLaunchKernelGGL(k_fill, dim3((unsigned)blocks), dim3(256), 0, s, z);
     return hipGetLastError();
 }
 

@@ -37,7 +37,7 @@ def test_config1(api, oracle, path):
 
 
 @pytest.mark.parametrize("B,P,L", [(1, 1, 1), (2, 5, 17), (3, 300, 1000), (1, 64, 33), (2, 257, 4099), (1, 2048, 64),
-                                   (1, 64, 8192), (1, 70, 5000)])
+                                   (1, 64, 8192), (1, 70, 5000), (2, 2053, 700), (16, 300, 1000)])
 @pytest.mark.parametrize("with_x0", [False, True])
 @pytest.mark.parametrize("path", ["single_pass", "chunk_carry"])
 def test_shapes(api, oracle, B, P, L, with_x0, path):

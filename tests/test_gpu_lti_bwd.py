@@ -45,7 +45,7 @@ def test_config1_backward(api, oracle):
 
 
 @pytest.mark.parametrize("B,P,L", [(1, 1, 1), (2, 5, 17), (3, 300, 1000), (1, 64, 33), (2, 257, 4099), (1, 2048, 64),
-                                   (1, 64, 8192), (1, 70, 5000), (2, 64, 128), (1, 64, 129)])
+                                   (1, 64, 8192), (1, 70, 5000), (2, 2053, 700), (16, 300, 1000), (2, 64, 128), (1, 64, 129)])
 @pytest.mark.parametrize("with_x0", [False, True])
 def test_shapes(api, oracle, B, P, L, with_x0):
     _run(api, oracle, B, P, L, with_x0, seed=B * 1000 + P + L)
