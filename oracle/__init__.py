@@ -146,6 +146,24 @@ def lti_diag_scan(lam, v, x0=None):
     return x
 
 
+def diag_scan(a, b, x0=None):
+    """x [B,L,P] of x_k = a_k * x_{k-1} + b_k for caller-supplied coefficients; real (float64) or complex (complex128)
+    according to the dtype of the inputs."""
+    cplx = np.iscomplexobj(a) or np.iscomplexobj(b) or (x0 is not None and np.iscomplexobj(x0))
+    conv = _c128 if cplx else _f64
+    a, b = conv(a), conv(b)
+    Bsz, L, P = b.shape
+    assert a.shape == b.shape
+    x0c = None if x0 is None else conv(x0)
+    x = np.empty((Bsz, L, P), dtype=np.complex128 if cplx else np.float64)
+    cp = lambda t: ctypes.c_void_p(0) if t is None else t.ctypes.data_as(ctypes.c_void_p)
+    rc = _load().lrnnx_oracle_diag_scan(ctypes.c_int(Bsz), ctypes.c_long(L), ctypes.c_int(P), ctypes.c_int(int(cplx)),
+                                        cp(a), cp(b), cp(x0c), cp(x))
+    if rc != 0:
+        raise ValueError(f"oracle diag scan: bad arguments (rc={rc})")
+    return x
+
+
 def lti_diag_scan_bwd(lam, v, gx, x0=None):
     """Gradients (dv [B,L,P], dlam [P], dx0 [B,P]) of a real loss with dLoss/dRe(x) + i dLoss/dIm(x) = gx."""
     lam, v, gx = _c128(lam), _c128(v), _c128(gx)

@@ -22,7 +22,8 @@
  * convolution closed form, impulse response, scipy.signal.lfilter and
  * cont2discrete, exact-ZOH step response, central finite differences, adjoint
  * dot test, linearity / causality / chaining invariants; for the LTI backward: finite differences of a real
- * loss over real and imaginary parts, the L = 1 closed form, the reversed-forward-scan identity.
+ * loss over real and imaginary parts, the L = 1 closed form, the reversed-forward-scan identity; for the
+ * caller-supplied (a_k, b_k) scan: the product/sum closed form, reduction to the LTI and the selective scans.
  * Parity unpinned: which of the two "ZOH" input maps (disc 0 or 1) the
  * paper's own "zoh" string selects; the paper's asynchronous scheme is read
  * as "the caller supplies Delta per step" (delta_softplus = 0).
@@ -264,6 +265,40 @@ int lrnnx_oracle_lti_diag_scan(int B, long L, int P,
             double ni = lr * xi + li * xr + v[idx + 1];
             xr = nr; xi = ni;
             x[idx] = xr; x[idx + 1] = xi;
+        }
+    }
+    return 0;
+}
+
+/* Time-varying diagonal recurrence with the per-step coefficients supplied by the caller:
+ *     x_k = a_k (.) x_{k-1} + b_k          (Eq. 2 with A(k) = diag(a_k) and b_k = B(k) u_k already formed)
+ * the form shared by the time-varying S5-style layers of Sec. 2.2.2 (S7), the gated real recurrence (RG-LRU)
+ * and event-driven discretisation (Sec. 3), whose gates and step sizes are computed by the caller.
+ * a, b, x: [B, L, P]; x0: [B, P] or NULL.  is_complex = 0: doubles; 1: (re, im) pairs of doubles.            */
+int lrnnx_oracle_diag_scan(int B, long L, int P, int is_complex,
+                           const double *a, const double *b, const double *x0, double *x)
+{
+    if (B < 0 || L < 0 || P < 0) return 1;
+    long rows = (long)B * P;
+#pragma omp parallel for schedule(static)
+    for (long row = 0; row < rows; ++row) {
+        int bb = (int)(row / P), p = (int)(row % P);
+        if (!is_complex) {
+            double xr = x0 ? x0[row] : 0.0;
+            for (long k = 0; k < L; ++k) {
+                long idx = ((long)bb * L + k) * P + p;
+                xr = a[idx] * xr + b[idx];
+                x[idx] = xr;
+            }
+        } else {
+            double xr = x0 ? x0[2 * row] : 0.0, xi = x0 ? x0[2 * row + 1] : 0.0;
+            for (long k = 0; k < L; ++k) {
+                long idx = 2 * (((long)bb * L + k) * P + p);
+                double nr = a[idx] * xr - a[idx + 1] * xi + b[idx];
+                double ni = a[idx] * xi + a[idx + 1] * xr + b[idx + 1];
+                xr = nr; xi = ni;
+                x[idx] = xr; x[idx + 1] = xi;
+            }
         }
     }
     return 0;

@@ -392,3 +392,57 @@ def test_lti_bwd_matches_library_autograd(oracle):
     np.testing.assert_allclose(dv, tv.grad.numpy(), rtol=1e-12)
     np.testing.assert_allclose(dlam, tl.grad.numpy(), rtol=1e-12)
     np.testing.assert_allclose(dx0, tx0.grad.numpy(), rtol=1e-12)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Caller-supplied (a_k, b_k) diagonal scan (the time-varying layers of Sec. 2.2.2 without their gating networks).
+# ---------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cplx", [False, True])
+def test_diag_scan_product_sum_closed_form(oracle, cplx):
+    """x_k = (prod_{i<=k} a_i) x0 + sum_j (prod_{j<i<=k} a_i) b_j, written with explicit products."""
+    rng = np.random.default_rng(31)
+    B, L, P = 2, 11, 3
+    draw = (lambda *s: rng.uniform(0.5, 1.1, s) * np.exp(1j * rng.uniform(-1, 1, s))) if cplx else \
+           (lambda *s: rng.uniform(-1.1, 1.1, s))
+    a, b, x0 = draw(B, L, P), draw(B, L, P), draw(B, P)
+    x = oracle.diag_scan(a, b, x0=x0)
+    for k in range(L):
+        ref = np.prod(a[:, :k + 1], axis=1) * x0
+        for j in range(k + 1):
+            ref = ref + np.prod(a[:, j + 1:k + 1], axis=1) * b[:, j]
+        np.testing.assert_allclose(x[:, k], ref, rtol=1e-12, atol=1e-13)
+    assert x.dtype == (np.complex128 if cplx else np.float64)
+
+
+def test_diag_scan_reduces_to_the_lti_scan_and_to_the_selective_scan(oracle):
+    rng = np.random.default_rng(32)
+    B, L, P = 2, 50, 4
+    lam = 0.9 * np.exp(1j * rng.uniform(0, 6.28, P))
+    v = rng.standard_normal((B, L, P)) + 1j * rng.standard_normal((B, L, P))
+    x0 = rng.standard_normal((B, P)) + 0j
+    np.testing.assert_allclose(oracle.diag_scan(np.broadcast_to(lam, v.shape), v, x0=x0),
+                               oracle.lti_diag_scan(lam, v, x0=x0), rtol=1e-13)
+    # selective scan states: a = exp(dt A), b = dt B u per (d, n), with P = D * N
+    D, N = 3, 2
+    u, dl = rng.standard_normal((B, D, L)), rng.uniform(0.01, 0.2, (B, D, L))
+    A, Bm, Cm = -rng.uniform(0.5, 2, (D, N)), rng.standard_normal((B, L, N)), rng.standard_normal((B, L, N))
+    _, _, xs = oracle.selective_scan_fwd(u, dl, A, Bm, Cm, delta_softplus=False, return_states=True)
+    a = np.exp(dl.transpose(0, 2, 1)[..., None] * A[None, None])                 # [B,L,D,N]
+    b = (dl * u).transpose(0, 2, 1)[..., None] * Bm[:, :, None, :]
+    got = oracle.diag_scan(a.reshape(B, L, D * N), b.reshape(B, L, D * N)).reshape(B, L, D, N)
+    np.testing.assert_allclose(got, xs.transpose(0, 2, 1, 3), rtol=1e-12, atol=1e-14)
+
+
+def test_diag_scan_chaining_and_gates(oracle):
+    """Splitting the sequence and carrying the last state reproduces the one-shot scan; a_k = 0 resets the state and
+    a_k = 1, b_k = 0 holds it (the two extremes of a gate)."""
+    rng = np.random.default_rng(33)
+    B, L, P = 1, 30, 2
+    a, b = rng.uniform(0.2, 1.0, (B, L, P)), rng.standard_normal((B, L, P))
+    x = oracle.diag_scan(a, b)
+    x2 = oracle.diag_scan(a[:, 13:], b[:, 13:], x0=x[:, 12])
+    np.testing.assert_allclose(x2, x[:, 13:], rtol=1e-14)
+    a[:, 7], a[:, 20], b[:, 20] = 0.0, 1.0, 0.0
+    x = oracle.diag_scan(a, b)
+    np.testing.assert_array_equal(x[:, 7], b[:, 7])
+    np.testing.assert_array_equal(x[:, 20], x[:, 19])
