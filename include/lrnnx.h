@@ -49,7 +49,7 @@ typedef enum {
     LRNNX_ERR_LAUNCH = 4         /* the HIP runtime refused a launch; hipGetLastError has details */
 } lrnnx_status;
 
-typedef enum { LRNNX_F32 = 0, LRNNX_BF16 = 1 } lrnnx_dtype;
+typedef enum { LRNNX_F32 = 0, LRNNX_BF16 = 1, LRNNX_C64 = 2 /* complex, two floats; lrnnx_diag_scan only */ } lrnnx_dtype;
 
 /* Discretisation of x' = A x + B u with step Delta (schemes named in Sec. 3).
  * a is the state multiplier, g the input gain (Bbar = g * B).                */
@@ -178,6 +178,31 @@ typedef struct lrnnx_lti_args {
 
 int lrnnx_lti_diag_scan(const lrnnx_lti_args *args);
 
+/* ------------------------------------------------------------------ diagonal scan with caller-supplied coefficients
+ *     x[b,k,p] = a[b,k,p] * x[b,k-1,p] + b[b,k,p]
+ * Eq. 2 with A(k) = diag(a_k) and the input term b_k = B(k) u_k already formed: the recurrence of the
+ * time-varying S5-style layers (Sec. 2.2.2), of gated real recurrences, and of event-driven discretisation
+ * (Sec. 3), whose gates, step sizes and projections are the caller's.  dtype LRNNX_F32: real floats;
+ * LRNNX_C64: complex numbers as interleaved (re, im) float pairs.  a, b, x: [B,L,P], P contiguous, device memory
+ * aligned to the element size; x may alias b (not a).  x0, x_last: [B,P] or NULL.  Results are bitwise
+ * reproducible.  workspace: lrnnx_workspace_bytes(LRNNX_WS_DIAG, B, P, 0, L, dtype), contents on entry
+ * irrelevant.  Like the LTI scan, a bounded wait that runs out yields NaN states, never plausible wrong ones. */
+typedef struct lrnnx_diag_scan_args {
+    size_t struct_size;
+    int32_t B, P;
+    int64_t L;
+    int32_t dtype, reserved;    /* LRNNX_F32 or LRNNX_C64 */
+    const void *a;
+    const void *b;
+    const void *x0;
+    void *x;
+    void *x_last;
+    void *workspace;    size_t workspace_bytes;
+    void *stream;
+} lrnnx_diag_scan_args;
+
+int lrnnx_diag_scan(const lrnnx_diag_scan_args *args);
+
 /* ------------------------------------------------------------------ backward of the LTI scan
  * Adjoint of the recurrence above (Sec. 2.2.1; the paper trains these layers through the same scan).  For a real
  * loss, the gradient of a complex quantity q is dLoss/dRe(q) + i dLoss/dIm(q) (the convention of complex
@@ -247,10 +272,11 @@ typedef struct lrnnx_lti_step_args {
 int lrnnx_lti_step(const lrnnx_lti_step_args *args);
 
 /* ------------------------------------------------------------------ queries (host only, no GPU needed) */
-typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2, LRNNX_WS_LTI_BWD = 3 } lrnnx_ws_kind;
+typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2, LRNNX_WS_LTI_BWD = 3, LRNNX_WS_DIAG = 4 } lrnnx_ws_kind;
 
 /* Bytes of device scratch the call may need (the largest over its paths).
- * For LRNNX_WS_LTI and LRNNX_WS_LTI_BWD pass P as D and 0 for N.  Returns 0 for invalid sizes.   */
+ * For LRNNX_WS_LTI, LRNNX_WS_LTI_BWD and LRNNX_WS_DIAG pass P as D and 0 for N (LRNNX_WS_DIAG: io_dtype is
+ * LRNNX_F32 or LRNNX_C64).  Returns 0 for invalid sizes.   */
 size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t L, int io_dtype);
 
 const char *lrnnx_status_string(int status);

@@ -16,10 +16,10 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("LRNNX_LIB", os.path.join(_HERE, "liblrnnx.so"))   # LRNNX_LIB: alternative build of the same library
 
-F32, BF16 = 0, 1
+F32, BF16, C64 = 0, 1, 2
 DISC = {"zoh_s6": 0, "zoh": 1, "bilinear": 2, "dirac": 3}
 PATH = {"auto": 0, "single_pass": 1, "chunk_carry": 2}
-WS_FWD, WS_BWD, WS_LTI, WS_LTI_BWD = 0, 1, 2, 3
+WS_FWD, WS_BWD, WS_LTI, WS_LTI_BWD, WS_DIAG = 0, 1, 2, 3, 4
 STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported", 3: "workspace", 4: "launch"}
 
 _vp, _i32, _i64, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
@@ -76,6 +76,14 @@ class LtiBwdArgs(ctypes.Structure):
     ]
 
 
+class DiagScanArgs(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", _sz), ("B", _i32), ("P", _i32), ("L", _i64), ("dtype", _i32), ("reserved", _i32),
+        ("a", _vp), ("b", _vp), ("x0", _vp), ("x", _vp), ("x_last", _vp),
+        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
+    ]
+
+
 class StepArgs(ctypes.Structure):
     _fields_ = [
         ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32),
@@ -110,6 +118,8 @@ def lib():
         L.lrnnx_lti_diag_scan.argtypes = [ctypes.POINTER(LtiArgs)]
         L.lrnnx_lti_diag_scan_bwd.argtypes = [ctypes.POINTER(LtiBwdArgs)]
         L.lrnnx_lti_diag_scan_bwd.restype = ctypes.c_int
+        L.lrnnx_diag_scan.argtypes = [ctypes.POINTER(DiagScanArgs)]
+        L.lrnnx_diag_scan.restype = ctypes.c_int
         L.lrnnx_selective_step.argtypes = [ctypes.POINTER(StepArgs)]
         L.lrnnx_lti_step.argtypes = [ctypes.POINTER(LtiStepArgs)]
         L.lrnnx_selective_step.restype = ctypes.c_int
@@ -348,6 +358,35 @@ def lrnnx_lti_diag_scan_bwd(lam, x, gx, x0=None, want_dx0=True, out=None, worksp
     a.stream = _stream()
     _check(lib().lrnnx_lti_diag_scan_bwd(ctypes.byref(a)))
     return dv, dlam, dx0
+
+
+def lrnnx_diag_scan(a, b, x0=None, return_last_state=False, out=None, workspace=None):
+    """x [B,L,P] of x_k = a_k * x_{k-1} + b_k for float32 or complex64 a, b; see lrnnx_diag_scan_args."""
+    if a.dtype not in (torch.float32, torch.complex64) or b.dtype != a.dtype:
+        raise TypeError("a and b must both be float32 or both complex64")
+    if not a.is_contiguous() or not b.is_contiguous() or a.shape != b.shape or b.dim() != 3:
+        raise ValueError("a and b must be contiguous [B,L,P] tensors of one shape")
+    Bsz, L, P = b.shape
+    dt = C64 if a.dtype == torch.complex64 else F32
+    g = DiagScanArgs()
+    g.struct_size = ctypes.sizeof(DiagScanArgs)
+    g.B, g.P, g.L, g.dtype = Bsz, P, L, dt
+    g.a, g.b = a.data_ptr(), b.data_ptr()
+    if x0 is not None:
+        if x0.dtype != a.dtype or not x0.is_contiguous() or tuple(x0.shape) != (Bsz, P):
+            raise ValueError("x0: expected a contiguous [B,P] tensor of the dtype of a")
+        g.x0 = x0.data_ptr()
+    x = out if out is not None else torch.empty_like(b)
+    g.x = x.data_ptr()
+    x_last = torch.empty((Bsz, P), dtype=a.dtype, device=b.device) if return_last_state else None
+    g.x_last = _ptr(x_last)
+    if workspace is None:
+        nbytes = lrnnx_workspace_bytes(WS_DIAG, Bsz, P, 0, L, dt)
+        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=b.device)
+    g.workspace, g.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    g.stream = _stream()
+    _check(lib().lrnnx_diag_scan(ctypes.byref(g)))
+    return (x, x_last) if return_last_state else x
 
 
 def _bd(t, name, io):

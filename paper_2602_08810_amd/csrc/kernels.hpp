@@ -55,6 +55,18 @@ struct LtiParams {
     float *dlambda;          // [P] complex as float pairs, accumulated with atomics (zero it first)
 };
 
+// scan with caller-supplied coefficients (single launch, chained groups)
+struct DiagParams {
+    int B, P;
+    int64_t L;
+    int is_complex, ngroups;
+    const void *a, *b, *x0;  // [B,L,P], [B,L,P], [B,P] of float or float2
+    void *x, *x_last;
+    float2 *ws_T;            // [B,ngroups,slots,P] group aggregates (slots: 1 real = (A,S); 2 complex = A, S)
+    float2 *ws_X;            // [B,ngroups/anchor+1,P] true end state of every anchor group
+    int *err;
+};
+
 struct StepParams {
     int B, D, N;
     int softplus;
@@ -76,6 +88,10 @@ hipError_t launch_lti_onepass(const LtiParams &p, hipStream_t s);
 int lti_onepass_group_steps(int64_t B, int64_t P);   // time steps per chained group for this shape
 int lti_onepass_min_group_steps();                   // the smallest it can be (sizes the workspace)
 hipError_t launch_lti_onepass_bwd(const LtiParams &p, hipStream_t s);
+hipError_t launch_diag_scan(const DiagParams &p, hipStream_t s);
+int diag_scan_group_steps(int64_t B, int64_t P, int is_complex);
+int diag_scan_min_group_steps(int is_complex);
+int diag_scan_anchor(int is_complex);
 int lti_onepass_bwd_group_steps();
 struct FillList {
     static constexpr int kMax = 5;

@@ -95,6 +95,29 @@ def make_lti(B, P, L, seed=1, with_x0=False, with_gx=False, **_unused):
     return {"lam": lam, "v": v, "x0": x0, "gx": gx}
 
 
+def make_diag(B, P, L, cplx=False, seed=1, with_x0=False, **_unused):
+    """Inputs of the scan with caller-supplied coefficients (time-varying S5-style / gated recurrences).
+
+    real: a ~ U(0.5, 1) (a forget gate), b ~ N(0,1), float32; complex: a = r e^{i theta} with r ~ U(0.9, 0.999),
+    theta ~ U(0, 2 pi) drawn per element, b = (N(0,1) + i N(0,1)) / sqrt(2), complex64.  All [B,L,P].
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    if not cplx:
+        a = rng.uniform(0.5, 1.0, size=(B, L, P)).astype(np.float32)
+        b = rng.standard_normal((B, L, P), dtype=np.float32)
+        x0 = rng.standard_normal((B, P), dtype=np.float32) if with_x0 else None
+        return {"a": a, "b": b, "x0": x0}
+    r = rng.uniform(0.9, 0.999, size=(B, L, P))
+    th = rng.uniform(0.0, 2.0 * np.pi, size=(B, L, P))
+    a = (r * np.exp(1j * th)).astype(np.complex64)
+    s = np.float32(1.0 / np.sqrt(2.0))
+    b = np.empty((B, L, P), dtype=np.complex64)
+    b.real = rng.standard_normal((B, L, P), dtype=np.float32) * s
+    b.imag = rng.standard_normal((B, L, P), dtype=np.float32) * s
+    x0 = (rng.standard_normal((B, P)) + 1j * rng.standard_normal((B, P))).astype(np.complex64) if with_x0 else None
+    return {"a": a, "b": b, "x0": x0}
+
+
 def make(name: str, **overrides):
     """Inputs of BASELINE configuration ``name`` ("c0".."c4"), optionally with fields overridden."""
     cfg = dict(CONFIGS[name])
