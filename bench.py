@@ -259,6 +259,25 @@ def _other_configs(api, torch, dev):
                                      "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
     del vl, xl, gl, wsl
 
+    # scan with caller-supplied (a_k, b_k): reads a and b, writes x
+    for tag, dt, esz in (("real", torch.float32, 4), ("complex", torch.complex64, 8)):
+        Bd, Pd, Ld = 8, 1024, 8192
+        if dt == torch.float32:
+            ad = torch.rand(Bd, Ld, Pd, device=dev, generator=g) * 0.5 + 0.5
+            bd = torch.randn(Bd, Ld, Pd, device=dev, generator=g)
+        else:
+            ad = torch.polar(torch.rand(Bd, Ld, Pd, device=dev, generator=g) * 0.099 + 0.9,
+                             torch.rand(Bd, Ld, Pd, device=dev, generator=g) * 6.2831853)
+            bd = torch.randn(Bd, Ld, Pd, dtype=dt, device=dev, generator=g) * 0.70710678
+        xd = torch.empty_like(bd)
+        wsd = torch.empty(max(api.lrnnx_workspace_bytes(api.WS_DIAG, Bd, Pd, 0, Ld, api.C64 if esz == 8 else api.F32), 16),
+                          dtype=torch.uint8, device=dev)
+        tt = _time(torch, lambda: api.lrnnx_diag_scan(ad, bd, out=xd, workspace=wsd), 10)
+        nb = 3 * Bd * Ld * Pd * esz
+        out[f"diag_scan_{tag}_B8_P1024_L8192"] = {"us": tt * 1e6, "elements_per_s": Bd * Ld * Pd / tt,
+                                                  "hbm_GBs": nb / tt / 1e9, "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
+        del ad, bd, xd, wsd
+
     # single-token step (generation): state [B,D,N] read and written once per token
     Bs, Ds, Ns = 64, 1536, 16
     ts = sel(Bs, Ds, Ns, 1, True)
