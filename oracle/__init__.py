@@ -81,6 +81,16 @@ def _disc(disc) -> int:
     return DISC[disc] if isinstance(disc, str) else int(disc)
 
 
+def _groups(Bm, Cm, Bsz, L, N):
+    """Number of B/C groups: Bm, Cm are [B,L,N] (one group) or [B,G,L,N] (channel d reads group d // (D/G))."""
+    assert Bm.shape == Cm.shape
+    if Bm.ndim == 3:
+        assert Bm.shape == (Bsz, L, N)
+        return 1
+    assert Bm.ndim == 4 and Bm.shape[0] == Bsz and Bm.shape[2:] == (L, N)
+    return Bm.shape[1]
+
+
 def selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, x0=None,
                        disc="zoh_s6", delta_softplus=True, return_states=False):
     """y [B,D,L], x_last [B,D,N] (and every state [B,D,L,N] if asked) of Eq. 2 with diagonal A(k)."""
@@ -89,12 +99,12 @@ def selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None,
     Bsz, D, L = u.shape
     N = A.shape[1]
     assert delta.shape == (Bsz, D, L) and A.shape == (D, N)
-    assert Bm.shape == (Bsz, L, N) and Cm.shape == (Bsz, L, N)
+    G = _groups(Bm, Cm, Bsz, L, N)
     y = np.empty((Bsz, D, L))
     x_last = np.empty((Bsz, D, N))
     xs = np.empty((Bsz, D, L, N)) if return_states else None
     rc = _load().lrnnx_oracle_selective_scan_fwd(
-        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_long(L),
+        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_int(G), ctypes.c_long(L),
         ctypes.c_int(_disc(disc)), ctypes.c_int(int(bool(delta_softplus))),
         _p(u), _p(delta), _p(A), _p(Bm), _p(Cm), _p(Dskip), _p(delta_bias), _p(z), _p(x0),
         _p(y), _p(x_last), _p(xs))
@@ -110,16 +120,17 @@ def selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=N
     Dskip, delta_bias, z, x0 = map(_f64, (Dskip, delta_bias, z, x0))
     Bsz, D, L = u.shape
     N = A.shape[1]
+    G = _groups(Bm, Cm, Bsz, L, N)
     out = {
         "du": np.empty((Bsz, D, L)), "ddelta": np.empty((Bsz, D, L)),
-        "dA": np.empty((D, N)), "dBm": np.empty((Bsz, L, N)), "dCm": np.empty((Bsz, L, N)),
+        "dA": np.empty((D, N)), "dBm": np.empty(Bm.shape), "dCm": np.empty(Cm.shape),
         "dD": np.empty(D) if Dskip is not None else None,
         "dbias": np.empty(D) if delta_bias is not None else None,
         "dz": np.empty((Bsz, D, L)) if z is not None else None,
         "dx0": np.empty((Bsz, D, N)),
     }
     rc = _load().lrnnx_oracle_selective_scan_bwd(
-        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_long(L),
+        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_int(G), ctypes.c_long(L),
         ctypes.c_int(_disc(disc)), ctypes.c_int(int(bool(delta_softplus))),
         _p(u), _p(delta), _p(A), _p(Bm), _p(Cm), _p(Dskip), _p(delta_bias), _p(z), _p(x0), _p(dy),
         _p(out["du"]), _p(out["ddelta"]), _p(out["dA"]), _p(out["dBm"]), _p(out["dCm"]),

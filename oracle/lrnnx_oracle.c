@@ -31,7 +31,8 @@
  * Layouts (all contiguous, all double):
  *   u, delta, z, y, dy, du, ddelta, dz : [B, D, L]
  *   A, dA                               : [D, N]
- *   Bm, Cm, dBm, dCm                    : [B, L, N]   (shared by all channels)
+ *   Bm, Cm, dBm, dCm                    : [B, G, L, N] (shared by the D/G consecutive channels of a group;
+ *                                          G = 1: by all channels)
  *   Dskip, delta_bias, dD, dbias        : [D]
  *   x0, x_last, dx0                     : [B, D, N]
  *   xs (optional dump of every state)   : [B, D, L, N]
@@ -111,17 +112,18 @@ double lrnnx_oracle_softplus(double s) { return softplus(s); }
 /* Forward selective scan (Eq. 2 with diagonal, input-dependent A(k), B(k), C(k)).
  * Optional pointers may be NULL: Dskip, delta_bias, z, x0, x_last, xs.        */
 int lrnnx_oracle_selective_scan_fwd(
-    int B, int D, int N, long L, int disc, int delta_softplus,
+    int B, int D, int N, int G, long L, int disc, int delta_softplus,
     const double *u, const double *delta, const double *A,
     const double *Bm, const double *Cm, const double *Dskip,
     const double *delta_bias, const double *z, const double *x0,
     double *y, double *x_last, double *xs)
 {
-    if (B < 0 || D < 0 || N < 1 || L < 0 || disc < 0 || disc > 3) return 1;
+    if (B < 0 || D < 0 || N < 1 || L < 0 || disc < 0 || disc > 3 || G < 1 || D % G) return 1;
     long rows = (long)B * D;
 #pragma omp parallel for schedule(static)
     for (long row = 0; row < rows; ++row) {
         int b = (int)(row / D), d = (int)(row % D);
+        long bg = (long)b * G + d / (D / G);          /* row of Bm, Cm this channel reads: its batch entry and group */
         double *x = (double *)malloc(sizeof(double) * N);
         for (int n = 0; n < N; ++n) x[n] = x0 ? x0[row * N + n] : 0.0;
         for (long l = 0; l < L; ++l) {
@@ -132,8 +134,8 @@ int lrnnx_oracle_selective_scan_fwd(
             for (int n = 0; n < N; ++n) {
                 double a, g;
                 disc_eval(disc, dt, A[(long)d * N + n], &a, &g, 0, 0, 0, 0);
-                x[n] = a * x[n] + g * Bm[((long)b * L + l) * N + n] * uu;   /* Eq. 2, line 1 */
-                acc += Cm[((long)b * L + l) * N + n] * x[n];                /* Eq. 2, line 2 */
+                x[n] = a * x[n] + g * Bm[(bg * L + l) * N + n] * uu;   /* Eq. 2, line 1 */
+                acc += Cm[(bg * L + l) * N + n] * x[n];                /* Eq. 2, line 2 */
                 if (xs) xs[(row * L + l) * N + n] = x[n];
             }
             double ypre = acc + (Dskip ? Dskip[d] * uu : 0.0);
@@ -151,7 +153,7 @@ int lrnnx_oracle_selective_scan_fwd(
  * GPU path recomputes.  Outputs dA, dD, dbias, dBm, dCm are overwritten.
  * Optional (may be NULL): Dskip, delta_bias, z, x0, dD, dbias, dz, dx0.       */
 int lrnnx_oracle_selective_scan_bwd(
-    int B, int D, int N, long L, int disc, int delta_softplus,
+    int B, int D, int N, int G, long L, int disc, int delta_softplus,
     const double *u, const double *delta, const double *A,
     const double *Bm, const double *Cm, const double *Dskip,
     const double *delta_bias, const double *z, const double *x0,
@@ -159,8 +161,8 @@ int lrnnx_oracle_selective_scan_bwd(
     double *du, double *ddelta, double *dA, double *dBm, double *dCm,
     double *dD, double *dbias, double *dz, double *dx0)
 {
-    if (B < 0 || D < 0 || N < 1 || L < 0 || disc < 0 || disc > 3) return 1;
-    long nBC = (long)B * L * N;
+    if (B < 0 || D < 0 || N < 1 || L < 0 || disc < 0 || disc > 3 || G < 1 || D % G) return 1;
+    long nBC = (long)B * G * L * N;
     memset(dA, 0, sizeof(double) * (size_t)D * N);
     memset(dBm, 0, sizeof(double) * (size_t)nBC);
     memset(dCm, 0, sizeof(double) * (size_t)nBC);
@@ -185,6 +187,7 @@ int lrnnx_oracle_selective_scan_bwd(
         double *h = (double *)malloc(sizeof(double) * N);
         for (int b = 0; b < B; ++b) {
             long row = (long)b * D + d;
+            long bg = (long)b * G + d / (D / G);      /* row of Bm, Cm, dBm, dCm of this channel's group */
             for (int n = 0; n < N; ++n) xs[n] = x0 ? x0[row * N + n] : 0.0;
             for (long l = 0; l < L; ++l) {                      /* forward sweep, states kept */
                 double s = delta[row * L + l] + (delta_bias ? delta_bias[d] : 0.0);
@@ -193,7 +196,7 @@ int lrnnx_oracle_selective_scan_bwd(
                 for (int n = 0; n < N; ++n) {
                     double a, g;
                     disc_eval(disc, dt, A[(long)d * N + n], &a, &g, 0, 0, 0, 0);
-                    xs[(l + 1) * N + n] = a * xs[l * N + n] + g * Bm[((long)b * L + l) * N + n] * uu;
+                    xs[(l + 1) * N + n] = a * xs[l * N + n] + g * Bm[(bg * L + l) * N + n] * uu;
                 }
             }
             for (int n = 0; n < N; ++n) h[n] = 0.0;            /* h[n] = a_{l+1} * (dLoss/dx_{l+1}), zero past the end */
@@ -202,7 +205,7 @@ int lrnnx_oracle_selective_scan_bwd(
                 double dt = delta_softplus ? softplus(s) : s;
                 double uu = u[row * L + l];
                 double acc = 0.0;
-                for (int n = 0; n < N; ++n) acc += Cm[((long)b * L + l) * N + n] * xs[(l + 1) * N + n];
+                for (int n = 0; n < N; ++n) acc += Cm[(bg * L + l) * N + n] * xs[(l + 1) * N + n];
                 double ypre = acc + (Dskip ? Dskip[d] * uu : 0.0);
                 double dypre = dy[row * L + l];
                 if (z) {
@@ -214,7 +217,7 @@ int lrnnx_oracle_selective_scan_bwd(
                 double du_l = Dskip ? dypre * Dskip[d] : 0.0;
                 double ddt = 0.0;
                 for (int n = 0; n < N; ++n) {
-                    long bc = ((long)b * L + l) * N + n;
+                    long bc = (bg * L + l) * N + n;
                     double a, g, a_t, a_A, g_t, g_A;
                     disc_eval(disc, dt, A[(long)d * N + n], &a, &g, &a_t, &a_A, &g_t, &g_A);
                     double hx = Cm[bc] * dypre + h[n];           /* dLoss/dx_l */

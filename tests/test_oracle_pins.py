@@ -446,3 +446,70 @@ def test_diag_scan_chaining_and_gates(oracle):
     x = oracle.diag_scan(a, b)
     np.testing.assert_array_equal(x[:, 7], b[:, 7])
     np.testing.assert_array_equal(x[:, 20], x[:, 19])
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Grouped input/output maps: Bm, Cm [B,G,L,N], channel d reads group d // (D/G)  (a workload variant of Eq. 2's
+# B(k), C(k): several heads, each with its own input-dependent maps).
+# ---------------------------------------------------------------------------------------------------------------
+def _grouped_problem(seed, B=2, D=6, N=3, L=8, G=3):
+    rng = np.random.default_rng(seed)
+    p = _rand_problem(rng, B=B, D=D, N=N, L=L)
+    p["Bm"], p["Cm"] = rng.standard_normal((B, G, L, N)), rng.standard_normal((B, G, L, N))
+    return p, rng.standard_normal((B, D, L))
+
+
+def test_grouped_forward_is_the_unrolled_sum_with_the_group_lookup(oracle):
+    p, _ = _grouped_problem(41)
+    B, D, L = p["u"].shape
+    G, N = p["Bm"].shape[1], p["A"].shape[1]
+    q = dict(p, z=None, x0=None)
+    y, _ = oracle.selective_scan_fwd(**q)
+    for b in range(B):
+        for d in range(D):
+            grp = d // (D // G)
+            dt = np.logaddexp(0.0, p["delta"][b, d] + p["delta_bias"][d])
+            for l in range(L):
+                acc = p["Dskip"][d] * p["u"][b, d, l]
+                for n in range(N):
+                    for j in range(l + 1):
+                        acc += p["Cm"][b, grp, l, n] * np.exp(p["A"][d, n] * dt[j + 1:l + 1].sum()) * dt[j] \
+                               * p["Bm"][b, grp, j, n] * p["u"][b, d, j]
+                assert y[b, d, l] == pytest.approx(acc, rel=1e-11, abs=1e-12)
+
+
+def test_grouped_equals_one_ungrouped_problem_per_group(oracle):
+    """Each group is an independent ungrouped problem over its own channels; its dBm, dCm sum over those channels only."""
+    p, dy = _grouped_problem(42)
+    D, G = p["u"].shape[1], p["Bm"].shape[1]
+    y, xl = oracle.selective_scan_fwd(**p)
+    g = oracle.selective_scan_bwd(dy=dy, **p)
+    for grp in range(G):
+        ds = slice(grp * (D // G), (grp + 1) * (D // G))
+        q = dict(u=p["u"][:, ds], delta=p["delta"][:, ds], A=p["A"][ds], Bm=p["Bm"][:, grp], Cm=p["Cm"][:, grp],
+                 Dskip=p["Dskip"][ds], delta_bias=p["delta_bias"][ds], z=p["z"][:, ds], x0=p["x0"][:, ds])
+        yq, xq = oracle.selective_scan_fwd(**q)
+        gq = oracle.selective_scan_bwd(dy=dy[:, ds], **q)
+        np.testing.assert_allclose(y[:, ds], yq, rtol=1e-14)
+        np.testing.assert_allclose(xl[:, ds], xq, rtol=1e-14)
+        for k in ("du", "ddelta", "dz", "dx0"):
+            np.testing.assert_allclose(g[k][:, ds], gq[k], rtol=1e-13, atol=1e-15)
+        for k in ("dA", "dD", "dbias"):
+            np.testing.assert_allclose(g[k][ds], gq[k], rtol=1e-13, atol=1e-15)
+        for k in ("dBm", "dCm"):
+            np.testing.assert_allclose(g[k][:, grp], gq[k], rtol=1e-13, atol=1e-15)
+
+
+def test_grouped_gradients_of_the_maps_by_finite_differences(oracle):
+    p, dy = _grouped_problem(43, B=1, D=4, N=2, L=5, G=2)
+    g = oracle.selective_scan_bwd(dy=dy, **p)
+    loss = lambda q: float((oracle.selective_scan_fwd(**q)[0] * dy).sum())
+    h = 1e-6
+    for k, gk in (("Bm", "dBm"), ("Cm", "dCm")):
+        for idx in np.ndindex(p[k].shape):
+            q = {n: (v.copy() if isinstance(v, np.ndarray) else v) for n, v in p.items()}
+            q[k][idx] += h
+            up = loss(q)
+            q[k][idx] -= 2 * h
+            num = (up - loss(q)) / (2 * h)
+            assert num == pytest.approx(g[gk][idx], rel=1e-6, abs=1e-8), (k, idx)
