@@ -80,6 +80,8 @@ int64_t lrnnx_ckpt_interval(void);
  *     ypre_l  = sum_n Cm[b,l,n] x_{l,n} + Dskip[d] u[b,d,l]                            (Eq. 2, line 2)
  *     y[b,d,l] = ypre_l * z[b,d,l] * sigmoid(z[b,d,l])   if z != NULL, else ypre_l
  * x_{-1} = x0[b,d,:] or 0.  Optional (NULL allowed): Dskip, delta_bias, z, x0, x_last, ckpt.
+ * Grouped maps: with bc_groups = G > 1, Bm and Cm are [B,G,L,N] and channel d reads group d / (D/G)
+ * (D must be a multiple of G); G = 0 or 1 is the plain [B,L,N] case.
  * workspace is needed only by LRNNX_PATH_CHUNK_CARRY (AUTO falls back to the single
  * pass when it is missing or too small).                                              */
 typedef struct lrnnx_ss_fwd_args {
@@ -104,6 +106,8 @@ typedef struct lrnnx_ss_fwd_args {
     float *ckpt;                                                   /* [B,D,ceil(L/interval),N] out or NULL */
     void *workspace;    size_t workspace_bytes;
     void *stream;
+    int32_t bc_groups;       /* number of Bm/Cm groups; callers built against the shorter struct get 1 */
+    int32_t reserved;
 } lrnnx_ss_fwd_args;
 
 int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *args);
@@ -124,7 +128,8 @@ typedef struct lrnnx_ss_bwd_args {
     size_t struct_size;
     int32_t B, D, N;
     int64_t L;
-    int32_t io_dtype, disc, delta_softplus, reserved;
+    int32_t io_dtype, disc, delta_softplus;
+    int32_t bc_groups;                                             /* as in the forward call; 0 or 1: none */
     const void *u;      int64_t u_stride_b, u_stride_d;
     const void *delta;  int64_t delta_stride_b, delta_stride_d;
     const float *A;
@@ -140,8 +145,8 @@ typedef struct lrnnx_ss_bwd_args {
     void *ddelta;       int64_t ddelta_stride_b, ddelta_stride_d;  /* [B,D,L] io, out */
     void *dz;           int64_t dz_stride_b, dz_stride_d;          /* [B,D,L] io, out or NULL */
     float *dA;                                                     /* [D,N] out */
-    float *dBm;                                                    /* [B,L,N] out */
-    float *dCm;                                                    /* [B,L,N] out */
+    float *dBm;                                                    /* [B,L,N] ([B,G,L,N] if grouped) out */
+    float *dCm;                                                    /* same shape as dBm, out */
     float *dD;                                                     /* [D] out or NULL */
     float *dbias;                                                  /* [D] out or NULL */
     float *dx0;                                                    /* [B,D,N] out or NULL */

@@ -37,13 +37,14 @@ class FwdArgs(ctypes.Structure):
         ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
         ("x_last", _vp), ("ckpt", _vp),
         ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
+        ("bc_groups", _i32), ("reserved", _i32),
     ]
 
 
 class BwdArgs(ctypes.Structure):
     _fields_ = [
         ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32), ("L", _i64),
-        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32), ("reserved", _i32),
+        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32), ("bc_groups", _i32),
         ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
         ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
         ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
@@ -191,6 +192,19 @@ def lrnnx_workspace_bytes(which, B, D, N, L, io_dtype) -> int:
     return int(lib().lrnnx_workspace_bytes(which, B, D, N, L, io_dtype))
 
 
+def _bc_groups(Bm, Cm, io, Bsz, D, L, N):
+    """Number of groups of the maps: [B,L,N] -> 1, [B,G,L,N] -> G (channel d reads group d // (D/G))."""
+    for name, t in (("Bm", Bm), ("Cm", Cm)):
+        ok = t.dtype == io and t.is_contiguous() and t.shape == Bm.shape and (
+            tuple(t.shape) == (Bsz, L, N) or (t.dim() == 4 and t.shape[0] == Bsz and tuple(t.shape[2:]) == (L, N)))
+        if not ok:
+            raise ValueError(f"{name}: expected contiguous [B,L,N] or [B,G,L,N] of dtype {io}")
+    G = Bm.shape[1] if Bm.dim() == 4 else 1
+    if D % G:
+        raise ValueError("D must be a multiple of the number of Bm/Cm groups")
+    return G
+
+
 def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, x0=None,
                              disc="zoh_s6", delta_softplus=True, path="auto",
                              return_last_state=False, return_ckpt=False, out=None, ckpt_out=None, workspace=None):
@@ -211,9 +225,7 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
     a.delta, a.delta_stride_b, a.delta_stride_d = _bdl(delta, "delta", io)
     a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io)
     a.A = _ptr(_f32c(A, "A", (D, N)))
-    for name, t in (("Bm", Bm), ("Cm", Cm)):
-        if t.dtype != io or not t.is_contiguous() or tuple(t.shape) != (Bsz, L, N):
-            raise ValueError(f"{name}: expected contiguous [B,L,N] of dtype {io}")
+    a.bc_groups = _bc_groups(Bm, Cm, io, Bsz, D, L, N)
     a.Bm, a.Cm = Bm.data_ptr(), Cm.data_ptr()
     a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
     a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
@@ -270,9 +282,7 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
     a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io)
     a.dy, a.dy_stride_b, a.dy_stride_d = _bdl(dy, "dy", io)
     a.A = _ptr(_f32c(A, "A", (D, N)))
-    for name, t in (("Bm", Bm), ("Cm", Cm)):
-        if t.dtype != io or not t.is_contiguous() or tuple(t.shape) != (Bsz, L, N):
-            raise ValueError(f"{name}: expected contiguous [B,L,N] of dtype {io}")
+    a.bc_groups = _bc_groups(Bm, Cm, io, Bsz, D, L, N)
     a.Bm, a.Cm = Bm.data_ptr(), Cm.data_ptr()
     a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
     a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
@@ -283,8 +293,8 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
     if z is not None:
         a.dz, a.dz_stride_b, a.dz_stride_d = _bdl(new("dz", (Bsz, D, L), io), "dz", io)
     a.dA = new("dA", (D, N), torch.float32).data_ptr()
-    a.dBm = new("dBm", (Bsz, L, N), torch.float32).data_ptr()
-    a.dCm = new("dCm", (Bsz, L, N), torch.float32).data_ptr()
+    a.dBm = new("dBm", tuple(Bm.shape), torch.float32).data_ptr()
+    a.dCm = new("dCm", tuple(Cm.shape), torch.float32).data_ptr()
     if Dskip is not None:
         a.dD = new("dD", (D,), torch.float32).data_ptr()
     if delta_bias is not None:

@@ -116,7 +116,10 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
 }
 
 int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *a) {
-    if (!a || a->struct_size < sizeof(lrnnx_ss_fwd_args)) return LRNNX_ERR_INVALID_ARG;
+    constexpr size_t kOldSize = offsetof(lrnnx_ss_fwd_args, bc_groups);  // struct before `bc_groups` was appended
+    if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
+    const int bcg = (a->struct_size >= sizeof(lrnnx_ss_fwd_args) && a->bc_groups > 1) ? a->bc_groups : 1;
+    if (a->struct_size >= sizeof(lrnnx_ss_fwd_args) && a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
@@ -127,11 +130,13 @@ int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *a) {
         return LRNNX_ERR_INVALID_ARG;
     if (!supported_n(a->N)) return LRNNX_ERR_UNSUPPORTED;
     if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
+    if (a->D % bcg) return LRNNX_ERR_INVALID_ARG;
     const size_t es = elem_size(a->io_dtype);
     if (!aligned16(a->Bm) || !aligned16(a->Cm)) return LRNNX_ERR_INVALID_ARG;
 
     FwdParams p{};
     p.B = a->B; p.D = a->D; p.N = a->N; p.L = a->L;
+    p.bcg = bcg; p.dpg = a->D / bcg;
     p.softplus = a->delta_softplus ? 1 : 0;
     p.u = a->u; p.delta = a->delta; p.z = a->z; p.y = a->y;
     p.u_sb = a->u_stride_b; p.u_sd = a->u_stride_d;
@@ -191,6 +196,9 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
         return LRNNX_ERR_INVALID_ARG;
     if (!supported_n(a->N)) return LRNNX_ERR_UNSUPPORTED;
     if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
+    if (a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
+    const int bcg = a->bc_groups > 1 ? a->bc_groups : 1;
+    if (a->D % bcg) return LRNNX_ERR_INVALID_ARG;
     if (!aligned16(a->Bm) || !aligned16(a->Cm) || !aligned16(a->dBm) || !aligned16(a->dCm)) return LRNNX_ERR_INVALID_ARG;
     const size_t es = elem_size(a->io_dtype);
     const int64_t nck = cdiv(a->L, kCkptInterval);
@@ -202,6 +210,7 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     if (!ckpt) {                                   // state-only forward sweep: writes the checkpoints
         FwdParams f{};
         f.B = a->B; f.D = a->D; f.N = a->N; f.L = a->L;
+        f.bcg = bcg; f.dpg = a->D / bcg;
         f.softplus = a->delta_softplus ? 1 : 0;
         f.u = a->u; f.delta = a->delta;
         f.u_sb = a->u_stride_b; f.u_sd = a->u_stride_d; f.dl_sb = a->delta_stride_b; f.dl_sd = a->delta_stride_d;
@@ -215,6 +224,7 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
 
     BwdParams p{};
     p.B = a->B; p.D = a->D; p.N = a->N; p.L = a->L;
+    p.bcg = bcg; p.dpg = a->D / bcg;
     p.softplus = a->delta_softplus ? 1 : 0;
     p.u = a->u; p.delta = a->delta; p.z = a->z; p.dy = a->dy;
     p.du = a->du; p.ddelta = a->ddelta; p.dz = a->dz;
@@ -229,10 +239,10 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
             row_vec_ok(a->dy, p.dy_sb, p.dy_sd, es) && (!a->z || row_vec_ok(a->z, p.z_sb, p.z_sd, es)) &&
             row_vec_ok(a->du, p.du_sb, p.du_sd, es) && row_vec_ok(a->ddelta, p.dd_sb, p.dd_sd, es) &&
             (!a->dz || row_vec_ok(a->dz, p.dz_sb, p.dz_sd, es));
-    p.G = bwd_channels_per_group(a->B, a->D, a->N, a->L);
+    p.G = bwd_channels_per_group(a->B * bcg, a->D / bcg, a->N, a->L);
 
     // reduced outputs are accumulated with atomics: clear them on the stream first
-    const int64_t nbc = (int64_t)a->B * a->L * a->N;
+    const int64_t nbc = (int64_t)a->B * bcg * a->L * a->N;
     FillList z{};
     z.ptr[0] = a->dBm; z.count[0] = nbc;
     z.ptr[1] = a->dCm; z.count[1] = nbc;

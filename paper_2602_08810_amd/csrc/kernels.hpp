@@ -13,6 +13,7 @@ struct FwdParams {
     int B, D, N;
     int64_t L;
     int softplus, mode, vec;
+    int bcg, dpg;            // number of Bm/Cm groups and channels per group (D = bcg * dpg)
     int nchunks;
     int64_t tiles_per_chunk;
     const void *u, *delta, *z;
@@ -29,6 +30,7 @@ struct BwdParams {
     int64_t L;
     int softplus, vec;
     int G;                   // channels per workgroup
+    int bcg, dpg;            // number of Bm/Cm groups and channels per group (D = bcg * dpg)
     const void *u, *delta, *z, *dy;
     void *du, *ddelta, *dz;
     int64_t u_sb, u_sd, dl_sb, dl_sd, z_sb, z_sd, dy_sb, dy_sd, du_sb, du_sd, dd_sb, dd_sd, dz_sb, dz_sd;

@@ -56,8 +56,13 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b = blockIdx.y;
-    const int d0 = blockIdx.x * p.G;
-    const int Gact = (p.D - d0 < p.G) ? p.D - d0 : p.G;
+    // a workgroup takes up to G consecutive channels of ONE Bm/Cm group
+    const int chunks_per_grp = (p.dpg + p.G - 1) / p.G;
+    const int grp = blockIdx.x / chunks_per_grp;
+    const int din0 = (blockIdx.x % chunks_per_grp) * p.G;
+    const int d0 = grp * p.dpg + din0;
+    const int Gact = (p.dpg - din0 < p.G) ? p.dpg - din0 : p.G;
+    const int64_t bg = (int64_t)b * p.bcg + grp;                     // row of Bm, Cm, dBm, dCm
     const int64_t L = p.L;
     const int64_t ntiles = (L + TILE - 1) / TILE;
     const int64_t nck = (L + kCkptInterval - 1) / kCkptInterval;
@@ -67,8 +72,8 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     for (int i = tid; i < kMaxG * N; i += NT) { sH[i] = 0.0f; sdA[i] = 0.0f; }
     for (int i = tid; i < W * kMaxG; i += NT) { sdD[i] = 0.0f; sdb[i] = 0.0f; }
 
-    const IO *Bm = reinterpret_cast<const IO *>(p.Bm) + (int64_t)b * L * N;
-    const IO *Cm = reinterpret_cast<const IO *>(p.Cm) + (int64_t)b * L * N;
+    const IO *Bm = reinterpret_cast<const IO *>(p.Bm) + bg * L * N;
+    const IO *Cm = reinterpret_cast<const IO *>(p.Cm) + bg * L * N;
 
     // flat position of this thread in prologue / epilogue, and its slot in the [q][lane][4] layout
     const int f0 = tid * TPW;
@@ -326,7 +331,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
             }
             __syncthreads();
             const int step0 = j * 16 * T;                                // within the tile
-            float *gB = p.dBm + ((int64_t)b * L + l0 + step0) * N, *gC = p.dCm + ((int64_t)b * L + l0 + step0) * N;
+            float *gB = p.dBm + (bg * L + l0 + step0) * N, *gC = p.dCm + (bg * L + l0 + step0) * N;
             for (int idx = tid; idx < 16 * T * N; idx += NT) {
                 if (step0 + idx / N < rem) {
                     unsafeAtomicAdd(gB + (unsigned)idx, fbB[idx]);
@@ -355,6 +360,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
 
 #ifndef LRNNX_KERNEL_ONLY
 // ---------------------------------------------------------------- launchers
+// channels per workgroup: D here is the number of channels that share one pair of Bm/Cm maps
 int bwd_channels_per_group(int B, int D, int, int64_t) {
     int64_t G = ((int64_t)B * D) / 512;               // aim at >= 512 workgroups (two per CU)
     if (G < 8) G = 8;
@@ -367,7 +373,7 @@ int bwd_channels_per_group(int B, int D, int, int64_t) {
 
 template <typename IO, int N, int NK, int DISC, int T = 8>
 static hipError_t launch_bwd_n(const BwdParams &p, hipStream_t s) {
-    dim3 grid((p.D + p.G - 1) / p.G, p.B);
+    dim3 grid(p.bcg * ((p.dpg + p.G - 1) / p.G), p.B);
     hipLaunchKernelGGL((k_ss_bwd<IO, N, NK, T, DISC>), grid, dim3((N / NK) * 64), 0, s, p);
     return hipGetLastError();
 }

@@ -34,9 +34,12 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int b = blockIdx.y;
-    const int d_raw = blockIdx.x * W + w;
-    const bool active = d_raw < p.D;
-    const int d = active ? d_raw : p.D - 1;
+    // a workgroup takes W consecutive channels of ONE Bm/Cm group (it stages that group's maps in LDS)
+    const int blk_per_grp = (p.dpg + W - 1) / W;
+    const int grp = blockIdx.x / blk_per_grp;
+    const int d_in = (blockIdx.x % blk_per_grp) * W + w;
+    const bool active = d_in < p.dpg;
+    const int d = grp * p.dpg + (active ? d_in : p.dpg - 1);
     const int chunk = blockIdx.z;
     const int64_t L = p.L;
     const int64_t ntiles = (L + TILE - 1) / TILE;
@@ -50,8 +53,8 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
     const IO *drow = reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd;
     const IO *zrow = p.z ? reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd : nullptr;
     IO *yrow = p.y ? reinterpret_cast<IO *>(p.y) + b * p.y_sb + d * p.y_sd : nullptr;
-    const IO *Bm = reinterpret_cast<const IO *>(p.Bm) + (int64_t)b * L * N;
-    const IO *Cm = reinterpret_cast<const IO *>(p.Cm) + (int64_t)b * L * N;
+    const IO *Bm = reinterpret_cast<const IO *>(p.Bm) + ((int64_t)b * p.bcg + grp) * L * N;
+    const IO *Cm = reinterpret_cast<const IO *>(p.Cm) + ((int64_t)b * p.bcg + grp) * L * N;
 
     // Per-state uniform values live one per lane (lane n holds state n) and are read with
     // v_readlane, so the loop over n stays rolled and nothing is indexed dynamically.
@@ -224,7 +227,7 @@ int fwd_tile_steps(int) { return 64 * kFwdT; }
 
 template <typename IO, int N, int DISC>
 static hipError_t launch_fwd_n(const FwdParams &p, hipStream_t s) {
-    dim3 grid((p.D + kFwdW - 1) / kFwdW, p.B, p.nchunks);
+    dim3 grid(p.bcg * ((p.dpg + kFwdW - 1) / kFwdW), p.B, p.nchunks);
     const bool want_y = (p.mode == MODE_FULL || p.mode == MODE_APPLY);
     const dim3 block(kFwdW * 64);
     if (want_y && p.ckpt) hipLaunchKernelGGL((k_ss_fwd<IO, N, kFwdT, kFwdW, DISC, true, true>), grid, block, 0, s, p);

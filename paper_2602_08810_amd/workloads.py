@@ -41,12 +41,12 @@ def _io_round(x: np.ndarray, io: str) -> np.ndarray:
 
 
 def make_selective(B, D, N, L, io="f32", gate=False, bias=("const", -2.0), seed=0,
-                   with_dy=True, with_x0=False, **_unused):
+                   with_dy=True, with_x0=False, bc_groups=1, **_unused):
     """Inputs of the selective scan.
 
     A[d,n] = -exp(U(-1,1)); delta ~ N(0,1) (raw, pre-bias, pre-softplus);
     delta_bias constant or U(lo,hi) per channel; Bm, Cm ~ N(0,1) [B,L,N] shared
-    by all channels; u, Dskip, z, dy ~ N(0,1).
+    by all channels ([B,G,L,N] with bc_groups = G > 1); u, Dskip, z, dy ~ N(0,1).
     """
     rng = np.random.Generator(np.random.PCG64(seed))
     f32 = np.float32
@@ -59,8 +59,9 @@ def make_selective(B, D, N, L, io="f32", gate=False, bias=("const", -2.0), seed=
         out["delta_bias"] = np.full(D, bias[1], dtype=f32)
     else:
         out["delta_bias"] = rng.uniform(bias[1], bias[2], size=D).astype(f32)
-    out["Bm"] = _io_round(rng.standard_normal((B, L, N), dtype=f32), io)
-    out["Cm"] = _io_round(rng.standard_normal((B, L, N), dtype=f32), io)
+    bc_shape = (B, L, N) if bc_groups <= 1 else (B, bc_groups, L, N)
+    out["Bm"] = _io_round(rng.standard_normal(bc_shape, dtype=f32), io)
+    out["Cm"] = _io_round(rng.standard_normal(bc_shape, dtype=f32), io)
     out["u"] = _io_round(rng.standard_normal((B, D, L), dtype=f32), io)
     out["delta"] = _io_round(rng.standard_normal((B, D, L), dtype=f32), io)
     out["z"] = _io_round(rng.standard_normal((B, D, L), dtype=f32), io) if gate else None
