@@ -292,6 +292,29 @@ def _other_configs(api, torch, dev):
                                  "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS,
                                  "note": "includes the Python call overhead of one launch per token"}
 
+    # the same step as a generation loop of 64 tokens captured once in a HIP graph and replayed (Sec. 4.2 of the
+    # paper measures generation this way): per-token time without the per-call host overhead
+    Tg = 64
+    tg = sel(Bs, Ds, Ns, Tg, True)
+    ug, dg, zg = (tg[k].permute(2, 0, 1).contiguous() for k in ("u", "delta", "z"))         # [T,B,D]
+    Bg, Cg = tg["Bm"].permute(1, 0, 2).contiguous(), tg["Cm"].permute(1, 0, 2).contiguous()  # [T,B,N]
+    yg = torch.empty((Tg, Bs, Ds), dtype=bf, device=dev)
+
+    def gen_loop():
+        for t in range(Tg):
+            api.lrnnx_selective_step(xs, ug[t], dg[t], ts["A"], Bg[t], Cg[t], Dskip=ts["Dskip"],
+                                     delta_bias=ts["delta_bias"], z=zg[t], out=yg[t])
+    gen_loop()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        gen_loop()
+    tt = _time(torch, graph.replay, 20) / Tg
+    out["step_B64_D1536_N16_graph"] = {"us": tt * 1e6, "elements_per_s": Bs * Ds * Ns / tt, "hbm_GBs": nb / tt / 1e9,
+                                       "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS,
+                                       "note": "per token, 64 step calls replayed from one HIP graph"}
+    del graph
+
     # config 3: long-sequence forward, both paths
     B3, D3, N3, L3 = 1, 2048, 16, 65536
     t3 = sel(B3, D3, N3, L3, False)
