@@ -6,55 +6,64 @@
 
 namespace lrnnx {
 
-// One thread per (b,d): x[b,d,:] <- a (.) x[b,d,:] + g Bm[b,:] u[b,d];  y[b,d] = Cm[b,:] . x + Dskip[d] u, gated.
+// x[b,d,:] <- a (.) x[b,d,:] + g Bm[b,:] u[b,d];  y[b,d] = Cm[b,:] . x + Dskip[d] u, gated.
+// A thread owns 4 consecutive states of one (b,d) (all of them when N < 4), so that the lanes of a wavefront read and
+// write the state as one contiguous run of 16-byte pieces; the N/4 lanes of a row are neighbours and sum their parts of
+// y with xor-shuffles.  The per-row scalars (u, delta, z, bias) are loaded by every lane of the row (same address).
 template <typename IO, int N, int DISC>
 __global__ __launch_bounds__(256) void k_ss_step(const StepParams p) {
-    const int d = blockIdx.x * 256 + threadIdx.x;
-    const int b = blockIdx.y;
-    if (d >= p.D) return;
-    const int64_t row = (int64_t)b * p.D + d;
+    constexpr int NPT = N >= 4 ? 4 : N;        // states per thread
+    constexpr int Q = N / NPT;                 // threads per (b,d) row: a power of two, at most 64
+    const int64_t i = blockIdx.x * (int64_t)256 + threadIdx.x;
+    const int64_t total = (int64_t)p.B * p.D * Q;
+    const bool live = i < total;               // dead lanes still take part in the shuffles below
+    const int64_t row = live ? i / Q : 0;
+    const int q = (int)(i % Q);
+    const int b = (int)(row / p.D), d = (int)(row % p.D);
     const float uu = io_traits<IO>::get(reinterpret_cast<const IO *>(p.u), b * p.u_sb + d * p.u_sd);
     const float s = io_traits<IO>::get(reinterpret_cast<const IO *>(p.delta), b * p.dl_sb + d * p.dl_sd) +
                     (p.bias ? p.bias[d] : 0.0f);
     float dt = s, sg;
     if (p.softplus) softplus_sigmoid(s, dt, sg);
-    float xs[N], Av[N], Bv[N], Cv[N];
-    if constexpr (N % 4 == 0) {
-#pragma unroll
-        for (int q = 0; q < N / 4; ++q) {
-            const float4 vx = reinterpret_cast<const float4 *>(p.x + row * N)[q];
-            const float4 va = reinterpret_cast<const float4 *>(p.A + (int64_t)d * N)[q];
-            xs[4 * q] = vx.x; xs[4 * q + 1] = vx.y; xs[4 * q + 2] = vx.z; xs[4 * q + 3] = vx.w;
-            Av[4 * q] = va.x; Av[4 * q + 1] = va.y; Av[4 * q + 2] = va.z; Av[4 * q + 3] = va.w;
-        }
+    float xs[NPT], Av[NPT], Bv[NPT], Cv[NPT];
+    float *xp = p.x + row * N + q * NPT;
+    const float *ap = p.A + (int64_t)d * N + q * NPT;
+    if constexpr (NPT == 4) {
+        const float4 vx = *reinterpret_cast<const float4 *>(xp), va = *reinterpret_cast<const float4 *>(ap);
+        xs[0] = vx.x; xs[1] = vx.y; xs[2] = vx.z; xs[3] = vx.w;
+        Av[0] = va.x; Av[1] = va.y; Av[2] = va.z; Av[3] = va.w;
     } else {
 #pragma unroll
-        for (int n = 0; n < N; ++n) { xs[n] = p.x[row * N + n]; Av[n] = p.A[(int64_t)d * N + n]; }
+        for (int n = 0; n < NPT; ++n) { xs[n] = xp[n]; Av[n] = ap[n]; }
     }
-    load_row<IO, N>(reinterpret_cast<const IO *>(p.Bm) + (int64_t)b * N, Bv);
-    load_row<IO, N>(reinterpret_cast<const IO *>(p.Cm) + (int64_t)b * N, Cv);
-    float acc = p.Dskip ? p.Dskip[d] * uu : 0.0f;
+    load_row<IO, NPT>(reinterpret_cast<const IO *>(p.Bm) + (int64_t)b * N + q * NPT, Bv);
+    load_row<IO, NPT>(reinterpret_cast<const IO *>(p.Cm) + (int64_t)b * N + q * NPT, Cv);
+    float acc = 0.0f;
 #pragma unroll
-    for (int n = 0; n < N; ++n) {
+    for (int n = 0; n < NPT; ++n) {
         const ACoef ac = make_acoef<DISC>(Av[n]);
         float a, g;
         disc_ag<DISC>(dt, ac, a, g);
         xs[n] = __builtin_fmaf(a, xs[n], g * Bv[n] * uu);
         acc = __builtin_fmaf(Cv[n], xs[n], acc);
     }
-    if constexpr (N % 4 == 0) {
+    if (live) {
+        if constexpr (NPT == 4) *reinterpret_cast<float4 *>(xp) = make_float4(xs[0], xs[1], xs[2], xs[3]);
+        else {
 #pragma unroll
-        for (int q = 0; q < N / 4; ++q)
-            reinterpret_cast<float4 *>(p.x + row * N)[q] = make_float4(xs[4 * q], xs[4 * q + 1], xs[4 * q + 2], xs[4 * q + 3]);
-    } else {
+            for (int n = 0; n < NPT; ++n) xp[n] = xs[n];
+        }
+    }
 #pragma unroll
-        for (int n = 0; n < N; ++n) p.x[row * N + n] = xs[n];
+    for (int m = 1; m < Q; m <<= 1) acc += __shfl_xor(acc, m, 64);
+    if (live && q == 0) {
+        if (p.Dskip) acc = __builtin_fmaf(p.Dskip[d], uu, acc);
+        if (p.z) {
+            const float zz = io_traits<IO>::get(reinterpret_cast<const IO *>(p.z), b * p.z_sb + d * p.z_sd);
+            acc *= zz * sigmoid_fast(zz);
+        }
+        io_traits<IO>::put(reinterpret_cast<IO *>(p.y), b * p.y_sb + d * p.y_sd, acc);
     }
-    if (p.z) {
-        const float zz = io_traits<IO>::get(reinterpret_cast<const IO *>(p.z), b * p.z_sb + d * p.z_sd);
-        acc *= zz * sigmoid_fast(zz);
-    }
-    io_traits<IO>::put(reinterpret_cast<IO *>(p.y), b * p.y_sb + d * p.y_sd, acc);
 }
 
 // One thread per (b,p): x[b,p] <- lambda[p] x[b,p] + v[b,p], complex.
@@ -68,7 +77,8 @@ __global__ __launch_bounds__(256) void k_lti_step(int B, int P, const float2 *la
 
 template <typename IO, int DISC>
 static hipError_t launch_step_disc(const StepParams &p, hipStream_t s) {
-    dim3 grid((p.D + 255) / 256, p.B), block(256);
+    const int64_t threads = (int64_t)p.B * p.D * (p.N >= 4 ? p.N / 4 : 1);
+    dim3 grid((unsigned)((threads + 255) / 256)), block(256);
     switch (p.N) {
         case 1: hipLaunchKernelGGL((k_ss_step<IO, 1, DISC>), grid, block, 0, s, p); break;
         case 2: hipLaunchKernelGGL((k_ss_step<IO, 2, DISC>), grid, block, 0, s, p); break;
