@@ -513,3 +513,91 @@ def test_grouped_gradients_of_the_maps_by_finite_differences(oracle):
             q[k][idx] -= 2 * h
             num = (up - loss(q)) / (2 * h)
             assert num == pytest.approx(g[gk][idx], rel=1e-6, abs=1e-8), (k, idx)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Packed variable-length batches (independent sequences one after the other on one time axis).
+# ---------------------------------------------------------------------------------------------------------------
+def _packed_problem(seed, D=3, N=2, L=23, cu=(0, 5, 6, 14, 23), G=None):
+    rng = np.random.default_rng(seed)
+    S = len(cu) - 1
+    bc = (L, N) if G is None else (G, L, N)
+    p = dict(u=rng.standard_normal((D, L)), delta=rng.standard_normal((D, L)), A=-np.exp(rng.uniform(-1, 1, (D, N))),
+             Bm=rng.standard_normal(bc), Cm=rng.standard_normal(bc), Dskip=rng.standard_normal(D),
+             delta_bias=rng.uniform(-2, 0, D), z=rng.standard_normal((D, L)), x0=rng.standard_normal((S, D, N)))
+    return p, np.array(cu), rng.standard_normal((D, L))
+
+
+def test_packed_states_equal_one_long_scan_whose_multiplier_is_zeroed_at_every_boundary(oracle):
+    """An independent route to the same numbers: ONE recurrence over the whole packed axis in which the first step of
+    every sequence forgets the past (a = 0) and takes that sequence's x0 through b."""
+    p, cu, _ = _packed_problem(51)
+    D, L = p["u"].shape
+    N = p["A"].shape[1]
+    dt = np.logaddexp(0.0, p["delta"] + p["delta_bias"][:, None])                       # [D,L]
+    a = np.exp(dt.T[:, :, None] * p["A"][None])                                         # [L,D,N]
+    b = (dt * p["u"]).T[:, :, None] * p["Bm"][:, None, :]
+    for s, o in enumerate(cu[:-1]):
+        if o < L:
+            b[o] += a[o] * p["x0"][s]
+            a[o] = 0.0
+    x = oracle.diag_scan(a.reshape(1, L, D * N), b.reshape(1, L, D * N)).reshape(L, D, N)
+    ypre = np.einsum("ln,ldn->dl", p["Cm"], x) + p["Dskip"][:, None] * p["u"]
+    yref = ypre * p["z"] / (1 + np.exp(-p["z"]))
+    y, x_last = oracle.selective_scan_fwd_packed(cu_seqlens=cu, **p)
+    np.testing.assert_allclose(y, yref, rtol=1e-12, atol=1e-13)
+    for s in range(len(cu) - 1):
+        np.testing.assert_allclose(x_last[s], x[cu[s + 1] - 1], rtol=1e-12)
+
+
+def test_packed_sequences_do_not_see_each_other(oracle):
+    p, cu, dy = _packed_problem(52)
+    y, xl = oracle.selective_scan_fwd_packed(cu_seqlens=cu, **p)
+    g = oracle.selective_scan_bwd_packed(dy=dy, cu_seqlens=cu, **p)
+    q = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in p.items()}
+    o, e = cu[2], cu[3]                                    # disturb sequence 2 only
+    q["u"][:, o:e] += 1.0
+    q["Bm"][o:e] *= 2.0
+    q["x0"][2] -= 3.0
+    y2, xl2 = oracle.selective_scan_fwd_packed(cu_seqlens=cu, **q)
+    g2 = oracle.selective_scan_bwd_packed(dy=dy, cu_seqlens=cu, **q)
+    keep = np.ones(p["u"].shape[1], bool)
+    keep[o:e] = False
+    assert np.array_equal(y[:, keep], y2[:, keep]) and not np.allclose(y[:, o:e], y2[:, o:e])
+    assert np.array_equal(np.delete(xl, 2, 0), np.delete(xl2, 2, 0))
+    for k in ("du", "ddelta", "dz"):
+        assert np.array_equal(g[k][:, keep], g2[k][:, keep]), k
+    assert np.array_equal(g["dBm"][keep], g2["dBm"][keep]) and np.array_equal(g["dCm"][keep], g2["dCm"][keep])
+
+
+def test_packed_with_one_sequence_is_the_plain_call_and_gaps_stay_zero(oracle):
+    p, _, dy = _packed_problem(53, cu=(0, 23))
+    y, xl = oracle.selective_scan_fwd_packed(cu_seqlens=np.array([0, 23]), **p)
+    q = dict(u=p["u"][None], delta=p["delta"][None], A=p["A"], Bm=p["Bm"][None], Cm=p["Cm"][None], Dskip=p["Dskip"],
+             delta_bias=p["delta_bias"], z=p["z"][None], x0=p["x0"])
+    yr, xr = oracle.selective_scan_fwd(**q)
+    np.testing.assert_array_equal(y, yr[0])
+    np.testing.assert_array_equal(xl, xr)
+    # a batch that leaves steps 0..2 and 20..22 outside every sequence, with an empty sequence in the middle
+    cu = np.array([3, 9, 9, 20])
+    p3, _, _ = _packed_problem(54, cu=(3, 9, 9, 20))
+    y3, xl3 = oracle.selective_scan_fwd_packed(cu_seqlens=cu, **p3)
+    assert np.all(y3[:, :3] == 0) and np.all(y3[:, 20:] == 0)
+    np.testing.assert_array_equal(xl3[1], p3["x0"][1])     # an empty sequence hands its x0 through
+
+
+def test_packed_backward_by_finite_differences_with_grouped_maps(oracle):
+    p, cu, dy = _packed_problem(55, D=4, N=2, L=11, cu=(0, 4, 11), G=2)
+    g = oracle.selective_scan_bwd_packed(dy=dy, cu_seqlens=cu, **p)
+    loss = lambda q: float((oracle.selective_scan_fwd_packed(cu_seqlens=cu, **q)[0] * dy).sum())
+    h = 1e-6
+    names = {"u": "du", "delta": "ddelta", "A": "dA", "Bm": "dBm", "Cm": "dCm", "Dskip": "dD", "delta_bias": "dbias",
+             "z": "dz", "x0": "dx0"}
+    for k, gk in names.items():
+        for idx in np.ndindex(p[k].shape):
+            q = {n: (v.copy() if isinstance(v, np.ndarray) else v) for n, v in p.items()}
+            q[k][idx] += h
+            up = loss(q)
+            q[k][idx] -= 2 * h
+            num = (up - loss(q)) / (2 * h)
+            assert num == pytest.approx(g[gk][idx], rel=2e-6, abs=1e-7), (k, idx)
