@@ -72,6 +72,8 @@ typedef enum {
  * The forward pass can write them; the backward pass restarts its recomputation
  * from them.  The interval is a constant of the build.                        */
 int64_t lrnnx_ckpt_interval(void);
+/* Checkpoint slots per channel in packed variable-length mode: L / interval + B. */
+int64_t lrnnx_packed_ckpt_slots(int64_t L, int64_t B);
 
 /* ------------------------------------------------------------------ selective scan, forward
  * For every row (b,d), with s_l = delta[b,d,l] + delta_bias[d],
@@ -82,6 +84,12 @@ int64_t lrnnx_ckpt_interval(void);
  * x_{-1} = x0[b,d,:] or 0.  Optional (NULL allowed): Dskip, delta_bias, z, x0, x_last, ckpt.
  * Grouped maps: with bc_groups = G > 1, Bm and Cm are [B,G,L,N] and channel d reads group d / (D/G)
  * (D must be a multiple of G); G = 0 or 1 is the plain [B,L,N] case.
+ * Packed variable-length sequences: with cu_seqlens != NULL, B independent sequences lie one after the other on
+ * ONE time axis of L steps, sequence b being steps cu_seqlens[b] .. cu_seqlens[b+1]-1 (each starts from x0[b] or 0,
+ * nothing crosses a boundary; steps outside every sequence are not touched).  u, delta, z, y are then [D,L] (the
+ * batch strides are ignored), Bm and Cm [G,L,N], x0 and x_last [B,D,N], and ckpt is
+ * [D, lrnnx_packed_ckpt_slots(L,B), N].  Boundaries are clamped to [0,L] on the device; the single-pass path
+ * is used (LRNNX_PATH_CHUNK_CARRY is refused).
  * workspace is needed only by LRNNX_PATH_CHUNK_CARRY (AUTO falls back to the single
  * pass when it is missing or too small).                                              */
 typedef struct lrnnx_ss_fwd_args {
@@ -108,6 +116,7 @@ typedef struct lrnnx_ss_fwd_args {
     void *stream;
     int32_t bc_groups;       /* number of Bm/Cm groups; callers built against the shorter struct get 1 */
     int32_t reserved;
+    const int64_t *cu_seqlens;   /* packed variable-length mode (see below), device memory [B+1], or NULL */
 } lrnnx_ss_fwd_args;
 
 int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *args);
@@ -152,6 +161,9 @@ typedef struct lrnnx_ss_bwd_args {
     float *dx0;                                                    /* [B,D,N] out or NULL */
     void *workspace;    size_t workspace_bytes;
     void *stream;
+    const int64_t *cu_seqlens;   /* as in the forward call (then dBm, dCm are [G,L,N]); callers built against the
+                                    shorter struct get NULL.  With ckpt == NULL the workspace must hold
+                                    D * lrnnx_packed_ckpt_slots(L,B) * N floats. */
 } lrnnx_ss_bwd_args;
 
 int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *args);

@@ -37,7 +37,7 @@ class FwdArgs(ctypes.Structure):
         ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
         ("x_last", _vp), ("ckpt", _vp),
         ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
-        ("bc_groups", _i32), ("reserved", _i32),
+        ("bc_groups", _i32), ("reserved", _i32), ("cu_seqlens", _vp),
     ]
 
 
@@ -56,7 +56,7 @@ class BwdArgs(ctypes.Structure):
         ("ddelta", _vp), ("ddelta_stride_b", _i64), ("ddelta_stride_d", _i64),
         ("dz", _vp), ("dz_stride_b", _i64), ("dz_stride_d", _i64),
         ("dA", _vp), ("dBm", _vp), ("dCm", _vp), ("dD", _vp), ("dbias", _vp), ("dx0", _vp),
-        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
+        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp), ("cu_seqlens", _vp),
     ]
 
 
@@ -192,6 +192,13 @@ def lrnnx_workspace_bytes(which, B, D, N, L, io_dtype) -> int:
     return int(lib().lrnnx_workspace_bytes(which, B, D, N, L, io_dtype))
 
 
+def _check_cu(cu):
+    """Number of sequences of a packed batch; cu is int64 [S+1] on the device."""
+    if cu.dtype != torch.int64 or cu.dim() != 1 or not cu.is_contiguous() or not cu.is_cuda or cu.numel() < 2:
+        raise ValueError("cu_seqlens: expected a contiguous int64 device tensor [S+1]")
+    return cu.numel() - 1
+
+
 def _bc_groups(Bm, Cm, io, Bsz, D, L, N):
     """Number of groups of the maps: [B,L,N] -> 1, [B,G,L,N] -> G (channel d reads group d // (D/G))."""
     for name, t in (("Bm", Bm), ("Cm", Cm)):
@@ -207,16 +214,28 @@ def _bc_groups(Bm, Cm, io, Bsz, D, L, N):
 
 def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, x0=None,
                              disc="zoh_s6", delta_softplus=True, path="auto",
-                             return_last_state=False, return_ckpt=False, out=None, ckpt_out=None, workspace=None):
+                             return_last_state=False, return_ckpt=False, out=None, ckpt_out=None, workspace=None,
+                             cu_seqlens=None):
     """y (and optionally x_last, ckpt) of the forward selective scan; see lrnnx_ss_fwd_args.
 
-    `out`, `ckpt_out` and `workspace` may supply preallocated buffers (ckpt_out implies return_ckpt)."""
+    `out`, `ckpt_out` and `workspace` may supply preallocated buffers (ckpt_out implies return_ckpt).
+    With `cu_seqlens` (int64 [S+1] on the device) the call is in packed variable-length mode: u, delta, z, y are
+    [D,L], Bm and Cm [L,N] or [G,L,N], x0 and x_last [S,D,N]."""
     io = u.dtype
-    Bsz, D, L = u.shape
+    packed = cu_seqlens is not None
+    if packed:
+        Bsz = _check_cu(cu_seqlens)
+        u, delta, z, out = (None if t is None else t.unsqueeze(0) for t in (u, delta, z, out))
+        Bm, Cm = Bm.unsqueeze(0), Cm.unsqueeze(0)
+    Bio = 1 if packed else u.shape[0]                   # leading dimension of the I/O tensors and of the maps
+    if not packed:
+        Bsz = Bio
+    _, D, L = u.shape
     N = A.shape[1]
     a = FwdArgs()
     a.struct_size = ctypes.sizeof(FwdArgs)
     a.B, a.D, a.N, a.L = Bsz, D, N, L
+    a.cu_seqlens = _ptr(cu_seqlens)
     a.io_dtype = _io_dtype(u)
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
     a.delta_softplus = int(bool(delta_softplus))
@@ -225,12 +244,12 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
     a.delta, a.delta_stride_b, a.delta_stride_d = _bdl(delta, "delta", io)
     a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io)
     a.A = _ptr(_f32c(A, "A", (D, N)))
-    a.bc_groups = _bc_groups(Bm, Cm, io, Bsz, D, L, N)
+    a.bc_groups = _bc_groups(Bm, Cm, io, Bio, D, L, N)
     a.Bm, a.Cm = Bm.data_ptr(), Cm.data_ptr()
     a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
     a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
     a.x0 = _ptr(_f32c(x0, "x0", (Bsz, D, N)))
-    y = out if out is not None else torch.empty((Bsz, D, L), dtype=io, device=u.device)
+    y = out if out is not None else torch.empty((Bio, D, L), dtype=io, device=u.device)
     a.y, a.y_stride_b, a.y_stride_d = _bdl(y, "y", io)
     x_last = torch.empty((Bsz, D, N), dtype=torch.float32, device=u.device) if return_last_state else None
     a.x_last = _ptr(x_last)
@@ -238,9 +257,10 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
     return_ckpt = return_ckpt or ckpt_out is not None
     if return_ckpt:
         I = lrnnx_ckpt_interval()
+        ck_shape = (D, L // I + Bsz, N) if packed else (Bsz, D, (L + I - 1) // I, N)
         if ckpt is None:
-            ckpt = torch.empty((Bsz, D, (L + I - 1) // I, N), dtype=torch.float32, device=u.device)
-        _f32c(ckpt, "ckpt_out", (Bsz, D, (L + I - 1) // I, N))
+            ckpt = torch.empty(ck_shape, dtype=torch.float32, device=u.device)
+        _f32c(ckpt, "ckpt_out", ck_shape)
     a.ckpt = _ptr(ckpt)
     if workspace is None:
         nbytes = lrnnx_workspace_bytes(WS_FWD, Bsz, D, N, L, a.io_dtype)
@@ -248,7 +268,7 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
     a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
     a.stream = _stream()
     _check(lib().lrnnx_selective_scan_fwd(ctypes.byref(a)))
-    res = (y,)
+    res = (y[0] if packed else y,)
     if return_last_state:
         res += (x_last,)
     if return_ckpt:
@@ -258,13 +278,24 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
 
 def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,
                              ckpt=None, disc="zoh_s6", delta_softplus=True, want_dx0=False,
-                             outs=None, workspace=None):
-    """Gradients of sum(dy*y) as a dict; see lrnnx_ss_bwd_args.  `outs` may supply preallocated outputs."""
+                             outs=None, workspace=None, cu_seqlens=None):
+    """Gradients of sum(dy*y) as a dict; see lrnnx_ss_bwd_args.  `outs` may supply preallocated outputs.
+    `cu_seqlens`: packed variable-length mode as in the forward call (du, ddelta, dz are [D,L]; dBm, dCm as Bm)."""
     io = u.dtype
-    Bsz, D, L = u.shape
+    packed = cu_seqlens is not None
+    if packed:
+        Bsz = _check_cu(cu_seqlens)
+        u, delta, z, dy = (None if t is None else t.unsqueeze(0) for t in (u, delta, z, dy))
+        Bm, Cm = Bm.unsqueeze(0), Cm.unsqueeze(0)
+    Bio = 1 if packed else u.shape[0]
+    if not packed:
+        Bsz = Bio
+    _, D, L = u.shape
     N = A.shape[1]
     dev = u.device
     outs = dict(outs or {})
+    if packed:                                          # caller-supplied outputs are in the packed shapes
+        outs = {k: (v.unsqueeze(0) if k in ("du", "ddelta", "dz", "dBm", "dCm") else v) for k, v in outs.items()}
 
     def new(name, shape, dtype):
         if name not in outs:
@@ -274,6 +305,7 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
     a = BwdArgs()
     a.struct_size = ctypes.sizeof(BwdArgs)
     a.B, a.D, a.N, a.L = Bsz, D, N, L
+    a.cu_seqlens = _ptr(cu_seqlens)
     a.io_dtype = _io_dtype(u)
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
     a.delta_softplus = int(bool(delta_softplus))
@@ -282,16 +314,16 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
     a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io)
     a.dy, a.dy_stride_b, a.dy_stride_d = _bdl(dy, "dy", io)
     a.A = _ptr(_f32c(A, "A", (D, N)))
-    a.bc_groups = _bc_groups(Bm, Cm, io, Bsz, D, L, N)
+    a.bc_groups = _bc_groups(Bm, Cm, io, Bio, D, L, N)
     a.Bm, a.Cm = Bm.data_ptr(), Cm.data_ptr()
     a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
     a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
     a.x0 = _ptr(_f32c(x0, "x0", (Bsz, D, N)))
     a.ckpt = _ptr(_f32c(ckpt, "ckpt"))
-    a.du, a.du_stride_b, a.du_stride_d = _bdl(new("du", (Bsz, D, L), io), "du", io)
-    a.ddelta, a.ddelta_stride_b, a.ddelta_stride_d = _bdl(new("ddelta", (Bsz, D, L), io), "ddelta", io)
+    a.du, a.du_stride_b, a.du_stride_d = _bdl(new("du", (Bio, D, L), io), "du", io)
+    a.ddelta, a.ddelta_stride_b, a.ddelta_stride_d = _bdl(new("ddelta", (Bio, D, L), io), "ddelta", io)
     if z is not None:
-        a.dz, a.dz_stride_b, a.dz_stride_d = _bdl(new("dz", (Bsz, D, L), io), "dz", io)
+        a.dz, a.dz_stride_b, a.dz_stride_d = _bdl(new("dz", (Bio, D, L), io), "dz", io)
     a.dA = new("dA", (D, N), torch.float32).data_ptr()
     a.dBm = new("dBm", tuple(Bm.shape), torch.float32).data_ptr()
     a.dCm = new("dCm", tuple(Cm.shape), torch.float32).data_ptr()
@@ -302,12 +334,15 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
     if want_dx0:
         a.dx0 = new("dx0", (Bsz, D, N), torch.float32).data_ptr()
     if workspace is None and ckpt is None:
-        nbytes = lrnnx_workspace_bytes(WS_BWD, Bsz, D, N, L, a.io_dtype)
+        nbytes = (D * (L // lrnnx_ckpt_interval() + Bsz) * N * 4 if packed
+                  else lrnnx_workspace_bytes(WS_BWD, Bsz, D, N, L, a.io_dtype))
         workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
     if workspace is not None:
         a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
     a.stream = _stream()
     _check(lib().lrnnx_selective_scan_bwd(ctypes.byref(a)))
+    if packed:
+        outs = {k: (v[0] if k in ("du", "ddelta", "dz", "dBm", "dCm") else v) for k, v in outs.items()}
     return outs
 
 

@@ -77,6 +77,7 @@ FillList onepass_fill(const LtiParams &p) {
 extern "C" {
 
 int64_t lrnnx_ckpt_interval(void) { return kCkptInterval; }
+int64_t lrnnx_packed_ckpt_slots(int64_t L, int64_t B) { return (L < 0 || B < 0) ? 0 : L / kCkptInterval + B; }
 int lrnnx_version(void) { return 100; }
 
 const char *lrnnx_status_string(int status) {
@@ -118,8 +119,13 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
 int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *a) {
     constexpr size_t kOldSize = offsetof(lrnnx_ss_fwd_args, bc_groups);  // struct before `bc_groups` was appended
     if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
-    const int bcg = (a->struct_size >= sizeof(lrnnx_ss_fwd_args) && a->bc_groups > 1) ? a->bc_groups : 1;
-    if (a->struct_size >= sizeof(lrnnx_ss_fwd_args) && a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
+    constexpr size_t kSizeWithGroups = offsetof(lrnnx_ss_fwd_args, cu_seqlens);   // ... and before `cu_seqlens`
+    const bool has_groups = a->struct_size >= kSizeWithGroups;
+    const int bcg = (has_groups && a->bc_groups > 1) ? a->bc_groups : 1;
+    if (has_groups && a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
+    const int64_t *cu = a->struct_size >= sizeof(lrnnx_ss_fwd_args) ? a->cu_seqlens : nullptr;
+    if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
+    if (cu && a->path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_UNSUPPORTED;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
@@ -137,6 +143,7 @@ int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *a) {
     FwdParams p{};
     p.B = a->B; p.D = a->D; p.N = a->N; p.L = a->L;
     p.bcg = bcg; p.dpg = a->D / bcg;
+    p.cu = cu; p.nslots = lrnnx_packed_ckpt_slots(a->L, a->B);
     p.softplus = a->delta_softplus ? 1 : 0;
     p.u = a->u; p.delta = a->delta; p.z = a->z; p.y = a->y;
     p.u_sb = a->u_stride_b; p.u_sd = a->u_stride_d;
@@ -157,7 +164,7 @@ int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *a) {
         const size_t need = (size_t)2 * a->B * a->D * nch * a->N * sizeof(float);
         if (!a->workspace || a->workspace_bytes < need) return LRNNX_ERR_WORKSPACE;
         chunked = true;
-    } else if (a->path == LRNNX_PATH_AUTO && wgs < kNumCU / 2 && ntiles >= 4) {
+    } else if (a->path == LRNNX_PATH_AUTO && !cu && wgs < kNumCU / 2 && ntiles >= 4) {
         nch = fwd_chunks(a->B, a->D, a->L, a->io_dtype, false);
         const size_t need = (size_t)2 * a->B * a->D * nch * a->N * sizeof(float);
         chunked = nch > 1 && a->workspace && a->workspace_bytes >= need;
@@ -182,7 +189,10 @@ int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *a) {
 }
 
 int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
-    if (!a || a->struct_size < sizeof(lrnnx_ss_bwd_args)) return LRNNX_ERR_INVALID_ARG;
+    constexpr size_t kOldSize = offsetof(lrnnx_ss_bwd_args, cu_seqlens);  // struct before `cu_seqlens` was appended
+    if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
+    const int64_t *cu = a->struct_size >= sizeof(lrnnx_ss_bwd_args) ? a->cu_seqlens : nullptr;
+    if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
@@ -202,7 +212,9 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     if (!aligned16(a->Bm) || !aligned16(a->Cm) || !aligned16(a->dBm) || !aligned16(a->dCm)) return LRNNX_ERR_INVALID_ARG;
     const size_t es = elem_size(a->io_dtype);
     const int64_t nck = cdiv(a->L, kCkptInterval);
-    const size_t ck_bytes = (size_t)a->B * a->D * nck * a->N * sizeof(float);
+    const int64_t nslots = lrnnx_packed_ckpt_slots(a->L, a->B);
+    const size_t ck_bytes = cu ? (size_t)a->D * nslots * a->N * sizeof(float)
+                               : (size_t)a->B * a->D * nck * a->N * sizeof(float);
     if (!a->ckpt && (!a->workspace || a->workspace_bytes < ck_bytes)) return LRNNX_ERR_WORKSPACE;
     hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
 
@@ -211,6 +223,7 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
         FwdParams f{};
         f.B = a->B; f.D = a->D; f.N = a->N; f.L = a->L;
         f.bcg = bcg; f.dpg = a->D / bcg;
+        f.cu = cu; f.nslots = nslots;
         f.softplus = a->delta_softplus ? 1 : 0;
         f.u = a->u; f.delta = a->delta;
         f.u_sb = a->u_stride_b; f.u_sd = a->u_stride_d; f.dl_sb = a->delta_stride_b; f.dl_sd = a->delta_stride_d;
@@ -225,6 +238,7 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     BwdParams p{};
     p.B = a->B; p.D = a->D; p.N = a->N; p.L = a->L;
     p.bcg = bcg; p.dpg = a->D / bcg;
+    p.cu = cu; p.nslots = lrnnx_packed_ckpt_slots(a->L, a->B);
     p.softplus = a->delta_softplus ? 1 : 0;
     p.u = a->u; p.delta = a->delta; p.z = a->z; p.dy = a->dy;
     p.du = a->du; p.ddelta = a->ddelta; p.dz = a->dz;
@@ -242,7 +256,7 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     p.G = bwd_channels_per_group(a->B * bcg, a->D / bcg, a->N, a->L);
 
     // reduced outputs are accumulated with atomics: clear them on the stream first
-    const int64_t nbc = (int64_t)a->B * bcg * a->L * a->N;
+    const int64_t nbc = (cu ? 1 : (int64_t)a->B) * bcg * a->L * a->N;   // packed mode: one time axis for all sequences
     FillList z{};
     z.ptr[0] = a->dBm; z.count[0] = nbc;
     z.ptr[1] = a->dCm; z.count[1] = nbc;

@@ -14,6 +14,8 @@ struct FwdParams {
     int64_t L;
     int softplus, mode, vec;
     int bcg, dpg;            // number of Bm/Cm groups and channels per group (D = bcg * dpg)
+    const int64_t *cu;       // packed variable-length mode: [B+1] sequence boundaries on the packed axis of L steps
+    int64_t nslots;          // packed mode: checkpoint slots per channel
     int nchunks;
     int64_t tiles_per_chunk;
     const void *u, *delta, *z;
@@ -31,6 +33,8 @@ struct BwdParams {
     int softplus, vec;
     int G;                   // channels per workgroup
     int bcg, dpg;            // number of Bm/Cm groups and channels per group (D = bcg * dpg)
+    const int64_t *cu;       // packed variable-length mode: [B+1] sequence boundaries on the packed axis of L steps
+    int64_t nslots;          // packed mode: checkpoint slots per channel
     const void *u, *delta, *z, *dy;
     void *du, *ddelta, *dz;
     int64_t u_sb, u_sd, dl_sb, dl_sd, z_sb, z_sd, dy_sb, dy_sd, du_sb, du_sd, dd_sb, dd_sd, dz_sb, dz_sd;

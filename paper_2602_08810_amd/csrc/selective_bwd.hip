@@ -62,18 +62,30 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     const int din0 = (blockIdx.x % chunks_per_grp) * p.G;
     const int d0 = grp * p.dpg + din0;
     const int Gact = (p.dpg - din0 < p.G) ? p.dpg - din0 : p.G;
-    const int64_t bg = (int64_t)b * p.bcg + grp;                     // row of Bm, Cm, dBm, dCm
-    const int64_t L = p.L;
+    const int bcrow = b * p.bcg + grp;                               // row of Bm, Cm, dBm, dCm (unpacked)
+    // Packed variable-length mode (p.cu != nullptr): batch entry b is the sequence of steps cu[b] .. cu[b+1]-1 of ONE
+    // packed time axis of p.L steps; I/O rows have no batch stride, the maps are [G, p.L, N].  The bounds are
+    // clamped to the packed axis, so no content of cu can send an access out of the buffers.
+    int64_t L = p.L, toff = 0, bs = b;
+    if (p.cu) {
+        int64_t o = p.cu[b], e = p.cu[b + 1];
+        o = o < 0 ? 0 : (o > p.L ? p.L : o);
+        e = e < o ? o : (e > p.L ? p.L : e);
+        toff = o; L = e - o; bs = 0;
+    }
     const int64_t ntiles = (L + TILE - 1) / TILE;
-    const int64_t nck = (L + kCkptInterval - 1) / kCkptInterval;
-    const bool vec = p.vec != 0;
+    // checkpoints of this workgroup's rows: [B,D,nck,N], or packed [D,nslots,N] with sequence b at slot toff/interval + b
+    const int64_t nck = p.cu ? p.nslots : (L + kCkptInterval - 1) / kCkptInterval;
+    const int64_t ck0 = p.cu ? toff / kCkptInterval + b : 0;
+    const bool vec = p.vec != 0 && (toff % 8) == 0;
     const bool has_z = p.z != nullptr;
 
     for (int i = tid; i < kMaxG * N; i += NT) { sH[i] = 0.0f; sdA[i] = 0.0f; }
     for (int i = tid; i < W * kMaxG; i += NT) { sdD[i] = 0.0f; sdb[i] = 0.0f; }
 
-    const IO *Bm = reinterpret_cast<const IO *>(p.Bm) + bg * L * N;
-    const IO *Cm = reinterpret_cast<const IO *>(p.Cm) + bg * L * N;
+    const int64_t bc0 = ((p.cu ? (int64_t)grp : (int64_t)bcrow) * p.L + toff) * N;   // first element of the maps of this sequence
+    const IO *Bm = reinterpret_cast<const IO *>(p.Bm) + bc0;
+    const IO *Cm = reinterpret_cast<const IO *>(p.Cm) + bc0;
 
     // flat position of this thread in prologue / epilogue, and its slot in the [q][lane][4] layout
     const int f0 = tid * TPW;
@@ -118,14 +130,14 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
         auto prefetch = [&](int g) {
             const int d = d0 + g;
             const int64_t row = (int64_t)b * p.D + d;
-            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.u) + b * p.u_sb + d * p.u_sd + l0, f0, rem, vec, r_u);
-            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd + l0, f0, rem, vec, r_dl);
-            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.dy) + b * p.dy_sb + d * p.dy_sd + l0, f0, rem, vec, r_dy);
-            if (has_z) load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd + l0, f0, rem, vec, r_z);
+            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.u) + bs * p.u_sb + d * p.u_sd + toff + l0, f0, rem, vec, r_u);
+            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.delta) + bs * p.dl_sb + d * p.dl_sd + toff + l0, f0, rem, vec, r_dl);
+            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.dy) + bs * p.dy_sb + d * p.dy_sd + toff + l0, f0, rem, vec, r_dy);
+            if (has_z) load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.z) + bs * p.z_sb + d * p.z_sd + toff + l0, f0, rem, vec, r_z);
 #pragma unroll
             for (int k = 0; k < NK; ++k) {
                 pA[k] = p.A[d * N + w * NK + k];
-                pck[k] = p.ckpt[(row * nck + tile * CK_PER_TILE) * N + w * NK + k];
+                pck[k] = p.ckpt[((p.cu ? (int64_t)d : row) * nck + ck0 + tile * CK_PER_TILE) * N + w * NK + k];
             }
             pDsk = p.Dskip ? p.Dskip[d] : 0.0f;
             pbias = p.bias ? p.bias[d] : 0.0f;
@@ -307,9 +319,9 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                     dD_part = __builtin_fmaf(e_dyp, e_u, dD_part);
                     db_part += (f0 + i < rem) ? o_dd[i] : 0.0f;
                 }
-                store_few<IO, TPW>(reinterpret_cast<IO *>(p.du) + b * p.du_sb + d * p.du_sd + l0, f0, rem, vec, o_du);
-                store_few<IO, TPW>(reinterpret_cast<IO *>(p.ddelta) + b * p.dd_sb + d * p.dd_sd + l0, f0, rem, vec, o_dd);
-                if (p.dz) store_few<IO, TPW>(reinterpret_cast<IO *>(p.dz) + b * p.dz_sb + d * p.dz_sd + l0, f0, rem, vec, o_dz);
+                store_few<IO, TPW>(reinterpret_cast<IO *>(p.du) + bs * p.du_sb + d * p.du_sd + toff + l0, f0, rem, vec, o_du);
+                store_few<IO, TPW>(reinterpret_cast<IO *>(p.ddelta) + bs * p.dd_sb + d * p.dd_sd + toff + l0, f0, rem, vec, o_dd);
+                if (p.dz) store_few<IO, TPW>(reinterpret_cast<IO *>(p.dz) + bs * p.dz_sb + d * p.dz_sd + toff + l0, f0, rem, vec, o_dz);
                 const float dD_tot = wave_sum(dD_part), db_tot = wave_sum(db_part);
                 if (lane == 0) { sdD[w * kMaxG + g] += dD_tot; sdb[w * kMaxG + g] += db_tot; }
             }
@@ -331,7 +343,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
             }
             __syncthreads();
             const int step0 = j * 16 * T;                                // within the tile
-            float *gB = p.dBm + (bg * L + l0 + step0) * N, *gC = p.dCm + (bg * L + l0 + step0) * N;
+            float *gB = p.dBm + bc0 + (l0 + step0) * N, *gC = p.dCm + bc0 + (l0 + step0) * N;
             for (int idx = tid; idx < 16 * T * N; idx += NT) {
                 if (step0 + idx / N < rem) {
                     unsafeAtomicAdd(gB + (unsigned)idx, fbB[idx]);

@@ -41,20 +41,30 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
     const bool active = d_in < p.dpg;
     const int d = grp * p.dpg + (active ? d_in : p.dpg - 1);
     const int chunk = blockIdx.z;
-    const int64_t L = p.L;
+    // Packed variable-length mode (p.cu != nullptr): batch entry b is the sequence of steps cu[b] .. cu[b+1]-1 of ONE
+    // packed time axis of p.L steps; I/O rows have no batch stride, the maps are [G, p.L, N].  The bounds are
+    // clamped to the packed axis, so no content of cu can send an access out of the buffers.
+    int64_t L = p.L, toff = 0, bs = b;
+    if (p.cu) {
+        int64_t o = p.cu[b], e = p.cu[b + 1];
+        o = o < 0 ? 0 : (o > p.L ? p.L : o);
+        e = e < o ? o : (e > p.L ? p.L : e);
+        toff = o; L = e - o; bs = 0;
+    }
     const int64_t ntiles = (L + TILE - 1) / TILE;
     const int64_t tile0 = (int64_t)chunk * p.tiles_per_chunk;
     const int64_t tile1 = (tile0 + p.tiles_per_chunk < ntiles) ? tile0 + p.tiles_per_chunk : ntiles;
     const int64_t row = (int64_t)b * p.D + d;
-    const bool vec = p.vec != 0;
+    const bool vec = p.vec != 0 && (toff % 8) == 0;
     const int mode = p.mode;
 
-    const IO *urow = reinterpret_cast<const IO *>(p.u) + b * p.u_sb + d * p.u_sd;
-    const IO *drow = reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd;
-    const IO *zrow = p.z ? reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd : nullptr;
-    IO *yrow = p.y ? reinterpret_cast<IO *>(p.y) + b * p.y_sb + d * p.y_sd : nullptr;
-    const IO *Bm = reinterpret_cast<const IO *>(p.Bm) + ((int64_t)b * p.bcg + grp) * L * N;
-    const IO *Cm = reinterpret_cast<const IO *>(p.Cm) + ((int64_t)b * p.bcg + grp) * L * N;
+    const IO *urow = reinterpret_cast<const IO *>(p.u) + bs * p.u_sb + d * p.u_sd + toff;
+    const IO *drow = reinterpret_cast<const IO *>(p.delta) + bs * p.dl_sb + d * p.dl_sd + toff;
+    const IO *zrow = p.z ? reinterpret_cast<const IO *>(p.z) + bs * p.z_sb + d * p.z_sd + toff : nullptr;
+    IO *yrow = p.y ? reinterpret_cast<IO *>(p.y) + bs * p.y_sb + d * p.y_sd + toff : nullptr;
+    const int64_t bc0 = ((bs * p.bcg + grp) * p.L + toff) * N;       // first element of the maps of this sequence
+    const IO *Bm = reinterpret_cast<const IO *>(p.Bm) + bc0;
+    const IO *Cm = reinterpret_cast<const IO *>(p.Cm) + bc0;
 
     // Per-state uniform values live one per lane (lane n holds state n) and are read with
     // v_readlane, so the loop over n stays rolled and nothing is indexed dynamically.
@@ -66,7 +76,9 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
     const float Av = (lane < N) ? p.A[d * N + lane] : 0.0f;
     const float Dsk = p.Dskip ? p.Dskip[d] : 0.0f;
     const float bias = p.bias ? p.bias[d] : 0.0f;
-    const int64_t nck = (L + kCkptInterval - 1) / kCkptInterval;
+    // checkpoints of this row: [B,D,nck,N], or packed [D,nslots,N] with sequence b starting at slot toff/interval + b
+    const int64_t ck0 = p.cu ? (int64_t)d * p.nslots + toff / kCkptInterval + b
+                             : row * ((L + kCkptInterval - 1) / kCkptInterval);
 
     for (int64_t tile = tile0; tile < tile1; ++tile) {
         const int64_t l0 = tile * TILE;
@@ -141,7 +153,7 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
             const float Sex = dpp<DPP_WAVE_SHR1>(0.0f, S);
             float x = __builtin_fmaf(Pex, xc, Sex);                  // state entering this lane's first step
             if constexpr (CKPT) {
-                if ((ll % kCkptInterval) == 0 && ll < L) p.ckpt[(row * nck + ll / kCkptInterval) * N + n] = x;
+                if ((ll % kCkptInterval) == 0 && ll < L) p.ckpt[(ck0 + ll / kCkptInterval) * N + n] = x;
             }
             if constexpr (!WANT_Y) {
                 const float xe = __builtin_fmaf(P, xc, S);           // state after this lane's last step

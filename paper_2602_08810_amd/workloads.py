@@ -70,6 +70,21 @@ def make_selective(B, D, N, L, io="f32", gate=False, bias=("const", -2.0), seed=
     return out
 
 
+def make_packed(D, N, lengths, io="f32", gate=True, seed=0, bc_groups=1, gap=0):
+    """A packed variable-length batch: sequences of the given lengths one after the other on one time axis
+    (`gap` unused steps before the first and after the last).  Same distributions as make_selective; returns the
+    [D,L] / [L,N] (or [G,L,N]) arrays, x0 [S,D,N] and cu_seqlens (int64 [S+1])."""
+    L = int(sum(lengths)) + 2 * gap
+    p = make_selective(B=1, D=D, N=N, L=L, io=io, gate=gate, bias=("uniform", -4.0, -2.0), seed=seed,
+                       bc_groups=bc_groups)
+    out = {k: (None if v is None else v[0]) for k, v in p.items() if k in ("u", "delta", "z", "dy", "Bm", "Cm")}
+    out.update(A=p["A"], Dskip=p["Dskip"], delta_bias=p["delta_bias"])
+    rng = np.random.Generator(np.random.PCG64(seed + 1000))
+    out["x0"] = rng.standard_normal((len(lengths), D, N), dtype=np.float32)
+    out["cu_seqlens"] = (gap + np.concatenate([[0], np.cumsum(lengths)])).astype(np.int64)
+    return out
+
+
 def make_lti(B, P, L, seed=1, with_x0=False, with_gx=False, **_unused):
     """Inputs of the LTI complex-diagonal scan.
 
