@@ -315,6 +315,28 @@ def _other_configs(api, torch, dev):
                                        "note": "per token, 64 step calls replayed from one HIP graph"}
     del graph
 
+    # packed variable-length batch of config 2's total size: 8 * 2048 steps as 24 sequences of mixed lengths
+    lens = [3000, 1500, 1000, 2048, 512, 512, 700, 324, 100, 100, 60, 40, 2200, 1800, 32, 8, 448, 900, 300, 300, 200, 100,
+            100, 100]
+    assert sum(lens) == 16384
+    Dp, Np, Lp = 1536, 16, 16384
+    tp = sel(1, Dp, Np, Lp, True)
+    cu = torch.tensor([0] + list(__import__("itertools").accumulate(lens)), dtype=torch.int64, device=dev)
+    pk = {k: (v[0] if k in ("u", "delta", "z", "Bm", "Cm") else v) for k, v in tp.items()}
+    dyp = torch.randn(Dp, Lp, device=dev, generator=g).to(bf)
+    yp = torch.empty_like(pk["u"])
+    ckp = torch.empty((Dp, Lp // api.lrnnx_ckpt_interval() + len(lens), Np), device=dev)
+    outs_p = {k: torch.empty_like(pk["u"]) for k in ("du", "ddelta", "dz")}
+    outs_p.update(dA=torch.empty((Dp, Np), device=dev), dBm=torch.empty((Lp, Np), device=dev),
+                  dCm=torch.empty((Lp, Np), device=dev), dD=torch.empty(Dp, device=dev), dbias=torch.empty(Dp, device=dev))
+    tf = _time(torch, lambda: api.lrnnx_selective_scan_fwd(**pk, cu_seqlens=cu, out=yp, ckpt_out=ckp), 10)
+    tb = _time(torch, lambda: api.lrnnx_selective_scan_bwd(**pk, dy=dyp, cu_seqlens=cu, ckpt=ckp, outs=outs_p), 10)
+    out["packed_24seq_D1536_L16384"] = {"fwd_us": tf * 1e6, "bwd_us": tb * 1e6,
+                                        "elements_per_s": 2 * Dp * Np * Lp / (tf + tb),
+                                        "note": "same total size as config 2; sequence starts are not 16-byte aligned, "
+                                                "so rows are read element by element"}
+    del tp, pk, dyp, yp, ckp, outs_p
+
     # config 3: long-sequence forward, both paths
     B3, D3, N3, L3 = 1, 2048, 16, 65536
     t3 = sel(B3, D3, N3, L3, False)

@@ -253,7 +253,7 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
             row_vec_ok(a->dy, p.dy_sb, p.dy_sd, es) && (!a->z || row_vec_ok(a->z, p.z_sb, p.z_sd, es)) &&
             row_vec_ok(a->du, p.du_sb, p.du_sd, es) && row_vec_ok(a->ddelta, p.dd_sb, p.dd_sd, es) &&
             (!a->dz || row_vec_ok(a->dz, p.dz_sb, p.dz_sd, es));
-    p.G = bwd_channels_per_group(a->B * bcg, a->D / bcg, a->N, a->L);
+    p.G = bwd_channels_per_group(a->B * bcg, a->D / bcg, a->N, a->L, cu == nullptr);
 
     // reduced outputs are accumulated with atomics: clear them on the stream first
     const int64_t nbc = (cu ? 1 : (int64_t)a->B) * bcg * a->L * a->N;   // packed mode: one time axis for all sequences

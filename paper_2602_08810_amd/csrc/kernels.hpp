@@ -109,6 +109,6 @@ hipError_t launch_fill(const FillList &z, hipStream_t s);
 
 // Tile geometry the host needs for grids, workspaces and the choice of path.
 int fwd_tile_steps(int io_dtype);            // time steps one workgroup covers per tile
-int bwd_channels_per_group(int B, int D, int N, int64_t L);
+int bwd_channels_per_group(int B, int D, int N, int64_t L, bool balanced);
 
 }  // namespace lrnnx

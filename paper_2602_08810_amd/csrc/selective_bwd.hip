@@ -372,9 +372,11 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
 
 #ifndef LRNNX_KERNEL_ONLY
 // ---------------------------------------------------------------- launchers
-// channels per workgroup: D here is the number of channels that share one pair of Bm/Cm maps
-int bwd_channels_per_group(int B, int D, int, int64_t) {
-    int64_t G = ((int64_t)B * D) / 512;               // aim at >= 512 workgroups (two per CU)
+// channels per workgroup: D here is the number of channels that share one pair of Bm/Cm maps.  `balanced` says
+// that all batch entries have the same length; otherwise (packed variable-length batches) four times as many,
+// smaller, workgroups let the dispatcher even out sequences of different lengths.
+int bwd_channels_per_group(int B, int D, int, int64_t, bool balanced) {
+    int64_t G = ((int64_t)B * D) / (balanced ? 512 : 2048);   // aim at >= 512 workgroups (two per CU)
     if (G < 8) G = 8;
     if (G > kMaxG) G = kMaxG;
     if (G > D) G = D;
