@@ -175,7 +175,7 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *args);
  * lambda[P], v and x [B,L,P] (P contiguous), x0 and x_last [B,P] (optional, NULL
  * allowed).  x may alias v.  workspace: lrnnx_workspace_bytes(LRNNX_WS_LTI, B, P, 0, L, 0); its contents on entry
  * do not matter (the library clears what it uses on the stream).  The single-launch path chains workgroups
- * through flags in global memory with bounded waits; should a wait ever run out, the states from that point of
+ * through values published in global memory, with bounded waits; should a wait ever run out, the states from that point of
  * that sequence on are written as NaN rather than left plausible.                     */
 typedef struct lrnnx_lti_args {
     size_t struct_size;

@@ -83,7 +83,7 @@ __global__ __launch_bounds__(kLtiThreads) void k_lti_chunk(const LtiParams p) {
 // its end-state-from-zero T_g as soon as it has it, then rebuilds its carry-in from the T_j of the groups
 // before it, back to the last "anchor" group, whose true end state X it takes.  Every T_g is available
 // after one load phase, so only anchors wait on a chain (one hop per 16 groups).  A published value is its own
-// ready flag (see publish() below), so a hop costs one store and one load round trip and needs no fence.
+// ready flag (see publish() in chain.hpp), so a hop costs one store and one load round trip and needs no fence.
 // Workgroups are ordered so that a group is dispatched after the groups it looks back on (blockIdx.y = group),
 // and every wait is bounded: after kSpinLimit polls a wavefront gives up, raises *err and finishes with a NaN
 // carry rather than hang.
