@@ -4,11 +4,12 @@
 // v and x are [B,L,P] with P contiguous, so the lanes run along P (coalesced 8-byte
 // complex elements) and the time axis is cut into chunks that different workgroups take.
 // Because lambda is constant the affine aggregate of a chunk is (lambda^len, end state
-// from zero): only end states are stored.  Two launches.  The first scans every chunk from zero
-// and, inside each workgroup (4 consecutive chunks), chains the end states through LDS.  The
-// second rebuilds each chunk's true carry-in from the end states of the groups before it and its in-group
-// prefix, rescans the chunk and writes x (the second read of v is served by the L2 / Infinity
-// Cache at these sizes, so v comes from HBM once and x is written once).
+// from zero): only end states are stored.  Two forms.  The default is the single-launch chained scan
+// further down (k_lti_onepass, also used for the adjoint).  The other takes two launches and no
+// inter-workgroup waiting: the first scans every chunk from zero and, inside each workgroup (4 consecutive
+// chunks), chains the end states through LDS; the second rebuilds each chunk's true carry-in from the end
+// states of the groups before it and its in-group prefix, rescans the chunk and writes x (the second read
+// of v is served by the L2 / Infinity Cache at these sizes).
 #include "kernels.hpp"
 #include "chain.hpp"
 
