@@ -118,21 +118,19 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
             yv[t] = Dsk * uv[t];
         }
 
-        // One state: fold the lane's T steps, wavefront prefix, replay.  (Bc,Cc) hold this state's Bm/Cm
-        // for the lane; (Bn,Cn) receive the next state's while this one computes (ping-pong, no copies).
-        auto one_state = [&](int n, const float4 (&Bc)[TQ], const float4 (&Cc)[TQ], float4 (&Bn)[TQ], float4 (&Cn)[TQ]) {
+        // One state: fold the lane's T steps, wavefront prefix, replay.  Bc holds this state's Bm for the lane; Bn
+        // receives the next state's while this one computes (ping-pong, no copies).  Cm is only needed by the
+        // replay, so it is read from LDS after the fold and its latency hides behind the prefix.
+        auto one_state = [&](int n, const float4 (&Bc)[TQ], float4 (&Bn)[TQ]) {
             if (n + 1 < N) {
 #pragma unroll
-                for (int q = 0; q < TQ; ++q) {
+                for (int q = 0; q < TQ; ++q)
                     Bn[q] = *reinterpret_cast<const float4 *>(&sB[(n + 1) * PLANE + q * QS + lane * 4]);
-                    Cn[q] = *reinterpret_cast<const float4 *>(&sC[(n + 1) * PLANE + q * QS + lane * 4]);
-                }
             }
-            float Bv[T], Cv[T], a[T], bb[T];
+            float Bv[T], a[T], bb[T];
 #pragma unroll
             for (int q = 0; q < TQ; ++q) {
                 Bv[4 * q] = Bc[q].x; Bv[4 * q + 1] = Bc[q].y; Bv[4 * q + 2] = Bc[q].z; Bv[4 * q + 3] = Bc[q].w;
-                Cv[4 * q] = Cc[q].x; Cv[4 * q + 1] = Cc[q].y; Cv[4 * q + 2] = Cc[q].z; Cv[4 * q + 3] = Cc[q].w;
             }
             const ACoef ac = make_acoef<DISC>(readlane(Av, n));
             const float xc = readlane(xcv, n);
@@ -144,8 +142,14 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
                 if constexpr (DISC == DISC_ZOH_S6) bb[t] = du[t] * Bv[t];
                 else if constexpr (DISC == DISC_DIRAC) bb[t] = uv[t] * Bv[t];
                 else bb[t] = g * uv[t] * Bv[t];
-                S = __builtin_fmaf(a[t], S, bb[t]);
+                S = (t == 0) ? bb[0] : __builtin_fmaf(a[t], S, bb[t]);   // the fold starts from zero
                 if constexpr (DISC == DISC_BILINEAR) P *= a[t];
+            }
+            float4 Cc[TQ];
+            if constexpr (WANT_Y) {
+#pragma unroll
+                for (int q = 0; q < TQ; ++q)
+                    Cc[q] = *reinterpret_cast<const float4 *>(&sC[n * PLANE + q * QS + lane * 4]);
             }
             if constexpr (DISC != DISC_BILINEAR) P = exp2_fast(sum_dl * ac.A2);   // product of the T multipliers
             wave_scan_fwd(P, S);
@@ -160,6 +164,11 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
                 xcv = writelane(xcv, readlane(xe, 63), n);
                 pcv = writelane(pcv, readlane(pcv, n) * readlane(P, 63), n);
             } else {
+                float Cv[T];
+#pragma unroll
+                for (int q = 0; q < TQ; ++q) {
+                    Cv[4 * q] = Cc[q].x; Cv[4 * q + 1] = Cc[q].y; Cv[4 * q + 2] = Cc[q].z; Cv[4 * q + 3] = Cc[q].w;
+                }
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
                     x = __builtin_fmaf(a[t], x, bb[t]);
@@ -168,16 +177,13 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
                 xcv = writelane(xcv, readlane(x, 63), n);            // lane 63 ends on the tile's last step
             }
         };
-        float4 Bq0[TQ], Cq0[TQ], Bq1[TQ], Cq1[TQ];
+        float4 Bq0[TQ], Bq1[TQ];
 #pragma unroll
-        for (int q = 0; q < TQ; ++q) {
-            Bq0[q] = *reinterpret_cast<const float4 *>(&sB[q * QS + lane * 4]);
-            Cq0[q] = *reinterpret_cast<const float4 *>(&sC[q * QS + lane * 4]);
-        }
+        for (int q = 0; q < TQ; ++q) Bq0[q] = *reinterpret_cast<const float4 *>(&sB[q * QS + lane * 4]);
 #pragma unroll 1
         for (int n = 0; n < N; n += 2) {
-            one_state(n, Bq0, Cq0, Bq1, Cq1);
-            if (n + 1 < N) one_state(n + 1, Bq1, Cq1, Bq0, Cq0);
+            one_state(n, Bq0, Bq1);
+            if (n + 1 < N) one_state(n + 1, Bq1, Bq0);
         }
 
         if constexpr (WANT_Y) {
