@@ -33,9 +33,12 @@ constexpr int DPP_WAVE_SHL1 = 0x130, DPP_WAVE_SHR1 = 0x138;
 constexpr int DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
 
 __device__ __forceinline__ float readlane(float x, int lane) { return i2f(__builtin_amdgcn_readlane(f2i(x), lane)); }
-// copy of `old` with lane `lane` replaced by the (wave-uniform) value v
+// copy of `old` with lane `lane` replaced by the wave-uniform value v: one v_writelane_b32.  This compiler has no
+// builtin for it, so the LLVM intrinsic is declared by its name (the compiler still sees an ordinary instruction
+// and handles its hazards).
+extern "C" __device__ int lrnnx_llvm_writelane_i32(int value, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
 __device__ __forceinline__ float writelane(float old, float v, int lane) {
-    return ((int)(threadIdx.x & 63) == lane) ? v : old;
+    return i2f(lrnnx_llvm_writelane_i32(f2i(v), lane, f2i(old)));
 }
 __device__ __forceinline__ float bpermute(int src_lane, float x) { return i2f(__builtin_amdgcn_ds_bpermute(src_lane << 2, f2i(x))); }
 

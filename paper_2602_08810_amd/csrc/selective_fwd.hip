@@ -152,16 +152,14 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
                     Cc[q] = *reinterpret_cast<const float4 *>(&sC[n * PLANE + q * QS + lane * 4]);
             }
             if constexpr (DISC != DISC_BILINEAR) P = exp2_fast(sum_dl * ac.A2);   // product of the T multipliers
+            if (lane == 0) S = __builtin_fmaf(P, xc, S);             // the carried state enters through lane 0
             wave_scan_fwd(P, S);
-            const float Pex = dpp<DPP_WAVE_SHR1>(1.0f, P);
-            const float Sex = dpp<DPP_WAVE_SHR1>(0.0f, S);
-            float x = __builtin_fmaf(Pex, xc, Sex);                  // state entering this lane's first step
+            float x = dpp<DPP_WAVE_SHR1>(xc, S);                     // state entering this lane's first step
             if constexpr (CKPT) {
                 if ((ll % kCkptInterval) == 0 && ll < L) p.ckpt[(ck0 + ll / kCkptInterval) * N + n] = x;
             }
             if constexpr (!WANT_Y) {
-                const float xe = __builtin_fmaf(P, xc, S);           // state after this lane's last step
-                xcv = writelane(xcv, readlane(xe, 63), n);
+                xcv = writelane(xcv, readlane(S, 63), n);            // inclusive prefix at lane 63 = state after the tile
                 pcv = writelane(pcv, readlane(pcv, n) * readlane(P, 63), n);
             } else {
                 float Cv[T];
