@@ -217,14 +217,13 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                     if constexpr (DISC == DISC_ZOH_S6) x[t] = dlu[t] * Bk[t];
                     else if constexpr (DISC == DISC_DIRAC) x[t] = dlu[t] * Bk[t];
                     else x[t] = gg[t] * dlu[t] * Bk[t];
-                    S = __builtin_fmaf(a[t], S, x[t]);
+                    S = (t == 0) ? x[0] : __builtin_fmaf(a[t], S, x[t]);     // the fold starts from zero
                     if constexpr (DISC == DISC_BILINEAR) P *= a[t];
                 }
                 if constexpr (DISC != DISC_BILINEAR) P = exp2_fast(sum_dl * ac.A2);
+                if (lane == 0) S = __builtin_fmaf(P, xck, S);               // the checkpointed state enters through lane 0
                 wave_scan_fwd(P, S);
-                const float Pex = dpp<DPP_WAVE_SHR1>(1.0f, P);
-                const float Sex = dpp<DPP_WAVE_SHR1>(0.0f, S);
-                const float xin = __builtin_fmaf(Pex, xck, Sex);            // x entering this lane's first step
+                const float xin = dpp<DPP_WAVE_SHR1>(xck, S);               // x entering this lane's first step
                 {
                     float xp = xin;
 #pragma unroll
@@ -237,15 +236,14 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 float Pr = 1.0f, Sr = 0.0f;
 #pragma unroll
                 for (int t = T - 1; t >= 0; --t) {
-                    Sr = __builtin_fmaf(a[t + 1], Sr, Cv[k][t] * dyp[t]);
+                    Sr = (t == T - 1) ? Cv[k][t] * dyp[t] : __builtin_fmaf(a[t + 1], Sr, Cv[k][t] * dyp[t]);
                     if constexpr (DISC == DISC_BILINEAR) Pr *= a[t + 1];
                 }
                 if constexpr (DISC != DISC_BILINEAR) Pr = exp2_fast(sum_shift * ac.A2);
+                if (lane == 63) Sr = __builtin_fmaf(Pr, hc, Sr);            // the carried adjoint enters through lane 63
                 wave_scan_rev(Pr, Sr, lane);
-                const float Pn = dpp<DPP_WAVE_SHL1>(1.0f, Pr);
-                const float Sn = dpp<DPP_WAVE_SHL1>(0.0f, Sr);
-                float R = __builtin_fmaf(Pn, hc, Sn);                       // H of the next lane's first step (the carry itself past lane 63)
-                const float H0 = __builtin_fmaf(Pr, hc, Sr);               // H of this lane's first step
+                const float H0 = Sr;                                        // H of this lane's first step
+                float R = dpp<DPP_WAVE_SHL1>(hc, Sr);                       // H of the next lane's first step (the carry itself past lane 63)
                 const float hc_new = readlane(a[0] * H0, 0);
                 if (lane == 0) sH[g * N + n] = hc_new;
 
