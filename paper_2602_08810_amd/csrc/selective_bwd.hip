@@ -48,7 +48,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     __shared__ __attribute__((aligned(16))) float sPart[W * 3 * TILE];    // per wave: ypre, du, ddelta partials
     __shared__ __attribute__((aligned(16))) float sBt[N * TILE];          // Bm columns of the tile, fp32: [n][q][lane][4], wave-private slices
     __shared__ float sH[kMaxG * N];       // a_{l0} H_{l0} carried to the earlier tile, per (channel, n)
-    __shared__ float sdA[kMaxG * N];
+    __shared__ float sdA[2][kMaxG * N];   // per half-wavefront partial sums of dA (added up when they are flushed)
     __shared__ float sdD[W * kMaxG];
     __shared__ float sdb[W * kMaxG];
 
@@ -80,7 +80,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     const bool vec = p.vec != 0 && (toff % 8) == 0;
     const bool has_z = p.z != nullptr;
 
-    for (int i = tid; i < kMaxG * N; i += NT) { sH[i] = 0.0f; sdA[i] = 0.0f; }
+    for (int i = tid; i < kMaxG * N; i += NT) { sH[i] = 0.0f; sdA[0][i] = 0.0f; sdA[1][i] = 0.0f; }
     for (int i = tid; i < W * kMaxG; i += NT) { sdD[i] = 0.0f; sdb[i] = 0.0f; }
 
     const int64_t bc0 = ((p.cu ? (int64_t)grp : (int64_t)bcrow) * p.L + toff) * N;   // first element of the maps of this sequence
@@ -195,6 +195,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
             const float dl_next0 = dpp<DPP_WAVE_SHL1>(0.0f, dl[0]);        // first Delta of the next lane (0 past lane 63)
             const float sum_shift = sum_dl - dl[0] + dl_next0;
 
+            float dA4[NK];
 #pragma unroll
             for (int k = 0; k < NK; ++k) {
                 const int n = w * NK + k;
@@ -247,7 +248,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 const float hc_new = readlane(a[0] * H0, 0);
                 if (lane == 0) sH[g * N + n] = hc_new;
 
-                float dA_part = 0.0f;
+                float dA_part = 0.0f;                                       // this lane's share of dA[d, n]
 #pragma unroll
                 for (int t = T - 1; t >= 0; --t) {
                     R = __builtin_fmaf(a[t + 1], R, Cv[k][t] * dyp[t]);       // H_t (the product is recomputed: registers are scarcer than VALU slots here)
@@ -272,9 +273,28 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                         dA_part = __builtin_fmaf(da, a_A, __builtin_fmaf(dg, g_A, dA_part));
                     }
                 }
-                const float dA_tot = wave_sum(dA_part);
-                if (lane == 0) sdA[g * N + n] += dA_tot;
-
+                if constexpr (NK == 4) {
+                    dA4[k] = dA_part;
+                } else {
+                    const float dA_tot = wave_sum(dA_part);
+                    if (lane == 0) sdA[0][g * N + n] += dA_tot;
+                }
+            }
+            if constexpr (NK == 4) {
+                // The four per-lane partial sums are reduced together: two exchange steps leave each lane of a quad
+                // with the quad's sum of ONE state (lane%4 = 0,1,2,3 -> state 0,2,1,3), two rotations sum the quads of
+                // a row, one swizzle sums the two rows of a half-wavefront; lanes 0-3 and 32-35 own the results.
+                const bool b0 = lane & 1, b1 = lane & 2;
+                float kA = b0 ? dA4[2] : dA4[0], kB = b0 ? dA4[3] : dA4[1];
+                const float sA = b0 ? dA4[0] : dA4[2], sB = b0 ? dA4[1] : dA4[3];
+                kA += dpp<0xB1>(0.0f, sA);                                  // quad_perm [1,0,3,2]
+                kB += dpp<0xB1>(0.0f, sB);
+                float v = b1 ? kB : kA;
+                v += dpp<0x4E>(0.0f, b1 ? kA : kB);                         // quad_perm [2,3,0,1]
+                v += dpp<0x124>(0.0f, v);                                   // row_ror:4
+                v += dpp<0x128>(0.0f, v);                                   // row_ror:8
+                v += i2f(__builtin_amdgcn_ds_swizzle(f2i(v), 0x401F));      // lane ^ 16
+                if ((lane & 0x1C) == 0) sdA[lane >> 5][g * N + w * NK + ((lane & 1) << 1) + ((lane >> 1) & 1)] += v;
             }
             if constexpr (DISC == DISC_ZOH_S6) {     // dDelta += u sum_n H B ;  du = Delta sum_n H B
 #pragma unroll
@@ -355,7 +375,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     // ---- per-channel results of this workgroup
     for (int i = tid; i < Gact * N; i += NT) {
         const int g = i / N, n = i % N;
-        unsafeAtomicAdd(p.dA + (int64_t)(d0 + g) * N + n, sdA[g * N + n]);
+        unsafeAtomicAdd(p.dA + (int64_t)(d0 + g) * N + n, sdA[0][g * N + n] + sdA[1][g * N + n]);
         if (p.dx0) p.dx0[((int64_t)b * p.D + d0 + g) * N + n] = sH[g * N + n];
     }
     for (int g = tid; g < Gact; g += NT) {
