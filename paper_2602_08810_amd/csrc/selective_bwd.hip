@@ -49,8 +49,8 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     __shared__ __attribute__((aligned(16))) float sBt[N * TILE];          // Bm columns of the tile, fp32: [n][q][lane][4], wave-private slices
     __shared__ float sH[kMaxG * N];       // a_{l0} H_{l0} carried to the earlier tile, per (channel, n)
     __shared__ float sdA[2][kMaxG * N];   // per half-wavefront partial sums of dA (added up when they are flushed)
-    __shared__ float sdD[W * kMaxG];
-    __shared__ float sdb[W * kMaxG];
+    __shared__ float sdD[2 * W * kMaxG];  // dD and dbias partial sums per (half-wavefront, wavefront, channel)
+    __shared__ float sdb[2 * W * kMaxG];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -81,7 +81,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     const bool has_z = p.z != nullptr;
 
     for (int i = tid; i < kMaxG * N; i += NT) { sH[i] = 0.0f; sdA[0][i] = 0.0f; sdA[1][i] = 0.0f; }
-    for (int i = tid; i < W * kMaxG; i += NT) { sdD[i] = 0.0f; sdb[i] = 0.0f; }
+    for (int i = tid; i < 2 * W * kMaxG; i += NT) { sdD[i] = 0.0f; sdb[i] = 0.0f; }
 
     const int64_t bc0 = ((p.cu ? (int64_t)grp : (int64_t)bcrow) * p.L + toff) * N;   // first element of the maps of this sequence
     const IO *Bm = reinterpret_cast<const IO *>(p.Bm) + bc0;
@@ -245,8 +245,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 wave_scan_rev(Pr, Sr, lane);
                 const float H0 = Sr;                                        // H of this lane's first step
                 float R = dpp<DPP_WAVE_SHL1>(hc, Sr);                       // H of the next lane's first step (the carry itself past lane 63)
-                const float hc_new = readlane(a[0] * H0, 0);
-                if (lane == 0) sH[g * N + n] = hc_new;
+                if (lane == 0) sH[g * N + n] = a[0] * H0;                   // carried to the earlier tile
 
                 float dA_part = 0.0f;                                       // this lane's share of dA[d, n]
 #pragma unroll
@@ -340,8 +339,16 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 store_few<IO, TPW>(reinterpret_cast<IO *>(p.du) + bs * p.du_sb + d * p.du_sd + toff + l0, f0, rem, vec, o_du);
                 store_few<IO, TPW>(reinterpret_cast<IO *>(p.ddelta) + bs * p.dd_sb + d * p.dd_sd + toff + l0, f0, rem, vec, o_dd);
                 if (p.dz) store_few<IO, TPW>(reinterpret_cast<IO *>(p.dz) + bs * p.dz_sb + d * p.dz_sd + toff + l0, f0, rem, vec, o_dz);
-                const float dD_tot = wave_sum(dD_part), db_tot = wave_sum(db_part);
-                if (lane == 0) { sdD[w * kMaxG + g] += dD_tot; sdb[w * kMaxG + g] += db_tot; }
+                // joint reduction of the two per-lane sums: one exchange leaves even lanes with dD and odd lanes with
+                // dbias pair sums, then lanes of equal parity are summed over the half-wavefront (lanes 0,1 / 32,33)
+                const bool odd = lane & 1;
+                float v = odd ? db_part : dD_part;
+                v += dpp<0xB1>(0.0f, odd ? dD_part : db_part);             // quad_perm [1,0,3,2]
+                v += dpp<0x4E>(0.0f, v);                                    // quad_perm [2,3,0,1]
+                v += dpp<0x124>(0.0f, v);                                   // row_ror:4
+                v += dpp<0x128>(0.0f, v);                                   // row_ror:8
+                v += i2f(__builtin_amdgcn_ds_swizzle(f2i(v), 0x401F));      // lane ^ 16
+                if ((lane & 0x1E) == 0) (odd ? sdb : sdD)[((lane >> 5) * W + w) * kMaxG + g] += v;
             }
         }
 
@@ -381,7 +388,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     for (int g = tid; g < Gact; g += NT) {
         float sD = 0.0f, sb = 0.0f;
 #pragma unroll
-        for (int ww = 0; ww < W; ++ww) { sD += sdD[ww * kMaxG + g]; sb += sdb[ww * kMaxG + g]; }
+        for (int ww = 0; ww < 2 * W; ++ww) { sD += sdD[ww * kMaxG + g]; sb += sdb[ww * kMaxG + g]; }
         if (p.dD) unsafeAtomicAdd(p.dD + d0 + g, sD);
         if (p.dbias) unsafeAtomicAdd(p.dbias + d0 + g, sb);
     }
