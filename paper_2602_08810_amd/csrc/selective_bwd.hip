@@ -152,9 +152,10 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
             for (int k = 0; k < NK; ++k) { cA[k] = pA[k]; cck[k] = pck[k]; }
 
             // ---- prologue: each thread prepares TPW flat steps for everybody
-            float e_sg[TPW], e_dy[TPW], e_z[TPW], e_sz[TPW];
+            // kept for the epilogue: d softplus / ds, and the factor that turns ypre into dz
+            float e_sg[TPW], e_zf[TPW];
             {
-                float e_u[TPW], r_d[TPW];
+                float e_u[TPW], r_d[TPW], e_dy[TPW], e_z[TPW];
                 unpack_few<IO, TPW>(r_u, e_u);
                 unpack_few<IO, TPW>(r_dl, r_d);
                 unpack_few<IO, TPW>(r_dy, e_dy);
@@ -164,8 +165,12 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                     float s = r_d[i] + bias, sp, sg, dyp;
                     if (p.softplus) softplus_sigmoid(s, sp, sg); else { sp = s; sg = 1.0f; }
                     e_sg[i] = sg;
-                    if (has_z) { e_sz[i] = sigmoid_fast(e_z[i]); dyp = e_dy[i] * e_z[i] * e_sz[i]; }
-                    else { e_z[i] = 0.0f; e_sz[i] = 0.0f; dyp = e_dy[i]; }
+                    if (has_z) {                                 // y = ypre z sig(z): dz = dy ypre sig (1 + z (1 - sig))
+                        const float sz = sigmoid_fast(e_z[i]);
+                        const float dsz = e_dy[i] * sz;
+                        dyp = dsz * e_z[i];
+                        e_zf[i] = dsz * __builtin_fmaf(e_z[i], 1.0f - sz, 1.0f);
+                    } else { e_zf[i] = 0.0f; dyp = e_dy[i]; }
                     sIn[0 * TILE + fslot(f0 + i)] = (f0 + i < rem) ? sp : 0.0f;
                     sIn[1 * TILE + fslot(f0 + i)] = e_u[i];
                     sIn[2 * TILE + fslot(f0 + i)] = dyp;
@@ -332,7 +337,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                     }
                     o_du[i] = __builtin_fmaf(e_dyp, Dsk, s_du);
                     o_dd[i] = s_dd * e_sg[i];
-                    o_dz[i] = e_dy[i] * yp * e_sz[i] * (1.0f + e_z[i] * (1.0f - e_sz[i]));
+                    o_dz[i] = yp * e_zf[i];
                     dD_part = __builtin_fmaf(e_dyp, e_u, dD_part);
                     db_part += (f0 + i < rem) ? o_dd[i] : 0.0f;
                 }
