@@ -277,7 +277,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                         dA_part = __builtin_fmaf(da, a_A, __builtin_fmaf(dg, g_A, dA_part));
                     }
                 }
-                if constexpr (NK == 4) {
+                if constexpr (NK == 4 || NK == 2) {
                     dA4[k] = dA_part;
                 } else {
                     const float dA_tot = wave_sum(dA_part);
@@ -299,6 +299,16 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 v += dpp<0x128>(0.0f, v);                                   // row_ror:8
                 v += i2f(__builtin_amdgcn_ds_swizzle(f2i(v), 0x401F));      // lane ^ 16
                 if ((lane & 0x1C) == 0) sdA[lane >> 5][g * N + w * NK + ((lane & 1) << 1) + ((lane >> 1) & 1)] += v;
+            } else if constexpr (NK == 2) {
+                // the same with two partial sums: even lanes end up with state 0, odd lanes with state 1
+                const bool odd = lane & 1;
+                float v = odd ? dA4[1] : dA4[0];
+                v += dpp<0xB1>(0.0f, odd ? dA4[0] : dA4[1]);               // quad_perm [1,0,3,2]
+                v += dpp<0x4E>(0.0f, v);                                    // quad_perm [2,3,0,1]
+                v += dpp<0x124>(0.0f, v);                                   // row_ror:4
+                v += dpp<0x128>(0.0f, v);                                   // row_ror:8
+                v += i2f(__builtin_amdgcn_ds_swizzle(f2i(v), 0x401F));      // lane ^ 16
+                if ((lane & 0x1E) == 0) sdA[lane >> 5][g * N + w * NK + (lane & 1)] += v;
             }
             if constexpr (DISC == DISC_ZOH_S6) {     // dDelta += u sum_n H B ;  du = Delta sum_n H B
 #pragma unroll
