@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the MI355X diagonal linear-recurrence scan (one GPU).
 
-A step is one forward + one backward selective scan on BASELINE config 2 (Mamba-block
+A step is one forward + one backward selective scan on benchmark configuration 2 (Mamba-block
 shape: B=8, D=1536, N=16, L=2048, bf16 I/O, fp32 state, SiLU gate), inputs resident in
 HBM.  The metric is scan elements/s, elements = B*L*D*N per pass (2 passes per step).
 The same run also times the other single-kernel workloads (config 1 LTI scan, config 3
@@ -62,7 +62,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(rows (b,d) are independent, see DESIGN.md for how the path would shard)", file=sys.stderr)
+              "(rows (b,d) are independent recurrences: a multi-GPU job would shard B or D and all-reduce the shared gradients)", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -14,7 +14,7 @@ from __future__ import annotations
 
 import numpy as np
 
-# name -> description of BASELINE configs 0..4
+# name -> description of the benchmark configurations 0..4
 CONFIGS = {
     "c0": dict(kind="selective", B=1, D=16, N=4, L=256, io="f32", gate=False,
                bias=("const", -2.0), seed=0),
@@ -135,7 +135,7 @@ def make_diag(B, P, L, cplx=False, seed=1, with_x0=False, **_unused):
 
 
 def make(name: str, **overrides):
-    """Inputs of BASELINE configuration ``name`` ("c0".."c4"), optionally with fields overridden."""
+    """Inputs of benchmark configuration ``name`` ("c0".."c4"), optionally with fields overridden."""
     cfg = dict(CONFIGS[name])
     cfg.update(overrides)
     return (make_lti if cfg["kind"] == "lti" else make_selective)(**cfg), cfg

@@ -1,7 +1,7 @@
 """Shared helpers of the GPU parity tests: upload of seeded inputs, the error metric, tolerances."""
 import numpy as np
 
-# BASELINE tolerances: max|gpu - oracle| / max|oracle| per output tensor
+# tolerances of the benchmark definition: max|gpu - oracle| / max|oracle| per output tensor
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 

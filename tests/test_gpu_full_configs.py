@@ -1,4 +1,4 @@
-"""GPU parity at the FULL sizes of BASELINE configs 1-4, in the launch configuration bench.py times.
+"""GPU parity at the FULL sizes of the benchmark configurations 1-4, in the launch configuration bench.py times.
 
 Config 1 and config 2 are small enough for the oracle to compute every output.  Configs 3 and 4 are checked on
 sampled rows the oracle computes one by one (rows (b,d) are independent recurrences), on windows where the

@@ -32,7 +32,7 @@ def _run(api, oracle, B, P, L, with_x0, seed, inplace=False, path="auto"):
 
 @pytest.mark.parametrize("path", ["single_pass", "chunk_carry"])
 def test_config1(api, oracle, path):
-    """BASELINE config 1: B=4, P=256, L=4096, complex64; one-launch look-back path and two-launch path."""
+    """Benchmark configuration 1: B=4, P=256, L=4096, complex64; one-launch look-back path and two-launch path."""
     _run(api, oracle, 4, 256, 4096, False, 1, path=path)
 
 

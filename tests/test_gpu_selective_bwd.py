@@ -48,7 +48,7 @@ def _check(api, oracle, io, disc, softplus, use_fwd_ckpt, **shape):
 
 
 def test_config0_shape_fp32(api, oracle):
-    """BASELINE config 0 shape (B=1, D=16, N=4, L=256, fp32), gradients of every input."""
+    """Benchmark configuration 0 shape (B=1, D=16, N=4, L=256, fp32), gradients of every input."""
     _check(api, oracle, "f32", "zoh_s6", True, True, B=1, D=16, N=4, L=256, gate=False, seed=0, bias=("const", -2.0))
 
 

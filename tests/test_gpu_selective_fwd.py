@@ -43,7 +43,7 @@ def _run_case(api, oracle, io, disc, softplus, path="auto", check_ckpt=False, **
 
 
 def test_config0_fp32(api, oracle):
-    """BASELINE config 0: B=1, D=16, N=4, L=256, fp32, no gate, seed 0."""
+    """Benchmark configuration 0: B=1, D=16, N=4, L=256, fp32, no gate, seed 0."""
     p, cfg = workloads.make("c0")
     t = sel_inputs_dev(p, "f32")
     y = api.lrnnx_selective_scan_fwd(**t)
