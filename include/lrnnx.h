@@ -5,12 +5,16 @@
  *
  *     x_k = A(k) x_{k-1} + B(k) u_k,        y_k = C(k) x_k + D(k) u_k
  *
- * for a diagonal state matrix, in two forms:
+ * for a diagonal state matrix, in three forms:
  *   - time-varying, input-dependent ("selective", the S6 row of Table 1; Sec. 2.2.2),
- *     with the discretisation fused into the scan (Sec. 3: ZOH, bilinear, dirac; the
- *     asynchronous / event-driven scheme is served by delta_softplus = 0 with the
- *     caller's own per-step Delta) and with the output projection fused in;
- *   - time-invariant complex-diagonal (the S5 / LRU rows of Table 1; Sec. 2.2.1).
+ *     forward and backward, with the discretisation fused into the scan (Sec. 3: ZOH,
+ *     bilinear, dirac; the asynchronous / event-driven scheme is served by
+ *     delta_softplus = 0 with the caller's own per-step Delta) and with the output
+ *     projection fused in; also as a single-token update (the `step` method, Sec. 3);
+ *   - time-invariant complex-diagonal (the S5 / LRU rows of Table 1; Sec. 2.2.1),
+ *     forward, backward and single-token update;
+ *   - time-varying with the per-step coefficients a_k, b_k supplied by the caller, real or
+ *     complex (the time-varying S5-style and gated layers of Sec. 2.2.2).
  * The hidden state x[B,D,L,N] is never written to memory (Sec. 3, the stated
  * advantage of the fused kernels); the backward pass recomputes it.
  *
@@ -22,7 +26,8 @@
  *   - The return value is an lrnnx_status.  On any status other than LRNNX_OK nothing
  *     has been launched and no output has been touched.  No C++ exception crosses the
  *     ABI and the library never aborts.
- *   - `struct_size` must be set to sizeof(the struct); a smaller value is rejected.
+ *   - `struct_size` must be set to sizeof(the struct); a smaller value is rejected, except
+ *     where a struct has grown: fields appended later default as their comments say.
  *   - Tensors named [B,D,L] have the time axis contiguous (stride 1) and explicit
  *     batch / channel strides counted in ELEMENTS; a channel stride of 0 broadcasts
  *     one row over all channels (inputs only).  Tensors [B,L,N], [D,N], [D], [B,D,N]
