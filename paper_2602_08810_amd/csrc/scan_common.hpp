@@ -134,6 +134,16 @@ __device__ __forceinline__ void disc_partials(float dt, const ACoef &c, float a,
         "v_mul_f32_dpp %1, %1, %1 " CTRL                                              \
         : "+v"(S), "+v"(P))
 
+// The same step on two independent pairs at once.  Each pair's instructions give the other pair the wait states its
+// next DPP read needs, so only the first step of a sequence carries the s_nop; the two dependent chains also fill
+// each other's issue gaps.
+#define LRNNX_PAIR_STEP2(NOP, P, S, CTRL, Q, R, CTRL2)                                \
+    asm(NOP "v_fmac_f32_dpp %0, %0, %1 " CTRL "\n\t"                                  \
+            "v_mul_f32_dpp %1, %1, %1 " CTRL "\n\t"                                   \
+            "v_fmac_f32_dpp %2, %2, %3 " CTRL2 "\n\t"                                 \
+            "v_mul_f32_dpp %3, %3, %3 " CTRL2                                         \
+        : "+v"(S), "+v"(P), "+v"(R), "+v"(Q))
+
 // Inclusive prefix over the 64 lanes, lane 0 first:  (P,S)_i <- (P,S)_i o ... o (P,S)_0.
 __device__ __forceinline__ void wave_scan_fwd(float &P, float &S) {
     LRNNX_PAIR_STEP(P, S, "row_shr:1 row_mask:0xf bank_mask:0xf");
@@ -163,6 +173,31 @@ __device__ __forceinline__ void wave_scan_rev(float &P, float &S, int lane) {
         const bool take = lane < 32;
         Pp = take ? Pp : 1.0f; Sp = take ? Sp : 0.0f;
         S = __builtin_fmaf(P, Sp, S); P = P * Pp;
+    }
+}
+
+// Both scans of the backward pass at once: inclusive prefix of (P,S) and inclusive suffix of (Pr,Sr).  The four
+// in-row steps are interleaved pairwise; the suffix's hand-over between rows (two lane permutes) overlaps the
+// prefix's two broadcast steps.
+__device__ __forceinline__ void wave_scan_fwd_rev(float &P, float &S, float &Pr, float &Sr, int lane) {
+    LRNNX_PAIR_STEP2("s_nop 1\n\t", P, S, "row_shr:1 row_mask:0xf bank_mask:0xf", Pr, Sr, "row_shl:1 row_mask:0xf bank_mask:0xf");
+    LRNNX_PAIR_STEP2("", P, S, "row_shr:2 row_mask:0xf bank_mask:0xf", Pr, Sr, "row_shl:2 row_mask:0xf bank_mask:0xf");
+    LRNNX_PAIR_STEP2("", P, S, "row_shr:4 row_mask:0xf bank_mask:0xf", Pr, Sr, "row_shl:4 row_mask:0xf bank_mask:0xf");
+    LRNNX_PAIR_STEP2("", P, S, "row_shr:8 row_mask:0xf bank_mask:0xf", Pr, Sr, "row_shl:8 row_mask:0xf bank_mask:0xf");
+    const int src = ((lane & 0x30) + 16) & 63;                          // first lane of the next row
+    float Pp = bpermute(src, Pr), Sp = bpermute(src, Sr);
+    LRNNX_PAIR_STEP(P, S, "row_bcast:15 row_mask:0xa bank_mask:0xf");   // lane 15 of rows 0,2 -> rows 1,3
+    LRNNX_PAIR_STEP(P, S, "row_bcast:31 row_mask:0xc bank_mask:0xf");   // lane 31 -> rows 2,3
+    {   // rows 0 and 2 take the suffix held by the first lane of the next row
+        const bool take = ((lane >> 4) & 1) == 0;
+        Pp = take ? Pp : 1.0f; Sp = take ? Sp : 0.0f;
+        Sr = __builtin_fmaf(Pr, Sp, Sr); Pr = Pr * Pp;
+    }
+    {   // rows 0 and 1 take the suffix held by lane 32
+        float Pq = bpermute(32, Pr), Sq = bpermute(32, Sr);
+        const bool take = lane < 32;
+        Pq = take ? Pq : 1.0f; Sq = take ? Sq : 0.0f;
+        Sr = __builtin_fmaf(Pr, Sq, Sr); Pr = Pr * Pq;
     }
 }
 

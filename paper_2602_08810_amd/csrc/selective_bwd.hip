@@ -228,15 +228,8 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 }
                 if constexpr (DISC != DISC_BILINEAR) P = exp2_fast(sum_dl * ac.A2);
                 if (lane == 0) S = __builtin_fmaf(P, xck, S);               // the checkpointed state enters through lane 0
-                wave_scan_fwd(P, S);
-                const float xin = dpp<DPP_WAVE_SHR1>(xck, S);               // x entering this lane's first step
-                {
-                    float xp = xin;
-#pragma unroll
-                    for (int t = 0; t < T; ++t) { xp = __builtin_fmaf(a[t], xp, x[t]); x[t] = xp; }
-                }
 
-                // reverse scan of H_l = c_l + a_{l+1} H_{l+1}; the multiplier of the tile's last step is 1
+                // lane aggregate of the adjoint H_l = c_l + a_{l+1} H_{l+1}; the multiplier of the tile's last step is 1
                 // because the carried value is already a_{l1} H_{l1}
                 a[T] = dpp<DPP_WAVE_SHL1>(1.0f, a[0]);
                 float Pr = 1.0f, Sr = 0.0f;
@@ -247,7 +240,15 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 }
                 if constexpr (DISC != DISC_BILINEAR) Pr = exp2_fast(sum_shift * ac.A2);
                 if (lane == 63) Sr = __builtin_fmaf(Pr, hc, Sr);            // the carried adjoint enters through lane 63
-                wave_scan_rev(Pr, Sr, lane);
+
+                // state prefix (forward in time) and adjoint suffix (backward in time) are independent: scanned together
+                wave_scan_fwd_rev(P, S, Pr, Sr, lane);
+                const float xin = dpp<DPP_WAVE_SHR1>(xck, S);               // x entering this lane's first step
+                {
+                    float xp = xin;
+#pragma unroll
+                    for (int t = 0; t < T; ++t) { xp = __builtin_fmaf(a[t], xp, x[t]); x[t] = xp; }
+                }
                 const float H0 = Sr;                                        // H of this lane's first step
                 float R = dpp<DPP_WAVE_SHL1>(hc, Sr);                       // H of the next lane's first step (the carry itself past lane 63)
                 if (lane == 0) sH[g * N + n] = a[0] * H0;                   // carried to the earlier tile
