@@ -154,6 +154,16 @@ __device__ __forceinline__ void wave_scan_fwd(float &P, float &S) {
     LRNNX_PAIR_STEP(P, S, "row_bcast:31 row_mask:0xc bank_mask:0xf");   // lane 31 -> rows 2,3
 }
 
+// Inclusive prefixes of two independent pairs at once (two states of one channel): see LRNNX_PAIR_STEP2.
+__device__ __forceinline__ void wave_scan_fwd2(float &P, float &S, float &Q, float &R) {
+    LRNNX_PAIR_STEP2("s_nop 1\n\t", P, S, "row_shr:1 row_mask:0xf bank_mask:0xf", Q, R, "row_shr:1 row_mask:0xf bank_mask:0xf");
+    LRNNX_PAIR_STEP2("", P, S, "row_shr:2 row_mask:0xf bank_mask:0xf", Q, R, "row_shr:2 row_mask:0xf bank_mask:0xf");
+    LRNNX_PAIR_STEP2("", P, S, "row_shr:4 row_mask:0xf bank_mask:0xf", Q, R, "row_shr:4 row_mask:0xf bank_mask:0xf");
+    LRNNX_PAIR_STEP2("", P, S, "row_shr:8 row_mask:0xf bank_mask:0xf", Q, R, "row_shr:8 row_mask:0xf bank_mask:0xf");
+    LRNNX_PAIR_STEP2("", P, S, "row_bcast:15 row_mask:0xa bank_mask:0xf", Q, R, "row_bcast:15 row_mask:0xa bank_mask:0xf");
+    LRNNX_PAIR_STEP2("", P, S, "row_bcast:31 row_mask:0xc bank_mask:0xf", Q, R, "row_bcast:31 row_mask:0xc bank_mask:0xf");
+}
+
 // Inclusive suffix over the 64 lanes, lane 63 first (time runs right to left):
 //   (P,S)_i <- (P,S)_i o (P,S)_{i+1} o ... o (P,S)_63.
 __device__ __forceinline__ void wave_scan_rev(float &P, float &S, int lane) {

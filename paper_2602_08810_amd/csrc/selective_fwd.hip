@@ -175,13 +175,86 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
                 xcv = writelane(xcv, readlane(x, 63), n);            // lane 63 ends on the tile's last step
             }
         };
-        float4 Bq0[TQ], Bq1[TQ];
+        // Two states at a time (every supported N > 1 is even): their folds and replays are independent chains and
+        // their prefix scans are interleaved step by step, which fills the issue gaps a single dependent chain leaves.
+        auto two_states = [&](int n) {
+            float4 B0[TQ], B1[TQ];
 #pragma unroll
-        for (int q = 0; q < TQ; ++q) Bq0[q] = *reinterpret_cast<const float4 *>(&sB[q * QS + lane * 4]);
+            for (int q = 0; q < TQ; ++q) {
+                B0[q] = *reinterpret_cast<const float4 *>(&sB[n * PLANE + q * QS + lane * 4]);
+                B1[q] = *reinterpret_cast<const float4 *>(&sB[(n + 1) * PLANE + q * QS + lane * 4]);
+            }
+            const ACoef ac0 = make_acoef<DISC>(readlane(Av, n)), ac1 = make_acoef<DISC>(readlane(Av, n + 1));
+            const float xc0 = readlane(xcv, n), xc1 = readlane(xcv, n + 1);
+            float a0[T], b0[T], a1[T], b1[T];
+            float P0 = 1.0f, S0 = 0.0f, P1 = 1.0f, S1 = 0.0f;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const float Bt0 = reinterpret_cast<const float *>(&B0[t / 4])[t % 4];
+                const float Bt1 = reinterpret_cast<const float *>(&B1[t / 4])[t % 4];
+                float g0, g1;
+                disc_ag<DISC>(dl[t], ac0, a0[t], g0);
+                disc_ag<DISC>(dl[t], ac1, a1[t], g1);
+                if constexpr (DISC == DISC_ZOH_S6) { b0[t] = du[t] * Bt0; b1[t] = du[t] * Bt1; }
+                else if constexpr (DISC == DISC_DIRAC) { b0[t] = uv[t] * Bt0; b1[t] = uv[t] * Bt1; }
+                else { b0[t] = g0 * uv[t] * Bt0; b1[t] = g1 * uv[t] * Bt1; }
+                S0 = (t == 0) ? b0[0] : __builtin_fmaf(a0[t], S0, b0[t]);   // the folds start from zero
+                S1 = (t == 0) ? b1[0] : __builtin_fmaf(a1[t], S1, b1[t]);
+                if constexpr (DISC == DISC_BILINEAR) { P0 *= a0[t]; P1 *= a1[t]; }
+            }
+            float4 C0[TQ], C1[TQ];
+            if constexpr (WANT_Y) {
+#pragma unroll
+                for (int q = 0; q < TQ; ++q) {
+                    C0[q] = *reinterpret_cast<const float4 *>(&sC[n * PLANE + q * QS + lane * 4]);
+                    C1[q] = *reinterpret_cast<const float4 *>(&sC[(n + 1) * PLANE + q * QS + lane * 4]);
+                }
+            }
+            if constexpr (DISC != DISC_BILINEAR) {                   // product of the T multipliers
+                P0 = exp2_fast(sum_dl * ac0.A2);
+                P1 = exp2_fast(sum_dl * ac1.A2);
+            }
+            if (lane == 0) {                                         // the carried states enter through lane 0
+                S0 = __builtin_fmaf(P0, xc0, S0);
+                S1 = __builtin_fmaf(P1, xc1, S1);
+            }
+            wave_scan_fwd2(P0, S0, P1, S1);
+            float x0 = dpp<DPP_WAVE_SHR1>(xc0, S0);                  // states entering this lane's first step
+            float x1 = dpp<DPP_WAVE_SHR1>(xc1, S1);
+            if constexpr (CKPT) {
+                if ((ll % kCkptInterval) == 0 && ll < L) {
+                    float *ck = p.ckpt + (ck0 + ll / kCkptInterval) * N + n;
+                    ck[0] = x0; ck[1] = x1;
+                }
+            }
+            if constexpr (!WANT_Y) {
+                xcv = writelane(xcv, readlane(S0, 63), n);           // inclusive prefix at lane 63 = state after the tile
+                xcv = writelane(xcv, readlane(S1, 63), n + 1);
+                pcv = writelane(pcv, readlane(pcv, n) * readlane(P0, 63), n);
+                pcv = writelane(pcv, readlane(pcv, n + 1) * readlane(P1, 63), n + 1);
+            } else {
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    const float Ct0 = reinterpret_cast<const float *>(&C0[t / 4])[t % 4];
+                    const float Ct1 = reinterpret_cast<const float *>(&C1[t / 4])[t % 4];
+                    x0 = __builtin_fmaf(a0[t], x0, b0[t]);
+                    x1 = __builtin_fmaf(a1[t], x1, b1[t]);
+                    yv[t] = __builtin_fmaf(Ct0, x0, yv[t]);
+                    yv[t] = __builtin_fmaf(Ct1, x1, yv[t]);
+                }
+                xcv = writelane(xcv, readlane(x0, 63), n);           // lane 63 ends on the tile's last step
+                xcv = writelane(xcv, readlane(x1, 63), n + 1);
+            }
+        };
+        if constexpr (N == 1) {
+            float4 Bq0[TQ], Bq1[TQ];
+#pragma unroll
+            for (int q = 0; q < TQ; ++q) Bq0[q] = *reinterpret_cast<const float4 *>(&sB[q * QS + lane * 4]);
+            one_state(0, Bq0, Bq1);
+        } else {
+            static_assert(N == 1 || N % 2 == 0, "states are processed in pairs");
 #pragma unroll 1
-        for (int n = 0; n < N; n += 2) {
-            one_state(n, Bq0, Bq1);
-            if (n + 1 < N) one_state(n + 1, Bq1, Bq0);
+            for (int n = 0; n < N; n += 2) two_states(n);
         }
 
         if constexpr (WANT_Y) {
