@@ -80,6 +80,17 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
     const int64_t ck0 = p.cu ? (int64_t)d * p.nslots + toff / kCkptInterval + b
                              : row * ((L + kCkptInterval - 1) / kCkptInterval);
 
+    // this lane's T steps of u, Delta and z are fetched one tile ahead (raw, converted when their tile starts), so
+    // that their latency hides behind the previous tile's state loop
+    RawFew<IO, T> r_u, r_dl, r_z;
+    auto fetch = [&](int64_t tile) {
+        const int64_t lf = tile * TILE + lane * T;
+        load_few_raw<IO, T>(urow, lf, L, vec, r_u);
+        load_few_raw<IO, T>(drow, lf, L, vec, r_dl);
+        if constexpr (WANT_Y) { if (zrow) load_few_raw<IO, T>(zrow, lf, L, vec, r_z); }
+    };
+    if (active && tile0 < tile1) fetch(tile0);
+
     for (int64_t tile = tile0; tile < tile1; ++tile) {
         const int64_t l0 = tile * TILE;
         const int64_t ll = l0 + lane * T;
@@ -105,8 +116,10 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
 
         // ---- this lane's T steps of u and Delta
         float uv[T], dl[T], du[T], yv[T];
-        load_seg<IO, T>(urow, ll, L, vec, uv);
-        load_seg<IO, T>(drow, ll, L, vec, dl);
+        unpack_few<IO, T>(r_u, uv);
+        unpack_few<IO, T>(r_dl, dl);
+        const RawFew<IO, T> c_z = r_z;                // this tile's gate values, needed after the state loop
+        if (tile + 1 < tile1) fetch(tile + 1);
         float sum_dl = 0.0f;
 #pragma unroll
         for (int t = 0; t < T; ++t) {
@@ -260,7 +273,7 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
         if constexpr (WANT_Y) {
             if (zrow) {
                 float zv[T];
-                load_seg<IO, T>(zrow, ll, L, vec, zv);
+                unpack_few<IO, T>(c_z, zv);
 #pragma unroll
                 for (int t = 0; t < T; ++t) yv[t] *= zv[t] * sigmoid_fast(zv[t]);
             }
