@@ -90,26 +90,47 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_fwd(const FwdParams p) {
         if constexpr (WANT_Y) { if (zrow) load_few_raw<IO, T>(zrow, lf, L, vec, r_z); }
     };
     if (active && tile0 < tile1) fetch(tile0);
+    // likewise the row of Bm and Cm this thread stages (one step of the tile per thread when the tile has as many
+    // steps as the workgroup has threads); rows past the sequence read as zero
+    RawFew<IO, N> r_B, r_C;
+    auto fetch_maps = [&](int64_t tile) {
+        const int64_t l = tile * TILE + threadIdx.x;
+        load_few_raw<IO, N>(Bm + l * N, (int64_t)0, l < L ? (int64_t)N : (int64_t)0, true, r_B);
+        load_few_raw<IO, N>(Cm + l * N, (int64_t)0, l < L ? (int64_t)N : (int64_t)0, true, r_C);
+    };
+    if constexpr (TILE == W * 64) { if (tile0 < tile1) fetch_maps(tile0); }
 
     for (int64_t tile = tile0; tile < tile1; ++tile) {
         const int64_t l0 = tile * TILE;
         const int64_t ll = l0 + lane * T;
 
-        // ---- stage the Bm/Cm tile (all wavefronts), fp32, layout [n][t/4][lane][t%4]
+        // ---- stage the Bm/Cm tile (all wavefronts), fp32, layout [n][t/4][lane][t%4]; the rows were fetched (raw) one
+        // tile ahead
         __syncthreads();
-        for (int r = threadIdx.x; r < TILE; r += W * 64) {
+        if constexpr (TILE == W * 64) {
+            const int r = threadIdx.x;
             float bv[N], cv[N];
-            const int64_t l = l0 + r;
-            if (l < L) {
-                load_row<IO, N>(Bm + l * N, bv);
-                load_row<IO, N>(Cm + l * N, cv);
-            } else {
-#pragma unroll
-                for (int k = 0; k < N; ++k) { bv[k] = 0.0f; cv[k] = 0.0f; }
-            }
+            unpack_few<IO, N>(r_B, bv);
+            unpack_few<IO, N>(r_C, cv);
             const int off = ((r % T) / 4) * QS + (r / T) * 4 + (r % 4);
 #pragma unroll
             for (int k = 0; k < N; ++k) { sB[k * PLANE + off] = bv[k]; sC[k * PLANE + off] = cv[k]; }
+            if (tile + 1 < tile1) fetch_maps(tile + 1);
+        } else {
+            for (int r = threadIdx.x; r < TILE; r += W * 64) {
+                float bv[N], cv[N];
+                const int64_t l = l0 + r;
+                if (l < L) {
+                    load_row<IO, N>(Bm + l * N, bv);
+                    load_row<IO, N>(Cm + l * N, cv);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < N; ++k) { bv[k] = 0.0f; cv[k] = 0.0f; }
+                }
+                const int off = ((r % T) / 4) * QS + (r / T) * 4 + (r % 4);
+#pragma unroll
+                for (int k = 0; k < N; ++k) { sB[k * PLANE + off] = bv[k]; sC[k * PLANE + off] = cv[k]; }
+            }
         }
         __syncthreads();
         if (!active) continue;
