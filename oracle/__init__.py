@@ -262,10 +262,12 @@ def selective_step(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, 
     u, delta, A, Bm, Cm = map(_f64, (u, delta, A, Bm, Cm))
     Dskip, delta_bias, z = map(_f64, (Dskip, delta_bias, z))
     Bsz, D, N = x.shape
-    assert u.shape == (Bsz, D) and delta.shape == (Bsz, D) and Bm.shape == (Bsz, N) and Cm.shape == (Bsz, N)
+    assert u.shape == (Bsz, D) and delta.shape == (Bsz, D) and Bm.shape == Cm.shape
+    assert Bm.shape == (Bsz, N) or (Bm.ndim == 3 and Bm.shape[0] == Bsz and Bm.shape[2] == N)
+    G = 1 if Bm.ndim == 2 else Bm.shape[1]
     y = np.empty((Bsz, D))
     rc = _load().lrnnx_oracle_selective_step(
-        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_int(_disc(disc)),
+        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_int(G), ctypes.c_int(_disc(disc)),
         ctypes.c_int(int(bool(delta_softplus))), _p(x), _p(u), _p(delta), _p(A), _p(Bm), _p(Cm),
         _p(Dskip), _p(delta_bias), _p(z), _p(y))
     if rc != 0:

@@ -360,25 +360,27 @@ int lrnnx_oracle_lti_diag_scan_bwd(int B, long L, int P,
 
 /* Single-token update (the `step` method of Sec. 3, "Library Design"): one application of
  * Eq. 2 to a carried state.  x[B,D,N] is updated in place; u, delta, z, y are [B,D];
- * Bm, Cm are [B,N].  Optional (NULL allowed): Dskip, delta_bias, z.                   */
+ * Bm, Cm are [B,G,N] (channel d reads group d / (D/G); G = 1: [B,N]).  Optional (NULL allowed): Dskip,
+ * delta_bias, z.                                                                      */
 int lrnnx_oracle_selective_step(
-    int B, int D, int N, int disc, int delta_softplus,
+    int B, int D, int N, int G, int disc, int delta_softplus,
     double *x, const double *u, const double *delta, const double *A,
     const double *Bm, const double *Cm, const double *Dskip,
     const double *delta_bias, const double *z, double *y)
 {
-    if (B < 0 || D < 0 || N < 1 || disc < 0 || disc > 3) return 1;
+    if (B < 0 || D < 0 || N < 1 || disc < 0 || disc > 3 || G < 1 || D % G) return 1;
     for (int b = 0; b < B; ++b)
         for (int d = 0; d < D; ++d) {
             long row = (long)b * D + d;
+            long bg = (long)b * G + d / (D / G);
             double s = delta[row] + (delta_bias ? delta_bias[d] : 0.0);
             double dt = delta_softplus ? softplus(s) : s;
             double acc = 0.0;
             for (int n = 0; n < N; ++n) {
                 double a, g;
                 disc_eval(disc, dt, A[(long)d * N + n], &a, &g, 0, 0, 0, 0);
-                x[row * N + n] = a * x[row * N + n] + g * Bm[(long)b * N + n] * u[row];
-                acc += Cm[(long)b * N + n] * x[row * N + n];
+                x[row * N + n] = a * x[row * N + n] + g * Bm[bg * N + n] * u[row];
+                acc += Cm[bg * N + n] * x[row * N + n];
             }
             double ypre = acc + (Dskip ? Dskip[d] * u[row] : 0.0);
             if (z) ypre *= z[row] * sigmoid(z[row]);

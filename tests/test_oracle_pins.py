@@ -305,6 +305,25 @@ def test_step_by_step_equals_the_scan(oracle, disc):
     assert x1[b, d, n] == pytest.approx(a * p["x0"][b, d, n] + g * p["Bm"][b, 0, n] * p["u"][b, d, 0], rel=1e-13)
 
 
+def test_grouped_step_by_step_equals_the_grouped_scan(oracle):
+    """With grouped maps [B,G,N] per token the step update reproduces the grouped scan (itself pinned above), and one
+    state entry matches Eq. 2 written by hand with the group lookup."""
+    p, _ = _grouped_problem(44, B=2, D=6, N=3, L=7, G=3)
+    y_scan, x_last = oracle.selective_scan_fwd(**p)
+    x = p["x0"].copy()
+    for l in range(7):
+        y, x = oracle.selective_step(x, p["u"][:, :, l], p["delta"][:, :, l], p["A"], p["Bm"][:, :, l], p["Cm"][:, :, l],
+                                     Dskip=p["Dskip"], delta_bias=p["delta_bias"], z=p["z"][:, :, l])
+        np.testing.assert_allclose(y, y_scan[:, :, l], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(x, x_last, rtol=1e-12, atol=1e-13)
+    b, d, n = 1, 5, 2                                    # channel 5 of 6 in 3 groups -> group 2
+    dt = np.logaddexp(0, p["delta"][b, d, 0] + p["delta_bias"][d])
+    _, x1 = oracle.selective_step(p["x0"], p["u"][:, :, 0], p["delta"][:, :, 0], p["A"], p["Bm"][:, :, 0],
+                                  p["Cm"][:, :, 0], delta_bias=p["delta_bias"])
+    assert x1[b, d, n] == pytest.approx(np.exp(dt * p["A"][d, n]) * p["x0"][b, d, n]
+                                        + dt * p["Bm"][b, 2, 0, n] * p["u"][b, d, 0], rel=1e-13)
+
+
 def test_lti_step_equals_the_scan(oracle):
     rng = np.random.default_rng(13)
     Bsz, L, P = 2, 9, 5
