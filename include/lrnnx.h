@@ -261,7 +261,8 @@ int lrnnx_lti_diag_scan_bwd(const lrnnx_lti_bwd_args *args);
  * y[b,d] = Cm[b,:] . x[b,d,:] + Dskip[d] u[b,d], times z sigmoid(z) if z != NULL; same Delta transform and
  * discretisations as the scan.  u, delta, z, y are [B,D] in io_dtype with element strides (so a time slice
  * of a [B,D,L] tensor can be passed); Bm, Cm are contiguous [B,N] in io_dtype.  L calls reproduce
- * lrnnx_selective_scan_fwd on L steps up to fp32 rounding.  Optional: Dskip, delta_bias, z.        */
+ * lrnnx_selective_scan_fwd on L steps up to fp32 rounding.  Optional: Dskip, delta_bias, z.
+ * With bc_groups = G > 1, Bm and Cm are [B,G,N] and channel d reads group d / (D/G), as in the scan. */
 typedef struct lrnnx_ss_step_args {
     size_t struct_size;
     int32_t B, D, N;
@@ -277,6 +278,8 @@ typedef struct lrnnx_ss_step_args {
     const void *z;      int64_t z_stride_b, z_stride_d;
     void *y;            int64_t y_stride_b, y_stride_d;
     void *stream;
+    int32_t bc_groups;      /* callers built against the shorter struct get 1 */
+    int32_t reserved;
 } lrnnx_ss_step_args;
 
 int lrnnx_selective_step(const lrnnx_ss_step_args *args);

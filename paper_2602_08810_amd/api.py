@@ -95,7 +95,7 @@ class StepArgs(ctypes.Structure):
         ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
         ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
         ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
-        ("stream", _vp),
+        ("stream", _vp), ("bc_groups", _i32), ("reserved", _i32),
     ]
 
 
@@ -461,8 +461,13 @@ def lrnnx_selective_step(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=
     a.z, a.z_stride_b, a.z_stride_d = _bd(z, "z", io)
     a.A = _ptr(_f32c(A, "A", (D, N)))
     for name, t in (("Bm", Bm), ("Cm", Cm)):
-        if t.dtype != io or not t.is_contiguous() or tuple(t.shape) != (Bsz, N):
-            raise ValueError(f"{name}: expected contiguous [B,N] of dtype {io}")
+        ok = t.dtype == io and t.is_contiguous() and t.shape == Bm.shape and (
+            tuple(t.shape) == (Bsz, N) or (t.dim() == 3 and t.shape[0] == Bsz and t.shape[2] == N))
+        if not ok:
+            raise ValueError(f"{name}: expected contiguous [B,N] or [B,G,N] of dtype {io}")
+    a.bc_groups = Bm.shape[1] if Bm.dim() == 3 else 1
+    if D % a.bc_groups:
+        raise ValueError("D must be a multiple of the number of Bm/Cm groups")
     a.Bm, a.Cm = Bm.data_ptr(), Cm.data_ptr()
     a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
     a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))

@@ -379,7 +379,12 @@ int lrnnx_diag_scan(const lrnnx_diag_scan_args *a) {
 }
 
 int lrnnx_selective_step(const lrnnx_ss_step_args *a) {
-    if (!a || a->struct_size < sizeof(lrnnx_ss_step_args)) return LRNNX_ERR_INVALID_ARG;
+    constexpr size_t kOldSize = offsetof(lrnnx_ss_step_args, bc_groups);  // struct before `bc_groups` was appended
+    if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
+    const bool has_groups = a->struct_size >= sizeof(lrnnx_ss_step_args);
+    if (has_groups && a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
+    const int bcg = (has_groups && a->bc_groups > 1) ? a->bc_groups : 1;
+    if (a->D % bcg) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->D < 1 || a->N < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
@@ -389,6 +394,7 @@ int lrnnx_selective_step(const lrnnx_ss_step_args *a) {
     if (!aligned16(a->x) || !aligned16(a->A) || !aligned16(a->Bm) || !aligned16(a->Cm)) return LRNNX_ERR_INVALID_ARG;
     StepParams p{};
     p.B = a->B; p.D = a->D; p.N = a->N; p.softplus = a->delta_softplus ? 1 : 0;
+    p.bcg = bcg; p.dpg = a->D / bcg;
     p.x = a->x; p.u = a->u; p.delta = a->delta; p.z = a->z; p.Bm = a->Bm; p.Cm = a->Cm; p.y = a->y;
     p.u_sb = a->u_stride_b; p.u_sd = a->u_stride_d; p.dl_sb = a->delta_stride_b; p.dl_sd = a->delta_stride_d;
     p.z_sb = a->z_stride_b; p.z_sd = a->z_stride_d; p.y_sb = a->y_stride_b; p.y_sd = a->y_stride_d;

@@ -76,6 +76,7 @@ struct DiagParams {
 struct StepParams {
     int B, D, N;
     int softplus;
+    int bcg, dpg;                              // number of Bm/Cm groups and channels per group
     float *x;                                  // [B,D,N] in/out
     const void *u, *delta, *z, *Bm, *Cm;       // u, delta, z: [B,D] with strides; Bm, Cm: [B,N]
     void *y;

@@ -36,8 +36,9 @@ __global__ __launch_bounds__(256) void k_ss_step(const StepParams p) {
 #pragma unroll
         for (int n = 0; n < NPT; ++n) { xs[n] = xp[n]; Av[n] = ap[n]; }
     }
-    load_row<IO, NPT>(reinterpret_cast<const IO *>(p.Bm) + (int64_t)b * N + q * NPT, Bv);
-    load_row<IO, NPT>(reinterpret_cast<const IO *>(p.Cm) + (int64_t)b * N + q * NPT, Cv);
+    const int64_t bc = ((int64_t)b * p.bcg + d / p.dpg) * N + q * NPT;   // this channel's group of the maps
+    load_row<IO, NPT>(reinterpret_cast<const IO *>(p.Bm) + bc, Bv);
+    load_row<IO, NPT>(reinterpret_cast<const IO *>(p.Cm) + bc, Cv);
     float acc = 0.0f;
 #pragma unroll
     for (int n = 0; n < NPT; ++n) {

@@ -82,3 +82,27 @@ def test_error_codes(api):
         api.lrnnx_selective_step(x, u, u, torch.zeros((4, 3), device="cuda"), torch.zeros((1, 3), device="cuda"),
                                  torch.zeros((1, 3), device="cuda"))
     assert e.value.code == 2
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("N,D,G", [(16, 24, 3), (4, 10, 5), (2, 6, 6), (8, 64, 2)])
+def test_selective_step_with_grouped_maps(api, oracle, io, N, D, G):
+    """Bm, Cm [B,G,N] per token: against the oracle, and step by step against the grouped scan kernel."""
+    import torch
+    B, L = 3, 6
+    p = workloads.make_selective(B=B, D=D, N=N, L=L, io=io, gate=True, with_x0=True, with_dy=False, seed=50 + G,
+                                 bias=("uniform", -4.0, -2.0), bc_groups=G)
+    t = sel_inputs_dev(p, io)
+    y_scan, x_last = api.lrnnx_selective_scan_fwd(**t, return_last_state=True)
+    x = t["x0"].clone()
+    xr = p["x0"].astype(np.float64)
+    for l in range(L):
+        y = api.lrnnx_selective_step(x, t["u"][:, :, l], t["delta"][:, :, l], t["A"], t["Bm"][:, :, l].contiguous(),
+                                     t["Cm"][:, :, l].contiguous(), Dskip=t["Dskip"], delta_bias=t["delta_bias"],
+                                     z=t["z"][:, :, l])
+        yr, xr = oracle.selective_step(xr, p["u"][:, :, l], p["delta"][:, :, l], p["A"], p["Bm"][:, :, l],
+                                       p["Cm"][:, :, l], Dskip=p["Dskip"], delta_bias=p["delta_bias"], z=p["z"][:, :, l])
+        assert rel_err(host(y), yr) <= TOL[io], f"y at token {l}"
+        assert rel_err(host(x), xr) <= 1e-4, f"state at token {l}"
+        assert rel_err(host(y), host(y_scan[:, :, l])) <= TOL[io]
+    assert rel_err(host(x), host(x_last)) <= 1e-4
