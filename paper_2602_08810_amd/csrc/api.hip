@@ -9,8 +9,6 @@ using namespace lrnnx;
 namespace {
 
 constexpr int kNumCU = 256;              // MI355X
-constexpr int kFwdWaves = 8;             // channels (wavefronts) per forward workgroup
-constexpr int kLtiGroup = 4;             // chunks (wavefronts) per LTI workgroup; must match lti_scan.hip
 
 inline bool supported_n(int n) { return n == 1 || n == 2 || n == 4 || n == 8 || n == 16; }
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -24,7 +22,7 @@ inline bool row_vec_ok(const void *p, int64_t sb, int64_t sd, size_t es) {
 
 // Number of time chunks of the chunk-carry forward path.
 int fwd_chunks(int64_t B, int64_t D, int64_t L, int io, bool forced) {
-    const int64_t wgs = B * cdiv(D, kFwdWaves);
+    const int64_t wgs = B * cdiv(D, fwd_channels_per_workgroup());
     const int64_t ntiles = cdiv(L, fwd_tile_steps(io));
     int64_t n = cdiv(forced ? 8 * kNumCU : 2 * kNumCU, wgs);
     if (forced && n < 2) n = 2;
@@ -44,9 +42,8 @@ int lti_chunks(int64_t B, int64_t P, int64_t L) {
 }
 
 // single-pass LTI workspace: T [B,ngroups,P] and X [B,ngroups/16+1,P] complex, then the error word
-constexpr int kLtiAnchor = 16;            // must match lti_scan.hip
 size_t onepass_bytes(int64_t B, int64_t P, int64_t ng) {
-    return (size_t)(B * (ng + ng / kLtiAnchor + 1) * P * 2 * sizeof(float)) + 64 * sizeof(int);
+    return (size_t)(B * (ng + ng / lti_onepass_anchor() + 1) * P * 2 * sizeof(float)) + 64 * sizeof(int);
 }
 size_t lti_onepass_bytes(int64_t B, int64_t P, int64_t L) { return onepass_bytes(B, P, cdiv(L, lti_onepass_min_group_steps())); }
 size_t lti_onepass_bwd_bytes(int64_t B, int64_t P, int64_t L) {
@@ -60,13 +57,13 @@ size_t diag_scan_bytes(int64_t B, int64_t P, int64_t L, int is_complex) {
 void set_onepass_workspace(LtiParams &p, void *ws) {
     p.ws_T = reinterpret_cast<float2 *>(ws);
     p.ws_X = p.ws_T + (size_t)p.B * p.ngroups * p.P;
-    p.err = reinterpret_cast<int *>(p.ws_X + (size_t)p.B * (p.ngroups / kLtiAnchor + 1) * p.P);
+    p.err = reinterpret_cast<int *>(p.ws_X + (size_t)p.B * (p.ngroups / lti_onepass_anchor() + 1) * p.P);
 }
 // every slot starts as "not published" (all-ones words), the error word as zero
 FillList onepass_fill(const LtiParams &p) {
     FillList z{};
     z.ptr[0] = reinterpret_cast<float *>(p.ws_T);
-    z.count[0] = 2 * (int64_t)p.B * (p.ngroups + p.ngroups / kLtiAnchor + 1) * p.P;
+    z.count[0] = 2 * (int64_t)p.B * (p.ngroups + p.ngroups / lti_onepass_anchor() + 1) * p.P;
     z.bits[0] = 0xffffffffu;
     z.ptr[1] = reinterpret_cast<float *>(p.err); z.count[1] = 1;
     return z;
@@ -104,7 +101,7 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
     }
     if (which == LRNNX_WS_LTI) {
         const int nch = lti_chunks(B, D, L);
-        const size_t two = nch > 1 ? (size_t)B * (nch + cdiv(nch, kLtiGroup)) * D * 2 * sizeof(float) : 0;
+        const size_t two = nch > 1 ? (size_t)B * (nch + cdiv(nch, lti_chunk_group())) * D * 2 * sizeof(float) : 0;
         const size_t one = lti_onepass_bytes(B, D, L);
         return two > one ? two : one;
     }
@@ -156,7 +153,7 @@ int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *a) {
             row_vec_ok(a->y, p.y_sb, p.y_sd, es) && (!a->z || row_vec_ok(a->z, p.z_sb, p.z_sd, es));
 
     const int64_t ntiles = cdiv(a->L, fwd_tile_steps(a->io_dtype));
-    const int64_t wgs = (int64_t)a->B * cdiv(a->D, kFwdWaves);
+    const int64_t wgs = (int64_t)a->B * cdiv(a->D, fwd_channels_per_workgroup());
     bool chunked = false;
     int nch = 1;
     if (a->path == LRNNX_PATH_CHUNK_CARRY) {
@@ -303,7 +300,7 @@ int lrnnx_lti_diag_scan(const lrnnx_lti_args *a) {
     int nch = lti_chunks(a->B, a->P, a->L);
     p.chunk = cdiv(a->L, nch);
     p.nchunks = (int)cdiv(a->L, p.chunk);
-    p.ngroups = (int)cdiv(p.nchunks, kLtiGroup);
+    p.ngroups = (int)cdiv(p.nchunks, lti_chunk_group());
     if (p.ngroups > 65535) return LRNNX_ERR_UNSUPPORTED;
     if (p.nchunks > 1) {
         const size_t need = (size_t)a->B * (p.nchunks + p.ngroups) * a->P * 2 * sizeof(float);

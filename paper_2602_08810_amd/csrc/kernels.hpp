@@ -108,7 +108,10 @@ struct FillList {
 };
 hipError_t launch_fill(const FillList &z, hipStream_t s);
 
-// Tile geometry the host needs for grids, workspaces and the choice of path.
+// Tile geometry the host needs for grids, workspaces and the choice of path (each constant lives beside its kernel).
+int fwd_channels_per_workgroup();            // wavefronts (= channels) of one forward workgroup
+int lti_chunk_group();                       // chunks (wavefronts) of one workgroup of the two-launch LTI path
+int lti_onepass_anchor();                    // every how many groups the single-launch LTI scan publishes a true state
 int fwd_tile_steps(int io_dtype);            // time steps one workgroup covers per tile
 int bwd_channels_per_group(int B, int D, int N, int64_t L, bool balanced);
 

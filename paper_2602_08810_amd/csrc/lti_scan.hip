@@ -256,6 +256,8 @@ static int onepass_gw(int64_t B, int64_t P) { return B * ((P + 63) / 64) >= 64 ?
 int lti_onepass_group_steps(int64_t B, int64_t P) { return kOneCS * onepass_gw(B, P); }
 int lti_onepass_min_group_steps() { return kOneCS * kOneGWSmall; }
 int lti_onepass_bwd_group_steps() { return kOneBwdCS * kOneBwdGW; }
+int lti_onepass_anchor() { return kAnchor; }
+int lti_chunk_group() { return kLtiWaves; }
 
 hipError_t launch_lti_onepass(const LtiParams &p, hipStream_t s) {
     const int npslab = (p.P + 63) / 64;

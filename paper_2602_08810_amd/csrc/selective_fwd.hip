@@ -347,6 +347,7 @@ constexpr int kFwdT = 8;
 constexpr int kFwdW = 8;
 
 int fwd_tile_steps(int) { return 64 * kFwdT; }
+int fwd_channels_per_workgroup() { return kFwdW; }
 
 template <typename IO, int N, int DISC>
 static hipError_t launch_fwd_n(const FwdParams &p, hipStream_t s) {
