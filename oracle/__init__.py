@@ -113,6 +113,29 @@ def selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None,
     return (y, x_last, xs) if return_states else (y, x_last)
 
 
+def selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, x0=None,
+                               disc="zoh_s6", delta_softplus=True):
+    """y [B,D,L] (real) and x_last [B,D,N] (complex128) of Eq. 2 with a complex diagonal A [D,N] and complex
+    maps Bm, Cm [B,L,N]: y = Re(sum_n Cm x) + Dskip u, then the optional gate."""
+    u, delta = _f64(u), _f64(delta)
+    A, Bm, Cm = _c128(A), _c128(Bm), _c128(Cm)
+    Dskip, delta_bias, z = map(_f64, (Dskip, delta_bias, z))
+    x0c = None if x0 is None else _c128(x0)
+    Bsz, D, L = u.shape
+    N = A.shape[1]
+    assert A.shape == (D, N) and Bm.shape == (Bsz, L, N) and Cm.shape == (Bsz, L, N)
+    y = np.empty((Bsz, D, L))
+    x_last = np.empty((Bsz, D, N), dtype=np.complex128)
+    cp = lambda t: ctypes.c_void_p(0) if t is None else t.ctypes.data_as(ctypes.c_void_p)
+    rc = _load().lrnnx_oracle_selective_scan_fwd_complex(
+        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_long(L),
+        ctypes.c_int(_disc(disc)), ctypes.c_int(int(bool(delta_softplus))),
+        _p(u), _p(delta), cp(A), cp(Bm), cp(Cm), _p(Dskip), _p(delta_bias), _p(z), cp(x0c), _p(y), cp(x_last))
+    if rc != 0:
+        raise ValueError(f"oracle complex fwd: bad arguments (rc={rc})")
+    return y, x_last
+
+
 def selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,
                        disc="zoh_s6", delta_softplus=True):
     """Gradients of sum(dy * y) w.r.t. every input, as a dict of float64 arrays."""

@@ -148,6 +148,83 @@ int lrnnx_oracle_selective_scan_fwd(
     return 0;
 }
 
+/* Complex discretisation of x' = A x + B u for complex A (same four schemes as disc_eval, complex arithmetic).
+ * a = (ar, ai) is the state multiplier, g = (gr, gi) the input gain (Bbar = g * B).                        */
+static void disc_eval_c(int disc, double dt, double Ar, double Ai, double *ar, double *ai, double *gr, double *gi)
+{
+    if (disc == DISC_BILINEAR) {
+        /* a = (1 + dt A/2) / (1 - dt A/2), g = dt / (1 - dt A/2) */
+        double wr = 1.0 - 0.5 * dt * Ar, wi = -0.5 * dt * Ai;
+        double nr = 1.0 + 0.5 * dt * Ar, ni = 0.5 * dt * Ai;
+        double den = wr * wr + wi * wi;
+        *ar = (nr * wr + ni * wi) / den;
+        *ai = (ni * wr - nr * wi) / den;
+        *gr = dt * wr / den;
+        *gi = -dt * wi / den;
+        return;
+    }
+    double e = exp(dt * Ar);
+    *ar = e * cos(dt * Ai);
+    *ai = e * sin(dt * Ai);
+    if (disc == DISC_ZOH_S6) { *gr = dt; *gi = 0.0; }
+    else if (disc == DISC_DIRAC) { *gr = 1.0; *gi = 0.0; }
+    else {                                   /* exact ZOH: g = (a - 1) / A */
+        if (Ar == 0.0 && Ai == 0.0) { *gr = dt; *gi = 0.0; return; }
+        /* a - 1 without cancellation: exp(z) - 1 = expm1(zr) cos(zi) + (cos(zi) - 1) + i e^{zr} sin(zi),
+         * and cos(zi) - 1 = -2 sin^2(zi/2) */
+        double zr = dt * Ar, zi = dt * Ai, sh = sin(0.5 * zi);
+        double mr = expm1(zr) * cos(zi) - 2.0 * sh * sh, mi = e * sin(zi);
+        double den = Ar * Ar + Ai * Ai;
+        *gr = (mr * Ar + mi * Ai) / den;
+        *gi = (mi * Ar - mr * Ai) / den;
+    }
+}
+
+/* Forward selective scan with a complex diagonal state matrix (the recurrence of Eq. 2 for the complex-diagonal
+ * layers of Sec. 2.2.1 when their step size or maps depend on the input):
+ *     x_{l,n} = a(Delta_l, A[d,n]) x_{l-1,n} + g(Delta_l, A[d,n]) Bm[b,l,n] u[b,d,l]      (complex)
+ *     y[b,d,l] = Re( sum_n Cm[b,l,n] x_{l,n} ) + Dskip[d] u[b,d,l],   then the optional gate.
+ * A [D,N], Bm, Cm [B,L,N], x0, x_last [B,D,N] are complex ((re, im) pairs of doubles); u, delta, z, y, Dskip,
+ * delta_bias real.  Optional (NULL allowed): Dskip, delta_bias, z, x0, x_last.                                 */
+int lrnnx_oracle_selective_scan_fwd_complex(
+    int B, int D, int N, long L, int disc, int delta_softplus,
+    const double *u, const double *delta, const double *A,
+    const double *Bm, const double *Cm, const double *Dskip,
+    const double *delta_bias, const double *z, const double *x0,
+    double *y, double *x_last)
+{
+    if (B < 0 || D < 0 || N < 1 || L < 0 || disc < 0 || disc > 3) return 1;
+    long rows = (long)B * D;
+#pragma omp parallel for schedule(static)
+    for (long row = 0; row < rows; ++row) {
+        int b = (int)(row / D), d = (int)(row % D);
+        double *x = (double *)malloc(sizeof(double) * 2 * N);
+        for (int n = 0; n < 2 * N; ++n) x[n] = x0 ? x0[row * 2 * N + n] : 0.0;
+        for (long l = 0; l < L; ++l) {
+            double s = delta[row * L + l] + (delta_bias ? delta_bias[d] : 0.0);
+            double dt = delta_softplus ? softplus(s) : s;
+            double uu = u[row * L + l];
+            double acc = 0.0;
+            for (int n = 0; n < N; ++n) {
+                double ar, ai, gr, gi;
+                disc_eval_c(disc, dt, A[2 * ((long)d * N + n)], A[2 * ((long)d * N + n) + 1], &ar, &ai, &gr, &gi);
+                long bc = 2 * (((long)b * L + l) * N + n);
+                double br = (gr * Bm[bc] - gi * Bm[bc + 1]) * uu, bi = (gr * Bm[bc + 1] + gi * Bm[bc]) * uu;
+                double xr = ar * x[2 * n] - ai * x[2 * n + 1] + br;
+                double xi = ar * x[2 * n + 1] + ai * x[2 * n] + bi;
+                x[2 * n] = xr; x[2 * n + 1] = xi;
+                acc += Cm[bc] * xr - Cm[bc + 1] * xi;                       /* Re(C x) */
+            }
+            double ypre = acc + (Dskip ? Dskip[d] * uu : 0.0);
+            if (z) { double zz = z[row * L + l]; ypre *= zz * sigmoid(zz); }
+            y[row * L + l] = ypre;
+        }
+        if (x_last) for (int n = 0; n < 2 * N; ++n) x_last[row * 2 * N + n] = x[n];
+        free(x);
+    }
+    return 0;
+}
+
 /* Reverse-mode derivative of the forward above for a given upstream dy.
  * Every state of a row is kept (L*N doubles) -- the oracle stores what the
  * GPU path recomputes.  Outputs dA, dD, dbias, dBm, dCm are overwritten.

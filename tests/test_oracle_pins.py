@@ -620,3 +620,88 @@ def test_packed_backward_by_finite_differences_with_grouped_maps(oracle):
             q[k][idx] -= 2 * h
             num = (up - loss(q)) / (2 * h)
             assert num == pytest.approx(g[gk][idx], rel=2e-6, abs=1e-7), (k, idx)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Selective scan with a complex diagonal A and complex maps: y = Re(sum_n C x) + D u  (Sec. 2.2.1 layers made
+# input-dependent; the "Re" of the recurrence as the paper's complex-diagonal layers use it).
+# ---------------------------------------------------------------------------------------------------------------
+def _disc_py_c(disc, dt, A):
+    """Independent restatement of the four schemes for complex A with numpy complex scalars."""
+    if disc == "bilinear":
+        return (1 + dt * A / 2) / (1 - dt * A / 2), dt / (1 - dt * A / 2)
+    a = np.exp(dt * A)
+    return a, {"zoh_s6": dt, "zoh": (a - 1) / A, "dirac": 1.0}[disc]
+
+
+def _complex_problem(seed, B=2, D=3, N=4, L=9):
+    rng = np.random.default_rng(seed)
+    c = lambda *s: rng.standard_normal(s) + 1j * rng.standard_normal(s)
+    return dict(u=rng.standard_normal((B, D, L)), delta=rng.standard_normal((B, D, L)),
+                A=-np.exp(rng.uniform(-1, 1, (D, N))) + 1j * rng.uniform(-3, 3, (D, N)),
+                Bm=c(B, L, N), Cm=c(B, L, N), Dskip=rng.standard_normal(D), delta_bias=rng.uniform(-2, 0, D),
+                z=rng.standard_normal((B, D, L)), x0=c(B, D, N))
+
+
+@pytest.mark.parametrize("disc", DISCS)
+def test_complex_forward_is_the_unrolled_sum(oracle, disc):
+    p = _complex_problem(61)
+    B, D, L = p["u"].shape
+    N = p["A"].shape[1]
+    y, x_last = oracle.selective_scan_fwd_complex(**p, disc=disc)
+    dt = np.logaddexp(0.0, p["delta"] + p["delta_bias"][None, :, None])
+    for b in range(B):
+        for d in range(D):
+            a, g = _disc_py_c(disc, dt[b, d][:, None], p["A"][d][None, :])           # [L,N]
+            g = np.broadcast_to(g, a.shape)
+            bvec = g * p["Bm"][b] * p["u"][b, d][:, None]
+            for l in range(L):
+                x = np.prod(a[:l + 1], axis=0) * p["x0"][b, d]
+                for j in range(l + 1):
+                    x = x + np.prod(a[j + 1:l + 1], axis=0) * bvec[j]
+                ypre = (p["Cm"][b, l] * x).sum().real + p["Dskip"][d] * p["u"][b, d, l]
+                zz = p["z"][b, d, l]
+                assert y[b, d, l] == pytest.approx(ypre * zz / (1 + np.exp(-zz)), rel=1e-10, abs=1e-11)
+            np.testing.assert_allclose(x_last[b, d], x, rtol=1e-10)
+
+
+@pytest.mark.parametrize("disc", DISCS)
+def test_complex_forward_with_real_data_is_the_real_scan(oracle, disc):
+    rng = np.random.default_rng(62)
+    p = _rand_problem(rng, B=2, D=3, N=4, L=12)
+    y, xl = oracle.selective_scan_fwd(**p, disc=disc)
+    q = dict(p, A=p["A"] + 0j, Bm=p["Bm"] + 0j, Cm=p["Cm"] + 0j, x0=p["x0"] + 0j)
+    yc, xlc = oracle.selective_scan_fwd_complex(**q, disc=disc)
+    np.testing.assert_allclose(yc, y, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(xlc.real, xl, rtol=1e-12, atol=1e-13)
+    assert np.all(xlc.imag == 0)
+
+
+@pytest.mark.parametrize("dt,A", [(0.05, -1.3 + 2.0j), (0.7, -0.4 - 5.0j), (1e-4, -2.5 + 0.3j)])
+def test_complex_zoh_and_bilinear_match_scipy_cont2discrete(oracle, dt, A):
+    """One complex state driven by u = 1 from rest for one step: x_1 = g, and from x0 = 1 with u = 0: x_1 = a."""
+    sys_c = (np.array([[A]]), np.array([[1.0 + 0j]]), np.array([[1.0 + 0j]]), np.array([[0.0 + 0j]]))
+    one = np.ones((1, 1, 1))
+    for disc in ("zoh", "bilinear"):
+        Ad, Bd, *_ = scipy.signal.cont2discrete(sys_c, dt, method=disc)
+        kw = dict(A=np.array([[A]]), Bm=one + 0j, Cm=one + 0j, disc=disc, delta_softplus=False)
+        _, g = oracle.selective_scan_fwd_complex(one, dt * one, **kw)
+        _, a = oracle.selective_scan_fwd_complex(0 * one, dt * one, x0=one + 0j, **kw)
+        assert g[0, 0, 0] == pytest.approx(Bd[0, 0], rel=1e-11)
+        assert a[0, 0, 0] == pytest.approx(Ad[0, 0], rel=1e-12)
+
+
+def test_complex_forward_with_constant_step_is_the_lti_scan(oracle):
+    """Constant Delta and time-invariant maps: the states are those of the LTI complex-diagonal scan with
+    lambda = exp(Delta A) and v = Delta B u, and y = Re(sum C x)."""
+    rng = np.random.default_rng(63)
+    L, N = 40, 5
+    A = -rng.uniform(0.1, 1, N) + 1j * rng.uniform(-3, 3, N)
+    Bv, Cv = rng.standard_normal(N) + 1j * rng.standard_normal(N), rng.standard_normal(N) + 1j * rng.standard_normal(N)
+    u = rng.standard_normal(L)
+    dt = 0.3
+    x = oracle.lti_diag_scan(np.exp(dt * A), (dt * Bv[None, :] * u[:, None])[None])            # [1,L,N]
+    y, xl = oracle.selective_scan_fwd_complex(u[None, None], np.full((1, 1, L), dt), A[None], np.tile(Bv, (1, L, 1)),
+                                              np.tile(Cv, (1, L, 1)), delta_softplus=False)
+    np.testing.assert_allclose(y[0, 0], (x[0] * Cv[None, :]).sum(-1).real, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(xl[0, 0], x[0, -1], rtol=1e-12)
