@@ -126,6 +126,37 @@ typedef struct lrnnx_ss_fwd_args {
 
 int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *args);
 
+/* ------------------------------------------------------------------ selective scan, forward, complex diagonal A
+ * The same recurrence with a complex diagonal state matrix and complex maps, the output taken as the real part:
+ *     x_{l,n} = a(Delta_l, A[d,n]) x_{l-1,n} + g(Delta_l, A[d,n]) Bm[b,l,n] u[b,d,l]      (complex)
+ *     ypre_l  = Re( sum_n Cm[b,l,n] x_{l,n} ) + Dskip[d] u[b,d,l],   then the optional gate as above
+ * (Eq. 2 with y = Re(C x) + D u: the complex-diagonal layers of Sec. 2.2.1 with an input-dependent step size and
+ * input-dependent maps; time-invariant maps are passed with every row equal).  u, delta, z, y, Dskip, delta_bias are
+ * real as above.  A [D,N] complex float pairs; Bm, Cm [B,L,N] complex in io_dtype (interleaved re, im: bfloat16
+ * pairs or float pairs), contiguous, 16-byte aligned; x0, x_last [B,D,N] complex float pairs (optional).
+ * a and g are the four schemes of lrnnx_disc in complex arithmetic.  Delta * Im(A) must stay within
+ * +-256 * 2 pi (the range of the hardware sine and cosine).  Forward only; one pass over the sequence.       */
+typedef struct lrnnx_ss_fwd_complex_args {
+    size_t struct_size;
+    int32_t B, D, N;
+    int64_t L;
+    int32_t io_dtype, disc, delta_softplus, reserved;
+    const void *u;      int64_t u_stride_b, u_stride_d;
+    const void *delta;  int64_t delta_stride_b, delta_stride_d;
+    const void *A;                                                 /* [D,N] complex float */
+    const void *Bm;                                                /* [B,L,N] complex io */
+    const void *Cm;                                                /* [B,L,N] complex io */
+    const float *Dskip;
+    const float *delta_bias;
+    const void *z;      int64_t z_stride_b, z_stride_d;
+    const void *x0;                                                /* [B,D,N] complex float or NULL */
+    void *y;            int64_t y_stride_b, y_stride_d;
+    void *x_last;                                                  /* [B,D,N] complex float, out or NULL */
+    void *stream;
+} lrnnx_ss_fwd_complex_args;
+
+int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *args);
+
 /* ------------------------------------------------------------------ selective scan, backward
  * Reverse-mode derivative of the forward above for an upstream gradient dy[B,D,L]:
  * the gradients of sum(dy * y) with respect to u, the raw delta, A, Bm, Cm, Dskip,

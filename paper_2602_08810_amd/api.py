@@ -41,6 +41,20 @@ class FwdArgs(ctypes.Structure):
     ]
 
 
+class FwdComplexArgs(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32), ("L", _i64),
+        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32), ("reserved", _i32),
+        ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
+        ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
+        ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
+        ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
+        ("x0", _vp),
+        ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
+        ("x_last", _vp), ("stream", _vp),
+    ]
+
+
 class BwdArgs(ctypes.Structure):
     _fields_ = [
         ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32), ("L", _i64),
@@ -116,6 +130,8 @@ def lib():
         L = ctypes.CDLL(LIB_PATH)
         L.lrnnx_selective_scan_fwd.argtypes = [ctypes.POINTER(FwdArgs)]
         L.lrnnx_selective_scan_bwd.argtypes = [ctypes.POINTER(BwdArgs)]
+        L.lrnnx_selective_scan_fwd_complex.argtypes = [ctypes.POINTER(FwdComplexArgs)]
+        L.lrnnx_selective_scan_fwd_complex.restype = ctypes.c_int
         L.lrnnx_lti_diag_scan.argtypes = [ctypes.POINTER(LtiArgs)]
         L.lrnnx_lti_diag_scan_bwd.argtypes = [ctypes.POINTER(LtiBwdArgs)]
         L.lrnnx_lti_diag_scan_bwd.restype = ctypes.c_int
@@ -274,6 +290,47 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
     if return_ckpt:
         res += (ckpt,)
     return res[0] if len(res) == 1 else res
+
+
+def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, x0=None,
+                                     disc="zoh_s6", delta_softplus=True, return_last_state=False, out=None):
+    """y (and optionally x_last) of the forward selective scan with complex A, Bm, Cm; see lrnnx_ss_fwd_complex_args.
+
+    A [D,N] complex64.  Bm, Cm [B,L,N]: complex64 for float32 I/O; for bfloat16 I/O a bfloat16 tensor [B,L,N,2]
+    of (re, im) pairs.  x0, x_last [B,D,N] complex64."""
+    io = u.dtype
+    Bsz, D, L = u.shape
+    if A.dtype != torch.complex64 or A.dim() != 2 or A.shape[0] != D or not A.is_contiguous():
+        raise ValueError("A: expected contiguous complex64 [D,N]")
+    N = A.shape[1]
+    for name, t in (("Bm", Bm), ("Cm", Cm)):
+        ok = t.is_contiguous() and ((io == torch.float32 and t.dtype == torch.complex64 and tuple(t.shape) == (Bsz, L, N)) or
+                                    (io == torch.bfloat16 and t.dtype == torch.bfloat16 and tuple(t.shape) == (Bsz, L, N, 2)))
+        if not ok:
+            raise ValueError(f"{name}: expected contiguous complex64 [B,L,N] (float32 I/O) or bfloat16 [B,L,N,2]")
+    a = FwdComplexArgs()
+    a.struct_size = ctypes.sizeof(FwdComplexArgs)
+    a.B, a.D, a.N, a.L = Bsz, D, N, L
+    a.io_dtype = _io_dtype(u)
+    a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
+    a.delta_softplus = int(bool(delta_softplus))
+    a.u, a.u_stride_b, a.u_stride_d = _bdl(u, "u", io)
+    a.delta, a.delta_stride_b, a.delta_stride_d = _bdl(delta, "delta", io)
+    a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io)
+    a.A, a.Bm, a.Cm = A.data_ptr(), Bm.data_ptr(), Cm.data_ptr()
+    a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
+    a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
+    if x0 is not None:
+        if x0.dtype != torch.complex64 or not x0.is_contiguous() or tuple(x0.shape) != (Bsz, D, N):
+            raise ValueError("x0: expected contiguous complex64 [B,D,N]")
+        a.x0 = x0.data_ptr()
+    y = out if out is not None else torch.empty((Bsz, D, L), dtype=io, device=u.device)
+    a.y, a.y_stride_b, a.y_stride_d = _bdl(y, "y", io)
+    x_last = torch.empty((Bsz, D, N), dtype=torch.complex64, device=u.device) if return_last_state else None
+    a.x_last = _ptr(x_last)
+    a.stream = _stream()
+    _check(lib().lrnnx_selective_scan_fwd_complex(ctypes.byref(a)))
+    return (y, x_last) if return_last_state else y
 
 
 def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,

@@ -185,6 +185,40 @@ int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *a) {
     return launch_ss_fwd(p, a->io_dtype, a->disc, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }
 
+int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *a) {
+    if (!a || a->struct_size < sizeof(lrnnx_ss_fwd_complex_args)) return LRNNX_ERR_INVALID_ARG;
+    if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
+    if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
+    if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
+    if (!a->u || !a->delta || !a->A || !a->Bm || !a->Cm || !a->y) return LRNNX_ERR_INVALID_ARG;
+    if (a->u_stride_b < 0 || a->u_stride_d < 0 || a->delta_stride_b < 0 || a->delta_stride_d < 0 ||
+        a->y_stride_b < 0 || a->y_stride_d < a->L || (a->z && (a->z_stride_b < 0 || a->z_stride_d < 0)))
+        return LRNNX_ERR_INVALID_ARG;
+    if (!supported_n(a->N)) return LRNNX_ERR_UNSUPPORTED;
+    if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
+    if (!aligned16(a->Bm) || !aligned16(a->Cm)) return LRNNX_ERR_INVALID_ARG;
+    for (const void *q : {a->A, a->x0, (const void *)a->x_last})
+        if (reinterpret_cast<uintptr_t>(q) & 7u) return LRNNX_ERR_INVALID_ARG;
+    const size_t es = elem_size(a->io_dtype);
+    CFwdParams p{};
+    p.B = a->B; p.D = a->D; p.N = a->N; p.L = a->L;
+    p.softplus = a->delta_softplus ? 1 : 0;
+    p.u = a->u; p.delta = a->delta; p.z = a->z; p.y = a->y;
+    p.u_sb = a->u_stride_b; p.u_sd = a->u_stride_d;
+    p.dl_sb = a->delta_stride_b; p.dl_sd = a->delta_stride_d;
+    p.z_sb = a->z_stride_b; p.z_sd = a->z_stride_d;
+    p.y_sb = a->y_stride_b; p.y_sd = a->y_stride_d;
+    p.A = reinterpret_cast<const float2 *>(a->A);
+    p.Dskip = a->Dskip; p.bias = a->delta_bias;
+    p.x0 = reinterpret_cast<const float2 *>(a->x0);
+    p.Bm = a->Bm; p.Cm = a->Cm;
+    p.x_last = reinterpret_cast<float2 *>(a->x_last);
+    p.vec = row_vec_ok(a->u, p.u_sb, p.u_sd, es) && row_vec_ok(a->delta, p.dl_sb, p.dl_sd, es) &&
+            row_vec_ok(a->y, p.y_sb, p.y_sd, es) && (!a->z || row_vec_ok(a->z, p.z_sb, p.z_sd, es));
+    return launch_ss_cfwd(p, a->io_dtype, a->disc, reinterpret_cast<hipStream_t>(a->stream)) == hipSuccess
+               ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+}
+
 int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     constexpr size_t kOldSize = offsetof(lrnnx_ss_bwd_args, cu_seqlens);  // struct before `cu_seqlens` was appended
     if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;

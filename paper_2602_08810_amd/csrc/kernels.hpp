@@ -27,6 +27,21 @@ struct FwdParams {
     float *ws_P, *ws_S;      // [B,D,nchunks,N] chunk aggregates; ws_S is overwritten with the chunk carry-in
 };
 
+// forward selective scan with a complex diagonal A and complex maps (single pass)
+struct CFwdParams {
+    int B, D, N;
+    int64_t L;
+    int softplus, vec;
+    const void *u, *delta, *z;
+    void *y;
+    int64_t u_sb, u_sd, dl_sb, dl_sd, z_sb, z_sd, y_sb, y_sd;
+    const float2 *A;         // [D,N] complex
+    const float *Dskip, *bias;
+    const float2 *x0;        // [B,D,N] complex
+    const void *Bm, *Cm;     // [B,L,N] complex in the I/O type
+    float2 *x_last;
+};
+
 struct BwdParams {
     int B, D, N;
     int64_t L;
@@ -89,6 +104,7 @@ hipError_t launch_ss_step(const StepParams &p, int io_dtype, int disc, hipStream
 hipError_t launch_lti_step(int B, int P, const float2 *lambda, float2 *x, const float2 *v, hipStream_t s);
 hipError_t launch_ss_fwd(const FwdParams &p, int io_dtype, int disc, hipStream_t s);
 hipError_t launch_ss_carry(const FwdParams &p, hipStream_t s);
+hipError_t launch_ss_cfwd(const CFwdParams &p, int io_dtype, int disc, hipStream_t s);
 hipError_t launch_ss_bwd(const BwdParams &p, int io_dtype, int disc, hipStream_t s);
 hipError_t launch_lti(const LtiParams &p, hipStream_t s);
 hipError_t launch_lti_onepass(const LtiParams &p, hipStream_t s);

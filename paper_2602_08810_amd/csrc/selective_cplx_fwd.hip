@@ -1,0 +1,262 @@
+// Selective scan, forward, with a COMPLEX diagonal state matrix for gfx950:
+//     x_{l,n} = a(Delta_l, A[d,n]) x_{l-1,n} + g(Delta_l, A[d,n]) Bm[b,l,n] u[b,d,l]        (complex)
+//     y[b,d,l] = Re( sum_n Cm[b,l,n] x_{l,n} ) + Dskip[d] u[b,d,l],  then the optional gate
+// (Eq. 2 of the paper with the output taken as Re(C x): the complex-diagonal layers of Sec. 2.2.1 with an
+// input-dependent step size and input-dependent maps).
+//
+// Same mapping as the real forward kernel: time on lanes (a lane owns T = 8 consecutive steps), one wavefront per
+// channel, the 8 wavefronts of a workgroup share the staged Bm/Cm tile.  The complex maps stay in LDS in their I/O
+// type (a bf16 pair is one 32-bit word, so the tile is as large as the real kernel's fp32 tile) and are copied there
+// word by word.  The affine pairs are complex: one Hillis-Steele step composes (P,S) o (P',S') = (P P', P S' + S)
+// with four DPP reads and eight multiply-adds.  Per-state values that are uniform over the wavefront (A, the carried
+// state) live one per lane and are read with v_readlane, so the loop over states stays rolled.
+#include "kernels.hpp"
+#include "scan_common.hpp"
+
+namespace lrnnx {
+
+namespace {
+
+template <typename IO> struct cword;                   // one complex number in the I/O type, as stored in LDS
+template <> struct cword<bf16_t> {
+    using type = uint32_t;
+    static __device__ __forceinline__ float2 unpack(uint32_t w) { return make_float2(i2f((int)(w << 16)), i2f((int)(w & 0xFFFF0000u))); }
+};
+template <> struct cword<float> {
+    using type = float2;
+    static __device__ __forceinline__ float2 unpack(float2 w) { return w; }
+};
+
+constexpr float kInv2Pi = 0.15915494309189535f;
+
+// a = exp(dt A) for complex A = (Ar, Ai): e^{dt Ar} (cos(dt Ai), sin(dt Ai)); v_sin/v_cos take revolutions
+__device__ __forceinline__ float2 cexp_dt(float dt, float A2r, float Arev) {
+    const float e = exp2_fast(dt * A2r);
+    const float rev = dt * Arev;
+    return make_float2(e * __builtin_amdgcn_cosf(rev), e * __builtin_amdgcn_sinf(rev));
+}
+
+struct CCoef {
+    float Ar, Ai;       // A
+    float A2r, Arev;    // Ar * log2(e), Ai / (2 pi): arguments of the hardware exp2 / sin / cos
+    float iAr, iAi;     // 1 / A
+};
+__device__ __forceinline__ CCoef make_ccoef(float Ar, float Ai) {
+    CCoef c;
+    c.Ar = Ar; c.Ai = Ai; c.A2r = Ar * kLog2e; c.Arev = Ai * kInv2Pi;
+    const float den = Ar * Ar + Ai * Ai;
+    const float r = den > 0.0f ? rcp_fast(den) : 0.0f;
+    c.iAr = Ar * r; c.iAi = -Ai * r;
+    return c;
+}
+
+// multiplier a and input gain g of one step (schemes of Sec. 3, complex arithmetic)
+template <int DISC>
+__device__ __forceinline__ void cdisc_ag(float dt, const CCoef &c, float2 &a, float2 &g) {
+    if constexpr (DISC == DISC_BILINEAR) {
+        const float hr = 0.5f * dt * c.Ar, hi = 0.5f * dt * c.Ai;           // dt A / 2
+        const float wr = 1.0f - hr, wi = -hi;                               // 1 - dt A / 2
+        const float r = rcp_fast(wr * wr + wi * wi);
+        const float ir = wr * r, ii = -wi * r;                              // 1 / (1 - dt A / 2)
+        a = make_float2((1.0f + hr) * ir - hi * ii, (1.0f + hr) * ii + hi * ir);
+        g = make_float2(dt * ir, dt * ii);
+    } else {
+        a = cexp_dt(dt, c.A2r, c.Arev);
+        if constexpr (DISC == DISC_ZOH_S6) g = make_float2(dt, 0.0f);
+        else if constexpr (DISC == DISC_DIRAC) g = make_float2(1.0f, 0.0f);
+        else {                                                              // exact ZOH: (a - 1) / A
+            const float zr = dt * c.Ar, zi = dt * c.Ai;
+            // small |z|: dt (1 + z/2 + z^2/6 + z^3/24), Horner in complex arithmetic
+            float pr = 1.0f + zr * 0.25f, pi = zi * 0.25f;                  // 1 + z/4
+            float tr = pr * zr - pi * zi, ti = pr * zi + pi * zr;           // z (1 + z/4)
+            pr = 1.0f + tr * 0.33333334f; pi = ti * 0.33333334f;            // 1 + z/3 (1 + z/4)
+            tr = pr * zr - pi * zi; ti = pr * zi + pi * zr;
+            pr = 1.0f + tr * 0.5f; pi = ti * 0.5f;                          // 1 + z/2 (1 + z/3 (1 + z/4))
+            const float sr = dt * pr, si = dt * pi;
+            const float mr = a.x - 1.0f, mi = a.y;
+            const float dr = mr * c.iAr - mi * c.iAi, di = mr * c.iAi + mi * c.iAr;
+            const bool small = zr * zr + zi * zi < 0.015625f;
+            g = make_float2(small ? sr : dr, small ? si : di);
+        }
+    }
+}
+
+// One Hillis-Steele step on a complex affine pair.  Lanes without a source lane (or in a masked row) read the
+// identity pair, which leaves them unchanged.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void cpair_step(float2 &P, float2 &S) {
+    const float qr = dpp<CTRL, ROW_MASK>(1.0f, P.x), qi = dpp<CTRL, ROW_MASK>(0.0f, P.y);
+    const float tr = dpp<CTRL, ROW_MASK>(0.0f, S.x), ti = dpp<CTRL, ROW_MASK>(0.0f, S.y);
+    S = make_float2(__builtin_fmaf(P.x, tr, __builtin_fmaf(-P.y, ti, S.x)),
+                    __builtin_fmaf(P.x, ti, __builtin_fmaf(P.y, tr, S.y)));
+    P = make_float2(P.x * qr - P.y * qi, P.x * qi + P.y * qr);
+}
+__device__ __forceinline__ void cwave_scan_fwd(float2 &P, float2 &S) {
+    cpair_step<0x111, 0xF>(P, S);
+    cpair_step<0x112, 0xF>(P, S);
+    cpair_step<0x114, 0xF>(P, S);
+    cpair_step<0x118, 0xF>(P, S);
+    cpair_step<DPP_ROW_BCAST15, 0xA>(P, S);
+    cpair_step<DPP_ROW_BCAST31, 0xC>(P, S);
+}
+
+}  // namespace
+
+template <typename IO, int N, int T, int W, int DISC>
+__global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
+    using CW = typename cword<IO>::type;
+    constexpr int TQ = T / 4;
+    constexpr int QS = 256 + (TQ > 1 ? 32 / TQ : 0);   // words per quarter-plane, padded against bank conflicts on staging
+    constexpr int PLANE = TQ * QS;                     // words per state index n
+    constexpr int TILE = 64 * T;
+    static_assert(T % 4 == 0, "steps per lane");
+    __shared__ __attribute__((aligned(16))) CW sB[N * PLANE];
+    __shared__ __attribute__((aligned(16))) CW sC[N * PLANE];
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int b = blockIdx.y;
+    const int d_raw = blockIdx.x * W + w;
+    const bool active = d_raw < p.D;
+    const int d = active ? d_raw : p.D - 1;
+    const int64_t L = p.L;
+    const int64_t ntiles = (L + TILE - 1) / TILE;
+    const int64_t row = (int64_t)b * p.D + d;
+    const bool vec = p.vec != 0;
+
+    const IO *urow = reinterpret_cast<const IO *>(p.u) + b * p.u_sb + d * p.u_sd;
+    const IO *drow = reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd;
+    const IO *zrow = p.z ? reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd : nullptr;
+    IO *yrow = reinterpret_cast<IO *>(p.y) + b * p.y_sb + d * p.y_sd;
+    const CW *Bm = reinterpret_cast<const CW *>(p.Bm) + (int64_t)b * L * N;
+    const CW *Cm = reinterpret_cast<const CW *>(p.Cm) + (int64_t)b * L * N;
+
+    // lane n holds the constants and the carried state of state n
+    float Arv = 0.0f, Aiv = 0.0f, xrv = 0.0f, xiv = 0.0f;
+    if (lane < N) {
+        const float2 Av = p.A[d * N + lane];
+        Arv = Av.x; Aiv = Av.y;
+        if (p.x0) { const float2 x0 = p.x0[row * N + lane]; xrv = x0.x; xiv = x0.y; }
+    }
+    const float Dsk = p.Dskip ? p.Dskip[d] : 0.0f;
+    const float bias = p.bias ? p.bias[d] : 0.0f;
+
+    for (int64_t tile = 0; tile < ntiles; ++tile) {
+        const int64_t l0 = tile * TILE;
+        const int64_t ll = l0 + lane * T;
+
+        // ---- stage the Bm/Cm tile (all wavefronts): plain copy of complex words, layout [n][t/4][lane][t%4]
+        __syncthreads();
+        for (int r = threadIdx.x; r < TILE; r += W * 64) {
+            const int64_t l = l0 + r;
+            const int off = ((r % T) / 4) * QS + (r / T) * 4 + (r % 4);
+            CW bw[N], cw[N];
+            if (l < L) {
+#pragma unroll
+                for (int k = 0; k < N; ++k) { bw[k] = Bm[l * N + k]; cw[k] = Cm[l * N + k]; }
+            } else {
+#pragma unroll
+                for (int k = 0; k < N; ++k) { bw[k] = CW{}; cw[k] = CW{}; }
+            }
+#pragma unroll
+            for (int k = 0; k < N; ++k) { sB[k * PLANE + off] = bw[k]; sC[k * PLANE + off] = cw[k]; }
+        }
+        __syncthreads();
+        if (!active) continue;
+
+        // ---- this lane's T steps of u and Delta
+        float uv[T], dl[T], yv[T];
+        load_seg<IO, T>(urow, ll, L, vec, uv);
+        load_seg<IO, T>(drow, ll, L, vec, dl);
+        float sum_dl = 0.0f;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            float s = dl[t] + bias, sp, sg;
+            if (p.softplus) softplus_sigmoid(s, sp, sg); else sp = s;
+            dl[t] = (ll + t < L) ? sp : 0.0f;         // steps past the end are the identity map (a = 1, b = 0)
+            uv[t] = (ll + t < L) ? uv[t] : 0.0f;
+            sum_dl += dl[t];
+            yv[t] = Dsk * uv[t];
+        }
+
+#pragma unroll 1
+        for (int n = 0; n < N; ++n) {
+            const CCoef cc = make_ccoef(readlane(Arv, n), readlane(Aiv, n));
+            const float2 xc = make_float2(readlane(xrv, n), readlane(xiv, n));
+            float2 a[T], bb[T];
+            float2 P = make_float2(1.0f, 0.0f), S = make_float2(0.0f, 0.0f);
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const float2 Bv = cword<IO>::unpack(sB[n * PLANE + (t / 4) * QS + lane * 4 + (t % 4)]);
+                float2 g;
+                cdisc_ag<DISC>(dl[t], cc, a[t], g);
+                const float gu_r = g.x * uv[t], gu_i = g.y * uv[t];
+                bb[t] = make_float2(gu_r * Bv.x - gu_i * Bv.y, gu_r * Bv.y + gu_i * Bv.x);
+                S = make_float2(__builtin_fmaf(a[t].x, S.x, __builtin_fmaf(-a[t].y, S.y, bb[t].x)),
+                                __builtin_fmaf(a[t].x, S.y, __builtin_fmaf(a[t].y, S.x, bb[t].y)));
+                if constexpr (DISC == DISC_BILINEAR) P = make_float2(P.x * a[t].x - P.y * a[t].y, P.x * a[t].y + P.y * a[t].x);
+            }
+            if constexpr (DISC != DISC_BILINEAR) P = cexp_dt(sum_dl, cc.A2r, cc.Arev);   // product of the T multipliers
+            if (lane == 0) {                                          // the carried state enters through lane 0
+                S = make_float2(__builtin_fmaf(P.x, xc.x, __builtin_fmaf(-P.y, xc.y, S.x)),
+                                __builtin_fmaf(P.x, xc.y, __builtin_fmaf(P.y, xc.x, S.y)));
+            }
+            cwave_scan_fwd(P, S);
+            float2 x = make_float2(dpp<DPP_WAVE_SHR1>(xc.x, S.x), dpp<DPP_WAVE_SHR1>(xc.y, S.y));
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const float2 Cv = cword<IO>::unpack(sC[n * PLANE + (t / 4) * QS + lane * 4 + (t % 4)]);
+                x = make_float2(__builtin_fmaf(a[t].x, x.x, __builtin_fmaf(-a[t].y, x.y, bb[t].x)),
+                                __builtin_fmaf(a[t].x, x.y, __builtin_fmaf(a[t].y, x.x, bb[t].y)));
+                yv[t] = __builtin_fmaf(Cv.x, x.x, __builtin_fmaf(-Cv.y, x.y, yv[t]));   // Re(C x)
+            }
+            xrv = writelane(xrv, readlane(x.x, 63), n);               // lane 63 ends on the tile's last step
+            xiv = writelane(xiv, readlane(x.y, 63), n);
+        }
+
+        if (zrow) {
+            float zv[T];
+            load_seg<IO, T>(zrow, ll, L, vec, zv);
+#pragma unroll
+            for (int t = 0; t < T; ++t) yv[t] *= zv[t] * sigmoid_fast(zv[t]);
+        }
+        store_seg<IO, T>(yrow, ll, L, vec, yv);
+    }
+
+    if (active && lane < N && p.x_last) p.x_last[row * N + lane] = make_float2(xrv, xiv);
+}
+
+// ---------------------------------------------------------------- launchers
+template <typename IO, int N, int DISC>
+static hipError_t launch_cfwd_n(const CFwdParams &p, hipStream_t s) {
+    constexpr int W = 8, T = 8;
+    dim3 grid((p.D + W - 1) / W, p.B);
+    hipLaunchKernelGGL((k_ss_cfwd<IO, N, T, W, DISC>), grid, dim3(W * 64), 0, s, p);
+    return hipGetLastError();
+}
+template <typename IO, int DISC>
+static hipError_t launch_cfwd_disc(const CFwdParams &p, hipStream_t s) {
+    switch (p.N) {
+        case 1: return launch_cfwd_n<IO, 1, DISC>(p, s);
+        case 2: return launch_cfwd_n<IO, 2, DISC>(p, s);
+        case 4: return launch_cfwd_n<IO, 4, DISC>(p, s);
+        case 8: return launch_cfwd_n<IO, 8, DISC>(p, s);
+        case 16: return launch_cfwd_n<IO, 16, DISC>(p, s);
+    }
+    return hipErrorInvalidValue;
+}
+template <typename IO>
+static hipError_t launch_cfwd_io(const CFwdParams &p, int disc, hipStream_t s) {
+    switch (disc) {
+        case DISC_ZOH_S6: return launch_cfwd_disc<IO, DISC_ZOH_S6>(p, s);
+        case DISC_ZOH: return launch_cfwd_disc<IO, DISC_ZOH>(p, s);
+        case DISC_BILINEAR: return launch_cfwd_disc<IO, DISC_BILINEAR>(p, s);
+        case DISC_DIRAC: return launch_cfwd_disc<IO, DISC_DIRAC>(p, s);
+    }
+    return hipErrorInvalidValue;
+}
+hipError_t launch_ss_cfwd(const CFwdParams &p, int io_dtype, int disc, hipStream_t s) {
+    return io_dtype == 1 ? launch_cfwd_io<bf16_t>(p, disc, s) : launch_cfwd_io<float>(p, disc, s);
+}
+
+}  // namespace lrnnx

@@ -70,6 +70,27 @@ def make_selective(B, D, N, L, io="f32", gate=False, bias=("const", -2.0), seed=
     return out
 
 
+def make_selective_complex(B, D, N, L, io="f32", gate=False, seed=0, with_x0=False):
+    """Inputs of the selective scan with a complex diagonal A: as make_selective, with
+    A[d,n] = -exp(U(-1,1)) + i U(-10,10) (complex64) and Bm, Cm = (N(0,1) + i N(0,1)) / sqrt(2), stored as
+    float32 [B,L,N,2] (re, im) rounded to the I/O type; delta_bias ~ U(-4,-2) per channel; x0 complex64."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    f32 = np.float32
+    out = {}
+    out["A"] = (-np.exp(rng.uniform(-1.0, 1.0, size=(D, N))) + 1j * rng.uniform(-10.0, 10.0, size=(D, N))).astype(np.complex64)
+    out["Dskip"] = rng.standard_normal(D, dtype=f32)
+    out["delta_bias"] = rng.uniform(-4.0, -2.0, size=D).astype(f32)
+    s = f32(1.0 / np.sqrt(2.0))
+    out["Bm"] = _io_round(rng.standard_normal((B, L, N, 2), dtype=f32) * s, io)
+    out["Cm"] = _io_round(rng.standard_normal((B, L, N, 2), dtype=f32) * s, io)
+    out["u"] = _io_round(rng.standard_normal((B, D, L), dtype=f32), io)
+    out["delta"] = _io_round(rng.standard_normal((B, D, L), dtype=f32), io)
+    out["z"] = _io_round(rng.standard_normal((B, D, L), dtype=f32), io) if gate else None
+    out["x0"] = ((rng.standard_normal((B, D, N)) + 1j * rng.standard_normal((B, D, N))).astype(np.complex64)
+                 if with_x0 else None)
+    return out
+
+
 def make_packed(D, N, lengths, io="f32", gate=True, seed=0, bc_groups=1, gap=0):
     """A packed variable-length batch: sequences of the given lengths one after the other on one time axis
     (`gap` unused steps before the first and after the last).  Same distributions as make_selective; returns the

@@ -1,0 +1,81 @@
+"""GPU parity: lrnnx_selective_scan_fwd_complex (complex diagonal A, complex maps, y = Re(C x) + D u; through the
+C ABI) against the fp64 oracle.  Tolerances as for the real scan: 1e-4 (fp32 I/O), 2e-2 (bf16 I/O) of max|y|."""
+import numpy as np
+import pytest
+
+from paper_2602_08810_amd import workloads
+from _util import TOL, dev, host, rel_err
+
+pytestmark = pytest.mark.gpu
+
+DISCS = ["zoh_s6", "zoh", "bilinear", "dirac"]
+
+
+@pytest.fixture(scope="module")
+def api():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2602_08810_amd import api as _api
+    _api.lib()
+    return _api
+
+
+def _cplx(a):
+    return a[..., 0].astype(np.float64) + 1j * a[..., 1].astype(np.float64)
+
+
+def _maps_dev(a, io):
+    """[B,L,N,2] float32 (already rounded) -> the tensor the binding wants for this I/O type."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t.to(torch.bfloat16) if io == "bf16" else torch.view_as_complex(t)
+
+
+def _run(api, oracle, B, D, N, L, io, disc, gate, x0, seed, softplus=True):
+    import torch
+    p = workloads.make_selective_complex(B=B, D=D, N=N, L=L, io=io, gate=gate, seed=seed, with_x0=x0)
+    if not softplus:
+        p["delta"] = workloads._io_round(np.abs(p["delta"]) * 0.1 + 0.01, io)
+        p["delta_bias"] = None
+    t = dict(u=dev(p["u"], io), delta=dev(p["delta"], io), A=torch.from_numpy(p["A"]).cuda(), Bm=_maps_dev(p["Bm"], io),
+             Cm=_maps_dev(p["Cm"], io), Dskip=dev(p["Dskip"]), delta_bias=dev(p["delta_bias"]), z=dev(p["z"], io),
+             x0=None if p["x0"] is None else torch.from_numpy(p["x0"]).cuda())
+    y, x_last = api.lrnnx_selective_scan_fwd_complex(**t, disc=disc, delta_softplus=softplus, return_last_state=True)
+    yr, xr = oracle.selective_scan_fwd_complex(p["u"], p["delta"], p["A"], _cplx(p["Bm"]), _cplx(p["Cm"]), Dskip=p["Dskip"],
+                                               delta_bias=p["delta_bias"], z=p["z"], x0=p["x0"], disc=disc,
+                                               delta_softplus=softplus)
+    assert rel_err(host(y), yr) <= TOL[io], "y"
+    xl = x_last.cpu().numpy()
+    assert max(rel_err(xl.real, xr.real), rel_err(xl.imag, xr.imag)) <= 1e-4, "x_last"
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("disc", DISCS)
+def test_all_discretisations(api, oracle, io, disc):
+    _run(api, oracle, 2, 10, 16, 1300, io, disc, gate=True, x0=True, seed=1)
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("B,D,N,L", [(1, 1, 1, 1), (2, 3, 2, 7), (1, 13, 4, 511), (3, 8, 8, 513), (1, 9, 16, 1025),
+                                     (2, 24, 16, 2048)])
+def test_shapes(api, oracle, io, B, D, N, L):
+    _run(api, oracle, B, D, N, L, io, "zoh_s6", gate=bool(L % 2), x0=bool(D % 2), seed=B + D + N + L)
+
+
+def test_caller_supplied_step_sizes(api, oracle):
+    _run(api, oracle, 2, 6, 16, 700, "f32", "zoh", gate=False, x0=True, seed=5, softplus=False)
+
+
+def test_long_sequence(api, oracle):
+    _run(api, oracle, 1, 8, 16, 20000, "bf16", "zoh_s6", gate=True, x0=False, seed=6)
+
+
+def test_real_data_reproduces_the_real_kernel(api):
+    """With zero imaginary parts the complex entry point computes what the real one does."""
+    import torch
+    p = workloads.make_selective(B=2, D=12, N=16, L=900, io="f32", gate=True, seed=7, with_dy=False)
+    t = dict(u=dev(p["u"]), delta=dev(p["delta"]), Dskip=dev(p["Dskip"]), delta_bias=dev(p["delta_bias"]), z=dev(p["z"]))
+    y = api.lrnnx_selective_scan_fwd(**t, A=dev(p["A"]), Bm=dev(p["Bm"]), Cm=dev(p["Cm"]))
+    yc = api.lrnnx_selective_scan_fwd_complex(**t, A=dev(p["A"]).to(torch.complex64), Bm=dev(p["Bm"]).to(torch.complex64),
+                                              Cm=dev(p["Cm"]).to(torch.complex64))
+    assert float((y - yc).abs().max()) <= 2e-5 * float(y.abs().max())
