@@ -278,6 +278,20 @@ def _other_configs(api, torch, dev):
                                                   "hbm_GBs": nb / tt / 1e9, "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
         del ad, bd, xd, wsd
 
+    # forward with a complex diagonal A and complex maps at config 2's shape (bf16 I/O)
+    Bc, Dc, Nc, Lc = 8, 1536, 16, 2048
+    tc = sel(Bc, Dc, Nc, Lc, True)
+    Ac = torch.complex(tc["A"], torch.rand(Dc, Nc, device=dev, generator=g) * 20 - 10)
+    Bmc = (torch.randn(Bc, Lc, Nc, 2, device=dev, generator=g) * 0.70710678).to(bf)
+    Cmc = (torch.randn(Bc, Lc, Nc, 2, device=dev, generator=g) * 0.70710678).to(bf)
+    yc = torch.empty_like(tc["u"])
+    tt = _time(torch, lambda: api.lrnnx_selective_scan_fwd_complex(tc["u"], tc["delta"], Ac, Bmc, Cmc, Dskip=tc["Dskip"],
+                                                                   delta_bias=tc["delta_bias"], z=tc["z"], out=yc), 10)
+    nb = _selective_bytes(Bc, Dc, Nc, Lc, 2, True, False) + 2 * Bc * Lc * Nc * 2
+    out["complex_fwd_B8_D1536_N16_L2048"] = {"us": tt * 1e6, "elements_per_s": Bc * Dc * Nc * Lc / tt,
+                                             "hbm_GBs": nb / tt / 1e9, "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
+    del tc, Ac, Bmc, Cmc, yc
+
     # single-token step (generation): state [B,D,N] read and written once per token
     Bs, Ds, Ns = 64, 1536, 16
     ts = sel(Bs, Ds, Ns, 1, True)
