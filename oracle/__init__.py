@@ -262,6 +262,25 @@ def diag_scan(a, b, x0=None):
     return x
 
 
+def diag_scan_bwd(a, b, gx, x0=None):
+    """Gradients (da, db [B,L,P], dx0 [B,P]) of a real loss through x_k = a_k x_{k-1} + b_k, gx being the gradient
+    reaching the states; real or complex like diag_scan."""
+    cplx = any(np.iscomplexobj(t) for t in (a, b, gx) if t is not None) or (x0 is not None and np.iscomplexobj(x0))
+    conv = _c128 if cplx else _f64
+    a, b, gx = conv(a), conv(b), conv(gx)
+    Bsz, L, P = b.shape
+    assert a.shape == b.shape == gx.shape
+    x0c = None if x0 is None else conv(x0)
+    dt = np.complex128 if cplx else np.float64
+    da, db, dx0 = np.empty((Bsz, L, P), dtype=dt), np.empty((Bsz, L, P), dtype=dt), np.empty((Bsz, P), dtype=dt)
+    cp = lambda t: ctypes.c_void_p(0) if t is None else t.ctypes.data_as(ctypes.c_void_p)
+    rc = _load().lrnnx_oracle_diag_scan_bwd(ctypes.c_int(Bsz), ctypes.c_long(L), ctypes.c_int(P), ctypes.c_int(int(cplx)),
+                                            cp(a), cp(b), cp(x0c), cp(gx), cp(da), cp(db), cp(dx0))
+    if rc != 0:
+        raise ValueError(f"oracle diag scan bwd: bad arguments (rc={rc})")
+    return da, db, dx0
+
+
 def lti_diag_scan_bwd(lam, v, gx, x0=None):
     """Gradients (dv [B,L,P], dlam [P], dx0 [B,P]) of a real loss with dLoss/dRe(x) + i dLoss/dIm(x) = gx."""
     lam, v, gx = _c128(lam), _c128(v), _c128(gx)

@@ -384,6 +384,54 @@ int lrnnx_oracle_diag_scan(int B, long L, int P, int is_complex,
     return 0;
 }
 
+/* Backward of the recurrence with caller-supplied coefficients x_k = a_k x_{k-1} + b_k.  gx_k is the gradient of a
+ * real loss reaching x_k (for complex data: dLoss/dRe + i dLoss/dIm, and the chain rule multiplies by conjugates):
+ *     g_k  = gx_k + conj(a_{k+1}) g_{k+1},  g_{L+1} = 0
+ *     db_k = g_k,   da_k = conj(x_{k-1}) g_k,   dx0 = conj(a_1) g_1            (k = 1..L, x_0 the initial state)
+ * The states are recomputed here from (a, b, x0).                                                              */
+int lrnnx_oracle_diag_scan_bwd(int B, long L, int P, int is_complex,
+                               const double *a, const double *b, const double *x0, const double *gx,
+                               double *da, double *db, double *dx0)
+{
+    if (B < 0 || L < 0 || P < 0) return 1;
+    long rows = (long)B * P;
+    int c = is_complex ? 2 : 1;
+#pragma omp parallel
+    {
+        double *xs = (double *)malloc(sizeof(double) * 2 * (size_t)(L + 1));
+#pragma omp for schedule(static)
+        for (long row = 0; row < rows; ++row) {
+            int bb = (int)(row / P), p = (int)(row % P);
+            xs[0] = x0 ? x0[c * row] : 0.0;
+            xs[1] = (x0 && is_complex) ? x0[c * row + 1] : 0.0;
+            for (long k = 0; k < L; ++k) {                          /* x after step k in slot k+1 */
+                long idx = c * (((long)bb * L + k) * P + p);
+                double ar = a[idx], ai = is_complex ? a[idx + 1] : 0.0;
+                double br = b[idx], bi = is_complex ? b[idx + 1] : 0.0;
+                xs[2 * (k + 1)]     = ar * xs[2 * k] - ai * xs[2 * k + 1] + br;
+                xs[2 * (k + 1) + 1] = ar * xs[2 * k + 1] + ai * xs[2 * k] + bi;
+            }
+            double hr = 0.0, hi = 0.0;                               /* conj(a_{k+1}) g_{k+1}, carried backwards */
+            for (long k = L - 1; k >= 0; --k) {
+                long idx = c * (((long)bb * L + k) * P + p);
+                double gr = gx[idx] + hr, gi = (is_complex ? gx[idx + 1] : 0.0) + hi;
+                db[idx] = gr;
+                da[idx] = xs[2 * k] * gr + xs[2 * k + 1] * gi;       /* conj(x_{k-1}) g_k */
+                if (is_complex) {
+                    db[idx + 1] = gi;
+                    da[idx + 1] = xs[2 * k] * gi - xs[2 * k + 1] * gr;
+                }
+                double ar = a[idx], ai = is_complex ? a[idx + 1] : 0.0;
+                hr = ar * gr + ai * gi;                              /* conj(a_k) g_k */
+                hi = ar * gi - ai * gr;
+            }
+            if (dx0) { dx0[c * row] = hr; if (is_complex) dx0[c * row + 1] = hi; }
+        }
+        free(xs);
+    }
+    return 0;
+}
+
 /* Backward of the time-invariant complex-diagonal recurrence (the adjoint recurrence of Sec. 2.2.1's
  * x_k = lambda x_{k-1} + v_k).  A real loss depends on x through gx_k = dLoss/dRe(x_k) + i dLoss/dIm(x_k);
  * gradients of complex quantities follow the same convention.  Because x_k is holomorphic in x_{k-1}, v_k and

@@ -705,3 +705,61 @@ def test_complex_forward_with_constant_step_is_the_lti_scan(oracle):
                                               np.tile(Cv, (1, L, 1)), delta_softplus=False)
     np.testing.assert_allclose(y[0, 0], (x[0] * Cv[None, :]).sum(-1).real, rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(xl[0, 0], x[0, -1], rtol=1e-12)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Backward of the caller-supplied (a_k, b_k) scan.
+# ---------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cplx", [False, True])
+def test_diag_scan_bwd_finite_differences(oracle, cplx):
+    rng = np.random.default_rng(71)
+    B, L, P = 2, 7, 3
+    draw = (lambda *s: rng.standard_normal(s) + 1j * rng.standard_normal(s)) if cplx else (lambda *s: rng.standard_normal(s))
+    a, b, x0, w = draw(B, L, P) * 0.7, draw(B, L, P), draw(B, P), draw(B, L, P)
+    da, db, dx0 = oracle.diag_scan_bwd(a, b, w, x0=x0)
+    loss = lambda a_, b_, x0_: float(np.sum((np.conj(w) * oracle.diag_scan(a_, b_, x0=x0_)).real))
+    h = 1e-6
+    for which, grad in ((0, da), (1, db), (2, dx0)):
+        for idx in np.ndindex(grad.shape):
+            num = 0.0
+            for unit in ((1.0, 1j) if cplx else (1.0,)):
+                args = [a.copy(), b.copy(), x0.copy()]
+                args[which][idx] += h * unit
+                up = loss(*args)
+                args[which][idx] -= 2 * h * unit
+                num = num + unit * (up - loss(*args)) / (2 * h)
+            assert abs(num - grad[idx]) <= 1e-7 * (1 + abs(grad[idx])), (which, idx, num, grad[idx])
+
+
+def test_diag_scan_bwd_one_step_and_constant_coefficient_cases(oracle):
+    rng = np.random.default_rng(72)
+    c = lambda *s: rng.standard_normal(s) + 1j * rng.standard_normal(s)
+    a, b, x0, w = c(2, 1, 3), c(2, 1, 3), c(2, 3), c(2, 1, 3)
+    da, db, dx0 = oracle.diag_scan_bwd(a, b, w, x0=x0)
+    np.testing.assert_allclose(db, w, rtol=1e-15)
+    np.testing.assert_allclose(da[:, 0], np.conj(x0) * w[:, 0], rtol=1e-14)
+    np.testing.assert_allclose(dx0, np.conj(a[:, 0]) * w[:, 0], rtol=1e-14)
+    # a_k = lambda for every k: db is the LTI backward's dv, dx0 agrees, and dlambda is the sum of da over b and k
+    lam, v, x0l, wl = _lti_case(73, B=2, L=30, P=4)
+    dv, dlam, dx0l = oracle.lti_diag_scan_bwd(lam, v, wl, x0=x0l)
+    da, db, dx0 = oracle.diag_scan_bwd(np.broadcast_to(lam, v.shape), v, wl, x0=x0l)
+    np.testing.assert_allclose(db, dv, rtol=1e-13)
+    np.testing.assert_allclose(dx0, dx0l, rtol=1e-13)
+    np.testing.assert_allclose(da.sum(axis=(0, 1)), dlam, rtol=1e-12)
+
+
+def test_diag_scan_bwd_matches_library_autograd_on_real_gates(oracle):
+    import torch
+    rng = np.random.default_rng(74)
+    a, b, x0, w = rng.uniform(0.2, 1.0, (2, 9, 3)), rng.standard_normal((2, 9, 3)), rng.standard_normal((2, 3)), rng.standard_normal((2, 9, 3))
+    ta, tb, tx0 = (torch.tensor(t, requires_grad=True) for t in (a, b, x0))
+    x, xs = tx0, []
+    for k in range(9):
+        x = ta[:, k] * x + tb[:, k]
+        xs.append(x)
+    (torch.tensor(w) * torch.stack(xs, 1)).sum().backward()
+    da, db, dx0 = oracle.diag_scan_bwd(a, b, w, x0=x0)
+    np.testing.assert_allclose(da, ta.grad.numpy(), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(db, tb.grad.numpy(), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(dx0, tx0.grad.numpy(), rtol=1e-12, atol=1e-14)
+    assert da.dtype == np.float64
