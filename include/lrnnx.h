@@ -257,6 +257,33 @@ typedef struct lrnnx_diag_scan_args {
 
 int lrnnx_diag_scan(const lrnnx_diag_scan_args *args);
 
+/* ------------------------------------------------------------------ backward of lrnnx_diag_scan
+ * For a real loss, with gx[b,k,p] the gradient reaching x[b,k,p] (complex data: dLoss/dRe + i dLoss/dIm, the chain
+ * rule then multiplies by conjugates; real data: no conjugates):
+ *     g_k  = gx_k + conj(a_{k+1}) g_{k+1}   (g beyond the last step is 0),
+ *     db_k = g_k,    da_k = conj(x_{k-1}) g_k   (x_{-1} = x0),    dx0 = conj(a_0) g_0.
+ * x is the array the forward call wrote, a and x0 the forward call's.  All of a, x, gx, da, db are [B,L,P] of
+ * `dtype` (LRNNX_F32 or LRNNX_C64), contiguous, aligned to the element size; db may alias gx; da must not alias an
+ * input.  dx0 [B,P] or NULL.  Results are bitwise reproducible.  workspace:
+ * lrnnx_workspace_bytes(LRNNX_WS_DIAG_BWD, B, P, 0, L, dtype), contents on entry irrelevant.                  */
+typedef struct lrnnx_diag_scan_bwd_args {
+    size_t struct_size;
+    int32_t B, P;
+    int64_t L;
+    int32_t dtype, reserved;
+    const void *a;          /* [B,L,P] */
+    const void *x;          /* [B,L,P] forward states */
+    const void *x0;         /* [B,P] or NULL */
+    const void *gx;         /* [B,L,P] */
+    void *da;               /* [B,L,P] out */
+    void *db;               /* [B,L,P] out */
+    void *dx0;              /* [B,P] out or NULL */
+    void *workspace;    size_t workspace_bytes;
+    void *stream;
+} lrnnx_diag_scan_bwd_args;
+
+int lrnnx_diag_scan_bwd(const lrnnx_diag_scan_bwd_args *args);
+
 /* ------------------------------------------------------------------ backward of the LTI scan
  * Adjoint of the recurrence above (Sec. 2.2.1; the paper trains these layers through the same scan).  For a real
  * loss, the gradient of a complex quantity q is dLoss/dRe(q) + i dLoss/dIm(q) (the convention of complex
@@ -329,11 +356,12 @@ typedef struct lrnnx_lti_step_args {
 int lrnnx_lti_step(const lrnnx_lti_step_args *args);
 
 /* ------------------------------------------------------------------ queries (host only, no GPU needed) */
-typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2, LRNNX_WS_LTI_BWD = 3, LRNNX_WS_DIAG = 4 } lrnnx_ws_kind;
+typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2, LRNNX_WS_LTI_BWD = 3, LRNNX_WS_DIAG = 4,
+               LRNNX_WS_DIAG_BWD = 5 } lrnnx_ws_kind;
 
 /* Bytes of device scratch the call may need (the largest over its paths).
- * For LRNNX_WS_LTI, LRNNX_WS_LTI_BWD and LRNNX_WS_DIAG pass P as D and 0 for N (LRNNX_WS_DIAG: io_dtype is
- * LRNNX_F32 or LRNNX_C64).  Returns 0 for invalid sizes.   */
+ * For LRNNX_WS_LTI, LRNNX_WS_LTI_BWD, LRNNX_WS_DIAG and LRNNX_WS_DIAG_BWD pass P as D and 0 for N (the DIAG kinds:
+ * io_dtype is LRNNX_F32 or LRNNX_C64).  Returns 0 for invalid sizes.   */
 size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t L, int io_dtype);
 
 const char *lrnnx_status_string(int status);

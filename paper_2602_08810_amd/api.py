@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("LRNNX_LIB", os.path.join(_HERE, "liblrnnx.so"))   # L
 F32, BF16, C64 = 0, 1, 2
 DISC = {"zoh_s6": 0, "zoh": 1, "bilinear": 2, "dirac": 3}
 PATH = {"auto": 0, "single_pass": 1, "chunk_carry": 2}
-WS_FWD, WS_BWD, WS_LTI, WS_LTI_BWD, WS_DIAG = 0, 1, 2, 3, 4
+WS_FWD, WS_BWD, WS_LTI, WS_LTI_BWD, WS_DIAG, WS_DIAG_BWD = 0, 1, 2, 3, 4, 5
 STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported", 3: "workspace", 4: "launch"}
 
 _vp, _i32, _i64, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
@@ -99,6 +99,14 @@ class DiagScanArgs(ctypes.Structure):
     ]
 
 
+class DiagScanBwdArgs(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", _sz), ("B", _i32), ("P", _i32), ("L", _i64), ("dtype", _i32), ("reserved", _i32),
+        ("a", _vp), ("x", _vp), ("x0", _vp), ("gx", _vp), ("da", _vp), ("db", _vp), ("dx0", _vp),
+        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
+    ]
+
+
 class StepArgs(ctypes.Structure):
     _fields_ = [
         ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32),
@@ -137,6 +145,8 @@ def lib():
         L.lrnnx_lti_diag_scan_bwd.restype = ctypes.c_int
         L.lrnnx_diag_scan.argtypes = [ctypes.POINTER(DiagScanArgs)]
         L.lrnnx_diag_scan.restype = ctypes.c_int
+        L.lrnnx_diag_scan_bwd.argtypes = [ctypes.POINTER(DiagScanBwdArgs)]
+        L.lrnnx_diag_scan_bwd.restype = ctypes.c_int
         L.lrnnx_selective_step.argtypes = [ctypes.POINTER(StepArgs)]
         L.lrnnx_lti_step.argtypes = [ctypes.POINTER(LtiStepArgs)]
         L.lrnnx_selective_step.restype = ctypes.c_int
@@ -489,6 +499,36 @@ def lrnnx_diag_scan(a, b, x0=None, return_last_state=False, out=None, workspace=
     g.stream = _stream()
     _check(lib().lrnnx_diag_scan(ctypes.byref(g)))
     return (x, x_last) if return_last_state else x
+
+
+def lrnnx_diag_scan_bwd(a, x, gx, x0=None, want_dx0=True, workspace=None):
+    """(da, db [B,L,P], dx0 [B,P] or None) from the forward call's a, saved states x and the incoming gradient gx;
+    see lrnnx_diag_scan_bwd_args."""
+    for t, name in ((a, "a"), (x, "x"), (gx, "gx")):
+        if t.dtype != a.dtype or not t.is_contiguous() or t.shape != a.shape:
+            raise ValueError(f"{name}: expected a contiguous tensor of the dtype and shape of a")
+    if a.dtype not in (torch.float32, torch.complex64) or a.dim() != 3:
+        raise TypeError("a must be a float32 or complex64 [B,L,P] tensor")
+    Bsz, L, P = a.shape
+    dt = C64 if a.dtype == torch.complex64 else F32
+    g = DiagScanBwdArgs()
+    g.struct_size = ctypes.sizeof(DiagScanBwdArgs)
+    g.B, g.P, g.L, g.dtype = Bsz, P, L, dt
+    g.a, g.x, g.gx = a.data_ptr(), x.data_ptr(), gx.data_ptr()
+    if x0 is not None:
+        if x0.dtype != a.dtype or not x0.is_contiguous() or tuple(x0.shape) != (Bsz, P):
+            raise ValueError("x0: expected a contiguous [B,P] tensor of the dtype of a")
+        g.x0 = x0.data_ptr()
+    da, db = torch.empty_like(a), torch.empty_like(a)
+    dx0 = torch.empty((Bsz, P), dtype=a.dtype, device=a.device) if want_dx0 else None
+    g.da, g.db, g.dx0 = da.data_ptr(), db.data_ptr(), _ptr(dx0)
+    if workspace is None:
+        nbytes = lrnnx_workspace_bytes(WS_DIAG_BWD, Bsz, P, 0, L, dt)
+        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=a.device)
+    g.workspace, g.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    g.stream = _stream()
+    _check(lib().lrnnx_diag_scan_bwd(ctypes.byref(g)))
+    return da, db, dx0
 
 
 def _bd(t, name, io):

@@ -54,6 +54,24 @@ size_t diag_scan_bytes(int64_t B, int64_t P, int64_t L, int is_complex) {
     const int64_t slots = ng * (is_complex ? 2 : 1) + ng / diag_scan_anchor(is_complex) + 1;
     return (size_t)(B * slots * P * 2 * sizeof(float)) + 64 * sizeof(int);
 }
+size_t diag_scan_bwd_bytes(int64_t B, int64_t P, int64_t L, int is_complex) {
+    const int64_t ng = cdiv(L, diag_scan_bwd_group_steps(is_complex));
+    const int64_t slots = ng * (is_complex ? 2 : 1) + ng / diag_scan_anchor(is_complex) + 1;
+    return (size_t)(B * slots * P * 2 * sizeof(float)) + 64 * sizeof(int);
+}
+// lays the chain workspace of a caller-coefficient scan out and returns the fill list that arms it
+FillList set_diag_workspace(DiagParams &p, void *ws) {
+    const int cplx = p.is_complex;
+    const int64_t nT = (int64_t)p.B * p.ngroups * (cplx ? 2 : 1) * p.P;
+    const int64_t nX = (int64_t)p.B * (p.ngroups / diag_scan_anchor(cplx) + 1) * p.P;
+    p.ws_T = reinterpret_cast<float2 *>(ws);
+    p.ws_X = p.ws_T + nT;
+    p.err = reinterpret_cast<int *>(p.ws_X + nX);
+    FillList z{};                                  // every slot starts as "not published", the error word as zero
+    z.ptr[0] = reinterpret_cast<float *>(p.ws_T); z.count[0] = 2 * (nT + nX); z.bits[0] = 0xffffffffu;
+    z.ptr[1] = reinterpret_cast<float *>(p.err);  z.count[1] = 1;
+    return z;
+}
 void set_onepass_workspace(LtiParams &p, void *ws) {
     p.ws_T = reinterpret_cast<float2 *>(ws);
     p.ws_X = p.ws_T + (size_t)p.B * p.ngroups * p.P;
@@ -106,9 +124,10 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
         return two > one ? two : one;
     }
     if (which == LRNNX_WS_LTI_BWD) return lti_onepass_bwd_bytes(B, D, L);
-    if (which == LRNNX_WS_DIAG) {
+    if (which == LRNNX_WS_DIAG || which == LRNNX_WS_DIAG_BWD) {
         if (io_dtype != LRNNX_F32 && io_dtype != LRNNX_C64) return 0;
-        return diag_scan_bytes(B, D, L, io_dtype == LRNNX_C64);
+        return which == LRNNX_WS_DIAG ? diag_scan_bytes(B, D, L, io_dtype == LRNNX_C64)
+                                      : diag_scan_bwd_bytes(B, D, L, io_dtype == LRNNX_C64);
     }
     return 0;
 }
@@ -397,16 +416,37 @@ int lrnnx_diag_scan(const lrnnx_diag_scan_args *a) {
     p.B = a->B; p.P = a->P; p.L = a->L;
     p.is_complex = cplx; p.ngroups = (int)ng;
     p.a = a->a; p.b = a->b; p.x0 = a->x0; p.x = a->x; p.x_last = a->x_last;
-    const int64_t nT = (int64_t)a->B * ng * (cplx ? 2 : 1) * a->P;
-    const int64_t nX = (int64_t)a->B * (ng / diag_scan_anchor(cplx) + 1) * a->P;
-    p.ws_T = reinterpret_cast<float2 *>(a->workspace);
-    p.ws_X = p.ws_T + nT;
-    p.err = reinterpret_cast<int *>(p.ws_X + nX);
-    FillList z{};                                  // every slot starts as "not published", the error word as zero
-    z.ptr[0] = reinterpret_cast<float *>(p.ws_T); z.count[0] = 2 * (nT + nX); z.bits[0] = 0xffffffffu;
-    z.ptr[1] = reinterpret_cast<float *>(p.err);  z.count[1] = 1;
+    const FillList z = set_diag_workspace(p, a->workspace);
     if (launch_fill(z, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
     return launch_diag_scan(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+}
+
+int lrnnx_diag_scan_bwd(const lrnnx_diag_scan_bwd_args *a) {
+    if (!a || a->struct_size < sizeof(lrnnx_diag_scan_bwd_args)) return LRNNX_ERR_INVALID_ARG;
+    if (a->B < 1 || a->P < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
+    if (a->dtype != LRNNX_F32 && a->dtype != LRNNX_C64) return LRNNX_ERR_INVALID_ARG;
+    if (!a->a || !a->x || !a->gx || !a->da || !a->db) return LRNNX_ERR_INVALID_ARG;
+    if (a->da == a->a || a->da == a->x || a->da == a->gx || a->da == a->db) return LRNNX_ERR_INVALID_ARG;
+    const int cplx = a->dtype == LRNNX_C64;
+    const uintptr_t mask = cplx ? 7u : 3u;
+    for (const void *q : {a->a, a->x, a->x0, a->gx, (const void *)a->da, (const void *)a->db, (const void *)a->dx0})
+        if (reinterpret_cast<uintptr_t>(q) & mask) return LRNNX_ERR_INVALID_ARG;
+    if ((int64_t)a->P * (cplx ? 8 : 4) > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;   // 32-bit byte offsets in a row
+    const int64_t ng = cdiv(a->L, diag_scan_bwd_group_steps(cplx));
+    const int64_t wgx = (int64_t)a->B * cdiv(a->P, 64);
+    if (ng > 65535 || wgx > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;
+    if (!a->workspace || a->workspace_bytes < diag_scan_bwd_bytes(a->B, a->P, a->L, cplx) ||
+        (reinterpret_cast<uintptr_t>(a->workspace) & 7u))
+        return LRNNX_ERR_WORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
+    DiagParams p{};
+    p.B = a->B; p.P = a->P; p.L = a->L;
+    p.is_complex = cplx; p.ngroups = (int)ng;
+    p.a = a->a; p.b = a->gx; p.xs = a->x; p.x0 = a->x0;
+    p.x = a->db; p.da = a->da; p.x_last = a->dx0;
+    const FillList z = set_diag_workspace(p, a->workspace);
+    if (launch_fill(z, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    return launch_diag_scan_bwd(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }
 
 int lrnnx_selective_step(const lrnnx_ss_step_args *a) {

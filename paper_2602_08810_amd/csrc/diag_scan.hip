@@ -21,6 +21,7 @@ template <> struct Elem<false> {
     static __device__ __forceinline__ T mul(T a, T b) { return a * b; }
     static __device__ __forceinline__ T fma(T a, T x, T b) { return __builtin_fmaf(a, x, b); }
     static __device__ __forceinline__ T nan() { return __builtin_nanf(""); }
+    static __device__ __forceinline__ T conj(T a) { return a; }
 };
 template <> struct Elem<true> {
     using T = float2;
@@ -29,6 +30,7 @@ template <> struct Elem<true> {
     static __device__ __forceinline__ T mul(T a, T b) { return cmul(a, b); }
     static __device__ __forceinline__ T fma(T a, T x, T b) { return cfma(a, x, b); }
     static __device__ __forceinline__ T nan() { return make_float2(__builtin_nanf(""), __builtin_nanf("")); }
+    static __device__ __forceinline__ T conj(T a) { return make_float2(a.x, -a.y); }
 };
 
 template <typename E>
@@ -41,7 +43,11 @@ __device__ __forceinline__ E &el(E *row, unsigned byte_off) {
 }
 
 // ANCH: every ANCH-th group publishes its true end state; a group looks back over at most ANCH-1 aggregates.
-template <bool CPLX, int CS, int GW, int ANCH>
+// BWD = false: the scan.  BWD = true: its adjoint, the same chain over reversed time (scan position j is time
+// k = L-1-j): g_k = gx_k + conj(a_{k+1}) g_{k+1}, read through p.b = gx and written through p.x = db; the coefficient
+// of a position is therefore the NEXT time step's a, conjugated.  Each step also loads the saved state before it
+// and writes da_k = conj(x_{k-1}) g_k; the last position writes dx0 = conj(a_0) g_0 through p.x_last.
+template <bool CPLX, int CS, int GW, int ANCH, bool BWD>
 __global__ __launch_bounds__(GW * 64) void k_diag_scan(const DiagParams p) {
     using EL = Elem<CPLX>;
     using E = typename EL::T;
@@ -57,24 +63,49 @@ __global__ __launch_bounds__(GW * 64) void k_diag_scan(const DiagParams p) {
     const bool okp = pp < p.P;
     const int64_t P = p.P;
     const int64_t k0 = ((int64_t)g * GW + w) * CS;
-    const int64_t row0 = ((int64_t)b * p.L + k0) * P;
+    const int64_t tstep = BWD ? -P : P;                        // element stride between consecutive scan positions
+    const int64_t row0 = ((int64_t)b * p.L + (BWD ? p.L - 1 - k0 : k0)) * P;
     const bool full = k0 + CS <= p.L;
 
     // ---- this wavefront's steps of (a, b), all loads in flight at once; steps beyond the sequence are identities
     E a[CS], bv[CS];
 #pragma unroll
     for (int i = 0; i < CS; ++i) { a[i] = EL::one(); bv[i] = EL::zero(); }
-    const E *arow = reinterpret_cast<const E *>(p.a) + row0;
+    // forward: a of the step itself; adjoint: a of the next time step (one row further), none for the last time step
+    const E *arow = reinterpret_cast<const E *>(p.a) + row0 + (BWD ? P : 0);
     const E *brow = reinterpret_cast<const E *>(p.b) + row0;
-    if (full) {
+    if (full && (!BWD || k0 > 0)) {
         if (okp) {
 #pragma unroll
-            for (int i = 0; i < CS; ++i) { a[i] = el(arow + i * P, boff); bv[i] = el(brow + i * P, boff); }
+            for (int i = 0; i < CS; ++i) { a[i] = el(arow + i * tstep, boff); bv[i] = el(brow + i * tstep, boff); }
         }
     } else if (okp) {
 #pragma unroll
         for (int i = 0; i < CS; ++i)
-            if (k0 + i < p.L) { a[i] = el(arow + i * P, boff); bv[i] = el(brow + i * P, boff); }
+            if (k0 + i < p.L) {
+                if (!BWD || k0 + i > 0) a[i] = el(arow + i * tstep, boff);
+                bv[i] = el(brow + i * tstep, boff);
+            }
+    }
+    E xprev[BWD ? CS : 1];
+    if constexpr (BWD) {
+#pragma unroll
+        for (int i = 0; i < CS; ++i) { a[i] = EL::conj(a[i]); xprev[i] = EL::zero(); }
+        // state before time step k = L-1-(k0+i): the saved x at k-1, or x0 (zero if absent) for k = 0
+        const E *xrow = reinterpret_cast<const E *>(p.xs) + row0 - P;
+        if (k0 + CS < p.L) {
+            if (okp) {
+#pragma unroll
+                for (int i = 0; i < CS; ++i) xprev[i] = el(xrow + i * tstep, boff);
+            }
+        } else if (okp) {
+#pragma unroll
+            for (int i = 0; i < CS; ++i) {
+                const int64_t k = p.L - 1 - (k0 + i);
+                if (k > 0) xprev[i] = el(xrow + i * tstep, boff);
+                else if (k == 0 && p.x0) xprev[i] = reinterpret_cast<const E *>(p.x0)[(int64_t)b * P + pp];
+            }
+        }
     }
     E A = EL::one(), x = EL::zero();
 #pragma unroll
@@ -125,7 +156,7 @@ __global__ __launch_bounds__(GW * 64) void k_diag_scan(const DiagParams p) {
         if (m >= 0) {
             const float2 f = from_bits(xb);
             if constexpr (CPLX) acc = f; else acc = f.x;
-        } else if (p.x0 && okp) {
+        } else if (!BWD && p.x0 && okp) {                      // the adjoint starts from zero
             acc = reinterpret_cast<const E *>(p.x0)[(int64_t)b * P + pp];
         }
 #pragma unroll
@@ -149,28 +180,45 @@ __global__ __launch_bounds__(GW * 64) void k_diag_scan(const DiagParams p) {
 
     // ---- replay from the true carry-in, out of registers
     x = EL::fma(Ae, sCarry[lane], e);
-    E *xrow = reinterpret_cast<E *>(p.x) + row0;
+    E *xrow_out = reinterpret_cast<E *>(p.x) + row0;
+    E *darow = BWD ? reinterpret_cast<E *>(p.da) + row0 : nullptr;
     E xl = x;
     if (full) {
         if (okp) {
 #pragma unroll
-            for (int i = 0; i < CS; ++i) { x = EL::fma(a[i], x, bv[i]); el(xrow + i * P, boff) = x; }
+            for (int i = 0; i < CS; ++i) {
+                x = EL::fma(a[i], x, bv[i]);
+                el(xrow_out + i * tstep, boff) = x;
+                if constexpr (BWD) el(darow + i * tstep, boff) = EL::mul(EL::conj(xprev[i]), x);
+            }
         }
         xl = x;
     } else if (okp) {
 #pragma unroll
         for (int i = 0; i < CS; ++i) {
             x = EL::fma(a[i], x, bv[i]);
-            if (k0 + i < p.L) { el(xrow + i * P, boff) = x; xl = x; }
+            if (k0 + i < p.L) {
+                el(xrow_out + i * tstep, boff) = x;
+                if constexpr (BWD) el(darow + i * tstep, boff) = EL::mul(EL::conj(xprev[i]), x);
+                xl = x;
+            }
         }
     }
-    if (p.x_last && okp && k0 < p.L && p.L <= k0 + CS) reinterpret_cast<E *>(p.x_last)[(int64_t)b * P + pp] = xl;
+    if (p.x_last && okp && k0 < p.L && p.L <= k0 + CS) {
+        if constexpr (BWD) {                                   // dx0 = conj(a at time 0) g_0
+            const E a0 = reinterpret_cast<const E *>(p.a)[((int64_t)b * p.L) * P + pp];
+            xl = EL::mul(EL::conj(a0), xl);
+        }
+        reinterpret_cast<E *>(p.x_last)[(int64_t)b * P + pp] = xl;
+    }
 }
 
 // ---------------------------------------------------------------- launchers
 constexpr int kDsCS = 32;                        // steps of (a, b) a wavefront keeps in registers
 constexpr int kDsGWSmall = 4, kDsGWLarge = 8;    // real: wavefronts per group, by the number of independent chains
 constexpr int kDsCplxGW = 4, kDsCplxAnchor = 8;  // complex: twice the registers per step and two slots per aggregate
+// adjoint: three arrays per step (coefficient, gx, saved state); real keeps 32 steps, complex 16
+constexpr int kDsBwdGW = 4, kDsBwdCplxCS = 16;
 
 static int ds_gw(int64_t B, int64_t P, int is_complex) {
     if (is_complex) return kDsCplxGW;
@@ -179,16 +227,27 @@ static int ds_gw(int64_t B, int64_t P, int is_complex) {
 int diag_scan_group_steps(int64_t B, int64_t P, int is_complex) { return kDsCS * ds_gw(B, P, is_complex); }
 int diag_scan_min_group_steps(int is_complex) { return kDsCS * (is_complex ? kDsCplxGW : kDsGWSmall); }
 int diag_scan_anchor(int is_complex) { return is_complex ? kDsCplxAnchor : kAnchor; }
+int diag_scan_bwd_group_steps(int is_complex) { return (is_complex ? kDsBwdCplxCS : kDsCS) * kDsBwdGW; }
 
 hipError_t launch_diag_scan(const DiagParams &p, hipStream_t s) {
     const int npslab = (p.P + 63) / 64;
     dim3 grid((unsigned)(npslab * p.B), p.ngroups);
     if (p.is_complex)
-        hipLaunchKernelGGL((k_diag_scan<true, kDsCS, kDsCplxGW, kDsCplxAnchor>), grid, dim3(kDsCplxGW * 64), 0, s, p);
+        hipLaunchKernelGGL((k_diag_scan<true, kDsCS, kDsCplxGW, kDsCplxAnchor, false>), grid, dim3(kDsCplxGW * 64), 0, s, p);
     else if (ds_gw(p.B, p.P, 0) == kDsGWSmall)
-        hipLaunchKernelGGL((k_diag_scan<false, kDsCS, kDsGWSmall, kAnchor>), grid, dim3(kDsGWSmall * 64), 0, s, p);
+        hipLaunchKernelGGL((k_diag_scan<false, kDsCS, kDsGWSmall, kAnchor, false>), grid, dim3(kDsGWSmall * 64), 0, s, p);
     else
-        hipLaunchKernelGGL((k_diag_scan<false, kDsCS, kDsGWLarge, kAnchor>), grid, dim3(kDsGWLarge * 64), 0, s, p);
+        hipLaunchKernelGGL((k_diag_scan<false, kDsCS, kDsGWLarge, kAnchor, false>), grid, dim3(kDsGWLarge * 64), 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_diag_scan_bwd(const DiagParams &p, hipStream_t s) {
+    const int npslab = (p.P + 63) / 64;
+    dim3 grid((unsigned)(npslab * p.B), p.ngroups);
+    if (p.is_complex)
+        hipLaunchKernelGGL((k_diag_scan<true, kDsBwdCplxCS, kDsBwdGW, kDsCplxAnchor, true>), grid, dim3(kDsBwdGW * 64), 0, s, p);
+    else
+        hipLaunchKernelGGL((k_diag_scan<false, kDsCS, kDsBwdGW, kAnchor, true>), grid, dim3(kDsBwdGW * 64), 0, s, p);
     return hipGetLastError();
 }
 

@@ -86,6 +86,9 @@ struct DiagParams {
     float2 *ws_T;            // [B,ngroups,slots,P] group aggregates (slots: 1 real = (A,S); 2 complex = A, S)
     float2 *ws_X;            // [B,ngroups/anchor+1,P] true end state of every anchor group
     int *err;
+    // adjoint only: b = gx, x = db, x_last = dx0, x0 = the forward pass's x0
+    const void *xs;          // [B,L,P] states saved by the forward scan
+    void *da;                // [B,L,P] out
 };
 
 struct StepParams {
@@ -115,6 +118,8 @@ hipError_t launch_diag_scan(const DiagParams &p, hipStream_t s);
 int diag_scan_group_steps(int64_t B, int64_t P, int is_complex);
 int diag_scan_min_group_steps(int is_complex);
 int diag_scan_anchor(int is_complex);
+hipError_t launch_diag_scan_bwd(const DiagParams &p, hipStream_t s);
+int diag_scan_bwd_group_steps(int is_complex);
 int lti_onepass_bwd_group_steps();
 struct FillList {
     static constexpr int kMax = 5;

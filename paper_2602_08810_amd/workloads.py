@@ -132,7 +132,7 @@ def make_lti(B, P, L, seed=1, with_x0=False, with_gx=False, **_unused):
     return {"lam": lam, "v": v, "x0": x0, "gx": gx}
 
 
-def make_diag(B, P, L, cplx=False, seed=1, with_x0=False, **_unused):
+def make_diag(B, P, L, cplx=False, seed=1, with_x0=False, with_gx=False, **_unused):
     """Inputs of the scan with caller-supplied coefficients (time-varying S5-style / gated recurrences).
 
     real: a ~ U(0.5, 1) (a forget gate), b ~ N(0,1), float32; complex: a = r e^{i theta} with r ~ U(0.9, 0.999),
@@ -143,7 +143,8 @@ def make_diag(B, P, L, cplx=False, seed=1, with_x0=False, **_unused):
         a = rng.uniform(0.5, 1.0, size=(B, L, P)).astype(np.float32)
         b = rng.standard_normal((B, L, P), dtype=np.float32)
         x0 = rng.standard_normal((B, P), dtype=np.float32) if with_x0 else None
-        return {"a": a, "b": b, "x0": x0}
+        gx = rng.standard_normal((B, L, P), dtype=np.float32) if with_gx else None      # drawn last
+        return {"a": a, "b": b, "x0": x0, "gx": gx}
     r = rng.uniform(0.9, 0.999, size=(B, L, P))
     th = rng.uniform(0.0, 2.0 * np.pi, size=(B, L, P))
     a = (r * np.exp(1j * th)).astype(np.complex64)
@@ -152,7 +153,12 @@ def make_diag(B, P, L, cplx=False, seed=1, with_x0=False, **_unused):
     b.real = rng.standard_normal((B, L, P), dtype=np.float32) * s
     b.imag = rng.standard_normal((B, L, P), dtype=np.float32) * s
     x0 = (rng.standard_normal((B, P)) + 1j * rng.standard_normal((B, P))).astype(np.complex64) if with_x0 else None
-    return {"a": a, "b": b, "x0": x0}
+    gx = None
+    if with_gx:                                                                          # drawn last, like b
+        gx = np.empty((B, L, P), dtype=np.complex64)
+        gx.real = rng.standard_normal((B, L, P), dtype=np.float32) * s
+        gx.imag = rng.standard_normal((B, L, P), dtype=np.float32) * s
+    return {"a": a, "b": b, "x0": x0, "gx": gx}
 
 
 def make(name: str, **overrides):
