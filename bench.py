@@ -276,7 +276,15 @@ def _other_configs(api, torch, dev):
         nb = 3 * Bd * Ld * Pd * esz
         out[f"diag_scan_{tag}_B8_P1024_L8192"] = {"us": tt * 1e6, "elements_per_s": Bd * Ld * Pd / tt,
                                                   "hbm_GBs": nb / tt / 1e9, "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
-        del ad, bd, xd, wsd
+        # its backward: reads a, x, gx, writes da, db
+        wsb = torch.empty(max(api.lrnnx_workspace_bytes(api.WS_DIAG_BWD, Bd, Pd, 0, Ld, api.C64 if esz == 8 else api.F32), 16),
+                          dtype=torch.uint8, device=dev)
+        tt = _time(torch, lambda: api.lrnnx_diag_scan_bwd(ad, xd, bd, workspace=wsb), 10)   # bd stands in for gx
+        nb = 5 * Bd * Ld * Pd * esz
+        out[f"diag_scan_bwd_{tag}_B8_P1024_L8192"] = {"us": tt * 1e6, "elements_per_s": Bd * Ld * Pd / tt,
+                                                      "hbm_GBs": nb / tt / 1e9, "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS,
+                                                      "note": "includes the allocation of da and db by the binding"}
+        del ad, bd, xd, wsd, wsb
 
     # forward with a complex diagonal A and complex maps at config 2's shape (bf16 I/O)
     Bc, Dc, Nc, Lc = 8, 1536, 16, 2048

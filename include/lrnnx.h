@@ -15,7 +15,7 @@
  *   - time-invariant complex-diagonal (the S5 / LRU rows of Table 1; Sec. 2.2.1),
  *     forward, backward and single-token update;
  *   - time-varying with the per-step coefficients a_k, b_k supplied by the caller, real or
- *     complex (the time-varying S5-style and gated layers of Sec. 2.2.2).
+ *     complex (the time-varying S5-style and gated layers of Sec. 2.2.2), forward and backward.
  * The hidden state x[B,D,L,N] is never written to memory (Sec. 3, the stated
  * advantage of the fused kernels); the backward pass recomputes it.
  *
