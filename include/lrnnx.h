@@ -365,7 +365,7 @@ typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2, LRNNX_WS_LT
 size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t L, int io_dtype);
 
 const char *lrnnx_status_string(int status);
-int lrnnx_version(void);
+int lrnnx_version(void);   /* major * 100 + minor; grows whenever an entry point or a struct field is added */
 
 #ifdef __cplusplus
 }
