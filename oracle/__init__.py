@@ -42,6 +42,7 @@ def _load():
         _lib.lrnnx_oracle_softplus.restype = ctypes.c_double
         _lib.lrnnx_oracle_softplus.argtypes = [ctypes.c_double]
         _lib.lrnnx_oracle_disc.restype = None
+        _lib.lrnnx_oracle_disc_complex.restype = None
         _lib.lrnnx_oracle_num_threads.restype = ctypes.c_int
     return _lib
 
@@ -134,6 +135,47 @@ def selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None,
     if rc != 0:
         raise ValueError(f"oracle complex fwd: bad arguments (rc={rc})")
     return y, x_last
+
+
+def disc_terms_complex(disc, dt: float, A: complex):
+    """(a, g, da/ddt, da/dA, dg/ddt, dg/dA) of one discretisation at real dt and complex A, as complex numbers."""
+    out = (ctypes.c_double * 12)()
+    A = complex(A)
+    _load().lrnnx_oracle_disc_complex(ctypes.c_int(_disc(disc)), ctypes.c_double(dt), ctypes.c_double(A.real),
+                                      ctypes.c_double(A.imag), out)
+    return tuple(complex(out[2 * i], out[2 * i + 1]) for i in range(6))
+
+
+def selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,
+                               disc="zoh_s6", delta_softplus=True):
+    """Gradients of sum(dy * y) for selective_scan_fwd_complex.  The gradient of a complex input q is
+    dLoss/dRe q + i dLoss/dIm q (complex128: dA, dBm, dCm, dx0); du, ddelta, dz, dD, dbias are real."""
+    u, delta, dy = _f64(u), _f64(delta), _f64(dy)
+    A, Bm, Cm = _c128(A), _c128(Bm), _c128(Cm)
+    Dskip, delta_bias, z = map(_f64, (Dskip, delta_bias, z))
+    x0c = None if x0 is None else _c128(x0)
+    Bsz, D, L = u.shape
+    N = A.shape[1]
+    assert A.shape == (D, N) and Bm.shape == (Bsz, L, N) and Cm.shape == (Bsz, L, N) and dy.shape == (Bsz, D, L)
+    c128 = np.complex128
+    out = {
+        "du": np.empty((Bsz, D, L)), "ddelta": np.empty((Bsz, D, L)),
+        "dA": np.empty((D, N), dtype=c128), "dBm": np.empty(Bm.shape, dtype=c128), "dCm": np.empty(Cm.shape, dtype=c128),
+        "dD": np.empty(D) if Dskip is not None else None,
+        "dbias": np.empty(D) if delta_bias is not None else None,
+        "dz": np.empty((Bsz, D, L)) if z is not None else None,
+        "dx0": np.empty((Bsz, D, N), dtype=c128),
+    }
+    cp = lambda t: ctypes.c_void_p(0) if t is None else t.ctypes.data_as(ctypes.c_void_p)
+    rc = _load().lrnnx_oracle_selective_scan_bwd_complex(
+        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_long(L),
+        ctypes.c_int(_disc(disc)), ctypes.c_int(int(bool(delta_softplus))),
+        _p(u), _p(delta), cp(A), cp(Bm), cp(Cm), _p(Dskip), _p(delta_bias), _p(z), cp(x0c), _p(dy),
+        _p(out["du"]), _p(out["ddelta"]), cp(out["dA"]), cp(out["dBm"]), cp(out["dCm"]),
+        _p(out["dD"]), _p(out["dbias"]), _p(out["dz"]), cp(out["dx0"]))
+    if rc != 0:
+        raise ValueError(f"oracle complex bwd: bad arguments (rc={rc})")
+    return out
 
 
 def selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,

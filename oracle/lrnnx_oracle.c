@@ -24,6 +24,10 @@
  * dot test, linearity / causality / chaining invariants; for the LTI backward: finite differences of a real
  * loss over real and imaginary parts, the L = 1 closed form, the reversed-forward-scan identity; for the
  * caller-supplied (a_k, b_k) scan: the product/sum closed form, reduction to the LTI and the selective scans.
+ * Complex-A selective scan: the unrolled complex sum, reduction to the real scan and to the LTI scan, cont2discrete
+ * with a complex pole; its backward: finite differences over real and imaginary parts, a library's complex
+ * automatic differentiation of the plain loop, reduction to the real backward, the partials of the complex
+ * discretisations one by one.
  * Parity unpinned: which of the two "ZOH" input maps (disc 0 or 1) the
  * paper's own "zoh" string selects; the paper's asynchronous scheme is read
  * as "the caller supplies Delta per step" (delta_softplus = 0).
@@ -38,6 +42,7 @@
  *   xs (optional dump of every state)   : [B, D, L, N]
  *   LTI: lambda [P], v, x [B, L, P], x0 [B, P] -- complex, (re, im) pairs
  */
+#include <complex.h>
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
@@ -308,6 +313,154 @@ int lrnnx_oracle_selective_scan_bwd(
                     h[n] = a * hx;
                 }
                 double ds = delta_softplus ? ddt * sigmoid(s) : ddt;   /* d softplus / ds = sigmoid */
+                ddelta[row * L + l] = ds;
+                if (dbias && delta_bias) dbias[d] += ds;
+                du[row * L + l] = du_l;
+            }
+            if (dx0) for (int n = 0; n < N; ++n) dx0[row * N + n] = h[n];
+        }
+        free(xs); free(h);
+    }
+    for (int t = 0; t < nthreads; ++t)
+        for (long i = 0; i < nBC; ++i) {
+            dBm[i] += privB[(size_t)t * nBC + i];
+            dCm[i] += privC[(size_t)t * nBC + i];
+        }
+    free(privB); free(privC);
+    return 0;
+}
+
+/* Complex discretisation with its partial derivatives.  a and g are holomorphic in A and differentiable in the real
+ * step dt; the four partials are ordinary complex derivatives (d/d dt along the real axis, d/dA complex).      */
+static void disc_eval_cd(int disc, double dt, double complex A, double complex *a, double complex *g,
+                         double complex *a_t, double complex *a_A, double complex *g_t, double complex *g_A)
+{
+    if (disc == DISC_BILINEAR) {
+        double complex q = 1.0 / (1.0 - 0.5 * dt * A);
+        *a = (1.0 + 0.5 * dt * A) * q;
+        *g = dt * q;
+        *a_t = A * q * q;
+        *a_A = dt * q * q;
+        *g_t = q * q;
+        *g_A = 0.5 * dt * dt * q * q;
+        return;
+    }
+    double complex zc = dt * A;
+    *a = cexp(zc);
+    *a_t = A * (*a);
+    *a_A = dt * (*a);
+    if (disc == DISC_ZOH_S6) { *g = dt; *g_t = 1.0; *g_A = 0.0; }
+    else if (disc == DISC_DIRAC) { *g = 1.0; *g_t = 0.0; *g_A = 0.0; }
+    else {                                   /* exact ZOH: g = (a - 1) / A = dt (e^z - 1) / z */
+        *g_t = *a;
+        if (cabs(zc) < 1e-3) {
+            /* (e^z - 1)/z = 1 + z/2 + z^2/6 + z^3/24 + ...;  d/dA of g = dt^2 (z e^z - e^z + 1)/z^2
+             * = dt^2 (1/2 + z/3 + z^2/8 + z^3/30 + ...): the omitted terms are below 1e-14 relative here */
+            *g = dt * (1.0 + zc * (0.5 + zc * (1.0 / 6.0 + zc * (1.0 / 24.0 + zc / 120.0))));
+            *g_A = dt * dt * (0.5 + zc * (1.0 / 3.0 + zc * (0.125 + zc * (1.0 / 30.0 + zc / 144.0))));
+        } else {
+            *g = (*a - 1.0) / A;
+            *g_A = (zc * (*a) - (*a - 1.0)) / (A * A);
+        }
+    }
+}
+
+/* Expose the complex discretisation so the tests can pin it: out = (a, g, a_t, a_A, g_t, g_A) as (re, im) pairs. */
+void lrnnx_oracle_disc_complex(int disc, double dt, double Ar, double Ai, double *out12)
+{
+    double complex v[6];
+    disc_eval_cd(disc, dt, Ar + Ai * I, &v[0], &v[1], &v[2], &v[3], &v[4], &v[5]);
+    for (int i = 0; i < 6; ++i) { out12[2 * i] = creal(v[i]); out12[2 * i + 1] = cimag(v[i]); }
+}
+
+/* Reverse-mode derivative of lrnnx_oracle_selective_scan_fwd_complex for a given upstream dy (real).
+ * The gradient of the real loss with respect to a complex quantity q is written dLoss/dRe q + i dLoss/dIm q
+ * (the convention of complex automatic differentiation); with it, for w = p q (complex product),
+ * grad p = grad w * conj(q), and for y = Re(c x), grad x = dy conj(c), grad c = dy conj(x).  A real input that
+ * enters a complex expression receives the real part.
+ * Complex ((re, im) pairs): A, dA [D,N]; Bm, Cm, dBm, dCm [B,L,N]; x0, dx0 [B,D,N].  Real: u, delta, z, dy, du,
+ * ddelta, dz [B,D,L]; Dskip, delta_bias, dD, dbias [D].  dA, dBm, dCm, dD, dbias are overwritten.
+ * Optional (may be NULL): Dskip, delta_bias, z, x0, dD, dbias, dz, dx0.                                        */
+int lrnnx_oracle_selective_scan_bwd_complex(
+    int B, int D, int N, long L, int disc, int delta_softplus,
+    const double *u, const double *delta, const double *A_,
+    const double *Bm_, const double *Cm_, const double *Dskip,
+    const double *delta_bias, const double *z, const double *x0_,
+    const double *dy,
+    double *du, double *ddelta, double *dA_, double *dBm_, double *dCm_,
+    double *dD, double *dbias, double *dz, double *dx0_)
+{
+    if (B < 0 || D < 0 || N < 1 || L < 0 || disc < 0 || disc > 3) return 1;
+    const double complex *A = (const double complex *)A_, *Bm = (const double complex *)Bm_;
+    const double complex *Cm = (const double complex *)Cm_, *x0 = (const double complex *)x0_;
+    double complex *dA = (double complex *)dA_, *dBm = (double complex *)dBm_;
+    double complex *dCm = (double complex *)dCm_, *dx0 = (double complex *)dx0_;
+    long nBC = (long)B * L * N;
+    for (long i = 0; i < (long)D * N; ++i) dA[i] = 0.0;
+    for (long i = 0; i < nBC; ++i) { dBm[i] = 0.0; dCm[i] = 0.0; }
+    if (dD) memset(dD, 0, sizeof(double) * (size_t)D);
+    if (dbias) memset(dbias, 0, sizeof(double) * (size_t)D);
+
+    int nthreads = lrnnx_oracle_num_threads();
+    double complex *privB = (double complex *)calloc((size_t)nthreads * nBC + 1, sizeof(double complex));
+    double complex *privC = (double complex *)calloc((size_t)nthreads * nBC + 1, sizeof(double complex));
+    if (!privB || !privC) { free(privB); free(privC); return 2; }
+
+#pragma omp parallel for schedule(static)
+    for (int d = 0; d < D; ++d) {
+#ifdef _OPENMP
+        int tid = omp_get_thread_num();
+#else
+        int tid = 0;
+#endif
+        double complex *pB = privB + (size_t)tid * nBC, *pC = privC + (size_t)tid * nBC;
+        double complex *xs = (double complex *)malloc(sizeof(double complex) * (size_t)(L + 1) * N); /* xs[(l+1)N+n] = x_l */
+        double complex *h = (double complex *)malloc(sizeof(double complex) * N);
+        for (int b = 0; b < B; ++b) {
+            long row = (long)b * D + d;
+            for (int n = 0; n < N; ++n) xs[n] = x0 ? x0[row * N + n] : 0.0;
+            for (long l = 0; l < L; ++l) {                      /* forward sweep, states kept */
+                double s = delta[row * L + l] + (delta_bias ? delta_bias[d] : 0.0);
+                double dt = delta_softplus ? softplus(s) : s;
+                double uu = u[row * L + l];
+                for (int n = 0; n < N; ++n) {
+                    double complex a, g, t0, t1, t2, t3;
+                    disc_eval_cd(disc, dt, A[(long)d * N + n], &a, &g, &t0, &t1, &t2, &t3);
+                    xs[(l + 1) * N + n] = a * xs[l * N + n] + g * Bm[((long)b * L + l) * N + n] * uu;
+                }
+            }
+            for (int n = 0; n < N; ++n) h[n] = 0.0;            /* h[n] = conj(a_{l+1}) grad x_{l+1}, zero past the end */
+            for (long l = L - 1; l >= 0; --l) {                 /* reverse sweep */
+                double s = delta[row * L + l] + (delta_bias ? delta_bias[d] : 0.0);
+                double dt = delta_softplus ? softplus(s) : s;
+                double uu = u[row * L + l];
+                double acc = 0.0;
+                for (int n = 0; n < N; ++n) acc += creal(Cm[((long)b * L + l) * N + n] * xs[(l + 1) * N + n]);
+                double ypre = acc + (Dskip ? Dskip[d] * uu : 0.0);
+                double dypre = dy[row * L + l];
+                if (z) {
+                    double zz = z[row * L + l], sg = sigmoid(zz);
+                    if (dz) dz[row * L + l] = dypre * ypre * sg * (1.0 + zz * (1.0 - sg));
+                    dypre *= zz * sg;
+                }
+                if (dD && Dskip) dD[d] += dypre * uu;
+                double du_l = Dskip ? dypre * Dskip[d] : 0.0;
+                double ddt = 0.0;
+                for (int n = 0; n < N; ++n) {
+                    long bc = ((long)b * L + l) * N + n;
+                    double complex a, g, a_t, a_A, g_t, g_A;
+                    disc_eval_cd(disc, dt, A[(long)d * N + n], &a, &g, &a_t, &a_A, &g_t, &g_A);
+                    double complex hx = dypre * conj(Cm[bc]) + h[n];        /* grad x_l */
+                    pC[bc] += dypre * conj(xs[(l + 1) * N + n]);
+                    double complex ga = hx * conj(xs[l * N + n]);           /* grad a_l:  x_l = a x_{l-1} + g Bm u */
+                    double complex gg = hx * conj(Bm[bc]) * uu;             /* grad g_l */
+                    pB[bc] += hx * conj(g) * uu;
+                    du_l += creal(hx * conj(g * Bm[bc]));
+                    ddt += creal(ga * conj(a_t)) + creal(gg * conj(g_t));
+                    dA[(long)d * N + n] += ga * conj(a_A) + gg * conj(g_A);
+                    h[n] = conj(a) * hx;
+                }
+                double ds = delta_softplus ? ddt * sigmoid(s) : ddt;
                 ddelta[row * L + l] = ds;
                 if (dbias && delta_bias) dbias[d] += ds;
                 du[row * L + l] = du_l;

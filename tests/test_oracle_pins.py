@@ -763,3 +763,113 @@ def test_diag_scan_bwd_matches_library_autograd_on_real_gates(oracle):
     np.testing.assert_allclose(db, tb.grad.numpy(), rtol=1e-12, atol=1e-14)
     np.testing.assert_allclose(dx0, tx0.grad.numpy(), rtol=1e-12, atol=1e-14)
     assert da.dtype == np.float64
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Backward of the selective scan with a complex diagonal A (gradient of a complex q = dLoss/dRe q + i dLoss/dIm q).
+# ---------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("disc", DISCS)
+@pytest.mark.parametrize("dt,A", [(0.3, -0.8 + 2.5j), (1e-5, -1.5 - 0.7j), (2.0, -0.05 + 9.0j)])
+def test_complex_disc_partials_by_finite_differences(oracle, disc, dt, A):
+    """a and g restated with numpy complex scalars; their partials by central differences along dt and, a and g
+    being holomorphic in A, along the real axis of A (the step along the imaginary axis must give the same)."""
+    a, g, a_t, a_A, g_t, g_A = oracle.disc_terms_complex(disc, dt, A)
+    ra, rg = _disc_py_c(disc, dt, A)
+    assert a == pytest.approx(ra, rel=1e-12)
+    assert g == pytest.approx(rg, rel=1e-9 if dt < 1e-3 else 1e-12)
+    h = 1e-6 * max(dt, 1e-3)
+    f = lambda t, z: np.array([complex(v) for v in _disc_py_c(disc, t, z)])
+    num_t = (f(dt + h, A) - f(dt - h, A)) / (2 * h)
+    hA = 1e-6
+    num_A = (f(dt, A + hA) - f(dt, A - hA)) / (2 * hA)
+    num_Ai = (f(dt, A + 1j * hA) - f(dt, A - 1j * hA)) / (2j * hA)
+    tol = dict(rel=2e-5, abs=1e-9) if dt < 1e-3 else dict(rel=1e-7, abs=1e-10)
+    assert a_t == pytest.approx(num_t[0], **tol) and g_t == pytest.approx(num_t[1], **tol)
+    assert a_A == pytest.approx(num_A[0], **tol) and a_A == pytest.approx(num_Ai[0], **tol)
+    if dt >= 1e-3:      # (e^z - 1)/A loses digits in the restated form for tiny z; the series is pinned below
+        assert g_A == pytest.approx(num_A[1], **tol) and g_A == pytest.approx(num_Ai[1], **tol)
+
+
+def test_complex_zoh_gain_series_meets_the_closed_form(oracle):
+    """The exact-ZOH gain and its A-derivative switch to a power series for |dt A| < 1e-3: both branches agree at
+    the switch, and for tiny z they tend to dt and dt^2/2."""
+    A = -0.6 + 0.8j                                    # |A| = 1
+    lo, hi = oracle.disc_terms_complex("zoh", 0.999e-3, A), oracle.disc_terms_complex("zoh", 1.001e-3, A)
+    for i in (1, 5):
+        scale = (1.001 / 0.999) ** (1 if i == 1 else 2)
+        assert hi[i] == pytest.approx(lo[i] * scale, rel=1e-5)
+        assert hi[i] == pytest.approx(lo[i] * scale * (1 + (0.002e-3 * A) * (0.5 if i == 1 else 2 / 3)), rel=1e-9)
+    tiny = oracle.disc_terms_complex("zoh", 1e-9, A)
+    assert tiny[1] == pytest.approx(1e-9, rel=1e-8) and tiny[5] == pytest.approx(0.5e-18, rel=1e-8)
+
+
+@pytest.mark.parametrize("disc", DISCS)
+@pytest.mark.parametrize("softplus", [True, False])
+def test_complex_backward_finite_differences(oracle, disc, softplus):
+    """Central differences of sum(dy * y) over every real input and over the real and imaginary parts of every
+    complex input, against the forward oracle."""
+    p = _complex_problem(81, B=2, D=2, N=3, L=6)
+    if not softplus:
+        p["delta"] = np.abs(p["delta"]) * 0.3 + 0.05
+        p["delta_bias"] = np.abs(p["delta_bias"]) * 0.1
+    rng = np.random.default_rng(82)
+    dy = rng.standard_normal(p["u"].shape)
+    kw = dict(disc=disc, delta_softplus=softplus)
+    g = oracle.selective_scan_bwd_complex(**p, dy=dy, **kw)
+    loss = lambda q: float(np.sum(dy * oracle.selective_scan_fwd_complex(**q, **kw)[0]))
+    names = {"u": "du", "delta": "ddelta", "A": "dA", "Bm": "dBm", "Cm": "dCm", "Dskip": "dD", "delta_bias": "dbias",
+             "z": "dz", "x0": "dx0"}
+    h = 1e-6
+    for k, gk in names.items():
+        flat_idx = rng.choice(p[k].size, size=min(p[k].size, 6), replace=False)
+        for fi in flat_idx:
+            idx = np.unravel_index(fi, p[k].shape)
+            parts = (1.0, 1j) if np.iscomplexobj(p[k]) else (1.0,)
+            num = 0.0
+            for part in parts:
+                q = {n: (v.copy() if isinstance(v, np.ndarray) else v) for n, v in p.items()}
+                q[k][idx] += h * part
+                up = loss(q)
+                q[k][idx] -= 2 * h * part
+                num = num + part * (up - loss(q)) / (2 * h)
+            assert num == pytest.approx(g[gk][idx], rel=2e-6, abs=2e-7), (k, idx)
+
+
+@pytest.mark.parametrize("disc", DISCS)
+def test_complex_backward_matches_library_autograd(oracle, disc):
+    """torch's complex autograd (same gradient convention) on a plain Python loop of the recurrence."""
+    import torch
+    p = _complex_problem(83, B=2, D=2, N=3, L=7)
+    dy = np.random.default_rng(84).standard_normal(p["u"].shape)
+    t = {k: torch.tensor(v, dtype=torch.complex128 if np.iscomplexobj(v) else torch.float64, requires_grad=True)
+         for k, v in p.items()}
+    dt = torch.nn.functional.softplus(t["delta"] + t["delta_bias"][None, :, None])          # [B,D,L]
+    x, ys = t["x0"], []
+    for l in range(p["u"].shape[2]):
+        zA = dt[:, :, l, None] * t["A"][None]                                                # [B,D,N]
+        if disc == "bilinear":
+            a, gain = (1 + zA / 2) / (1 - zA / 2), dt[:, :, l, None] / (1 - zA / 2)
+        else:
+            a = torch.exp(zA)
+            gain = {"zoh_s6": dt[:, :, l, None] + 0j, "zoh": (a - 1) / t["A"][None], "dirac": torch.ones_like(a)}[disc]
+        x = a * x + gain * t["Bm"][:, None, l, :] * t["u"][:, :, l, None]
+        ypre = (t["Cm"][:, None, l, :] * x).sum(-1).real + t["Dskip"][None] * t["u"][:, :, l]
+        ys.append(ypre * t["z"][:, :, l] * torch.sigmoid(t["z"][:, :, l]))
+    (torch.stack(ys, -1) * torch.tensor(dy)).sum().backward()
+    g = oracle.selective_scan_bwd_complex(**p, dy=dy, disc=disc)
+    for k, gk in {"u": "du", "delta": "ddelta", "A": "dA", "Bm": "dBm", "Cm": "dCm", "Dskip": "dD",
+                  "delta_bias": "dbias", "z": "dz", "x0": "dx0"}.items():
+        np.testing.assert_allclose(g[gk], t[k].grad.numpy(), rtol=1e-10, atol=1e-12, err_msg=k)
+
+
+@pytest.mark.parametrize("disc", DISCS)
+def test_complex_backward_with_real_data_is_the_real_backward(oracle, disc):
+    """Zero imaginary parts everywhere: the real parts of the gradients are those of the real scan's backward."""
+    rng = np.random.default_rng(85)
+    p = _rand_problem(rng, B=2, D=3, N=4, L=10)
+    dy = rng.standard_normal(p["u"].shape)
+    g = oracle.selective_scan_bwd(**p, dy=dy, disc=disc)
+    q = dict(p, A=p["A"] + 0j, Bm=p["Bm"] + 0j, Cm=p["Cm"] + 0j, x0=p["x0"] + 0j)
+    gc = oracle.selective_scan_bwd_complex(**q, dy=dy, disc=disc)
+    for k in g:
+        np.testing.assert_allclose(np.real(gc[k]), g[k], rtol=1e-11, atol=1e-13, err_msg=k)
