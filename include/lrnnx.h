@@ -136,7 +136,10 @@ int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *args);
  * real as above.  A [D,N] complex float pairs; Bm, Cm [B,L,N] complex in io_dtype (interleaved re, im: bfloat16
  * pairs or float pairs), contiguous, 16-byte aligned; x0, x_last [B,D,N] complex float pairs (optional).
  * a and g are the four schemes of lrnnx_disc in complex arithmetic.  Delta * Im(A) must stay within
- * +-256 * 2 pi (the range of the hardware sine and cosine).  Forward only; one pass over the sequence.       */
+ * +-256 * 2 pi (the range of the hardware sine and cosine).  One pass over the sequence.
+ * ckpt (optional): [B,D,ceil(L/lrnnx_ckpt_interval()),N] complex float pairs, the state entering every
+ * lrnnx_ckpt_interval()-th step, for lrnnx_selective_scan_bwd_complex.  y may be NULL when only the checkpoints
+ * (and x_last) are wanted.                                                                                     */
 typedef struct lrnnx_ss_fwd_complex_args {
     size_t struct_size;
     int32_t B, D, N;
@@ -154,9 +157,52 @@ typedef struct lrnnx_ss_fwd_complex_args {
     void *y;            int64_t y_stride_b, y_stride_d;
     void *x_last;                                                  /* [B,D,N] complex float, out or NULL */
     void *stream;
+    void *ckpt;         /* out or NULL; callers built against the shorter struct get NULL */
 } lrnnx_ss_fwd_complex_args;
 
 int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *args);
+
+/* ------------------------------------------------------------------ selective scan, backward, complex diagonal A
+ * Reverse-mode derivative of lrnnx_selective_scan_fwd_complex for an upstream gradient dy[B,D,L] (real): the
+ * gradients of sum(dy * y).  The gradient with respect to a complex input q is dLoss/dRe q + i dLoss/dIm q (the
+ * convention of complex automatic differentiation), stored as float pairs: dA [D,N], dBm, dCm [B,L,N],
+ * dx0 [B,D,N].  du, ddelta, dz [B,D,L] in io_dtype and dD, dbias [D] float are real.  The states are recomputed
+ * tile by tile from checkpoints (Sec. 3): `ckpt` is the array a forward call wrote for the same inputs; if NULL the
+ * library first runs a state-only forward sweep into `workspace`
+ * (lrnnx_workspace_bytes(LRNNX_WS_BWD_COMPLEX, B, D, N, L, io_dtype)).  dA, dBm, dCm, dD, dbias are OVERWRITTEN
+ * (cleared on the stream, then accumulated with atomics: their last bits may differ from run to run).
+ * Optional (NULL allowed): Dskip, delta_bias, z, x0, ckpt, dD, dbias, dz, dx0.  dD requires Dskip, dbias requires
+ * delta_bias, dz requires z.  Alignment: Bm, Cm, dBm, dCm 16 bytes; A, x0, ckpt, dA, dx0 8 bytes.              */
+typedef struct lrnnx_ss_bwd_complex_args {
+    size_t struct_size;
+    int32_t B, D, N;
+    int64_t L;
+    int32_t io_dtype, disc, delta_softplus, reserved;
+    const void *u;      int64_t u_stride_b, u_stride_d;
+    const void *delta;  int64_t delta_stride_b, delta_stride_d;
+    const void *A;                                                 /* [D,N] complex float */
+    const void *Bm;                                                /* [B,L,N] complex io */
+    const void *Cm;                                                /* [B,L,N] complex io */
+    const float *Dskip;
+    const float *delta_bias;
+    const void *z;      int64_t z_stride_b, z_stride_d;
+    const void *x0;                                                /* [B,D,N] complex float or NULL */
+    const void *dy;     int64_t dy_stride_b, dy_stride_d;          /* [B,D,L] io */
+    const void *ckpt;                                              /* from the forward call, or NULL */
+    void *du;           int64_t du_stride_b, du_stride_d;          /* [B,D,L] io, out */
+    void *ddelta;       int64_t ddelta_stride_b, ddelta_stride_d;  /* [B,D,L] io, out */
+    void *dz;           int64_t dz_stride_b, dz_stride_d;          /* [B,D,L] io, out or NULL */
+    void *dA;                                                      /* [D,N] complex float, out */
+    void *dBm;                                                     /* [B,L,N] complex float, out */
+    void *dCm;                                                     /* [B,L,N] complex float, out */
+    float *dD;                                                     /* [D] out or NULL */
+    float *dbias;                                                  /* [D] out or NULL */
+    void *dx0;                                                     /* [B,D,N] complex float, out or NULL */
+    void *workspace;    size_t workspace_bytes;
+    void *stream;
+} lrnnx_ss_bwd_complex_args;
+
+int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *args);
 
 /* ------------------------------------------------------------------ selective scan, backward
  * Reverse-mode derivative of the forward above for an upstream gradient dy[B,D,L]:
@@ -357,7 +403,7 @@ int lrnnx_lti_step(const lrnnx_lti_step_args *args);
 
 /* ------------------------------------------------------------------ queries (host only, no GPU needed) */
 typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2, LRNNX_WS_LTI_BWD = 3, LRNNX_WS_DIAG = 4,
-               LRNNX_WS_DIAG_BWD = 5 } lrnnx_ws_kind;
+               LRNNX_WS_DIAG_BWD = 5, LRNNX_WS_BWD_COMPLEX = 6 } lrnnx_ws_kind;
 
 /* Bytes of device scratch the call may need (the largest over its paths).
  * For LRNNX_WS_LTI, LRNNX_WS_LTI_BWD, LRNNX_WS_DIAG and LRNNX_WS_DIAG_BWD pass P as D and 0 for N (the DIAG kinds:

@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("LRNNX_LIB", os.path.join(_HERE, "liblrnnx.so"))   # L
 F32, BF16, C64 = 0, 1, 2
 DISC = {"zoh_s6": 0, "zoh": 1, "bilinear": 2, "dirac": 3}
 PATH = {"auto": 0, "single_pass": 1, "chunk_carry": 2}
-WS_FWD, WS_BWD, WS_LTI, WS_LTI_BWD, WS_DIAG, WS_DIAG_BWD = 0, 1, 2, 3, 4, 5
+WS_FWD, WS_BWD, WS_LTI, WS_LTI_BWD, WS_DIAG, WS_DIAG_BWD, WS_BWD_COMPLEX = 0, 1, 2, 3, 4, 5, 6
 STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported", 3: "workspace", 4: "launch"}
 
 _vp, _i32, _i64, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
@@ -51,7 +51,26 @@ class FwdComplexArgs(ctypes.Structure):
         ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
         ("x0", _vp),
         ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
-        ("x_last", _vp), ("stream", _vp),
+        ("x_last", _vp), ("stream", _vp), ("ckpt", _vp),
+    ]
+
+
+class BwdComplexArgs(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32), ("L", _i64),
+        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32), ("reserved", _i32),
+        ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
+        ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
+        ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
+        ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
+        ("x0", _vp),
+        ("dy", _vp), ("dy_stride_b", _i64), ("dy_stride_d", _i64),
+        ("ckpt", _vp),
+        ("du", _vp), ("du_stride_b", _i64), ("du_stride_d", _i64),
+        ("ddelta", _vp), ("ddelta_stride_b", _i64), ("ddelta_stride_d", _i64),
+        ("dz", _vp), ("dz_stride_b", _i64), ("dz_stride_d", _i64),
+        ("dA", _vp), ("dBm", _vp), ("dCm", _vp), ("dD", _vp), ("dbias", _vp), ("dx0", _vp),
+        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
     ]
 
 
@@ -140,6 +159,8 @@ def lib():
         L.lrnnx_selective_scan_bwd.argtypes = [ctypes.POINTER(BwdArgs)]
         L.lrnnx_selective_scan_fwd_complex.argtypes = [ctypes.POINTER(FwdComplexArgs)]
         L.lrnnx_selective_scan_fwd_complex.restype = ctypes.c_int
+        L.lrnnx_selective_scan_bwd_complex.argtypes = [ctypes.POINTER(BwdComplexArgs)]
+        L.lrnnx_selective_scan_bwd_complex.restype = ctypes.c_int
         L.lrnnx_lti_diag_scan.argtypes = [ctypes.POINTER(LtiArgs)]
         L.lrnnx_lti_diag_scan_bwd.argtypes = [ctypes.POINTER(LtiBwdArgs)]
         L.lrnnx_lti_diag_scan_bwd.restype = ctypes.c_int
@@ -303,21 +324,16 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
 
 
 def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, x0=None,
-                                     disc="zoh_s6", delta_softplus=True, return_last_state=False, out=None):
-    """y (and optionally x_last) of the forward selective scan with complex A, Bm, Cm; see lrnnx_ss_fwd_complex_args.
+                                     disc="zoh_s6", delta_softplus=True, return_last_state=False, out=None,
+                                     return_ckpt=False):
+    """y (and optionally x_last, ckpt) of the forward selective scan with complex A, Bm, Cm; see
+    lrnnx_ss_fwd_complex_args.
 
     A [D,N] complex64.  Bm, Cm [B,L,N]: complex64 for float32 I/O; for bfloat16 I/O a bfloat16 tensor [B,L,N,2]
-    of (re, im) pairs.  x0, x_last [B,D,N] complex64."""
+    of (re, im) pairs.  x0, x_last [B,D,N] complex64; ckpt [B,D,ceil(L/interval),N] complex64."""
     io = u.dtype
     Bsz, D, L = u.shape
-    if A.dtype != torch.complex64 or A.dim() != 2 or A.shape[0] != D or not A.is_contiguous():
-        raise ValueError("A: expected contiguous complex64 [D,N]")
-    N = A.shape[1]
-    for name, t in (("Bm", Bm), ("Cm", Cm)):
-        ok = t.is_contiguous() and ((io == torch.float32 and t.dtype == torch.complex64 and tuple(t.shape) == (Bsz, L, N)) or
-                                    (io == torch.bfloat16 and t.dtype == torch.bfloat16 and tuple(t.shape) == (Bsz, L, N, 2)))
-        if not ok:
-            raise ValueError(f"{name}: expected contiguous complex64 [B,L,N] (float32 I/O) or bfloat16 [B,L,N,2]")
+    N = _check_complex_maps(A, Bm, Cm, io, Bsz, D, L)
     a = FwdComplexArgs()
     a.struct_size = ctypes.sizeof(FwdComplexArgs)
     a.B, a.D, a.N, a.L = Bsz, D, N, L
@@ -338,9 +354,90 @@ def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias
     a.y, a.y_stride_b, a.y_stride_d = _bdl(y, "y", io)
     x_last = torch.empty((Bsz, D, N), dtype=torch.complex64, device=u.device) if return_last_state else None
     a.x_last = _ptr(x_last)
+    ckpt = None
+    if return_ckpt:
+        ckpt = torch.empty((Bsz, D, -(-L // lrnnx_ckpt_interval()), N), dtype=torch.complex64, device=u.device)
+        a.ckpt = ckpt.data_ptr()
     a.stream = _stream()
     _check(lib().lrnnx_selective_scan_fwd_complex(ctypes.byref(a)))
-    return (y, x_last) if return_last_state else y
+    res = (y,) + ((x_last,) if return_last_state else ()) + ((ckpt,) if return_ckpt else ())
+    return res if len(res) > 1 else y
+
+
+def _check_complex_maps(A, Bm, Cm, io, Bsz, D, L):
+    """Validate A [D,N] complex64 and the complex maps for this I/O type; returns N."""
+    if A.dtype != torch.complex64 or A.dim() != 2 or A.shape[0] != D or not A.is_contiguous():
+        raise ValueError("A: expected contiguous complex64 [D,N]")
+    N = A.shape[1]
+    for name, t in (("Bm", Bm), ("Cm", Cm)):
+        ok = t.is_contiguous() and ((io == torch.float32 and t.dtype == torch.complex64 and tuple(t.shape) == (Bsz, L, N)) or
+                                    (io == torch.bfloat16 and t.dtype == torch.bfloat16 and tuple(t.shape) == (Bsz, L, N, 2)))
+        if not ok:
+            raise ValueError(f"{name}: expected contiguous complex64 [B,L,N] (float32 I/O) or bfloat16 [B,L,N,2]")
+    return N
+
+
+def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,
+                                     ckpt=None, disc="zoh_s6", delta_softplus=True, want_dx0=False, outs=None,
+                                     workspace=None):
+    """Gradients of sum(dy*y) of the complex-A selective scan as a dict; see lrnnx_ss_bwd_complex_args.
+    dA [D,N], dBm, dCm [B,L,N], dx0 [B,D,N] are complex64 (dLoss/dRe + i dLoss/dIm); du, ddelta, dz in the I/O
+    type; dD, dbias float32.  `ckpt`: the checkpoints a forward call returned (else they are recomputed)."""
+    io = u.dtype
+    Bsz, D, L = u.shape
+    N = _check_complex_maps(A, Bm, Cm, io, Bsz, D, L)
+    dev = u.device
+    outs = dict(outs or {})
+
+    def new(name, shape, dtype):
+        if name not in outs:
+            outs[name] = torch.empty(shape, dtype=dtype, device=dev)
+        t = outs[name]
+        if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous():
+            raise ValueError(f"{name}: expected contiguous {dtype} {tuple(shape)}")
+        return t
+
+    a = BwdComplexArgs()
+    a.struct_size = ctypes.sizeof(BwdComplexArgs)
+    a.B, a.D, a.N, a.L = Bsz, D, N, L
+    a.io_dtype = _io_dtype(u)
+    a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
+    a.delta_softplus = int(bool(delta_softplus))
+    a.u, a.u_stride_b, a.u_stride_d = _bdl(u, "u", io)
+    a.delta, a.delta_stride_b, a.delta_stride_d = _bdl(delta, "delta", io)
+    a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io)
+    a.dy, a.dy_stride_b, a.dy_stride_d = _bdl(dy, "dy", io)
+    a.A, a.Bm, a.Cm = A.data_ptr(), Bm.data_ptr(), Cm.data_ptr()
+    a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
+    a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
+    nck = -(-L // lrnnx_ckpt_interval())
+    for name, t, shape in (("x0", x0, (Bsz, D, N)), ("ckpt", ckpt, (Bsz, D, nck, N))):
+        if t is not None:
+            if t.dtype != torch.complex64 or not t.is_contiguous() or tuple(t.shape) != shape:
+                raise ValueError(f"{name}: expected contiguous complex64 {shape}")
+            setattr(a, name, t.data_ptr())
+    a.du, a.du_stride_b, a.du_stride_d = _bdl(new("du", (Bsz, D, L), io), "du", io)
+    a.ddelta, a.ddelta_stride_b, a.ddelta_stride_d = _bdl(new("ddelta", (Bsz, D, L), io), "ddelta", io)
+    if z is not None:
+        a.dz, a.dz_stride_b, a.dz_stride_d = _bdl(new("dz", (Bsz, D, L), io), "dz", io)
+    c64 = torch.complex64
+    a.dA = new("dA", (D, N), c64).data_ptr()
+    a.dBm = new("dBm", (Bsz, L, N), c64).data_ptr()
+    a.dCm = new("dCm", (Bsz, L, N), c64).data_ptr()
+    if Dskip is not None:
+        a.dD = new("dD", (D,), torch.float32).data_ptr()
+    if delta_bias is not None:
+        a.dbias = new("dbias", (D,), torch.float32).data_ptr()
+    if want_dx0:
+        a.dx0 = new("dx0", (Bsz, D, N), c64).data_ptr()
+    if workspace is None and ckpt is None:
+        nbytes = lrnnx_workspace_bytes(WS_BWD_COMPLEX, Bsz, D, N, L, a.io_dtype)
+        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
+    if workspace is not None:
+        a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    a.stream = _stream()
+    _check(lib().lrnnx_selective_scan_bwd_complex(ctypes.byref(a)))
+    return outs
 
 
 def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,

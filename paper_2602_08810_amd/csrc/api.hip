@@ -117,6 +117,10 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
         if (!supported_n((int)N)) return 0;
         return (size_t)B * D * cdiv(L, kCkptInterval) * N * sizeof(float);
     }
+    if (which == LRNNX_WS_BWD_COMPLEX) {
+        if (!supported_n((int)N)) return 0;
+        return (size_t)B * D * cdiv(L, kCkptInterval) * N * sizeof(float2);
+    }
     if (which == LRNNX_WS_LTI) {
         const int nch = lti_chunks(B, D, L);
         const size_t two = nch > 1 ? (size_t)B * (nch + cdiv(nch, lti_chunk_group())) * D * 2 * sizeof(float) : 0;
@@ -205,13 +209,17 @@ int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *a) {
 }
 
 int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *a) {
-    if (!a || a->struct_size < sizeof(lrnnx_ss_fwd_complex_args)) return LRNNX_ERR_INVALID_ARG;
+    constexpr size_t kOldSize = offsetof(lrnnx_ss_fwd_complex_args, ckpt);   // struct before `ckpt` was appended
+    if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
+    void *ckpt = a->struct_size >= sizeof(lrnnx_ss_fwd_complex_args) ? a->ckpt : nullptr;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
-    if (!a->u || !a->delta || !a->A || !a->Bm || !a->Cm || !a->y) return LRNNX_ERR_INVALID_ARG;
+    if (!a->u || !a->delta || !a->A || !a->Bm || !a->Cm) return LRNNX_ERR_INVALID_ARG;
+    if (!a->y && !ckpt && !a->x_last) return LRNNX_ERR_INVALID_ARG;          // nothing to compute
+    if (reinterpret_cast<uintptr_t>(ckpt) & 7u) return LRNNX_ERR_INVALID_ARG;
     if (a->u_stride_b < 0 || a->u_stride_d < 0 || a->delta_stride_b < 0 || a->delta_stride_d < 0 ||
-        a->y_stride_b < 0 || a->y_stride_d < a->L || (a->z && (a->z_stride_b < 0 || a->z_stride_d < 0)))
+        (a->y && (a->y_stride_b < 0 || a->y_stride_d < a->L)) || (a->z && (a->z_stride_b < 0 || a->z_stride_d < 0)))
         return LRNNX_ERR_INVALID_ARG;
     if (!supported_n(a->N)) return LRNNX_ERR_UNSUPPORTED;
     if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
@@ -232,10 +240,82 @@ int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *a) {
     p.x0 = reinterpret_cast<const float2 *>(a->x0);
     p.Bm = a->Bm; p.Cm = a->Cm;
     p.x_last = reinterpret_cast<float2 *>(a->x_last);
+    p.ckpt = reinterpret_cast<float2 *>(ckpt);
     p.vec = row_vec_ok(a->u, p.u_sb, p.u_sd, es) && row_vec_ok(a->delta, p.dl_sb, p.dl_sd, es) &&
-            row_vec_ok(a->y, p.y_sb, p.y_sd, es) && (!a->z || row_vec_ok(a->z, p.z_sb, p.z_sd, es));
+            (!a->y || row_vec_ok(a->y, p.y_sb, p.y_sd, es)) && (!a->z || row_vec_ok(a->z, p.z_sb, p.z_sd, es));
     return launch_ss_cfwd(p, a->io_dtype, a->disc, reinterpret_cast<hipStream_t>(a->stream)) == hipSuccess
                ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+}
+
+int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
+    if (!a || a->struct_size < sizeof(lrnnx_ss_bwd_complex_args)) return LRNNX_ERR_INVALID_ARG;
+    if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
+    if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
+    if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
+    if (!a->u || !a->delta || !a->A || !a->Bm || !a->Cm || !a->dy) return LRNNX_ERR_INVALID_ARG;
+    if (!a->du || !a->ddelta || !a->dA || !a->dBm || !a->dCm) return LRNNX_ERR_INVALID_ARG;
+    if ((a->dz && !a->z) || (a->dD && !a->Dskip) || (a->dbias && !a->delta_bias)) return LRNNX_ERR_INVALID_ARG;
+    if (a->u_stride_b < 0 || a->u_stride_d < 0 || a->delta_stride_b < 0 || a->delta_stride_d < 0 ||
+        a->dy_stride_b < 0 || a->dy_stride_d < 0 || (a->z && (a->z_stride_b < 0 || a->z_stride_d < 0)) ||
+        a->du_stride_b < 0 || a->du_stride_d < a->L || a->ddelta_stride_b < 0 || a->ddelta_stride_d < a->L ||
+        (a->dz && (a->dz_stride_b < 0 || a->dz_stride_d < a->L)))
+        return LRNNX_ERR_INVALID_ARG;
+    if (!supported_n(a->N)) return LRNNX_ERR_UNSUPPORTED;
+    if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
+    if (!aligned16(a->Bm) || !aligned16(a->Cm) || !aligned16(a->dBm) || !aligned16(a->dCm)) return LRNNX_ERR_INVALID_ARG;
+    for (const void *q : {a->A, a->x0, a->ckpt, (const void *)a->dA, (const void *)a->dx0, (const void *)a->workspace})
+        if (reinterpret_cast<uintptr_t>(q) & 7u) return LRNNX_ERR_INVALID_ARG;
+    const size_t es = elem_size(a->io_dtype);
+    const size_t ck_bytes = (size_t)a->B * a->D * cdiv(a->L, kCkptInterval) * a->N * sizeof(float2);
+    if (!a->ckpt && (!a->workspace || a->workspace_bytes < ck_bytes)) return LRNNX_ERR_WORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
+
+    const float2 *ckpt = reinterpret_cast<const float2 *>(a->ckpt);
+    if (!ckpt) {                                   // state-only forward sweep: writes the checkpoints
+        CFwdParams f{};
+        f.B = a->B; f.D = a->D; f.N = a->N; f.L = a->L;
+        f.softplus = a->delta_softplus ? 1 : 0;
+        f.u = a->u; f.delta = a->delta;
+        f.u_sb = a->u_stride_b; f.u_sd = a->u_stride_d; f.dl_sb = a->delta_stride_b; f.dl_sd = a->delta_stride_d;
+        f.A = reinterpret_cast<const float2 *>(a->A); f.bias = a->delta_bias;
+        f.x0 = reinterpret_cast<const float2 *>(a->x0);
+        f.Bm = a->Bm; f.Cm = a->Cm;
+        f.ckpt = reinterpret_cast<float2 *>(a->workspace);
+        f.vec = row_vec_ok(a->u, f.u_sb, f.u_sd, es) && row_vec_ok(a->delta, f.dl_sb, f.dl_sd, es);
+        if (launch_ss_cfwd(f, a->io_dtype, a->disc, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+        ckpt = f.ckpt;
+    }
+
+    CBwdParams p{};
+    p.B = a->B; p.D = a->D; p.N = a->N; p.L = a->L;
+    p.softplus = a->delta_softplus ? 1 : 0;
+    p.u = a->u; p.delta = a->delta; p.z = a->z; p.dy = a->dy;
+    p.du = a->du; p.ddelta = a->ddelta; p.dz = a->dz;
+    p.u_sb = a->u_stride_b; p.u_sd = a->u_stride_d; p.dl_sb = a->delta_stride_b; p.dl_sd = a->delta_stride_d;
+    p.z_sb = a->z_stride_b; p.z_sd = a->z_stride_d; p.dy_sb = a->dy_stride_b; p.dy_sd = a->dy_stride_d;
+    p.du_sb = a->du_stride_b; p.du_sd = a->du_stride_d; p.dd_sb = a->ddelta_stride_b; p.dd_sd = a->ddelta_stride_d;
+    p.dz_sb = a->dz_stride_b; p.dz_sd = a->dz_stride_d;
+    p.A = reinterpret_cast<const float2 *>(a->A); p.ckpt = ckpt;
+    p.Dskip = a->Dskip; p.bias = a->delta_bias;
+    p.Bm = a->Bm; p.Cm = a->Cm;
+    p.dA = reinterpret_cast<float2 *>(a->dA); p.dBm = reinterpret_cast<float2 *>(a->dBm);
+    p.dCm = reinterpret_cast<float2 *>(a->dCm); p.dx0 = reinterpret_cast<float2 *>(a->dx0);
+    p.dD = a->dD; p.dbias = a->dbias;
+    p.vec = row_vec_ok(a->u, p.u_sb, p.u_sd, es) && row_vec_ok(a->delta, p.dl_sb, p.dl_sd, es) &&
+            row_vec_ok(a->dy, p.dy_sb, p.dy_sd, es) && (!a->z || row_vec_ok(a->z, p.z_sb, p.z_sd, es)) &&
+            row_vec_ok(a->du, p.du_sb, p.du_sd, es) && row_vec_ok(a->ddelta, p.dd_sb, p.dd_sd, es) &&
+            (!a->dz || row_vec_ok(a->dz, p.dz_sb, p.dz_sd, es));
+    p.G = cbwd_channels_per_group(a->B, a->D, a->N);
+
+    const int64_t nbc = (int64_t)a->B * a->L * a->N * 2;                 // floats
+    FillList z{};
+    z.ptr[0] = reinterpret_cast<float *>(a->dBm); z.count[0] = nbc;
+    z.ptr[1] = reinterpret_cast<float *>(a->dCm); z.count[1] = nbc;
+    z.ptr[2] = reinterpret_cast<float *>(a->dA); z.count[2] = (int64_t)a->D * a->N * 2;
+    z.ptr[3] = a->dD; z.count[3] = a->D;
+    z.ptr[4] = a->dbias; z.count[4] = a->D;
+    if (launch_fill(z, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    return launch_ss_cbwd(p, a->io_dtype, a->disc, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }
 
 int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {

@@ -40,6 +40,23 @@ struct CFwdParams {
     const float2 *x0;        // [B,D,N] complex
     const void *Bm, *Cm;     // [B,L,N] complex in the I/O type
     float2 *x_last;
+    float2 *ckpt;            // [B,D,ceil(L/kCkptInterval),N] complex: state entering every kCkptInterval-th step, or null
+};
+
+// backward of the same
+struct CBwdParams {
+    int B, D, N;
+    int64_t L;
+    int softplus, vec;
+    int G;                   // channels per workgroup
+    const void *u, *delta, *z, *dy;
+    void *du, *ddelta, *dz;
+    int64_t u_sb, u_sd, dl_sb, dl_sd, z_sb, z_sd, dy_sb, dy_sd, du_sb, du_sd, dd_sb, dd_sd, dz_sb, dz_sd;
+    const float2 *A, *ckpt;
+    const float *Dskip, *bias;
+    const void *Bm, *Cm;     // [B,L,N] complex in the I/O type
+    float2 *dA, *dBm, *dCm, *dx0;
+    float *dD, *dbias;
 };
 
 struct BwdParams {
@@ -108,6 +125,8 @@ hipError_t launch_lti_step(int B, int P, const float2 *lambda, float2 *x, const 
 hipError_t launch_ss_fwd(const FwdParams &p, int io_dtype, int disc, hipStream_t s);
 hipError_t launch_ss_carry(const FwdParams &p, hipStream_t s);
 hipError_t launch_ss_cfwd(const CFwdParams &p, int io_dtype, int disc, hipStream_t s);
+hipError_t launch_ss_cbwd(const CBwdParams &p, int io_dtype, int disc, hipStream_t s);
+int cbwd_channels_per_group(int B, int D, int N);
 hipError_t launch_ss_bwd(const BwdParams &p, int io_dtype, int disc, hipStream_t s);
 hipError_t launch_lti(const LtiParams &p, hipStream_t s);
 hipError_t launch_lti_onepass(const LtiParams &p, hipStream_t s);

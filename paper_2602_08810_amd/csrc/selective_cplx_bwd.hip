@@ -1,0 +1,469 @@
+// Backward selective scan with a COMPLEX diagonal state matrix for gfx950: reverse-mode derivative of
+//     x_{l,n} = a(Delta_l, A[d,n]) x_{l-1,n} + g(Delta_l, A[d,n]) Bm[b,l,n] u[b,d,l]        (complex)
+//     y[b,d,l] = Re( sum_n Cm[b,l,n] x_{l,n} ) + Dskip[d] u[b,d,l],  then the optional gate
+// (Eq. 2 of the paper with a complex diagonal A as in the layers of Sec. 2.2.1, states recomputed from checkpoints
+// as Sec. 3 prescribes for the real scan).
+//
+// The gradient of the real loss with respect to a complex quantity q is dLoss/dRe q + i dLoss/dIm q.  With it, for
+// one (b,d) row and one state n, H_l = grad x_l:
+//     H_l       = dypre_l conj(Cm_l) + conj(a_{l+1}) H_{l+1}        (the same affine scan, time reversed)
+//     dCm_l    += dypre_l conj(x_l)            dBm_l += H_l conj(g_l) u_l
+//     du_l     += Re(H_l conj(g_l Bm_l))       grad a_l = H_l conj(x_{l-1})     grad g_l = H_l conj(Bm_l) u_l
+//     dDelta_l += Re(grad a_l conj(da/dDelta) + grad g_l conj(dg/dDelta))
+//     dA_n     += grad a_l conj(da/dA) + grad g_l conj(dg/dA)
+//
+// Mapping: that of the real backward kernel.  Time runs along the lanes (a lane owns T consecutive steps of a tile),
+// the N states are split over the W = N/NK wavefronts of a workgroup, which work on the same channel at the same
+// time and loop over G channels, so the sums of dBm/dCm over channels stay in registers.  Both complex maps of the
+// tile live in LDS in their I/O type (a bf16 pair is one 32-bit word), in slices private to the wavefront that owns
+// the states.  What is summed over n (du, dDelta, ypre) goes through LDS once per (channel, tile).
+#include "kernels.hpp"
+#include "scan_common.hpp"
+#include "cplx_common.hpp"
+
+namespace lrnnx {
+
+constexpr int kMaxGc = 64;
+
+namespace {
+
+// NK consecutive complex words, 16 bytes at a time where they fill whole 16-byte chunks (the caller's base pointer
+// is 16-byte aligned and the row pitch N * sizeof(CW) is then a multiple of 16 too)
+template <typename CW, int NK>
+__device__ __forceinline__ void load_cwords(const CW *p, CW *out) {
+    constexpr int BYTES = NK * (int)sizeof(CW);
+    if constexpr (BYTES % 16 == 0) {
+        uint4 r[BYTES / 16];
+#pragma unroll
+        for (int c = 0; c < BYTES / 16; ++c) r[c] = reinterpret_cast<const uint4 *>(p)[c];
+        __builtin_memcpy(out, r, BYTES);
+    } else {
+#pragma unroll
+        for (int k = 0; k < NK; ++k) out[k] = p[k];
+    }
+}
+
+// Sum over the 32 lanes of each half-wavefront of four per-lane values at once: two exchange steps leave each lane
+// of a quad with the quad's sum of ONE value (lane%4 = 0,1,2,3 -> value 0,2,1,3), two rotations sum the quads of a
+// row, one swizzle sums the two rows.  Lanes 0-3 and 32-35 own the results.
+__device__ __forceinline__ float half_sum4(const float *v4, int lane) {
+    const bool b0 = lane & 1, b1 = lane & 2;
+    float kA = b0 ? v4[2] : v4[0], kB = b0 ? v4[3] : v4[1];
+    const float sA = b0 ? v4[0] : v4[2], sB = b0 ? v4[1] : v4[3];
+    kA += dpp<0xB1>(0.0f, sA);                                  // quad_perm [1,0,3,2]
+    kB += dpp<0xB1>(0.0f, sB);
+    float v = b1 ? kB : kA;
+    v += dpp<0x4E>(0.0f, b1 ? kA : kB);                         // quad_perm [2,3,0,1]
+    v += dpp<0x124>(0.0f, v);                                   // row_ror:4
+    v += dpp<0x128>(0.0f, v);                                   // row_ror:8
+    v += i2f(__builtin_amdgcn_ds_swizzle(f2i(v), 0x401F));      // lane ^ 16
+    return v;
+}
+__device__ __forceinline__ float half_sum(float v) {
+    v += dpp<0xB1>(0.0f, v);
+    v += dpp<0x4E>(0.0f, v);
+    v += dpp<0x124>(0.0f, v);
+    v += dpp<0x128>(0.0f, v);
+    v += i2f(__builtin_amdgcn_ds_swizzle(f2i(v), 0x401F));
+    return v;
+}
+
+}  // namespace
+
+template <typename IO, int N, int NK, int T, int DISC>
+__global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p) {
+    using CW = typename cword<IO>::type;
+    constexpr int W = N / NK;
+    constexpr int NT = W * 64;
+    constexpr int TILE = 64 * T;
+    constexpr int TPW = TILE / NT;                   // flat steps per thread in prologue / epilogue
+    constexpr int TQ = T / 4;
+    constexpr int CK_PER_TILE = TILE / (int)kCkptInterval;
+    constexpr int FL = 8;                            // lanes whose dBm/dCm sums are flushed together
+    static_assert(T % 4 == 0 && T % W == 0 && TPW >= 1 && TPW <= 8, "tile shape");
+    static_assert(TILE % kCkptInterval == 0, "tiles must start on checkpoints");
+    static_assert(W * 3 * TILE >= 2 * FL * T * N * 2, "flush buffer must fit in the partials area");
+
+    __shared__ __attribute__((aligned(16))) float sIn[3 * TILE];          // delta, u, dypre   [q][lane][4]
+    __shared__ __attribute__((aligned(16))) float sPart[W * 3 * TILE];    // per wave: ypre, du, ddelta partials
+    __shared__ __attribute__((aligned(16))) CW sB[N * TILE];              // maps of the tile: [n][q][lane][4], wave-private slices
+    __shared__ __attribute__((aligned(16))) CW sC[N * TILE];
+    __shared__ float2 sH[kMaxGc * N];     // conj(a_{l0}) H_{l0} carried to the earlier tile, per (channel, n)
+    __shared__ float2 sdA[2][kMaxGc * N]; // per half-wavefront partial sums of dA
+    __shared__ float sdD[2 * W * kMaxGc]; // dD and dbias partial sums per (half-wavefront, wavefront, channel)
+    __shared__ float sdb[2 * W * kMaxGc];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int b = blockIdx.y;
+    const int d0 = blockIdx.x * p.G;
+    const int Gact = (p.D - d0 < p.G) ? p.D - d0 : p.G;
+    const int64_t L = p.L;
+    const int64_t ntiles = (L + TILE - 1) / TILE;
+    const int64_t nck = (L + kCkptInterval - 1) / kCkptInterval;
+    const bool vec = p.vec != 0;
+    const bool has_z = p.z != nullptr;
+
+    for (int i = tid; i < kMaxGc * N; i += NT) {
+        sH[i] = make_float2(0.0f, 0.0f); sdA[0][i] = make_float2(0.0f, 0.0f); sdA[1][i] = make_float2(0.0f, 0.0f);
+    }
+    for (int i = tid; i < 2 * W * kMaxGc; i += NT) { sdD[i] = 0.0f; sdb[i] = 0.0f; }
+
+    const int64_t bc0 = (int64_t)b * L * N;                           // first complex element of this batch entry's maps
+    const CW *Bm = reinterpret_cast<const CW *>(p.Bm) + bc0;
+    const CW *Cm = reinterpret_cast<const CW *>(p.Cm) + bc0;
+
+    const int f0 = tid * TPW;
+    auto fslot = [](int f) { return (((f % T) / 4) * 64 + f / T) * 4 + (f % 4); };
+
+    for (int64_t tile = ntiles - 1; tile >= 0; --tile) {
+        const int64_t l0 = tile * TILE;
+        const int rem = (L - l0 < TILE) ? (int)(L - l0) : TILE;      // valid steps of this tile
+
+        // ---- this wavefront's NK columns of both maps into its own slices of LDS; zeroed dBm/dCm sums
+        float2 dBacc[NK][T], dCacc[NK][T];
+        {
+            const CW *BmT = Bm + l0 * N + w * NK, *CmT = Cm + l0 * N + w * NK;
+            CW tb[T][NK], tc[T][NK];
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                if (lane * T + t < rem) {
+                    load_cwords<CW, NK>(BmT + (unsigned)((lane * T + t) * N), tb[t]);
+                    load_cwords<CW, NK>(CmT + (unsigned)((lane * T + t) * N), tc[t]);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < NK; ++k) { tb[t][k] = CW{}; tc[t][k] = CW{}; }
+                }
+#pragma unroll
+                for (int k = 0; k < NK; ++k) { dBacc[k][t] = make_float2(0.0f, 0.0f); dCacc[k][t] = make_float2(0.0f, 0.0f); }
+            }
+#pragma unroll
+            for (int k = 0; k < NK; ++k)
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    sB[(((w * NK + k) * TQ + t / 4) * 64 + lane) * 4 + (t % 4)] = tb[t][k];
+                    sC[(((w * NK + k) * TQ + t / 4) * 64 + lane) * 4 + (t % 4)] = tc[t][k];
+                }
+        }
+
+        // per-channel inputs are fetched one channel ahead
+        RawFew<IO, TPW> r_u, r_dl, r_dy, r_z;
+        float2 pA[NK], pck[NK];
+        float pDsk, pbias;
+        auto prefetch = [&](int g) {
+            const int d = d0 + g;
+            const int64_t row = (int64_t)b * p.D + d;
+            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.u) + b * p.u_sb + d * p.u_sd + l0, f0, rem, vec, r_u);
+            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd + l0, f0, rem, vec, r_dl);
+            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.dy) + b * p.dy_sb + d * p.dy_sd + l0, f0, rem, vec, r_dy);
+            if (has_z) load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd + l0, f0, rem, vec, r_z);
+#pragma unroll
+            for (int k = 0; k < NK; ++k) {
+                pA[k] = p.A[d * N + w * NK + k];
+                pck[k] = p.ckpt[(row * nck + tile * CK_PER_TILE) * N + w * NK + k];
+            }
+            pDsk = p.Dskip ? p.Dskip[d] : 0.0f;
+            pbias = p.bias ? p.bias[d] : 0.0f;
+        };
+        prefetch(0);
+
+        for (int g = 0; g < Gact; ++g) {
+            const int d = d0 + g;
+            const float Dsk = pDsk, bias = pbias;
+            float2 cA[NK], cck[NK];
+#pragma unroll
+            for (int k = 0; k < NK; ++k) { cA[k] = pA[k]; cck[k] = pck[k]; }
+
+            // ---- prologue: each thread prepares TPW flat steps for everybody
+            float e_sg[TPW], e_zf[TPW];
+            {
+                float e_u[TPW], r_d[TPW], e_dy[TPW], e_z[TPW];
+                unpack_few<IO, TPW>(r_u, e_u);
+                unpack_few<IO, TPW>(r_dl, r_d);
+                unpack_few<IO, TPW>(r_dy, e_dy);
+                if (has_z) unpack_few<IO, TPW>(r_z, e_z);
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) {
+                    float s = r_d[i] + bias, sp, sg, dyp;
+                    if (p.softplus) softplus_sigmoid(s, sp, sg); else { sp = s; sg = 1.0f; }
+                    e_sg[i] = sg;
+                    if (has_z) {                                 // y = ypre z sig(z): dz = dy ypre sig (1 + z (1 - sig))
+                        const float sz = sigmoid_fast(e_z[i]);
+                        const float dsz = e_dy[i] * sz;
+                        dyp = dsz * e_z[i];
+                        e_zf[i] = dsz * __builtin_fmaf(e_z[i], 1.0f - sz, 1.0f);
+                    } else { e_zf[i] = 0.0f; dyp = e_dy[i]; }
+                    sIn[0 * TILE + fslot(f0 + i)] = (f0 + i < rem) ? sp : 0.0f;
+                    sIn[1 * TILE + fslot(f0 + i)] = e_u[i];
+                    sIn[2 * TILE + fslot(f0 + i)] = dyp;
+                }
+            }
+            __syncthreads();
+            if (g + 1 < Gact) prefetch(g + 1);
+
+            // ---- main: this lane's T steps, this wavefront's NK states
+            float dl[T], dyp[T], uv[T], ypre[T], pdu[T], pdd[T];
+#pragma unroll
+            for (int q = 0; q < TQ; ++q) {
+                const float4 v0 = *reinterpret_cast<const float4 *>(&sIn[0 * TILE + (q * 64 + lane) * 4]);
+                const float4 v1 = *reinterpret_cast<const float4 *>(&sIn[1 * TILE + (q * 64 + lane) * 4]);
+                const float4 v2 = *reinterpret_cast<const float4 *>(&sIn[2 * TILE + (q * 64 + lane) * 4]);
+                dl[4 * q] = v0.x; dl[4 * q + 1] = v0.y; dl[4 * q + 2] = v0.z; dl[4 * q + 3] = v0.w;
+                uv[4 * q] = v1.x; uv[4 * q + 1] = v1.y; uv[4 * q + 2] = v1.z; uv[4 * q + 3] = v1.w;
+                dyp[4 * q] = v2.x; dyp[4 * q + 1] = v2.y; dyp[4 * q + 2] = v2.z; dyp[4 * q + 3] = v2.w;
+            }
+            float sum_dl = 0.0f;
+#pragma unroll
+            for (int t = 0; t < T; ++t) { sum_dl += dl[t]; ypre[t] = 0.0f; pdu[t] = 0.0f; pdd[t] = 0.0f; }
+            const float dl_next0 = dpp<DPP_WAVE_SHL1>(0.0f, dl[0]);        // first Delta of the next lane (0 past lane 63)
+            const float sum_shift = sum_dl - dl[0] + dl_next0;
+
+            float dAr4[NK], dAi4[NK];
+#pragma unroll
+            for (int k = 0; k < NK; ++k) {
+                const int n = w * NK + k;
+                const CCoef cc = make_ccoef(cA[k].x, cA[k].y);
+                const float2 xck = cck[k];
+                const float2 hc = sH[g * N + n];
+                const CW *sBn = &sB[(n * TQ * 64 + lane) * 4], *sCn = &sC[(n * TQ * 64 + lane) * 4];
+                auto mapB = [&](int t) { return cword<IO>::unpack(sBn[(t / 4) * 256 + (t % 4)]); };
+                auto mapC = [&](int t) { return cword<IO>::unpack(sCn[(t / 4) * 256 + (t % 4)]); };
+
+                // forward recompute of the states of this tile
+                float2 a[T + 1], gg[T], x[T];
+                float2 P = make_float2(1.0f, 0.0f), S = make_float2(0.0f, 0.0f);
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    cdisc_ag<DISC>(dl[t], cc, a[t], gg[t]);
+                    const float2 Bv = mapB(t);
+                    if constexpr (DISC == DISC_ZOH_S6 || DISC == DISC_DIRAC) {
+                        const float gu = gg[t].x * uv[t];                  // the gain is real
+                        x[t] = make_float2(gu * Bv.x, gu * Bv.y);
+                    } else {
+                        x[t] = cxmul(make_float2(gg[t].x * uv[t], gg[t].y * uv[t]), Bv);
+                    }
+                    S = (t == 0) ? x[0] : cxfma(a[t], S, x[t]);           // the fold starts from zero
+                    if constexpr (DISC == DISC_BILINEAR) P = cxmul(P, a[t]);
+                }
+                if constexpr (DISC != DISC_BILINEAR) P = cexp_dt(sum_dl, cc.A2r, cc.Arev);
+                if (lane == 0) S = cxfma(P, xck, S);                       // the checkpointed state enters through lane 0
+
+                // lane aggregate of the adjoint H_l = c_l + conj(a_{l+1}) H_{l+1}; the multiplier of the tile's last
+                // step is 1 because the carried value is already conj(a_{l1}) H_{l1}
+                a[T] = make_float2(dpp<DPP_WAVE_SHL1>(1.0f, a[0].x), dpp<DPP_WAVE_SHL1>(0.0f, a[0].y));
+                float2 Pr = make_float2(1.0f, 0.0f), Sr = make_float2(0.0f, 0.0f);
+#pragma unroll
+                for (int t = T - 1; t >= 0; --t) {
+                    const float2 Cv = mapC(t);
+                    const float2 c = make_float2(Cv.x * dyp[t], -Cv.y * dyp[t]);
+                    Sr = (t == T - 1) ? c : cxcfma(a[t + 1], Sr, c);
+                    if constexpr (DISC == DISC_BILINEAR) Pr = cxmulc(Pr, a[t + 1]);
+                }
+                if constexpr (DISC != DISC_BILINEAR) {
+                    const float2 e = cexp_dt(sum_shift, cc.A2r, cc.Arev);
+                    Pr = make_float2(e.x, -e.y);
+                }
+                if (lane == 63) Sr = cxfma(Pr, hc, Sr);                    // the carried adjoint enters through lane 63
+
+                cwave_scan_fwd_rev(P, S, Pr, Sr, lane);
+                const float2 xin = make_float2(dpp<DPP_WAVE_SHR1>(xck.x, S.x), dpp<DPP_WAVE_SHR1>(xck.y, S.y));
+                {
+                    float2 xp = xin;
+#pragma unroll
+                    for (int t = 0; t < T; ++t) { xp = cxfma(a[t], xp, x[t]); x[t] = xp; }
+                }
+                const float2 H0 = Sr;                                       // H of this lane's first step
+                float2 R = make_float2(dpp<DPP_WAVE_SHL1>(hc.x, Sr.x), dpp<DPP_WAVE_SHL1>(hc.y, Sr.y));   // H of the next lane's first step
+                if (lane == 0) sH[g * N + n] = cxcfma(a[0], H0, make_float2(0.0f, 0.0f));   // carried to the earlier tile
+
+                float2 dA_part = make_float2(0.0f, 0.0f);
+#pragma unroll
+                for (int t = T - 1; t >= 0; --t) {
+                    const float2 Cv = mapC(t), Bv = mapB(t);
+                    R = cxcfma(a[t + 1], R, make_float2(Cv.x * dyp[t], -Cv.y * dyp[t]));   // H_t
+                    const float2 xprev = (t > 0) ? x[t - 1] : xin;
+                    dCacc[k][t].x = __builtin_fmaf(dyp[t], x[t].x, dCacc[k][t].x);        // dypre conj(x)
+                    dCacc[k][t].y = __builtin_fmaf(-dyp[t], x[t].y, dCacc[k][t].y);
+                    ypre[t] = __builtin_fmaf(Cv.x, x[t].x, __builtin_fmaf(-Cv.y, x[t].y, ypre[t]));   // Re(C x)
+                    const float2 hb = cxmulc(R, Bv);                        // H conj(B)
+                    const float2 ga = cxmulc(R, xprev);                     // grad a
+                    if constexpr (DISC == DISC_ZOH_S6) {
+                        pdu[t] += hb.x;                                      // sum_n Re(H conj(B)); scaled by Delta resp. u after the loop
+                        const float du_ = dl[t] * uv[t];
+                        dBacc[k][t].x = __builtin_fmaf(R.x, du_, dBacc[k][t].x);
+                        dBacc[k][t].y = __builtin_fmaf(R.y, du_, dBacc[k][t].y);
+                        const float2 q = cxmulc(ga, a[t]);                   // grad a conj(a)
+                        pdd[t] = __builtin_fmaf(q.x, cc.Ar, __builtin_fmaf(q.y, cc.Ai, pdd[t]));   // Re(q conj(A))
+                        dA_part.x = __builtin_fmaf(q.x, dl[t], dA_part.x);
+                        dA_part.y = __builtin_fmaf(q.y, dl[t], dA_part.y);
+                    } else {
+                        float2 a_t, a_A, g_t, g_A;
+                        cdisc_partials<DISC>(dl[t], cc, a[t], gg[t], a_t, a_A, g_t, g_A);
+                        const float2 gq = make_float2(hb.x * uv[t], hb.y * uv[t]);      // grad g
+                        pdu[t] += cxmulc(hb, gg[t]).x;                                     // Re(H conj(B) conj(g))
+                        const float2 rg = cxmulc(R, gg[t]);
+                        dBacc[k][t].x = __builtin_fmaf(rg.x, uv[t], dBacc[k][t].x);
+                        dBacc[k][t].y = __builtin_fmaf(rg.y, uv[t], dBacc[k][t].y);
+                        pdd[t] += cxmulc(ga, a_t).x + cxmulc(gq, g_t).x;
+                        const float2 s1 = cxmulc(ga, a_A), s2 = cxmulc(gq, g_A);
+                        dA_part.x += s1.x + s2.x;
+                        dA_part.y += s1.y + s2.y;
+                    }
+                }
+                dAr4[k] = dA_part.x; dAi4[k] = dA_part.y;
+                __builtin_amdgcn_sched_barrier(0);   // keep the states apart: interleaving them costs more registers than there are
+            }
+            if constexpr (NK == 4) {
+                const float vr = half_sum4(dAr4, lane), vi = half_sum4(dAi4, lane);
+                if ((lane & 0x1C) == 0) {
+                    float2 &dst = sdA[lane >> 5][g * N + w * NK + ((lane & 1) << 1) + ((lane >> 1) & 1)];
+                    dst.x += vr; dst.y += vi;
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < NK; ++k) {
+                    const float vr = half_sum(dAr4[k]), vi = half_sum(dAi4[k]);
+                    if ((lane & 31) == 0) { float2 &dst = sdA[lane >> 5][g * N + w * NK + k]; dst.x += vr; dst.y += vi; }
+                }
+            }
+            if constexpr (DISC == DISC_ZOH_S6) {     // dDelta += u sum_n Re(H conj(B)) ;  du = Delta sum_n Re(H conj(B))
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    pdd[t] = __builtin_fmaf(uv[t], pdu[t], pdd[t]);
+                    pdu[t] *= dl[t];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < TQ; ++q) {
+                float *base = &sPart[(w * 3) * TILE + (q * 64 + lane) * 4];
+                *reinterpret_cast<float4 *>(base) = make_float4(ypre[4 * q], ypre[4 * q + 1], ypre[4 * q + 2], ypre[4 * q + 3]);
+                *reinterpret_cast<float4 *>(base + TILE) = make_float4(pdu[4 * q], pdu[4 * q + 1], pdu[4 * q + 2], pdu[4 * q + 3]);
+                *reinterpret_cast<float4 *>(base + 2 * TILE) = make_float4(pdd[4 * q], pdd[4 * q + 1], pdd[4 * q + 2], pdd[4 * q + 3]);
+            }
+            __syncthreads();
+
+            // ---- epilogue: the threads share the tile in flat order
+            {
+                float o_du[TPW], o_dd[TPW], o_dz[TPW];
+                float dD_part = 0.0f, db_part = 0.0f;
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) {
+                    const float e_u = sIn[1 * TILE + fslot(f0 + i)], e_dyp = sIn[2 * TILE + fslot(f0 + i)];
+                    float yp = Dsk * e_u, s_du = 0.0f, s_dd = 0.0f;
+#pragma unroll
+                    for (int ww = 0; ww < W; ++ww) {
+                        yp += sPart[(ww * 3 + 0) * TILE + fslot(f0 + i)];
+                        s_du += sPart[(ww * 3 + 1) * TILE + fslot(f0 + i)];
+                        s_dd += sPart[(ww * 3 + 2) * TILE + fslot(f0 + i)];
+                    }
+                    o_du[i] = __builtin_fmaf(e_dyp, Dsk, s_du);
+                    o_dd[i] = s_dd * e_sg[i];
+                    o_dz[i] = yp * e_zf[i];
+                    dD_part = __builtin_fmaf(e_dyp, e_u, dD_part);
+                    db_part += (f0 + i < rem) ? o_dd[i] : 0.0f;
+                }
+                store_few<IO, TPW>(reinterpret_cast<IO *>(p.du) + b * p.du_sb + d * p.du_sd + l0, f0, rem, vec, o_du);
+                store_few<IO, TPW>(reinterpret_cast<IO *>(p.ddelta) + b * p.dd_sb + d * p.dd_sd + l0, f0, rem, vec, o_dd);
+                if (p.dz) store_few<IO, TPW>(reinterpret_cast<IO *>(p.dz) + b * p.dz_sb + d * p.dz_sd + l0, f0, rem, vec, o_dz);
+                const float vD = half_sum(dD_part), vb = half_sum(db_part);
+                if ((lane & 31) == 0) {
+                    sdD[((lane >> 5) * W + w) * kMaxGc + g] += vD;
+                    sdb[((lane >> 5) * W + w) * kMaxGc + g] += vb;
+                }
+            }
+        }
+
+        // ---- add this tile's dBm/dCm sums (over the G channels) to global memory, transposed through LDS so that
+        // consecutive threads hit consecutive addresses; FL lanes (FL * T time steps) at a time
+        float2 *fbB = reinterpret_cast<float2 *>(sPart), *fbC = fbB + FL * T * N;
+        for (int j = 0; j < 64 / FL; ++j) {
+            __syncthreads();
+            if (lane / FL == j) {
+#pragma unroll
+                for (int t = 0; t < T; ++t)
+#pragma unroll
+                    for (int k = 0; k < NK; ++k) {
+                        fbB[((lane % FL) * T + t) * N + w * NK + k] = dBacc[k][t];
+                        fbC[((lane % FL) * T + t) * N + w * NK + k] = dCacc[k][t];
+                    }
+            }
+            __syncthreads();
+            const int step0 = j * FL * T;                                // within the tile
+            float *gB = reinterpret_cast<float *>(p.dBm + bc0 + (l0 + step0) * N);
+            float *gC = reinterpret_cast<float *>(p.dCm + bc0 + (l0 + step0) * N);
+            const float *lB = reinterpret_cast<const float *>(fbB), *lC = reinterpret_cast<const float *>(fbC);
+            for (int idx = tid; idx < FL * T * N * 2; idx += NT) {
+                if (step0 + idx / (2 * N) < rem) {
+                    unsafeAtomicAdd(gB + (unsigned)idx, lB[idx]);
+                    unsafeAtomicAdd(gC + (unsigned)idx, lC[idx]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- per-channel results of this workgroup
+    for (int i = tid; i < Gact * N; i += NT) {
+        const int g = i / N, n = i % N;
+        float *dst = reinterpret_cast<float *>(p.dA + (int64_t)(d0 + g) * N + n);
+        unsafeAtomicAdd(dst, sdA[0][g * N + n].x + sdA[1][g * N + n].x);
+        unsafeAtomicAdd(dst + 1, sdA[0][g * N + n].y + sdA[1][g * N + n].y);
+        if (p.dx0) p.dx0[((int64_t)b * p.D + d0 + g) * N + n] = sH[g * N + n];
+    }
+    for (int g = tid; g < Gact; g += NT) {
+        float sD = 0.0f, sb = 0.0f;
+#pragma unroll
+        for (int ww = 0; ww < 2 * W; ++ww) { sD += sdD[ww * kMaxGc + g]; sb += sdb[ww * kMaxGc + g]; }
+        if (p.dD) unsafeAtomicAdd(p.dD + d0 + g, sD);
+        if (p.dbias) unsafeAtomicAdd(p.dbias + d0 + g, sb);
+    }
+}
+
+// ---------------------------------------------------------------- launchers
+// channels per workgroup: aim at >= 512 workgroups (two per CU)
+int cbwd_channels_per_group(int B, int D, int) {
+    int64_t G = ((int64_t)B * D) / 512;
+    if (G < 8) G = 8;
+    if (G > kMaxGc) G = kMaxGc;
+    if (G > D) G = D;
+    const int64_t groups = (D + G - 1) / G;
+    G = (D + groups - 1) / groups;                     // even split
+    return (int)G;
+}
+
+template <typename IO, int N, int NK, int DISC>
+static hipError_t launch_cbwd_n(const CBwdParams &p, hipStream_t s) {
+    dim3 grid((p.D + p.G - 1) / p.G, p.B);
+    hipLaunchKernelGGL((k_ss_cbwd<IO, N, NK, 4, DISC>), grid, dim3((N / NK) * 64), 0, s, p);
+    return hipGetLastError();
+}
+
+template <typename IO, int DISC>
+static hipError_t launch_cbwd_disc(const CBwdParams &p, hipStream_t s) {
+    switch (p.N) {
+        case 1: return launch_cbwd_n<IO, 1, 1, DISC>(p, s);
+        case 2: return launch_cbwd_n<IO, 2, 2, DISC>(p, s);
+        case 4: return launch_cbwd_n<IO, 4, 4, DISC>(p, s);
+        case 8: return launch_cbwd_n<IO, 8, 4, DISC>(p, s);
+        case 16: return launch_cbwd_n<IO, 16, 4, DISC>(p, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+template <typename IO>
+static hipError_t launch_cbwd_io(const CBwdParams &p, int disc, hipStream_t s) {
+    switch (disc) {
+        case DISC_ZOH_S6: return launch_cbwd_disc<IO, DISC_ZOH_S6>(p, s);
+        case DISC_ZOH: return launch_cbwd_disc<IO, DISC_ZOH>(p, s);
+        case DISC_BILINEAR: return launch_cbwd_disc<IO, DISC_BILINEAR>(p, s);
+        case DISC_DIRAC: return launch_cbwd_disc<IO, DISC_DIRAC>(p, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_ss_cbwd(const CBwdParams &p, int io_dtype, int disc, hipStream_t s) {
+    return io_dtype == 1 ? launch_cbwd_io<bf16_t>(p, disc, s) : launch_cbwd_io<float>(p, disc, s);
+}
+
+}  // namespace lrnnx

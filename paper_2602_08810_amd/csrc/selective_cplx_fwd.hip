@@ -12,95 +12,10 @@
 // state) live one per lane and are read with v_readlane, so the loop over states stays rolled.
 #include "kernels.hpp"
 #include "scan_common.hpp"
+#include "cplx_common.hpp"
 
 namespace lrnnx {
 
-namespace {
-
-template <typename IO> struct cword;                   // one complex number in the I/O type, as stored in LDS
-template <> struct cword<bf16_t> {
-    using type = uint32_t;
-    static __device__ __forceinline__ float2 unpack(uint32_t w) { return make_float2(i2f((int)(w << 16)), i2f((int)(w & 0xFFFF0000u))); }
-};
-template <> struct cword<float> {
-    using type = float2;
-    static __device__ __forceinline__ float2 unpack(float2 w) { return w; }
-};
-
-constexpr float kInv2Pi = 0.15915494309189535f;
-
-// a = exp(dt A) for complex A = (Ar, Ai): e^{dt Ar} (cos(dt Ai), sin(dt Ai)); v_sin/v_cos take revolutions
-__device__ __forceinline__ float2 cexp_dt(float dt, float A2r, float Arev) {
-    const float e = exp2_fast(dt * A2r);
-    const float rev = dt * Arev;
-    return make_float2(e * __builtin_amdgcn_cosf(rev), e * __builtin_amdgcn_sinf(rev));
-}
-
-struct CCoef {
-    float Ar, Ai;       // A
-    float A2r, Arev;    // Ar * log2(e), Ai / (2 pi): arguments of the hardware exp2 / sin / cos
-    float iAr, iAi;     // 1 / A
-};
-__device__ __forceinline__ CCoef make_ccoef(float Ar, float Ai) {
-    CCoef c;
-    c.Ar = Ar; c.Ai = Ai; c.A2r = Ar * kLog2e; c.Arev = Ai * kInv2Pi;
-    const float den = Ar * Ar + Ai * Ai;
-    const float r = den > 0.0f ? rcp_fast(den) : 0.0f;
-    c.iAr = Ar * r; c.iAi = -Ai * r;
-    return c;
-}
-
-// multiplier a and input gain g of one step (schemes of Sec. 3, complex arithmetic)
-template <int DISC>
-__device__ __forceinline__ void cdisc_ag(float dt, const CCoef &c, float2 &a, float2 &g) {
-    if constexpr (DISC == DISC_BILINEAR) {
-        const float hr = 0.5f * dt * c.Ar, hi = 0.5f * dt * c.Ai;           // dt A / 2
-        const float wr = 1.0f - hr, wi = -hi;                               // 1 - dt A / 2
-        const float r = rcp_fast(wr * wr + wi * wi);
-        const float ir = wr * r, ii = -wi * r;                              // 1 / (1 - dt A / 2)
-        a = make_float2((1.0f + hr) * ir - hi * ii, (1.0f + hr) * ii + hi * ir);
-        g = make_float2(dt * ir, dt * ii);
-    } else {
-        a = cexp_dt(dt, c.A2r, c.Arev);
-        if constexpr (DISC == DISC_ZOH_S6) g = make_float2(dt, 0.0f);
-        else if constexpr (DISC == DISC_DIRAC) g = make_float2(1.0f, 0.0f);
-        else {                                                              // exact ZOH: (a - 1) / A
-            const float zr = dt * c.Ar, zi = dt * c.Ai;
-            // small |z|: dt (1 + z/2 + z^2/6 + z^3/24), Horner in complex arithmetic
-            float pr = 1.0f + zr * 0.25f, pi = zi * 0.25f;                  // 1 + z/4
-            float tr = pr * zr - pi * zi, ti = pr * zi + pi * zr;           // z (1 + z/4)
-            pr = 1.0f + tr * 0.33333334f; pi = ti * 0.33333334f;            // 1 + z/3 (1 + z/4)
-            tr = pr * zr - pi * zi; ti = pr * zi + pi * zr;
-            pr = 1.0f + tr * 0.5f; pi = ti * 0.5f;                          // 1 + z/2 (1 + z/3 (1 + z/4))
-            const float sr = dt * pr, si = dt * pi;
-            const float mr = a.x - 1.0f, mi = a.y;
-            const float dr = mr * c.iAr - mi * c.iAi, di = mr * c.iAi + mi * c.iAr;
-            const bool small = zr * zr + zi * zi < 0.015625f;
-            g = make_float2(small ? sr : dr, small ? si : di);
-        }
-    }
-}
-
-// One Hillis-Steele step on a complex affine pair.  Lanes without a source lane (or in a masked row) read the
-// identity pair, which leaves them unchanged.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ void cpair_step(float2 &P, float2 &S) {
-    const float qr = dpp<CTRL, ROW_MASK>(1.0f, P.x), qi = dpp<CTRL, ROW_MASK>(0.0f, P.y);
-    const float tr = dpp<CTRL, ROW_MASK>(0.0f, S.x), ti = dpp<CTRL, ROW_MASK>(0.0f, S.y);
-    S = make_float2(__builtin_fmaf(P.x, tr, __builtin_fmaf(-P.y, ti, S.x)),
-                    __builtin_fmaf(P.x, ti, __builtin_fmaf(P.y, tr, S.y)));
-    P = make_float2(P.x * qr - P.y * qi, P.x * qi + P.y * qr);
-}
-__device__ __forceinline__ void cwave_scan_fwd(float2 &P, float2 &S) {
-    cpair_step<0x111, 0xF>(P, S);
-    cpair_step<0x112, 0xF>(P, S);
-    cpair_step<0x114, 0xF>(P, S);
-    cpair_step<0x118, 0xF>(P, S);
-    cpair_step<DPP_ROW_BCAST15, 0xA>(P, S);
-    cpair_step<DPP_ROW_BCAST31, 0xC>(P, S);
-}
-
-}  // namespace
 
 template <typename IO, int N, int T, int W, int DISC>
 __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
@@ -127,7 +42,9 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
     const IO *urow = reinterpret_cast<const IO *>(p.u) + b * p.u_sb + d * p.u_sd;
     const IO *drow = reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd;
     const IO *zrow = p.z ? reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd : nullptr;
+    const bool want_y = p.y != nullptr;                 // a state-only sweep (checkpoints for the backward pass) has no y
     IO *yrow = reinterpret_cast<IO *>(p.y) + b * p.y_sb + d * p.y_sd;
+    const int64_t nck = (L + kCkptInterval - 1) / kCkptInterval;
     const CW *Bm = reinterpret_cast<const CW *>(p.Bm) + (int64_t)b * L * N;
     const CW *Cm = reinterpret_cast<const CW *>(p.Cm) + (int64_t)b * L * N;
 
@@ -203,6 +120,9 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
             }
             cwave_scan_fwd(P, S);
             float2 x = make_float2(dpp<DPP_WAVE_SHR1>(xc.x, S.x), dpp<DPP_WAVE_SHR1>(xc.y, S.y));
+            // the state entering every kCkptInterval-th step is what the backward pass restarts from
+            if (p.ckpt && (lane * T) % (int)kCkptInterval == 0 && ll < L)
+                p.ckpt[(row * nck + ll / kCkptInterval) * N + n] = x;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 const float2 Cv = cword<IO>::unpack(sC[n * PLANE + (t / 4) * QS + lane * 4 + (t % 4)]);
@@ -214,6 +134,7 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
             xiv = writelane(xiv, readlane(x.y, 63), n);
         }
 
+        if (!want_y) continue;
         if (zrow) {
             float zv[T];
             load_seg<IO, T>(zrow, ll, L, vec, zv);

@@ -44,6 +44,7 @@ def test_host_queries(lib):
     assert lib.lrnnx_workspace_bytes(4, 4, 256, 0, 4096, 2) > lib.lrnnx_workspace_bytes(4, 4, 256, 0, 4096, 0) > 0
     assert lib.lrnnx_workspace_bytes(4, 4, 256, 0, 4096, 1) == 0      # bf16 is not a dtype of the raw scan
     assert lib.lrnnx_workspace_bytes(5, 4, 256, 0, 4096, 2) > lib.lrnnx_workspace_bytes(5, 4, 256, 0, 4096, 0) > 0
+    assert lib.lrnnx_workspace_bytes(6, 2, 3, 16, 1000, 1) == 2 * 3 * ((1000 + I - 1) // I) * 16 * 8
     assert lib.lrnnx_status_string(0) == b"ok" and lib.lrnnx_status_string(3).startswith(b"workspace")
     assert lib.lrnnx_version() >= 100
 
@@ -60,6 +61,8 @@ def test_null_and_bad_struct_are_rejected_without_a_gpu(lib):
     assert lib.lrnnx_lti_diag_scan_bwd(None) == 1
     lib.lrnnx_selective_scan_fwd_complex.argtypes = [ctypes.c_void_p]
     assert lib.lrnnx_selective_scan_fwd_complex(None) == 1
+    lib.lrnnx_selective_scan_bwd_complex.argtypes = [ctypes.c_void_p]
+    assert lib.lrnnx_selective_scan_bwd_complex(None) == 1
     lib.lrnnx_diag_scan_bwd.argtypes = [ctypes.c_void_p]
     assert lib.lrnnx_diag_scan_bwd(None) == 1
     lib.lrnnx_diag_scan.argtypes = [ctypes.c_void_p]
