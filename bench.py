@@ -298,7 +298,19 @@ def _other_configs(api, torch, dev):
     nb = _selective_bytes(Bc, Dc, Nc, Lc, 2, True, False) + 2 * Bc * Lc * Nc * 2
     out["complex_fwd_B8_D1536_N16_L2048"] = {"us": tt * 1e6, "elements_per_s": Bc * Dc * Nc * Lc / tt,
                                              "hbm_GBs": nb / tt / 1e9, "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
-    del tc, Ac, Bmc, Cmc, yc
+    # its backward with the forward's checkpoints: reads u, delta, z, dy, the maps and checkpoints; writes du, ddelta, dz
+    # and the float32 complex dBm, dCm
+    _, ckc = api.lrnnx_selective_scan_fwd_complex(tc["u"], tc["delta"], Ac, Bmc, Cmc, Dskip=tc["Dskip"],
+                                                  delta_bias=tc["delta_bias"], z=tc["z"], out=yc, return_ckpt=True)
+    dyc = torch.randn(Bc, Dc, Lc, device=dev, generator=g).to(bf)
+    outs_c = {}
+    tt = _time(torch, lambda: outs_c.update(api.lrnnx_selective_scan_bwd_complex(
+        tc["u"], tc["delta"], Ac, Bmc, Cmc, dyc, Dskip=tc["Dskip"], delta_bias=tc["delta_bias"], z=tc["z"], ckpt=ckc,
+        outs=outs_c)), 10)
+    nb = 7 * Bc * Dc * Lc * 2 + 2 * Bc * Lc * Nc * 4 + 2 * Bc * Lc * Nc * 8 + Bc * Dc * (Lc // 256) * Nc * 8
+    out["complex_bwd_B8_D1536_N16_L2048"] = {"us": tt * 1e6, "elements_per_s": Bc * Dc * Nc * Lc / tt,
+                                             "hbm_GBs": nb / tt / 1e9, "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
+    del tc, Ac, Bmc, Cmc, yc, ckc, dyc, outs_c
 
     # single-token step (generation): state [B,D,N] read and written once per token
     Bs, Ds, Ns = 64, 1536, 16

@@ -76,11 +76,12 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     constexpr int W = N / NK;
     constexpr int NT = W * 64;
     constexpr int TILE = 64 * T;
-    constexpr int TPW = TILE / NT;                   // flat steps per thread in prologue / epilogue
+    constexpr int TPW = TILE / NT > 0 ? TILE / NT : 1;   // flat steps per thread in prologue / epilogue
+    constexpr int NA = TILE / TPW;                   // threads that take part in them (all, or the first wavefronts)
     constexpr int TQ = T / 4;
     constexpr int CK_PER_TILE = TILE / (int)kCkptInterval;
     constexpr int FL = 8;                            // lanes whose dBm/dCm sums are flushed together
-    static_assert(T % 4 == 0 && T % W == 0 && TPW >= 1 && TPW <= 8, "tile shape");
+    static_assert(T % 4 == 0 && (T % W == 0 || W % T == 0) && TPW <= 8 && NA % 64 == 0 && NA <= NT, "tile shape");
     static_assert(TILE % kCkptInterval == 0, "tiles must start on checkpoints");
     static_assert(W * 3 * TILE >= 2 * FL * T * N * 2, "flush buffer must fit in the partials area");
 
@@ -89,7 +90,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     __shared__ __attribute__((aligned(16))) CW sB[N * TILE];              // maps of the tile: [n][q][lane][4], wave-private slices
     __shared__ __attribute__((aligned(16))) CW sC[N * TILE];
     __shared__ float2 sH[kMaxGc * N];     // conj(a_{l0}) H_{l0} carried to the earlier tile, per (channel, n)
-    __shared__ float2 sdA[2][kMaxGc * N]; // per half-wavefront partial sums of dA
+    __shared__ float sdA[2][kMaxGc * N * 2];   // per half-wavefront partial sums of dA, (re, im) pairs
     __shared__ float sdD[2 * W * kMaxGc]; // dD and dbias partial sums per (half-wavefront, wavefront, channel)
     __shared__ float sdb[2 * W * kMaxGc];
 
@@ -106,7 +107,8 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     const bool has_z = p.z != nullptr;
 
     for (int i = tid; i < kMaxGc * N; i += NT) {
-        sH[i] = make_float2(0.0f, 0.0f); sdA[0][i] = make_float2(0.0f, 0.0f); sdA[1][i] = make_float2(0.0f, 0.0f);
+        sH[i] = make_float2(0.0f, 0.0f);
+        sdA[0][2 * i] = 0.0f; sdA[0][2 * i + 1] = 0.0f; sdA[1][2 * i] = 0.0f; sdA[1][2 * i + 1] = 0.0f;
     }
     for (int i = tid; i < 2 * W * kMaxGc; i += NT) { sdD[i] = 0.0f; sdb[i] = 0.0f; }
 
@@ -115,6 +117,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     const CW *Cm = reinterpret_cast<const CW *>(p.Cm) + bc0;
 
     const int f0 = tid * TPW;
+    const bool io_thread = NA == NT || tid < NA;                      // wave-uniform: NA is a multiple of 64
     auto fslot = [](int f) { return (((f % T) / 4) * 64 + f / T) * 4 + (f % 4); };
 
     for (int64_t tile = ntiles - 1; tile >= 0; --tile) {
@@ -154,10 +157,12 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
         auto prefetch = [&](int g) {
             const int d = d0 + g;
             const int64_t row = (int64_t)b * p.D + d;
-            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.u) + b * p.u_sb + d * p.u_sd + l0, f0, rem, vec, r_u);
-            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd + l0, f0, rem, vec, r_dl);
-            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.dy) + b * p.dy_sb + d * p.dy_sd + l0, f0, rem, vec, r_dy);
-            if (has_z) load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd + l0, f0, rem, vec, r_z);
+            if (io_thread) {
+                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.u) + b * p.u_sb + d * p.u_sd + l0, f0, rem, vec, r_u);
+                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd + l0, f0, rem, vec, r_dl);
+                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.dy) + b * p.dy_sb + d * p.dy_sd + l0, f0, rem, vec, r_dy);
+                if (has_z) load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd + l0, f0, rem, vec, r_z);
+            }
 #pragma unroll
             for (int k = 0; k < NK; ++k) {
                 pA[k] = p.A[d * N + w * NK + k];
@@ -177,7 +182,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
 
             // ---- prologue: each thread prepares TPW flat steps for everybody
             float e_sg[TPW], e_zf[TPW];
-            {
+            if (io_thread) {
                 float e_u[TPW], r_d[TPW], e_dy[TPW], e_z[TPW];
                 unpack_few<IO, TPW>(r_u, e_u);
                 unpack_few<IO, TPW>(r_dl, r_d);
@@ -314,18 +319,18 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
                 dAr4[k] = dA_part.x; dAi4[k] = dA_part.y;
                 __builtin_amdgcn_sched_barrier(0);   // keep the states apart: interleaving them costs more registers than there are
             }
-            if constexpr (NK == 4) {
-                const float vr = half_sum4(dAr4, lane), vi = half_sum4(dAi4, lane);
-                if ((lane & 0x1C) == 0) {
-                    float2 &dst = sdA[lane >> 5][g * N + w * NK + ((lane & 1) << 1) + ((lane >> 1) & 1)];
-                    dst.x += vr; dst.y += vi;
+            // the per-lane sums of dA: four real values (two states) per joint reduction; lanes 0-3 and 32-35 own them
+            if constexpr (NK % 2 == 0) {
+#pragma unroll
+                for (int k2 = 0; k2 < NK; k2 += 2) {
+                    const float v4[4] = {dAr4[k2], dAr4[k2 + 1], dAi4[k2], dAi4[k2 + 1]};
+                    const float v = half_sum4(v4, lane);       // lane % 4 = 0,1,2,3 holds value 0,2,1,3
+                    if ((lane & 0x1C) == 0)
+                        sdA[lane >> 5][((g * N + w * NK + k2 + ((lane >> 1) & 1)) << 1) + (lane & 1)] += v;
                 }
             } else {
-#pragma unroll
-                for (int k = 0; k < NK; ++k) {
-                    const float vr = half_sum(dAr4[k]), vi = half_sum(dAi4[k]);
-                    if ((lane & 31) == 0) { float2 &dst = sdA[lane >> 5][g * N + w * NK + k]; dst.x += vr; dst.y += vi; }
-                }
+                const float vr = half_sum(dAr4[0]), vi = half_sum(dAi4[0]);
+                if ((lane & 31) == 0) { sdA[lane >> 5][(g * N + w) << 1] += vr; sdA[lane >> 5][((g * N + w) << 1) + 1] += vi; }
             }
             if constexpr (DISC == DISC_ZOH_S6) {     // dDelta += u sum_n Re(H conj(B)) ;  du = Delta sum_n Re(H conj(B))
 #pragma unroll
@@ -344,7 +349,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
             __syncthreads();
 
             // ---- epilogue: the threads share the tile in flat order
-            {
+            if (io_thread) {
                 float o_du[TPW], o_dd[TPW], o_dz[TPW];
                 float dD_part = 0.0f, db_part = 0.0f;
 #pragma unroll
@@ -407,8 +412,8 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     for (int i = tid; i < Gact * N; i += NT) {
         const int g = i / N, n = i % N;
         float *dst = reinterpret_cast<float *>(p.dA + (int64_t)(d0 + g) * N + n);
-        unsafeAtomicAdd(dst, sdA[0][g * N + n].x + sdA[1][g * N + n].x);
-        unsafeAtomicAdd(dst + 1, sdA[0][g * N + n].y + sdA[1][g * N + n].y);
+        unsafeAtomicAdd(dst, sdA[0][2 * (g * N + n)] + sdA[1][2 * (g * N + n)]);
+        unsafeAtomicAdd(dst + 1, sdA[0][2 * (g * N + n) + 1] + sdA[1][2 * (g * N + n) + 1]);
         if (p.dx0) p.dx0[((int64_t)b * p.D + d0 + g) * N + n] = sH[g * N + n];
     }
     for (int g = tid; g < Gact; g += NT) {
@@ -444,9 +449,11 @@ static hipError_t launch_cbwd_disc(const CBwdParams &p, hipStream_t s) {
     switch (p.N) {
         case 1: return launch_cbwd_n<IO, 1, 1, DISC>(p, s);
         case 2: return launch_cbwd_n<IO, 2, 2, DISC>(p, s);
-        case 4: return launch_cbwd_n<IO, 4, 4, DISC>(p, s);
-        case 8: return launch_cbwd_n<IO, 8, 4, DISC>(p, s);
-        case 16: return launch_cbwd_n<IO, 16, 4, DISC>(p, s);
+        // two states per wavefront: with four, the complex sums of dBm/dCm alone take 64 registers and the
+        // compiler spills to scratch memory (measured 1.9x slower on the Mamba-block shape)
+        case 4: return launch_cbwd_n<IO, 4, 2, DISC>(p, s);
+        case 8: return launch_cbwd_n<IO, 8, 2, DISC>(p, s);
+        case 16: return launch_cbwd_n<IO, 16, 2, DISC>(p, s);
     }
     return hipErrorInvalidValue;
 }
