@@ -325,9 +325,9 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
 
 def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, x0=None,
                                      disc="zoh_s6", delta_softplus=True, return_last_state=False, out=None,
-                                     return_ckpt=False):
+                                     return_ckpt=False, ckpt_out=None):
     """y (and optionally x_last, ckpt) of the forward selective scan with complex A, Bm, Cm; see
-    lrnnx_ss_fwd_complex_args.
+    lrnnx_ss_fwd_complex_args.  `ckpt_out`: a preallocated checkpoint array to fill (implies return_ckpt).
 
     A [D,N] complex64.  Bm, Cm [B,L,N]: complex64 for float32 I/O; for bfloat16 I/O a bfloat16 tensor [B,L,N,2]
     of (re, im) pairs.  x0, x_last [B,D,N] complex64; ckpt [B,D,ceil(L/interval),N] complex64."""
@@ -355,9 +355,13 @@ def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias
     x_last = torch.empty((Bsz, D, N), dtype=torch.complex64, device=u.device) if return_last_state else None
     a.x_last = _ptr(x_last)
     ckpt = None
-    if return_ckpt:
-        ckpt = torch.empty((Bsz, D, -(-L // lrnnx_ckpt_interval()), N), dtype=torch.complex64, device=u.device)
+    if return_ckpt or ckpt_out is not None:
+        shape = (Bsz, D, -(-L // lrnnx_ckpt_interval()), N)
+        ckpt = ckpt_out if ckpt_out is not None else torch.empty(shape, dtype=torch.complex64, device=u.device)
+        if ckpt.dtype != torch.complex64 or not ckpt.is_contiguous() or tuple(ckpt.shape) != shape:
+            raise ValueError(f"ckpt_out: expected contiguous complex64 {shape}")
         a.ckpt = ckpt.data_ptr()
+        return_ckpt = True
     a.stream = _stream()
     _check(lib().lrnnx_selective_scan_fwd_complex(ctypes.byref(a)))
     res = (y,) + ((x_last,) if return_last_state else ()) + ((ckpt,) if return_ckpt else ())

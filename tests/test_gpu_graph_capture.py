@@ -88,6 +88,41 @@ def test_forward_backward_pair_replays(api):
         _eager_noise(torch)
 
 
+def test_complex_forward_backward_pair_replays(api):
+    import numpy as np
+    import torch
+    p = workloads.make_selective_complex(B=2, D=40, N=16, L=1100, io="bf16", gate=True, seed=8, with_x0=True)
+    bf = torch.bfloat16
+    maps = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda().to(bf)
+    t = dict(u=dev(p["u"], "bf16"), delta=dev(p["delta"], "bf16"), A=torch.from_numpy(p["A"]).cuda(), Bm=maps(p["Bm"]),
+             Cm=maps(p["Cm"]), Dskip=dev(p["Dskip"]), delta_bias=dev(p["delta_bias"]), z=dev(p["z"], "bf16"),
+             x0=torch.from_numpy(p["x0"]).cuda())
+    dy = dev(p["u"][:, :, ::-1].copy(), "bf16")
+    y_ref, ck_ref = api.lrnnx_selective_scan_fwd_complex(**t, return_ckpt=True)
+    g_ref = api.lrnnx_selective_scan_bwd_complex(**t, dy=dy, ckpt=ck_ref, want_dx0=True)
+    torch.cuda.synchronize()
+
+    y, ck = torch.empty_like(y_ref), torch.empty_like(ck_ref)
+    outs = {k: torch.empty_like(v) for k, v in g_ref.items() if v is not None}
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        api.lrnnx_selective_scan_fwd_complex(**t, out=y, ckpt_out=ck)
+        api.lrnnx_selective_scan_bwd_complex(**t, dy=dy, ckpt=ck, outs=outs, want_dx0=True)
+    for _ in range(3):
+        for v in (y, ck, *outs.values()):
+            v.fill_(7.0)                                   # stale contents must not survive a replay
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_ref) and torch.equal(torch.view_as_real(ck), torch.view_as_real(ck_ref))
+        for k in ("du", "ddelta", "dz"):
+            assert torch.equal(outs[k], g_ref[k]), k
+        assert torch.equal(torch.view_as_real(outs["dx0"]), torch.view_as_real(g_ref["dx0"]))
+        for k in ("dA", "dBm", "dCm", "dD", "dbias"):    # float atomics: equal up to summation order
+            scale = float(g_ref[k].abs().max())
+            assert float((outs[k] - g_ref[k]).abs().max()) <= 1e-5 * scale, k
+        _eager_noise(torch)
+
+
 def test_chained_scans_replay(api):
     """The single-launch LTI scan, its adjoint and the caller-coefficient scan re-arm their workspace on every replay."""
     import torch
