@@ -15,7 +15,7 @@
 // Mapping: that of the real backward kernel.  Time runs along the lanes (a lane owns T consecutive steps of a tile),
 // the N states are split over the W = N/NK wavefronts of a workgroup, which work on the same channel at the same
 // time and loop over G channels, so the sums of dBm/dCm over channels stay in registers.  Both complex maps of the
-// tile live in LDS in their I/O type (a bf16 pair is one 32-bit word), in slices private to the wavefront that owns
+// tile live in LDS as fp32 pairs (converted once per tile), in slices private to the wavefront that owns
 // the states.  What is summed over n (du, dDelta, ypre) goes through LDS once per (channel, tile).
 #include "kernels.hpp"
 #include "scan_common.hpp"
@@ -85,10 +85,12 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     static_assert(TILE % kCkptInterval == 0, "tiles must start on checkpoints");
     static_assert(W * 3 * TILE >= 2 * FL * T * N * 2, "flush buffer must fit in the partials area");
 
-    __shared__ __attribute__((aligned(16))) float sIn[3 * TILE];          // delta, u, dypre   [q][lane][4]
+    __shared__ __attribute__((aligned(16))) float sIn[2][5 * TILE];       // two channels in flight: delta, u, dypre, d softplus, dz factor; [q][lane][4]
     __shared__ __attribute__((aligned(16))) float sPart[W * 3 * TILE];    // per wave: ypre, du, ddelta partials
-    __shared__ __attribute__((aligned(16))) CW sB[N * TILE];              // maps of the tile: [n][q][lane][4], wave-private slices
-    __shared__ __attribute__((aligned(16))) CW sC[N * TILE];
+    // maps of the tile as fp32 pairs: [n][q][lane][4], wave-private slices (converted once per tile; every channel
+    // of the workgroup then reads them five times)
+    __shared__ __attribute__((aligned(16))) float2 sB[N * TILE];
+    __shared__ __attribute__((aligned(16))) float2 sC[N * TILE];
     __shared__ float2 sH[kMaxGc * N];     // conj(a_{l0}) H_{l0} carried to the earlier tile, per (channel, n)
     __shared__ float sdA[2][kMaxGc * N * 2];   // per half-wavefront partial sums of dA, (re, im) pairs
     __shared__ float sdD[2 * W * kMaxGc]; // dD and dbias partial sums per (half-wavefront, wavefront, channel)
@@ -116,8 +118,14 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     const CW *Bm = reinterpret_cast<const CW *>(p.Bm) + bc0;
     const CW *Cm = reinterpret_cast<const CW *>(p.Cm) + bc0;
 
-    const int f0 = tid * TPW;
-    const bool io_thread = NA == NT || tid < NA;                      // wave-uniform: NA is a multiple of 64
+    // The flat prologue (inputs of a channel -> LDS) and epilogue (partials -> outputs) need NA threads each.  A
+    // workgroup of 2 NA threads gives the prologue to its first half and the epilogue to its second half, which then
+    // run side by side (epilogue of channel g, prologue of channel g + 1); otherwise the same threads do both.
+    constexpr bool SPLIT = NT == 2 * NA;
+    const bool pro_thread = NA == NT || tid < NA;                     // wave-uniform: NA is a multiple of 64
+    const bool epi_thread = SPLIT ? tid >= NA : pro_thread;
+    const int f0 = tid * TPW;                                         // first flat step of a prologue thread
+    const int f0e = (SPLIT ? tid - NA : tid) * TPW;                   // ... of an epilogue thread
     auto fslot = [](int f) { return (((f % T) / 4) * 64 + f / T) * 4 + (f % 4); };
 
     for (int64_t tile = ntiles - 1; tile >= 0; --tile) {
@@ -145,8 +153,8 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
             for (int k = 0; k < NK; ++k)
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
-                    sB[(((w * NK + k) * TQ + t / 4) * 64 + lane) * 4 + (t % 4)] = tb[t][k];
-                    sC[(((w * NK + k) * TQ + t / 4) * 64 + lane) * 4 + (t % 4)] = tc[t][k];
+                    sB[(((w * NK + k) * TQ + t / 4) * 64 + lane) * 4 + (t % 4)] = cword<IO>::unpack(tb[t][k]);
+                    sC[(((w * NK + k) * TQ + t / 4) * 64 + lane) * 4 + (t % 4)] = cword<IO>::unpack(tc[t][k]);
                 }
         }
 
@@ -157,7 +165,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
         auto prefetch = [&](int g) {
             const int d = d0 + g;
             const int64_t row = (int64_t)b * p.D + d;
-            if (io_thread) {
+            if (pro_thread) {
                 load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.u) + b * p.u_sb + d * p.u_sd + l0, f0, rem, vec, r_u);
                 load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd + l0, f0, rem, vec, r_dl);
                 load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.dy) + b * p.dy_sb + d * p.dy_sd + l0, f0, rem, vec, r_dy);
@@ -173,37 +181,42 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
         };
         prefetch(0);
 
+        // ---- prologue of channel g: each prologue thread prepares TPW flat steps for everybody
+        auto prologue = [&](int g) {
+            float *in = sIn[g & 1];
+            const float bias = pbias;
+            float e_u[TPW], r_d[TPW], e_dy[TPW], e_z[TPW];
+            unpack_few<IO, TPW>(r_u, e_u);
+            unpack_few<IO, TPW>(r_dl, r_d);
+            unpack_few<IO, TPW>(r_dy, e_dy);
+            if (has_z) unpack_few<IO, TPW>(r_z, e_z);
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                float s = r_d[i] + bias, sp, sg, dyp, zf;
+                if (p.softplus) softplus_sigmoid(s, sp, sg); else { sp = s; sg = 1.0f; }
+                if (has_z) {                                     // y = ypre z sig(z): dz = dy ypre sig (1 + z (1 - sig))
+                    const float sz = sigmoid_fast(e_z[i]);
+                    const float dsz = e_dy[i] * sz;
+                    dyp = dsz * e_z[i];
+                    zf = dsz * __builtin_fmaf(e_z[i], 1.0f - sz, 1.0f);
+                } else { zf = 0.0f; dyp = e_dy[i]; }
+                in[0 * TILE + fslot(f0 + i)] = (f0 + i < rem) ? sp : 0.0f;
+                in[1 * TILE + fslot(f0 + i)] = e_u[i];
+                in[2 * TILE + fslot(f0 + i)] = dyp;
+                in[3 * TILE + fslot(f0 + i)] = sg;
+                in[4 * TILE + fslot(f0 + i)] = zf;
+            }
+        };
+        if (pro_thread) prologue(0);
+
         for (int g = 0; g < Gact; ++g) {
             const int d = d0 + g;
-            const float Dsk = pDsk, bias = pbias;
+            const float Dsk = pDsk;
+            const float *in = sIn[g & 1];
             float2 cA[NK], cck[NK];
 #pragma unroll
             for (int k = 0; k < NK; ++k) { cA[k] = pA[k]; cck[k] = pck[k]; }
 
-            // ---- prologue: each thread prepares TPW flat steps for everybody
-            float e_sg[TPW], e_zf[TPW];
-            if (io_thread) {
-                float e_u[TPW], r_d[TPW], e_dy[TPW], e_z[TPW];
-                unpack_few<IO, TPW>(r_u, e_u);
-                unpack_few<IO, TPW>(r_dl, r_d);
-                unpack_few<IO, TPW>(r_dy, e_dy);
-                if (has_z) unpack_few<IO, TPW>(r_z, e_z);
-#pragma unroll
-                for (int i = 0; i < TPW; ++i) {
-                    float s = r_d[i] + bias, sp, sg, dyp;
-                    if (p.softplus) softplus_sigmoid(s, sp, sg); else { sp = s; sg = 1.0f; }
-                    e_sg[i] = sg;
-                    if (has_z) {                                 // y = ypre z sig(z): dz = dy ypre sig (1 + z (1 - sig))
-                        const float sz = sigmoid_fast(e_z[i]);
-                        const float dsz = e_dy[i] * sz;
-                        dyp = dsz * e_z[i];
-                        e_zf[i] = dsz * __builtin_fmaf(e_z[i], 1.0f - sz, 1.0f);
-                    } else { e_zf[i] = 0.0f; dyp = e_dy[i]; }
-                    sIn[0 * TILE + fslot(f0 + i)] = (f0 + i < rem) ? sp : 0.0f;
-                    sIn[1 * TILE + fslot(f0 + i)] = e_u[i];
-                    sIn[2 * TILE + fslot(f0 + i)] = dyp;
-                }
-            }
             __syncthreads();
             if (g + 1 < Gact) prefetch(g + 1);
 
@@ -211,9 +224,9 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
             float dl[T], dyp[T], uv[T], ypre[T], pdu[T], pdd[T];
 #pragma unroll
             for (int q = 0; q < TQ; ++q) {
-                const float4 v0 = *reinterpret_cast<const float4 *>(&sIn[0 * TILE + (q * 64 + lane) * 4]);
-                const float4 v1 = *reinterpret_cast<const float4 *>(&sIn[1 * TILE + (q * 64 + lane) * 4]);
-                const float4 v2 = *reinterpret_cast<const float4 *>(&sIn[2 * TILE + (q * 64 + lane) * 4]);
+                const float4 v0 = *reinterpret_cast<const float4 *>(&in[0 * TILE + (q * 64 + lane) * 4]);
+                const float4 v1 = *reinterpret_cast<const float4 *>(&in[1 * TILE + (q * 64 + lane) * 4]);
+                const float4 v2 = *reinterpret_cast<const float4 *>(&in[2 * TILE + (q * 64 + lane) * 4]);
                 dl[4 * q] = v0.x; dl[4 * q + 1] = v0.y; dl[4 * q + 2] = v0.z; dl[4 * q + 3] = v0.w;
                 uv[4 * q] = v1.x; uv[4 * q + 1] = v1.y; uv[4 * q + 2] = v1.z; uv[4 * q + 3] = v1.w;
                 dyp[4 * q] = v2.x; dyp[4 * q + 1] = v2.y; dyp[4 * q + 2] = v2.z; dyp[4 * q + 3] = v2.w;
@@ -231,9 +244,9 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
                 const CCoef cc = make_ccoef(cA[k].x, cA[k].y);
                 const float2 xck = cck[k];
                 const float2 hc = sH[g * N + n];
-                const CW *sBn = &sB[(n * TQ * 64 + lane) * 4], *sCn = &sC[(n * TQ * 64 + lane) * 4];
-                auto mapB = [&](int t) { return cword<IO>::unpack(sBn[(t / 4) * 256 + (t % 4)]); };
-                auto mapC = [&](int t) { return cword<IO>::unpack(sCn[(t / 4) * 256 + (t % 4)]); };
+                const float2 *sBn = &sB[(n * TQ * 64 + lane) * 4], *sCn = &sC[(n * TQ * 64 + lane) * 4];
+                auto mapB = [&](int t) { return sBn[(t / 4) * 256 + (t % 4)]; };
+                auto mapC = [&](int t) { return sCn[(t / 4) * 256 + (t % 4)]; };
 
                 // forward recompute of the states of this tile
                 float2 a[T + 1], gg[T], x[T];
@@ -287,22 +300,24 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
                 for (int t = T - 1; t >= 0; --t) {
                     const float2 Cv = mapC(t), Bv = mapB(t);
                     R = cxcfma(a[t + 1], R, make_float2(Cv.x * dyp[t], -Cv.y * dyp[t]));   // H_t
-                    const float2 xprev = (t > 0) ? x[t - 1] : xin;
+                    [[maybe_unused]] const float2 xprev = (t > 0) ? x[t - 1] : xin;
                     dCacc[k][t].x = __builtin_fmaf(dyp[t], x[t].x, dCacc[k][t].x);        // dypre conj(x)
                     dCacc[k][t].y = __builtin_fmaf(-dyp[t], x[t].y, dCacc[k][t].y);
                     ypre[t] = __builtin_fmaf(Cv.x, x[t].x, __builtin_fmaf(-Cv.y, x[t].y, ypre[t]));   // Re(C x)
                     const float2 hb = cxmulc(R, Bv);                        // H conj(B)
-                    const float2 ga = cxmulc(R, xprev);                     // grad a
                     if constexpr (DISC == DISC_ZOH_S6) {
                         pdu[t] += hb.x;                                      // sum_n Re(H conj(B)); scaled by Delta resp. u after the loop
                         const float du_ = dl[t] * uv[t];
                         dBacc[k][t].x = __builtin_fmaf(R.x, du_, dBacc[k][t].x);
                         dBacc[k][t].y = __builtin_fmaf(R.y, du_, dBacc[k][t].y);
-                        const float2 q = cxmulc(ga, a[t]);                   // grad a conj(a)
+                        // grad a conj(a) = H conj(a x_{l-1}), and a x_{l-1} = x_l - Delta u B
+                        const float2 ax = make_float2(__builtin_fmaf(-du_, Bv.x, x[t].x), __builtin_fmaf(-du_, Bv.y, x[t].y));
+                        const float2 q = cxmulc(R, ax);
                         pdd[t] = __builtin_fmaf(q.x, cc.Ar, __builtin_fmaf(q.y, cc.Ai, pdd[t]));   // Re(q conj(A))
                         dA_part.x = __builtin_fmaf(q.x, dl[t], dA_part.x);
                         dA_part.y = __builtin_fmaf(q.y, dl[t], dA_part.y);
                     } else {
+                        const float2 ga = cxmulc(R, xprev);                 // grad a
                         float2 a_t, a_A, g_t, g_A;
                         cdisc_partials<DISC>(dl[t], cc, a[t], gg[t], a_t, a_A, g_t, g_A);
                         const float2 gq = make_float2(hb.x * uv[t], hb.y * uv[t]);      // grad g
@@ -348,35 +363,39 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
             }
             __syncthreads();
 
-            // ---- epilogue: the threads share the tile in flat order
-            if (io_thread) {
+            // ---- epilogue: the epilogue threads share the tile in flat order
+            if (epi_thread) {
                 float o_du[TPW], o_dd[TPW], o_dz[TPW];
                 float dD_part = 0.0f, db_part = 0.0f;
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) {
-                    const float e_u = sIn[1 * TILE + fslot(f0 + i)], e_dyp = sIn[2 * TILE + fslot(f0 + i)];
+                    const int fs = fslot(f0e + i);
+                    const float e_u = in[1 * TILE + fs], e_dyp = in[2 * TILE + fs];
                     float yp = Dsk * e_u, s_du = 0.0f, s_dd = 0.0f;
 #pragma unroll
                     for (int ww = 0; ww < W; ++ww) {
-                        yp += sPart[(ww * 3 + 0) * TILE + fslot(f0 + i)];
-                        s_du += sPart[(ww * 3 + 1) * TILE + fslot(f0 + i)];
-                        s_dd += sPart[(ww * 3 + 2) * TILE + fslot(f0 + i)];
+                        yp += sPart[(ww * 3 + 0) * TILE + fs];
+                        s_du += sPart[(ww * 3 + 1) * TILE + fs];
+                        s_dd += sPart[(ww * 3 + 2) * TILE + fs];
                     }
                     o_du[i] = __builtin_fmaf(e_dyp, Dsk, s_du);
-                    o_dd[i] = s_dd * e_sg[i];
-                    o_dz[i] = yp * e_zf[i];
+                    o_dd[i] = s_dd * in[3 * TILE + fs];
+                    o_dz[i] = yp * in[4 * TILE + fs];
                     dD_part = __builtin_fmaf(e_dyp, e_u, dD_part);
-                    db_part += (f0 + i < rem) ? o_dd[i] : 0.0f;
+                    db_part += (f0e + i < rem) ? o_dd[i] : 0.0f;
                 }
-                store_few<IO, TPW>(reinterpret_cast<IO *>(p.du) + b * p.du_sb + d * p.du_sd + l0, f0, rem, vec, o_du);
-                store_few<IO, TPW>(reinterpret_cast<IO *>(p.ddelta) + b * p.dd_sb + d * p.dd_sd + l0, f0, rem, vec, o_dd);
-                if (p.dz) store_few<IO, TPW>(reinterpret_cast<IO *>(p.dz) + b * p.dz_sb + d * p.dz_sd + l0, f0, rem, vec, o_dz);
+                store_few<IO, TPW>(reinterpret_cast<IO *>(p.du) + b * p.du_sb + d * p.du_sd + l0, f0e, rem, vec, o_du);
+                store_few<IO, TPW>(reinterpret_cast<IO *>(p.ddelta) + b * p.dd_sb + d * p.dd_sd + l0, f0e, rem, vec, o_dd);
+                if (p.dz) store_few<IO, TPW>(reinterpret_cast<IO *>(p.dz) + b * p.dz_sb + d * p.dz_sd + l0, f0e, rem, vec, o_dz);
                 const float vD = half_sum(dD_part), vb = half_sum(db_part);
                 if ((lane & 31) == 0) {
                     sdD[((lane >> 5) * W + w) * kMaxGc + g] += vD;
                     sdb[((lane >> 5) * W + w) * kMaxGc + g] += vb;
                 }
             }
+            // the next channel's prologue fills the other half of sIn (the prefetch that feeds it was issued before
+            // the main pass)
+            if (pro_thread && g + 1 < Gact) prologue(g + 1);
         }
 
         // ---- add this tile's dBm/dCm sums (over the G channels) to global memory, transposed through LDS so that
