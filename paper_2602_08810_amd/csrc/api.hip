@@ -93,7 +93,7 @@ extern "C" {
 
 int64_t lrnnx_ckpt_interval(void) { return kCkptInterval; }
 int64_t lrnnx_packed_ckpt_slots(int64_t L, int64_t B) { return (L < 0 || B < 0) ? 0 : L / kCkptInterval + B; }
-int lrnnx_version(void) { return 130; }   // major * 100 + minor; bumped whenever an entry point or a struct field is added
+int lrnnx_version(void) { return 131; }   // major * 100 + minor; bumped whenever an entry point or a struct field is added
 
 const char *lrnnx_status_string(int status) {
     switch (status) {
