@@ -105,6 +105,31 @@ def test_long_sequence(api, oracle):
     _run(api, oracle, 1, 8, 16, 9000, "bf16", "zoh_s6", gate=True, x0=False, seed=6)
 
 
+def test_mamba_block_shape_full(api, oracle):
+    """The shape bench.py times for the complex-A scan (B=8, D=1536, N=16, L=2048, bf16 I/O, gate), in the same launch
+    configuration (checkpoints from the forward call): every output of both passes against the oracle."""
+    import torch
+    B, D, N, L, io = 8, 1536, 16, 2048, "bf16"
+    p = workloads.make_selective_complex(B=B, D=D, N=N, L=L, io=io, gate=True, seed=2)
+    dy = workloads._io_round(np.random.Generator(np.random.PCG64(99)).standard_normal((B, D, L), dtype=np.float32), io)
+    t = dict(u=dev(p["u"], io), delta=dev(p["delta"], io), A=torch.from_numpy(p["A"]).cuda(), Bm=_maps_dev(p["Bm"], io),
+             Cm=_maps_dev(p["Cm"], io), Dskip=dev(p["Dskip"]), delta_bias=dev(p["delta_bias"]), z=dev(p["z"], io))
+    y, ckpt = api.lrnnx_selective_scan_fwd_complex(**t, return_ckpt=True)
+    g = api.lrnnx_selective_scan_bwd_complex(**t, dy=dev(dy, io), ckpt=ckpt)
+    torch.cuda.synchronize()
+    kw = dict(Dskip=p["Dskip"], delta_bias=p["delta_bias"], z=p["z"])
+    Bc, Cc = _cplx(p["Bm"]), _cplx(p["Cm"])
+    yr, _ = oracle.selective_scan_fwd_complex(p["u"], p["delta"], p["A"], Bc, Cc, **kw)
+    assert rel_err(host(y), yr) <= TOL[io], "y"
+    del yr
+    r = oracle.selective_scan_bwd_complex(p["u"], p["delta"], p["A"], Bc, Cc, dy, **kw)
+    errs = {k: (rel_err(host(g[k]), r[k]), TOL[io]) for k in ("du", "ddelta", "dz")}
+    errs.update({k: (rel_err(host(g[k]), r[k]), GRAD_TOL_F32) for k in ("dD", "dbias")})
+    errs.update({k: (_crel(g[k].cpu().numpy(), r[k]), GRAD_TOL_F32) for k in ("dA", "dBm", "dCm")})
+    bad = {k: v for k, v in errs.items() if not v[0] <= v[1]}
+    assert not bad, f"rel errors over tolerance: {bad}  (all: {errs})"
+
+
 def test_real_data_reproduces_the_real_backward(api):
     """With zero imaginary parts the complex entry point returns the real kernel's gradients (real parts) and no
     imaginary gradient for Cm; the other complex gradients' real parts agree too."""
