@@ -266,16 +266,35 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                         const float q = R * xprev * a[t];
                         pdd[t] = __builtin_fmaf(q, ac.A, pdd[t]);
                         dA_part = __builtin_fmaf(q, dl[t], dA_part);
-                    } else {
+                    } else if constexpr (DISC == DISC_DIRAC) {
+                        // g = 1: only a = e^{Delta A} depends on Delta and A
+                        pdu[t] = __builtin_fmaf(R, Bk[t], pdu[t]);
+                        dBacc[k][t] = __builtin_fmaf(R, dlu[t], dBacc[k][t]);
+                        const float q = R * xprev * a[t];
+                        pdd[t] = __builtin_fmaf(q, ac.A, pdd[t]);
+                        dA_part = __builtin_fmaf(q, dl[t], dA_part);
+                    } else if constexpr (DISC == DISC_ZOH) {
+                        // da/dDelta = A a, da/dA = Delta a, dg/dDelta = a: the common factor a is taken out
                         float a_t, a_A, g_t, g_A;
                         disc_partials<DISC>(dl[t], ac, a[t], gg[t], a_t, a_A, g_t, g_A);
+                        const float hb = R * Bk[t];
+                        const float dg = hb * dlu[t];
+                        const float dax = R * a[t] * xprev;                  // H x_{l-1} a
+                        pdu[t] = __builtin_fmaf(hb, gg[t], pdu[t]);
+                        dBacc[k][t] = __builtin_fmaf(R * gg[t], dlu[t], dBacc[k][t]);
+                        pdd[t] = __builtin_fmaf(dax, ac.A, __builtin_fmaf(dg, a[t], pdd[t]));
+                        dA_part = __builtin_fmaf(dax, dl[t], __builtin_fmaf(dg, g_A, dA_part));
+                    } else {
+                        // bilinear: with q = 1 / (1 - Delta A / 2) all four partials are multiples of q^2
+                        const float q = rcp_fast(__builtin_fmaf(-dl[t], ac.hA, 1.0f));
+                        const float q2 = q * q;
                         const float da = R * xprev;
                         const float hb = R * Bk[t];
                         const float dg = hb * dlu[t];
                         pdu[t] = __builtin_fmaf(hb, gg[t], pdu[t]);
                         dBacc[k][t] = __builtin_fmaf(R * gg[t], dlu[t], dBacc[k][t]);
-                        pdd[t] = __builtin_fmaf(da, a_t, __builtin_fmaf(dg, g_t, pdd[t]));
-                        dA_part = __builtin_fmaf(da, a_A, __builtin_fmaf(dg, g_A, dA_part));
+                        pdd[t] = __builtin_fmaf(__builtin_fmaf(da, ac.A, dg), q2, pdd[t]);                       // A q^2 da + q^2 dg
+                        dA_part = __builtin_fmaf(__builtin_fmaf(0.5f * dl[t], dg, da) * dl[t], q2, dA_part);     // Delta q^2 da + Delta^2 q^2 dg / 2
                     }
                 }
                 if constexpr (NK == 4 || NK == 2) {
