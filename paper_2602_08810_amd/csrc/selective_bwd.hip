@@ -261,7 +261,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                     dCacc[k][t] = __builtin_fmaf(dyp[t], x[t], dCacc[k][t]);
                     ypre[t] = __builtin_fmaf(Cv[k][t], x[t], ypre[t]);
                     if constexpr (DISC == DISC_ZOH_S6) {
-                        pdu[t] = __builtin_fmaf(R, Bk[t], pdu[t]);       // sum_n H B; scaled by Delta / u after the loop
+                        pdu[t] = __builtin_fmaf(R, Bk[t], pdu[t]);       // sum_n H B; scaled by Delta resp. u in the epilogue
                         dBacc[k][t] = __builtin_fmaf(R, dlu[t], dBacc[k][t]);
                         const float q = R * xprev * a[t];
                         pdd[t] = __builtin_fmaf(q, ac.A, pdd[t]);
@@ -330,18 +330,6 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 v += i2f(__builtin_amdgcn_ds_swizzle(f2i(v), 0x401F));      // lane ^ 16
                 if ((lane & 0x1E) == 0) sdA[lane >> 5][g * N + w * NK + (lane & 1)] += v;
             }
-            if constexpr (DISC == DISC_ZOH_S6) {     // dDelta += u sum_n H B ;  du = Delta sum_n H B
-#pragma unroll
-                for (int q = 0; q < TQ; ++q) {
-                    const float4 v1 = *reinterpret_cast<const float4 *>(&sIn[1 * TILE + (q * 64 + lane) * 4]);
-                    const float uu[4] = {v1.x, v1.y, v1.z, v1.w};
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        pdd[4 * q + r] = __builtin_fmaf(uu[r], pdu[4 * q + r], pdd[4 * q + r]);
-                        pdu[4 * q + r] *= dl[4 * q + r];
-                    }
-                }
-            }
 #pragma unroll
             for (int q = 0; q < TQ; ++q) {
                 float *base = &sPart[(w * 3) * TILE + (q * 64 + lane) * 4];
@@ -364,6 +352,11 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                         yp += sPart[(ww * 3 + 0) * TILE + fslot(f0 + i)];
                         s_du += sPart[(ww * 3 + 1) * TILE + fslot(f0 + i)];
                         s_dd += sPart[(ww * 3 + 2) * TILE + fslot(f0 + i)];
+                    }
+                    if constexpr (DISC == DISC_ZOH_S6) {
+                        // the wavefronts' sums are sum_n H B: dDelta += u sum_n H B, du = Delta sum_n H B
+                        s_dd = __builtin_fmaf(e_u, s_du, s_dd);
+                        s_du *= sIn[0 * TILE + fslot(f0 + i)];
                     }
                     o_du[i] = __builtin_fmaf(e_dyp, Dsk, s_du);
                     o_dd[i] = s_dd * e_sg[i];

@@ -306,7 +306,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
                     ypre[t] = __builtin_fmaf(Cv.x, x[t].x, __builtin_fmaf(-Cv.y, x[t].y, ypre[t]));   // Re(C x)
                     const float2 hb = cxmulc(R, Bv);                        // H conj(B)
                     if constexpr (DISC == DISC_ZOH_S6) {
-                        pdu[t] += hb.x;                                      // sum_n Re(H conj(B)); scaled by Delta resp. u after the loop
+                        pdu[t] += hb.x;                                      // sum_n Re(H conj(B)); scaled by Delta resp. u in the epilogue
                         const float du_ = dl[t] * uv[t];
                         dBacc[k][t].x = __builtin_fmaf(R.x, du_, dBacc[k][t].x);
                         dBacc[k][t].y = __builtin_fmaf(R.y, du_, dBacc[k][t].y);
@@ -347,13 +347,6 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
                 const float vr = half_sum(dAr4[0]), vi = half_sum(dAi4[0]);
                 if ((lane & 31) == 0) { sdA[lane >> 5][(g * N + w) << 1] += vr; sdA[lane >> 5][((g * N + w) << 1) + 1] += vi; }
             }
-            if constexpr (DISC == DISC_ZOH_S6) {     // dDelta += u sum_n Re(H conj(B)) ;  du = Delta sum_n Re(H conj(B))
-#pragma unroll
-                for (int t = 0; t < T; ++t) {
-                    pdd[t] = __builtin_fmaf(uv[t], pdu[t], pdd[t]);
-                    pdu[t] *= dl[t];
-                }
-            }
 #pragma unroll
             for (int q = 0; q < TQ; ++q) {
                 float *base = &sPart[(w * 3) * TILE + (q * 64 + lane) * 4];
@@ -377,6 +370,11 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
                         yp += sPart[(ww * 3 + 0) * TILE + fs];
                         s_du += sPart[(ww * 3 + 1) * TILE + fs];
                         s_dd += sPart[(ww * 3 + 2) * TILE + fs];
+                    }
+                    if constexpr (DISC == DISC_ZOH_S6) {
+                        // the wavefronts' sums are sum_n Re(H conj(B)): dDelta += u times it, du = Delta times it
+                        s_dd = __builtin_fmaf(e_u, s_du, s_dd);
+                        s_du *= in[0 * TILE + fs];
                     }
                     o_du[i] = __builtin_fmaf(e_dyp, Dsk, s_du);
                     o_dd[i] = s_dd * in[3 * TILE + fs];
