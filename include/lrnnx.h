@@ -205,7 +205,7 @@ typedef struct lrnnx_ss_bwd_complex_args {
 int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *args);
 
 /* ------------------------------------------------------------------ selective scan, backward
- * Reverse-mode derivative of the forward above for an upstream gradient dy[B,D,L]:
+ * Reverse-mode derivative of lrnnx_selective_scan_fwd (real A) for an upstream gradient dy[B,D,L]:
  * the gradients of sum(dy * y) with respect to u, the raw delta, A, Bm, Cm, Dskip,
  * delta_bias, z and x0.  The state is recomputed tile by tile from checkpoints and
  * never stored per step (Sec. 3).  `ckpt` is the array a forward call wrote for the
