@@ -7,7 +7,7 @@
  *
  * for a diagonal state matrix, in three forms:
  *   - time-varying, input-dependent ("selective", the S6 row of Table 1; Sec. 2.2.2),
- *     forward and backward (and forward with a complex diagonal A and complex maps, y = Re(C x) + D u),
+ *     forward and backward (also with a complex diagonal A and complex maps, y = Re(C x) + D u),
  *     with the discretisation fused into the scan (Sec. 3: ZOH,
  *     bilinear, dirac; the asynchronous / event-driven scheme is served by
  *     delta_softplus = 0 with the caller's own per-step Delta) and with the output
