@@ -87,6 +87,38 @@ FillList onepass_fill(const LtiParams &p) {
     return z;
 }
 
+// The real and the complex backward entry points take the same per-row tensors (same field names in both argument
+// structs and both parameter blocks): checks and marshalling are written once.
+template <typename Args>
+bool bwd_rows_valid(const Args *a) {
+    if (!a->u || !a->delta || !a->A || !a->Bm || !a->Cm || !a->dy) return false;
+    if (!a->du || !a->ddelta || !a->dA || !a->dBm || !a->dCm) return false;
+    if ((a->dz && !a->z) || (a->dD && !a->Dskip) || (a->dbias && !a->delta_bias)) return false;
+    return !(a->u_stride_b < 0 || a->u_stride_d < 0 || a->delta_stride_b < 0 || a->delta_stride_d < 0 ||
+             a->dy_stride_b < 0 || a->dy_stride_d < 0 || (a->z && (a->z_stride_b < 0 || a->z_stride_d < 0)) ||
+             a->du_stride_b < 0 || a->du_stride_d < a->L || a->ddelta_stride_b < 0 || a->ddelta_stride_d < a->L ||
+             (a->dz && (a->dz_stride_b < 0 || a->dz_stride_d < a->L)));
+}
+template <typename Params, typename Args>
+void set_bwd_rows(Params &p, const Args *a) {
+    const size_t es = elem_size(a->io_dtype);
+    p.B = a->B; p.D = a->D; p.N = a->N; p.L = a->L;
+    p.softplus = a->delta_softplus ? 1 : 0;
+    p.u = a->u; p.delta = a->delta; p.z = a->z; p.dy = a->dy;
+    p.du = a->du; p.ddelta = a->ddelta; p.dz = a->dz;
+    p.u_sb = a->u_stride_b; p.u_sd = a->u_stride_d; p.dl_sb = a->delta_stride_b; p.dl_sd = a->delta_stride_d;
+    p.z_sb = a->z_stride_b; p.z_sd = a->z_stride_d; p.dy_sb = a->dy_stride_b; p.dy_sd = a->dy_stride_d;
+    p.du_sb = a->du_stride_b; p.du_sd = a->du_stride_d; p.dd_sb = a->ddelta_stride_b; p.dd_sd = a->ddelta_stride_d;
+    p.dz_sb = a->dz_stride_b; p.dz_sd = a->dz_stride_d;
+    p.Dskip = a->Dskip; p.bias = a->delta_bias;
+    p.Bm = a->Bm; p.Cm = a->Cm;
+    p.dD = a->dD; p.dbias = a->dbias;
+    p.vec = row_vec_ok(a->u, p.u_sb, p.u_sd, es) && row_vec_ok(a->delta, p.dl_sb, p.dl_sd, es) &&
+            row_vec_ok(a->dy, p.dy_sb, p.dy_sd, es) && (!a->z || row_vec_ok(a->z, p.z_sb, p.z_sd, es)) &&
+            row_vec_ok(a->du, p.du_sb, p.du_sd, es) && row_vec_ok(a->ddelta, p.dd_sb, p.dd_sd, es) &&
+            (!a->dz || row_vec_ok(a->dz, p.dz_sb, p.dz_sd, es));
+}
+
 }  // namespace
 
 extern "C" {
@@ -252,14 +284,7 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
-    if (!a->u || !a->delta || !a->A || !a->Bm || !a->Cm || !a->dy) return LRNNX_ERR_INVALID_ARG;
-    if (!a->du || !a->ddelta || !a->dA || !a->dBm || !a->dCm) return LRNNX_ERR_INVALID_ARG;
-    if ((a->dz && !a->z) || (a->dD && !a->Dskip) || (a->dbias && !a->delta_bias)) return LRNNX_ERR_INVALID_ARG;
-    if (a->u_stride_b < 0 || a->u_stride_d < 0 || a->delta_stride_b < 0 || a->delta_stride_d < 0 ||
-        a->dy_stride_b < 0 || a->dy_stride_d < 0 || (a->z && (a->z_stride_b < 0 || a->z_stride_d < 0)) ||
-        a->du_stride_b < 0 || a->du_stride_d < a->L || a->ddelta_stride_b < 0 || a->ddelta_stride_d < a->L ||
-        (a->dz && (a->dz_stride_b < 0 || a->dz_stride_d < a->L)))
-        return LRNNX_ERR_INVALID_ARG;
+    if (!bwd_rows_valid(a)) return LRNNX_ERR_INVALID_ARG;
     if (!supported_n(a->N)) return LRNNX_ERR_UNSUPPORTED;
     if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
     if (!aligned16(a->Bm) || !aligned16(a->Cm) || !aligned16(a->dBm) || !aligned16(a->dCm)) return LRNNX_ERR_INVALID_ARG;
@@ -287,24 +312,10 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
     }
 
     CBwdParams p{};
-    p.B = a->B; p.D = a->D; p.N = a->N; p.L = a->L;
-    p.softplus = a->delta_softplus ? 1 : 0;
-    p.u = a->u; p.delta = a->delta; p.z = a->z; p.dy = a->dy;
-    p.du = a->du; p.ddelta = a->ddelta; p.dz = a->dz;
-    p.u_sb = a->u_stride_b; p.u_sd = a->u_stride_d; p.dl_sb = a->delta_stride_b; p.dl_sd = a->delta_stride_d;
-    p.z_sb = a->z_stride_b; p.z_sd = a->z_stride_d; p.dy_sb = a->dy_stride_b; p.dy_sd = a->dy_stride_d;
-    p.du_sb = a->du_stride_b; p.du_sd = a->du_stride_d; p.dd_sb = a->ddelta_stride_b; p.dd_sd = a->ddelta_stride_d;
-    p.dz_sb = a->dz_stride_b; p.dz_sd = a->dz_stride_d;
+    set_bwd_rows(p, a);
     p.A = reinterpret_cast<const float2 *>(a->A); p.ckpt = ckpt;
-    p.Dskip = a->Dskip; p.bias = a->delta_bias;
-    p.Bm = a->Bm; p.Cm = a->Cm;
     p.dA = reinterpret_cast<float2 *>(a->dA); p.dBm = reinterpret_cast<float2 *>(a->dBm);
     p.dCm = reinterpret_cast<float2 *>(a->dCm); p.dx0 = reinterpret_cast<float2 *>(a->dx0);
-    p.dD = a->dD; p.dbias = a->dbias;
-    p.vec = row_vec_ok(a->u, p.u_sb, p.u_sd, es) && row_vec_ok(a->delta, p.dl_sb, p.dl_sd, es) &&
-            row_vec_ok(a->dy, p.dy_sb, p.dy_sd, es) && (!a->z || row_vec_ok(a->z, p.z_sb, p.z_sd, es)) &&
-            row_vec_ok(a->du, p.du_sb, p.du_sd, es) && row_vec_ok(a->ddelta, p.dd_sb, p.dd_sd, es) &&
-            (!a->dz || row_vec_ok(a->dz, p.dz_sb, p.dz_sd, es));
     p.G = cbwd_channels_per_group(a->B, a->D, a->N);
 
     const int64_t nbc = (int64_t)a->B * a->L * a->N * 2;                 // floats
@@ -326,14 +337,7 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
-    if (!a->u || !a->delta || !a->A || !a->Bm || !a->Cm || !a->dy) return LRNNX_ERR_INVALID_ARG;
-    if (!a->du || !a->ddelta || !a->dA || !a->dBm || !a->dCm) return LRNNX_ERR_INVALID_ARG;
-    if ((a->dz && !a->z) || (a->dD && !a->Dskip) || (a->dbias && !a->delta_bias)) return LRNNX_ERR_INVALID_ARG;
-    if (a->u_stride_b < 0 || a->u_stride_d < 0 || a->delta_stride_b < 0 || a->delta_stride_d < 0 ||
-        a->dy_stride_b < 0 || a->dy_stride_d < 0 || (a->z && (a->z_stride_b < 0 || a->z_stride_d < 0)) ||
-        a->du_stride_b < 0 || a->du_stride_d < a->L || a->ddelta_stride_b < 0 || a->ddelta_stride_d < a->L ||
-        (a->dz && (a->dz_stride_b < 0 || a->dz_stride_d < a->L)))
-        return LRNNX_ERR_INVALID_ARG;
+    if (!bwd_rows_valid(a)) return LRNNX_ERR_INVALID_ARG;
     if (!supported_n(a->N)) return LRNNX_ERR_UNSUPPORTED;
     if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
     if (a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
@@ -366,23 +370,11 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     }
 
     BwdParams p{};
-    p.B = a->B; p.D = a->D; p.N = a->N; p.L = a->L;
+    set_bwd_rows(p, a);
     p.bcg = bcg; p.dpg = a->D / bcg;
     p.cu = cu; p.nslots = lrnnx_packed_ckpt_slots(a->L, a->B);
-    p.softplus = a->delta_softplus ? 1 : 0;
-    p.u = a->u; p.delta = a->delta; p.z = a->z; p.dy = a->dy;
-    p.du = a->du; p.ddelta = a->ddelta; p.dz = a->dz;
-    p.u_sb = a->u_stride_b; p.u_sd = a->u_stride_d; p.dl_sb = a->delta_stride_b; p.dl_sd = a->delta_stride_d;
-    p.z_sb = a->z_stride_b; p.z_sd = a->z_stride_d; p.dy_sb = a->dy_stride_b; p.dy_sd = a->dy_stride_d;
-    p.du_sb = a->du_stride_b; p.du_sd = a->du_stride_d; p.dd_sb = a->ddelta_stride_b; p.dd_sd = a->ddelta_stride_d;
-    p.dz_sb = a->dz_stride_b; p.dz_sd = a->dz_stride_d;
-    p.A = a->A; p.Dskip = a->Dskip; p.bias = a->delta_bias; p.x0 = a->x0; p.ckpt = ckpt;
-    p.Bm = a->Bm; p.Cm = a->Cm;
-    p.dA = a->dA; p.dBm = a->dBm; p.dCm = a->dCm; p.dD = a->dD; p.dbias = a->dbias; p.dx0 = a->dx0;
-    p.vec = row_vec_ok(a->u, p.u_sb, p.u_sd, es) && row_vec_ok(a->delta, p.dl_sb, p.dl_sd, es) &&
-            row_vec_ok(a->dy, p.dy_sb, p.dy_sd, es) && (!a->z || row_vec_ok(a->z, p.z_sb, p.z_sd, es)) &&
-            row_vec_ok(a->du, p.du_sb, p.du_sd, es) && row_vec_ok(a->ddelta, p.dd_sb, p.dd_sd, es) &&
-            (!a->dz || row_vec_ok(a->dz, p.dz_sb, p.dz_sd, es));
+    p.A = a->A; p.x0 = a->x0; p.ckpt = ckpt;
+    p.dA = a->dA; p.dBm = a->dBm; p.dCm = a->dCm; p.dx0 = a->dx0;
     p.G = bwd_channels_per_group(a->B * bcg, a->D / bcg, a->N, a->L, cu == nullptr);
 
     // reduced outputs are accumulated with atomics: clear them on the stream first
