@@ -316,19 +316,49 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
                         pdd[t] = __builtin_fmaf(q.x, cc.Ar, __builtin_fmaf(q.y, cc.Ai, pdd[t]));   // Re(q conj(A))
                         dA_part.x = __builtin_fmaf(q.x, dl[t], dA_part.x);
                         dA_part.y = __builtin_fmaf(q.y, dl[t], dA_part.y);
+                    } else if constexpr (DISC == DISC_DIRAC) {
+                        // g = 1: the S6 expressions with u in place of Delta u
+                        pdu[t] += hb.x;
+                        dBacc[k][t].x = __builtin_fmaf(R.x, uv[t], dBacc[k][t].x);
+                        dBacc[k][t].y = __builtin_fmaf(R.y, uv[t], dBacc[k][t].y);
+                        const float2 ax = make_float2(__builtin_fmaf(-uv[t], Bv.x, x[t].x), __builtin_fmaf(-uv[t], Bv.y, x[t].y));
+                        const float2 q = cxmulc(R, ax);                      // grad a conj(a)
+                        pdd[t] = __builtin_fmaf(q.x, cc.Ar, __builtin_fmaf(q.y, cc.Ai, pdd[t]));
+                        dA_part.x = __builtin_fmaf(q.x, dl[t], dA_part.x);
+                        dA_part.y = __builtin_fmaf(q.y, dl[t], dA_part.y);
                     } else {
                         const float2 ga = cxmulc(R, xprev);                 // grad a
-                        float2 a_t, a_A, g_t, g_A;
-                        cdisc_partials<DISC>(dl[t], cc, a[t], gg[t], a_t, a_A, g_t, g_A);
                         const float2 gq = make_float2(hb.x * uv[t], hb.y * uv[t]);      // grad g
                         pdu[t] += cxmulc(hb, gg[t]).x;                                     // Re(H conj(B) conj(g))
                         const float2 rg = cxmulc(R, gg[t]);
                         dBacc[k][t].x = __builtin_fmaf(rg.x, uv[t], dBacc[k][t].x);
                         dBacc[k][t].y = __builtin_fmaf(rg.y, uv[t], dBacc[k][t].y);
-                        pdd[t] += cxmulc(ga, a_t).x + cxmulc(gq, g_t).x;
-                        const float2 s1 = cxmulc(ga, a_A), s2 = cxmulc(gq, g_A);
-                        dA_part.x += s1.x + s2.x;
-                        dA_part.y += s1.y + s2.y;
+                        if constexpr (DISC == DISC_ZOH) {
+                            // da/dDelta = A a, da/dA = Delta a, dg/dDelta = a: with q = grad a conj(a),
+                            // dDelta += Re(q conj(A) + grad g conj(a)), dA += Delta q + grad g conj(dg/dA)
+                            float2 a_t, a_A, g_t, g_A;
+                            cdisc_partials<DISC>(dl[t], cc, a[t], gg[t], a_t, a_A, g_t, g_A);
+                            const float2 q = cxmulc(ga, a[t]);
+                            pdd[t] = __builtin_fmaf(q.x, cc.Ar, __builtin_fmaf(q.y, cc.Ai, pdd[t])) + cxmulc(gq, a[t]).x;
+                            const float2 s2 = cxmulc(gq, g_A);
+                            dA_part.x = __builtin_fmaf(q.x, dl[t], dA_part.x) + s2.x;
+                            dA_part.y = __builtin_fmaf(q.y, dl[t], dA_part.y) + s2.y;
+                        } else {
+                            // bilinear: with q = 1 / (1 - Delta A / 2) all four partials are multiples of q^2:
+                            // dDelta += Re((grad a conj(A) + grad g) conj(q^2)),
+                            // dA += Delta (grad a + grad g Delta / 2) conj(q^2)
+                            const float r = (dl[t] != 0.0f) ? rcp_fast(dl[t]) : 0.0f;
+                            const float2 q = (dl[t] != 0.0f) ? make_float2(gg[t].x * r, gg[t].y * r) : make_float2(1.0f, 0.0f);
+                            const float2 q2 = cxmul(q, q);
+                            const float2 t1 = make_float2(__builtin_fmaf(ga.x, cc.Ar, __builtin_fmaf(ga.y, cc.Ai, gq.x)),
+                                                          __builtin_fmaf(ga.y, cc.Ar, __builtin_fmaf(-ga.x, cc.Ai, gq.y)));
+                            pdd[t] += cxmulc(t1, q2).x;
+                            const float hd = 0.5f * dl[t];
+                            const float2 t2 = make_float2(__builtin_fmaf(gq.x, hd, ga.x) * dl[t], __builtin_fmaf(gq.y, hd, ga.y) * dl[t]);
+                            const float2 s = cxmulc(t2, q2);
+                            dA_part.x += s.x;
+                            dA_part.y += s.y;
+                        }
                     }
                 }
                 dAr4[k] = dA_part.x; dAi4[k] = dA_part.y;
