@@ -79,3 +79,25 @@ def test_real_data_reproduces_the_real_kernel(api):
     yc = api.lrnnx_selective_scan_fwd_complex(**t, A=dev(p["A"]).to(torch.complex64), Bm=dev(p["Bm"]).to(torch.complex64),
                                               Cm=dev(p["Cm"]).to(torch.complex64))
     assert float((y - yc).abs().max()) <= 2e-5 * float(y.abs().max())
+
+
+def test_two_calls_chained_through_the_state_equal_one_call(api, oracle):
+    """Chunked prefill: the second call starts from the first call's x_last (x0); y of both calls is what one call
+    over the whole sequence gives, on the GPU and against the oracle."""
+    import torch
+    B, D, N, L, cut, io = 2, 12, 16, 1400, 777, "f32"
+    p = workloads.make_selective_complex(B=B, D=D, N=N, L=L, io=io, gate=True, seed=11, with_x0=True)
+    full = dict(u=dev(p["u"]), delta=dev(p["delta"]), A=torch.from_numpy(p["A"]).cuda(), Bm=_maps_dev(p["Bm"], io),
+                Cm=_maps_dev(p["Cm"], io), Dskip=dev(p["Dskip"]), delta_bias=dev(p["delta_bias"]), z=dev(p["z"]))
+    x0 = torch.from_numpy(p["x0"]).cuda()
+    y, xl = api.lrnnx_selective_scan_fwd_complex(**full, x0=x0, return_last_state=True)
+    part = lambda lo, hi: dict(full, u=full["u"][:, :, lo:hi], delta=full["delta"][:, :, lo:hi], z=full["z"][:, :, lo:hi],
+                               Bm=full["Bm"][:, lo:hi].contiguous(), Cm=full["Cm"][:, lo:hi].contiguous())
+    y1, xl1 = api.lrnnx_selective_scan_fwd_complex(**part(0, cut), x0=x0, return_last_state=True)
+    y2, xl2 = api.lrnnx_selective_scan_fwd_complex(**part(cut, L), x0=xl1, return_last_state=True)
+    yy = torch.cat([y1, y2], dim=2)
+    assert float((yy - y).abs().max()) <= 2e-6 * float(y.abs().max())
+    assert float((xl2 - xl).abs().max()) <= 2e-6 * float(xl.abs().max())
+    yr, xr = oracle.selective_scan_fwd_complex(p["u"], p["delta"], p["A"], _cplx(p["Bm"]), _cplx(p["Cm"]), Dskip=p["Dskip"],
+                                               delta_bias=p["delta_bias"], z=p["z"], x0=p["x0"])
+    assert rel_err(host(yy), yr) <= TOL[io]

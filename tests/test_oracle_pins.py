@@ -873,3 +873,57 @@ def test_complex_backward_with_real_data_is_the_real_backward(oracle, disc):
     gc = oracle.selective_scan_bwd_complex(**q, dy=dy, disc=disc)
     for k in g:
         np.testing.assert_allclose(np.real(gc[k]), g[k], rtol=1e-11, atol=1e-13, err_msg=k)
+
+
+def test_complex_backward_adjoint_dot_test(oracle):
+    """y is linear in (u, Dskip-free) for fixed step sizes and maps, and real-linear in x0: for any direction
+    (du, dx0), <dy, J (du, dx0)> must equal <J^T dy, (du, dx0)> with the real inner product Re(conj(a) b)."""
+    p = _complex_problem(91, B=2, D=3, N=4, L=11)
+    p["Dskip"] = None
+    rng = np.random.default_rng(92)
+    dy = rng.standard_normal(p["u"].shape)
+    du = rng.standard_normal(p["u"].shape)
+    dx0 = rng.standard_normal(p["x0"].shape) + 1j * rng.standard_normal(p["x0"].shape)
+    for disc in DISCS:
+        g = oracle.selective_scan_bwd_complex(**p, dy=dy, disc=disc)
+        # without the gate y is linear in (u, x0): J applied to a direction is the forward pass of that direction
+        q = dict(p, z=None)
+        gq = oracle.selective_scan_bwd_complex(**q, dy=dy, disc=disc)
+        Jd, _ = oracle.selective_scan_fwd_complex(**dict(q, u=du, x0=dx0), disc=disc)
+        lhs = float(np.sum(dy * Jd))
+        rhs = float(np.sum(gq["du"] * du) + np.sum((np.conj(gq["dx0"]) * dx0).real))
+        assert lhs == pytest.approx(rhs, rel=1e-11)
+        # with the gate: dz and the gated du follow from the ungated ones
+        zz = p["z"]
+        sg = 1 / (1 + np.exp(-zz))
+        gz = oracle.selective_scan_bwd_complex(**q, dy=dy * zz * sg, disc=disc)
+        np.testing.assert_allclose(g["du"], gz["du"], rtol=1e-11, atol=1e-13)
+        ypre, _ = oracle.selective_scan_fwd_complex(**q, disc=disc)
+        np.testing.assert_allclose(g["dz"], dy * ypre * sg * (1 + zz * (1 - sg)), rtol=1e-11, atol=1e-13)
+
+
+def test_complex_forward_chains_through_x0_and_x_last(oracle):
+    """Two calls on the halves of a sequence, the second starting from the first one's x_last, equal one call; the
+    backward pass chains the other way through dx0 (the gradient of a loss on both halves w.r.t. the first half's
+    inputs needs the second half's dx0 as the gradient reaching x_last)."""
+    p = _complex_problem(93, B=2, D=2, N=3, L=14)
+    cut = 6
+    y, xl = oracle.selective_scan_fwd_complex(**p, disc="zoh")
+    first = {k: (v[:, :, :cut] if k in ("u", "delta", "z") else v[:, :cut] if k in ("Bm", "Cm") else v) for k, v in p.items()}
+    second = {k: (v[:, :, cut:] if k in ("u", "delta", "z") else v[:, cut:] if k in ("Bm", "Cm") else v) for k, v in p.items()}
+    y1, xl1 = oracle.selective_scan_fwd_complex(**first, disc="zoh")
+    y2, xl2 = oracle.selective_scan_fwd_complex(**dict(second, x0=xl1), disc="zoh")
+    np.testing.assert_allclose(np.concatenate([y1, y2], axis=2), y, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(xl2, xl, rtol=1e-12)
+    dy = np.random.default_rng(94).standard_normal(y.shape)
+    g = oracle.selective_scan_bwd_complex(**p, dy=dy, disc="zoh")
+    g2 = oracle.selective_scan_bwd_complex(**dict(second, x0=xl1), dy=dy[:, :, cut:], disc="zoh")
+    np.testing.assert_allclose(g2["du"], g["du"][:, :, cut:], rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(g2["dCm"], g["dCm"][:, cut:], rtol=1e-11, atol=1e-13)
+    # the first half sees the second half only through x_last: its gradient there is the second half's dx0.  With
+    # y = Re(C x) the state enters linearly, so the contribution can be checked on dx0 of the whole sequence:
+    # dx0(whole) = dx0(first half alone) + (prod of the first half's multipliers)^H dx0(second half)
+    g1 = oracle.selective_scan_bwd_complex(**first, dy=dy[:, :, :cut], disc="zoh")
+    dt = np.logaddexp(0.0, p["delta"] + p["delta_bias"][None, :, None])[:, :, :cut]          # [B,D,cut]
+    prod_a = np.exp(dt.sum(-1)[..., None] * p["A"][None])                                      # [B,D,N]
+    np.testing.assert_allclose(g["dx0"], g1["dx0"] + np.conj(prod_a) * g2["dx0"], rtol=1e-10, atol=1e-12)
