@@ -35,7 +35,8 @@
  *     are contiguous.  io_dtype selects the element type of u, delta, z, Bm, Cm, y, dy,
  *     du, ddelta, dz (float or bfloat16); the state, all accumulation, A, Dskip,
  *     delta_bias, x0, x_last, checkpoints and the reduced gradients are float.
- *   - Supported: N in {1,2,4,8,16}; any B, D >= 1; any L >= 1 (B*D*L must fit int64).
+ *   - Supported: N in {1,2,4,8,16,32} (the complex-A entry points: up to 16); any B, D >= 1; any L >= 1
+ *     (B*D*L must fit int64).
  */
 #ifndef LRNNX_H
 #define LRNNX_H

@@ -10,7 +10,8 @@ namespace {
 
 constexpr int kNumCU = 256;              // MI355X
 
-inline bool supported_n(int n) { return n == 1 || n == 2 || n == 4 || n == 8 || n == 16; }
+inline bool supported_n(int n) { return n == 1 || n == 2 || n == 4 || n == 8 || n == 16 || n == 32; }
+inline bool supported_n_complex(int n) { return n <= 16 && supported_n(n); }   // complex-A entry points
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t elem_size(int io) { return io == LRNNX_BF16 ? 2 : 4; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -150,7 +151,7 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
         return (size_t)B * D * cdiv(L, kCkptInterval) * N * sizeof(float);
     }
     if (which == LRNNX_WS_BWD_COMPLEX) {
-        if (!supported_n((int)N)) return 0;
+        if (!supported_n_complex((int)N)) return 0;
         return (size_t)B * D * cdiv(L, kCkptInterval) * N * sizeof(float2);
     }
     if (which == LRNNX_WS_LTI) {
@@ -253,7 +254,7 @@ int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *a) {
     if (a->u_stride_b < 0 || a->u_stride_d < 0 || a->delta_stride_b < 0 || a->delta_stride_d < 0 ||
         (a->y && (a->y_stride_b < 0 || a->y_stride_d < a->L)) || (a->z && (a->z_stride_b < 0 || a->z_stride_d < 0)))
         return LRNNX_ERR_INVALID_ARG;
-    if (!supported_n(a->N)) return LRNNX_ERR_UNSUPPORTED;
+    if (!supported_n_complex(a->N)) return LRNNX_ERR_UNSUPPORTED;
     if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
     if (!aligned16(a->Bm) || !aligned16(a->Cm)) return LRNNX_ERR_INVALID_ARG;
     for (const void *q : {a->A, a->x0, (const void *)a->x_last})
@@ -285,7 +286,7 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
     if (!bwd_rows_valid(a)) return LRNNX_ERR_INVALID_ARG;
-    if (!supported_n(a->N)) return LRNNX_ERR_UNSUPPORTED;
+    if (!supported_n_complex(a->N)) return LRNNX_ERR_UNSUPPORTED;
     if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
     if (!aligned16(a->Bm) || !aligned16(a->Cm) || !aligned16(a->dBm) || !aligned16(a->dCm)) return LRNNX_ERR_INVALID_ARG;
     for (const void *q : {a->A, a->x0, a->ckpt, (const void *)a->dA, (const void *)a->dx0, (const void *)a->workspace})

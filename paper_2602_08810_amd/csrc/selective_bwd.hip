@@ -37,10 +37,11 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     constexpr int W = N / NK;
     constexpr int NT = W * 64;
     constexpr int TILE = 64 * T;
-    constexpr int TPW = TILE / NT;                   // flat steps per thread in prologue / epilogue
+    constexpr int TPW = TILE / NT > 0 ? TILE / NT : 1;   // flat steps per thread in prologue / epilogue
+    constexpr int NA = TILE / TPW;                   // threads that take part in them: all, or (N = 32) the first 256
     constexpr int TQ = T / 4;
     constexpr int CK_PER_TILE = TILE / (int)kCkptInterval;
-    static_assert(T % 4 == 0 && T % W == 0 && TPW >= 1 && TPW <= 8, "tile shape");
+    static_assert(T % 4 == 0 && (T % W == 0 || W % T == 0) && TPW <= 8 && NA % 64 == 0 && NA <= NT, "tile shape");
     static_assert(TILE % kCkptInterval == 0, "tiles must start on checkpoints");
     static_assert(W * 3 * TILE >= 2 * 16 * T * N, "flush buffer must fit in the partials area");
 
@@ -89,6 +90,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
 
     // flat position of this thread in prologue / epilogue, and its slot in the [q][lane][4] layout
     const int f0 = tid * TPW;
+    const bool io_thread = NA == NT || tid < NA;                     // wave-uniform: NA is a multiple of 64
     auto fslot = [](int f) { return (((f % T) / 4) * 64 + f / T) * 4 + (f % 4); };
 
     for (int64_t tile = ntiles - 1; tile >= 0; --tile) {
@@ -130,10 +132,12 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
         auto prefetch = [&](int g) {
             const int d = d0 + g;
             const int64_t row = (int64_t)b * p.D + d;
-            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.u) + bs * p.u_sb + d * p.u_sd + toff + l0, f0, rem, vec, r_u);
-            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.delta) + bs * p.dl_sb + d * p.dl_sd + toff + l0, f0, rem, vec, r_dl);
-            load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.dy) + bs * p.dy_sb + d * p.dy_sd + toff + l0, f0, rem, vec, r_dy);
-            if (has_z) load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.z) + bs * p.z_sb + d * p.z_sd + toff + l0, f0, rem, vec, r_z);
+            if (io_thread) {
+                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.u) + bs * p.u_sb + d * p.u_sd + toff + l0, f0, rem, vec, r_u);
+                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.delta) + bs * p.dl_sb + d * p.dl_sd + toff + l0, f0, rem, vec, r_dl);
+                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.dy) + bs * p.dy_sb + d * p.dy_sd + toff + l0, f0, rem, vec, r_dy);
+                if (has_z) load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.z) + bs * p.z_sb + d * p.z_sd + toff + l0, f0, rem, vec, r_z);
+            }
 #pragma unroll
             for (int k = 0; k < NK; ++k) {
                 pA[k] = p.A[d * N + w * NK + k];
@@ -154,7 +158,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
             // ---- prologue: each thread prepares TPW flat steps for everybody
             // kept for the epilogue: d softplus / ds, and the factor that turns ypre into dz
             float e_sg[TPW], e_zf[TPW];
-            {
+            if (io_thread) {
                 float e_u[TPW], r_d[TPW], e_dy[TPW], e_z[TPW];
                 unpack_few<IO, TPW>(r_u, e_u);
                 unpack_few<IO, TPW>(r_dl, r_d);
@@ -340,7 +344,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
             __syncthreads();
 
             // ---- epilogue: the threads share the tile in flat order
-            {
+            if (io_thread) {
                 float o_du[TPW], o_dd[TPW], o_dz[TPW];
                 float dD_part = 0.0f, db_part = 0.0f;
 #pragma unroll
@@ -428,8 +432,11 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
 // channels per workgroup: D here is the number of channels that share one pair of Bm/Cm maps.  `balanced` says
 // that all batch entries have the same length; otherwise (packed variable-length batches) four times as many,
 // smaller, workgroups let the dispatcher even out sequences of different lengths.
-int bwd_channels_per_group(int B, int D, int, int64_t, bool balanced) {
-    int64_t G = ((int64_t)B * D) / (balanced ? 512 : 2048);   // aim at >= 512 workgroups (two per CU)
+int bwd_channels_per_group(int B, int D, int N, int64_t, bool balanced) {
+    // aim at eight wavefronts per CU (two per SIMD, what the register budget allows): a workgroup has 8, 4, 2, 2, 1, 1
+    // of them for N = 32, 16, 8, 4, 2, 1, so 256, 512, 1024, 1024, 2048, 2048 workgroups
+    const int waves = N >= 8 ? N / 4 : (N == 4 ? 2 : 1);          // as dispatched in launch_bwd_disc
+    int64_t G = ((int64_t)B * D) / (balanced ? 2048 / waves : 2048);
     if (G < 8) G = 8;
     if (G > kMaxG) G = kMaxG;
     if (G > D) G = D;
@@ -452,9 +459,10 @@ static hipError_t launch_bwd_disc(const BwdParams &p, hipStream_t s) {
         // longer scans (measured 2.4x slower on the Mamba-block shape)
         case 1: return launch_bwd_n<IO, 1, 1, DISC, 4>(p, s);
         case 2: return launch_bwd_n<IO, 2, 2, DISC, 4>(p, s);
-        case 4: return launch_bwd_n<IO, 4, 4, DISC, 4>(p, s);
+        case 4: return launch_bwd_n<IO, 4, 2, DISC, 4>(p, s);
         case 8: return launch_bwd_n<IO, 8, 4, DISC, 4>(p, s);
         case 16: return launch_bwd_n<IO, 16, LRNNX_BWD_NK16, DISC, LRNNX_BWD_T16>(p, s);
+        case 32: return launch_bwd_n<IO, 32, 4, DISC, 4>(p, s);    // eight wavefronts: one workgroup per compute unit
     }
     return hipErrorInvalidValue;
 }

@@ -369,6 +369,7 @@ static hipError_t launch_fwd_disc(const FwdParams &p, hipStream_t s) {
         case 4: return launch_fwd_n<IO, 4, DISC>(p, s);
         case 8: return launch_fwd_n<IO, 8, DISC>(p, s);
         case 16: return launch_fwd_n<IO, 16, DISC>(p, s);
+        case 32: return launch_fwd_n<IO, 32, DISC>(p, s);
     }
     return hipErrorInvalidValue;
 }

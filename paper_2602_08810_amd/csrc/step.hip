@@ -86,6 +86,7 @@ static hipError_t launch_step_disc(const StepParams &p, hipStream_t s) {
         case 4: hipLaunchKernelGGL((k_ss_step<IO, 4, DISC>), grid, block, 0, s, p); break;
         case 8: hipLaunchKernelGGL((k_ss_step<IO, 8, DISC>), grid, block, 0, s, p); break;
         case 16: hipLaunchKernelGGL((k_ss_step<IO, 16, DISC>), grid, block, 0, s, p); break;
+        case 32: hipLaunchKernelGGL((k_ss_step<IO, 32, DISC>), grid, block, 0, s, p); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -26,7 +26,7 @@ def _cases():
     out = []
     for i in range(36):
         L = int(rng.choice(edge_L)) if i % 2 == 0 else int(rng.integers(1, 1400))
-        out.append(dict(B=int(rng.integers(1, 4)), D=int(rng.integers(1, 40)), N=int(rng.choice([1, 2, 4, 8, 16])), L=L,
+        out.append(dict(B=int(rng.integers(1, 4)), D=int(rng.integers(1, 40)), N=int(rng.choice([1, 2, 4, 8, 16, 32])), L=L,
                         io=str(rng.choice(["f32", "bf16"])), disc=str(rng.choice(DISCS)), gate=bool(rng.integers(0, 2)),
                         skip=bool(rng.integers(0, 2)), bias=bool(rng.integers(0, 2)), x0=bool(rng.integers(0, 2)),
                         softplus=bool(rng.integers(0, 4) > 0), path=str(rng.choice(["auto", "single_pass", "chunk_carry"])),

@@ -53,7 +53,7 @@ def test_config0_shape_fp32(api, oracle):
 
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
-@pytest.mark.parametrize("N", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("N", [1, 2, 4, 8, 16, 32])
 def test_state_sizes_multi_tile_ragged(api, oracle, io, N):
     _check(api, oracle, io, "zoh_s6", True, True, B=2, D=11, N=N, L=1300, gate=True, with_x0=True, seed=60 + N,
            bias=("uniform", -4.0, -2.0))

@@ -53,7 +53,7 @@ def test_config0_fp32(api, oracle):
 
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
-@pytest.mark.parametrize("N", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("N", [1, 2, 4, 8, 16, 32])
 def test_state_sizes_multi_tile_ragged(api, oracle, io, N):
     """Several 512-step tiles plus a ragged tail; D not a multiple of the workgroup's channel count."""
     _run_case(api, oracle, io, "zoh_s6", True, B=2, D=13, N=N, L=1300, gate=True, with_x0=True, seed=10 + N,

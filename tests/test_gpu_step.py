@@ -19,7 +19,7 @@ def api():
 
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
-@pytest.mark.parametrize("N", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("N", [1, 2, 4, 8, 16, 32])
 @pytest.mark.parametrize("disc", ["zoh_s6", "zoh", "bilinear", "dirac"])
 def test_selective_step_matches_oracle_over_several_tokens(api, oracle, io, N, disc):
     B, D, L = 3, 300, 5
