@@ -128,6 +128,21 @@ __device__ __forceinline__ void disc_partials(float dt, const ACoef &c, float a,
     }
 }
 
+// ---------------------------------------------------------------- per-step inputs of the backward pass
+// From the raw step input s = delta + bias, the upstream gradient dy and the gate input z of one time step:
+// Delta and d Delta / d s, the gradient reaching ypre (y = ypre z sigmoid(z)) and the factor that turns ypre into dz
+// (dz = dy ypre sigmoid(z) (1 + z (1 - sigmoid(z)))).
+__device__ __forceinline__ void bwd_step_inputs(float s, float dy, float z, bool softplus, bool has_z,
+                                                float &sp, float &sg, float &dyp, float &zf) {
+    if (softplus) softplus_sigmoid(s, sp, sg); else { sp = s; sg = 1.0f; }
+    if (has_z) {
+        const float sz = sigmoid_fast(z);
+        const float dsz = dy * sz;
+        dyp = dsz * z;
+        zf = dsz * __builtin_fmaf(z, 1.0f - sz, 1.0f);
+    } else { zf = 0.0f; dyp = dy; }
+}
+
 // ---------------------------------------------------------------- wavefront scans over affine pairs
 // One Hillis-Steele step on the pair held in (P,S): the pair of the lane named by the DPP
 // control is composed in from the earlier side.  Both updates are single VALU instructions

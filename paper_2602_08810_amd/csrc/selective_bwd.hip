@@ -166,15 +166,8 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 if (has_z) unpack_few<IO, TPW>(r_z, e_z);
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) {
-                    float s = r_d[i] + bias, sp, sg, dyp;
-                    if (p.softplus) softplus_sigmoid(s, sp, sg); else { sp = s; sg = 1.0f; }
-                    e_sg[i] = sg;
-                    if (has_z) {                                 // y = ypre z sig(z): dz = dy ypre sig (1 + z (1 - sig))
-                        const float sz = sigmoid_fast(e_z[i]);
-                        const float dsz = e_dy[i] * sz;
-                        dyp = dsz * e_z[i];
-                        e_zf[i] = dsz * __builtin_fmaf(e_z[i], 1.0f - sz, 1.0f);
-                    } else { e_zf[i] = 0.0f; dyp = e_dy[i]; }
+                    float sp, dyp;
+                    bwd_step_inputs(r_d[i] + bias, e_dy[i], has_z ? e_z[i] : 0.0f, p.softplus != 0, has_z, sp, e_sg[i], dyp, e_zf[i]);
                     sIn[0 * TILE + fslot(f0 + i)] = (f0 + i < rem) ? sp : 0.0f;
                     sIn[1 * TILE + fslot(f0 + i)] = e_u[i];
                     sIn[2 * TILE + fslot(f0 + i)] = dyp;

@@ -192,14 +192,8 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
             if (has_z) unpack_few<IO, TPW>(r_z, e_z);
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
-                float s = r_d[i] + bias, sp, sg, dyp, zf;
-                if (p.softplus) softplus_sigmoid(s, sp, sg); else { sp = s; sg = 1.0f; }
-                if (has_z) {                                     // y = ypre z sig(z): dz = dy ypre sig (1 + z (1 - sig))
-                    const float sz = sigmoid_fast(e_z[i]);
-                    const float dsz = e_dy[i] * sz;
-                    dyp = dsz * e_z[i];
-                    zf = dsz * __builtin_fmaf(e_z[i], 1.0f - sz, 1.0f);
-                } else { zf = 0.0f; dyp = e_dy[i]; }
+                float sp, sg, dyp, zf;
+                bwd_step_inputs(r_d[i] + bias, e_dy[i], has_z ? e_z[i] : 0.0f, p.softplus != 0, has_z, sp, sg, dyp, zf);
                 in[0 * TILE + fslot(f0 + i)] = (f0 + i < rem) ? sp : 0.0f;
                 in[1 * TILE + fslot(f0 + i)] = e_u[i];
                 in[2 * TILE + fslot(f0 + i)] = dyp;
