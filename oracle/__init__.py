@@ -359,6 +359,28 @@ def selective_step(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, 
     return y, x
 
 
+def selective_step_complex(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, disc="zoh_s6",
+                           delta_softplus=True):
+    """One token with a complex diagonal A: returns (y [B,D] real, new state [B,D,N] complex128); the input state is
+    not modified.  Bm, Cm [B,N] complex."""
+    x = np.array(_c128(x), copy=True)
+    u, delta = _f64(u), _f64(delta)
+    A, Bm, Cm = _c128(A), _c128(Bm), _c128(Cm)
+    Dskip, delta_bias, z = map(_f64, (Dskip, delta_bias, z))
+    Bsz, D, N = x.shape
+    assert u.shape == (Bsz, D) and delta.shape == (Bsz, D) and A.shape == (D, N)
+    assert Bm.shape == (Bsz, N) and Cm.shape == (Bsz, N)
+    y = np.empty((Bsz, D))
+    cp = lambda t: t.ctypes.data_as(ctypes.c_void_p)
+    rc = _load().lrnnx_oracle_selective_step_complex(
+        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_int(_disc(disc)),
+        ctypes.c_int(int(bool(delta_softplus))), cp(x), _p(u), _p(delta), cp(A), cp(Bm), cp(Cm),
+        _p(Dskip), _p(delta_bias), _p(z), _p(y))
+    if rc != 0:
+        raise ValueError(f"oracle complex step: bad arguments (rc={rc})")
+    return y, x
+
+
 def lti_step(lam, x, v):
     """One token of x <- lam * x + v for complex [B,P] arrays; returns the new state."""
     lam, v = _c128(lam), _c128(v)

@@ -667,6 +667,39 @@ int lrnnx_oracle_selective_step(
     return 0;
 }
 
+/* Single-token update with a complex diagonal A (the `step` method for the complex-A selective scan): one
+ * application of the recurrence of lrnnx_oracle_selective_scan_fwd_complex to a carried complex state.  x[B,D,N]
+ * complex, updated in place; u, delta, z, y [B,D] real; A [D,N], Bm, Cm [B,N] complex.  Optional: Dskip,
+ * delta_bias, z.                                                                                              */
+int lrnnx_oracle_selective_step_complex(
+    int B, int D, int N, int disc, int delta_softplus,
+    double *x_, const double *u, const double *delta, const double *A_,
+    const double *Bm_, const double *Cm_, const double *Dskip,
+    const double *delta_bias, const double *z, double *y)
+{
+    if (B < 0 || D < 0 || N < 1 || disc < 0 || disc > 3) return 1;
+    double complex *x = (double complex *)x_;
+    const double complex *A = (const double complex *)A_, *Bm = (const double complex *)Bm_;
+    const double complex *Cm = (const double complex *)Cm_;
+    for (int b = 0; b < B; ++b)
+        for (int d = 0; d < D; ++d) {
+            long row = (long)b * D + d;
+            double s = delta[row] + (delta_bias ? delta_bias[d] : 0.0);
+            double dt = delta_softplus ? softplus(s) : s;
+            double acc = 0.0;
+            for (int n = 0; n < N; ++n) {
+                double complex a, g, t0, t1, t2, t3;
+                disc_eval_cd(disc, dt, A[(long)d * N + n], &a, &g, &t0, &t1, &t2, &t3);
+                x[row * N + n] = a * x[row * N + n] + g * Bm[(long)b * N + n] * u[row];
+                acc += creal(Cm[(long)b * N + n] * x[row * N + n]);
+            }
+            double ypre = acc + (Dskip ? Dskip[d] * u[row] : 0.0);
+            if (z) ypre *= z[row] * sigmoid(z[row]);
+            y[row] = ypre;
+        }
+    return 0;
+}
+
 /* Single-token update of the LTI complex-diagonal recurrence: x[B,P] <- lambda (.) x + v[B,P]. */
 int lrnnx_oracle_lti_step(int B, int P, const double *lambda, double *x, const double *v)
 {

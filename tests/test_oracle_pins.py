@@ -927,3 +927,33 @@ def test_complex_forward_chains_through_x0_and_x_last(oracle):
     dt = np.logaddexp(0.0, p["delta"] + p["delta_bias"][None, :, None])[:, :, :cut]          # [B,D,cut]
     prod_a = np.exp(dt.sum(-1)[..., None] * p["A"][None])                                      # [B,D,N]
     np.testing.assert_allclose(g["dx0"], g1["dx0"] + np.conj(prod_a) * g2["dx0"], rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("disc", DISCS)
+def test_complex_step_by_step_equals_the_complex_scan(oracle, disc):
+    """Mode equivalence (Sec. 3) for the complex-A scan: L step calls reproduce the scan, and one step matches the
+    recurrence written out with numpy complex scalars; with zero imaginary parts it is the real step."""
+    p = _complex_problem(95, B=2, D=3, N=4, L=9)
+    y_scan, x_last = oracle.selective_scan_fwd_complex(**p, disc=disc)
+    x = p["x0"].copy()
+    for l in range(9):
+        y, x = oracle.selective_step_complex(x, p["u"][:, :, l], p["delta"][:, :, l], p["A"], p["Bm"][:, l], p["Cm"][:, l],
+                                             Dskip=p["Dskip"], delta_bias=p["delta_bias"], z=p["z"][:, :, l], disc=disc)
+        np.testing.assert_allclose(y, y_scan[:, :, l], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(x, x_last, rtol=1e-12, atol=1e-13)
+    b, d, n = 1, 2, 3
+    dt = np.logaddexp(0, p["delta"][b, d, 0] + p["delta_bias"][d])
+    a, g = _disc_py_c(disc, dt, p["A"][d, n])
+    y1, x1 = oracle.selective_step_complex(p["x0"], p["u"][:, :, 0], p["delta"][:, :, 0], p["A"], p["Bm"][:, 0],
+                                           p["Cm"][:, 0], delta_bias=p["delta_bias"], disc=disc)
+    assert x1[b, d, n] == pytest.approx(a * p["x0"][b, d, n] + g * p["Bm"][b, 0, n] * p["u"][b, d, 0], rel=1e-12)
+    assert y1[b, d] == pytest.approx((p["Cm"][b, 0] * x1[b, d]).sum().real, rel=1e-12)
+    rng = np.random.default_rng(96)
+    q = _rand_problem(rng, B=2, D=3, N=4, L=1)
+    yr, xr = oracle.selective_step(q["x0"], q["u"][:, :, 0], q["delta"][:, :, 0], q["A"], q["Bm"][:, 0], q["Cm"][:, 0],
+                                   Dskip=q["Dskip"], delta_bias=q["delta_bias"], z=q["z"][:, :, 0], disc=disc)
+    yc, xc = oracle.selective_step_complex(q["x0"] + 0j, q["u"][:, :, 0], q["delta"][:, :, 0], q["A"] + 0j,
+                                           q["Bm"][:, 0] + 0j, q["Cm"][:, 0] + 0j, Dskip=q["Dskip"],
+                                           delta_bias=q["delta_bias"], z=q["z"][:, :, 0], disc=disc)
+    np.testing.assert_allclose(yc, yr, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(xc.real, xr, rtol=1e-12, atol=1e-13)
