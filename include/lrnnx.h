@@ -390,6 +390,30 @@ typedef struct lrnnx_ss_step_args {
 
 int lrnnx_selective_step(const lrnnx_ss_step_args *args);
 
+/* lrnnx_selective_step_complex: the same single-token update for the scan with a complex diagonal A
+ * (lrnnx_selective_scan_fwd_complex): x[B,D,N] complex float pairs, updated IN PLACE; A [D,N] complex float pairs;
+ * Bm, Cm contiguous [B,N] complex in io_dtype (interleaved re, im); y[b,d] = Re(Cm[b,:] . x[b,d,:]) + Dskip[d] u[b,d],
+ * gated as above.  x, A, Bm, Cm must be 16-byte aligned.  L calls reproduce the scan on L steps up to fp32
+ * rounding.  Optional: Dskip, delta_bias, z.                                                                     */
+typedef struct lrnnx_ss_step_complex_args {
+    size_t struct_size;
+    int32_t B, D, N;
+    int32_t io_dtype, disc, delta_softplus;
+    void *x;                                                       /* [B,D,N] complex float, in/out */
+    const void *u;      int64_t u_stride_b, u_stride_d;
+    const void *delta;  int64_t delta_stride_b, delta_stride_d;
+    const void *A;                                                 /* [D,N] complex float */
+    const void *Bm;                                                /* [B,N] complex io */
+    const void *Cm;                                                /* [B,N] complex io */
+    const float *Dskip;
+    const float *delta_bias;
+    const void *z;      int64_t z_stride_b, z_stride_d;
+    void *y;            int64_t y_stride_b, y_stride_d;
+    void *stream;
+} lrnnx_ss_step_complex_args;
+
+int lrnnx_selective_step_complex(const lrnnx_ss_step_complex_args *args);
+
 /* lrnnx_lti_step: x[B,P] (complex64, IN PLACE) <- lambda[P] (.) x + v[B,P]. */
 typedef struct lrnnx_lti_step_args {
     size_t struct_size;

@@ -140,6 +140,20 @@ class StepArgs(ctypes.Structure):
     ]
 
 
+class StepComplexArgs(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32),
+        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32),
+        ("x", _vp),
+        ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
+        ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
+        ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
+        ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
+        ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
+        ("stream", _vp),
+    ]
+
+
 class LtiStepArgs(ctypes.Structure):
     _fields_ = [("struct_size", _sz), ("B", _i32), ("P", _i32), ("lambda_", _vp), ("x", _vp), ("v", _vp), ("stream", _vp)]
 
@@ -169,6 +183,8 @@ def lib():
         L.lrnnx_diag_scan_bwd.argtypes = [ctypes.POINTER(DiagScanBwdArgs)]
         L.lrnnx_diag_scan_bwd.restype = ctypes.c_int
         L.lrnnx_selective_step.argtypes = [ctypes.POINTER(StepArgs)]
+        L.lrnnx_selective_step_complex.argtypes = [ctypes.POINTER(StepComplexArgs)]
+        L.lrnnx_selective_step_complex.restype = ctypes.c_int
         L.lrnnx_lti_step.argtypes = [ctypes.POINTER(LtiStepArgs)]
         L.lrnnx_selective_step.restype = ctypes.c_int
         L.lrnnx_lti_step.restype = ctypes.c_int
@@ -673,6 +689,41 @@ def lrnnx_selective_step(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=
     a.y, a.y_stride_b, a.y_stride_d = _bd(y, "y", io)
     a.stream = _stream()
     _check(lib().lrnnx_selective_step(ctypes.byref(a)))
+    return y
+
+
+def lrnnx_selective_step_complex(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None,
+                                 disc="zoh_s6", delta_softplus=True, out=None):
+    """One token of the complex-A scan: updates the state x [B,D,N] complex64 in place and returns y [B,D]; see
+    lrnnx_ss_step_complex_args.  Bm, Cm [B,N]: complex64 (float32 I/O) or bfloat16 [B,N,2] (re, im) pairs."""
+    io = u.dtype
+    if x.dtype != torch.complex64 or x.dim() != 3 or not x.is_contiguous():
+        raise ValueError("x: expected contiguous complex64 [B,D,N]")
+    Bsz, D, N = x.shape
+    if A.dtype != torch.complex64 or tuple(A.shape) != (D, N) or not A.is_contiguous():
+        raise ValueError("A: expected contiguous complex64 [D,N]")
+    for name, t in (("Bm", Bm), ("Cm", Cm)):
+        ok = t.is_contiguous() and ((io == torch.float32 and t.dtype == torch.complex64 and tuple(t.shape) == (Bsz, N)) or
+                                    (io == torch.bfloat16 and t.dtype == torch.bfloat16 and tuple(t.shape) == (Bsz, N, 2)))
+        if not ok:
+            raise ValueError(f"{name}: expected contiguous complex64 [B,N] (float32 I/O) or bfloat16 [B,N,2]")
+    a = StepComplexArgs()
+    a.struct_size = ctypes.sizeof(StepComplexArgs)
+    a.B, a.D, a.N = Bsz, D, N
+    a.io_dtype = _io_dtype(u)
+    a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
+    a.delta_softplus = int(bool(delta_softplus))
+    a.x = x.data_ptr()
+    a.u, a.u_stride_b, a.u_stride_d = _bd(u, "u", io)
+    a.delta, a.delta_stride_b, a.delta_stride_d = _bd(delta, "delta", io)
+    a.z, a.z_stride_b, a.z_stride_d = _bd(z, "z", io)
+    a.A, a.Bm, a.Cm = A.data_ptr(), Bm.data_ptr(), Cm.data_ptr()
+    a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
+    a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
+    y = out if out is not None else torch.empty((Bsz, D), dtype=io, device=u.device)
+    a.y, a.y_stride_b, a.y_stride_d = _bd(y, "y", io)
+    a.stream = _stream()
+    _check(lib().lrnnx_selective_step_complex(ctypes.byref(a)))
     return y
 
 

@@ -126,7 +126,7 @@ extern "C" {
 
 int64_t lrnnx_ckpt_interval(void) { return kCkptInterval; }
 int64_t lrnnx_packed_ckpt_slots(int64_t L, int64_t B) { return (L < 0 || B < 0) ? 0 : L / kCkptInterval + B; }
-int lrnnx_version(void) { return 131; }   // major * 100 + minor; bumped whenever an entry point or a struct field is added
+int lrnnx_version(void) { return 132; }   // major * 100 + minor; bumped whenever an entry point or a struct field is added
 
 const char *lrnnx_status_string(int status) {
     switch (status) {
@@ -544,6 +544,25 @@ int lrnnx_selective_step(const lrnnx_ss_step_args *a) {
     p.z_sb = a->z_stride_b; p.z_sd = a->z_stride_d; p.y_sb = a->y_stride_b; p.y_sd = a->y_stride_d;
     p.A = a->A; p.Dskip = a->Dskip; p.bias = a->delta_bias;
     return launch_ss_step(p, a->io_dtype, a->disc, reinterpret_cast<hipStream_t>(a->stream)) == hipSuccess
+               ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+}
+
+int lrnnx_selective_step_complex(const lrnnx_ss_step_complex_args *a) {
+    if (!a || a->struct_size < sizeof(lrnnx_ss_step_complex_args)) return LRNNX_ERR_INVALID_ARG;
+    if (a->B < 1 || a->D < 1 || a->N < 1) return LRNNX_ERR_INVALID_ARG;
+    if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
+    if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
+    if (!a->x || !a->u || !a->delta || !a->A || !a->Bm || !a->Cm || !a->y) return LRNNX_ERR_INVALID_ARG;
+    if (!supported_n_complex(a->N)) return LRNNX_ERR_UNSUPPORTED;
+    if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
+    if (!aligned16(a->x) || !aligned16(a->A) || !aligned16(a->Bm) || !aligned16(a->Cm)) return LRNNX_ERR_INVALID_ARG;
+    CStepParams p{};
+    p.B = a->B; p.D = a->D; p.N = a->N; p.softplus = a->delta_softplus ? 1 : 0;
+    p.x = reinterpret_cast<float2 *>(a->x); p.u = a->u; p.delta = a->delta; p.z = a->z; p.Bm = a->Bm; p.Cm = a->Cm; p.y = a->y;
+    p.u_sb = a->u_stride_b; p.u_sd = a->u_stride_d; p.dl_sb = a->delta_stride_b; p.dl_sd = a->delta_stride_d;
+    p.z_sb = a->z_stride_b; p.z_sd = a->z_stride_d; p.y_sb = a->y_stride_b; p.y_sd = a->y_stride_d;
+    p.A = reinterpret_cast<const float2 *>(a->A); p.Dskip = a->Dskip; p.bias = a->delta_bias;
+    return launch_ss_cstep(p, a->io_dtype, a->disc, reinterpret_cast<hipStream_t>(a->stream)) == hipSuccess
                ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }
 

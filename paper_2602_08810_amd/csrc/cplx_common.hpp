@@ -16,6 +16,22 @@ template <> struct cword<float> {
     static __device__ __forceinline__ float2 unpack(float2 w) { return w; }
 };
 
+// NK consecutive complex words, 16 bytes at a time where they fill whole 16-byte chunks (the caller's base pointer
+// is 16-byte aligned and the row pitch N * sizeof(CW) is then a multiple of 16 too)
+template <typename CW, int NK>
+__device__ __forceinline__ void load_cwords(const CW *p, CW *out) {
+    constexpr int BYTES = NK * (int)sizeof(CW);
+    if constexpr (BYTES % 16 == 0) {
+        uint4 r[BYTES / 16];
+#pragma unroll
+        for (int c = 0; c < BYTES / 16; ++c) r[c] = reinterpret_cast<const uint4 *>(p)[c];
+        __builtin_memcpy(out, r, BYTES);
+    } else {
+#pragma unroll
+        for (int k = 0; k < NK; ++k) out[k] = p[k];
+    }
+}
+
 constexpr float kInv2Pi = 0.15915494309189535f;
 
 // a = exp(dt A) for complex A = (Ar, Ai): e^{dt Ar} (cos(dt Ai), sin(dt Ai)); v_sin/v_cos take revolutions

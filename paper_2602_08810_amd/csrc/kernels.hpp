@@ -119,8 +119,20 @@ struct StepParams {
     const float *A, *Dskip, *bias;
 };
 
+struct CStepParams {
+    int B, D, N;
+    int softplus;
+    float2 *x;                                 // [B,D,N] complex, in/out
+    const void *u, *delta, *z, *Bm, *Cm;       // u, delta, z: [B,D] with strides; Bm, Cm: [B,N] complex in the I/O type
+    void *y;
+    int64_t u_sb, u_sd, dl_sb, dl_sd, z_sb, z_sd, y_sb, y_sd;
+    const float2 *A;
+    const float *Dskip, *bias;
+};
+
 // Each launcher returns hipSuccess or the launch error; it validates nothing.
 hipError_t launch_ss_step(const StepParams &p, int io_dtype, int disc, hipStream_t s);
+hipError_t launch_ss_cstep(const CStepParams &p, int io_dtype, int disc, hipStream_t s);
 hipError_t launch_lti_step(int B, int P, const float2 *lambda, float2 *x, const float2 *v, hipStream_t s);
 hipError_t launch_ss_fwd(const FwdParams &p, int io_dtype, int disc, hipStream_t s);
 hipError_t launch_ss_carry(const FwdParams &p, hipStream_t s);

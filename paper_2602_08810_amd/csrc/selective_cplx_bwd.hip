@@ -27,22 +27,6 @@ constexpr int kMaxGc = 64;
 
 namespace {
 
-// NK consecutive complex words, 16 bytes at a time where they fill whole 16-byte chunks (the caller's base pointer
-// is 16-byte aligned and the row pitch N * sizeof(CW) is then a multiple of 16 too)
-template <typename CW, int NK>
-__device__ __forceinline__ void load_cwords(const CW *p, CW *out) {
-    constexpr int BYTES = NK * (int)sizeof(CW);
-    if constexpr (BYTES % 16 == 0) {
-        uint4 r[BYTES / 16];
-#pragma unroll
-        for (int c = 0; c < BYTES / 16; ++c) r[c] = reinterpret_cast<const uint4 *>(p)[c];
-        __builtin_memcpy(out, r, BYTES);
-    } else {
-#pragma unroll
-        for (int k = 0; k < NK; ++k) out[k] = p[k];
-    }
-}
-
 // Sum over the 32 lanes of each half-wavefront of four per-lane values at once: two exchange steps leave each lane
 // of a quad with the quad's sum of ONE value (lane%4 = 0,1,2,3 -> value 0,2,1,3), two rotations sum the quads of a
 // row, one swizzle sums the two rows.  Lanes 0-3 and 32-35 own the results.

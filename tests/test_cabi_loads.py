@@ -61,6 +61,8 @@ def test_null_and_bad_struct_are_rejected_without_a_gpu(lib):
     assert lib.lrnnx_lti_diag_scan_bwd(None) == 1
     lib.lrnnx_selective_scan_fwd_complex.argtypes = [ctypes.c_void_p]
     assert lib.lrnnx_selective_scan_fwd_complex(None) == 1
+    lib.lrnnx_selective_step_complex.argtypes = [ctypes.c_void_p]
+    assert lib.lrnnx_selective_step_complex(None) == 1
     lib.lrnnx_selective_scan_bwd_complex.argtypes = [ctypes.c_void_p]
     assert lib.lrnnx_selective_scan_bwd_complex(None) == 1
     lib.lrnnx_diag_scan_bwd.argtypes = [ctypes.c_void_p]

@@ -106,3 +106,52 @@ def test_selective_step_with_grouped_maps(api, oracle, io, N, D, G):
         assert rel_err(host(x), xr) <= 1e-4, f"state at token {l}"
         assert rel_err(host(y), host(y_scan[:, :, l])) <= TOL[io]
     assert rel_err(host(x), host(x_last)) <= 1e-4
+
+
+def _cmaps(a, io):
+    """[..., 2] float32 (re, im), already rounded -> complex64 (float32 I/O) or bfloat16 pairs."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t.to(torch.bfloat16) if io == "bf16" else torch.view_as_complex(t)
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("N", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("disc", ["zoh_s6", "zoh", "bilinear", "dirac"])
+def test_complex_step_matches_oracle_over_several_tokens(api, oracle, io, N, disc):
+    import torch
+    B, D, L = 3, 300, 5
+    p = workloads.make_selective_complex(B=B, D=D, N=N, L=L, io=io, gate=True, seed=190 + N, with_x0=True)
+    cplx = lambda a: a[..., 0].astype(np.float64) + 1j * a[..., 1].astype(np.float64)
+    u, dl, z = dev(p["u"], io), dev(p["delta"], io), dev(p["z"], io)
+    A = torch.from_numpy(p["A"]).cuda()
+    x = torch.from_numpy(p["x0"]).cuda().clone()
+    xr = p["x0"].astype(np.complex128)
+    for l in range(L):
+        y = api.lrnnx_selective_step_complex(x, u[:, :, l], dl[:, :, l], A, _cmaps(p["Bm"][:, l], io), _cmaps(p["Cm"][:, l], io),
+                                             Dskip=dev(p["Dskip"]), delta_bias=dev(p["delta_bias"]), z=z[:, :, l], disc=disc)
+        yr, xr = oracle.selective_step_complex(xr, p["u"][:, :, l], p["delta"][:, :, l], p["A"], cplx(p["Bm"][:, l]),
+                                               cplx(p["Cm"][:, l]), Dskip=p["Dskip"], delta_bias=p["delta_bias"],
+                                               z=p["z"][:, :, l], disc=disc)
+        assert rel_err(host(y), yr) <= TOL[io], f"y at token {l}"
+        xg = x.cpu().numpy()
+        assert float(np.abs(xg - xr).max() / np.abs(xr).max()) <= 1e-4, f"state at token {l}"
+
+
+def test_complex_step_by_step_equals_the_complex_scan_kernel(api):
+    """L complex step launches reproduce one launch of the complex scan (state and outputs)."""
+    import torch
+    B, D, N, L = 2, 40, 16, 300
+    p = workloads.make_selective_complex(B=B, D=D, N=N, L=L, io="f32", gate=True, seed=197, with_x0=True)
+    u, dl, z = dev(p["u"]), dev(p["delta"]), dev(p["z"])
+    A, x0 = torch.from_numpy(p["A"]).cuda(), torch.from_numpy(p["x0"]).cuda()
+    Bm, Cm = _cmaps(p["Bm"], "f32"), _cmaps(p["Cm"], "f32")
+    kw = dict(Dskip=dev(p["Dskip"]), delta_bias=dev(p["delta_bias"]))
+    y_scan, x_last = api.lrnnx_selective_scan_fwd_complex(u, dl, A, Bm, Cm, z=z, x0=x0, return_last_state=True, **kw)
+    x = x0.clone()
+    ys = torch.empty_like(y_scan)
+    Bt, Ct = Bm.transpose(0, 1).contiguous(), Cm.transpose(0, 1).contiguous()     # [L,B,N]
+    for l in range(L):
+        api.lrnnx_selective_step_complex(x, u[:, :, l], dl[:, :, l], A, Bt[l], Ct[l], z=z[:, :, l], out=ys[:, :, l], **kw)
+    assert rel_err(host(ys), host(y_scan)) <= 1e-4
+    assert float((x - x_last).abs().max() / x_last.abs().max()) <= 1e-4
