@@ -124,12 +124,13 @@ def selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None,
     x0c = None if x0 is None else _c128(x0)
     Bsz, D, L = u.shape
     N = A.shape[1]
-    assert A.shape == (D, N) and Bm.shape == (Bsz, L, N) and Cm.shape == (Bsz, L, N)
+    assert A.shape == (D, N)
+    G = _groups(Bm, Cm, Bsz, L, N)
     y = np.empty((Bsz, D, L))
     x_last = np.empty((Bsz, D, N), dtype=np.complex128)
     cp = lambda t: ctypes.c_void_p(0) if t is None else t.ctypes.data_as(ctypes.c_void_p)
     rc = _load().lrnnx_oracle_selective_scan_fwd_complex(
-        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_long(L),
+        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_int(G), ctypes.c_long(L),
         ctypes.c_int(_disc(disc)), ctypes.c_int(int(bool(delta_softplus))),
         _p(u), _p(delta), cp(A), cp(Bm), cp(Cm), _p(Dskip), _p(delta_bias), _p(z), cp(x0c), _p(y), cp(x_last))
     if rc != 0:
@@ -156,7 +157,8 @@ def selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=N
     x0c = None if x0 is None else _c128(x0)
     Bsz, D, L = u.shape
     N = A.shape[1]
-    assert A.shape == (D, N) and Bm.shape == (Bsz, L, N) and Cm.shape == (Bsz, L, N) and dy.shape == (Bsz, D, L)
+    assert A.shape == (D, N) and dy.shape == (Bsz, D, L)
+    G = _groups(Bm, Cm, Bsz, L, N)
     c128 = np.complex128
     out = {
         "du": np.empty((Bsz, D, L)), "ddelta": np.empty((Bsz, D, L)),
@@ -168,7 +170,7 @@ def selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=N
     }
     cp = lambda t: ctypes.c_void_p(0) if t is None else t.ctypes.data_as(ctypes.c_void_p)
     rc = _load().lrnnx_oracle_selective_scan_bwd_complex(
-        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_long(L),
+        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_int(G), ctypes.c_long(L),
         ctypes.c_int(_disc(disc)), ctypes.c_int(int(bool(delta_softplus))),
         _p(u), _p(delta), cp(A), cp(Bm), cp(Cm), _p(Dskip), _p(delta_bias), _p(z), cp(x0c), _p(dy),
         _p(out["du"]), _p(out["ddelta"]), cp(out["dA"]), cp(out["dBm"]), cp(out["dCm"]),
@@ -369,11 +371,13 @@ def selective_step_complex(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, 
     Dskip, delta_bias, z = map(_f64, (Dskip, delta_bias, z))
     Bsz, D, N = x.shape
     assert u.shape == (Bsz, D) and delta.shape == (Bsz, D) and A.shape == (D, N)
-    assert Bm.shape == (Bsz, N) and Cm.shape == (Bsz, N)
+    assert Bm.shape == Cm.shape
+    assert Bm.shape == (Bsz, N) or (Bm.ndim == 3 and Bm.shape[0] == Bsz and Bm.shape[2] == N)
+    G = 1 if Bm.ndim == 2 else Bm.shape[1]
     y = np.empty((Bsz, D))
     cp = lambda t: t.ctypes.data_as(ctypes.c_void_p)
     rc = _load().lrnnx_oracle_selective_step_complex(
-        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_int(_disc(disc)),
+        ctypes.c_int(Bsz), ctypes.c_int(D), ctypes.c_int(N), ctypes.c_int(G), ctypes.c_int(_disc(disc)),
         ctypes.c_int(int(bool(delta_softplus))), cp(x), _p(u), _p(delta), cp(A), cp(Bm), cp(Cm),
         _p(Dskip), _p(delta_bias), _p(z), _p(y))
     if rc != 0:

@@ -189,20 +189,21 @@ static void disc_eval_c(int disc, double dt, double Ar, double Ai, double *ar, d
  * layers of Sec. 2.2.1 when their step size or maps depend on the input):
  *     x_{l,n} = a(Delta_l, A[d,n]) x_{l-1,n} + g(Delta_l, A[d,n]) Bm[b,l,n] u[b,d,l]      (complex)
  *     y[b,d,l] = Re( sum_n Cm[b,l,n] x_{l,n} ) + Dskip[d] u[b,d,l],   then the optional gate.
- * A [D,N], Bm, Cm [B,L,N], x0, x_last [B,D,N] are complex ((re, im) pairs of doubles); u, delta, z, y, Dskip,
- * delta_bias real.  Optional (NULL allowed): Dskip, delta_bias, z, x0, x_last.                                 */
+ * A [D,N], Bm, Cm [B,G,L,N] (channel d reads group d / (D/G); G = 1: [B,L,N]), x0, x_last [B,D,N] are complex
+ * ((re, im) pairs of doubles); u, delta, z, y, Dskip, delta_bias real.  Optional (NULL allowed): Dskip, delta_bias, z, x0, x_last.                                 */
 int lrnnx_oracle_selective_scan_fwd_complex(
-    int B, int D, int N, long L, int disc, int delta_softplus,
+    int B, int D, int N, int G, long L, int disc, int delta_softplus,
     const double *u, const double *delta, const double *A,
     const double *Bm, const double *Cm, const double *Dskip,
     const double *delta_bias, const double *z, const double *x0,
     double *y, double *x_last)
 {
-    if (B < 0 || D < 0 || N < 1 || L < 0 || disc < 0 || disc > 3) return 1;
+    if (B < 0 || D < 0 || N < 1 || L < 0 || disc < 0 || disc > 3 || G < 1 || D % G) return 1;
     long rows = (long)B * D;
 #pragma omp parallel for schedule(static)
     for (long row = 0; row < rows; ++row) {
         int b = (int)(row / D), d = (int)(row % D);
+        long bg = (long)b * G + d / (D / G);          /* row of Bm, Cm this channel reads: its batch entry and group */
         double *x = (double *)malloc(sizeof(double) * 2 * N);
         for (int n = 0; n < 2 * N; ++n) x[n] = x0 ? x0[row * 2 * N + n] : 0.0;
         for (long l = 0; l < L; ++l) {
@@ -213,7 +214,7 @@ int lrnnx_oracle_selective_scan_fwd_complex(
             for (int n = 0; n < N; ++n) {
                 double ar, ai, gr, gi;
                 disc_eval_c(disc, dt, A[2 * ((long)d * N + n)], A[2 * ((long)d * N + n) + 1], &ar, &ai, &gr, &gi);
-                long bc = 2 * (((long)b * L + l) * N + n);
+                long bc = 2 * ((bg * L + l) * N + n);
                 double br = (gr * Bm[bc] - gi * Bm[bc + 1]) * uu, bi = (gr * Bm[bc + 1] + gi * Bm[bc]) * uu;
                 double xr = ar * x[2 * n] - ai * x[2 * n + 1] + br;
                 double xi = ar * x[2 * n + 1] + ai * x[2 * n] + bi;
@@ -378,11 +379,11 @@ void lrnnx_oracle_disc_complex(int disc, double dt, double Ar, double Ai, double
  * (the convention of complex automatic differentiation); with it, for w = p q (complex product),
  * grad p = grad w * conj(q), and for y = Re(c x), grad x = dy conj(c), grad c = dy conj(x).  A real input that
  * enters a complex expression receives the real part.
- * Complex ((re, im) pairs): A, dA [D,N]; Bm, Cm, dBm, dCm [B,L,N]; x0, dx0 [B,D,N].  Real: u, delta, z, dy, du,
+ * Complex ((re, im) pairs): A, dA [D,N]; Bm, Cm, dBm, dCm [B,G,L,N] (G = 1: [B,L,N]); x0, dx0 [B,D,N].  Real: u, delta, z, dy, du,
  * ddelta, dz [B,D,L]; Dskip, delta_bias, dD, dbias [D].  dA, dBm, dCm, dD, dbias are overwritten.
  * Optional (may be NULL): Dskip, delta_bias, z, x0, dD, dbias, dz, dx0.                                        */
 int lrnnx_oracle_selective_scan_bwd_complex(
-    int B, int D, int N, long L, int disc, int delta_softplus,
+    int B, int D, int N, int G, long L, int disc, int delta_softplus,
     const double *u, const double *delta, const double *A_,
     const double *Bm_, const double *Cm_, const double *Dskip,
     const double *delta_bias, const double *z, const double *x0_,
@@ -390,12 +391,12 @@ int lrnnx_oracle_selective_scan_bwd_complex(
     double *du, double *ddelta, double *dA_, double *dBm_, double *dCm_,
     double *dD, double *dbias, double *dz, double *dx0_)
 {
-    if (B < 0 || D < 0 || N < 1 || L < 0 || disc < 0 || disc > 3) return 1;
+    if (B < 0 || D < 0 || N < 1 || L < 0 || disc < 0 || disc > 3 || G < 1 || D % G) return 1;
     const double complex *A = (const double complex *)A_, *Bm = (const double complex *)Bm_;
     const double complex *Cm = (const double complex *)Cm_, *x0 = (const double complex *)x0_;
     double complex *dA = (double complex *)dA_, *dBm = (double complex *)dBm_;
     double complex *dCm = (double complex *)dCm_, *dx0 = (double complex *)dx0_;
-    long nBC = (long)B * L * N;
+    long nBC = (long)B * G * L * N;
     for (long i = 0; i < (long)D * N; ++i) dA[i] = 0.0;
     for (long i = 0; i < nBC; ++i) { dBm[i] = 0.0; dCm[i] = 0.0; }
     if (dD) memset(dD, 0, sizeof(double) * (size_t)D);
@@ -418,6 +419,7 @@ int lrnnx_oracle_selective_scan_bwd_complex(
         double complex *h = (double complex *)malloc(sizeof(double complex) * N);
         for (int b = 0; b < B; ++b) {
             long row = (long)b * D + d;
+            long bg = (long)b * G + d / (D / G);      /* row of Bm, Cm, dBm, dCm of this channel's group */
             for (int n = 0; n < N; ++n) xs[n] = x0 ? x0[row * N + n] : 0.0;
             for (long l = 0; l < L; ++l) {                      /* forward sweep, states kept */
                 double s = delta[row * L + l] + (delta_bias ? delta_bias[d] : 0.0);
@@ -426,7 +428,7 @@ int lrnnx_oracle_selective_scan_bwd_complex(
                 for (int n = 0; n < N; ++n) {
                     double complex a, g, t0, t1, t2, t3;
                     disc_eval_cd(disc, dt, A[(long)d * N + n], &a, &g, &t0, &t1, &t2, &t3);
-                    xs[(l + 1) * N + n] = a * xs[l * N + n] + g * Bm[((long)b * L + l) * N + n] * uu;
+                    xs[(l + 1) * N + n] = a * xs[l * N + n] + g * Bm[(bg * L + l) * N + n] * uu;
                 }
             }
             for (int n = 0; n < N; ++n) h[n] = 0.0;            /* h[n] = conj(a_{l+1}) grad x_{l+1}, zero past the end */
@@ -435,7 +437,7 @@ int lrnnx_oracle_selective_scan_bwd_complex(
                 double dt = delta_softplus ? softplus(s) : s;
                 double uu = u[row * L + l];
                 double acc = 0.0;
-                for (int n = 0; n < N; ++n) acc += creal(Cm[((long)b * L + l) * N + n] * xs[(l + 1) * N + n]);
+                for (int n = 0; n < N; ++n) acc += creal(Cm[(bg * L + l) * N + n] * xs[(l + 1) * N + n]);
                 double ypre = acc + (Dskip ? Dskip[d] * uu : 0.0);
                 double dypre = dy[row * L + l];
                 if (z) {
@@ -447,7 +449,7 @@ int lrnnx_oracle_selective_scan_bwd_complex(
                 double du_l = Dskip ? dypre * Dskip[d] : 0.0;
                 double ddt = 0.0;
                 for (int n = 0; n < N; ++n) {
-                    long bc = ((long)b * L + l) * N + n;
+                    long bc = (bg * L + l) * N + n;
                     double complex a, g, a_t, a_A, g_t, g_A;
                     disc_eval_cd(disc, dt, A[(long)d * N + n], &a, &g, &a_t, &a_A, &g_t, &g_A);
                     double complex hx = dypre * conj(Cm[bc]) + h[n];        /* grad x_l */
@@ -669,15 +671,15 @@ int lrnnx_oracle_selective_step(
 
 /* Single-token update with a complex diagonal A (the `step` method for the complex-A selective scan): one
  * application of the recurrence of lrnnx_oracle_selective_scan_fwd_complex to a carried complex state.  x[B,D,N]
- * complex, updated in place; u, delta, z, y [B,D] real; A [D,N], Bm, Cm [B,N] complex.  Optional: Dskip,
+ * complex, updated in place; u, delta, z, y [B,D] real; A [D,N], Bm, Cm [B,G,N] complex (G = 1: [B,N]).  Optional: Dskip,
  * delta_bias, z.                                                                                              */
 int lrnnx_oracle_selective_step_complex(
-    int B, int D, int N, int disc, int delta_softplus,
+    int B, int D, int N, int G, int disc, int delta_softplus,
     double *x_, const double *u, const double *delta, const double *A_,
     const double *Bm_, const double *Cm_, const double *Dskip,
     const double *delta_bias, const double *z, double *y)
 {
-    if (B < 0 || D < 0 || N < 1 || disc < 0 || disc > 3) return 1;
+    if (B < 0 || D < 0 || N < 1 || disc < 0 || disc > 3 || G < 1 || D % G) return 1;
     double complex *x = (double complex *)x_;
     const double complex *A = (const double complex *)A_, *Bm = (const double complex *)Bm_;
     const double complex *Cm = (const double complex *)Cm_;
@@ -690,8 +692,9 @@ int lrnnx_oracle_selective_step_complex(
             for (int n = 0; n < N; ++n) {
                 double complex a, g, t0, t1, t2, t3;
                 disc_eval_cd(disc, dt, A[(long)d * N + n], &a, &g, &t0, &t1, &t2, &t3);
-                x[row * N + n] = a * x[row * N + n] + g * Bm[(long)b * N + n] * u[row];
-                acc += creal(Cm[(long)b * N + n] * x[row * N + n]);
+                long bg = (long)b * G + d / (D / G);
+                x[row * N + n] = a * x[row * N + n] + g * Bm[bg * N + n] * u[row];
+                acc += creal(Cm[bg * N + n] * x[row * N + n]);
             }
             double ypre = acc + (Dskip ? Dskip[d] * u[row] : 0.0);
             if (z) ypre *= z[row] * sigmoid(z[row]);

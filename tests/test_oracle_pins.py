@@ -957,3 +957,34 @@ def test_complex_step_by_step_equals_the_complex_scan(oracle, disc):
                                            delta_bias=q["delta_bias"], z=q["z"][:, :, 0], disc=disc)
     np.testing.assert_allclose(yc, yr, rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(xc.real, xr, rtol=1e-12, atol=1e-13)
+
+
+def test_complex_grouped_equals_one_ungrouped_problem_per_group(oracle):
+    """Grouped maps for the complex-A scan: each group is an independent ungrouped problem over its own channels
+    (forward, backward and single-token step); the ungrouped functions are pinned above."""
+    B, D, N, L, G = 2, 6, 3, 8, 3
+    p = _complex_problem(97, B=B, D=D, N=N, L=L)
+    rng = np.random.default_rng(98)
+    c = lambda *s: rng.standard_normal(s) + 1j * rng.standard_normal(s)
+    p["Bm"], p["Cm"] = c(B, G, L, N), c(B, G, L, N)
+    dy = rng.standard_normal((B, D, L))
+    y, xl = oracle.selective_scan_fwd_complex(**p, disc="zoh")
+    g = oracle.selective_scan_bwd_complex(dy=dy, **p, disc="zoh")
+    ys, xs = oracle.selective_step_complex(p["x0"], p["u"][:, :, 0], p["delta"][:, :, 0], p["A"], p["Bm"][:, :, 0],
+                                           p["Cm"][:, :, 0], Dskip=p["Dskip"], delta_bias=p["delta_bias"],
+                                           z=p["z"][:, :, 0], disc="zoh")
+    np.testing.assert_allclose(ys, y[:, :, 0], rtol=1e-12, atol=1e-13)       # the step is the scan's first token
+    for grp in range(G):
+        ds = slice(grp * (D // G), (grp + 1) * (D // G))
+        q = dict(u=p["u"][:, ds], delta=p["delta"][:, ds], A=p["A"][ds], Bm=p["Bm"][:, grp], Cm=p["Cm"][:, grp],
+                 Dskip=p["Dskip"][ds], delta_bias=p["delta_bias"][ds], z=p["z"][:, ds], x0=p["x0"][:, ds])
+        yq, xq = oracle.selective_scan_fwd_complex(**q, disc="zoh")
+        gq = oracle.selective_scan_bwd_complex(dy=dy[:, ds], **q, disc="zoh")
+        np.testing.assert_allclose(y[:, ds], yq, rtol=1e-14)
+        np.testing.assert_allclose(xl[:, ds], xq, rtol=1e-14)
+        for k in ("du", "ddelta", "dz", "dx0"):
+            np.testing.assert_allclose(g[k][:, ds], gq[k], rtol=1e-13, atol=1e-15)
+        for k in ("dA", "dD", "dbias"):
+            np.testing.assert_allclose(g[k][ds], gq[k], rtol=1e-13, atol=1e-15)
+        for k in ("dBm", "dCm"):
+            np.testing.assert_allclose(g[k][:, grp], gq[k], rtol=1e-13, atol=1e-15)
