@@ -135,7 +135,8 @@ int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *args);
  * (Eq. 2 with y = Re(C x) + D u: the complex-diagonal layers of Sec. 2.2.1 with an input-dependent step size and
  * input-dependent maps; time-invariant maps are passed with every row equal).  u, delta, z, y, Dskip, delta_bias are
  * real as above.  A [D,N] complex float pairs; Bm, Cm [B,L,N] complex in io_dtype (interleaved re, im: bfloat16
- * pairs or float pairs), contiguous, 16-byte aligned; x0, x_last [B,D,N] complex float pairs (optional).
+ * pairs or float pairs), contiguous, 16-byte aligned ([B,G,L,N] with bc_groups = G > 1, as for the real scan);
+ * x0, x_last [B,D,N] complex float pairs (optional).
  * a and g are the four schemes of lrnnx_disc in complex arithmetic.  Delta * Im(A) must stay within
  * +-256 * 2 pi (the range of the hardware sine and cosine).  One pass over the sequence.
  * ckpt (optional): [B,D,ceil(L/lrnnx_ckpt_interval()),N] complex float pairs, the state entering every
@@ -159,6 +160,9 @@ typedef struct lrnnx_ss_fwd_complex_args {
     void *x_last;                                                  /* [B,D,N] complex float, out or NULL */
     void *stream;
     void *ckpt;         /* out or NULL; callers built against the shorter struct get NULL */
+    int32_t bc_groups;  /* number of Bm/Cm groups G (maps [B,G,L,N], channel d reads group d / (D/G), D a multiple of
+                           G); 0 or 1: none; callers built against a shorter struct get 1 */
+    int32_t reserved2;
 } lrnnx_ss_fwd_complex_args;
 
 int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *args);
@@ -178,7 +182,8 @@ typedef struct lrnnx_ss_bwd_complex_args {
     size_t struct_size;
     int32_t B, D, N;
     int64_t L;
-    int32_t io_dtype, disc, delta_softplus, reserved;
+    int32_t io_dtype, disc, delta_softplus;
+    int32_t bc_groups;                                             /* as in the forward call (then dBm, dCm are [B,G,L,N]); 0 or 1: none */
     const void *u;      int64_t u_stride_b, u_stride_d;
     const void *delta;  int64_t delta_stride_b, delta_stride_d;
     const void *A;                                                 /* [D,N] complex float */
@@ -410,6 +415,9 @@ typedef struct lrnnx_ss_step_complex_args {
     const void *z;      int64_t z_stride_b, z_stride_d;
     void *y;            int64_t y_stride_b, y_stride_d;
     void *stream;
+    int32_t bc_groups;      /* G > 1: Bm, Cm are [B,G,N] and channel d reads group d / (D/G); callers built against
+                               the shorter struct get 1 */
+    int32_t reserved;
 } lrnnx_ss_step_complex_args;
 
 int lrnnx_selective_step_complex(const lrnnx_ss_step_complex_args *args);

@@ -51,14 +51,14 @@ class FwdComplexArgs(ctypes.Structure):
         ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
         ("x0", _vp),
         ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
-        ("x_last", _vp), ("stream", _vp), ("ckpt", _vp),
+        ("x_last", _vp), ("stream", _vp), ("ckpt", _vp), ("bc_groups", _i32), ("reserved2", _i32),
     ]
 
 
 class BwdComplexArgs(ctypes.Structure):
     _fields_ = [
         ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32), ("L", _i64),
-        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32), ("reserved", _i32),
+        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32), ("bc_groups", _i32),
         ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
         ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
         ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
@@ -150,7 +150,7 @@ class StepComplexArgs(ctypes.Structure):
         ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
         ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
         ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
-        ("stream", _vp),
+        ("stream", _vp), ("bc_groups", _i32), ("reserved", _i32),
     ]
 
 
@@ -349,10 +349,11 @@ def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias
     of (re, im) pairs.  x0, x_last [B,D,N] complex64; ckpt [B,D,ceil(L/interval),N] complex64."""
     io = u.dtype
     Bsz, D, L = u.shape
-    N = _check_complex_maps(A, Bm, Cm, io, Bsz, D, L)
+    N, G = _check_complex_maps(A, Bm, Cm, io, Bsz, D, L)
     a = FwdComplexArgs()
     a.struct_size = ctypes.sizeof(FwdComplexArgs)
     a.B, a.D, a.N, a.L = Bsz, D, N, L
+    a.bc_groups = G
     a.io_dtype = _io_dtype(u)
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
     a.delta_softplus = int(bool(delta_softplus))
@@ -385,16 +386,28 @@ def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias
 
 
 def _check_complex_maps(A, Bm, Cm, io, Bsz, D, L):
-    """Validate A [D,N] complex64 and the complex maps for this I/O type; returns N."""
+    """Validate A [D,N] complex64 and the complex maps for this I/O type ([B,L,N], or [B,G,L,N] with G groups; the
+    bfloat16 form has a trailing axis of (re, im) pairs); returns (N, G)."""
     if A.dtype != torch.complex64 or A.dim() != 2 or A.shape[0] != D or not A.is_contiguous():
         raise ValueError("A: expected contiguous complex64 [D,N]")
     N = A.shape[1]
+    G = None
     for name, t in (("Bm", Bm), ("Cm", Cm)):
-        ok = t.is_contiguous() and ((io == torch.float32 and t.dtype == torch.complex64 and tuple(t.shape) == (Bsz, L, N)) or
-                                    (io == torch.bfloat16 and t.dtype == torch.bfloat16 and tuple(t.shape) == (Bsz, L, N, 2)))
-        if not ok:
-            raise ValueError(f"{name}: expected contiguous complex64 [B,L,N] (float32 I/O) or bfloat16 [B,L,N,2]")
-    return N
+        shape = tuple(t.shape)
+        if io == torch.bfloat16:
+            ok = t.dtype == torch.bfloat16 and shape[-1:] == (2,)
+            shape = shape[:-1]
+        else:
+            ok = io == torch.float32 and t.dtype == torch.complex64
+        ok = ok and t.is_contiguous() and (shape == (Bsz, L, N) or (len(shape) == 4 and shape[0] == Bsz and shape[2:] == (L, N)))
+        g = shape[1] if ok and len(shape) == 4 else 1
+        if not ok or (G is not None and g != G):
+            raise ValueError(f"{name}: expected contiguous complex64 [B,L,N] or [B,G,L,N] (float32 I/O), or bfloat16 "
+                             "with a trailing (re, im) axis")
+        G = g
+    if D % G:
+        raise ValueError("D must be a multiple of the number of Bm/Cm groups")
+    return N, G
 
 
 def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,
@@ -405,7 +418,7 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
     type; dD, dbias float32.  `ckpt`: the checkpoints a forward call returned (else they are recomputed)."""
     io = u.dtype
     Bsz, D, L = u.shape
-    N = _check_complex_maps(A, Bm, Cm, io, Bsz, D, L)
+    N, G = _check_complex_maps(A, Bm, Cm, io, Bsz, D, L)
     dev = u.device
     outs = dict(outs or {})
 
@@ -420,6 +433,7 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
     a = BwdComplexArgs()
     a.struct_size = ctypes.sizeof(BwdComplexArgs)
     a.B, a.D, a.N, a.L = Bsz, D, N, L
+    a.bc_groups = G
     a.io_dtype = _io_dtype(u)
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
     a.delta_softplus = int(bool(delta_softplus))
@@ -442,8 +456,9 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
         a.dz, a.dz_stride_b, a.dz_stride_d = _bdl(new("dz", (Bsz, D, L), io), "dz", io)
     c64 = torch.complex64
     a.dA = new("dA", (D, N), c64).data_ptr()
-    a.dBm = new("dBm", (Bsz, L, N), c64).data_ptr()
-    a.dCm = new("dCm", (Bsz, L, N), c64).data_ptr()
+    map_shape = (Bsz, L, N) if (Bm.dim() == 3 + (io == torch.bfloat16)) else (Bsz, G, L, N)
+    a.dBm = new("dBm", map_shape, c64).data_ptr()
+    a.dCm = new("dCm", map_shape, c64).data_ptr()
     if Dskip is not None:
         a.dD = new("dD", (D,), torch.float32).data_ptr()
     if delta_bias is not None:
@@ -702,14 +717,26 @@ def lrnnx_selective_step_complex(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=
     Bsz, D, N = x.shape
     if A.dtype != torch.complex64 or tuple(A.shape) != (D, N) or not A.is_contiguous():
         raise ValueError("A: expected contiguous complex64 [D,N]")
+    G = None
     for name, t in (("Bm", Bm), ("Cm", Cm)):
-        ok = t.is_contiguous() and ((io == torch.float32 and t.dtype == torch.complex64 and tuple(t.shape) == (Bsz, N)) or
-                                    (io == torch.bfloat16 and t.dtype == torch.bfloat16 and tuple(t.shape) == (Bsz, N, 2)))
-        if not ok:
-            raise ValueError(f"{name}: expected contiguous complex64 [B,N] (float32 I/O) or bfloat16 [B,N,2]")
+        shape = tuple(t.shape)
+        if io == torch.bfloat16:
+            ok = t.dtype == torch.bfloat16 and shape[-1:] == (2,)
+            shape = shape[:-1]
+        else:
+            ok = io == torch.float32 and t.dtype == torch.complex64
+        ok = ok and t.is_contiguous() and (shape == (Bsz, N) or (len(shape) == 3 and shape[0] == Bsz and shape[2] == N))
+        g = shape[1] if ok and len(shape) == 3 else 1
+        if not ok or (G is not None and g != G):
+            raise ValueError(f"{name}: expected contiguous complex64 [B,N] or [B,G,N] (float32 I/O), or bfloat16 with a "
+                             "trailing (re, im) axis")
+        G = g
+    if D % G:
+        raise ValueError("D must be a multiple of the number of Bm/Cm groups")
     a = StepComplexArgs()
     a.struct_size = ctypes.sizeof(StepComplexArgs)
     a.B, a.D, a.N = Bsz, D, N
+    a.bc_groups = G
     a.io_dtype = _io_dtype(u)
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
     a.delta_softplus = int(bool(delta_softplus))

@@ -32,6 +32,7 @@ struct CFwdParams {
     int B, D, N;
     int64_t L;
     int softplus, vec;
+    int bcg, dpg;            // number of Bm/Cm groups and channels per group (D = bcg * dpg)
     const void *u, *delta, *z;
     void *y;
     int64_t u_sb, u_sd, dl_sb, dl_sd, z_sb, z_sd, y_sb, y_sd;
@@ -49,6 +50,7 @@ struct CBwdParams {
     int64_t L;
     int softplus, vec;
     int G;                   // channels per workgroup
+    int bcg, dpg;            // number of Bm/Cm groups and channels per group (D = bcg * dpg)
     const void *u, *delta, *z, *dy;
     void *du, *ddelta, *dz;
     int64_t u_sb, u_sd, dl_sb, dl_sd, z_sb, z_sd, dy_sb, dy_sd, du_sb, du_sd, dd_sb, dd_sd, dz_sb, dz_sd;
@@ -122,6 +124,7 @@ struct StepParams {
 struct CStepParams {
     int B, D, N;
     int softplus;
+    int bcg, dpg;                              // number of Bm/Cm groups and channels per group
     float2 *x;                                 // [B,D,N] complex, in/out
     const void *u, *delta, *z, *Bm, *Cm;       // u, delta, z: [B,D] with strides; Bm, Cm: [B,N] complex in the I/O type
     void *y;

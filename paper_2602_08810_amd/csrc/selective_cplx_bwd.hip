@@ -84,8 +84,12 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b = blockIdx.y;
-    const int d0 = blockIdx.x * p.G;
-    const int Gact = (p.D - d0 < p.G) ? p.D - d0 : p.G;
+    // a workgroup takes up to G consecutive channels of ONE Bm/Cm group
+    const int chunks_per_grp = (p.dpg + p.G - 1) / p.G;
+    const int grp = blockIdx.x / chunks_per_grp;
+    const int din0 = (blockIdx.x % chunks_per_grp) * p.G;
+    const int d0 = grp * p.dpg + din0;
+    const int Gact = (p.dpg - din0 < p.G) ? p.dpg - din0 : p.G;
     const int64_t L = p.L;
     const int64_t ntiles = (L + TILE - 1) / TILE;
     const int64_t nck = (L + kCkptInterval - 1) / kCkptInterval;
@@ -98,7 +102,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     }
     for (int i = tid; i < 2 * W * kMaxGc; i += NT) { sdD[i] = 0.0f; sdb[i] = 0.0f; }
 
-    const int64_t bc0 = (int64_t)b * L * N;                           // first complex element of this batch entry's maps
+    const int64_t bc0 = ((int64_t)b * p.bcg + grp) * L * N;          // first complex element of the maps of this batch entry and group
     const CW *Bm = reinterpret_cast<const CW *>(p.Bm) + bc0;
     const CW *Cm = reinterpret_cast<const CW *>(p.Cm) + bc0;
 
@@ -466,7 +470,7 @@ int cbwd_channels_per_group(int B, int D, int) {
 
 template <typename IO, int N, int NK, int DISC>
 static hipError_t launch_cbwd_n(const CBwdParams &p, hipStream_t s) {
-    dim3 grid((p.D + p.G - 1) / p.G, p.B);
+    dim3 grid(p.bcg * ((p.dpg + p.G - 1) / p.G), p.B);
     hipLaunchKernelGGL((k_ss_cbwd<IO, N, NK, 4, DISC>), grid, dim3((N / NK) * 64), 0, s, p);
     return hipGetLastError();
 }

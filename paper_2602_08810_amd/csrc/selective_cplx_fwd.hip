@@ -31,9 +31,12 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int b = blockIdx.y;
-    const int d_raw = blockIdx.x * W + w;
-    const bool active = d_raw < p.D;
-    const int d = active ? d_raw : p.D - 1;
+    // a workgroup takes W consecutive channels of ONE Bm/Cm group (it stages that group's maps in LDS)
+    const int blk_per_grp = (p.dpg + W - 1) / W;
+    const int grp = blockIdx.x / blk_per_grp;
+    const int d_in = (blockIdx.x % blk_per_grp) * W + w;
+    const bool active = d_in < p.dpg;
+    const int d = grp * p.dpg + (active ? d_in : p.dpg - 1);
     const int64_t L = p.L;
     const int64_t ntiles = (L + TILE - 1) / TILE;
     const int64_t row = (int64_t)b * p.D + d;
@@ -45,8 +48,8 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
     const bool want_y = p.y != nullptr;                 // a state-only sweep (checkpoints for the backward pass) has no y
     IO *yrow = reinterpret_cast<IO *>(p.y) + b * p.y_sb + d * p.y_sd;
     const int64_t nck = (L + kCkptInterval - 1) / kCkptInterval;
-    const CW *Bm = reinterpret_cast<const CW *>(p.Bm) + (int64_t)b * L * N;
-    const CW *Cm = reinterpret_cast<const CW *>(p.Cm) + (int64_t)b * L * N;
+    const CW *Bm = reinterpret_cast<const CW *>(p.Bm) + ((int64_t)b * p.bcg + grp) * L * N;
+    const CW *Cm = reinterpret_cast<const CW *>(p.Cm) + ((int64_t)b * p.bcg + grp) * L * N;
 
     // lane n holds the constants and the carried state of state n
     float Arv = 0.0f, Aiv = 0.0f, xrv = 0.0f, xiv = 0.0f;
@@ -151,7 +154,7 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
 template <typename IO, int N, int DISC>
 static hipError_t launch_cfwd_n(const CFwdParams &p, hipStream_t s) {
     constexpr int W = 8, T = 8;
-    dim3 grid((p.D + W - 1) / W, p.B);
+    dim3 grid(p.bcg * ((p.dpg + W - 1) / W), p.B);
     hipLaunchKernelGGL((k_ss_cfwd<IO, N, T, W, DISC>), grid, dim3(W * 64), 0, s, p);
     return hipGetLastError();
 }

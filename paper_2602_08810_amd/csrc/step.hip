@@ -92,8 +92,9 @@ __global__ __launch_bounds__(256) void k_ss_cstep(const CStepParams p) {
     const float2 *ap = p.A + (int64_t)d * N + q * NPT;
     load_cwords<float2, NPT>(xp, xs);
     load_cwords<float2, NPT>(ap, Av);
-    load_cwords<CW, NPT>(reinterpret_cast<const CW *>(p.Bm) + (int64_t)b * N + q * NPT, bw);
-    load_cwords<CW, NPT>(reinterpret_cast<const CW *>(p.Cm) + (int64_t)b * N + q * NPT, cw);
+    const int64_t bc = ((int64_t)b * p.bcg + d / p.dpg) * N + q * NPT;   // this channel's group of the maps
+    load_cwords<CW, NPT>(reinterpret_cast<const CW *>(p.Bm) + bc, bw);
+    load_cwords<CW, NPT>(reinterpret_cast<const CW *>(p.Cm) + bc, cw);
     float acc = 0.0f;
 #pragma unroll
     for (int n = 0; n < NPT; ++n) {

@@ -70,10 +70,11 @@ def make_selective(B, D, N, L, io="f32", gate=False, bias=("const", -2.0), seed=
     return out
 
 
-def make_selective_complex(B, D, N, L, io="f32", gate=False, seed=0, with_x0=False):
+def make_selective_complex(B, D, N, L, io="f32", gate=False, seed=0, with_x0=False, bc_groups=1):
     """Inputs of the selective scan with a complex diagonal A: as make_selective, with
     A[d,n] = -exp(U(-1,1)) + i U(-10,10) (complex64) and Bm, Cm = (N(0,1) + i N(0,1)) / sqrt(2), stored as
-    float32 [B,L,N,2] (re, im) rounded to the I/O type; delta_bias ~ U(-4,-2) per channel; x0 complex64."""
+    float32 [B,L,N,2] (re, im) rounded to the I/O type ([B,G,L,N,2] with bc_groups = G > 1); delta_bias ~ U(-4,-2)
+    per channel; x0 complex64."""
     rng = np.random.Generator(np.random.PCG64(seed))
     f32 = np.float32
     out = {}
@@ -81,8 +82,9 @@ def make_selective_complex(B, D, N, L, io="f32", gate=False, seed=0, with_x0=Fal
     out["Dskip"] = rng.standard_normal(D, dtype=f32)
     out["delta_bias"] = rng.uniform(-4.0, -2.0, size=D).astype(f32)
     s = f32(1.0 / np.sqrt(2.0))
-    out["Bm"] = _io_round(rng.standard_normal((B, L, N, 2), dtype=f32) * s, io)
-    out["Cm"] = _io_round(rng.standard_normal((B, L, N, 2), dtype=f32) * s, io)
+    mshape = (B, L, N, 2) if bc_groups <= 1 else (B, bc_groups, L, N, 2)
+    out["Bm"] = _io_round(rng.standard_normal(mshape, dtype=f32) * s, io)
+    out["Cm"] = _io_round(rng.standard_normal(mshape, dtype=f32) * s, io)
     out["u"] = _io_round(rng.standard_normal((B, D, L), dtype=f32), io)
     out["delta"] = _io_round(rng.standard_normal((B, D, L), dtype=f32), io)
     out["z"] = _io_round(rng.standard_normal((B, D, L), dtype=f32), io) if gate else None

@@ -80,3 +80,51 @@ def test_grouped_chunk_carry_path_equals_single_pass(api, oracle):
     yr, _ = oracle.selective_scan_fwd(**{k: p[k] for k in ("u", "delta", "A", "Bm", "Cm", "Dskip", "delta_bias", "z")})
     for path in ("single_pass", "chunk_carry"):
         assert rel_err(host(api.lrnnx_selective_scan_fwd(**t, path=path)), yr) <= TOL["bf16"], path
+
+
+# ----------------------------------------------------------------------------- complex-A scan with grouped maps
+def _cmaps(a, io):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t.to(torch.bfloat16) if io == "bf16" else torch.view_as_complex(t)
+
+
+def _cplx(a):
+    return a[..., 0].astype(np.float64) + 1j * a[..., 1].astype(np.float64)
+
+
+def _crel(got, ref):
+    den = np.abs(ref).max()
+    return float(np.abs(np.asarray(got, dtype=np.complex128) - ref).max() / (den if den > 0 else 1.0))
+
+
+@pytest.mark.parametrize("B,D,N,L,G", [(2, 16, 16, 300, 2), (1, 24, 16, 1000, 3), (2, 20, 8, 257, 4), (1, 6, 16, 700, 6),
+                                       (3, 26, 4, 130, 2), (1, 192, 16, 520, 2), (2, 9, 2, 64, 9)])
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+def test_complex_grouped_shapes(api, oracle, B, D, N, L, G, io):
+    import torch
+    p = workloads.make_selective_complex(B=B, D=D, N=N, L=L, io=io, gate=True, seed=D * 7 + G, with_x0=True, bc_groups=G)
+    dy = workloads._io_round(np.random.Generator(np.random.PCG64(D + G)).standard_normal((B, D, L), dtype=np.float32), io)
+    t = dict(u=dev(p["u"], io), delta=dev(p["delta"], io), A=torch.from_numpy(p["A"]).cuda(), Bm=_cmaps(p["Bm"], io),
+             Cm=_cmaps(p["Cm"], io), Dskip=dev(p["Dskip"]), delta_bias=dev(p["delta_bias"]), z=dev(p["z"], io),
+             x0=torch.from_numpy(p["x0"]).cuda())
+    y, x_last, ckpt = api.lrnnx_selective_scan_fwd_complex(**t, disc="zoh", return_last_state=True, return_ckpt=True)
+    g = api.lrnnx_selective_scan_bwd_complex(**t, dy=dev(dy, io), disc="zoh", ckpt=ckpt if L % 2 else None, want_dx0=True)
+    ref = dict(u=p["u"], delta=p["delta"], A=p["A"], Bm=_cplx(p["Bm"]), Cm=_cplx(p["Cm"]), Dskip=p["Dskip"],
+               delta_bias=p["delta_bias"], z=p["z"], x0=p["x0"])
+    yr, xr = oracle.selective_scan_fwd_complex(**ref, disc="zoh")
+    r = oracle.selective_scan_bwd_complex(dy=dy, **ref, disc="zoh")
+    assert rel_err(host(y), yr) <= TOL[io]
+    assert _crel(x_last.cpu().numpy(), xr) <= 1e-4
+    assert tuple(g["dBm"].shape) == ref["Bm"].shape
+    errs = {k: (rel_err(host(g[k]), r[k]), TOL[io]) for k in ("du", "ddelta", "dz")}
+    errs.update({k: (rel_err(host(g[k]), r[k]), 1e-4) for k in ("dD", "dbias")})
+    errs.update({k: (_crel(g[k].cpu().numpy(), r[k]), 1e-4) for k in ("dA", "dBm", "dCm", "dx0")})
+    bad = {k: v for k, v in errs.items() if not v[0] <= v[1]}
+    assert not bad, f"{bad} (all {errs})"
+    # single-token step with the first step's maps [B,G,N] reproduces the scan's first output
+    x = t["x0"].clone()
+    y1 = api.lrnnx_selective_step_complex(x, t["u"][:, :, 0], t["delta"][:, :, 0], t["A"], t["Bm"][:, :, 0].contiguous(),
+                                          t["Cm"][:, :, 0].contiguous(), Dskip=t["Dskip"], delta_bias=t["delta_bias"],
+                                          z=t["z"][:, :, 0], disc="zoh")
+    assert rel_err(host(y1), yr[:, :, 0]) <= TOL[io]
