@@ -53,6 +53,15 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     __shared__ float sdD[2 * W * kMaxG];  // dD and dbias partial sums per (half-wavefront, wavefront, channel)
     __shared__ float sdb[2 * W * kMaxG];
 
+    // Two workgroups share a compute unit, so each SIMD holds one wavefront of each.  The issue arbiter prefers the
+    // older wavefront, the older workgroup finishes some 17 % earlier and the younger one then runs alone, badly
+    // hiding its latencies (measured: 474 us against 570 us on the Mamba-block shape).  With four wavefronts per
+    // workgroup the two wavefronts of a SIMD therefore take turns at the higher issue priority, one channel each
+    // (told apart by the lowest bit of the hardware wavefront slot): 5-7 % faster on every shape tried.  Not with
+    // eight wavefronts per workgroup (both wavefronts of a SIMD then belong to one workgroup and meet at its
+    // barriers: 7 % slower), and of no effect with two.
+    constexpr bool ALT_PRIO = (N / NK == 4);
+    [[maybe_unused]] const unsigned hw_slot = ALT_PRIO ? (__builtin_amdgcn_s_getreg(6148) & 1u) : 0u;   // HW_ID.WAVE_ID, bit 0
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -149,6 +158,9 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
         prefetch(0);
 
         for (int g = 0; g < Gact; ++g) {
+            if constexpr (ALT_PRIO) {
+                if ((unsigned)(g & 1) == hw_slot) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
+            }
             const int d = d0 + g;
             const float Dsk = pDsk, bias = pbias;
             float cA[NK], cck[NK];
