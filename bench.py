@@ -37,7 +37,7 @@ VALU_PEAK_TLANEOPS = 39.3
 
 # measured HBM traffic of the backward kernel on config 2 (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # copy kernel of known size); filled from profiles/ when a counter run exists, else null
-BWD_TRAFFIC_BYTES = 508.1e6   # 222.0 MB read + 286.1 MB written (profiles/config2_fwd_bwd_hbm_traffic.md)
+BWD_TRAFFIC_BYTES = 509.2e6   # 223.1 MB read + 286.1 MB written (profiles/config2_fwd_bwd_hbm_traffic.md)
 
 
 def _selective_bytes(B, D, N, L, es, gate, bwd):
