@@ -25,9 +25,9 @@ namespace lrnnx {
 // Two workgroups share a compute unit only if a wavefront stays within 128 vector registers.  With bfloat16 I/O the
 // compiler is held to that (the exact-ZOH variant otherwise takes 133 and runs 19 % slower alone on its CU); with
 // float32 I/O the staged rows are twice as large, 128 registers would mean spills (measured 32 % slower), and one
-// workgroup per CU is accepted.
+// workgroup per CU is accepted (as with N = 32, whose staged tile fills the LDS of a CU).
 template <typename IO, int N, int T, int W, int DISC, bool WANT_Y, bool CKPT>
-__global__ __launch_bounds__(W * 64, sizeof(IO) == 2 ? 4 : 2) void k_ss_fwd(const FwdParams p) {
+__global__ __launch_bounds__(W * 64, (sizeof(IO) == 2 && N <= 16) ? 4 : 2) void k_ss_fwd(const FwdParams p) {
     constexpr int TQ = T / 4;
     constexpr int QS = 256 + (TQ > 1 ? 32 / TQ : 0);   // floats per quarter-plane, padded against bank conflicts on staging
     constexpr int PLANE = TQ * QS;                     // floats per state index n
