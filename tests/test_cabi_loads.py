@@ -72,3 +72,13 @@ def test_null_and_bad_struct_are_rejected_without_a_gpu(lib):
     buf = (ctypes.c_char * 512)()                                       # struct_size = 0
     assert lib.lrnnx_selective_scan_fwd(ctypes.addressof(buf)) == 1
     assert lib.lrnnx_lti_diag_scan(ctypes.addressof(buf)) == 1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU benchmark: --gpus 2 ends with a message and a non-zero status before touching a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
