@@ -9,6 +9,7 @@ library has not been built, importing the entry points raises.
 from __future__ import annotations
 
 import ctypes
+import functools
 import os
 
 import torch
@@ -247,6 +248,38 @@ def _stream():
     return torch.cuda.current_stream().cuda_stream
 
 
+def _device_checked(fn):
+    """Every tensor argument of a compute entry point must live on ONE GPU: the library takes device pointers and
+    has no CPU path, so a host tensor is refused here, before anything is launched.  (Kept cheap: the single-token
+    step is called once per generated token.)"""
+    name = fn.__name__
+    Tensor = torch.Tensor
+
+    def bad(v, dev):
+        if not v.is_cuda:
+            return TypeError(f"{name}: a tensor argument is on {v.device}; the scan library needs GPU tensors")
+        return TypeError(f"{name}: tensors on different devices (cuda:{dev} and {v.device})")
+
+    @functools.wraps(fn)
+    def wrapper(*args, **kwargs):
+        dev = -1
+        for v in args + tuple(kwargs.values()):
+            if isinstance(v, Tensor):
+                d = v.get_device()                    # -1 for a host tensor
+                if d < 0 or (dev >= 0 and d != dev):
+                    raise bad(v, dev)
+                dev = d
+            elif isinstance(v, dict):
+                for t in v.values():
+                    if isinstance(t, Tensor):
+                        d = t.get_device()
+                        if d < 0 or (dev >= 0 and d != dev):
+                            raise bad(t, dev)
+                        dev = d
+        return fn(*args, **kwargs)
+    return wrapper
+
+
 def lrnnx_ckpt_interval() -> int:
     return int(lib().lrnnx_ckpt_interval())
 
@@ -275,6 +308,7 @@ def _bc_groups(Bm, Cm, io, Bsz, D, L, N):
     return G
 
 
+@_device_checked
 def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, x0=None,
                              disc="zoh_s6", delta_softplus=True, path="auto",
                              return_last_state=False, return_ckpt=False, out=None, ckpt_out=None, workspace=None,
@@ -339,6 +373,7 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
     return res[0] if len(res) == 1 else res
 
 
+@_device_checked
 def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, x0=None,
                                      disc="zoh_s6", delta_softplus=True, return_last_state=False, out=None,
                                      return_ckpt=False, ckpt_out=None):
@@ -410,6 +445,7 @@ def _check_complex_maps(A, Bm, Cm, io, Bsz, D, L):
     return N, G
 
 
+@_device_checked
 def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,
                                      ckpt=None, disc="zoh_s6", delta_softplus=True, want_dx0=False, outs=None,
                                      workspace=None):
@@ -475,6 +511,7 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
     return outs
 
 
+@_device_checked
 def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,
                              ckpt=None, disc="zoh_s6", delta_softplus=True, want_dx0=False,
                              outs=None, workspace=None, cu_seqlens=None):
@@ -545,6 +582,7 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
     return outs
 
 
+@_device_checked
 def lrnnx_lti_diag_scan(lam, v, x0=None, return_last_state=False, out=None, workspace=None, path="auto"):
     """x [B,L,P] complex64 of x_k = lam * x_{k-1} + v_k; see lrnnx_lti_args."""
     if v.dtype != torch.complex64 or lam.dtype != torch.complex64:
@@ -574,6 +612,7 @@ def lrnnx_lti_diag_scan(lam, v, x0=None, return_last_state=False, out=None, work
     return (x, x_last) if return_last_state else x
 
 
+@_device_checked
 def lrnnx_lti_diag_scan_bwd(lam, x, gx, x0=None, want_dx0=True, out=None, workspace=None):
     """(dv [B,L,P], dlam [P], dx0 [B,P] or None) from the saved states x and the incoming gradient gx;
     see lrnnx_lti_bwd_args."""
@@ -604,6 +643,7 @@ def lrnnx_lti_diag_scan_bwd(lam, x, gx, x0=None, want_dx0=True, out=None, worksp
     return dv, dlam, dx0
 
 
+@_device_checked
 def lrnnx_diag_scan(a, b, x0=None, return_last_state=False, out=None, workspace=None):
     """x [B,L,P] of x_k = a_k * x_{k-1} + b_k for float32 or complex64 a, b; see lrnnx_diag_scan_args."""
     if a.dtype not in (torch.float32, torch.complex64) or b.dtype != a.dtype:
@@ -633,6 +673,7 @@ def lrnnx_diag_scan(a, b, x0=None, return_last_state=False, out=None, workspace=
     return (x, x_last) if return_last_state else x
 
 
+@_device_checked
 def lrnnx_diag_scan_bwd(a, x, gx, x0=None, want_dx0=True, workspace=None):
     """(da, db [B,L,P], dx0 [B,P] or None) from the forward call's a, saved states x and the incoming gradient gx;
     see lrnnx_diag_scan_bwd_args."""
@@ -672,6 +713,7 @@ def _bd(t, name, io):
     return t.data_ptr(), t.stride(0), t.stride(1)
 
 
+@_device_checked
 def lrnnx_selective_step(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None,
                          disc="zoh_s6", delta_softplus=True, out=None):
     """One token: updates the state x [B,D,N] in place and returns y [B,D]; see lrnnx_ss_step_args."""
@@ -707,6 +749,7 @@ def lrnnx_selective_step(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=
     return y
 
 
+@_device_checked
 def lrnnx_selective_step_complex(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None,
                                  disc="zoh_s6", delta_softplus=True, out=None):
     """One token of the complex-A scan: updates the state x [B,D,N] complex64 in place and returns y [B,D]; see
@@ -754,6 +797,7 @@ def lrnnx_selective_step_complex(x, u, delta, A, Bm, Cm, Dskip=None, delta_bias=
     return y
 
 
+@_device_checked
 def lrnnx_lti_step(lam, x, v):
     """One token of the LTI recurrence: x [B,P] complex64 is updated in place and returned."""
     for name, t in (("lam", lam), ("x", x), ("v", v)):

@@ -82,3 +82,22 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0
     assert "ONE GPU" in (r.stdout + r.stderr)
+
+
+def test_binding_refuses_host_tensors():
+    """The Python binding passes device pointers to the library; a CPU tensor is refused before any launch."""
+    torch = pytest.importorskip("torch")
+    from paper_2602_08810_amd import api
+    u = torch.zeros(1, 2, 8)
+    A = -torch.ones(2, 4)
+    Bm = torch.zeros(1, 8, 4)
+    with pytest.raises(TypeError, match="GPU tensors"):
+        api.lrnnx_selective_scan_fwd(u, u, A, Bm, Bm)
+    with pytest.raises(TypeError, match="GPU tensors"):
+        api.lrnnx_selective_scan_bwd(u, u, A, Bm, Bm, dy=u)
+    lam = torch.zeros(4, dtype=torch.complex64)
+    v = torch.zeros(1, 8, 4, dtype=torch.complex64)
+    with pytest.raises(TypeError, match="GPU tensors"):
+        api.lrnnx_lti_diag_scan(lam, v)
+    with pytest.raises(TypeError, match="GPU tensors"):
+        api.lrnnx_selective_step(torch.zeros(1, 2, 4), u[:, :, 0], u[:, :, 0], A, Bm[:, 0], Bm[:, 0])
