@@ -22,12 +22,13 @@
 
 namespace lrnnx {
 
-// Two workgroups share a compute unit only if a wavefront stays within 128 vector registers.  With bfloat16 I/O the
-// compiler is held to that (the exact-ZOH variant otherwise takes 133 and runs 19 % slower alone on its CU); with
-// float32 I/O the staged rows are twice as large, 128 registers would mean spills (measured 32 % slower), and one
-// workgroup per CU is accepted (as with N = 32, whose staged tile fills the LDS of a CU).
+// Two workgroups share a compute unit only if a wavefront stays within 128 vector registers, and the second one is
+// worth 20-25 % (measured with a variant that needed 146).  The compiler is therefore held to 128 (the exact-ZOH
+// variant otherwise takes 133).  With float32 I/O the rows of Bm/Cm fetched one tile ahead would alone cost 2 N
+// registers, so that prefetch is for bfloat16 only (float32: 196 -> 171 us on the Mamba-block shape).  N = 32 fills
+// the LDS of a CU with one workgroup's tile and is left alone.
 template <typename IO, int N, int T, int W, int DISC, bool WANT_Y, bool CKPT>
-__global__ __launch_bounds__(W * 64, (sizeof(IO) == 2 && N <= 16) ? 4 : 2) void k_ss_fwd(const FwdParams p) {
+__global__ __launch_bounds__(W * 64, (N <= 16) ? 4 : 2) void k_ss_fwd(const FwdParams p) {
     constexpr int TQ = T / 4;
     constexpr int QS = 256 + (TQ > 1 ? 32 / TQ : 0);   // floats per quarter-plane, padded against bank conflicts on staging
     constexpr int PLANE = TQ * QS;                     // floats per state index n
@@ -96,13 +97,16 @@ __global__ __launch_bounds__(W * 64, (sizeof(IO) == 2 && N <= 16) ? 4 : 2) void 
     if (active && tile0 < tile1) fetch(tile0);
     // likewise the row of Bm and Cm this thread stages (one step of the tile per thread when the tile has as many
     // steps as the workgroup has threads); rows past the sequence read as zero
-    RawFew<IO, N> r_B, r_C;
+    constexpr bool PREFETCH_MAPS = TILE == W * 64 && sizeof(IO) == 2;   // float32 rows would cost 2 N registers
+    RawFew<IO, PREFETCH_MAPS ? N : 1> r_B, r_C;
     auto fetch_maps = [&](int64_t tile) {
         const int64_t l = tile * TILE + threadIdx.x;
-        load_few_raw<IO, N>(Bm + l * N, (int64_t)0, l < L ? (int64_t)N : (int64_t)0, true, r_B);
-        load_few_raw<IO, N>(Cm + l * N, (int64_t)0, l < L ? (int64_t)N : (int64_t)0, true, r_C);
+        if constexpr (PREFETCH_MAPS) {
+            load_few_raw<IO, N>(Bm + l * N, (int64_t)0, l < L ? (int64_t)N : (int64_t)0, true, r_B);
+            load_few_raw<IO, N>(Cm + l * N, (int64_t)0, l < L ? (int64_t)N : (int64_t)0, true, r_C);
+        }
     };
-    if constexpr (TILE == W * 64) { if (tile0 < tile1) fetch_maps(tile0); }
+    if constexpr (PREFETCH_MAPS) { if (tile0 < tile1) fetch_maps(tile0); }
 
     for (int64_t tile = tile0; tile < tile1; ++tile) {
         const int64_t l0 = tile * TILE;
@@ -111,11 +115,11 @@ __global__ __launch_bounds__(W * 64, (sizeof(IO) == 2 && N <= 16) ? 4 : 2) void 
         // ---- stage the Bm/Cm tile (all wavefronts), fp32, layout [n][t/4][lane][t%4]; the rows were fetched (raw) one
         // tile ahead
         __syncthreads();
-        if constexpr (TILE == W * 64) {
+        if constexpr (PREFETCH_MAPS) {
             const int r = threadIdx.x;
             float bv[N], cv[N];
-            unpack_few<IO, N>(r_B, bv);
-            unpack_few<IO, N>(r_C, cv);
+            unpack_few<IO, PREFETCH_MAPS ? N : 1>(r_B, bv);
+            unpack_few<IO, PREFETCH_MAPS ? N : 1>(r_C, cv);
             const int off = ((r % T) / 4) * QS + (r / T) * 4 + (r % 4);
 #pragma unroll
             for (int k = 0; k < N; ++k) { sB[k * PLANE + off] = bv[k]; sC[k * PLANE + off] = cv[k]; }
