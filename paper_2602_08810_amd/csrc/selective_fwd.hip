@@ -22,8 +22,9 @@
 
 namespace lrnnx {
 
-// Two workgroups share a compute unit only if a wavefront stays within 128 vector registers, and the second one is
-// worth 20-25 % (measured with a variant that needed 146).  The compiler is therefore held to 128 (the exact-ZOH
+// Two workgroups share a compute unit only if a wavefront stays within 128 vector registers, and with short rows
+// (many workgroups per CU, one after the other) the second one is worth 20-25 %: it covers the other's start-up
+// and drain (measured with a variant that needed 146 registers).  The compiler is therefore held to 128 (the exact-ZOH
 // variant otherwise takes 133).  With float32 I/O the rows of Bm/Cm fetched one tile ahead would alone cost 2 N
 // registers, so that prefetch is for bfloat16 only (float32: 196 -> 171 us on the Mamba-block shape).  N = 32 fills
 // the LDS of a CU with one workgroup's tile and is left alone.
