@@ -101,3 +101,40 @@ def test_binding_refuses_host_tensors():
         api.lrnnx_lti_diag_scan(lam, v)
     with pytest.raises(TypeError, match="GPU tensors"):
         api.lrnnx_selective_step(torch.zeros(1, 2, 4), u[:, :, 0], u[:, :, 0], A, Bm[:, 0], Bm[:, 0])
+
+
+def _fwd_args(**over):
+    """A syntactically valid forward argument block with fake (aligned, non-null, never dereferenced) pointers."""
+    from paper_2602_08810_amd import api
+    a = api.FwdArgs()
+    a.struct_size = ctypes.sizeof(api.FwdArgs)
+    a.B, a.D, a.N, a.L = 2, 8, 16, 100
+    a.io_dtype, a.disc, a.delta_softplus, a.path = api.BF16, 0, 1, 0
+    fake = 0x10000
+    a.u = a.delta = a.A = a.Bm = a.Cm = a.y = fake
+    a.u_stride_b = a.delta_stride_b = a.y_stride_b = 800
+    a.u_stride_d = a.delta_stride_d = a.y_stride_d = 100
+    for k, v in over.items():
+        setattr(a, k, v)
+    return a
+
+
+def test_host_side_validation_of_the_forward_call(lib):
+    """Every refusal below is decided on the host, before any HIP call: status codes as documented in lrnnx.h.
+    The pointers are fake, so the test only runs where no GPU could ever be handed them."""
+    torch = pytest.importorskip("torch")
+    if torch.cuda.device_count() > 0:
+        pytest.skip("host-only test: not run on a machine with a GPU")
+    from paper_2602_08810_amd import api
+    lib.lrnnx_selective_scan_fwd.argtypes = [ctypes.POINTER(api.FwdArgs)]
+    call = lambda **over: lib.lrnnx_selective_scan_fwd(ctypes.byref(_fwd_args(**over)))
+    assert call(B=65536) == 2                      # more batch entries than a launch grid holds: unsupported
+    assert call(N=3) == 2 and call(N=64) == 2      # state sizes without a kernel
+    assert call(L=0) == 1 and call(B=0) == 1 and call(D=0) == 1
+    assert call(io_dtype=7) == 1 and call(disc=4) == 1 and call(path=9) == 1
+    assert call(Bm=0x10004) == 1                   # maps must be 16-byte aligned
+    assert call(u=0) == 1 and call(y=0) == 1       # required pointers
+    assert call(u_stride_d=-1) == 1                # negative stride
+    assert call(y_stride_d=50) == 1                # output rows would overlap
+    assert call(bc_groups=3) == 1                  # D = 8 is not a multiple of 3 groups
+    assert call(path=2) == 3                       # the chunk-carry path needs a workspace
