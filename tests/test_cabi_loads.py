@@ -138,3 +138,49 @@ def test_host_side_validation_of_the_forward_call(lib):
     assert call(y_stride_d=50) == 1                # output rows would overlap
     assert call(bc_groups=3) == 1                  # D = 8 is not a multiple of 3 groups
     assert call(path=2) == 3                       # the chunk-carry path needs a workspace
+
+
+def test_host_side_validation_of_the_backward_and_lti_calls(lib):
+    """As above for lrnnx_selective_scan_bwd, lrnnx_lti_diag_scan and lrnnx_diag_scan (fake pointers, no GPU)."""
+    torch = pytest.importorskip("torch")
+    if torch.cuda.device_count() > 0:
+        pytest.skip("host-only test: not run on a machine with a GPU")
+    from paper_2602_08810_amd import api
+    fake = 0x10000
+
+    def bwd(**over):
+        a = api.BwdArgs()
+        a.struct_size = ctypes.sizeof(api.BwdArgs)
+        a.B, a.D, a.N, a.L = 2, 8, 16, 100
+        a.io_dtype, a.disc, a.delta_softplus = api.BF16, 0, 1
+        for f in ("u", "delta", "A", "Bm", "Cm", "dy", "du", "ddelta", "dA", "dBm", "dCm", "ckpt"):
+            setattr(a, f, fake)
+        for f in ("u", "delta", "dy", "du", "ddelta"):
+            setattr(a, f + "_stride_b", 800)
+            setattr(a, f + "_stride_d", 100)
+        for k, v in over.items():
+            setattr(a, k, v)
+        return lib.lrnnx_selective_scan_bwd(ctypes.byref(a))
+    lib.lrnnx_selective_scan_bwd.argtypes = [ctypes.POINTER(api.BwdArgs)]
+    assert bwd(ckpt=0) == 3                                   # no checkpoints and no workspace to recompute them into
+    assert bwd(ckpt=0, workspace=fake, workspace_bytes=16) == 3
+    assert bwd(dz=fake) == 1                                  # dz without z
+    assert bwd(dD=fake) == 1 and bwd(dbias=fake) == 1         # dD without Dskip, dbias without delta_bias
+    assert bwd(dBm=0x10008) == 1 and bwd(du=0) == 1 and bwd(dA=0) == 1
+    assert bwd(du_stride_d=99) == 1 and bwd(dy_stride_b=-1) == 1
+    assert bwd(N=5) == 2 and bwd(B=70000) == 2
+    assert bwd(bc_groups=3) == 1 and bwd(bc_groups=-1) == 1
+
+    def lti(**over):
+        a = api.LtiArgs()
+        a.struct_size = ctypes.sizeof(api.LtiArgs)
+        a.B, a.P, a.L = 2, 64, 100
+        a.lambda_ = a.v = a.x = fake
+        for k, v in over.items():
+            setattr(a, k, v)
+        return lib.lrnnx_lti_diag_scan(ctypes.byref(a))
+    lib.lrnnx_lti_diag_scan.argtypes = [ctypes.POINTER(api.LtiArgs)]
+    assert lti(P=0) == 1 and lti(L=0) == 1 and lti(B=0) == 1
+    assert lti(v=0x10004) == 1 and lti(x=0) == 1 and lti(path=7) == 1
+    assert lti(B=70000) == 2
+    assert lti() == 3                                         # every path of this call needs its workspace
