@@ -288,6 +288,67 @@ def selective_scan_bwd_packed(u, delta, A, Bm, Cm, dy, cu_seqlens, Dskip=None, d
     return out
 
 
+def _cmaps4(M):
+    """Packed complex maps [L,N] or [G,L,N] as [1,G,L,N]."""
+    M = _c128(M)
+    return M[None, None] if M.ndim == 2 else M[None]
+
+
+def selective_scan_fwd_complex_packed(u, delta, A, Bm, Cm, cu_seqlens, Dskip=None, delta_bias=None, z=None, x0=None,
+                                      disc="zoh_s6", delta_softplus=True):
+    """The packed variable-length batch of selective_scan_fwd_packed with a complex diagonal A: by definition the
+    complex scan of every sequence on its own slice.  u, delta, z: [D,L]; Bm, Cm: complex [L,N] or [G,L,N];
+    x0: complex [S,D,N].  Returns y [D,L] (zero outside every sequence) and x_last [S,D,N] complex128."""
+    u, delta = _f64(u), _f64(delta)
+    D, L = u.shape
+    Bm4, Cm4 = _cmaps4(Bm), _cmaps4(Cm)
+    sl = _packed_slices(cu_seqlens, L)
+    y = np.zeros((D, L))
+    x_last = np.zeros((len(sl), D, np.asarray(A).shape[1]), dtype=np.complex128)
+    for s, (o, e) in enumerate(sl):
+        ys, xs = selective_scan_fwd_complex(u[None, :, o:e], delta[None, :, o:e], A, Bm4[:, :, o:e], Cm4[:, :, o:e],
+                                            Dskip=Dskip, delta_bias=delta_bias,
+                                            z=None if z is None else np.asarray(z)[None, :, o:e],
+                                            x0=None if x0 is None else np.asarray(x0)[s:s + 1], disc=disc,
+                                            delta_softplus=delta_softplus)
+        y[:, o:e], x_last[s] = ys[0], xs[0]
+    return y, x_last
+
+
+def selective_scan_bwd_complex_packed(u, delta, A, Bm, Cm, dy, cu_seqlens, Dskip=None, delta_bias=None, z=None,
+                                      x0=None, disc="zoh_s6", delta_softplus=True):
+    """Gradients of sum(dy * y) for the packed complex batch above: per-step gradients are those of each sequence on
+    its slice, parameter gradients (dA, dD, dbias) add up over the sequences; dBm, dCm have the shape of Bm."""
+    u, delta, dy = _f64(u), _f64(delta), _f64(dy)
+    D, L = u.shape
+    Bm4, Cm4 = _cmaps4(Bm), _cmaps4(Cm)
+    sl = _packed_slices(cu_seqlens, L)
+    N = np.asarray(A).shape[1]
+    c128 = np.complex128
+    out = {"du": np.zeros((D, L)), "ddelta": np.zeros((D, L)), "dz": None if z is None else np.zeros((D, L)),
+           "dA": np.zeros((D, N), dtype=c128), "dBm": np.zeros(Bm4.shape[1:], dtype=c128),
+           "dCm": np.zeros(Cm4.shape[1:], dtype=c128),
+           "dD": None if Dskip is None else np.zeros(D), "dbias": None if delta_bias is None else np.zeros(D),
+           "dx0": np.zeros((len(sl), D, N), dtype=c128)}
+    for s, (o, e) in enumerate(sl):
+        g = selective_scan_bwd_complex(u[None, :, o:e], delta[None, :, o:e], A, Bm4[:, :, o:e], Cm4[:, :, o:e],
+                                       dy[None, :, o:e], Dskip=Dskip, delta_bias=delta_bias,
+                                       z=None if z is None else np.asarray(z)[None, :, o:e],
+                                       x0=None if x0 is None else np.asarray(x0)[s:s + 1], disc=disc,
+                                       delta_softplus=delta_softplus)
+        for k in ("du", "ddelta", "dz"):
+            if out[k] is not None:
+                out[k][:, o:e] = g[k][0]
+        out["dBm"][:, o:e], out["dCm"][:, o:e] = g["dBm"][0], g["dCm"][0]
+        for k in ("dA", "dD", "dbias"):
+            if out[k] is not None:
+                out[k] += g[k]
+        out["dx0"][s] = g["dx0"][0]
+    if np.asarray(Bm).ndim == 2:
+        out["dBm"], out["dCm"] = out["dBm"][0], out["dCm"][0]
+    return out
+
+
 def diag_scan(a, b, x0=None):
     """x [B,L,P] of x_k = a_k * x_{k-1} + b_k for caller-supplied coefficients; real (float64) or complex (complex128)
     according to the dtype of the inputs."""

@@ -988,3 +988,82 @@ def test_complex_grouped_equals_one_ungrouped_problem_per_group(oracle):
             np.testing.assert_allclose(g[k][ds], gq[k], rtol=1e-13, atol=1e-15)
         for k in ("dBm", "dCm"):
             np.testing.assert_allclose(g[k][:, grp], gq[k], rtol=1e-13, atol=1e-15)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Packed variable-length batches of the complex-A scan.
+# ---------------------------------------------------------------------------------------------------------------
+def _packed_complex_problem(seed, D=3, N=2, L=23, cu=(0, 5, 6, 14, 23), G=None):
+    rng = np.random.default_rng(seed)
+    c = lambda *s: rng.standard_normal(s) + 1j * rng.standard_normal(s)
+    S = len(cu) - 1
+    bc = (L, N) if G is None else (G, L, N)
+    p = dict(u=rng.standard_normal((D, L)), delta=rng.standard_normal((D, L)),
+             A=-np.exp(rng.uniform(-1, 1, (D, N))) + 1j * rng.uniform(-3, 3, (D, N)),
+             Bm=c(*bc), Cm=c(*bc), Dskip=rng.standard_normal(D), delta_bias=rng.uniform(-2, 0, D),
+             z=rng.standard_normal((D, L)), x0=c(S, D, N))
+    return p, np.array(cu), rng.standard_normal((D, L))
+
+
+@pytest.mark.parametrize("disc", DISCS)
+def test_packed_complex_states_equal_one_long_scan_zeroed_at_every_boundary(oracle, disc):
+    """An independent route: ONE complex recurrence over the whole packed axis (the caller-coefficient scan) whose
+    multiplier is zeroed at the first step of every sequence, that sequence's x0 entering through b."""
+    p, cu, _ = _packed_complex_problem(151)
+    D, L = p["u"].shape
+    N = p["A"].shape[1]
+    dt = np.logaddexp(0.0, p["delta"] + p["delta_bias"][:, None])                       # [D,L]
+    a, g = _disc_py_c(disc, dt.T[:, :, None], p["A"][None])                             # [L,D,N]
+    a = np.array(np.broadcast_to(a, (L, D, N)))
+    b = np.broadcast_to(g, (L, D, N)) * p["u"].T[:, :, None] * p["Bm"][:, None, :]
+    for s, o in enumerate(cu[:-1]):
+        if o < L and cu[s + 1] > o:
+            b[o] += a[o] * p["x0"][s]
+            a[o] = 0.0
+    x = oracle.diag_scan(a.reshape(1, L, D * N), b.reshape(1, L, D * N)).reshape(L, D, N)
+    ypre = np.einsum("ln,ldn->dl", p["Cm"], x).real + p["Dskip"][:, None] * p["u"]
+    yref = ypre * p["z"] / (1 + np.exp(-p["z"]))
+    y, x_last = oracle.selective_scan_fwd_complex_packed(cu_seqlens=cu, **p, disc=disc)
+    np.testing.assert_allclose(y, yref, rtol=1e-11, atol=1e-12)
+    for s in range(len(cu) - 1):
+        np.testing.assert_allclose(x_last[s], x[cu[s + 1] - 1], rtol=1e-11)
+
+
+def test_packed_complex_gaps_empty_sequences_and_isolation(oracle):
+    cu = np.array([3, 9, 9, 20])
+    p, _, dy = _packed_complex_problem(152, cu=(3, 9, 9, 20))
+    y, xl = oracle.selective_scan_fwd_complex_packed(cu_seqlens=cu, **p)
+    g = oracle.selective_scan_bwd_complex_packed(dy=dy, cu_seqlens=cu, **p)
+    assert np.all(y[:, :3] == 0) and np.all(y[:, 20:] == 0)
+    np.testing.assert_array_equal(xl[1], p["x0"][1])       # an empty sequence hands its x0 through
+    assert np.all(g["dx0"][1] == 0) and np.all(g["dBm"][:3] == 0) and np.all(g["du"][:, 20:] == 0)
+    q = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in p.items()}
+    q["u"][:, 9:20] += 1.0                                 # disturb the last sequence only
+    q["x0"][2] *= 2.0
+    y2, xl2 = oracle.selective_scan_fwd_complex_packed(cu_seqlens=cu, **q)
+    g2 = oracle.selective_scan_bwd_complex_packed(dy=dy, cu_seqlens=cu, **q)
+    assert np.array_equal(y[:, :9], y2[:, :9]) and not np.allclose(y[:, 9:20], y2[:, 9:20])
+    assert np.array_equal(xl[:2], xl2[:2])
+    for k in ("du", "ddelta", "dz"):
+        assert np.array_equal(g[k][:, :9], g2[k][:, :9]), k
+    assert np.array_equal(g["dBm"][:9], g2["dBm"][:9]) and np.array_equal(g["dCm"][:9], g2["dCm"][:9])
+
+
+def test_packed_complex_backward_by_finite_differences_with_grouped_maps(oracle):
+    p, cu, dy = _packed_complex_problem(153, D=4, N=2, L=9, cu=(0, 4, 9), G=2)
+    g = oracle.selective_scan_bwd_complex_packed(dy=dy, cu_seqlens=cu, **p, disc="zoh")
+    loss = lambda q: float((oracle.selective_scan_fwd_complex_packed(cu_seqlens=cu, **q, disc="zoh")[0] * dy).sum())
+    h = 1e-6
+    names = {"u": "du", "delta": "ddelta", "A": "dA", "Bm": "dBm", "Cm": "dCm", "Dskip": "dD", "delta_bias": "dbias",
+             "z": "dz", "x0": "dx0"}
+    for k, gk in names.items():
+        for idx in np.ndindex(p[k].shape):
+            parts = (1.0, 1j) if np.iscomplexobj(p[k]) else (1.0,)
+            num = 0.0
+            for part in parts:
+                q = {n: (v.copy() if isinstance(v, np.ndarray) else v) for n, v in p.items()}
+                q[k][idx] += h * part
+                up = loss(q)
+                q[k][idx] -= 2 * h * part
+                num = num + part * (up - loss(q)) / (2 * h)      # dLoss/dRe + i dLoss/dIm
+            assert abs(num - g[gk][idx]) <= 2e-6 * abs(g[gk][idx]) + 2e-7, (k, idx)
