@@ -141,7 +141,10 @@ int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *args);
  * +-256 * 2 pi (the range of the hardware sine and cosine).  One pass over the sequence.
  * ckpt (optional): [B,D,ceil(L/lrnnx_ckpt_interval()),N] complex float pairs, the state entering every
  * lrnnx_ckpt_interval()-th step, for lrnnx_selective_scan_bwd_complex.  y may be NULL when only the checkpoints
- * (and x_last) are wanted.                                                                                     */
+ * (and x_last) are wanted.
+ * Packed variable-length sequences (cu_seqlens != NULL) work as in lrnnx_selective_scan_fwd: u, delta, z, y are
+ * [D,L], Bm and Cm [G,L,N], x0 and x_last [B,D,N], ckpt [D, lrnnx_packed_ckpt_slots(L,B), N]; boundaries are
+ * clamped to [0,L] on the device.                                                                              */
 typedef struct lrnnx_ss_fwd_complex_args {
     size_t struct_size;
     int32_t B, D, N;
@@ -163,6 +166,8 @@ typedef struct lrnnx_ss_fwd_complex_args {
     int32_t bc_groups;  /* number of Bm/Cm groups G (maps [B,G,L,N], channel d reads group d / (D/G), D a multiple of
                            G); 0 or 1: none; callers built against a shorter struct get 1 */
     int32_t reserved2;
+    const int64_t *cu_seqlens;   /* packed variable-length mode, device memory [B+1], or NULL; callers built against a
+                                    shorter struct get NULL */
 } lrnnx_ss_fwd_complex_args;
 
 int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *args);
@@ -206,6 +211,10 @@ typedef struct lrnnx_ss_bwd_complex_args {
     void *dx0;                                                     /* [B,D,N] complex float, out or NULL */
     void *workspace;    size_t workspace_bytes;
     void *stream;
+    const int64_t *cu_seqlens;   /* packed mode as in the forward call (then du, ddelta, dz are [D,L], dBm, dCm
+                                    [G,L,N], ckpt [D, lrnnx_packed_ckpt_slots(L,B), N] and the workspace that replaces
+                                    it D * lrnnx_packed_ckpt_slots(L,B) * N float pairs); callers built against the
+                                    shorter struct get NULL */
 } lrnnx_ss_bwd_complex_args;
 
 int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *args);

@@ -53,6 +53,7 @@ class FwdComplexArgs(ctypes.Structure):
         ("x0", _vp),
         ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
         ("x_last", _vp), ("stream", _vp), ("ckpt", _vp), ("bc_groups", _i32), ("reserved2", _i32),
+        ("cu_seqlens", _vp),
     ]
 
 
@@ -71,7 +72,7 @@ class BwdComplexArgs(ctypes.Structure):
         ("ddelta", _vp), ("ddelta_stride_b", _i64), ("ddelta_stride_d", _i64),
         ("dz", _vp), ("dz_stride_b", _i64), ("dz_stride_d", _i64),
         ("dA", _vp), ("dBm", _vp), ("dCm", _vp), ("dD", _vp), ("dbias", _vp), ("dx0", _vp),
-        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
+        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp), ("cu_seqlens", _vp),
     ]
 
 
@@ -376,19 +377,31 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
 @_device_checked
 def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, x0=None,
                                      disc="zoh_s6", delta_softplus=True, return_last_state=False, out=None,
-                                     return_ckpt=False, ckpt_out=None):
+                                     return_ckpt=False, ckpt_out=None, cu_seqlens=None):
     """y (and optionally x_last, ckpt) of the forward selective scan with complex A, Bm, Cm; see
     lrnnx_ss_fwd_complex_args.  `ckpt_out`: a preallocated checkpoint array to fill (implies return_ckpt).
 
     A [D,N] complex64.  Bm, Cm [B,L,N]: complex64 for float32 I/O; for bfloat16 I/O a bfloat16 tensor [B,L,N,2]
-    of (re, im) pairs.  x0, x_last [B,D,N] complex64; ckpt [B,D,ceil(L/interval),N] complex64."""
+    of (re, im) pairs.  x0, x_last [B,D,N] complex64; ckpt [B,D,ceil(L/interval),N] complex64.
+    With `cu_seqlens` (int64 [S+1] on the device) the call is in packed variable-length mode: u, delta, z, y are
+    [D,L], Bm and Cm [L,N] or [G,L,N] (plus the pair axis for bfloat16), x0 and x_last [S,D,N], ckpt
+    [D, L // interval + S, N]."""
     io = u.dtype
-    Bsz, D, L = u.shape
-    N, G = _check_complex_maps(A, Bm, Cm, io, Bsz, D, L)
+    packed = cu_seqlens is not None
+    if packed:
+        Bsz = _check_cu(cu_seqlens)
+        u, delta, z, out = (None if t is None else t.unsqueeze(0) for t in (u, delta, z, out))
+        Bm, Cm = Bm.unsqueeze(0), Cm.unsqueeze(0)
+    Bio = 1 if packed else u.shape[0]                   # leading dimension of the I/O tensors and of the maps
+    if not packed:
+        Bsz = Bio
+    _, D, L = u.shape
+    N, G = _check_complex_maps(A, Bm, Cm, io, Bio, D, L)
     a = FwdComplexArgs()
     a.struct_size = ctypes.sizeof(FwdComplexArgs)
     a.B, a.D, a.N, a.L = Bsz, D, N, L
     a.bc_groups = G
+    a.cu_seqlens = _ptr(cu_seqlens)
     a.io_dtype = _io_dtype(u)
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
     a.delta_softplus = int(bool(delta_softplus))
@@ -402,13 +415,14 @@ def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias
         if x0.dtype != torch.complex64 or not x0.is_contiguous() or tuple(x0.shape) != (Bsz, D, N):
             raise ValueError("x0: expected contiguous complex64 [B,D,N]")
         a.x0 = x0.data_ptr()
-    y = out if out is not None else torch.empty((Bsz, D, L), dtype=io, device=u.device)
+    y = out if out is not None else torch.empty((Bio, D, L), dtype=io, device=u.device)
     a.y, a.y_stride_b, a.y_stride_d = _bdl(y, "y", io)
     x_last = torch.empty((Bsz, D, N), dtype=torch.complex64, device=u.device) if return_last_state else None
     a.x_last = _ptr(x_last)
     ckpt = None
     if return_ckpt or ckpt_out is not None:
-        shape = (Bsz, D, -(-L // lrnnx_ckpt_interval()), N)
+        I = lrnnx_ckpt_interval()
+        shape = (D, L // I + Bsz, N) if packed else (Bsz, D, -(-L // I), N)
         ckpt = ckpt_out if ckpt_out is not None else torch.empty(shape, dtype=torch.complex64, device=u.device)
         if ckpt.dtype != torch.complex64 or not ckpt.is_contiguous() or tuple(ckpt.shape) != shape:
             raise ValueError(f"ckpt_out: expected contiguous complex64 {shape}")
@@ -416,7 +430,7 @@ def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias
         return_ckpt = True
     a.stream = _stream()
     _check(lib().lrnnx_selective_scan_fwd_complex(ctypes.byref(a)))
-    res = (y,) + ((x_last,) if return_last_state else ()) + ((ckpt,) if return_ckpt else ())
+    res = (y[0] if packed else y,) + ((x_last,) if return_last_state else ()) + ((ckpt,) if return_ckpt else ())
     return res if len(res) > 1 else y
 
 
@@ -448,15 +462,27 @@ def _check_complex_maps(A, Bm, Cm, io, Bsz, D, L):
 @_device_checked
 def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,
                                      ckpt=None, disc="zoh_s6", delta_softplus=True, want_dx0=False, outs=None,
-                                     workspace=None):
+                                     workspace=None, cu_seqlens=None):
     """Gradients of sum(dy*y) of the complex-A selective scan as a dict; see lrnnx_ss_bwd_complex_args.
     dA [D,N], dBm, dCm [B,L,N], dx0 [B,D,N] are complex64 (dLoss/dRe + i dLoss/dIm); du, ddelta, dz in the I/O
-    type; dD, dbias float32.  `ckpt`: the checkpoints a forward call returned (else they are recomputed)."""
+    type; dD, dbias float32.  `ckpt`: the checkpoints a forward call returned (else they are recomputed).
+    `cu_seqlens`: packed variable-length mode as in the forward call (du, ddelta, dz are [D,L]; dBm, dCm [L,N] or
+    [G,L,N]; dx0 [S,D,N])."""
     io = u.dtype
-    Bsz, D, L = u.shape
-    N, G = _check_complex_maps(A, Bm, Cm, io, Bsz, D, L)
+    packed = cu_seqlens is not None
+    if packed:
+        Bsz = _check_cu(cu_seqlens)
+        u, delta, z, dy = (None if t is None else t.unsqueeze(0) for t in (u, delta, z, dy))
+        Bm, Cm = Bm.unsqueeze(0), Cm.unsqueeze(0)
+    Bio = 1 if packed else u.shape[0]
+    if not packed:
+        Bsz = Bio
+    _, D, L = u.shape
+    N, G = _check_complex_maps(A, Bm, Cm, io, Bio, D, L)
     dev = u.device
     outs = dict(outs or {})
+    if packed:                                          # caller-supplied outputs are in the packed shapes
+        outs = {k: (v.unsqueeze(0) if k in ("du", "ddelta", "dz", "dBm", "dCm") else v) for k, v in outs.items()}
 
     def new(name, shape, dtype):
         if name not in outs:
@@ -470,6 +496,7 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
     a.struct_size = ctypes.sizeof(BwdComplexArgs)
     a.B, a.D, a.N, a.L = Bsz, D, N, L
     a.bc_groups = G
+    a.cu_seqlens = _ptr(cu_seqlens)
     a.io_dtype = _io_dtype(u)
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
     a.delta_softplus = int(bool(delta_softplus))
@@ -480,19 +507,20 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
     a.A, a.Bm, a.Cm = A.data_ptr(), Bm.data_ptr(), Cm.data_ptr()
     a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
     a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
-    nck = -(-L // lrnnx_ckpt_interval())
-    for name, t, shape in (("x0", x0, (Bsz, D, N)), ("ckpt", ckpt, (Bsz, D, nck, N))):
+    I = lrnnx_ckpt_interval()
+    ck_shape = (D, L // I + Bsz, N) if packed else (Bsz, D, -(-L // I), N)
+    for name, t, shape in (("x0", x0, (Bsz, D, N)), ("ckpt", ckpt, ck_shape)):
         if t is not None:
             if t.dtype != torch.complex64 or not t.is_contiguous() or tuple(t.shape) != shape:
                 raise ValueError(f"{name}: expected contiguous complex64 {shape}")
             setattr(a, name, t.data_ptr())
-    a.du, a.du_stride_b, a.du_stride_d = _bdl(new("du", (Bsz, D, L), io), "du", io)
-    a.ddelta, a.ddelta_stride_b, a.ddelta_stride_d = _bdl(new("ddelta", (Bsz, D, L), io), "ddelta", io)
+    a.du, a.du_stride_b, a.du_stride_d = _bdl(new("du", (Bio, D, L), io), "du", io)
+    a.ddelta, a.ddelta_stride_b, a.ddelta_stride_d = _bdl(new("ddelta", (Bio, D, L), io), "ddelta", io)
     if z is not None:
-        a.dz, a.dz_stride_b, a.dz_stride_d = _bdl(new("dz", (Bsz, D, L), io), "dz", io)
+        a.dz, a.dz_stride_b, a.dz_stride_d = _bdl(new("dz", (Bio, D, L), io), "dz", io)
     c64 = torch.complex64
     a.dA = new("dA", (D, N), c64).data_ptr()
-    map_shape = (Bsz, L, N) if (Bm.dim() == 3 + (io == torch.bfloat16)) else (Bsz, G, L, N)
+    map_shape = (Bio, L, N) if (Bm.dim() == 3 + (io == torch.bfloat16)) else (Bio, G, L, N)
     a.dBm = new("dBm", map_shape, c64).data_ptr()
     a.dCm = new("dCm", map_shape, c64).data_ptr()
     if Dskip is not None:
@@ -502,12 +530,15 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
     if want_dx0:
         a.dx0 = new("dx0", (Bsz, D, N), c64).data_ptr()
     if workspace is None and ckpt is None:
-        nbytes = lrnnx_workspace_bytes(WS_BWD_COMPLEX, Bsz, D, N, L, a.io_dtype)
+        nbytes = (D * (L // I + Bsz) * N * 8 if packed
+                  else lrnnx_workspace_bytes(WS_BWD_COMPLEX, Bsz, D, N, L, a.io_dtype))
         workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
     if workspace is not None:
         a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
     a.stream = _stream()
     _check(lib().lrnnx_selective_scan_bwd_complex(ctypes.byref(a)))
+    if packed:
+        outs = {k: (v[0] if k in ("du", "ddelta", "dz", "dBm", "dCm") else v) for k, v in outs.items()}
     return outs
 
 

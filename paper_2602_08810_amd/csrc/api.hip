@@ -126,7 +126,7 @@ extern "C" {
 
 int64_t lrnnx_ckpt_interval(void) { return kCkptInterval; }
 int64_t lrnnx_packed_ckpt_slots(int64_t L, int64_t B) { return (L < 0 || B < 0) ? 0 : L / kCkptInterval + B; }
-int lrnnx_version(void) { return 133; }   // major * 100 + minor; bumped whenever an entry point or a struct field is added
+int lrnnx_version(void) { return 134; }   // major * 100 + minor; bumped whenever an entry point or a struct field is added
 
 const char *lrnnx_status_string(int status) {
     switch (status) {
@@ -246,10 +246,12 @@ int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *a) {
     constexpr size_t kSizeCkpt = offsetof(lrnnx_ss_fwd_complex_args, bc_groups);   // ... and before `bc_groups` was
     if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
     void *ckpt = a->struct_size >= kSizeCkpt ? a->ckpt : nullptr;
-    const bool has_groups = a->struct_size >= sizeof(lrnnx_ss_fwd_complex_args);
+    constexpr size_t kSizeGroups = offsetof(lrnnx_ss_fwd_complex_args, cu_seqlens);   // ... and before `cu_seqlens`
+    const bool has_groups = a->struct_size >= kSizeGroups;
     if (has_groups && a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
     const int bcg = (has_groups && a->bc_groups > 1) ? a->bc_groups : 1;
-    if (a->D % bcg) return LRNNX_ERR_INVALID_ARG;
+    const int64_t *cu = a->struct_size >= sizeof(lrnnx_ss_fwd_complex_args) ? a->cu_seqlens : nullptr;
+    if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
@@ -261,6 +263,7 @@ int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *a) {
         return LRNNX_ERR_INVALID_ARG;
     if (!supported_n_complex(a->N)) return LRNNX_ERR_UNSUPPORTED;
     if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
+    if (a->D % bcg) return LRNNX_ERR_INVALID_ARG;
     if (!aligned16(a->Bm) || !aligned16(a->Cm)) return LRNNX_ERR_INVALID_ARG;
     for (const void *q : {a->A, a->x0, (const void *)a->x_last})
         if (reinterpret_cast<uintptr_t>(q) & 7u) return LRNNX_ERR_INVALID_ARG;
@@ -268,6 +271,7 @@ int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *a) {
     CFwdParams p{};
     p.B = a->B; p.D = a->D; p.N = a->N; p.L = a->L;
     p.bcg = bcg; p.dpg = a->D / bcg;
+    p.cu = cu; p.nslots = lrnnx_packed_ckpt_slots(a->L, a->B);
     p.softplus = a->delta_softplus ? 1 : 0;
     p.u = a->u; p.delta = a->delta; p.z = a->z; p.y = a->y;
     p.u_sb = a->u_stride_b; p.u_sd = a->u_stride_d;
@@ -287,7 +291,10 @@ int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *a) {
 }
 
 int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
-    if (!a || a->struct_size < sizeof(lrnnx_ss_bwd_complex_args)) return LRNNX_ERR_INVALID_ARG;
+    constexpr size_t kOldSize = offsetof(lrnnx_ss_bwd_complex_args, cu_seqlens);  // struct before `cu_seqlens` was appended
+    if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
+    const int64_t *cu = a->struct_size >= sizeof(lrnnx_ss_bwd_complex_args) ? a->cu_seqlens : nullptr;
+    if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
@@ -301,7 +308,9 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
     for (const void *q : {a->A, a->x0, a->ckpt, (const void *)a->dA, (const void *)a->dx0, (const void *)a->workspace})
         if (reinterpret_cast<uintptr_t>(q) & 7u) return LRNNX_ERR_INVALID_ARG;
     const size_t es = elem_size(a->io_dtype);
-    const size_t ck_bytes = (size_t)a->B * a->D * cdiv(a->L, kCkptInterval) * a->N * sizeof(float2);
+    const int64_t nslots = lrnnx_packed_ckpt_slots(a->L, a->B);
+    const size_t ck_bytes = cu ? (size_t)a->D * nslots * a->N * sizeof(float2)
+                               : (size_t)a->B * a->D * cdiv(a->L, kCkptInterval) * a->N * sizeof(float2);
     if (!a->ckpt && (!a->workspace || a->workspace_bytes < ck_bytes)) return LRNNX_ERR_WORKSPACE;
     hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
 
@@ -310,6 +319,7 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
         CFwdParams f{};
         f.B = a->B; f.D = a->D; f.N = a->N; f.L = a->L;
         f.bcg = bcg; f.dpg = a->D / bcg;
+        f.cu = cu; f.nslots = nslots;
         f.softplus = a->delta_softplus ? 1 : 0;
         f.u = a->u; f.delta = a->delta;
         f.u_sb = a->u_stride_b; f.u_sd = a->u_stride_d; f.dl_sb = a->delta_stride_b; f.dl_sd = a->delta_stride_d;
@@ -325,12 +335,13 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
     CBwdParams p{};
     set_bwd_rows(p, a);
     p.bcg = bcg; p.dpg = a->D / bcg;
+    p.cu = cu; p.nslots = nslots;
     p.A = reinterpret_cast<const float2 *>(a->A); p.ckpt = ckpt;
     p.dA = reinterpret_cast<float2 *>(a->dA); p.dBm = reinterpret_cast<float2 *>(a->dBm);
     p.dCm = reinterpret_cast<float2 *>(a->dCm); p.dx0 = reinterpret_cast<float2 *>(a->dx0);
     p.G = cbwd_channels_per_group(a->B * bcg, a->D / bcg, a->N);
 
-    const int64_t nbc = (int64_t)a->B * bcg * a->L * a->N * 2;           // floats
+    const int64_t nbc = (cu ? 1 : (int64_t)a->B) * bcg * a->L * a->N * 2;   // floats; packed mode: one time axis for all sequences
     FillList z{};
     z.ptr[0] = reinterpret_cast<float *>(a->dBm); z.count[0] = nbc;
     z.ptr[1] = reinterpret_cast<float *>(a->dCm); z.count[1] = nbc;

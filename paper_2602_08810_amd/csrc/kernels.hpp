@@ -33,6 +33,8 @@ struct CFwdParams {
     int64_t L;
     int softplus, vec;
     int bcg, dpg;            // number of Bm/Cm groups and channels per group (D = bcg * dpg)
+    const int64_t *cu;       // packed variable-length mode: [B+1] sequence boundaries on the packed axis of L steps
+    int64_t nslots;          // packed mode: checkpoint slots per channel
     const void *u, *delta, *z;
     void *y;
     int64_t u_sb, u_sd, dl_sb, dl_sd, z_sb, z_sd, y_sb, y_sd;
@@ -51,6 +53,8 @@ struct CBwdParams {
     int softplus, vec;
     int G;                   // channels per workgroup
     int bcg, dpg;            // number of Bm/Cm groups and channels per group (D = bcg * dpg)
+    const int64_t *cu;       // packed variable-length mode: [B+1] sequence boundaries on the packed axis of L steps
+    int64_t nslots;          // packed mode: checkpoint slots per channel
     const void *u, *delta, *z, *dy;
     void *du, *ddelta, *dz;
     int64_t u_sb, u_sd, dl_sb, dl_sd, z_sb, z_sd, dy_sb, dy_sd, du_sb, du_sd, dd_sb, dd_sd, dz_sb, dz_sd;

@@ -90,10 +90,21 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     const int din0 = (blockIdx.x % chunks_per_grp) * p.G;
     const int d0 = grp * p.dpg + din0;
     const int Gact = (p.dpg - din0 < p.G) ? p.dpg - din0 : p.G;
-    const int64_t L = p.L;
+    // Packed variable-length mode (p.cu != nullptr): batch entry b is the sequence of steps cu[b] .. cu[b+1]-1 of ONE
+    // packed time axis of p.L steps; I/O rows have no batch stride, the maps and their gradients are [G, p.L, N].
+    // The bounds are clamped to the packed axis, so no content of cu can send an access out of the buffers.
+    int64_t L = p.L, toff = 0, bs = b;
+    if (p.cu) {
+        int64_t o = p.cu[b], e = p.cu[b + 1];
+        o = o < 0 ? 0 : (o > p.L ? p.L : o);
+        e = e < o ? o : (e > p.L ? p.L : e);
+        toff = o; L = e - o; bs = 0;
+    }
     const int64_t ntiles = (L + TILE - 1) / TILE;
-    const int64_t nck = (L + kCkptInterval - 1) / kCkptInterval;
-    const bool vec = p.vec != 0;
+    // checkpoints of this workgroup's rows: [B,D,nck,N], or packed [D,nslots,N] with sequence b at slot toff/interval + b
+    const int64_t nck = p.cu ? p.nslots : (L + kCkptInterval - 1) / kCkptInterval;
+    const int64_t ck0 = p.cu ? toff / kCkptInterval + b : 0;
+    const bool vec = p.vec != 0 && (toff % 8) == 0;
     const bool has_z = p.z != nullptr;
 
     for (int i = tid; i < kMaxGc * N; i += NT) {
@@ -102,7 +113,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     }
     for (int i = tid; i < 2 * W * kMaxGc; i += NT) { sdD[i] = 0.0f; sdb[i] = 0.0f; }
 
-    const int64_t bc0 = ((int64_t)b * p.bcg + grp) * L * N;          // first complex element of the maps of this batch entry and group
+    const int64_t bc0 = ((bs * p.bcg + grp) * p.L + toff) * N;       // first complex element of the maps of this sequence and group
     const CW *Bm = reinterpret_cast<const CW *>(p.Bm) + bc0;
     const CW *Cm = reinterpret_cast<const CW *>(p.Cm) + bc0;
 
@@ -154,15 +165,15 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
             const int d = d0 + g;
             const int64_t row = (int64_t)b * p.D + d;
             if (pro_thread) {
-                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.u) + b * p.u_sb + d * p.u_sd + l0, f0, rem, vec, r_u);
-                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd + l0, f0, rem, vec, r_dl);
-                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.dy) + b * p.dy_sb + d * p.dy_sd + l0, f0, rem, vec, r_dy);
-                if (has_z) load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd + l0, f0, rem, vec, r_z);
+                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.u) + bs * p.u_sb + d * p.u_sd + toff + l0, f0, rem, vec, r_u);
+                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.delta) + bs * p.dl_sb + d * p.dl_sd + toff + l0, f0, rem, vec, r_dl);
+                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.dy) + bs * p.dy_sb + d * p.dy_sd + toff + l0, f0, rem, vec, r_dy);
+                if (has_z) load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.z) + bs * p.z_sb + d * p.z_sd + toff + l0, f0, rem, vec, r_z);
             }
 #pragma unroll
             for (int k = 0; k < NK; ++k) {
                 pA[k] = p.A[d * N + w * NK + k];
-                pck[k] = p.ckpt[(row * nck + tile * CK_PER_TILE) * N + w * NK + k];
+                pck[k] = p.ckpt[((p.cu ? (int64_t)d : row) * nck + ck0 + tile * CK_PER_TILE) * N + w * NK + k];
             }
             pDsk = p.Dskip ? p.Dskip[d] : 0.0f;
             pbias = p.bias ? p.bias[d] : 0.0f;
@@ -394,9 +405,9 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
                     dD_part = __builtin_fmaf(e_dyp, e_u, dD_part);
                     db_part += (f0e + i < rem) ? o_dd[i] : 0.0f;
                 }
-                store_few<IO, TPW>(reinterpret_cast<IO *>(p.du) + b * p.du_sb + d * p.du_sd + l0, f0e, rem, vec, o_du);
-                store_few<IO, TPW>(reinterpret_cast<IO *>(p.ddelta) + b * p.dd_sb + d * p.dd_sd + l0, f0e, rem, vec, o_dd);
-                if (p.dz) store_few<IO, TPW>(reinterpret_cast<IO *>(p.dz) + b * p.dz_sb + d * p.dz_sd + l0, f0e, rem, vec, o_dz);
+                store_few<IO, TPW>(reinterpret_cast<IO *>(p.du) + bs * p.du_sb + d * p.du_sd + toff + l0, f0e, rem, vec, o_du);
+                store_few<IO, TPW>(reinterpret_cast<IO *>(p.ddelta) + bs * p.dd_sb + d * p.dd_sd + toff + l0, f0e, rem, vec, o_dd);
+                if (p.dz) store_few<IO, TPW>(reinterpret_cast<IO *>(p.dz) + bs * p.dz_sb + d * p.dz_sd + toff + l0, f0e, rem, vec, o_dz);
                 const float vD = half_sum(dD_part), vb = half_sum(db_part);
                 if ((lane & 31) == 0) {
                     sdD[((lane >> 5) * W + w) * kMaxGc + g] += vD;

@@ -37,19 +37,31 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
     const int d_in = (blockIdx.x % blk_per_grp) * W + w;
     const bool active = d_in < p.dpg;
     const int d = grp * p.dpg + (active ? d_in : p.dpg - 1);
-    const int64_t L = p.L;
+    // Packed variable-length mode (p.cu != nullptr): batch entry b is the sequence of steps cu[b] .. cu[b+1]-1 of ONE
+    // packed time axis of p.L steps; I/O rows have no batch stride, the maps are [G, p.L, N].  The bounds are
+    // clamped to the packed axis, so no content of cu can send an access out of the buffers.
+    int64_t L = p.L, toff = 0, bs = b;
+    if (p.cu) {
+        int64_t o = p.cu[b], e = p.cu[b + 1];
+        o = o < 0 ? 0 : (o > p.L ? p.L : o);
+        e = e < o ? o : (e > p.L ? p.L : e);
+        toff = o; L = e - o; bs = 0;
+    }
     const int64_t ntiles = (L + TILE - 1) / TILE;
     const int64_t row = (int64_t)b * p.D + d;
-    const bool vec = p.vec != 0;
+    const bool vec = p.vec != 0 && (toff % 8) == 0;
 
-    const IO *urow = reinterpret_cast<const IO *>(p.u) + b * p.u_sb + d * p.u_sd;
-    const IO *drow = reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd;
-    const IO *zrow = p.z ? reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd : nullptr;
+    const IO *urow = reinterpret_cast<const IO *>(p.u) + bs * p.u_sb + d * p.u_sd + toff;
+    const IO *drow = reinterpret_cast<const IO *>(p.delta) + bs * p.dl_sb + d * p.dl_sd + toff;
+    const IO *zrow = p.z ? reinterpret_cast<const IO *>(p.z) + bs * p.z_sb + d * p.z_sd + toff : nullptr;
     const bool want_y = p.y != nullptr;                 // a state-only sweep (checkpoints for the backward pass) has no y
-    IO *yrow = reinterpret_cast<IO *>(p.y) + b * p.y_sb + d * p.y_sd;
-    const int64_t nck = (L + kCkptInterval - 1) / kCkptInterval;
-    const CW *Bm = reinterpret_cast<const CW *>(p.Bm) + ((int64_t)b * p.bcg + grp) * L * N;
-    const CW *Cm = reinterpret_cast<const CW *>(p.Cm) + ((int64_t)b * p.bcg + grp) * L * N;
+    IO *yrow = reinterpret_cast<IO *>(p.y) + bs * p.y_sb + d * p.y_sd + toff;
+    // checkpoints of this row: [B,D,nck,N], or packed [D,nslots,N] with sequence b starting at slot toff/interval + b
+    const int64_t ck0 = p.cu ? (int64_t)d * p.nslots + toff / kCkptInterval + b
+                             : row * ((L + kCkptInterval - 1) / kCkptInterval);
+    const int64_t bc0 = ((bs * p.bcg + grp) * p.L + toff) * N;       // first complex element of the maps of this sequence
+    const CW *Bm = reinterpret_cast<const CW *>(p.Bm) + bc0;
+    const CW *Cm = reinterpret_cast<const CW *>(p.Cm) + bc0;
 
     // lane n holds the constants and the carried state of state n
     float Arv = 0.0f, Aiv = 0.0f, xrv = 0.0f, xiv = 0.0f;
@@ -125,7 +137,7 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
             float2 x = make_float2(dpp<DPP_WAVE_SHR1>(xc.x, S.x), dpp<DPP_WAVE_SHR1>(xc.y, S.y));
             // the state entering every kCkptInterval-th step is what the backward pass restarts from
             if (p.ckpt && (lane * T) % (int)kCkptInterval == 0 && ll < L)
-                p.ckpt[(row * nck + ll / kCkptInterval) * N + n] = x;
+                p.ckpt[(ck0 + ll / kCkptInterval) * N + n] = x;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 const float2 Cv = cword<IO>::unpack(sC[n * PLANE + (t / 4) * QS + lane * 4 + (t % 4)]);

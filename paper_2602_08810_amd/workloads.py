@@ -108,6 +108,21 @@ def make_packed(D, N, lengths, io="f32", gate=True, seed=0, bc_groups=1, gap=0):
     return out
 
 
+def make_packed_complex(D, N, lengths, io="f32", gate=True, seed=0, bc_groups=1, gap=0):
+    """make_packed for the complex-A scan: the arrays of make_selective_complex on one packed time axis ([D,L],
+    maps [L,N,2] or [G,L,N,2]), x0 complex64 [S,D,N], dy [D,L] and cu_seqlens (int64 [S+1])."""
+    L = int(sum(lengths)) + 2 * gap
+    p = make_selective_complex(B=1, D=D, N=N, L=L, io=io, gate=gate, seed=seed, bc_groups=bc_groups)
+    out = {k: (None if v is None else v[0]) for k, v in p.items() if k in ("u", "delta", "z", "Bm", "Cm")}
+    out.update(A=p["A"], Dskip=p["Dskip"], delta_bias=p["delta_bias"])
+    rng = np.random.Generator(np.random.PCG64(seed + 1000))
+    S = len(lengths)
+    out["x0"] = (rng.standard_normal((S, D, N)) + 1j * rng.standard_normal((S, D, N))).astype(np.complex64)
+    out["dy"] = _io_round(rng.standard_normal((D, L), dtype=np.float32), io)
+    out["cu_seqlens"] = (gap + np.concatenate([[0], np.cumsum(lengths)])).astype(np.int64)
+    return out
+
+
 def make_lti(B, P, L, seed=1, with_x0=False, with_gx=False, **_unused):
     """Inputs of the LTI complex-diagonal scan.
 
