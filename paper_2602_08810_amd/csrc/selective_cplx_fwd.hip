@@ -122,8 +122,13 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
                 const float2 Bv = cword<IO>::unpack(sB[n * PLANE + (t / 4) * QS + lane * 4 + (t % 4)]);
                 float2 g;
                 cdisc_ag<DISC>(dl[t], cc, a[t], g);
-                const float gu_r = g.x * uv[t], gu_i = g.y * uv[t];
-                bb[t] = make_float2(gu_r * Bv.x - gu_i * Bv.y, gu_r * Bv.y + gu_i * Bv.x);
+                if constexpr (DISC == DISC_ZOH_S6 || DISC == DISC_DIRAC) {
+                    const float gu = g.x * uv[t];                         // the gain is real
+                    bb[t] = make_float2(gu * Bv.x, gu * Bv.y);
+                } else {
+                    const float gu_r = g.x * uv[t], gu_i = g.y * uv[t];
+                    bb[t] = make_float2(gu_r * Bv.x - gu_i * Bv.y, gu_r * Bv.y + gu_i * Bv.x);
+                }
                 S = make_float2(__builtin_fmaf(a[t].x, S.x, __builtin_fmaf(-a[t].y, S.y, bb[t].x)),
                                 __builtin_fmaf(a[t].x, S.y, __builtin_fmaf(a[t].y, S.x, bb[t].y)));
                 if constexpr (DISC == DISC_BILINEAR) P = make_float2(P.x * a[t].x - P.y * a[t].y, P.x * a[t].y + P.y * a[t].x);
