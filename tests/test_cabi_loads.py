@@ -184,3 +184,60 @@ def test_host_side_validation_of_the_backward_and_lti_calls(lib):
     assert lti(v=0x10004) == 1 and lti(x=0) == 1 and lti(path=7) == 1
     assert lti(B=70000) == 2
     assert lti() == 3                                         # every path of this call needs its workspace
+
+
+def test_host_side_validation_of_the_complex_calls(lib):
+    """As above for the complex-A forward and backward entry points, including the shorter argument blocks of callers
+    built before fields were appended (fake pointers, no GPU: only refusals are exercised)."""
+    torch = pytest.importorskip("torch")
+    if torch.cuda.device_count() > 0:
+        pytest.skip("host-only test: not run on a machine with a GPU")
+    from paper_2602_08810_amd import api
+    fake = 0x10000
+
+    def fwd(size=None, **over):
+        a = api.FwdComplexArgs()
+        a.struct_size = ctypes.sizeof(api.FwdComplexArgs) if size is None else size
+        a.B, a.D, a.N, a.L = 2, 8, 16, 100
+        a.io_dtype, a.disc, a.delta_softplus = api.BF16, 0, 1
+        a.u = a.delta = a.A = a.Bm = a.Cm = a.y = fake
+        a.u_stride_b = a.delta_stride_b = a.y_stride_b = 800
+        a.u_stride_d = a.delta_stride_d = a.y_stride_d = 100
+        for k, v in over.items():
+            setattr(a, k, v)
+        return lib.lrnnx_selective_scan_fwd_complex(ctypes.byref(a))
+    lib.lrnnx_selective_scan_fwd_complex.argtypes = [ctypes.POINTER(api.FwdComplexArgs)]
+    assert fwd(N=32) == 2 and fwd(N=3) == 2 and fwd(B=65536) == 2      # complex states: N <= 16
+    assert fwd(L=0) == 1 and fwd(io_dtype=5) == 1 and fwd(disc=-1) == 1
+    assert fwd(y=0) == 1                                               # nothing to compute: no y, ckpt or x_last
+    assert fwd(A=0x10004) == 1 and fwd(x0=0x10004) == 1 and fwd(ckpt=0x10004) == 1 and fwd(Cm=0x10008) == 1
+    assert fwd(bc_groups=3) == 1 and fwd(bc_groups=-2) == 1
+    assert fwd(cu_seqlens=0x10004) == 1                                # boundaries are 8-byte integers
+    assert fwd(size=api.FwdComplexArgs.ckpt.offset - 8) == 1           # shorter than the first published block
+    # a block that ends before `cu_seqlens` is still read (its later fields are then ignored): the refusal
+    # comes from the fields it does have
+    assert fwd(size=api.FwdComplexArgs.cu_seqlens.offset, N=3, cu_seqlens=0x10004) == 2
+
+    def bwd(size=None, **over):
+        a = api.BwdComplexArgs()
+        a.struct_size = ctypes.sizeof(api.BwdComplexArgs) if size is None else size
+        a.B, a.D, a.N, a.L = 2, 8, 16, 100
+        a.io_dtype, a.disc, a.delta_softplus = api.BF16, 0, 1
+        for f in ("u", "delta", "A", "Bm", "Cm", "dy", "du", "ddelta", "dA", "dBm", "dCm", "ckpt"):
+            setattr(a, f, fake)
+        for f in ("u", "delta", "dy", "du", "ddelta"):
+            setattr(a, f + "_stride_b", 800)
+            setattr(a, f + "_stride_d", 100)
+        for k, v in over.items():
+            setattr(a, k, v)
+        return lib.lrnnx_selective_scan_bwd_complex(ctypes.byref(a))
+    lib.lrnnx_selective_scan_bwd_complex.argtypes = [ctypes.POINTER(api.BwdComplexArgs)]
+    assert bwd(ckpt=0) == 3 and bwd(ckpt=0, workspace=fake, workspace_bytes=64) == 3
+    assert bwd(N=32) == 2 and bwd(B=70000) == 2
+    assert bwd(dz=fake) == 1 and bwd(dD=fake) == 1 and bwd(dbias=fake) == 1
+    assert bwd(dA=0x10004) == 1 and bwd(dx0=0x10004) == 1 and bwd(dCm=0x10008) == 1
+    assert bwd(cu_seqlens=0x10004) == 1 and bwd(bc_groups=5) == 1
+    assert bwd(size=api.BwdComplexArgs.cu_seqlens.offset - 8) == 1
+    # packed mode sizes the recompute workspace by D * (L / interval + B) * N float pairs
+    need = 8 * (100 // int(lib.lrnnx_ckpt_interval()) + 2) * 16 * 8
+    assert bwd(ckpt=0, cu_seqlens=fake, workspace=fake, workspace_bytes=need - 1) == 3
