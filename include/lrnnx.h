@@ -225,7 +225,9 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *args);
  * delta_bias, z and x0.  The state is recomputed tile by tile from checkpoints and
  * never stored per step (Sec. 3).  `ckpt` is the array a forward call wrote for the
  * same inputs; if NULL the library first runs a state-only forward sweep into
- * `workspace` (size from lrnnx_workspace_bytes(LRNNX_WS_BWD, ...)).
+ * `workspace`.  lrnnx_workspace_bytes(LRNNX_WS_BWD, ...) covers that sweep and the chunk aggregates of the
+ * chunked path (`path`); with `ckpt` given, LRNNX_WS_BWD_CARRY bytes are enough for the latter, and with a
+ * workspace too small for it (or none) the call runs as a single pass.
  * Outputs du, ddelta, dz: io_dtype, written once each.  dA[D,N], dBm, dCm[B,L,N],
  * dD[D], dbias[D]: float, OVERWRITTEN (the library clears them on the stream, then
  * accumulates with atomics: their last bits may differ from run to run).
@@ -262,6 +264,13 @@ typedef struct lrnnx_ss_bwd_args {
     const int64_t *cu_seqlens;   /* as in the forward call (then dBm, dCm are [G,L,N]); callers built against the
                                     shorter struct get NULL.  With ckpt == NULL the workspace must hold
                                     D * lrnnx_packed_ckpt_slots(L,B) * N floats. */
+    int32_t path;                /* lrnnx_path.  CHUNK_CARRY: the time axis is cut into chunks that run side by side
+                                    (three launches: adjoint aggregate per chunk, chain, backward per chunk), for long
+                                    sequences with few rows; needs the workspace.  SINGLE_PASS: one workgroup walks a
+                                    whole row.  AUTO picks CHUNK_CARRY when a single pass would leave most of the chip
+                                    idle and the workspace allows it.  Not with cu_seqlens (single pass).  Callers
+                                    built against a shorter struct get AUTO. */
+    int32_t reserved;
 } lrnnx_ss_bwd_args;
 
 int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *args);
@@ -445,12 +454,19 @@ int lrnnx_lti_step(const lrnnx_lti_step_args *args);
 
 /* ------------------------------------------------------------------ queries (host only, no GPU needed) */
 typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2, LRNNX_WS_LTI_BWD = 3, LRNNX_WS_DIAG = 4,
-               LRNNX_WS_DIAG_BWD = 5, LRNNX_WS_BWD_COMPLEX = 6 } lrnnx_ws_kind;
+               LRNNX_WS_DIAG_BWD = 5, LRNNX_WS_BWD_COMPLEX = 6,
+               LRNNX_WS_BWD_CARRY = 7   /* the chunk aggregates of lrnnx_selective_scan_bwd alone (ckpt supplied) */
+             } lrnnx_ws_kind;
 
 /* Bytes of device scratch the call may need (the largest over its paths).
  * For LRNNX_WS_LTI, LRNNX_WS_LTI_BWD, LRNNX_WS_DIAG and LRNNX_WS_DIAG_BWD pass P as D and 0 for N (the DIAG kinds:
  * io_dtype is LRNNX_F32 or LRNNX_C64).  Returns 0 for invalid sizes.   */
 size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t L, int io_dtype);
+
+/* Number of chunks lrnnx_selective_scan_bwd cuts the time axis into for these sizes and this `path` when its
+ * workspace allows it (1: single pass); the aggregates then take 2 * B * D * chunks * N floats of the workspace.
+ * 0 for invalid sizes.                                                                                         */
+int lrnnx_selective_scan_bwd_chunks(int64_t B, int64_t D, int64_t N, int64_t L, int bc_groups, int path);
 
 const char *lrnnx_status_string(int status);
 int lrnnx_version(void);   /* major * 100 + minor; grows whenever an entry point or a struct field is added */

@@ -20,7 +20,7 @@ LIB_PATH = os.environ.get("LRNNX_LIB", os.path.join(_HERE, "liblrnnx.so"))   # L
 F32, BF16, C64 = 0, 1, 2
 DISC = {"zoh_s6": 0, "zoh": 1, "bilinear": 2, "dirac": 3}
 PATH = {"auto": 0, "single_pass": 1, "chunk_carry": 2}
-WS_FWD, WS_BWD, WS_LTI, WS_LTI_BWD, WS_DIAG, WS_DIAG_BWD, WS_BWD_COMPLEX = 0, 1, 2, 3, 4, 5, 6
+WS_FWD, WS_BWD, WS_LTI, WS_LTI_BWD, WS_DIAG, WS_DIAG_BWD, WS_BWD_COMPLEX, WS_BWD_CARRY = 0, 1, 2, 3, 4, 5, 6, 7
 STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported", 3: "workspace", 4: "launch"}
 
 _vp, _i32, _i64, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
@@ -92,6 +92,7 @@ class BwdArgs(ctypes.Structure):
         ("dz", _vp), ("dz_stride_b", _i64), ("dz_stride_d", _i64),
         ("dA", _vp), ("dBm", _vp), ("dCm", _vp), ("dD", _vp), ("dbias", _vp), ("dx0", _vp),
         ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp), ("cu_seqlens", _vp),
+        ("path", _i32), ("reserved", _i32),
     ]
 
 
@@ -194,6 +195,8 @@ def lib():
             f.restype = ctypes.c_int
         L.lrnnx_workspace_bytes.argtypes = [ctypes.c_int, _i64, _i64, _i64, _i64, ctypes.c_int]
         L.lrnnx_workspace_bytes.restype = _sz
+        L.lrnnx_selective_scan_bwd_chunks.argtypes = [_i64, _i64, _i64, _i64, ctypes.c_int, ctypes.c_int]
+        L.lrnnx_selective_scan_bwd_chunks.restype = ctypes.c_int
         L.lrnnx_ckpt_interval.restype = _i64
         L.lrnnx_status_string.argtypes = [ctypes.c_int]
         L.lrnnx_status_string.restype = ctypes.c_char_p
@@ -545,9 +548,10 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
 @_device_checked
 def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,
                              ckpt=None, disc="zoh_s6", delta_softplus=True, want_dx0=False,
-                             outs=None, workspace=None, cu_seqlens=None):
+                             outs=None, workspace=None, cu_seqlens=None, path="auto"):
     """Gradients of sum(dy*y) as a dict; see lrnnx_ss_bwd_args.  `outs` may supply preallocated outputs.
-    `cu_seqlens`: packed variable-length mode as in the forward call (du, ddelta, dz are [D,L]; dBm, dCm as Bm)."""
+    `cu_seqlens`: packed variable-length mode as in the forward call (du, ddelta, dz are [D,L]; dBm, dCm as Bm).
+    `path`: "auto", "single_pass" or "chunk_carry" (time axis cut into chunks that run side by side)."""
     io = u.dtype
     packed = cu_seqlens is not None
     if packed:
@@ -573,6 +577,7 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
     a.struct_size = ctypes.sizeof(BwdArgs)
     a.B, a.D, a.N, a.L = Bsz, D, N, L
     a.cu_seqlens = _ptr(cu_seqlens)
+    a.path = PATH[path] if isinstance(path, str) else int(path)
     a.io_dtype = _io_dtype(u)
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
     a.delta_softplus = int(bool(delta_softplus))
@@ -600,10 +605,16 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
         a.dbias = new("dbias", (D,), torch.float32).data_ptr()
     if want_dx0:
         a.dx0 = new("dx0", (Bsz, D, N), torch.float32).data_ptr()
-    if workspace is None and ckpt is None:
-        nbytes = (D * (L // lrnnx_ckpt_interval() + Bsz) * N * 4 if packed
-                  else lrnnx_workspace_bytes(WS_BWD, Bsz, D, N, L, a.io_dtype))
-        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
+    if workspace is None:
+        if packed:
+            nbytes = D * (L // lrnnx_ckpt_interval() + Bsz) * N * 4 if ckpt is None else 0
+        else:                                          # checkpoints of the recompute sweep, then the chunk aggregates
+            nch = int(lib().lrnnx_selective_scan_bwd_chunks(Bsz, D, N, L, a.bc_groups, a.path))
+            nbytes = 2 * Bsz * D * nch * N * 4 if nch > 1 else 0
+            if ckpt is None:
+                nbytes += (Bsz * D * -(-L // lrnnx_ckpt_interval()) * N * 4 + 255) // 256 * 256
+        if nbytes:
+            workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     if workspace is not None:
         a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
     a.stream = _stream()

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblrnnx.so")
-SOURCES = ["api.hip", "selective_fwd.hip", "selective_bwd.hip", "selective_cplx_fwd.hip", "selective_cplx_bwd.hip", "lti_scan.hip", "diag_scan.hip", "step.hip"]
+SOURCES = ["api.hip", "selective_fwd.hip", "selective_bwd.hip", "selective_bwd_carry.hip", "selective_cplx_fwd.hip", "selective_cplx_bwd.hip", "lti_scan.hip", "diag_scan.hip", "step.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -88,6 +88,13 @@ FillList onepass_fill(const LtiParams &p) {
     return z;
 }
 
+// bytes of the two aggregate arrays [B,D,nchunks,N] of the chunked backward, when that path is asked for
+size_t bwd_carry_bytes(int64_t B, int64_t D, int64_t N, int64_t L) {
+    const BwdPlan pl = bwd_plan((int)B, (int)D, (int)N, L, 2, true);
+    return pl.nchunks > 1 ? (size_t)2 * B * D * pl.nchunks * N * sizeof(float) : 0;
+}
+size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
 // The real and the complex backward entry points take the same per-row tensors (same field names in both argument
 // structs and both parameter blocks): checks and marshalling are written once.
 template <typename Args>
@@ -126,7 +133,15 @@ extern "C" {
 
 int64_t lrnnx_ckpt_interval(void) { return kCkptInterval; }
 int64_t lrnnx_packed_ckpt_slots(int64_t L, int64_t B) { return (L < 0 || B < 0) ? 0 : L / kCkptInterval + B; }
-int lrnnx_version(void) { return 134; }   // major * 100 + minor; bumped whenever an entry point or a struct field is added
+int lrnnx_version(void) { return 135; }   // major * 100 + minor; bumped whenever an entry point or a struct field is added
+
+int lrnnx_selective_scan_bwd_chunks(int64_t B, int64_t D, int64_t N, int64_t L, int bc_groups, int path) {
+    const int bcg = bc_groups > 1 ? bc_groups : 1;
+    if (B < 1 || D < 1 || L < 1 || B > 65535 || D > INT32_MAX || !supported_n((int)N) || D % bcg) return 0;
+    if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return 0;
+    if (path == LRNNX_PATH_SINGLE_PASS) return 1;
+    return bwd_plan((int)B * bcg, (int)(D / bcg), (int)N, L, path, true).nchunks;
+}
 
 const char *lrnnx_status_string(int status) {
     switch (status) {
@@ -146,10 +161,11 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
         const int nch = fwd_chunks(B, D, L, io_dtype, true);
         return (size_t)2 * B * D * nch * N * sizeof(float);
     }
-    if (which == LRNNX_WS_BWD) {
+    if (which == LRNNX_WS_BWD) {                    // checkpoints of the recompute sweep, then the chunk aggregates
         if (!supported_n((int)N)) return 0;
-        return (size_t)B * D * cdiv(L, kCkptInterval) * N * sizeof(float);
+        return align256((size_t)B * D * cdiv(L, kCkptInterval) * N * sizeof(float)) + bwd_carry_bytes(B, D, N, L);
     }
+    if (which == LRNNX_WS_BWD_CARRY) return supported_n((int)N) ? bwd_carry_bytes(B, D, N, L) : 0;
     if (which == LRNNX_WS_BWD_COMPLEX) {
         if (!supported_n_complex((int)N)) return 0;
         return (size_t)B * D * cdiv(L, kCkptInterval) * N * sizeof(float2);
@@ -354,9 +370,13 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
 
 int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     constexpr size_t kOldSize = offsetof(lrnnx_ss_bwd_args, cu_seqlens);  // struct before `cu_seqlens` was appended
+    constexpr size_t kSizeCu = offsetof(lrnnx_ss_bwd_args, path);         // ... and before `path` was
     if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
-    const int64_t *cu = a->struct_size >= sizeof(lrnnx_ss_bwd_args) ? a->cu_seqlens : nullptr;
+    const int64_t *cu = a->struct_size >= kSizeCu ? a->cu_seqlens : nullptr;
+    const int path = a->struct_size >= sizeof(lrnnx_ss_bwd_args) ? a->path : LRNNX_PATH_AUTO;
     if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
+    if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
+    if (cu && path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_UNSUPPORTED;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
@@ -373,7 +393,19 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     const size_t ck_bytes = cu ? (size_t)a->D * nslots * a->N * sizeof(float)
                                : (size_t)a->B * a->D * nck * a->N * sizeof(float);
     if (!a->ckpt && (!a->workspace || a->workspace_bytes < ck_bytes)) return LRNNX_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(a->workspace) & 3u) return LRNNX_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
+
+    // chunked path: the aggregates live in the workspace, after the checkpoints of the recompute sweep if there are any
+    BwdPlan pl = bwd_plan(a->B * bcg, a->D / bcg, a->N, a->L, path, cu == nullptr);
+    const size_t carry_off = a->ckpt ? 0 : align256(ck_bytes);
+    if (pl.nchunks > 1) {
+        const size_t need = carry_off + (size_t)2 * a->B * a->D * pl.nchunks * a->N * sizeof(float);
+        if (!a->workspace || a->workspace_bytes < need) {
+            if (path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_WORKSPACE;
+            pl = bwd_plan(a->B * bcg, a->D / bcg, a->N, a->L, LRNNX_PATH_SINGLE_PASS, true);
+        }
+    }
 
     const float *ckpt = a->ckpt;
     if (!ckpt) {                                   // state-only forward sweep: writes the checkpoints
@@ -398,7 +430,16 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     p.cu = cu; p.nslots = lrnnx_packed_ckpt_slots(a->L, a->B);
     p.A = a->A; p.x0 = a->x0; p.ckpt = ckpt;
     p.dA = a->dA; p.dBm = a->dBm; p.dCm = a->dCm; p.dx0 = a->dx0;
-    p.G = bwd_channels_per_group(a->B * bcg, a->D / bcg, a->N, a->L, cu == nullptr);
+    p.G = pl.G;
+    p.nchunks = pl.nchunks;
+    p.tiles_per_chunk = pl.tiles_per_chunk;
+    if (pl.nchunks > 1) {
+        p.ws_P = reinterpret_cast<float *>(static_cast<char *>(a->workspace) + carry_off);
+        p.ws_Q = p.ws_P + (size_t)a->B * a->D * p.nchunks * a->N;
+        p.hc = p.ws_Q;
+        if (launch_ss_bwd_agg(p, a->io_dtype, a->disc, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+        if (launch_ss_bwd_carry(p, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    }
 
     // reduced outputs are accumulated with atomics: clear them on the stream first
     const int64_t nbc = (cu ? 1 : (int64_t)a->B) * bcg * a->L * a->N;   // packed mode: one time axis for all sequences

@@ -79,7 +79,16 @@ struct BwdParams {
     const float *A, *Dskip, *bias, *x0, *ckpt;
     const void *Bm, *Cm;
     float *dA, *dBm, *dCm, *dD, *dbias, *dx0;
+    // Chunked backward for long sequences with few rows: the time axis is cut into nchunks chunks of
+    // tiles_per_chunk backward tiles (kBwdTileSteps steps each), one workgroup per (channel group, batch entry, chunk).
+    // ws_P, ws_Q [B,D,nchunks,N] receive each chunk's adjoint aggregate; the carry kernel turns ws_Q into `hc`, the
+    // adjoint carry a_{l1+1} H_{l1+1} entering each chunk from the later side.  nchunks <= 1: no chunking, hc unused.
+    int nchunks;
+    int64_t tiles_per_chunk;
+    float *ws_P, *ws_Q;
+    const float *hc;
 };
+constexpr int kBwdTileSteps = 256;
 
 struct LtiParams {
     int B, P;
@@ -147,6 +156,12 @@ hipError_t launch_ss_cfwd(const CFwdParams &p, int io_dtype, int disc, hipStream
 hipError_t launch_ss_cbwd(const CBwdParams &p, int io_dtype, int disc, hipStream_t s);
 int cbwd_channels_per_group(int B, int D, int N);
 hipError_t launch_ss_bwd(const BwdParams &p, int io_dtype, int disc, hipStream_t s);
+hipError_t launch_ss_bwd_agg(const BwdParams &p, int io_dtype, int disc, hipStream_t s);   // chunk aggregates -> ws_P, ws_Q
+hipError_t launch_ss_bwd_carry(const BwdParams &p, hipStream_t s);                         // ws_Q -> carries, in place
+// Launch shape of the backward pass: channels per workgroup, and (chunks > 1) the chunked path's cut of the time axis
+struct BwdPlan { int G, nchunks; int64_t tiles_per_chunk; };
+// rowsg = B * (number of Bm/Cm groups), dpg = channels per group; mode 0: automatic, 1: single pass, 2: chunked asked for
+BwdPlan bwd_plan(int rowsg, int dpg, int N, int64_t L, int mode, bool balanced);
 hipError_t launch_lti(const LtiParams &p, hipStream_t s);
 hipError_t launch_lti_onepass(const LtiParams &p, hipStream_t s);
 int lti_onepass_group_steps(int64_t B, int64_t P);   // time steps per chained group for this shape

@@ -43,6 +43,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     constexpr int CK_PER_TILE = TILE / (int)kCkptInterval;
     static_assert(T % 4 == 0 && (T % W == 0 || W % T == 0) && TPW <= 8 && NA % 64 == 0 && NA <= NT, "tile shape");
     static_assert(TILE % kCkptInterval == 0, "tiles must start on checkpoints");
+    static_assert(TILE == kBwdTileSteps, "the chunked launch counts its chunks in tiles of this kernel");
     static_assert(W * 3 * TILE >= 2 * 16 * T * N, "flush buffer must fit in the partials area");
 
     __shared__ __attribute__((aligned(16))) float sIn[3 * TILE];          // delta, u, dypre   [q][lane][4]
@@ -84,13 +85,22 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
         toff = o; L = e - o; bs = 0;
     }
     const int64_t ntiles = (L + TILE - 1) / TILE;
+    // chunked launch: this workgroup walks the tiles of chunk blockIdx.z only, starting from that chunk's carried adjoint
+    const int chunk = blockIdx.z;
+    const int64_t tile_lo = p.nchunks > 1 ? chunk * p.tiles_per_chunk : 0;
+    const int64_t tile_hi = (p.nchunks > 1 && tile_lo + p.tiles_per_chunk < ntiles) ? tile_lo + p.tiles_per_chunk : ntiles;
     // checkpoints of this workgroup's rows: [B,D,nck,N], or packed [D,nslots,N] with sequence b at slot toff/interval + b
     const int64_t nck = p.cu ? p.nslots : (L + kCkptInterval - 1) / kCkptInterval;
     const int64_t ck0 = p.cu ? toff / kCkptInterval + b : 0;
     const bool vec = p.vec != 0 && (toff % 8) == 0;
     const bool has_z = p.z != nullptr;
 
-    for (int i = tid; i < kMaxG * N; i += NT) { sH[i] = 0.0f; sdA[0][i] = 0.0f; sdA[1][i] = 0.0f; }
+    for (int i = tid; i < kMaxG * N; i += NT) {
+        float h = 0.0f;
+        if (p.nchunks > 1 && i < Gact * N)
+            h = p.hc[(((int64_t)b * p.D + d0 + i / N) * p.nchunks + chunk) * N + i % N];
+        sH[i] = h; sdA[0][i] = 0.0f; sdA[1][i] = 0.0f;
+    }
     for (int i = tid; i < 2 * W * kMaxG; i += NT) { sdD[i] = 0.0f; sdb[i] = 0.0f; }
 
     const int64_t bc0 = ((p.cu ? (int64_t)grp : (int64_t)bcrow) * p.L + toff) * N;   // first element of the maps of this sequence
@@ -102,7 +112,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     const bool io_thread = NA == NT || tid < NA;                     // wave-uniform: NA is a multiple of 64
     auto fslot = [](int f) { return (((f % T) / 4) * 64 + f / T) * 4 + (f % 4); };
 
-    for (int64_t tile = ntiles - 1; tile >= 0; --tile) {
+    for (int64_t tile = tile_hi - 1; tile >= tile_lo; --tile) {
         const int64_t l0 = tile * TILE;
         const int rem = (L - l0 < TILE) ? (int)(L - l0) : TILE;      // valid steps of this tile
         // all global addresses below are a wave-uniform base plus a small unsigned per-lane offset, so that
@@ -420,7 +430,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     for (int i = tid; i < Gact * N; i += NT) {
         const int g = i / N, n = i % N;
         unsafeAtomicAdd(p.dA + (int64_t)(d0 + g) * N + n, sdA[0][g * N + n] + sdA[1][g * N + n]);
-        if (p.dx0) p.dx0[((int64_t)b * p.D + d0 + g) * N + n] = sH[g * N + n];
+        if (p.dx0 && chunk == 0) p.dx0[((int64_t)b * p.D + d0 + g) * N + n] = sH[g * N + n];
     }
     for (int g = tid; g < Gact; g += NT) {
         float sD = 0.0f, sb = 0.0f;
@@ -437,10 +447,12 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
 // channels per workgroup: D here is the number of channels that share one pair of Bm/Cm maps.  `balanced` says
 // that all batch entries have the same length; otherwise (packed variable-length batches) four times as many,
 // smaller, workgroups let the dispatcher even out sequences of different lengths.
+int bwd_waves_per_workgroup(int N) { return N >= 8 ? N / 4 : (N == 4 ? 2 : 1); }   // as dispatched in launch_bwd_disc
+
 int bwd_channels_per_group(int B, int D, int N, int64_t, bool balanced) {
     // aim at eight wavefronts per CU (two per SIMD, what the register budget allows): a workgroup has 8, 4, 2, 2, 1, 1
     // of them for N = 32, 16, 8, 4, 2, 1, so 256, 512, 1024, 1024, 2048, 2048 workgroups
-    const int waves = N >= 8 ? N / 4 : (N == 4 ? 2 : 1);          // as dispatched in launch_bwd_disc
+    const int waves = bwd_waves_per_workgroup(N);
     int64_t G = ((int64_t)B * D) / (balanced ? 2048 / waves : 2048);
     if (G < 8) G = 8;
     if (G > kMaxG) G = kMaxG;
@@ -450,9 +462,58 @@ int bwd_channels_per_group(int B, int D, int N, int64_t, bool balanced) {
     return (int)G;
 }
 
+// Few rows and a long sequence: one workgroup per row group would leave most of the chip idle, so the time axis is cut
+// into chunks (selective_bwd_carry.hip).  Measured on one batch entry of 512-2048 channels and 16k-64k steps: what
+// counts is to have as many workgroups as the chip holds at once (two per CU with four wavefronts each) and not more
+// (768 workgroups: a second, half-empty round, 20-30 % slower than 512), with as many channels each as that allows
+// (staging of the maps and flush of dBm/dCm are paid per workgroup and tile: G = 8 -> 64 is 25 % faster at equal
+// workgroup count).  So: the largest G for which some chunk count fills the chip without exceeding it.
+BwdPlan bwd_plan(int rowsg, int dpg, int N, int64_t L, int mode, bool balanced) {
+    BwdPlan pl;
+    pl.G = bwd_channels_per_group(rowsg, dpg, N, L, balanced);
+    pl.nchunks = 1;
+    pl.tiles_per_chunk = (L + kBwdTileSteps - 1) / kBwdTileSteps;
+    if (mode == 1 || !balanced) return pl;
+    const int64_t ntiles = pl.tiles_per_chunk;
+    const int64_t full = 2048 / bwd_waves_per_workgroup(N);                   // workgroups the chip holds at once
+    const int64_t single = (int64_t)rowsg * ((dpg + pl.G - 1) / pl.G);
+    if (mode == 0 && single * 4 >= full * 3) return pl;                        // enough rows already
+    int64_t cmax = ntiles;                                                     // asked for: down to one tile per chunk
+    if (mode == 0) {                                                           // automatic: four tiles or more per chunk,
+        cmax = ntiles / 4;                                                     // two when the sequence is short
+        if (cmax < 4) cmax = ntiles / 2 < 4 ? ntiles / 2 : 4;
+    }
+    if (cmax > 64) cmax = 64;
+    int bestG = 0, bestC = 1;
+    int64_t bestW = 0;
+    for (int64_t c = 2; c <= cmax; ++c) {
+        const int64_t nb = full / ((int64_t)rowsg * c);                        // channel blocks per row group that fit
+        if (nb < 1) break;
+        int64_t g = (dpg + nb - 1) / nb;
+        if (g < 8) g = 8;
+        if (g > kMaxG) continue;                                               // would need more blocks than fit
+        if (g > dpg) g = dpg;
+        const int64_t blocks = (dpg + g - 1) / g;
+        g = (dpg + blocks - 1) / blocks;                                       // even split
+        const int64_t wgs = (int64_t)rowsg * blocks * c;
+        // fuller chip first; among equally full ones more channels per workgroup
+        if (wgs > bestW || (wgs == bestW && g > bestG)) { bestW = wgs; bestG = (int)g; bestC = (int)c; }
+    }
+    if (bestC < 2) {
+        if (mode != 2 || ntiles < 2) return pl;
+        bestC = 2; bestG = pl.G;                                               // asked for: two chunks at least
+    } else if (mode == 0 && bestW <= single) {
+        return pl;                                                             // chunking would not fill the chip better
+    }
+    pl.G = bestG;
+    pl.tiles_per_chunk = (ntiles + bestC - 1) / bestC;
+    pl.nchunks = (int)((ntiles + pl.tiles_per_chunk - 1) / pl.tiles_per_chunk);   // no empty trailing chunk
+    return pl;
+}
+
 template <typename IO, int N, int NK, int DISC, int T = 8>
 static hipError_t launch_bwd_n(const BwdParams &p, hipStream_t s) {
-    dim3 grid(p.bcg * ((p.dpg + p.G - 1) / p.G), p.B);
+    dim3 grid(p.bcg * ((p.dpg + p.G - 1) / p.G), p.B, p.nchunks > 1 ? p.nchunks : 1);
     hipLaunchKernelGGL((k_ss_bwd<IO, N, NK, T, DISC>), grid, dim3((N / NK) * 64), 0, s, p);
     return hipGetLastError();
 }

@@ -1,0 +1,183 @@
+// Chunked backward selective scan for gfx950, first two launches: the adjoint aggregate of every chunk of the time
+// axis and the chain over them.  The backward pass of Eq. 2 of the paper runs the adjoint recurrence
+//     H_l = Cm_{l,n} dypre_l + a_{l+1} H_{l+1}
+// from the last step to the first; one workgroup per row group walks the whole sequence.  With few rows and a long
+// sequence that leaves most of the chip idle, so the time axis is cut into chunks that run side by side (the same
+// idea as the forward pass's separate chunk-carry launch for very long L).  A chunk [l0, l1] needs the adjoint
+// entering it from the later side, h_in = a_{l1+1} H_{l1+1}; what it hands to the earlier side is affine in it:
+//     h_out = a_{l0} H_{l0} = Q + P h_in,   P = prod_{l0 <= j <= l1} a_j,   Q = sum_{l0 <= l <= l1} (prod_{l0 <= j <= l} a_j) Cm_l dypre_l.
+// k_ss_bwd_agg computes (P, Q) per (row, chunk, state); k_ss_bwd_carry chains them from the last chunk (h_in = 0) to
+// the first and leaves every chunk's h_in; the backward kernel proper then starts each chunk from it.  The forward
+// state needs no such chain: every tile restarts from the forward pass's checkpoint.
+//
+// Mapping of k_ss_bwd_agg: that of the forward kernel.  Time on lanes (a lane owns T = 8 consecutive steps), one
+// wavefront per channel, the 8 wavefronts of a workgroup share the Cm tile staged in LDS as fp32; the lanes' pairs
+// are composed by the suffix scan, lane 0 ends up with the tile's pair, and the chunk's pair is carried from tile to
+// tile in lane n of two registers.
+#include "kernels.hpp"
+#include "scan_common.hpp"
+
+namespace lrnnx {
+
+template <typename IO, int N, int DISC>
+__global__ __launch_bounds__(512, 2) void k_ss_bwd_agg(const BwdParams p) {
+    constexpr int T = 8, W = 8;
+    constexpr int TQ = T / 4;
+    constexpr int QS = 256 + 32 / TQ;                  // floats per quarter-plane, padded against bank conflicts on staging
+    constexpr int PLANE = TQ * QS;
+    constexpr int TILE = 64 * T;
+    __shared__ __attribute__((aligned(16))) float sC[N * PLANE];
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int b = blockIdx.y;
+    const int chunk = blockIdx.z;
+    // a workgroup takes W consecutive channels of ONE Bm/Cm group (it stages that group's Cm in LDS)
+    const int blk_per_grp = (p.dpg + W - 1) / W;
+    const int grp = blockIdx.x / blk_per_grp;
+    const int d_in = (blockIdx.x % blk_per_grp) * W + w;
+    const bool active = d_in < p.dpg;
+    const int d = grp * p.dpg + (active ? d_in : p.dpg - 1);
+    // the chunk's steps [s0, s1) of the sequence; s0 is a multiple of the backward tile (256 steps)
+    const int64_t s0 = (int64_t)chunk * p.tiles_per_chunk * kBwdTileSteps;
+    const int64_t s1 = (s0 + p.tiles_per_chunk * kBwdTileSteps < p.L) ? s0 + p.tiles_per_chunk * kBwdTileSteps : p.L;
+    const int64_t Lc = s1 - s0;
+    const int64_t ntiles = (Lc + TILE - 1) / TILE;
+    const bool vec = p.vec != 0;
+    const bool has_z = p.z != nullptr;
+
+    const IO *drow = reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd + s0;
+    const IO *gyrow = reinterpret_cast<const IO *>(p.dy) + b * p.dy_sb + d * p.dy_sd + s0;
+    const IO *zrow = has_z ? reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd + s0 : nullptr;
+    const IO *Cm = reinterpret_cast<const IO *>(p.Cm) + (((int64_t)b * p.bcg + grp) * p.L + s0) * N;
+
+    // lane n holds A[d,n] and the chunk's pair of state n
+    const float Av = (lane < N) ? p.A[d * N + lane] : 0.0f;
+    const float bias = p.bias ? p.bias[d] : 0.0f;
+    float pcv = 1.0f, qcv = 0.0f;
+
+    for (int64_t tile = ntiles - 1; tile >= 0; --tile) {
+        const int64_t l0 = tile * TILE;
+        const int64_t ll = l0 + lane * T;
+
+        // ---- stage the Cm tile (all wavefronts), fp32, layout [n][t/4][lane][t%4]; rows past the chunk read as zero
+        __syncthreads();
+        for (int r = threadIdx.x; r < TILE; r += W * 64) {
+            float cv[N];
+            const int64_t l = l0 + r;
+            if (l < Lc) {
+                load_row<IO, N>(Cm + l * N, cv);
+            } else {
+#pragma unroll
+                for (int k = 0; k < N; ++k) cv[k] = 0.0f;
+            }
+            const int off = ((r % T) / 4) * QS + (r / T) * 4 + (r % 4);
+#pragma unroll
+            for (int k = 0; k < N; ++k) sC[k * PLANE + off] = cv[k];
+        }
+        __syncthreads();
+        if (!active) continue;
+
+        // ---- this lane's T steps of Delta and of the gradient reaching ypre
+        float dl[T], dyp[T], zv[T];
+        load_seg<IO, T>(drow, ll, Lc, vec, dl);
+        load_seg<IO, T>(gyrow, ll, Lc, vec, dyp);
+        if (has_z) load_seg<IO, T>(zrow, ll, Lc, vec, zv);
+        float sum_dl = 0.0f;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            float sp, sg, gp, zf;
+            bwd_step_inputs(dl[t] + bias, dyp[t], has_z ? zv[t] : 0.0f, p.softplus != 0, has_z, sp, sg, gp, zf);
+            dl[t] = (ll + t < Lc) ? sp : 0.0f;        // steps past the end are the identity (a = 1, no source term)
+            dyp[t] = (ll + t < Lc) ? gp : 0.0f;
+            sum_dl += dl[t];
+        }
+
+#pragma unroll 1
+        for (int n = 0; n < N; ++n) {
+            const ACoef ac = make_acoef<DISC>(readlane(Av, n));
+            float4 Cc[TQ];
+#pragma unroll
+            for (int q = 0; q < TQ; ++q) Cc[q] = *reinterpret_cast<const float4 *>(&sC[n * PLANE + q * QS + lane * 4]);
+            // the lane's pair: Q = a_0 (c_0 + a_1 (c_1 + ...)), P = a_0 a_1 ... a_{T-1}
+            float P = 1.0f, Q = 0.0f;
+#pragma unroll
+            for (int t = T - 1; t >= 0; --t) {
+                float a, g;
+                disc_ag<DISC>(dl[t], ac, a, g);
+                const float Ct = reinterpret_cast<const float *>(&Cc[t / 4])[t % 4];
+                Q = a * __builtin_fmaf(Ct, dyp[t], Q);
+                if constexpr (DISC == DISC_BILINEAR) P *= a;
+            }
+            if constexpr (DISC != DISC_BILINEAR) P = exp2_fast(sum_dl * ac.A2);
+            wave_scan_rev(P, Q, lane);                                // lane 0: the tile's pair
+            const float Pt = readlane(P, 0), Qt = readlane(Q, 0);
+            // this tile lies before what has been accumulated so far: (Pt, Qt) o (Pc, Qc)
+            qcv = writelane(qcv, __builtin_fmaf(Pt, readlane(qcv, n), Qt), n);
+            pcv = writelane(pcv, Pt * readlane(pcv, n), n);
+        }
+    }
+
+    if (active && lane < N) {
+        const int64_t j = (((int64_t)b * p.D + d) * p.nchunks + chunk) * N + lane;
+        p.ws_P[j] = pcv;
+        p.ws_Q[j] = qcv;
+    }
+}
+
+// Chains the chunk aggregates of one (b,d,n) from the last chunk to the first: the adjoint entering chunk c from
+// the later side is Q_{c+1} + P_{c+1} (that entering chunk c+1), zero for the last chunk.  ws_Q[c] is replaced by it.
+__global__ void k_ss_bwd_carry(const BwdParams p) {
+    const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    const int64_t total = (int64_t)p.B * p.D * p.N;
+    if (i >= total) return;
+    const int64_t row = i / p.N;
+    const int n = (int)(i % p.N);
+    float h = 0.0f;
+    for (int c = p.nchunks - 1; c >= 0; --c) {
+        const int64_t j = (row * p.nchunks + c) * p.N + n;
+        const float P = p.ws_P[j], Q = p.ws_Q[j];
+        p.ws_Q[j] = h;
+        h = __builtin_fmaf(P, h, Q);
+    }
+}
+
+// ---------------------------------------------------------------- launchers
+template <typename IO, int N, int DISC>
+static hipError_t launch_agg_n(const BwdParams &p, hipStream_t s) {
+    dim3 grid(p.bcg * ((p.dpg + 7) / 8), p.B, p.nchunks);
+    hipLaunchKernelGGL((k_ss_bwd_agg<IO, N, DISC>), grid, dim3(512), 0, s, p);
+    return hipGetLastError();
+}
+template <typename IO, int DISC>
+static hipError_t launch_agg_disc(const BwdParams &p, hipStream_t s) {
+    switch (p.N) {
+        case 1: return launch_agg_n<IO, 1, DISC>(p, s);
+        case 2: return launch_agg_n<IO, 2, DISC>(p, s);
+        case 4: return launch_agg_n<IO, 4, DISC>(p, s);
+        case 8: return launch_agg_n<IO, 8, DISC>(p, s);
+        case 16: return launch_agg_n<IO, 16, DISC>(p, s);
+        case 32: return launch_agg_n<IO, 32, DISC>(p, s);
+    }
+    return hipErrorInvalidValue;
+}
+template <typename IO>
+static hipError_t launch_agg_io(const BwdParams &p, int disc, hipStream_t s) {
+    switch (disc) {
+        case DISC_ZOH_S6: return launch_agg_disc<IO, DISC_ZOH_S6>(p, s);
+        case DISC_ZOH: return launch_agg_disc<IO, DISC_ZOH>(p, s);
+        case DISC_BILINEAR: return launch_agg_disc<IO, DISC_BILINEAR>(p, s);
+        case DISC_DIRAC: return launch_agg_disc<IO, DISC_DIRAC>(p, s);
+    }
+    return hipErrorInvalidValue;
+}
+hipError_t launch_ss_bwd_agg(const BwdParams &p, int io_dtype, int disc, hipStream_t s) {
+    return io_dtype == 1 ? launch_agg_io<bf16_t>(p, disc, s) : launch_agg_io<float>(p, disc, s);
+}
+hipError_t launch_ss_bwd_carry(const BwdParams &p, hipStream_t s) {
+    const int64_t total = (int64_t)p.B * p.D * p.N;
+    hipLaunchKernelGGL(k_ss_bwd_carry, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace lrnnx

@@ -21,7 +21,7 @@ def api():
     return _api
 
 
-def _check(api, oracle, io, disc, softplus, use_fwd_ckpt, **shape):
+def _check(api, oracle, io, disc, softplus, use_fwd_ckpt, path="auto", **shape):
     p = workloads.make_selective(io=io, with_dy=True, **shape)
     if not softplus:
         p["delta"] = workloads._io_round(np.abs(p["delta"]) * 0.1 + 0.01, io)
@@ -31,7 +31,7 @@ def _check(api, oracle, io, disc, softplus, use_fwd_ckpt, **shape):
     ckpt = None
     if use_fwd_ckpt:
         _, ckpt = api.lrnnx_selective_scan_fwd(**t, disc=disc, delta_softplus=softplus, return_ckpt=True)
-    g = api.lrnnx_selective_scan_bwd(**t, dy=dy, ckpt=ckpt, disc=disc, delta_softplus=softplus, want_dx0=True)
+    g = api.lrnnx_selective_scan_bwd(**t, dy=dy, ckpt=ckpt, disc=disc, delta_softplus=softplus, want_dx0=True, path=path)
     r = oracle.selective_scan_bwd(p["u"], p["delta"], p["A"], p["Bm"], p["Cm"], p["dy"], Dskip=p["Dskip"],
                                   delta_bias=p["delta_bias"], z=p["z"], x0=p["x0"], disc=disc,
                                   delta_softplus=softplus)
@@ -83,6 +83,32 @@ def test_many_channels_per_group_and_groups(api, oracle):
     _check(api, oracle, "bf16", "zoh_s6", True, True, B=2, D=300, N=16, L=640, gate=True, seed=82)
 
 
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("disc", ["zoh_s6", "zoh", "bilinear", "dirac"])
+def test_chunked_over_time(api, oracle, io, disc):
+    """path = chunk_carry: the time axis is cut into chunks that run side by side, each started from the adjoint
+    carried in from the later chunks (ragged last chunk, with and without the forward pass's checkpoints)."""
+    _check(api, oracle, io, disc, True, True, path="chunk_carry", B=1, D=5, N=16, L=2100, gate=True, with_x0=True, seed=90,
+           bias=("uniform", -4.0, -2.0))
+    _check(api, oracle, io, disc, True, False, path="chunk_carry", B=2, D=9, N=4, L=1300, gate=False, with_x0=True, seed=91)
+
+
+@pytest.mark.parametrize("N", [1, 2, 8, 32])
+def test_chunked_over_time_state_sizes_and_groups(api, oracle, N):
+    _check(api, oracle, "bf16", "zoh_s6", True, True, path="chunk_carry", B=2, D=12, N=N, L=1800, gate=True, seed=92 + N,
+           bc_groups=3)
+    _check(api, oracle, "f32", "zoh_s6", False, True, path="chunk_carry", B=1, D=3, N=N, L=257, gate=True, seed=93 + N)
+
+
+def test_auto_path_chunks_long_sequences_with_few_rows(api, oracle):
+    """One batch entry, a handful of channels, 8192 steps: the automatic choice is the chunked path (the workspace the
+    binding allocates allows it); both it and the forced single pass match the oracle."""
+    shape = dict(B=1, D=8, N=16, L=8192, gate=True, with_x0=True, seed=94, bias=("uniform", -4.0, -2.0))
+    _check(api, oracle, "bf16", "zoh_s6", True, True, path="auto", **shape)
+    _check(api, oracle, "bf16", "zoh_s6", True, True, path="single_pass", **shape)
+    assert api.lib().lrnnx_selective_scan_bwd_chunks(1, 8, 16, 8192, 1, 0) > 1
+
+
 def test_non_reduced_outputs_are_deterministic(api):
     import torch
     p = workloads.make_selective(B=2, D=24, N=16, L=1100, io="bf16", gate=True, seed=83)
@@ -102,3 +128,13 @@ def test_error_codes(api):
     with pytest.raises(api.LrnnxError) as e:
         api.lrnnx_selective_scan_bwd(**t, dy=dy, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
     assert e.value.code == 3                                   # no ckpt and workspace too small
+    _, ck = api.lrnnx_selective_scan_fwd(**t, return_ckpt=True)
+    p2 = workloads.make_selective(B=1, D=4, N=4, L=600, io="f32")
+    t2 = sel_inputs_dev(p2, "f32")
+    _, ck2 = api.lrnnx_selective_scan_fwd(**t2, return_ckpt=True)
+    with pytest.raises(api.LrnnxError) as e:
+        api.lrnnx_selective_scan_bwd(**t2, dy=dev(p2["dy"]), ckpt=ck2, path="chunk_carry",
+                                     workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == 3                                   # the chunked path needs room for its aggregates
+    # one tile only: nothing to cut, the forced chunked path is the single pass
+    api.lrnnx_selective_scan_bwd(**t, dy=dy, ckpt=ck, path="chunk_carry")
