@@ -57,14 +57,17 @@ def test_generation_loop_of_step_calls_replays(api):
         _eager_noise(torch)
 
 
-def test_forward_backward_pair_replays(api):
+@pytest.mark.parametrize("path", ["single_pass", "chunk_carry"])
+def test_forward_backward_pair_replays(api, path):
+    """Forward + backward captured in one graph; the chunked backward path (three more launches, its aggregates in
+    the workspace) replays like the single pass."""
     import torch
     p = workloads.make_selective(B=2, D=32, N=16, L=1500, io="bf16", gate=True, seed=4, bias=("uniform", -4.0, -2.0))
     t = dict(u=dev(p["u"], "bf16"), delta=dev(p["delta"], "bf16"), A=dev(p["A"]), Bm=dev(p["Bm"], "bf16"),
              Cm=dev(p["Cm"], "bf16"), Dskip=dev(p["Dskip"]), delta_bias=dev(p["delta_bias"]), z=dev(p["z"], "bf16"))
     dy = dev(p["dy"], "bf16")
     y_ref, ck_ref = api.lrnnx_selective_scan_fwd(**t, return_ckpt=True)
-    g_ref = api.lrnnx_selective_scan_bwd(**t, dy=dy, ckpt=ck_ref)
+    g_ref = api.lrnnx_selective_scan_bwd(**t, dy=dy, ckpt=ck_ref, path=path)
     torch.cuda.synchronize()
 
     y, ck = torch.empty_like(y_ref), torch.empty_like(ck_ref)
@@ -73,10 +76,11 @@ def test_forward_backward_pair_replays(api):
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         api.lrnnx_selective_scan_fwd(**t, out=y, ckpt_out=ck, workspace=ws)
-        api.lrnnx_selective_scan_bwd(**t, dy=dy, ckpt=ck, outs=outs, workspace=ws)
+        api.lrnnx_selective_scan_bwd(**t, dy=dy, ckpt=ck, outs=outs, workspace=ws, path=path)
     for _ in range(3):
         for v in (y, ck, *outs.values()):
             v.fill_(7.0)                                   # stale contents must not survive a replay
+        ws.fill_(255)
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(y, y_ref) and torch.equal(ck, ck_ref)

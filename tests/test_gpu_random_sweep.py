@@ -47,7 +47,8 @@ def test_random_case(api, oracle, c):
     t = sel_inputs_dev(p, io)
     kw = dict(disc=c["disc"], delta_softplus=c["softplus"])
     y, x_last, ckpt = api.lrnnx_selective_scan_fwd(**t, **kw, path=c["path"], return_last_state=True, return_ckpt=True)
-    g = api.lrnnx_selective_scan_bwd(**t, dy=dev(p["dy"], io), ckpt=None if c["own_ckpt"] else ckpt, want_dx0=True, **kw)
+    g = api.lrnnx_selective_scan_bwd(**t, dy=dev(p["dy"], io), ckpt=None if c["own_ckpt"] else ckpt, want_dx0=True,
+                                     path=c["path"], **kw)
     okw = dict(Dskip=p["Dskip"], delta_bias=p["delta_bias"], z=p["z"], x0=p["x0"], **kw)
     yr, xr = oracle.selective_scan_fwd(p["u"], p["delta"], p["A"], p["Bm"], p["Cm"], **okw)
     r = oracle.selective_scan_bwd(p["u"], p["delta"], p["A"], p["Bm"], p["Cm"], p["dy"], **okw)
