@@ -381,7 +381,18 @@ def _other_configs(api, torch, dev):
         tt = _time(torch, lambda: api.lrnnx_selective_scan_fwd(**t3, path=path, out=y3, workspace=ws3), 5)
         out[f"c3_fwd_{path}"] = {"us": tt * 1e6, "elements_per_s": B3 * D3 * N3 * L3 / tt, "hbm_GBs": nb / tt / 1e9,
                                  "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
-    del t3, y3, ws3
+    # the backward pass at config 3's shape (one batch entry: few rows, long sequence), single pass and chunked
+    dy3 = torch.randn(B3, D3, L3, device=dev, generator=g).to(bf)
+    _, ck3 = api.lrnnx_selective_scan_fwd(**t3, out=y3, workspace=ws3, return_ckpt=True)
+    outs3 = {}
+    nb = _selective_bytes(B3, D3, N3, L3, 2, False, True) + ck3.numel() * 4
+    for path in ("single_pass", "chunk_carry"):
+        tt = _time(torch, lambda: outs3.update(api.lrnnx_selective_scan_bwd(**t3, dy=dy3, ckpt=ck3, outs=outs3, path=path)), 3,
+                   warm=2)
+        out[f"c3_shape_bwd_{path}"] = {"us": tt * 1e6, "elements_per_s": B3 * D3 * N3 * L3 / tt, "hbm_GBs": nb / tt / 1e9,
+                                       "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS,
+                                       "chunks": int(api.lib().lrnnx_selective_scan_bwd_chunks(B3, D3, N3, L3, 1, api.PATH[path]))}
+    del t3, y3, ws3, dy3, ck3, outs3
 
     # config 4: backward only (checkpoints from one untimed forward)
     B4, D4, N4, L4 = 16, 2560, 16, 4096

@@ -84,14 +84,18 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
         e = e < o ? o : (e > p.L ? p.L : e);
         toff = o; L = e - o; bs = 0;
     }
-    const int64_t ntiles = (L + TILE - 1) / TILE;
-    // chunked launch: this workgroup walks the tiles of chunk blockIdx.z only, starting from that chunk's carried adjoint
+    // Chunked launch: this workgroup walks chunk blockIdx.z of its rows only, i.e. the steps toff .. toff + L - 1 of
+    // the sequence, starting from that chunk's carried adjoint.
     const int chunk = blockIdx.z;
-    const int64_t tile_lo = p.nchunks > 1 ? chunk * p.tiles_per_chunk : 0;
-    const int64_t tile_hi = (p.nchunks > 1 && tile_lo + p.tiles_per_chunk < ntiles) ? tile_lo + p.tiles_per_chunk : ntiles;
+    if (p.nchunks > 1) {
+        const int64_t span = p.tiles_per_chunk * TILE;
+        toff = chunk * span;
+        L = (p.L - toff < span) ? p.L - toff : span;
+    }
+    const int64_t ntiles = (L + TILE - 1) / TILE;
     // checkpoints of this workgroup's rows: [B,D,nck,N], or packed [D,nslots,N] with sequence b at slot toff/interval + b
-    const int64_t nck = p.cu ? p.nslots : (L + kCkptInterval - 1) / kCkptInterval;
-    const int64_t ck0 = p.cu ? toff / kCkptInterval + b : 0;
+    const int64_t nck = p.cu ? p.nslots : (p.L + kCkptInterval - 1) / kCkptInterval;
+    const int64_t ck0 = p.cu ? toff / kCkptInterval + b : toff / kCkptInterval;
     const bool vec = p.vec != 0 && (toff % 8) == 0;
     const bool has_z = p.z != nullptr;
 
@@ -112,7 +116,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     const bool io_thread = NA == NT || tid < NA;                     // wave-uniform: NA is a multiple of 64
     auto fslot = [](int f) { return (((f % T) / 4) * 64 + f / T) * 4 + (f % 4); };
 
-    for (int64_t tile = tile_hi - 1; tile >= tile_lo; --tile) {
+    for (int64_t tile = ntiles - 1; tile >= 0; --tile) {
         const int64_t l0 = tile * TILE;
         const int rem = (L - l0 < TILE) ? (int)(L - l0) : TILE;      // valid steps of this tile
         // all global addresses below are a wave-uniform base plus a small unsigned per-lane offset, so that
