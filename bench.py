@@ -391,7 +391,7 @@ def _other_configs(api, torch, dev):
                    warm=2)
         out[f"c3_shape_bwd_{path}"] = {"us": tt * 1e6, "elements_per_s": B3 * D3 * N3 * L3 / tt, "hbm_GBs": nb / tt / 1e9,
                                        "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS,
-                                       "chunks": int(api.lib().lrnnx_selective_scan_bwd_chunks(B3, D3, N3, L3, 1, api.PATH[path]))}
+                                       "chunks": int(api.lib().lrnnx_selective_scan_bwd_chunks(B3, D3, N3, L3, 1, api.PATH[path], 0))}
     del t3, y3, ws3, dy3, ck3, outs3
 
     # config 4: backward only (checkpoints from one untimed forward)

@@ -215,6 +215,11 @@ typedef struct lrnnx_ss_bwd_complex_args {
                                     [G,L,N], ckpt [D, lrnnx_packed_ckpt_slots(L,B), N] and the workspace that replaces
                                     it D * lrnnx_packed_ckpt_slots(L,B) * N float pairs); callers built against the
                                     shorter struct get NULL */
+    int32_t path;                /* lrnnx_path, as in lrnnx_ss_bwd_args: CHUNK_CARRY cuts the time axis into chunks
+                                    that run side by side; its aggregates (2 * B * D * chunks * N float pairs) go into
+                                    the workspace, after the 256-byte-aligned checkpoints of the recompute sweep if
+                                    ckpt == NULL.  Callers built against a shorter struct get AUTO. */
+    int32_t reserved;
 } lrnnx_ss_bwd_complex_args;
 
 int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *args);
@@ -463,10 +468,10 @@ typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2, LRNNX_WS_LT
  * io_dtype is LRNNX_F32 or LRNNX_C64).  Returns 0 for invalid sizes.   */
 size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t L, int io_dtype);
 
-/* Number of chunks lrnnx_selective_scan_bwd cuts the time axis into for these sizes and this `path` when its
- * workspace allows it (1: single pass); the aggregates then take 2 * B * D * chunks * N floats of the workspace.
- * 0 for invalid sizes.                                                                                         */
-int lrnnx_selective_scan_bwd_chunks(int64_t B, int64_t D, int64_t N, int64_t L, int bc_groups, int path);
+/* Number of chunks lrnnx_selective_scan_bwd (complex_a = 0) or lrnnx_selective_scan_bwd_complex (complex_a = 1) cuts
+ * the time axis into for these sizes and this `path` when its workspace allows it (1: single pass); the aggregates
+ * then take 2 * B * D * chunks * N floats (float pairs for the complex scan) of the workspace.  0 for invalid sizes. */
+int lrnnx_selective_scan_bwd_chunks(int64_t B, int64_t D, int64_t N, int64_t L, int bc_groups, int path, int complex_a);
 
 const char *lrnnx_status_string(int status);
 int lrnnx_version(void);   /* major * 100 + minor; grows whenever an entry point or a struct field is added */

@@ -73,6 +73,7 @@ class BwdComplexArgs(ctypes.Structure):
         ("dz", _vp), ("dz_stride_b", _i64), ("dz_stride_d", _i64),
         ("dA", _vp), ("dBm", _vp), ("dCm", _vp), ("dD", _vp), ("dbias", _vp), ("dx0", _vp),
         ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp), ("cu_seqlens", _vp),
+        ("path", _i32), ("reserved", _i32),
     ]
 
 
@@ -195,7 +196,7 @@ def lib():
             f.restype = ctypes.c_int
         L.lrnnx_workspace_bytes.argtypes = [ctypes.c_int, _i64, _i64, _i64, _i64, ctypes.c_int]
         L.lrnnx_workspace_bytes.restype = _sz
-        L.lrnnx_selective_scan_bwd_chunks.argtypes = [_i64, _i64, _i64, _i64, ctypes.c_int, ctypes.c_int]
+        L.lrnnx_selective_scan_bwd_chunks.argtypes = [_i64, _i64, _i64, _i64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.lrnnx_selective_scan_bwd_chunks.restype = ctypes.c_int
         L.lrnnx_ckpt_interval.restype = _i64
         L.lrnnx_status_string.argtypes = [ctypes.c_int]
@@ -465,12 +466,12 @@ def _check_complex_maps(A, Bm, Cm, io, Bsz, D, L):
 @_device_checked
 def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,
                                      ckpt=None, disc="zoh_s6", delta_softplus=True, want_dx0=False, outs=None,
-                                     workspace=None, cu_seqlens=None):
+                                     workspace=None, cu_seqlens=None, path="auto"):
     """Gradients of sum(dy*y) of the complex-A selective scan as a dict; see lrnnx_ss_bwd_complex_args.
     dA [D,N], dBm, dCm [B,L,N], dx0 [B,D,N] are complex64 (dLoss/dRe + i dLoss/dIm); du, ddelta, dz in the I/O
     type; dD, dbias float32.  `ckpt`: the checkpoints a forward call returned (else they are recomputed).
     `cu_seqlens`: packed variable-length mode as in the forward call (du, ddelta, dz are [D,L]; dBm, dCm [L,N] or
-    [G,L,N]; dx0 [S,D,N])."""
+    [G,L,N]; dx0 [S,D,N]).  `path`: "auto", "single_pass" or "chunk_carry" as for the real scan."""
     io = u.dtype
     packed = cu_seqlens is not None
     if packed:
@@ -500,6 +501,7 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
     a.B, a.D, a.N, a.L = Bsz, D, N, L
     a.bc_groups = G
     a.cu_seqlens = _ptr(cu_seqlens)
+    a.path = PATH[path] if isinstance(path, str) else int(path)
     a.io_dtype = _io_dtype(u)
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
     a.delta_softplus = int(bool(delta_softplus))
@@ -532,10 +534,16 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
         a.dbias = new("dbias", (D,), torch.float32).data_ptr()
     if want_dx0:
         a.dx0 = new("dx0", (Bsz, D, N), c64).data_ptr()
-    if workspace is None and ckpt is None:
-        nbytes = (D * (L // I + Bsz) * N * 8 if packed
-                  else lrnnx_workspace_bytes(WS_BWD_COMPLEX, Bsz, D, N, L, a.io_dtype))
-        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
+    if workspace is None:
+        if packed:
+            nbytes = D * (L // I + Bsz) * N * 8 if ckpt is None else 0
+        else:                                          # checkpoints of the recompute sweep, then the chunk aggregates
+            nch = int(lib().lrnnx_selective_scan_bwd_chunks(Bsz, D, N, L, G, a.path, 1))
+            nbytes = 2 * Bsz * D * nch * N * 8 if nch > 1 else 0
+            if ckpt is None:
+                nbytes += (Bsz * D * -(-L // I) * N * 8 + 255) // 256 * 256
+        if nbytes:
+            workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     if workspace is not None:
         a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
     a.stream = _stream()
@@ -609,7 +617,7 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
         if packed:
             nbytes = D * (L // lrnnx_ckpt_interval() + Bsz) * N * 4 if ckpt is None else 0
         else:                                          # checkpoints of the recompute sweep, then the chunk aggregates
-            nch = int(lib().lrnnx_selective_scan_bwd_chunks(Bsz, D, N, L, a.bc_groups, a.path))
+            nch = int(lib().lrnnx_selective_scan_bwd_chunks(Bsz, D, N, L, a.bc_groups, a.path, 0))
             nbytes = 2 * Bsz * D * nch * N * 4 if nch > 1 else 0
             if ckpt is None:
                 nbytes += (Bsz * D * -(-L // lrnnx_ckpt_interval()) * N * 4 + 255) // 256 * 256

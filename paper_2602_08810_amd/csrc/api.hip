@@ -88,10 +88,12 @@ FillList onepass_fill(const LtiParams &p) {
     return z;
 }
 
-// bytes of the two aggregate arrays [B,D,nchunks,N] of the chunked backward, when that path is asked for
+// bytes of the two aggregate arrays [B,D,nchunks,N] of the chunked backward: the larger of what the automatic choice
+// and an explicit request for that path take
 size_t bwd_carry_bytes(int64_t B, int64_t D, int64_t N, int64_t L) {
-    const BwdPlan pl = bwd_plan((int)B, (int)D, (int)N, L, 2, true);
-    return pl.nchunks > 1 ? (size_t)2 * B * D * pl.nchunks * N * sizeof(float) : 0;
+    const int a = bwd_plan((int)B, (int)D, (int)N, L, 0, true).nchunks, f = bwd_plan((int)B, (int)D, (int)N, L, 2, true).nchunks;
+    const int nch = a > f ? a : f;
+    return nch > 1 ? (size_t)2 * B * D * nch * N * sizeof(float) : 0;
 }
 size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 
@@ -133,14 +135,16 @@ extern "C" {
 
 int64_t lrnnx_ckpt_interval(void) { return kCkptInterval; }
 int64_t lrnnx_packed_ckpt_slots(int64_t L, int64_t B) { return (L < 0 || B < 0) ? 0 : L / kCkptInterval + B; }
-int lrnnx_version(void) { return 135; }   // major * 100 + minor; bumped whenever an entry point or a struct field is added
+int lrnnx_version(void) { return 136; }   // major * 100 + minor; bumped whenever an entry point or a struct field is added
 
-int lrnnx_selective_scan_bwd_chunks(int64_t B, int64_t D, int64_t N, int64_t L, int bc_groups, int path) {
+int lrnnx_selective_scan_bwd_chunks(int64_t B, int64_t D, int64_t N, int64_t L, int bc_groups, int path, int complex_a) {
     const int bcg = bc_groups > 1 ? bc_groups : 1;
-    if (B < 1 || D < 1 || L < 1 || B > 65535 || D > INT32_MAX || !supported_n((int)N) || D % bcg) return 0;
+    if (B < 1 || D < 1 || L < 1 || B > 65535 || D > INT32_MAX || D % bcg) return 0;
+    if (!(complex_a ? supported_n_complex((int)N) : supported_n((int)N))) return 0;
     if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return 0;
     if (path == LRNNX_PATH_SINGLE_PASS) return 1;
-    return bwd_plan((int)B * bcg, (int)(D / bcg), (int)N, L, path, true).nchunks;
+    return complex_a ? cbwd_plan((int)B * bcg, (int)(D / bcg), (int)N, L, path, true).nchunks
+                     : bwd_plan((int)B * bcg, (int)(D / bcg), (int)N, L, path, true).nchunks;
 }
 
 const char *lrnnx_status_string(int status) {
@@ -308,9 +312,13 @@ int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *a) {
 
 int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
     constexpr size_t kOldSize = offsetof(lrnnx_ss_bwd_complex_args, cu_seqlens);  // struct before `cu_seqlens` was appended
+    constexpr size_t kSizeCu = offsetof(lrnnx_ss_bwd_complex_args, path);         // ... and before `path` was
     if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
-    const int64_t *cu = a->struct_size >= sizeof(lrnnx_ss_bwd_complex_args) ? a->cu_seqlens : nullptr;
+    const int64_t *cu = a->struct_size >= kSizeCu ? a->cu_seqlens : nullptr;
+    const int path = a->struct_size >= sizeof(lrnnx_ss_bwd_complex_args) ? a->path : LRNNX_PATH_AUTO;
     if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
+    if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
+    if (cu && path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_UNSUPPORTED;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
@@ -329,6 +337,17 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
                                : (size_t)a->B * a->D * cdiv(a->L, kCkptInterval) * a->N * sizeof(float2);
     if (!a->ckpt && (!a->workspace || a->workspace_bytes < ck_bytes)) return LRNNX_ERR_WORKSPACE;
     hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
+
+    // chunked path: the aggregates live in the workspace, after the checkpoints of the recompute sweep if there are any
+    BwdPlan pl = cbwd_plan(a->B * bcg, a->D / bcg, a->N, a->L, path, cu == nullptr);
+    const size_t carry_off = a->ckpt ? 0 : align256(ck_bytes);
+    if (pl.nchunks > 1) {
+        const size_t need = carry_off + (size_t)2 * a->B * a->D * pl.nchunks * a->N * sizeof(float2);
+        if (!a->workspace || a->workspace_bytes < need) {
+            if (path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_WORKSPACE;
+            pl = cbwd_plan(a->B * bcg, a->D / bcg, a->N, a->L, LRNNX_PATH_SINGLE_PASS, true);
+        }
+    }
 
     const float2 *ckpt = reinterpret_cast<const float2 *>(a->ckpt);
     if (!ckpt) {                                   // state-only forward sweep: writes the checkpoints
@@ -355,7 +374,16 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
     p.A = reinterpret_cast<const float2 *>(a->A); p.ckpt = ckpt;
     p.dA = reinterpret_cast<float2 *>(a->dA); p.dBm = reinterpret_cast<float2 *>(a->dBm);
     p.dCm = reinterpret_cast<float2 *>(a->dCm); p.dx0 = reinterpret_cast<float2 *>(a->dx0);
-    p.G = cbwd_channels_per_group(a->B * bcg, a->D / bcg, a->N);
+    p.G = pl.G;
+    p.nchunks = pl.nchunks;
+    p.tiles_per_chunk = pl.tiles_per_chunk;
+    if (pl.nchunks > 1) {
+        p.ws_P = reinterpret_cast<float2 *>(static_cast<char *>(a->workspace) + carry_off);
+        p.ws_Q = p.ws_P + (size_t)a->B * a->D * p.nchunks * a->N;
+        p.hc = p.ws_Q;
+        if (launch_ss_cbwd_agg(p, a->io_dtype, a->disc, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+        if (launch_ss_cbwd_carry(p, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    }
 
     const int64_t nbc = (cu ? 1 : (int64_t)a->B) * bcg * a->L * a->N * 2;   // floats; packed mode: one time axis for all sequences
     FillList z{};

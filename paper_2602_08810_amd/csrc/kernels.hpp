@@ -63,6 +63,11 @@ struct CBwdParams {
     const void *Bm, *Cm;     // [B,L,N] complex in the I/O type
     float2 *dA, *dBm, *dCm, *dx0;
     float *dD, *dbias;
+    // chunked backward, as in BwdParams below (complex aggregates and carries)
+    int nchunks;
+    int64_t tiles_per_chunk;
+    float2 *ws_P, *ws_Q;
+    const float2 *hc;
 };
 
 struct BwdParams {
@@ -162,6 +167,58 @@ hipError_t launch_ss_bwd_carry(const BwdParams &p, hipStream_t s);              
 struct BwdPlan { int G, nchunks; int64_t tiles_per_chunk; };
 // rowsg = B * (number of Bm/Cm groups), dpg = channels per group; mode 0: automatic, 1: single pass, 2: chunked asked for
 BwdPlan bwd_plan(int rowsg, int dpg, int N, int64_t L, int mode, bool balanced);
+BwdPlan cbwd_plan(int rowsg, int dpg, int N, int64_t L, int mode, bool balanced);          // the complex-A backward
+hipError_t launch_ss_cbwd_agg(const CBwdParams &p, int io_dtype, int disc, hipStream_t s);
+hipError_t launch_ss_cbwd_carry(const CBwdParams &p, hipStream_t s);
+
+// Few rows and a long sequence: one workgroup per row group would leave most of the chip idle, so the time axis is cut
+// into chunks that run side by side.  Measured with the real kernel on one batch entry of 512-2048 channels and
+// 16k-64k steps: what counts is to have as many workgroups as the chip holds at once (`full`) and not more (1.5 x
+// full: a second, half-empty round, 20-30 % slower), with as many channels each as that allows (staging of the maps
+// and flush of dBm/dCm are paid per workgroup and tile: G = 8 -> 64 is 25 % faster at equal workgroup count).  So:
+// the largest G <= maxG for which some chunk count fills the chip without exceeding it; baseG is the single pass's G.
+inline BwdPlan plan_time_chunks(int rowsg, int dpg, int64_t L, int mode, int baseG, int64_t full, int maxG) {
+    BwdPlan pl;
+    pl.G = baseG;
+    pl.nchunks = 1;
+    pl.tiles_per_chunk = (L + kBwdTileSteps - 1) / kBwdTileSteps;
+    if (mode == 1) return pl;
+    const int64_t ntiles = pl.tiles_per_chunk;
+    const int64_t single = (int64_t)rowsg * ((dpg + pl.G - 1) / pl.G);
+    // enough rows already, unless they come as many small workgroups (G at its minimum) that leave room on the chip
+    if (mode == 0 && single * 4 >= full * 3 && (pl.G >= 16 || single >= full)) return pl;
+    int64_t cmax = ntiles;                                                     // asked for: down to one tile per chunk
+    if (mode == 0) {                                                           // automatic: four tiles or more per chunk,
+        cmax = ntiles / 4;                                                     // two when the sequence is short
+        if (cmax < 4) cmax = ntiles / 2 < 4 ? ntiles / 2 : 4;
+    }
+    if (cmax > 64) cmax = 64;
+    int bestG = 0, bestC = 1;
+    int64_t bestW = 0;
+    for (int64_t c = 2; c <= cmax; ++c) {
+        const int64_t nb = full / ((int64_t)rowsg * c);                        // channel blocks per row group that fit
+        if (nb < 1) break;
+        int64_t g = (dpg + nb - 1) / nb;
+        if (g < 8) g = 8;
+        if (g > maxG) continue;                                                // would need more blocks than fit
+        if (g > dpg) g = dpg;
+        const int64_t blocks = (dpg + g - 1) / g;
+        g = (dpg + blocks - 1) / blocks;                                       // even split
+        const int64_t wgs = (int64_t)rowsg * blocks * c;
+        // fuller chip first; among equally full ones more channels per workgroup
+        if (wgs > bestW || (wgs == bestW && g > bestG)) { bestW = wgs; bestG = (int)g; bestC = (int)c; }
+    }
+    if (bestC < 2) {
+        if (mode != 2 || ntiles < 2) return pl;
+        bestC = 2; bestG = pl.G;                                               // asked for: two chunks at least
+    } else if (mode == 0 && bestW <= single) {
+        return pl;                                                             // chunking would not fill the chip better
+    }
+    pl.G = bestG;
+    pl.tiles_per_chunk = (ntiles + bestC - 1) / bestC;
+    pl.nchunks = (int)((ntiles + pl.tiles_per_chunk - 1) / pl.tiles_per_chunk);   // no empty trailing chunk
+    return pl;
+}
 hipError_t launch_lti(const LtiParams &p, hipStream_t s);
 hipError_t launch_lti_onepass(const LtiParams &p, hipStream_t s);
 int lti_onepass_group_steps(int64_t B, int64_t P);   // time steps per chained group for this shape

@@ -466,53 +466,11 @@ int bwd_channels_per_group(int B, int D, int N, int64_t, bool balanced) {
     return (int)G;
 }
 
-// Few rows and a long sequence: one workgroup per row group would leave most of the chip idle, so the time axis is cut
-// into chunks (selective_bwd_carry.hip).  Measured on one batch entry of 512-2048 channels and 16k-64k steps: what
-// counts is to have as many workgroups as the chip holds at once (two per CU with four wavefronts each) and not more
-// (768 workgroups: a second, half-empty round, 20-30 % slower than 512), with as many channels each as that allows
-// (staging of the maps and flush of dBm/dCm are paid per workgroup and tile: G = 8 -> 64 is 25 % faster at equal
-// workgroup count).  So: the largest G for which some chunk count fills the chip without exceeding it.
+// launch shape incl. the chunked path for few rows and long sequences (selective_bwd_carry.hip)
 BwdPlan bwd_plan(int rowsg, int dpg, int N, int64_t L, int mode, bool balanced) {
-    BwdPlan pl;
-    pl.G = bwd_channels_per_group(rowsg, dpg, N, L, balanced);
-    pl.nchunks = 1;
-    pl.tiles_per_chunk = (L + kBwdTileSteps - 1) / kBwdTileSteps;
-    if (mode == 1 || !balanced) return pl;
-    const int64_t ntiles = pl.tiles_per_chunk;
-    const int64_t full = 2048 / bwd_waves_per_workgroup(N);                   // workgroups the chip holds at once
-    const int64_t single = (int64_t)rowsg * ((dpg + pl.G - 1) / pl.G);
-    if (mode == 0 && single * 4 >= full * 3) return pl;                        // enough rows already
-    int64_t cmax = ntiles;                                                     // asked for: down to one tile per chunk
-    if (mode == 0) {                                                           // automatic: four tiles or more per chunk,
-        cmax = ntiles / 4;                                                     // two when the sequence is short
-        if (cmax < 4) cmax = ntiles / 2 < 4 ? ntiles / 2 : 4;
-    }
-    if (cmax > 64) cmax = 64;
-    int bestG = 0, bestC = 1;
-    int64_t bestW = 0;
-    for (int64_t c = 2; c <= cmax; ++c) {
-        const int64_t nb = full / ((int64_t)rowsg * c);                        // channel blocks per row group that fit
-        if (nb < 1) break;
-        int64_t g = (dpg + nb - 1) / nb;
-        if (g < 8) g = 8;
-        if (g > kMaxG) continue;                                               // would need more blocks than fit
-        if (g > dpg) g = dpg;
-        const int64_t blocks = (dpg + g - 1) / g;
-        g = (dpg + blocks - 1) / blocks;                                       // even split
-        const int64_t wgs = (int64_t)rowsg * blocks * c;
-        // fuller chip first; among equally full ones more channels per workgroup
-        if (wgs > bestW || (wgs == bestW && g > bestG)) { bestW = wgs; bestG = (int)g; bestC = (int)c; }
-    }
-    if (bestC < 2) {
-        if (mode != 2 || ntiles < 2) return pl;
-        bestC = 2; bestG = pl.G;                                               // asked for: two chunks at least
-    } else if (mode == 0 && bestW <= single) {
-        return pl;                                                             // chunking would not fill the chip better
-    }
-    pl.G = bestG;
-    pl.tiles_per_chunk = (ntiles + bestC - 1) / bestC;
-    pl.nchunks = (int)((ntiles + pl.tiles_per_chunk - 1) / pl.tiles_per_chunk);   // no empty trailing chunk
-    return pl;
+    const int G = bwd_channels_per_group(rowsg, dpg, N, L, balanced);
+    // two wavefronts per SIMD are what the chip holds of this kernel: 2048 wavefronts
+    return plan_time_chunks(rowsg, dpg, L, balanced ? mode : 1, G, 2048 / bwd_waves_per_workgroup(N), kMaxG);
 }
 
 template <typename IO, int N, int NK, int DISC, int T = 8>

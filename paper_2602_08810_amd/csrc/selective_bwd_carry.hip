@@ -16,6 +16,7 @@
 // tile in lane n of two registers.
 #include "kernels.hpp"
 #include "scan_common.hpp"
+#include "cplx_common.hpp"
 
 namespace lrnnx {
 
@@ -142,6 +143,137 @@ __global__ void k_ss_bwd_carry(const BwdParams p) {
     }
 }
 
+// ---------------------------------------------------------------- the same for the complex-A scan
+// H_l = dypre_l conj(Cm_l) + conj(a_{l+1}) H_{l+1}: the pair of a chunk is P = prod conj(a_j),
+// Q = sum_l (prod_{l0 <= j <= l} conj(a_j)) dypre_l conj(Cm_l).  Only the tile's total is needed, so the lanes take the
+// tile's time slots in reverse order (lane 63 the earliest): the composition "earlier o later" then runs towards
+// higher lanes and is the forward scan, all DPP steps; lane 63 ends up with the tile's pair.
+template <typename IO, int N, int DISC>
+__global__ __launch_bounds__(512, 2) void k_ss_cbwd_agg(const CBwdParams p) {
+    using CW = typename cword<IO>::type;
+    constexpr int T = 8, W = 8;
+    constexpr int TQ = T / 4;
+    constexpr int QS = 256 + 32 / TQ;
+    constexpr int PLANE = TQ * QS;
+    constexpr int TILE = 64 * T;
+    __shared__ __attribute__((aligned(16))) CW sC[N * PLANE];
+
+    const int lane = threadIdx.x & 63;
+    const int slot = 63 - lane;                        // this lane's time slot within a tile
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int b = blockIdx.y;
+    const int chunk = blockIdx.z;
+    const int blk_per_grp = (p.dpg + W - 1) / W;
+    const int grp = blockIdx.x / blk_per_grp;
+    const int d_in = (blockIdx.x % blk_per_grp) * W + w;
+    const bool active = d_in < p.dpg;
+    const int d = grp * p.dpg + (active ? d_in : p.dpg - 1);
+    const int64_t s0 = (int64_t)chunk * p.tiles_per_chunk * kBwdTileSteps;
+    const int64_t s1 = (s0 + p.tiles_per_chunk * kBwdTileSteps < p.L) ? s0 + p.tiles_per_chunk * kBwdTileSteps : p.L;
+    const int64_t Lc = s1 - s0;
+    const int64_t ntiles = (Lc + TILE - 1) / TILE;
+    const bool vec = p.vec != 0;
+    const bool has_z = p.z != nullptr;
+
+    const IO *drow = reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd + s0;
+    const IO *gyrow = reinterpret_cast<const IO *>(p.dy) + b * p.dy_sb + d * p.dy_sd + s0;
+    const IO *zrow = has_z ? reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd + s0 : nullptr;
+    const CW *Cm = reinterpret_cast<const CW *>(p.Cm) + (((int64_t)b * p.bcg + grp) * p.L + s0) * N;
+
+    // lane n holds A[d,n] and the chunk's pair of state n
+    float Arv = 0.0f, Aiv = 0.0f;
+    if (lane < N) { const float2 Av = p.A[d * N + lane]; Arv = Av.x; Aiv = Av.y; }
+    const float bias = p.bias ? p.bias[d] : 0.0f;
+    float pr = 1.0f, pi = 0.0f, qr = 0.0f, qi = 0.0f;
+
+    for (int64_t tile = ntiles - 1; tile >= 0; --tile) {
+        const int64_t l0 = tile * TILE;
+        const int64_t ll = l0 + slot * T;
+
+        // ---- stage the Cm tile (all wavefronts): plain copy of complex words, layout [n][t/4][slot][t%4]
+        __syncthreads();
+        for (int r = threadIdx.x; r < TILE; r += W * 64) {
+            const int64_t l = l0 + r;
+            const int off = ((r % T) / 4) * QS + (r / T) * 4 + (r % 4);
+            CW cw[N];
+            if (l < Lc) {
+#pragma unroll
+                for (int k = 0; k < N; ++k) cw[k] = Cm[l * N + k];
+            } else {
+#pragma unroll
+                for (int k = 0; k < N; ++k) cw[k] = CW{};
+            }
+#pragma unroll
+            for (int k = 0; k < N; ++k) sC[k * PLANE + off] = cw[k];
+        }
+        __syncthreads();
+        if (!active) continue;
+
+        float dl[T], dyp[T], zv[T];
+        load_seg<IO, T>(drow, ll, Lc, vec, dl);
+        load_seg<IO, T>(gyrow, ll, Lc, vec, dyp);
+        if (has_z) load_seg<IO, T>(zrow, ll, Lc, vec, zv);
+        float sum_dl = 0.0f;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            float sp, sg, gp, zf;
+            bwd_step_inputs(dl[t] + bias, dyp[t], has_z ? zv[t] : 0.0f, p.softplus != 0, has_z, sp, sg, gp, zf);
+            dl[t] = (ll + t < Lc) ? sp : 0.0f;        // steps past the end are the identity (a = 1, no source term)
+            dyp[t] = (ll + t < Lc) ? gp : 0.0f;
+            sum_dl += dl[t];
+        }
+
+#pragma unroll 1
+        for (int n = 0; n < N; ++n) {
+            const CCoef cc = make_ccoef(readlane(Arv, n), readlane(Aiv, n));
+            // the lane's pair: Q = conj(a_0) (c_0 + conj(a_1) (c_1 + ...)), P = conj(a_0 a_1 ... a_{T-1})
+            float2 P = make_float2(1.0f, 0.0f), Q = make_float2(0.0f, 0.0f);
+#pragma unroll
+            for (int t = T - 1; t >= 0; --t) {
+                float2 a, g;
+                cdisc_ag<DISC>(dl[t], cc, a, g);
+                const float2 Cv = cword<IO>::unpack(sC[n * PLANE + (t / 4) * QS + slot * 4 + (t % 4)]);
+                const float2 tmp = make_float2(__builtin_fmaf(Cv.x, dyp[t], Q.x), __builtin_fmaf(-Cv.y, dyp[t], Q.y));
+                Q = cxmulc(tmp, a);
+                if constexpr (DISC == DISC_BILINEAR) P = cxmulc(P, a);
+            }
+            if constexpr (DISC != DISC_BILINEAR) {
+                const float2 e = cexp_dt(sum_dl, cc.A2r, cc.Arev);
+                P = make_float2(e.x, -e.y);
+            }
+            cwave_scan_fwd(P, Q);                                      // lane 63 (the earliest slot): the tile's pair
+            const float Ptr = readlane(P.x, 63), Pti = readlane(P.y, 63), Qtr = readlane(Q.x, 63), Qti = readlane(Q.y, 63);
+            // this tile lies before what has been accumulated so far: (Pt, Qt) o (Pc, Qc)
+            const float cqr = readlane(qr, n), cqi = readlane(qi, n), cpr = readlane(pr, n), cpi = readlane(pi, n);
+            qr = writelane(qr, __builtin_fmaf(Ptr, cqr, __builtin_fmaf(-Pti, cqi, Qtr)), n);
+            qi = writelane(qi, __builtin_fmaf(Ptr, cqi, __builtin_fmaf(Pti, cqr, Qti)), n);
+            pr = writelane(pr, Ptr * cpr - Pti * cpi, n);
+            pi = writelane(pi, Ptr * cpi + Pti * cpr, n);
+        }
+    }
+
+    if (active && lane < N) {
+        const int64_t j = (((int64_t)b * p.D + d) * p.nchunks + chunk) * N + lane;
+        p.ws_P[j] = make_float2(pr, pi);
+        p.ws_Q[j] = make_float2(qr, qi);
+    }
+}
+
+__global__ void k_ss_cbwd_carry(const CBwdParams p) {
+    const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    const int64_t total = (int64_t)p.B * p.D * p.N;
+    if (i >= total) return;
+    const int64_t row = i / p.N;
+    const int n = (int)(i % p.N);
+    float2 h = make_float2(0.0f, 0.0f);
+    for (int c = p.nchunks - 1; c >= 0; --c) {
+        const int64_t j = (row * p.nchunks + c) * p.N + n;
+        const float2 P = p.ws_P[j], Q = p.ws_Q[j];
+        p.ws_Q[j] = h;
+        h = cxfma(P, h, Q);
+    }
+}
+
 // ---------------------------------------------------------------- launchers
 template <typename IO, int N, int DISC>
 static hipError_t launch_agg_n(const BwdParams &p, hipStream_t s) {
@@ -173,6 +305,38 @@ static hipError_t launch_agg_io(const BwdParams &p, int disc, hipStream_t s) {
 }
 hipError_t launch_ss_bwd_agg(const BwdParams &p, int io_dtype, int disc, hipStream_t s) {
     return io_dtype == 1 ? launch_agg_io<bf16_t>(p, disc, s) : launch_agg_io<float>(p, disc, s);
+}
+template <typename IO, int DISC>
+static hipError_t launch_cagg_disc(const CBwdParams &p, hipStream_t s) {
+    dim3 grid(p.bcg * ((p.dpg + 7) / 8), p.B, p.nchunks);
+#define LRNNX_CAGG(NN) hipLaunchKernelGGL((k_ss_cbwd_agg<IO, NN, DISC>), grid, dim3(512), 0, s, p); return hipGetLastError()
+    switch (p.N) {
+        case 1: LRNNX_CAGG(1);
+        case 2: LRNNX_CAGG(2);
+        case 4: LRNNX_CAGG(4);
+        case 8: LRNNX_CAGG(8);
+        case 16: LRNNX_CAGG(16);
+    }
+#undef LRNNX_CAGG
+    return hipErrorInvalidValue;
+}
+template <typename IO>
+static hipError_t launch_cagg_io(const CBwdParams &p, int disc, hipStream_t s) {
+    switch (disc) {
+        case DISC_ZOH_S6: return launch_cagg_disc<IO, DISC_ZOH_S6>(p, s);
+        case DISC_ZOH: return launch_cagg_disc<IO, DISC_ZOH>(p, s);
+        case DISC_BILINEAR: return launch_cagg_disc<IO, DISC_BILINEAR>(p, s);
+        case DISC_DIRAC: return launch_cagg_disc<IO, DISC_DIRAC>(p, s);
+    }
+    return hipErrorInvalidValue;
+}
+hipError_t launch_ss_cbwd_agg(const CBwdParams &p, int io_dtype, int disc, hipStream_t s) {
+    return io_dtype == 1 ? launch_cagg_io<bf16_t>(p, disc, s) : launch_cagg_io<float>(p, disc, s);
+}
+hipError_t launch_ss_cbwd_carry(const CBwdParams &p, hipStream_t s) {
+    const int64_t total = (int64_t)p.B * p.D * p.N;
+    hipLaunchKernelGGL(k_ss_cbwd_carry, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p);
+    return hipGetLastError();
 }
 hipError_t launch_ss_bwd_carry(const BwdParams &p, hipStream_t s) {
     const int64_t total = (int64_t)p.B * p.D * p.N;

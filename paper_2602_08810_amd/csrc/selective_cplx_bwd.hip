@@ -67,6 +67,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     constexpr int FL = 8;                            // lanes whose dBm/dCm sums are flushed together
     static_assert(T % 4 == 0 && (T % W == 0 || W % T == 0) && TPW <= 8 && NA % 64 == 0 && NA <= NT, "tile shape");
     static_assert(TILE % kCkptInterval == 0, "tiles must start on checkpoints");
+    static_assert(TILE == kBwdTileSteps, "the chunked launch counts its chunks in tiles of this kernel");
     static_assert(W * 3 * TILE >= 2 * FL * T * N * 2, "flush buffer must fit in the partials area");
 
     __shared__ __attribute__((aligned(16))) float sIn[2][5 * TILE];       // two channels in flight: delta, u, dypre, d softplus, dz factor; [q][lane][4]
@@ -100,15 +101,26 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
         e = e < o ? o : (e > p.L ? p.L : e);
         toff = o; L = e - o; bs = 0;
     }
+    // Chunked launch: this workgroup walks chunk blockIdx.z of its rows only, i.e. the steps toff .. toff + L - 1 of
+    // the sequence, starting from that chunk's carried adjoint.
+    const int chunk = blockIdx.z;
+    if (p.nchunks > 1) {
+        const int64_t span = p.tiles_per_chunk * TILE;
+        toff = chunk * span;
+        L = (p.L - toff < span) ? p.L - toff : span;
+    }
     const int64_t ntiles = (L + TILE - 1) / TILE;
     // checkpoints of this workgroup's rows: [B,D,nck,N], or packed [D,nslots,N] with sequence b at slot toff/interval + b
-    const int64_t nck = p.cu ? p.nslots : (L + kCkptInterval - 1) / kCkptInterval;
-    const int64_t ck0 = p.cu ? toff / kCkptInterval + b : 0;
+    const int64_t nck = p.cu ? p.nslots : (p.L + kCkptInterval - 1) / kCkptInterval;
+    const int64_t ck0 = p.cu ? toff / kCkptInterval + b : toff / kCkptInterval;
     const bool vec = p.vec != 0 && (toff % 8) == 0;
     const bool has_z = p.z != nullptr;
 
     for (int i = tid; i < kMaxGc * N; i += NT) {
-        sH[i] = make_float2(0.0f, 0.0f);
+        float2 h = make_float2(0.0f, 0.0f);
+        if (p.nchunks > 1 && i < Gact * N)
+            h = p.hc[(((int64_t)b * p.D + d0 + i / N) * p.nchunks + chunk) * N + i % N];
+        sH[i] = h;
         sdA[0][2 * i] = 0.0f; sdA[0][2 * i + 1] = 0.0f; sdA[1][2 * i] = 0.0f; sdA[1][2 * i + 1] = 0.0f;
     }
     for (int i = tid; i < 2 * W * kMaxGc; i += NT) { sdD[i] = 0.0f; sdb[i] = 0.0f; }
@@ -454,7 +466,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
         float *dst = reinterpret_cast<float *>(p.dA + (int64_t)(d0 + g) * N + n);
         unsafeAtomicAdd(dst, sdA[0][2 * (g * N + n)] + sdA[1][2 * (g * N + n)]);
         unsafeAtomicAdd(dst + 1, sdA[0][2 * (g * N + n) + 1] + sdA[1][2 * (g * N + n) + 1]);
-        if (p.dx0) p.dx0[((int64_t)b * p.D + d0 + g) * N + n] = sH[g * N + n];
+        if (p.dx0 && chunk == 0) p.dx0[((int64_t)b * p.D + d0 + g) * N + n] = sH[g * N + n];
     }
     for (int g = tid; g < Gact; g += NT) {
         float sD = 0.0f, sb = 0.0f;
@@ -479,9 +491,16 @@ int cbwd_channels_per_group(int B, int D, int) {
     return (int)G;
 }
 
+// launch shape incl. the chunked path for few rows and long sequences (selective_bwd_carry.hip): the chip holds one
+// 512-thread workgroup per CU for N = 16, two smaller ones below
+BwdPlan cbwd_plan(int rowsg, int dpg, int N, int64_t L, int mode, bool balanced) {
+    const int G = cbwd_channels_per_group(rowsg, dpg, N);
+    return plan_time_chunks(rowsg, dpg, L, balanced ? mode : 1, G, N >= 16 ? 256 : 512, kMaxGc);
+}
+
 template <typename IO, int N, int NK, int DISC>
 static hipError_t launch_cbwd_n(const CBwdParams &p, hipStream_t s) {
-    dim3 grid(p.bcg * ((p.dpg + p.G - 1) / p.G), p.B);
+    dim3 grid(p.bcg * ((p.dpg + p.G - 1) / p.G), p.B, p.nchunks > 1 ? p.nchunks : 1);
     hipLaunchKernelGGL((k_ss_cbwd<IO, N, NK, 4, DISC>), grid, dim3((N / NK) * 64), 0, s, p);
     return hipGetLastError();
 }

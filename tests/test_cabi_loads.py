@@ -43,13 +43,15 @@ def test_host_queries(lib):
     assert lib.lrnnx_workspace_bytes(1, 2, 3, 16, 1000, 1) == (ck + 255) // 256 * 256 + carry
     assert lib.lrnnx_workspace_bytes(7, 1, 8, 16, 200, 1) == 0        # a single tile: nothing to cut
     chunks = lib.lrnnx_selective_scan_bwd_chunks
-    chunks.argtypes = [ctypes.c_int64] * 4 + [ctypes.c_int] * 2
-    assert chunks(16, 2560, 16, 4096, 1, 0) == 1                      # enough rows to fill the chip: one pass
-    assert chunks(16, 2560, 16, 4096, 1, 2) == 2                      # ... unless the chunked path is asked for
-    assert chunks(1, 2048, 16, 65536, 1, 0) == 32 and chunks(1, 1024, 16, 32768, 1, 0) == 32   # 512 workgroups each
-    assert chunks(2, 768, 16, 8192, 1, 0) == 8 and chunks(8, 1536, 16, 2048, 1, 0) == 1
-    assert chunks(1, 1024, 16, 32768, 1, 1) == 1 and chunks(1, 8, 16, 200, 1, 2) == 1
-    assert chunks(1, 8, 3, 200, 1, 0) == 0 and chunks(1, 9, 16, 200, 2, 0) == 0
+    chunks.argtypes = [ctypes.c_int64] * 4 + [ctypes.c_int] * 3
+    assert chunks(16, 2560, 16, 4096, 1, 0, 0) == 1                   # enough rows to fill the chip: one pass
+    assert chunks(16, 2560, 16, 4096, 1, 2, 0) == 2                   # ... unless the chunked path is asked for
+    assert chunks(1, 2048, 16, 65536, 1, 0, 0) == 32 and chunks(1, 1024, 16, 32768, 1, 0, 0) == 32   # 512 workgroups each
+    assert chunks(2, 768, 16, 8192, 1, 0, 0) == 8 and chunks(8, 1536, 16, 2048, 1, 0, 0) == 1
+    assert chunks(1, 1024, 16, 32768, 1, 1, 0) == 1 and chunks(1, 8, 16, 200, 1, 2, 0) == 1
+    assert chunks(1, 8, 3, 200, 1, 0, 0) == 0 and chunks(1, 9, 16, 200, 2, 0, 0) == 0
+    assert chunks(1, 512, 16, 65536, 1, 0, 1) > 1 and chunks(8, 1536, 16, 2048, 1, 0, 1) == 1    # the complex-A scan
+    assert chunks(1, 64, 32, 4096, 1, 0, 1) == 0                      # ... takes N <= 16
     assert lib.lrnnx_workspace_bytes(0, 1, 2048, 16, 65536, 1) > 0
     assert lib.lrnnx_workspace_bytes(0, 1, 8, 3, 64, 1) == 0          # unsupported N
     assert lib.lrnnx_workspace_bytes(2, 4, 256, 0, 4096, 0) > 0

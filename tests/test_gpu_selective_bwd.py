@@ -106,7 +106,7 @@ def test_auto_path_chunks_long_sequences_with_few_rows(api, oracle):
     shape = dict(B=1, D=8, N=16, L=8192, gate=True, with_x0=True, seed=94, bias=("uniform", -4.0, -2.0))
     _check(api, oracle, "bf16", "zoh_s6", True, True, path="auto", **shape)
     _check(api, oracle, "bf16", "zoh_s6", True, True, path="single_pass", **shape)
-    assert api.lib().lrnnx_selective_scan_bwd_chunks(1, 8, 16, 8192, 1, 0) > 1
+    assert api.lib().lrnnx_selective_scan_bwd_chunks(1, 8, 16, 8192, 1, 0, 0) > 1
 
 
 def test_non_reduced_outputs_are_deterministic(api):

@@ -41,9 +41,10 @@ def _crel(got, ref):
     return float(np.abs(np.asarray(got, dtype=np.complex128) - ref).max() / (den if den > 0 else 1.0))
 
 
-def _run(api, oracle, B, D, N, L, io, disc, gate, x0, seed, softplus=True, use_ckpt=False, bias=True, skip=True):
+def _run(api, oracle, B, D, N, L, io, disc, gate, x0, seed, softplus=True, use_ckpt=False, bias=True, skip=True,
+         path="auto", groups=1):
     import torch
-    p = workloads.make_selective_complex(B=B, D=D, N=N, L=L, io=io, gate=gate, seed=seed, with_x0=x0)
+    p = workloads.make_selective_complex(B=B, D=D, N=N, L=L, io=io, gate=gate, seed=seed, with_x0=x0, bc_groups=groups)
     rng = np.random.Generator(np.random.PCG64(seed + 77))
     dy = workloads._io_round(rng.standard_normal((B, D, L), dtype=np.float32), io)
     if not softplus:
@@ -60,7 +61,7 @@ def _run(api, oracle, B, D, N, L, io, disc, gate, x0, seed, softplus=True, use_c
     if use_ckpt:
         _, ckpt = api.lrnnx_selective_scan_fwd_complex(**t, disc=disc, delta_softplus=softplus, return_ckpt=True)
     g = api.lrnnx_selective_scan_bwd_complex(**t, dy=dev(dy, io), ckpt=ckpt, disc=disc, delta_softplus=softplus,
-                                             want_dx0=True)
+                                             want_dx0=True, path=path)
     torch.cuda.synchronize()
     r = oracle.selective_scan_bwd_complex(p["u"], p["delta"], p["A"], _cplx(p["Bm"]), _cplx(p["Cm"]), dy, Dskip=p["Dskip"],
                                           delta_bias=p["delta_bias"], z=p["z"], x0=p["x0"], disc=disc,
@@ -157,3 +158,24 @@ def test_bad_arguments_are_rejected(api):
         api.lrnnx_selective_scan_bwd_complex(**t, ckpt=torch.zeros((1, 4, 2, 16), dtype=torch.complex64, device="cuda"))
     with pytest.raises(RuntimeError):                    # workspace too small for the checkpoints
         api.lrnnx_selective_scan_bwd_complex(**t, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("disc", DISCS)
+def test_chunked_over_time(api, oracle, io, disc):
+    """path = chunk_carry: chunks of the time axis side by side, each started from the adjoint carried in from the
+    later chunks (ragged last chunk, with and without the forward pass's checkpoints)."""
+    _run(api, oracle, 1, 5, 16, 2100, io, disc, True, True, seed=300, use_ckpt=True, path="chunk_carry")
+    _run(api, oracle, 2, 9, 4, 1300, io, disc, False, True, seed=301, use_ckpt=False, path="chunk_carry")
+
+
+@pytest.mark.parametrize("N", [1, 2, 8])
+def test_chunked_over_time_state_sizes_and_groups(api, oracle, N):
+    _run(api, oracle, 2, 12, N, 1800, "bf16", "zoh_s6", True, False, seed=310 + N, use_ckpt=True, path="chunk_carry", groups=3)
+    _run(api, oracle, 1, 3, N, 257, "f32", "zoh_s6", True, True, seed=320 + N, softplus=False, use_ckpt=True, path="chunk_carry")
+
+
+def test_auto_path_chunks_long_sequences_with_few_rows(api, oracle):
+    assert api.lib().lrnnx_selective_scan_bwd_chunks(1, 8, 16, 8192, 1, 0, 1) > 1
+    _run(api, oracle, 1, 8, 16, 8192, "bf16", "zoh_s6", True, True, seed=330, use_ckpt=True, path="auto")
+    _run(api, oracle, 1, 8, 16, 8192, "bf16", "zoh_s6", True, True, seed=330, use_ckpt=True, path="single_pass")
