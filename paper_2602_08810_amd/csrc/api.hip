@@ -237,7 +237,7 @@ int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *a) {
         const size_t need = (size_t)2 * a->B * a->D * nch * a->N * sizeof(float);
         if (!a->workspace || a->workspace_bytes < need) return LRNNX_ERR_WORKSPACE;
         chunked = true;
-    } else if (a->path == LRNNX_PATH_AUTO && !cu && wgs < kNumCU / 2 && ntiles >= 4) {
+    } else if (a->path == LRNNX_PATH_AUTO && !cu && wgs <= kNumCU / 2 && ntiles >= 4) {
         nch = fwd_chunks(a->B, a->D, a->L, a->io_dtype, false);
         const size_t need = (size_t)2 * a->B * a->D * nch * a->N * sizeof(float);
         chunked = nch > 1 && a->workspace && a->workspace_bytes >= need;
