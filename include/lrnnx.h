@@ -168,6 +168,13 @@ typedef struct lrnnx_ss_fwd_complex_args {
     int32_t reserved2;
     const int64_t *cu_seqlens;   /* packed variable-length mode, device memory [B+1], or NULL; callers built against a
                                     shorter struct get NULL */
+    void *workspace;    size_t workspace_bytes;   /* needed by LRNNX_PATH_CHUNK_CARRY only:
+                                    lrnnx_workspace_bytes(LRNNX_WS_FWD_COMPLEX, B, D, N, L, io_dtype) */
+    int32_t path;                /* lrnnx_path as in lrnnx_ss_fwd_args: CHUNK_CARRY = aggregate per chunk of the time
+                                    axis, chain, rerun from the true carry-in (three launches, for few rows and long
+                                    sequences); AUTO picks it then if the workspace allows; not with cu_seqlens.
+                                    Callers built against a shorter struct get SINGLE_PASS. */
+    int32_t reserved3;
 } lrnnx_ss_fwd_complex_args;
 
 int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *args);
@@ -460,7 +467,8 @@ int lrnnx_lti_step(const lrnnx_lti_step_args *args);
 /* ------------------------------------------------------------------ queries (host only, no GPU needed) */
 typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2, LRNNX_WS_LTI_BWD = 3, LRNNX_WS_DIAG = 4,
                LRNNX_WS_DIAG_BWD = 5, LRNNX_WS_BWD_COMPLEX = 6,
-               LRNNX_WS_BWD_CARRY = 7   /* the chunk aggregates of lrnnx_selective_scan_bwd alone (ckpt supplied) */
+               LRNNX_WS_BWD_CARRY = 7,  /* the chunk aggregates of lrnnx_selective_scan_bwd alone (ckpt supplied) */
+               LRNNX_WS_FWD_COMPLEX = 8
              } lrnnx_ws_kind;
 
 /* Bytes of device scratch the call may need (the largest over its paths).
@@ -472,6 +480,10 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
  * the time axis into for these sizes and this `path` when its workspace allows it (1: single pass); the aggregates
  * then take 2 * B * D * chunks * N floats (float pairs for the complex scan) of the workspace.  0 for invalid sizes. */
 int lrnnx_selective_scan_bwd_chunks(int64_t B, int64_t D, int64_t N, int64_t L, int bc_groups, int path, int complex_a);
+
+/* The same for lrnnx_selective_scan_fwd_complex: chunks of its chunk-carry path (1: single pass); the aggregates take
+ * 2 * B * D * chunks * N float pairs of the workspace.                                                          */
+int lrnnx_selective_scan_fwd_complex_chunks(int64_t B, int64_t D, int64_t N, int64_t L, int bc_groups, int path);
 
 const char *lrnnx_status_string(int status);
 int lrnnx_version(void);   /* major * 100 + minor; grows whenever an entry point or a struct field is added */

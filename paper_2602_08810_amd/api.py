@@ -20,7 +20,7 @@ LIB_PATH = os.environ.get("LRNNX_LIB", os.path.join(_HERE, "liblrnnx.so"))   # L
 F32, BF16, C64 = 0, 1, 2
 DISC = {"zoh_s6": 0, "zoh": 1, "bilinear": 2, "dirac": 3}
 PATH = {"auto": 0, "single_pass": 1, "chunk_carry": 2}
-WS_FWD, WS_BWD, WS_LTI, WS_LTI_BWD, WS_DIAG, WS_DIAG_BWD, WS_BWD_COMPLEX, WS_BWD_CARRY = 0, 1, 2, 3, 4, 5, 6, 7
+WS_FWD, WS_BWD, WS_LTI, WS_LTI_BWD, WS_DIAG, WS_DIAG_BWD, WS_BWD_COMPLEX, WS_BWD_CARRY, WS_FWD_COMPLEX = 0, 1, 2, 3, 4, 5, 6, 7, 8
 STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported", 3: "workspace", 4: "launch"}
 
 _vp, _i32, _i64, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
@@ -53,7 +53,7 @@ class FwdComplexArgs(ctypes.Structure):
         ("x0", _vp),
         ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
         ("x_last", _vp), ("stream", _vp), ("ckpt", _vp), ("bc_groups", _i32), ("reserved2", _i32),
-        ("cu_seqlens", _vp),
+        ("cu_seqlens", _vp), ("workspace", _vp), ("workspace_bytes", _sz), ("path", _i32), ("reserved3", _i32),
     ]
 
 
@@ -198,6 +198,8 @@ def lib():
         L.lrnnx_workspace_bytes.restype = _sz
         L.lrnnx_selective_scan_bwd_chunks.argtypes = [_i64, _i64, _i64, _i64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.lrnnx_selective_scan_bwd_chunks.restype = ctypes.c_int
+        L.lrnnx_selective_scan_fwd_complex_chunks.argtypes = [_i64, _i64, _i64, _i64, ctypes.c_int, ctypes.c_int]
+        L.lrnnx_selective_scan_fwd_complex_chunks.restype = ctypes.c_int
         L.lrnnx_ckpt_interval.restype = _i64
         L.lrnnx_status_string.argtypes = [ctypes.c_int]
         L.lrnnx_status_string.restype = ctypes.c_char_p
@@ -381,7 +383,7 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
 @_device_checked
 def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z=None, x0=None,
                                      disc="zoh_s6", delta_softplus=True, return_last_state=False, out=None,
-                                     return_ckpt=False, ckpt_out=None, cu_seqlens=None):
+                                     return_ckpt=False, ckpt_out=None, cu_seqlens=None, path="auto", workspace=None):
     """y (and optionally x_last, ckpt) of the forward selective scan with complex A, Bm, Cm; see
     lrnnx_ss_fwd_complex_args.  `ckpt_out`: a preallocated checkpoint array to fill (implies return_ckpt).
 
@@ -389,7 +391,8 @@ def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias
     of (re, im) pairs.  x0, x_last [B,D,N] complex64; ckpt [B,D,ceil(L/interval),N] complex64.
     With `cu_seqlens` (int64 [S+1] on the device) the call is in packed variable-length mode: u, delta, z, y are
     [D,L], Bm and Cm [L,N] or [G,L,N] (plus the pair axis for bfloat16), x0 and x_last [S,D,N], ckpt
-    [D, L // interval + S, N]."""
+    [D, L // interval + S, N].  `path`: "auto", "single_pass" or "chunk_carry" (few rows, long sequences); `workspace`
+    may supply the scratch buffer of the latter."""
     io = u.dtype
     packed = cu_seqlens is not None
     if packed:
@@ -432,6 +435,13 @@ def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias
             raise ValueError(f"ckpt_out: expected contiguous complex64 {shape}")
         a.ckpt = ckpt.data_ptr()
         return_ckpt = True
+    a.path = PATH[path] if isinstance(path, str) else int(path)
+    if workspace is None and not packed:
+        nch = int(lib().lrnnx_selective_scan_fwd_complex_chunks(Bsz, D, N, L, G, a.path))
+        if nch > 1:
+            workspace = torch.empty(2 * Bsz * D * nch * N * 8, dtype=torch.uint8, device=u.device)
+    if workspace is not None:
+        a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
     a.stream = _stream()
     _check(lib().lrnnx_selective_scan_fwd_complex(ctypes.byref(a)))
     res = (y[0] if packed else y,) + ((x_last,) if return_last_state else ()) + ((ckpt,) if return_ckpt else ())

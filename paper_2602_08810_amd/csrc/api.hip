@@ -32,6 +32,20 @@ int fwd_chunks(int64_t B, int64_t D, int64_t L, int io, bool forced) {
     return (int)n;
 }
 
+// the complex forward kernel: 8 channels per workgroup, tiles of 512 steps for both I/O types
+constexpr int kCfwdTile = 512;
+int cfwd_chunks(int64_t wgs, int64_t L, bool forced) {
+    const int64_t ntiles = cdiv(L, kCfwdTile);
+    int64_t n = cdiv(forced ? 8 * kNumCU : 2 * kNumCU, wgs);
+    if (forced && n < 2) n = 2;
+    if (n > ntiles) n = ntiles;
+    return n < 1 ? 1 : (int)n;
+}
+// one pass over whole rows (also what the backward entry point's recompute sweep runs)
+void set_cfwd_single_pass(CFwdParams &p) {
+    p.mode = MODE_FULL; p.nchunks = 1; p.tiles_per_chunk = (int64_t)1 << 40;
+}
+
 int lti_chunks(int64_t B, int64_t P, int64_t L) {
     const int64_t waves_per_chunk = B * cdiv(P, 64);
     int64_t n = cdiv(8 * kNumCU, waves_per_chunk);
@@ -135,7 +149,7 @@ extern "C" {
 
 int64_t lrnnx_ckpt_interval(void) { return kCkptInterval; }
 int64_t lrnnx_packed_ckpt_slots(int64_t L, int64_t B) { return (L < 0 || B < 0) ? 0 : L / kCkptInterval + B; }
-int lrnnx_version(void) { return 136; }   // major * 100 + minor; bumped whenever an entry point or a struct field is added
+int lrnnx_version(void) { return 137; }   // major * 100 + minor; bumped whenever an entry point or a struct field is added
 
 int lrnnx_selective_scan_bwd_chunks(int64_t B, int64_t D, int64_t N, int64_t L, int bc_groups, int path, int complex_a) {
     const int bcg = bc_groups > 1 ? bc_groups : 1;
@@ -145,6 +159,16 @@ int lrnnx_selective_scan_bwd_chunks(int64_t B, int64_t D, int64_t N, int64_t L, 
     if (path == LRNNX_PATH_SINGLE_PASS) return 1;
     return complex_a ? cbwd_plan((int)B * bcg, (int)(D / bcg), (int)N, L, path, true).nchunks
                      : bwd_plan((int)B * bcg, (int)(D / bcg), (int)N, L, path, true).nchunks;
+}
+
+int lrnnx_selective_scan_fwd_complex_chunks(int64_t B, int64_t D, int64_t N, int64_t L, int bc_groups, int path) {
+    const int bcg = bc_groups > 1 ? bc_groups : 1;
+    if (B < 1 || D < 1 || L < 1 || B > 65535 || D > INT32_MAX || D % bcg || !supported_n_complex((int)N)) return 0;
+    if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return 0;
+    const int64_t wgs = B * bcg * cdiv(D / bcg, 8);
+    if (path == LRNNX_PATH_CHUNK_CARRY) return cfwd_chunks(wgs, L, true);
+    if (path == LRNNX_PATH_AUTO && wgs <= kNumCU / 2 && cdiv(L, kCfwdTile) >= 4) return cfwd_chunks(wgs, L, false);
+    return 1;
 }
 
 const char *lrnnx_status_string(int status) {
@@ -170,6 +194,10 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
         return align256((size_t)B * D * cdiv(L, kCkptInterval) * N * sizeof(float)) + bwd_carry_bytes(B, D, N, L);
     }
     if (which == LRNNX_WS_BWD_CARRY) return supported_n((int)N) ? bwd_carry_bytes(B, D, N, L) : 0;
+    if (which == LRNNX_WS_FWD_COMPLEX) {
+        if (!supported_n_complex((int)N)) return 0;
+        return (size_t)2 * B * D * cfwd_chunks(B * cdiv(D, 8), L, true) * N * sizeof(float2);
+    }
     if (which == LRNNX_WS_BWD_COMPLEX) {
         if (!supported_n_complex((int)N)) return 0;
         return (size_t)B * D * cdiv(L, kCkptInterval) * N * sizeof(float2);
@@ -267,11 +295,19 @@ int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *a) {
     if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
     void *ckpt = a->struct_size >= kSizeCkpt ? a->ckpt : nullptr;
     constexpr size_t kSizeGroups = offsetof(lrnnx_ss_fwd_complex_args, cu_seqlens);   // ... and before `cu_seqlens`
+    constexpr size_t kSizeCu = offsetof(lrnnx_ss_fwd_complex_args, workspace);        // ... and before `workspace`, `path`
     const bool has_groups = a->struct_size >= kSizeGroups;
     if (has_groups && a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
     const int bcg = (has_groups && a->bc_groups > 1) ? a->bc_groups : 1;
-    const int64_t *cu = a->struct_size >= sizeof(lrnnx_ss_fwd_complex_args) ? a->cu_seqlens : nullptr;
+    const int64_t *cu = a->struct_size >= kSizeCu ? a->cu_seqlens : nullptr;
     if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
+    const bool has_path = a->struct_size >= sizeof(lrnnx_ss_fwd_complex_args);
+    const int path = has_path ? a->path : LRNNX_PATH_SINGLE_PASS;
+    void *ws = has_path ? a->workspace : nullptr;
+    const size_t ws_bytes = has_path ? a->workspace_bytes : 0;
+    if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
+    if (cu && path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_UNSUPPORTED;
+    if (reinterpret_cast<uintptr_t>(ws) & 7u) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
@@ -306,8 +342,30 @@ int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *a) {
     p.ckpt = reinterpret_cast<float2 *>(ckpt);
     p.vec = row_vec_ok(a->u, p.u_sb, p.u_sd, es) && row_vec_ok(a->delta, p.dl_sb, p.dl_sd, es) &&
             (!a->y || row_vec_ok(a->y, p.y_sb, p.y_sd, es)) && (!a->z || row_vec_ok(a->z, p.z_sb, p.z_sd, es));
-    return launch_ss_cfwd(p, a->io_dtype, a->disc, reinterpret_cast<hipStream_t>(a->stream)) == hipSuccess
-               ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+    hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
+
+    // chunk-carry path: asked for, or (automatic) few rows and a sequence of four tiles or more
+    const int64_t ntiles = cdiv(a->L, kCfwdTile);
+    const int64_t wgs = (int64_t)a->B * bcg * cdiv(a->D / bcg, 8);
+    int nch = cu ? 1 : lrnnx_selective_scan_fwd_complex_chunks(a->B, a->D, a->N, a->L, bcg, path);
+    if (nch > 1 && (!ws || ws_bytes < (size_t)2 * a->B * a->D * nch * a->N * sizeof(float2))) {
+        if (path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_WORKSPACE;
+        nch = 1;
+    }
+    if (nch < 2) {
+        set_cfwd_single_pass(p);
+        return launch_ss_cfwd(p, a->io_dtype, a->disc, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+    }
+    p.tiles_per_chunk = cdiv(ntiles, nch);
+    p.nchunks = (int)cdiv(ntiles, p.tiles_per_chunk);          // no empty trailing chunk
+    p.ws_P = reinterpret_cast<float2 *>(ws);
+    p.ws_S = p.ws_P + (size_t)a->B * a->D * p.nchunks * a->N;
+    CFwdParams pa = p;
+    pa.mode = MODE_AGG; pa.ckpt = nullptr; pa.x_last = nullptr; pa.y = nullptr;
+    if (launch_ss_cfwd(pa, a->io_dtype, a->disc, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    if (launch_ss_ccarry(p, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    p.mode = MODE_APPLY;
+    return launch_ss_cfwd(p, a->io_dtype, a->disc, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }
 
 int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
@@ -363,6 +421,7 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
         f.Bm = a->Bm; f.Cm = a->Cm;
         f.ckpt = reinterpret_cast<float2 *>(a->workspace);
         f.vec = row_vec_ok(a->u, f.u_sb, f.u_sd, es) && row_vec_ok(a->delta, f.dl_sb, f.dl_sd, es);
+        set_cfwd_single_pass(f);
         if (launch_ss_cfwd(f, a->io_dtype, a->disc, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
         ckpt = f.ckpt;
     }

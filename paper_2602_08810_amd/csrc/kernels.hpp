@@ -44,6 +44,12 @@ struct CFwdParams {
     const void *Bm, *Cm;     // [B,L,N] complex in the I/O type
     float2 *x_last;
     float2 *ckpt;            // [B,D,ceil(L/kCkptInterval),N] complex: state entering every kCkptInterval-th step, or null
+    // chunk-carry path (blockIdx.z = chunk), as for the real forward: MODE_AGG writes each chunk's pair (product of
+    // the multipliers, end state from zero) to ws_P, ws_S [B,D,nchunks,N]; the carry kernel turns ws_S into each
+    // chunk's true carry-in; MODE_APPLY reruns the chunk from it.  MODE_FULL: one pass, nchunks = 1.
+    int mode, nchunks;
+    int64_t tiles_per_chunk;
+    float2 *ws_P, *ws_S;
 };
 
 // backward of the same
@@ -168,6 +174,7 @@ struct BwdPlan { int G, nchunks; int64_t tiles_per_chunk; };
 // rowsg = B * (number of Bm/Cm groups), dpg = channels per group; mode 0: automatic, 1: single pass, 2: chunked asked for
 BwdPlan bwd_plan(int rowsg, int dpg, int N, int64_t L, int mode, bool balanced);
 BwdPlan cbwd_plan(int rowsg, int dpg, int N, int64_t L, int mode, bool balanced);          // the complex-A backward
+hipError_t launch_ss_ccarry(const CFwdParams &p, hipStream_t s);
 hipError_t launch_ss_cbwd_agg(const CBwdParams &p, int io_dtype, int disc, hipStream_t s);
 hipError_t launch_ss_cbwd_carry(const CBwdParams &p, hipStream_t s);
 

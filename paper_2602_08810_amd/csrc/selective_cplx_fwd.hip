@@ -17,7 +17,8 @@
 namespace lrnnx {
 
 
-template <typename IO, int N, int T, int W, int DISC>
+// AGG: the aggregate launch of the chunk-carry path (no y, no checkpoints; the chunk's pair instead)
+template <typename IO, int N, int T, int W, int DISC, bool AGG>
 __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
     using CW = typename cword<IO>::type;
     constexpr int TQ = T / 4;
@@ -48,13 +49,17 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
         toff = o; L = e - o; bs = 0;
     }
     const int64_t ntiles = (L + TILE - 1) / TILE;
+    const int chunk = blockIdx.z;
+    [[maybe_unused]] const int mode = p.mode;
+    const int64_t tile0 = (int64_t)chunk * p.tiles_per_chunk;
+    const int64_t tile1 = (tile0 + p.tiles_per_chunk < ntiles) ? tile0 + p.tiles_per_chunk : ntiles;
     const int64_t row = (int64_t)b * p.D + d;
     const bool vec = p.vec != 0 && (toff % 8) == 0;
 
     const IO *urow = reinterpret_cast<const IO *>(p.u) + bs * p.u_sb + d * p.u_sd + toff;
     const IO *drow = reinterpret_cast<const IO *>(p.delta) + bs * p.dl_sb + d * p.dl_sd + toff;
     const IO *zrow = p.z ? reinterpret_cast<const IO *>(p.z) + bs * p.z_sb + d * p.z_sd + toff : nullptr;
-    const bool want_y = p.y != nullptr;                 // a state-only sweep (checkpoints for the backward pass) has no y
+    const bool want_y = !AGG && p.y != nullptr;         // a state-only sweep (checkpoints for the backward pass) has no y
     IO *yrow = reinterpret_cast<IO *>(p.y) + bs * p.y_sb + d * p.y_sd + toff;
     // checkpoints of this row: [B,D,nck,N], or packed [D,nslots,N] with sequence b starting at slot toff/interval + b
     const int64_t ck0 = p.cu ? (int64_t)d * p.nslots + toff / kCkptInterval + b
@@ -65,15 +70,17 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
 
     // lane n holds the constants and the carried state of state n
     float Arv = 0.0f, Aiv = 0.0f, xrv = 0.0f, xiv = 0.0f;
+    float prv = 1.0f, piv = 0.0f;                       // MODE_AGG: product of the chunk's multipliers
     if (lane < N) {
         const float2 Av = p.A[d * N + lane];
         Arv = Av.x; Aiv = Av.y;
-        if (p.x0) { const float2 x0 = p.x0[row * N + lane]; xrv = x0.x; xiv = x0.y; }
+        if (!AGG && mode == MODE_APPLY) { const float2 x0 = p.ws_S[(row * p.nchunks + chunk) * N + lane]; xrv = x0.x; xiv = x0.y; }
+        else if (!AGG && p.x0) { const float2 x0 = p.x0[row * N + lane]; xrv = x0.x; xiv = x0.y; }
     }
     const float Dsk = p.Dskip ? p.Dskip[d] : 0.0f;
     const float bias = p.bias ? p.bias[d] : 0.0f;
 
-    for (int64_t tile = 0; tile < ntiles; ++tile) {
+    for (int64_t tile = tile0; tile < tile1; ++tile) {
         const int64_t l0 = tile * TILE;
         const int64_t ll = l0 + lane * T;
 
@@ -140,8 +147,13 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
             }
             cwave_scan_fwd(P, S);
             float2 x = make_float2(dpp<DPP_WAVE_SHR1>(xc.x, S.x), dpp<DPP_WAVE_SHR1>(xc.y, S.y));
+            if constexpr (AGG) {                                      // lane 63: product of the tile's multipliers
+                const float tr = readlane(P.x, 63), ti = readlane(P.y, 63), cr = readlane(prv, n), ci = readlane(piv, n);
+                prv = writelane(prv, tr * cr - ti * ci, n);
+                piv = writelane(piv, tr * ci + ti * cr, n);
+            }
             // the state entering every kCkptInterval-th step is what the backward pass restarts from
-            if (p.ckpt && (lane * T) % (int)kCkptInterval == 0 && ll < L)
+            if (!AGG && p.ckpt && (lane * T) % (int)kCkptInterval == 0 && ll < L)
                 p.ckpt[(ck0 + ll / kCkptInterval) * N + n] = x;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
@@ -164,15 +176,41 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
         store_seg<IO, T>(yrow, ll, L, vec, yv);
     }
 
-    if (active && lane < N && p.x_last) p.x_last[row * N + lane] = make_float2(xrv, xiv);
+    if constexpr (AGG) {
+        if (active && lane < N) {
+            const int64_t j = (row * p.nchunks + chunk) * N + lane;
+            p.ws_P[j] = make_float2(prv, piv);
+            p.ws_S[j] = make_float2(xrv, xiv);
+        }
+        return;
+    }
+    if (active && lane < N && p.x_last && chunk == p.nchunks - 1) p.x_last[row * N + lane] = make_float2(xrv, xiv);
+}
+
+// Chains the chunk aggregates of one (b,d,n): carry-in of chunk c+1 = P_c * carry-in of chunk c + S_c.
+// ws_S[c] is replaced by the carry-in of chunk c.
+__global__ void k_ss_ccarry(const CFwdParams p) {
+    const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    const int64_t total = (int64_t)p.B * p.D * p.N;
+    if (i >= total) return;
+    const int64_t row = i / p.N;
+    const int n = (int)(i % p.N);
+    float2 x = p.x0 ? p.x0[i] : make_float2(0.0f, 0.0f);
+    for (int c = 0; c < p.nchunks; ++c) {
+        const int64_t j = (row * p.nchunks + c) * p.N + n;
+        const float2 P = p.ws_P[j], S = p.ws_S[j];
+        p.ws_S[j] = x;
+        x = cxfma(P, x, S);
+    }
 }
 
 // ---------------------------------------------------------------- launchers
 template <typename IO, int N, int DISC>
 static hipError_t launch_cfwd_n(const CFwdParams &p, hipStream_t s) {
     constexpr int W = 8, T = 8;
-    dim3 grid(p.bcg * ((p.dpg + W - 1) / W), p.B);
-    hipLaunchKernelGGL((k_ss_cfwd<IO, N, T, W, DISC>), grid, dim3(W * 64), 0, s, p);
+    dim3 grid(p.bcg * ((p.dpg + W - 1) / W), p.B, p.nchunks > 1 ? p.nchunks : 1);
+    if (p.mode == MODE_AGG) hipLaunchKernelGGL((k_ss_cfwd<IO, N, T, W, DISC, true>), grid, dim3(W * 64), 0, s, p);
+    else hipLaunchKernelGGL((k_ss_cfwd<IO, N, T, W, DISC, false>), grid, dim3(W * 64), 0, s, p);
     return hipGetLastError();
 }
 template <typename IO, int DISC>
@@ -195,6 +233,11 @@ static hipError_t launch_cfwd_io(const CFwdParams &p, int disc, hipStream_t s) {
         case DISC_DIRAC: return launch_cfwd_disc<IO, DISC_DIRAC>(p, s);
     }
     return hipErrorInvalidValue;
+}
+hipError_t launch_ss_ccarry(const CFwdParams &p, hipStream_t s) {
+    const int64_t total = (int64_t)p.B * p.D * p.N;
+    hipLaunchKernelGGL(k_ss_ccarry, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p);
+    return hipGetLastError();
 }
 hipError_t launch_ss_cfwd(const CFwdParams &p, int io_dtype, int disc, hipStream_t s) {
     return io_dtype == 1 ? launch_cfwd_io<bf16_t>(p, disc, s) : launch_cfwd_io<float>(p, disc, s);

@@ -31,16 +31,17 @@ def _maps_dev(a, io):
     return t.to(torch.bfloat16) if io == "bf16" else torch.view_as_complex(t)
 
 
-def _run(api, oracle, B, D, N, L, io, disc, gate, x0, seed, softplus=True):
+def _run(api, oracle, B, D, N, L, io, disc, gate, x0, seed, softplus=True, path="auto", groups=1):
     import torch
-    p = workloads.make_selective_complex(B=B, D=D, N=N, L=L, io=io, gate=gate, seed=seed, with_x0=x0)
+    p = workloads.make_selective_complex(B=B, D=D, N=N, L=L, io=io, gate=gate, seed=seed, with_x0=x0, bc_groups=groups)
     if not softplus:
         p["delta"] = workloads._io_round(np.abs(p["delta"]) * 0.1 + 0.01, io)
         p["delta_bias"] = None
     t = dict(u=dev(p["u"], io), delta=dev(p["delta"], io), A=torch.from_numpy(p["A"]).cuda(), Bm=_maps_dev(p["Bm"], io),
              Cm=_maps_dev(p["Cm"], io), Dskip=dev(p["Dskip"]), delta_bias=dev(p["delta_bias"]), z=dev(p["z"], io),
              x0=None if p["x0"] is None else torch.from_numpy(p["x0"]).cuda())
-    y, x_last = api.lrnnx_selective_scan_fwd_complex(**t, disc=disc, delta_softplus=softplus, return_last_state=True)
+    y, x_last = api.lrnnx_selective_scan_fwd_complex(**t, disc=disc, delta_softplus=softplus, return_last_state=True,
+                                                     path=path)
     yr, xr = oracle.selective_scan_fwd_complex(p["u"], p["delta"], p["A"], _cplx(p["Bm"]), _cplx(p["Cm"]), Dskip=p["Dskip"],
                                                delta_bias=p["delta_bias"], z=p["z"], x0=p["x0"], disc=disc,
                                                delta_softplus=softplus)
@@ -101,3 +102,30 @@ def test_two_calls_chained_through_the_state_equal_one_call(api, oracle):
     yr, xr = oracle.selective_scan_fwd_complex(p["u"], p["delta"], p["A"], _cplx(p["Bm"]), _cplx(p["Cm"]), Dskip=p["Dskip"],
                                                delta_bias=p["delta_bias"], z=p["z"], x0=p["x0"])
     assert rel_err(host(yy), yr) <= TOL[io]
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("disc", DISCS)
+def test_chunk_carry_path(api, oracle, io, disc):
+    """Aggregate per chunk, chain, rerun from the true carry-in: ragged last chunk, initial state, every scheme."""
+    _run(api, oracle, 1, 5, 16, 2100, io, disc, gate=True, x0=True, seed=400, path="chunk_carry")
+    _run(api, oracle, 2, 9, 4, 1300, io, disc, gate=False, x0=False, seed=401, path="chunk_carry", groups=3)
+
+
+def test_chunk_carry_checkpoints_feed_the_backward_pass(api, oracle):
+    """The checkpoints written by the chunked forward are those of the single pass (the backward restarts from them)."""
+    import torch
+    p = workloads.make_selective_complex(B=1, D=6, N=8, L=4096, io="bf16", gate=True, seed=402, with_x0=True)
+    t = dict(u=dev(p["u"], "bf16"), delta=dev(p["delta"], "bf16"), A=torch.from_numpy(p["A"]).cuda(),
+             Bm=_maps_dev(p["Bm"], "bf16"), Cm=_maps_dev(p["Cm"], "bf16"), Dskip=dev(p["Dskip"]),
+             delta_bias=dev(p["delta_bias"]), z=dev(p["z"], "bf16"), x0=torch.from_numpy(p["x0"]).cuda())
+    assert api.lib().lrnnx_selective_scan_fwd_complex_chunks(1, 6, 8, 4096, 1, 0) > 1      # the automatic choice chunks
+    y1, x1, c1 = api.lrnnx_selective_scan_fwd_complex(**t, return_last_state=True, return_ckpt=True, path="single_pass")
+    y2, x2, c2 = api.lrnnx_selective_scan_fwd_complex(**t, return_last_state=True, return_ckpt=True, path="auto")
+    scale = float(torch.view_as_real(c1).abs().max())
+    assert float(torch.view_as_real(c1 - c2).abs().max()) <= 1e-5 * scale
+    assert float(torch.view_as_real(x1 - x2).abs().max()) <= 1e-5 * float(torch.view_as_real(x1).abs().max())
+    assert float((y1.float() - y2.float()).abs().max()) <= 2e-2 * float(y1.float().abs().max())
+    with pytest.raises(api.LrnnxError) as e:
+        api.lrnnx_selective_scan_fwd_complex(**t, path="chunk_carry", workspace=torch.empty(64, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == 3
