@@ -185,6 +185,9 @@ def test_host_side_validation_of_the_backward_and_lti_calls(lib):
     assert bwd(du_stride_d=99) == 1 and bwd(dy_stride_b=-1) == 1
     assert bwd(N=5) == 2 and bwd(B=70000) == 2
     assert bwd(bc_groups=3) == 1 and bwd(bc_groups=-1) == 1
+    assert bwd(path=9) == 1 and bwd(path=-1) == 1
+    assert bwd(path=2, L=2000, du_stride_d=2000, ddelta_stride_d=2000) == 3   # the chunked path keeps its aggregates in the workspace
+    assert bwd(path=2, cu_seqlens=fake) == 2                  # ... and is not offered for packed batches
 
     def lti(**over):
         a = api.LtiArgs()
@@ -228,6 +231,9 @@ def test_host_side_validation_of_the_complex_calls(lib):
     assert fwd(A=0x10004) == 1 and fwd(x0=0x10004) == 1 and fwd(ckpt=0x10004) == 1 and fwd(Cm=0x10008) == 1
     assert fwd(bc_groups=3) == 1 and fwd(bc_groups=-2) == 1
     assert fwd(cu_seqlens=0x10004) == 1                                # boundaries are 8-byte integers
+    assert fwd(path=5) == 1 and fwd(path=2, cu_seqlens=fake) == 2
+    assert fwd(path=2, L=4000, y_stride_d=4000) == 3                   # the chunk-carry path needs its workspace
+    assert fwd(path=2, L=4000, y_stride_d=4000, workspace=0x10004, workspace_bytes=1 << 30) == 1
     assert fwd(size=api.FwdComplexArgs.ckpt.offset - 8) == 1           # shorter than the first published block
     # a block that ends before `cu_seqlens` is still read (its later fields are then ignored): the refusal
     # comes from the fields it does have
@@ -252,6 +258,8 @@ def test_host_side_validation_of_the_complex_calls(lib):
     assert bwd(dz=fake) == 1 and bwd(dD=fake) == 1 and bwd(dbias=fake) == 1
     assert bwd(dA=0x10004) == 1 and bwd(dx0=0x10004) == 1 and bwd(dCm=0x10008) == 1
     assert bwd(cu_seqlens=0x10004) == 1 and bwd(bc_groups=5) == 1
+    assert bwd(path=4) == 1 and bwd(path=2, cu_seqlens=fake) == 2
+    assert bwd(path=2, L=2000, du_stride_d=2000, ddelta_stride_d=2000) == 3
     assert bwd(size=api.BwdComplexArgs.cu_seqlens.offset - 8) == 1
     # packed mode sizes the recompute workspace by D * (L / interval + B) * N float pairs
     need = 8 * (100 // int(lib.lrnnx_ckpt_interval()) + 2) * 16 * 8
