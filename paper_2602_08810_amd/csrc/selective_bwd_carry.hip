@@ -11,9 +11,10 @@
 // state needs no such chain: every tile restarts from the forward pass's checkpoint.
 //
 // Mapping of k_ss_bwd_agg: that of the forward kernel.  Time on lanes (a lane owns T = 8 consecutive steps), one
-// wavefront per channel, the 8 wavefronts of a workgroup share the Cm tile staged in LDS as fp32; the lanes' pairs
-// are composed by the suffix scan, lane 0 ends up with the tile's pair, and the chunk's pair is carried from tile to
-// tile in lane n of two registers.
+// wavefront per channel, the 8 wavefronts of a workgroup share the Cm tile staged in LDS as fp32.  Only the tile's
+// total pair is needed, so the lanes take the tile's time slots in reverse order (lane 63 the earliest): the
+// composition "earlier o later" then runs towards higher lanes and is the forward scan, all DPP steps; lane 63 ends up
+// with the tile's pair, and the chunk's pair is carried from tile to tile in lane n of two registers.
 #include "kernels.hpp"
 #include "scan_common.hpp"
 #include "cplx_common.hpp"
@@ -30,6 +31,7 @@ __global__ __launch_bounds__(512, 2) void k_ss_bwd_agg(const BwdParams p) {
     __shared__ __attribute__((aligned(16))) float sC[N * PLANE];
 
     const int lane = threadIdx.x & 63;
+    const int slot = 63 - lane;                        // this lane's time slot within a tile
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int b = blockIdx.y;
     const int chunk = blockIdx.z;
@@ -59,9 +61,9 @@ __global__ __launch_bounds__(512, 2) void k_ss_bwd_agg(const BwdParams p) {
 
     for (int64_t tile = ntiles - 1; tile >= 0; --tile) {
         const int64_t l0 = tile * TILE;
-        const int64_t ll = l0 + lane * T;
+        const int64_t ll = l0 + slot * T;
 
-        // ---- stage the Cm tile (all wavefronts), fp32, layout [n][t/4][lane][t%4]; rows past the chunk read as zero
+        // ---- stage the Cm tile (all wavefronts), fp32, layout [n][t/4][slot][t%4]; rows past the chunk read as zero
         __syncthreads();
         for (int r = threadIdx.x; r < TILE; r += W * 64) {
             float cv[N];
@@ -99,7 +101,7 @@ __global__ __launch_bounds__(512, 2) void k_ss_bwd_agg(const BwdParams p) {
             const ACoef ac = make_acoef<DISC>(readlane(Av, n));
             float4 Cc[TQ];
 #pragma unroll
-            for (int q = 0; q < TQ; ++q) Cc[q] = *reinterpret_cast<const float4 *>(&sC[n * PLANE + q * QS + lane * 4]);
+            for (int q = 0; q < TQ; ++q) Cc[q] = *reinterpret_cast<const float4 *>(&sC[n * PLANE + q * QS + slot * 4]);
             // the lane's pair: Q = a_0 (c_0 + a_1 (c_1 + ...)), P = a_0 a_1 ... a_{T-1}
             float P = 1.0f, Q = 0.0f;
 #pragma unroll
@@ -111,8 +113,8 @@ __global__ __launch_bounds__(512, 2) void k_ss_bwd_agg(const BwdParams p) {
                 if constexpr (DISC == DISC_BILINEAR) P *= a;
             }
             if constexpr (DISC != DISC_BILINEAR) P = exp2_fast(sum_dl * ac.A2);
-            wave_scan_rev(P, Q, lane);                                // lane 0: the tile's pair
-            const float Pt = readlane(P, 0), Qt = readlane(Q, 0);
+            wave_scan_fwd(P, Q);                                      // lane 63 (the earliest slot): the tile's pair
+            const float Pt = readlane(P, 63), Qt = readlane(Q, 63);
             // this tile lies before what has been accumulated so far: (Pt, Qt) o (Pc, Qc)
             qcv = writelane(qcv, __builtin_fmaf(Pt, readlane(qcv, n), Qt), n);
             pcv = writelane(pcv, Pt * readlane(pcv, n), n);
