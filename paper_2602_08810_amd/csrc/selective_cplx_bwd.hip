@@ -483,6 +483,11 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
 // 256 workgroups, 1.76 ms with 512, 1.90 ms with 1024.
 int cbwd_channels_per_group(int B, int D, int) {
     int64_t G = ((int64_t)B * D) / 256;
+    // never a few workgroups more than a whole number of rounds of 256 (see bwd_channels_per_group)
+    int64_t rounds = 1;
+    while ((int64_t)B * ((D + kMaxGc - 1) / kMaxGc) > rounds * 256 && rounds < 64) ++rounds;
+    const int64_t nb = rounds * 256 / B;
+    if (nb >= 1) G = (D + nb - 1) / nb;
     if (G < 8) G = 8;
     if (G > kMaxGc) G = kMaxGc;
     if (G > D) G = D;
