@@ -133,15 +133,18 @@ def test_config4_backward_sampled_rows_windows_identities(api, oracle):
 
 
 def test_long_sequence_backward(api, oracle):
-    """Backward over 256 tiles (L = 65536) for a handful of channels: adjoint and checkpoint carries across many tiles."""
+    """Backward over 256 tiles (L = 65536) for a handful of channels: adjoint and checkpoint carries across many tiles
+    in one workgroup (single pass), and the same sequence cut into 64 chunks (the automatic choice for so few rows)."""
     p = workloads.make_selective(B=1, D=12, N=16, L=65536, io="bf16", gate=True, seed=33, bias=("uniform", -4.0, -2.0))
     t = _upload(p, "bf16")
     y, ckpt = api.lrnnx_selective_scan_fwd(**t, return_ckpt=True)
-    g = api.lrnnx_selective_scan_bwd(**t, dy=dev(p["dy"], "bf16"), ckpt=ckpt, want_dx0=True)
     r = oracle.selective_scan_bwd(p["u"], p["delta"], p["A"], p["Bm"], p["Cm"], p["dy"], Dskip=p["Dskip"],
                                   delta_bias=p["delta_bias"], z=p["z"])
-    errs = {k: rel_err(host(g[k]), r[k]) for k in ("du", "ddelta", "dz", "dA", "dBm", "dCm", "dD", "dbias", "dx0")}
-    tol = {"du": 2e-2, "ddelta": 2e-2, "dz": 2e-2, "dA": 1e-4, "dBm": 1e-4, "dCm": 1e-4, "dD": 1e-4, "dbias": 1e-4,
-           "dx0": 1e-4}
-    bad = {k: v for k, v in errs.items() if not v <= tol[k]}
-    assert not bad, f"{bad} (all {errs})"
+    assert api.lib().lrnnx_selective_scan_bwd_chunks(1, 12, 16, 65536, 1, 0, 0) == 64
+    for path in ("single_pass", "auto"):
+        g = api.lrnnx_selective_scan_bwd(**t, dy=dev(p["dy"], "bf16"), ckpt=ckpt, want_dx0=True, path=path)
+        errs = {k: rel_err(host(g[k]), r[k]) for k in ("du", "ddelta", "dz", "dA", "dBm", "dCm", "dD", "dbias", "dx0")}
+        tol = {"du": 2e-2, "ddelta": 2e-2, "dz": 2e-2, "dA": 1e-4, "dBm": 1e-4, "dCm": 1e-4, "dD": 1e-4, "dbias": 1e-4,
+               "dx0": 1e-4}
+        bad = {k: v for k, v in errs.items() if not v <= tol[k]}
+        assert not bad, f"{path}: {bad} (all {errs})"
