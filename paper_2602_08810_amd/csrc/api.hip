@@ -109,6 +109,11 @@ size_t bwd_carry_bytes(int64_t B, int64_t D, int64_t N, int64_t L) {
     const int nch = a > f ? a : f;
     return nch > 1 ? (size_t)2 * B * D * nch * N * sizeof(float) : 0;
 }
+size_t cbwd_carry_bytes(int64_t B, int64_t D, int64_t N, int64_t L) {    // the same for the complex-A backward
+    const int a = cbwd_plan((int)B, (int)D, (int)N, L, 0, true).nchunks, f = cbwd_plan((int)B, (int)D, (int)N, L, 2, true).nchunks;
+    const int nch = a > f ? a : f;
+    return nch > 1 ? (size_t)2 * B * D * nch * N * sizeof(float2) : 0;
+}
 size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 // The real and the complex backward entry points take the same per-row tensors (same field names in both argument
@@ -198,9 +203,9 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
         if (!supported_n_complex((int)N)) return 0;
         return (size_t)2 * B * D * cfwd_chunks(B * cdiv(D, 8), L, true) * N * sizeof(float2);
     }
-    if (which == LRNNX_WS_BWD_COMPLEX) {
+    if (which == LRNNX_WS_BWD_COMPLEX) {            // checkpoints of the recompute sweep, then the chunk aggregates
         if (!supported_n_complex((int)N)) return 0;
-        return (size_t)B * D * cdiv(L, kCkptInterval) * N * sizeof(float2);
+        return align256((size_t)B * D * cdiv(L, kCkptInterval) * N * sizeof(float2)) + cbwd_carry_bytes(B, D, N, L);
     }
     if (which == LRNNX_WS_LTI) {
         const int nch = lti_chunks(B, D, L);
