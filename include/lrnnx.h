@@ -186,8 +186,9 @@ int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *args);
  * dx0 [B,D,N].  du, ddelta, dz [B,D,L] in io_dtype and dD, dbias [D] float are real.  The states are recomputed
  * tile by tile from checkpoints (Sec. 3): `ckpt` is the array a forward call wrote for the same inputs; if NULL the
  * library first runs a state-only forward sweep into `workspace`
- * (lrnnx_workspace_bytes(LRNNX_WS_BWD_COMPLEX, B, D, N, L, io_dtype), which also covers the chunked path's aggregates).  dA, dBm, dCm, dD, dbias are OVERWRITTEN
- * (cleared on the stream, then accumulated with atomics: their last bits may differ from run to run).
+ * (lrnnx_workspace_bytes(LRNNX_WS_BWD_COMPLEX, B, D, N, L, io_dtype), which also covers the chunked path's
+ * aggregates).  dA, dBm, dCm, dD, dbias are OVERWRITTEN (cleared on the stream, then accumulated with atomics: their
+ * last bits may differ from run to run).
  * Optional (NULL allowed): Dskip, delta_bias, z, x0, ckpt, dD, dbias, dz, dx0.  dD requires Dskip, dbias requires
  * delta_bias, dz requires z.  Alignment: Bm, Cm, dBm, dCm 16 bytes; A, x0, ckpt, dA, dx0 8 bytes.              */
 typedef struct lrnnx_ss_bwd_complex_args {
