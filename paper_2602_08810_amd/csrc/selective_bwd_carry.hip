@@ -34,7 +34,7 @@ __global__ __launch_bounds__(512, 2) void k_ss_bwd_agg(const BwdParams p) {
     const int slot = 63 - lane;                        // this lane's time slot within a tile
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int b = blockIdx.y;
-    const int chunk = blockIdx.z;
+    const int chunk = blockIdx.z + 1;                  // chunk 0 hands its adjoint to nobody: its pair is not needed
     // a workgroup takes W consecutive channels of ONE Bm/Cm group (it stages that group's Cm in LDS)
     const int blk_per_grp = (p.dpg + W - 1) / W;
     const int grp = blockIdx.x / blk_per_grp;
@@ -139,6 +139,7 @@ __global__ void k_ss_bwd_carry(const BwdParams p) {
     float h = 0.0f;
     for (int c = p.nchunks - 1; c >= 0; --c) {
         const int64_t j = (row * p.nchunks + c) * p.N + n;
+        if (c == 0) { p.ws_Q[j] = h; break; }                // the pair of chunk 0 was not computed
         const float P = p.ws_P[j], Q = p.ws_Q[j];
         p.ws_Q[j] = h;
         h = __builtin_fmaf(P, h, Q);
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(512, 2) void k_ss_cbwd_agg(const CBwdParams p) {
     const int slot = 63 - lane;                        // this lane's time slot within a tile
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int b = blockIdx.y;
-    const int chunk = blockIdx.z;
+    const int chunk = blockIdx.z + 1;                  // chunk 0 hands its adjoint to nobody: its pair is not needed
     const int blk_per_grp = (p.dpg + W - 1) / W;
     const int grp = blockIdx.x / blk_per_grp;
     const int d_in = (blockIdx.x % blk_per_grp) * W + w;
@@ -270,6 +271,7 @@ __global__ void k_ss_cbwd_carry(const CBwdParams p) {
     float2 h = make_float2(0.0f, 0.0f);
     for (int c = p.nchunks - 1; c >= 0; --c) {
         const int64_t j = (row * p.nchunks + c) * p.N + n;
+        if (c == 0) { p.ws_Q[j] = h; break; }                // the pair of chunk 0 was not computed
         const float2 P = p.ws_P[j], Q = p.ws_Q[j];
         p.ws_Q[j] = h;
         h = cxfma(P, h, Q);
@@ -279,7 +281,7 @@ __global__ void k_ss_cbwd_carry(const CBwdParams p) {
 // ---------------------------------------------------------------- launchers
 template <typename IO, int N, int DISC>
 static hipError_t launch_agg_n(const BwdParams &p, hipStream_t s) {
-    dim3 grid(p.bcg * ((p.dpg + 7) / 8), p.B, p.nchunks);
+    dim3 grid(p.bcg * ((p.dpg + 7) / 8), p.B, p.nchunks - 1);
     hipLaunchKernelGGL((k_ss_bwd_agg<IO, N, DISC>), grid, dim3(512), 0, s, p);
     return hipGetLastError();
 }
@@ -310,7 +312,7 @@ hipError_t launch_ss_bwd_agg(const BwdParams &p, int io_dtype, int disc, hipStre
 }
 template <typename IO, int DISC>
 static hipError_t launch_cagg_disc(const CBwdParams &p, hipStream_t s) {
-    dim3 grid(p.bcg * ((p.dpg + 7) / 8), p.B, p.nchunks);
+    dim3 grid(p.bcg * ((p.dpg + 7) / 8), p.B, p.nchunks - 1);
 #define LRNNX_CAGG(NN) hipLaunchKernelGGL((k_ss_cbwd_agg<IO, NN, DISC>), grid, dim3(512), 0, s, p); return hipGetLastError()
     switch (p.N) {
         case 1: LRNNX_CAGG(1);

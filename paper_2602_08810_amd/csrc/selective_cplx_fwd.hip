@@ -198,6 +198,7 @@ __global__ void k_ss_ccarry(const CFwdParams p) {
     float2 x = p.x0 ? p.x0[i] : make_float2(0.0f, 0.0f);
     for (int c = 0; c < p.nchunks; ++c) {
         const int64_t j = (row * p.nchunks + c) * p.N + n;
+        if (c + 1 == p.nchunks) { p.ws_S[j] = x; break; }     // nothing follows the last chunk: its pair was not computed
         const float2 P = p.ws_P[j], S = p.ws_S[j];
         p.ws_S[j] = x;
         x = cxfma(P, x, S);
@@ -208,7 +209,8 @@ __global__ void k_ss_ccarry(const CFwdParams p) {
 template <typename IO, int N, int DISC>
 static hipError_t launch_cfwd_n(const CFwdParams &p, hipStream_t s) {
     constexpr int W = 8, T = 8;
-    dim3 grid(p.bcg * ((p.dpg + W - 1) / W), p.B, p.nchunks > 1 ? p.nchunks : 1);
+    // the aggregate launch skips the last chunk: nobody needs its pair
+    dim3 grid(p.bcg * ((p.dpg + W - 1) / W), p.B, p.nchunks > 1 ? (p.mode == MODE_AGG ? p.nchunks - 1 : p.nchunks) : 1);
     if (p.mode == MODE_AGG) hipLaunchKernelGGL((k_ss_cfwd<IO, N, T, W, DISC, true>), grid, dim3(W * 64), 0, s, p);
     else hipLaunchKernelGGL((k_ss_cfwd<IO, N, T, W, DISC, false>), grid, dim3(W * 64), 0, s, p);
     return hipGetLastError();

@@ -332,6 +332,7 @@ __global__ void k_ss_carry(const FwdParams p) {
     float x = p.x0 ? p.x0[i] : 0.0f;
     for (int c = 0; c < p.nchunks; ++c) {
         const int64_t j = (row * p.nchunks + c) * p.N + n;
+        if (c + 1 == p.nchunks) { p.ws_S[j] = x; break; }     // nothing follows the last chunk: its pair was not computed
         const float P = p.ws_P[j], S = p.ws_S[j];
         p.ws_S[j] = x;
         x = __builtin_fmaf(P, x, S);
@@ -360,7 +361,9 @@ int fwd_channels_per_workgroup() { return kFwdW; }
 
 template <typename IO, int N, int DISC>
 static hipError_t launch_fwd_n(const FwdParams &p, hipStream_t s) {
-    dim3 grid(p.bcg * ((p.dpg + kFwdW - 1) / kFwdW), p.B, p.nchunks);
+    // the aggregate launch skips the last chunk: nobody needs its pair
+    if (p.mode == MODE_AGG && p.nchunks < 2) return hipSuccess;
+    dim3 grid(p.bcg * ((p.dpg + kFwdW - 1) / kFwdW), p.B, p.mode == MODE_AGG ? p.nchunks - 1 : p.nchunks);
     const bool want_y = (p.mode == MODE_FULL || p.mode == MODE_APPLY);
     const dim3 block(kFwdW * 64);
     if (want_y && p.ckpt) hipLaunchKernelGGL((k_ss_fwd<IO, N, kFwdT, kFwdW, DISC, true, true>), grid, block, 0, s, p);
