@@ -98,7 +98,8 @@ int64_t lrnnx_packed_ckpt_slots(int64_t L, int64_t B);
  * [D, lrnnx_packed_ckpt_slots(L,B), N].  Boundaries are clamped to [0,L] on the device; the single-pass path
  * is used (LRNNX_PATH_CHUNK_CARRY is refused).  A sequence whose first step is a multiple of 8 steps into the packed
  * axis is read and written with 16-byte accesses like an unpacked row; any other start is correct too but takes the
- * element-by-element path (about 40 % slower), so pad sequences to multiples of 8 steps where the rate matters.
+ * element-by-element path (forward about 30 % slower, backward a few per cent), so pad sequences to multiples of 8
+ * steps where the rate matters.
  * workspace is needed only by LRNNX_PATH_CHUNK_CARRY (AUTO falls back to the single
  * pass when it is missing or too small).                                              */
 typedef struct lrnnx_ss_fwd_args {
