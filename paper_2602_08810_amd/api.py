@@ -624,8 +624,9 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
     if want_dx0:
         a.dx0 = new("dx0", (Bsz, D, N), torch.float32).data_ptr()
     if workspace is None:
-        if packed:
-            nbytes = D * (L // lrnnx_ckpt_interval() + Bsz) * N * 4 if ckpt is None else 0
+        if packed:                                     # checkpoints of the recompute sweep, then the launch order
+            nbytes = (D * (L // lrnnx_ckpt_interval() + Bsz) * N * 4 + 255) // 256 * 256 if ckpt is None else 0
+            nbytes += 4 * Bsz
         else:                                          # checkpoints of the recompute sweep, then the chunk aggregates
             nch = int(lib().lrnnx_selective_scan_bwd_chunks(Bsz, D, N, L, a.bc_groups, a.path, 0))
             nbytes = 2 * Bsz * D * nch * N * 4 if nch > 1 else 0

@@ -532,6 +532,13 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
         if (launch_ss_bwd_agg(p, a->io_dtype, a->disc, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
         if (launch_ss_bwd_carry(p, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
     }
+    // packed batches: longest sequences first, if the workspace has room for the order (B ints, after the checkpoints
+    // of the recompute sweep if there are any)
+    if (cu && a->B > 1 && a->B <= kMaxOrdered && a->workspace && a->workspace_bytes >= carry_off + sizeof(int) * (size_t)a->B) {
+        int *order = reinterpret_cast<int *>(static_cast<char *>(a->workspace) + carry_off);
+        if (launch_seq_order(cu, a->B, a->L, order, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+        p.order = order;
+    }
 
     // reduced outputs are accumulated with atomics: clear them on the stream first
     const int64_t nbc = (cu ? 1 : (int64_t)a->B) * bcg * a->L * a->N;   // packed mode: one time axis for all sequences

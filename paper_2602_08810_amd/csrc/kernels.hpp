@@ -98,8 +98,12 @@ struct BwdParams {
     int64_t tiles_per_chunk;
     float *ws_P, *ws_Q;
     const float *hc;
+    // packed mode: sequences in the order the launch should start them (longest first), or null for 0, 1, 2, ...
+    const int *order;
 };
 constexpr int kBwdTileSteps = 256;
+constexpr int kMaxOrdered = 4096;    // packed batches of more sequences than this are not reordered
+hipError_t launch_seq_order(const int64_t *cu, int B, int64_t L, int *order, hipStream_t s);
 
 struct LtiParams {
     int B, P;

@@ -278,6 +278,30 @@ __global__ void k_ss_cbwd_carry(const CBwdParams p) {
     }
 }
 
+// Packed variable-length batches: order[r] = index of the sequence with the r-th largest length (ties by index).
+// One small block; B is at most kMaxOrdered, so the quadratic ranking is a few microseconds.
+__global__ void k_seq_order(const int64_t *cu, int B, int64_t L, int *order) {
+    auto len = [&](int j) {
+        int64_t o = cu[j], e = cu[j + 1];
+        o = o < 0 ? 0 : (o > L ? L : o);
+        e = e < o ? o : (e > L ? L : e);
+        return e - o;
+    };
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        const int64_t lb = len(b);
+        int rank = 0;
+        for (int j = 0; j < B; ++j) {
+            const int64_t lj = len(j);
+            rank += (lj > lb || (lj == lb && j < b)) ? 1 : 0;
+        }
+        order[rank] = b;
+    }
+}
+hipError_t launch_seq_order(const int64_t *cu, int B, int64_t L, int *order, hipStream_t s) {
+    hipLaunchKernelGGL(k_seq_order, dim3(1), dim3(256), 0, s, cu, B, L, order);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- launchers
 template <typename IO, int N, int DISC>
 static hipError_t launch_agg_n(const BwdParams &p, hipStream_t s) {
