@@ -224,7 +224,8 @@ typedef struct lrnnx_ss_bwd_complex_args {
     void *stream;
     const int64_t *cu_seqlens;   /* packed mode as in the forward call (then du, ddelta, dz are [D,L], dBm, dCm
                                     [G,L,N], ckpt [D, lrnnx_packed_ckpt_slots(L,B), N] and the workspace that replaces
-                                    it D * lrnnx_packed_ckpt_slots(L,B) * N float pairs); callers built against the
+                                    it D * lrnnx_packed_ckpt_slots(L,B) * N float pairs; B more ints after that let
+                                    the launch start the longest sequences first); callers built against the
                                     shorter struct get NULL */
     int32_t path;                /* lrnnx_path, as in lrnnx_ss_bwd_args: CHUNK_CARRY cuts the time axis into chunks
                                     that run side by side; its aggregates (2 * B * D * chunks * N float pairs) go into

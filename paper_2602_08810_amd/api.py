@@ -545,8 +545,9 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
     if want_dx0:
         a.dx0 = new("dx0", (Bsz, D, N), c64).data_ptr()
     if workspace is None:
-        if packed:
-            nbytes = D * (L // I + Bsz) * N * 8 if ckpt is None else 0
+        if packed:                                     # checkpoints of the recompute sweep, then the launch order
+            nbytes = (D * (L // I + Bsz) * N * 8 + 255) // 256 * 256 if ckpt is None else 0
+            nbytes += 4 * Bsz
         else:                                          # checkpoints of the recompute sweep, then the chunk aggregates
             nch = int(lib().lrnnx_selective_scan_bwd_chunks(Bsz, D, N, L, G, a.path, 1))
             nbytes = 2 * Bsz * D * nch * N * 8 if nch > 1 else 0

@@ -448,6 +448,12 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
         if (launch_ss_cbwd_agg(p, a->io_dtype, a->disc, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
         if (launch_ss_cbwd_carry(p, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
     }
+    // packed batches: longest sequences first, if the workspace has room for the order (as in the real backward)
+    if (cu && a->B > 1 && a->B <= kMaxOrdered && a->workspace && a->workspace_bytes >= carry_off + sizeof(int) * (size_t)a->B) {
+        int *order = reinterpret_cast<int *>(static_cast<char *>(a->workspace) + carry_off);
+        if (launch_seq_order(cu, a->B, a->L, order, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+        p.order = order;
+    }
 
     const int64_t nbc = (cu ? 1 : (int64_t)a->B) * bcg * a->L * a->N * 2;   // floats; packed mode: one time axis for all sequences
     FillList z{};

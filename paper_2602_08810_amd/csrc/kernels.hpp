@@ -74,6 +74,7 @@ struct CBwdParams {
     int64_t tiles_per_chunk;
     float2 *ws_P, *ws_Q;
     const float2 *hc;
+    const int *order;        // packed mode: sequences in the order the launch should start them, or null
 };
 
 struct BwdParams {

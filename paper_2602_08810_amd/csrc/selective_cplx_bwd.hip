@@ -84,7 +84,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int b = blockIdx.y;
+    const int b = p.order ? p.order[blockIdx.y] : blockIdx.y;   // packed batches: the longest sequences start first
     // a workgroup takes up to G consecutive channels of ONE Bm/Cm group
     const int chunks_per_grp = (p.dpg + p.G - 1) / p.G;
     const int grp = blockIdx.x / chunks_per_grp;
