@@ -103,7 +103,7 @@ struct BwdParams {
     const int *order;
 };
 constexpr int kBwdTileSteps = 256;
-constexpr int kMaxOrdered = 4096;    // packed batches of more sequences than this are not reordered
+constexpr int kMaxOrdered = 256;     // packed batches of more sequences than this are not reordered
 hipError_t launch_seq_order(const int64_t *cu, int B, int64_t L, int *order, hipStream_t s);
 
 struct LtiParams {

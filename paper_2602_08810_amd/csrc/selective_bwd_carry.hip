@@ -279,19 +279,21 @@ __global__ void k_ss_cbwd_carry(const CBwdParams p) {
 }
 
 // Packed variable-length batches: order[r] = index of the sequence with the r-th largest length (ties by index).
-// One small block; B is at most kMaxOrdered, so the quadratic ranking is a few microseconds.
+// One small block; B is at most kMaxOrdered, the lengths sit in LDS, so the quadratic ranking is a few microseconds.
 __global__ void k_seq_order(const int64_t *cu, int B, int64_t L, int *order) {
-    auto len = [&](int j) {
+    __shared__ int64_t slen[kMaxOrdered];
+    for (int j = threadIdx.x; j < B; j += blockDim.x) {
         int64_t o = cu[j], e = cu[j + 1];
         o = o < 0 ? 0 : (o > L ? L : o);
         e = e < o ? o : (e > L ? L : e);
-        return e - o;
-    };
+        slen[j] = e - o;
+    }
+    __syncthreads();
     for (int b = threadIdx.x; b < B; b += blockDim.x) {
-        const int64_t lb = len(b);
+        const int64_t lb = slen[b];
         int rank = 0;
         for (int j = 0; j < B; ++j) {
-            const int64_t lj = len(j);
+            const int64_t lj = slen[j];
             rank += (lj > lb || (lj == lb && j < b)) ? 1 : 0;
         }
         order[rank] = b;
