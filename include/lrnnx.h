@@ -282,7 +282,8 @@ typedef struct lrnnx_ss_bwd_args {
                                     shorter struct get NULL.  With ckpt == NULL the workspace must hold
                                     D * lrnnx_packed_ckpt_slots(L,B) * N floats.  If it has room for B more ints
                                     (after those floats, rounded up to 256 bytes; at its start when ckpt is given)
-                                    the launch starts the longest sequences first, which shortens its tail. */
+                                    the launch starts the longest sequences first (batches of up to 256
+                                    sequences), which shortens its tail. */
     int32_t path;                /* lrnnx_path.  CHUNK_CARRY: the time axis is cut into chunks that run side by side
                                     (three launches: adjoint aggregate per chunk, chain, backward per chunk), for long
                                     sequences with few rows; needs the workspace.  SINGLE_PASS: one workgroup walks a
