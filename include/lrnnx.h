@@ -140,8 +140,9 @@ int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *args);
  * real as above.  A [D,N] complex float pairs; Bm, Cm [B,L,N] complex in io_dtype (interleaved re, im: bfloat16
  * pairs or float pairs), contiguous, 16-byte aligned ([B,G,L,N] with bc_groups = G > 1, as for the real scan);
  * x0, x_last [B,D,N] complex float pairs (optional).
- * a and g are the four schemes of lrnnx_disc in complex arithmetic.  Delta * Im(A) must stay within
- * +-256 * 2 pi (the range of the hardware sine and cosine).  One pass over the sequence.
+ * a and g are the four schemes of lrnnx_disc in complex arithmetic.  Any Delta * Im(A) is accepted (whole
+ * revolutions are dropped before the hardware sine and cosine); the phase of a step is as accurate as its fp32
+ * product, |Delta Im(A)| * 2^-24 radians.
  * ckpt (optional): [B,D,ceil(L/lrnnx_ckpt_interval()),N] complex float pairs, the state entering every
  * lrnnx_ckpt_interval()-th step, for lrnnx_selective_scan_bwd_complex.  y may be NULL when only the checkpoints
  * (and x_last) are wanted.

@@ -10,14 +10,18 @@ namespace lrnnx {
 __device__ __forceinline__ float2 cmul(float2 a, float2 b) {
     return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
 }
-__device__ __forceinline__ float2 cpow(float2 a, int64_t e) {            // a^e by repeated squaring
-    float2 r = make_float2(1.0f, 0.0f);
+// a^e by repeated squaring, carried in double precision and rounded once.  The powers lambda^len multiply the states
+// carried between wavefronts and workgroups; a relative error eps in lambda^len acts like an error eps/len in lambda
+// itself, to which a state with memory 1/(1-|lambda|) steps is 1/(1-|lambda|) times as sensitive: squaring in fp32
+// (eps of about len * 2^-24) cost an order of magnitude in the accuracy of x and of the gradient with respect to lambda.
+__device__ __forceinline__ float2 cpow(float2 a, int64_t e) {
+    double ar = a.x, ai = a.y, rr = 1.0, ri = 0.0;
     while (e > 0) {
-        if (e & 1) r = cmul(r, a);
-        a = cmul(a, a);
+        if (e & 1) { const double t = rr * ar - ri * ai; ri = rr * ai + ri * ar; rr = t; }
+        const double t = ar * ar - ai * ai; ai = 2.0 * ar * ai; ar = t;
         e >>= 1;
     }
-    return r;
+    return make_float2((float)rr, (float)ri);
 }
 __device__ __forceinline__ float2 cfma(float2 a, float2 b, float2 c) {   // a*b + c
     return make_float2(__builtin_fmaf(a.x, b.x, __builtin_fmaf(-a.y, b.y, c.x)),

@@ -34,10 +34,12 @@ __device__ __forceinline__ void load_cwords(const CW *p, CW *out) {
 
 constexpr float kInv2Pi = 0.15915494309189535f;
 
-// a = exp(dt A) for complex A = (Ar, Ai): e^{dt Ar} (cos(dt Ai), sin(dt Ai)); v_sin/v_cos take revolutions
+// a = exp(dt A) for complex A = (Ar, Ai): e^{dt Ar} (cos(dt Ai), sin(dt Ai)).  v_sin/v_cos take revolutions and are
+// only valid within +-256 of them, so the whole revolutions are dropped first (v_fract_f32): any dt Im(A) is
+// accepted; the phase keeps the absolute accuracy of the fp32 product, |dt Im(A) / 2 pi| * 2^-24 revolutions.
 __device__ __forceinline__ float2 cexp_dt(float dt, float A2r, float Arev) {
     const float e = exp2_fast(dt * A2r);
-    const float rev = dt * Arev;
+    const float rev = __builtin_amdgcn_fractf(dt * Arev);
     return make_float2(e * __builtin_amdgcn_cosf(rev), e * __builtin_amdgcn_sinf(rev));
 }
 

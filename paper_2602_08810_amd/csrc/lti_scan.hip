@@ -41,10 +41,10 @@ __global__ __launch_bounds__(kLtiThreads) void k_lti_chunk(const LtiParams p) {
     if (APPLY && okp && okc) {
         if (p.x0) x = p.x0[(int64_t)b * p.P + pp];
         if (p.nchunks > 1) {
-            const float2 lg = cpow(lp, kLtiWaves);
+            const float2 lg = cpow(lam, p.chunk * kLtiWaves);
             const float2 *G = p.ws_G + (int64_t)b * p.ngroups * p.P + pp;
             for (int g = 0; g < grp; ++g) x = cfma(lg, x, G[(int64_t)g * p.P]);
-            x = cfma(cpow(lp, w), x, p.ws_S[((int64_t)b * p.nchunks + c) * p.P + pp]);
+            x = cfma(cpow(lam, p.chunk * w), x, p.ws_S[((int64_t)b * p.nchunks + c) * p.P + pp]);
         }
     }
     if (okp && okc) {
@@ -113,7 +113,7 @@ __global__ __launch_bounds__(kOneGW * 64) void k_lti_onepass(const LtiParams p) 
     const int64_t k0 = ((int64_t)g * kOneGW + w) * CS;
     float2 lam = okp ? p.lambda[pp] : make_float2(0.0f, 0.0f);
     if (BWD) lam.y = -lam.y;
-    const float2 lp = cpow(lam, CS), lg = cpow(lp, kOneGW);
+    const float2 lp = cpow(lam, CS), lg = cpow(lam, CS * kOneGW);
     // Row pointers are wave-uniform (scalar registers) and the lane adds only its p, so a whole chunk needs one
     // vector offset register; scan position k0+i is time k0+i (forward) or L-1-(k0+i) (adjoint).
     const int64_t tstep = BWD ? -P : P;                        // element stride between consecutive scan positions
@@ -206,7 +206,7 @@ __global__ __launch_bounds__(kOneGW * 64) void k_lti_onepass(const LtiParams p) 
     __syncthreads();
 
     // ---- replay from the true carry-in, out of registers
-    x = cfma(cpow(lp, w), sCarry[lane], e);
+    x = cfma(cpow(lam, CS * w), sCarry[lane], e);
     float2 *xrow_out = p.x + row0;
     float2 dl = make_float2(0.0f, 0.0f);
     float2 xl = x;                                             // state at the last scan position of the sequence

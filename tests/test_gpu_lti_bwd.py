@@ -2,10 +2,9 @@
 
 The kernel takes the states its own forward call saved; the oracle recomputes them in fp64 from (lam, v, x0).
 Tolerance: max-abs error over the tensor's max-abs value <= 1e-4 for fp32 storage (the bar of the forward scan) for
-dv and dx0.  dlam = sum conj(x_{k-1}) g_k multiplies two fp32-scanned sequences whose rounding errors are correlated
-over the memory length 1/(1-|lam|) (so they do not average out over the sum) and whose error relative to their RMS is
-about four times the max-normalised one: its bar is 5e-4 (observed up to 2e-4 with |lam| up to 0.999; the
-accumulation itself, checked against an fp64 sum of the kernel's own x and dv, is at 1e-6).
+every output, dlam = sum conj(x_{k-1}) g_k included.  (dlam sums products of two fp32-scanned sequences and is the
+output most sensitive to a systematic error in the powers lambda^len that carry states between wavefronts and
+workgroups: those powers are formed in double precision and rounded once.)
 """
 import numpy as np
 import pytest
@@ -39,7 +38,7 @@ def _run(api, oracle, B, P, L, with_x0, seed, inplace=False):
     rdv, rdlam, rdx0 = oracle.lti_diag_scan_bwd(q["lam"], q["v"], q["gx"], x0=q["x0"])
     got = dv.cpu().numpy()
     assert _crel(got, rdv) <= 1e-4, "dv"
-    assert _crel(dlam.cpu().numpy(), rdlam) <= 5e-4, "dlam"
+    assert _crel(dlam.cpu().numpy(), rdlam) <= 1e-4, "dlam"
     assert _crel(dx0.cpu().numpy(), rdx0) <= 1e-4, "dx0"
     return got, dlam.cpu().numpy()
 
