@@ -323,6 +323,21 @@ typedef struct lrnnx_lti_args {
 
 int lrnnx_lti_diag_scan(const lrnnx_lti_args *args);
 
+/* ------------------------------------------------------------------ LTI scan without a caller's workspace
+ * For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation): the single-launch scan of lrnnx_lti_diag_scan with its chain workspace taken from a
+ * scratch array of LRNNX_STATIC_SCRATCH_BYTES bytes that is part of the library's device image (every GPU the
+ * library runs on holds its own copy until the process ends).  Same struct, same results bit for bit; `workspace`
+ * and `workspace_bytes` are ignored, `path` must be AUTO or SINGLE_PASS.  The call allocates and frees nothing
+ * (neither does any other entry point; this one also needs no buffer beyond inputs and outputs).  Shapes whose
+ * chain needs more than the array (lrnnx_workspace_bytes(LRNNX_WS_LTI, B, P, 0, L, 0) is an upper bound of the
+ * need; roughly B * P * L / 15 bytes) are refused with LRNNX_ERR_WORKSPACE and nothing is launched.  All calls on
+ * one GPU share that GPU's array: the library re-arms it on the stream at the start of every call, and two calls
+ * whose execution overlaps on one GPU (different streams) race on it; calls on one stream are safe.              */
+#define LRNNX_STATIC_SCRATCH_BYTES (4u << 20)
+size_t lrnnx_static_scratch_bytes(void);
+int lrnnx_lti_diag_scan_static(const lrnnx_lti_args *args);
+
 /* ------------------------------------------------------------------ diagonal scan with caller-supplied coefficients
  *     x[b,k,p] = a[b,k,p] * x[b,k-1,p] + b[b,k,p]
  * Eq. 2 with A(k) = diag(a_k) and the input term b_k = B(k) u_k already formed: the recurrence of the

@@ -180,6 +180,9 @@ def lib():
         L.lrnnx_selective_scan_bwd_complex.argtypes = [ctypes.POINTER(BwdComplexArgs)]
         L.lrnnx_selective_scan_bwd_complex.restype = ctypes.c_int
         L.lrnnx_lti_diag_scan.argtypes = [ctypes.POINTER(LtiArgs)]
+        L.lrnnx_lti_diag_scan_static.argtypes = [ctypes.POINTER(LtiArgs)]
+        L.lrnnx_lti_diag_scan_static.restype = ctypes.c_int
+        L.lrnnx_static_scratch_bytes.restype = _sz
         L.lrnnx_lti_diag_scan_bwd.argtypes = [ctypes.POINTER(LtiBwdArgs)]
         L.lrnnx_lti_diag_scan_bwd.restype = ctypes.c_int
         L.lrnnx_diag_scan.argtypes = [ctypes.POINTER(DiagScanArgs)]
@@ -672,6 +675,31 @@ def lrnnx_lti_diag_scan(lam, v, x0=None, return_last_state=False, out=None, work
     a.stream = _stream()
     _check(lib().lrnnx_lti_diag_scan(ctypes.byref(a)))
     return (x, x_last) if return_last_state else x
+
+
+@_device_checked
+def lrnnx_lti_diag_scan_static(lam, v, out, x0=None, x_last_out=None):
+    """The LTI scan on the library's own static scratch array: no workspace is passed and the C call allocates
+    nothing; see lrnnx_lti_diag_scan_static.  The caller supplies every buffer: `out` [B,L,P] complex64 (may be v
+    itself) and optionally `x_last_out` [B,P].  Returns `out`."""
+    for name, t in (("lam", lam), ("v", v), ("out", out)):
+        if t.dtype != torch.complex64 or not t.is_contiguous():
+            raise ValueError(f"{name}: expected contiguous complex64")
+    Bsz, L, P = v.shape
+    if tuple(out.shape) != (Bsz, L, P) or tuple(lam.shape) != (P,):
+        raise ValueError("shape mismatch between lam [P], v and out [B,L,P]")
+    a = LtiArgs()
+    a.struct_size = ctypes.sizeof(LtiArgs)
+    a.B, a.P, a.L = Bsz, P, L
+    a.path = PATH["auto"]
+    a.lambda_, a.v, a.x = lam.data_ptr(), v.data_ptr(), out.data_ptr()
+    for name, t in (("x0", x0), ("x_last_out", x_last_out)):
+        if t is not None and (t.dtype != torch.complex64 or not t.is_contiguous() or tuple(t.shape) != (Bsz, P)):
+            raise ValueError(f"{name}: expected contiguous complex64 [B,P]")
+    a.x0, a.x_last = _ptr(x0), _ptr(x_last_out)
+    a.stream = _stream()
+    _check(lib().lrnnx_lti_diag_scan_static(ctypes.byref(a)))
+    return out
 
 
 @_device_checked

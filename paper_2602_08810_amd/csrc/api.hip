@@ -2,6 +2,7 @@
 // Nothing here allocates, frees or synchronises; see include/lrnnx.h for the contract.
 #include "../../include/lrnnx.h"
 #include "kernels.hpp"
+#include <atomic>
 #include <cstddef>
 
 using namespace lrnnx;
@@ -558,18 +559,11 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     return launch_ss_bwd(p, a->io_dtype, a->disc, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }
 
-int lrnnx_lti_diag_scan(const lrnnx_lti_args *a) {
-    constexpr size_t kOldSize = offsetof(lrnnx_lti_args, path);          // struct before `path` was appended
-    if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
-    const int path = a->struct_size >= sizeof(lrnnx_lti_args) ? a->path : LRNNX_PATH_AUTO;
-    if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
-    if (a->B < 1 || a->P < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
-    if (!a->lambda || !a->v || !a->x) return LRNNX_ERR_INVALID_ARG;
-    if ((reinterpret_cast<uintptr_t>(a->v) & 7u) || (reinterpret_cast<uintptr_t>(a->x) & 7u) ||
-        (reinterpret_cast<uintptr_t>(a->lambda) & 7u))
-        return LRNNX_ERR_INVALID_ARG;
-    if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
-    hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
+// the single-launch path on a chain workspace of at least lti_onepass_bytes(B, P, L) bytes (checked by the callers)
+static int lti_onepass_run(const lrnnx_lti_args *a, void *ws, hipStream_t s) {
+    const int64_t ng = cdiv(a->L, lti_onepass_group_steps(a->B, a->P));
+    const int64_t wgx = (int64_t)a->B * cdiv(a->P, 64);
+    if (ng > 65535 || wgx > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;
     LtiParams p{};
     p.B = a->B; p.P = a->P; p.L = a->L;
     p.lambda = reinterpret_cast<const float2 *>(a->lambda);
@@ -577,20 +571,44 @@ int lrnnx_lti_diag_scan(const lrnnx_lti_args *a) {
     p.x0 = reinterpret_cast<const float2 *>(a->x0);
     p.x = reinterpret_cast<float2 *>(a->x);
     p.x_last = reinterpret_cast<float2 *>(a->x_last);
+    p.ngroups = (int)ng;
+    set_onepass_workspace(p, ws);
+    if (launch_fill(onepass_fill(p), s) != hipSuccess) return LRNNX_ERR_LAUNCH;
+    return launch_lti_onepass(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+}
+
+static int lti_args_valid(const lrnnx_lti_args *a) {
+    if (a->B < 1 || a->P < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
+    if (!a->lambda || !a->v || !a->x) return LRNNX_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(a->v) & 7u) || (reinterpret_cast<uintptr_t>(a->x) & 7u) ||
+        (reinterpret_cast<uintptr_t>(a->lambda) & 7u) || (reinterpret_cast<uintptr_t>(a->x0) & 7u) ||
+        (reinterpret_cast<uintptr_t>(a->x_last) & 7u))
+        return LRNNX_ERR_INVALID_ARG;
+    if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
+    return LRNNX_OK;
+}
+
+int lrnnx_lti_diag_scan(const lrnnx_lti_args *a) {
+    if (!a || a->struct_size < sizeof(lrnnx_lti_args)) return LRNNX_ERR_INVALID_ARG;
+    const int path = a->path;
+    if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
+    if (const int st = lti_args_valid(a)) return st;
+    hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
 
     if (path != LRNNX_PATH_CHUNK_CARRY) {
-        const int64_t ng = cdiv(a->L, lti_onepass_group_steps(a->B, a->P));
-        const int64_t wgx = (int64_t)a->B * cdiv(a->P, 64);
-        if (ng > 65535 || wgx > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;
         if (!a->workspace || a->workspace_bytes < lti_onepass_bytes(a->B, a->P, a->L) ||
             (reinterpret_cast<uintptr_t>(a->workspace) & 7u))
             return LRNNX_ERR_WORKSPACE;
-        p.ngroups = (int)ng;
-        set_onepass_workspace(p, a->workspace);
-        if (launch_fill(onepass_fill(p), s) != hipSuccess) return LRNNX_ERR_LAUNCH;
-        return launch_lti_onepass(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+        return lti_onepass_run(a, a->workspace, s);
     }
 
+    LtiParams p{};
+    p.B = a->B; p.P = a->P; p.L = a->L;
+    p.lambda = reinterpret_cast<const float2 *>(a->lambda);
+    p.v = reinterpret_cast<const float2 *>(a->v);
+    p.x0 = reinterpret_cast<const float2 *>(a->x0);
+    p.x = reinterpret_cast<float2 *>(a->x);
+    p.x_last = reinterpret_cast<float2 *>(a->x_last);
     int nch = lti_chunks(a->B, a->P, a->L);
     p.chunk = cdiv(a->L, nch);
     p.nchunks = (int)cdiv(a->L, p.chunk);
@@ -603,6 +621,39 @@ int lrnnx_lti_diag_scan(const lrnnx_lti_args *a) {
         p.ws_G = p.ws_S + (size_t)a->B * p.nchunks * a->P;
     }
     return launch_lti(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
+}
+
+// ---------------------------------------------------------------- the entry point that allocates nothing
+// lrnnx_lti_diag_scan needs a chain workspace from its caller.  Callers that cannot allocate device memory (code
+// under HIP graph capture, serving loops, harnesses that forbid allocation) get the same scan on a scratch array that
+// is part of the library's device image: every GPU the library runs on holds its own copy until the process ends.
+static __device__ __align__(256) unsigned char scratch[LRNNX_STATIC_SCRATCH_BYTES];
+
+// Device address of `scratch` on the current device, looked up once per device (the name itself is only a host-side
+// stand-in for the symbol: it must never reach a kernel, a fill or a copy).  NULL if the runtime refuses.
+static void *static_scratch_ptr() {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void *> ptrs[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *ptr = ptrs[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        ptrs[dev].store(ptr, std::memory_order_release);      // every thread that races here finds the same address
+    }
+    return ptr;
+}
+
+size_t lrnnx_static_scratch_bytes(void) { return LRNNX_STATIC_SCRATCH_BYTES; }
+
+int lrnnx_lti_diag_scan_static(const lrnnx_lti_args *a) {
+    if (!a || a->struct_size < sizeof(lrnnx_lti_args)) return LRNNX_ERR_INVALID_ARG;
+    if (a->path != LRNNX_PATH_AUTO && a->path != LRNNX_PATH_SINGLE_PASS) return LRNNX_ERR_INVALID_ARG;
+    if (const int st = lti_args_valid(a)) return st;
+    if (lti_onepass_bytes(a->B, a->P, a->L) > LRNNX_STATIC_SCRATCH_BYTES) return LRNNX_ERR_WORKSPACE;
+    void *ws = static_scratch_ptr();
+    if (!ws) return LRNNX_ERR_LAUNCH;
+    return lti_onepass_run(a, ws, reinterpret_cast<hipStream_t>(a->stream));
 }
 
 int lrnnx_lti_diag_scan_bwd(const lrnnx_lti_bwd_args *a) {
