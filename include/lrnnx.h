@@ -27,15 +27,16 @@
  *   - The return value is an lrnnx_status.  On any status other than LRNNX_OK nothing
  *     has been launched and no output has been touched.  No C++ exception crosses the
  *     ABI and the library never aborts.
- *   - `struct_size` must be set to sizeof(the struct); a smaller value is rejected, except
- *     where a struct has grown: fields appended later default as their comments say.
+ *   - `struct_size` must be set to sizeof(the struct) of the header the caller was built with; any other
+ *     value is rejected (lrnnx_version() tells which layout a library build expects).
  *   - Tensors named [B,D,L] have the time axis contiguous (stride 1) and explicit
  *     batch / channel strides counted in ELEMENTS; a channel stride of 0 broadcasts
  *     one row over all channels (inputs only).  Tensors [B,L,N], [D,N], [D], [B,D,N]
  *     are contiguous.  io_dtype selects the element type of u, delta, z, Bm, Cm, y, dy,
  *     du, ddelta, dz (float or bfloat16); the state, all accumulation, A, Dskip,
  *     delta_bias, x0, x_last, checkpoints and the reduced gradients are float.
- *   - Supported: N in {1,2,4,8,16,32} (the complex-A entry points: up to 16); any B, D >= 1; any L >= 1
+ *   - Supported: N in {1,2,4,8,16,32} (the complex-A entry points: up to 16); 1 <= B <= 65535 (a launch grid
+ *     dimension; more batch entries are refused with LRNNX_ERR_UNSUPPORTED); any D >= 1; any L >= 1
  *     (B*D*L must fit int64).
  */
 #ifndef LRNNX_H
@@ -105,11 +106,13 @@ int64_t lrnnx_packed_ckpt_slots(int64_t L, int64_t B);
 typedef struct lrnnx_ss_fwd_args {
     size_t struct_size;
     int32_t B, D, N;
+    int32_t bc_groups;       /* number of Bm/Cm groups G; 0 or 1: none */
     int64_t L;
     int32_t io_dtype;        /* lrnnx_dtype */
     int32_t disc;            /* lrnnx_disc */
     int32_t delta_softplus;  /* 0 or 1 */
     int32_t path;            /* lrnnx_path */
+    const int64_t *cu_seqlens;   /* packed variable-length mode: device memory [B+1], 8-byte aligned; or NULL */
     const void *u;      int64_t u_stride_b, u_stride_d;            /* [B,D,L] io */
     const void *delta;  int64_t delta_stride_b, delta_stride_d;    /* [B,D,L] io, raw (pre-bias, pre-softplus) */
     const float *A;                                                /* [D,N] */
@@ -124,9 +127,6 @@ typedef struct lrnnx_ss_fwd_args {
     float *ckpt;                                                   /* [B,D,ceil(L/interval),N] out or NULL */
     void *workspace;    size_t workspace_bytes;
     void *stream;
-    int32_t bc_groups;       /* number of Bm/Cm groups; callers built against the shorter struct get 1 */
-    int32_t reserved;
-    const int64_t *cu_seqlens;   /* packed variable-length mode (see below), device memory [B+1], or NULL */
 } lrnnx_ss_fwd_args;
 
 int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *args);
@@ -152,8 +152,14 @@ int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *args);
 typedef struct lrnnx_ss_fwd_complex_args {
     size_t struct_size;
     int32_t B, D, N;
+    int32_t bc_groups;       /* number of Bm/Cm groups G (maps [B,G,L,N], channel d reads group d / (D/G), D a multiple of
+                                G); 0 or 1: none */
     int64_t L;
-    int32_t io_dtype, disc, delta_softplus, reserved;
+    int32_t io_dtype, disc, delta_softplus;
+    int32_t path;            /* lrnnx_path as in lrnnx_ss_fwd_args: CHUNK_CARRY = aggregate per chunk of the time axis,
+                                chain, rerun from the true carry-in (three launches, for few rows and long sequences);
+                                AUTO picks it then if the workspace allows; not with cu_seqlens */
+    const int64_t *cu_seqlens;   /* packed variable-length mode, device memory [B+1], or NULL */
     const void *u;      int64_t u_stride_b, u_stride_d;
     const void *delta;  int64_t delta_stride_b, delta_stride_d;
     const void *A;                                                 /* [D,N] complex float */
@@ -165,20 +171,9 @@ typedef struct lrnnx_ss_fwd_complex_args {
     const void *x0;                                                /* [B,D,N] complex float or NULL */
     void *y;            int64_t y_stride_b, y_stride_d;
     void *x_last;                                                  /* [B,D,N] complex float, out or NULL */
+    void *ckpt;                                                    /* out or NULL */
+    void *workspace;    size_t workspace_bytes;   /* needed by LRNNX_PATH_CHUNK_CARRY only: LRNNX_WS_FWD_COMPLEX */
     void *stream;
-    void *ckpt;         /* out or NULL; callers built against the shorter struct get NULL */
-    int32_t bc_groups;  /* number of Bm/Cm groups G (maps [B,G,L,N], channel d reads group d / (D/G), D a multiple of
-                           G); 0 or 1: none; callers built against a shorter struct get 1 */
-    int32_t reserved2;
-    const int64_t *cu_seqlens;   /* packed variable-length mode, device memory [B+1], or NULL; callers built against a
-                                    shorter struct get NULL */
-    void *workspace;    size_t workspace_bytes;   /* needed by LRNNX_PATH_CHUNK_CARRY only:
-                                    lrnnx_workspace_bytes(LRNNX_WS_FWD_COMPLEX, B, D, N, L, io_dtype) */
-    int32_t path;                /* lrnnx_path as in lrnnx_ss_fwd_args: CHUNK_CARRY = aggregate per chunk of the time
-                                    axis, chain, rerun from the true carry-in (three launches, for few rows and long
-                                    sequences); AUTO picks it then if the workspace allows; not with cu_seqlens.
-                                    Callers built against a shorter struct get SINGLE_PASS. */
-    int32_t reserved3;
 } lrnnx_ss_fwd_complex_args;
 
 int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *args);
@@ -198,9 +193,15 @@ int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *args);
 typedef struct lrnnx_ss_bwd_complex_args {
     size_t struct_size;
     int32_t B, D, N;
+    int32_t bc_groups;                                             /* as in the forward call (then dBm, dCm are [B,G,L,N]); 0 or 1: none */
     int64_t L;
     int32_t io_dtype, disc, delta_softplus;
-    int32_t bc_groups;                                             /* as in the forward call (then dBm, dCm are [B,G,L,N]); 0 or 1: none */
+    int32_t path;                /* lrnnx_path, as in lrnnx_ss_bwd_args: CHUNK_CARRY cuts the time axis into chunks
+                                    that run side by side; its aggregates (2 * B * D * chunks * N float pairs) go into
+                                    the workspace, after the 256-byte-aligned checkpoints of the recompute sweep if
+                                    ckpt == NULL */
+    const int64_t *cu_seqlens;   /* packed mode as in the forward call (then du, ddelta, dz are [D,L], dBm, dCm
+                                    [G,L,N], ckpt [D, lrnnx_packed_ckpt_slots(L,B), N]), or NULL */
     const void *u;      int64_t u_stride_b, u_stride_d;
     const void *delta;  int64_t delta_stride_b, delta_stride_d;
     const void *A;                                                 /* [D,N] complex float */
@@ -221,18 +222,8 @@ typedef struct lrnnx_ss_bwd_complex_args {
     float *dD;                                                     /* [D] out or NULL */
     float *dbias;                                                  /* [D] out or NULL */
     void *dx0;                                                     /* [B,D,N] complex float, out or NULL */
-    void *workspace;    size_t workspace_bytes;
+    void *workspace;    size_t workspace_bytes;                    /* LRNNX_WS_BWD_COMPLEX */
     void *stream;
-    const int64_t *cu_seqlens;   /* packed mode as in the forward call (then du, ddelta, dz are [D,L], dBm, dCm
-                                    [G,L,N], ckpt [D, lrnnx_packed_ckpt_slots(L,B), N] and the workspace that replaces
-                                    it D * lrnnx_packed_ckpt_slots(L,B) * N float pairs; B more ints after that let
-                                    the launch start the longest sequences first); callers built against the
-                                    shorter struct get NULL */
-    int32_t path;                /* lrnnx_path, as in lrnnx_ss_bwd_args: CHUNK_CARRY cuts the time axis into chunks
-                                    that run side by side; its aggregates (2 * B * D * chunks * N float pairs) go into
-                                    the workspace, after the 256-byte-aligned checkpoints of the recompute sweep if
-                                    ckpt == NULL.  Callers built against a shorter struct get AUTO. */
-    int32_t reserved;
 } lrnnx_ss_bwd_complex_args;
 
 int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *args);
@@ -254,9 +245,18 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *args);
 typedef struct lrnnx_ss_bwd_args {
     size_t struct_size;
     int32_t B, D, N;
+    int32_t bc_groups;                                             /* as in the forward call; 0 or 1: none */
     int64_t L;
     int32_t io_dtype, disc, delta_softplus;
-    int32_t bc_groups;                                             /* as in the forward call; 0 or 1: none */
+    int32_t path;                /* lrnnx_path.  CHUNK_CARRY: the time axis is cut into chunks that run side by side
+                                    (three launches: adjoint aggregate per chunk, chain, backward per chunk), for long
+                                    sequences with few rows; needs the workspace.  SINGLE_PASS: one workgroup walks a
+                                    whole row.  AUTO picks CHUNK_CARRY when a single pass would leave most of the chip
+                                    idle and the workspace allows it.  Not with cu_seqlens (single pass). */
+    const int64_t *cu_seqlens;   /* as in the forward call (then dBm, dCm are [G,L,N]), or NULL.  In packed mode the
+                                    workspace also holds B ints that let the launch start the longest sequences first
+                                    (batches of up to 256 sequences), which shortens its tail; a workspace without
+                                    room for them is accepted and the launch keeps the caller's order. */
     const void *u;      int64_t u_stride_b, u_stride_d;
     const void *delta;  int64_t delta_stride_b, delta_stride_d;
     const float *A;
@@ -277,21 +277,8 @@ typedef struct lrnnx_ss_bwd_args {
     float *dD;                                                     /* [D] out or NULL */
     float *dbias;                                                  /* [D] out or NULL */
     float *dx0;                                                    /* [B,D,N] out or NULL */
-    void *workspace;    size_t workspace_bytes;
+    void *workspace;    size_t workspace_bytes;                    /* LRNNX_WS_BWD, or LRNNX_WS_BWD_CARRY with ckpt */
     void *stream;
-    const int64_t *cu_seqlens;   /* as in the forward call (then dBm, dCm are [G,L,N]); callers built against the
-                                    shorter struct get NULL.  With ckpt == NULL the workspace must hold
-                                    D * lrnnx_packed_ckpt_slots(L,B) * N floats.  If it has room for B more ints
-                                    (after those floats, rounded up to 256 bytes; at its start when ckpt is given)
-                                    the launch starts the longest sequences first (batches of up to 256
-                                    sequences), which shortens its tail. */
-    int32_t path;                /* lrnnx_path.  CHUNK_CARRY: the time axis is cut into chunks that run side by side
-                                    (three launches: adjoint aggregate per chunk, chain, backward per chunk), for long
-                                    sequences with few rows; needs the workspace.  SINGLE_PASS: one workgroup walks a
-                                    whole row.  AUTO picks CHUNK_CARRY when a single pass would leave most of the chip
-                                    idle and the workspace allows it.  Not with cu_seqlens (single pass).  Callers
-                                    built against a shorter struct get AUTO. */
-    int32_t reserved;
 } lrnnx_ss_bwd_args;
 
 int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *args);
@@ -304,21 +291,23 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *args);
  * allowed).  x may alias v.  workspace: lrnnx_workspace_bytes(LRNNX_WS_LTI, B, P, 0, L, 0); its contents on entry
  * do not matter (the library clears what it uses on the stream).  The single-launch path chains workgroups
  * through values published in global memory, with bounded waits; should a wait ever run out, the states from that point of
- * that sequence on are written as NaN rather than left plausible.                     */
+ * that sequence on are written as NaN rather than left plausible, and *chain_status (if given) is set to 1.  */
 typedef struct lrnnx_lti_args {
     size_t struct_size;
     int32_t B, P;
     int64_t L;
+    int32_t path;            /* lrnnx_path: AUTO / SINGLE_PASS = one launch with look-back between time groups;
+                                CHUNK_CARRY = two launches */
+    int32_t reserved;
     const void *lambda;
     const void *v;
     const void *x0;
     void *x;
     void *x_last;
+    int32_t *chain_status;   /* device memory or NULL: set to 1 if a bounded wait of the single-launch path ran out
+                                (never cleared by the library: clear it before the call) */
     void *workspace;    size_t workspace_bytes;
     void *stream;
-    int32_t path;            /* lrnnx_path: AUTO / SINGLE_PASS = one launch with look-back between time groups;
-                                CHUNK_CARRY = two launches.  Callers built against the shorter struct get AUTO. */
-    int32_t reserved;
 } lrnnx_lti_args;
 
 int lrnnx_lti_diag_scan(const lrnnx_lti_args *args);
@@ -357,6 +346,7 @@ typedef struct lrnnx_diag_scan_args {
     const void *x0;
     void *x;
     void *x_last;
+    int32_t *chain_status;      /* as in lrnnx_lti_args, or NULL */
     void *workspace;    size_t workspace_bytes;
     void *stream;
 } lrnnx_diag_scan_args;
@@ -384,6 +374,7 @@ typedef struct lrnnx_diag_scan_bwd_args {
     void *da;               /* [B,L,P] out */
     void *db;               /* [B,L,P] out */
     void *dx0;              /* [B,P] out or NULL */
+    int32_t *chain_status;  /* as in lrnnx_lti_args, or NULL */
     void *workspace;    size_t workspace_bytes;
     void *stream;
 } lrnnx_diag_scan_bwd_args;
@@ -412,6 +403,7 @@ typedef struct lrnnx_lti_bwd_args {
     void *dv;               /* [B,L,P] out */
     void *dlambda;          /* [P] out */
     void *dx0;              /* [B,P] out or NULL */
+    int32_t *chain_status;  /* as in lrnnx_lti_args, or NULL */
     void *workspace;    size_t workspace_bytes;
     void *stream;
 } lrnnx_lti_bwd_args;
@@ -431,7 +423,8 @@ int lrnnx_lti_diag_scan_bwd(const lrnnx_lti_bwd_args *args);
 typedef struct lrnnx_ss_step_args {
     size_t struct_size;
     int32_t B, D, N;
-    int32_t io_dtype, disc, delta_softplus;
+    int32_t bc_groups;      /* G > 1: Bm, Cm are [B,G,N] and channel d reads group d / (D/G); 0 or 1: none */
+    int32_t io_dtype, disc, delta_softplus, reserved;
     float *x;
     const void *u;      int64_t u_stride_b, u_stride_d;
     const void *delta;  int64_t delta_stride_b, delta_stride_d;
@@ -443,8 +436,6 @@ typedef struct lrnnx_ss_step_args {
     const void *z;      int64_t z_stride_b, z_stride_d;
     void *y;            int64_t y_stride_b, y_stride_d;
     void *stream;
-    int32_t bc_groups;      /* callers built against the shorter struct get 1 */
-    int32_t reserved;
 } lrnnx_ss_step_args;
 
 int lrnnx_selective_step(const lrnnx_ss_step_args *args);
@@ -457,7 +448,8 @@ int lrnnx_selective_step(const lrnnx_ss_step_args *args);
 typedef struct lrnnx_ss_step_complex_args {
     size_t struct_size;
     int32_t B, D, N;
-    int32_t io_dtype, disc, delta_softplus;
+    int32_t bc_groups;      /* G > 1: Bm, Cm are [B,G,N] and channel d reads group d / (D/G); 0 or 1: none */
+    int32_t io_dtype, disc, delta_softplus, reserved;
     void *x;                                                       /* [B,D,N] complex float, in/out */
     const void *u;      int64_t u_stride_b, u_stride_d;
     const void *delta;  int64_t delta_stride_b, delta_stride_d;
@@ -469,9 +461,6 @@ typedef struct lrnnx_ss_step_complex_args {
     const void *z;      int64_t z_stride_b, z_stride_d;
     void *y;            int64_t y_stride_b, y_stride_d;
     void *stream;
-    int32_t bc_groups;      /* G > 1: Bm, Cm are [B,G,N] and channel d reads group d / (D/G); callers built against
-                               the shorter struct get 1 */
-    int32_t reserved;
 } lrnnx_ss_step_complex_args;
 
 int lrnnx_selective_step_complex(const lrnnx_ss_step_complex_args *args);
@@ -495,10 +484,13 @@ typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2, LRNNX_WS_LT
                LRNNX_WS_FWD_COMPLEX = 8
              } lrnnx_ws_kind;
 
-/* Bytes of device scratch the call may need (the largest over its paths).
- * For LRNNX_WS_LTI, LRNNX_WS_LTI_BWD, LRNNX_WS_DIAG and LRNNX_WS_DIAG_BWD pass P as D and 0 for N (the DIAG kinds:
- * io_dtype is LRNNX_F32 or LRNNX_C64).  Returns 0 for invalid sizes.   */
-size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t L, int io_dtype);
+/* Bytes of device scratch the call may need (the largest over its paths).  bc_groups as in the call's struct (0 or 1:
+ * none); packed != 0: the call will be given cu_seqlens (B sequences on one time axis of L steps; the backward kinds
+ * then cover the checkpoints of the recompute sweep in the packed layout and the B ints of the launch order).
+ * For LRNNX_WS_LTI, LRNNX_WS_LTI_BWD, LRNNX_WS_DIAG and LRNNX_WS_DIAG_BWD pass P as D and 0 for N, bc_groups and packed
+ * (the DIAG kinds: io_dtype is LRNNX_F32 or LRNNX_C64).  Returns 0 for invalid sizes and for calls that need none.   */
+size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t L, int io_dtype, int bc_groups,
+                             int packed);
 
 /* Number of chunks lrnnx_selective_scan_bwd (complex_a = 0) or lrnnx_selective_scan_bwd_complex (complex_a = 1) cuts
  * the time axis into for these sizes and this `path` when its workspace allows it (1: single pass); the aggregates
@@ -510,7 +502,7 @@ int lrnnx_selective_scan_bwd_chunks(int64_t B, int64_t D, int64_t N, int64_t L, 
 int lrnnx_selective_scan_fwd_complex_chunks(int64_t B, int64_t D, int64_t N, int64_t L, int bc_groups, int path);
 
 const char *lrnnx_status_string(int status);
-int lrnnx_version(void);   /* major * 100 + minor; grows whenever an entry point or a struct field is added */
+int lrnnx_version(void);   /* major * 100 + minor; the major number changes with any struct layout */
 
 #ifdef __cplusplus
 }

@@ -15,7 +15,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("LRNNX_LIB", os.path.join(_HERE, "liblrnnx.so"))   # LRNNX_LIB: alternative build of the same library
+LIB_PATH = os.path.join(_HERE, "liblrnnx.so")
 
 F32, BF16, C64 = 0, 1, 2
 DISC = {"zoh_s6": 0, "zoh": 1, "bilinear": 2, "dirac": 3}
@@ -26,83 +26,44 @@ STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported", 3: "workspace", 4: "
 _vp, _i32, _i64, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
 
 
-class FwdArgs(ctypes.Structure):
-    _fields_ = [
-        ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32), ("L", _i64),
-        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32), ("path", _i32),
-        ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
-        ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
-        ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
-        ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
-        ("x0", _vp),
-        ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
-        ("x_last", _vp), ("ckpt", _vp),
-        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
-        ("bc_groups", _i32), ("reserved", _i32), ("cu_seqlens", _vp),
-    ]
+_SEL_HEAD = [("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32), ("bc_groups", _i32), ("L", _i64),
+             ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32), ("path", _i32), ("cu_seqlens", _vp)]
+_SEL_INPUTS = [("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
+               ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
+               ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
+               ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
+               ("x0", _vp)]
+_SEL_FWD_TAIL = [("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64), ("x_last", _vp), ("ckpt", _vp),
+                 ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp)]
+_SEL_BWD_TAIL = [("dy", _vp), ("dy_stride_b", _i64), ("dy_stride_d", _i64), ("ckpt", _vp),
+                 ("du", _vp), ("du_stride_b", _i64), ("du_stride_d", _i64),
+                 ("ddelta", _vp), ("ddelta_stride_b", _i64), ("ddelta_stride_d", _i64),
+                 ("dz", _vp), ("dz_stride_b", _i64), ("dz_stride_d", _i64),
+                 ("dA", _vp), ("dBm", _vp), ("dCm", _vp), ("dD", _vp), ("dbias", _vp), ("dx0", _vp),
+                 ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp)]
 
 
-class FwdComplexArgs(ctypes.Structure):
-    _fields_ = [
-        ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32), ("L", _i64),
-        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32), ("reserved", _i32),
-        ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
-        ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
-        ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
-        ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
-        ("x0", _vp),
-        ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
-        ("x_last", _vp), ("stream", _vp), ("ckpt", _vp), ("bc_groups", _i32), ("reserved2", _i32),
-        ("cu_seqlens", _vp), ("workspace", _vp), ("workspace_bytes", _sz), ("path", _i32), ("reserved3", _i32),
-    ]
+class FwdArgs(ctypes.Structure):                  # lrnnx_ss_fwd_args
+    _fields_ = _SEL_HEAD + _SEL_INPUTS + _SEL_FWD_TAIL
 
 
-class BwdComplexArgs(ctypes.Structure):
-    _fields_ = [
-        ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32), ("L", _i64),
-        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32), ("bc_groups", _i32),
-        ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
-        ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
-        ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
-        ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
-        ("x0", _vp),
-        ("dy", _vp), ("dy_stride_b", _i64), ("dy_stride_d", _i64),
-        ("ckpt", _vp),
-        ("du", _vp), ("du_stride_b", _i64), ("du_stride_d", _i64),
-        ("ddelta", _vp), ("ddelta_stride_b", _i64), ("ddelta_stride_d", _i64),
-        ("dz", _vp), ("dz_stride_b", _i64), ("dz_stride_d", _i64),
-        ("dA", _vp), ("dBm", _vp), ("dCm", _vp), ("dD", _vp), ("dbias", _vp), ("dx0", _vp),
-        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp), ("cu_seqlens", _vp),
-        ("path", _i32), ("reserved", _i32),
-    ]
+class FwdComplexArgs(ctypes.Structure):           # lrnnx_ss_fwd_complex_args (same layout, complex pointers)
+    _fields_ = _SEL_HEAD + _SEL_INPUTS + _SEL_FWD_TAIL
 
 
-class BwdArgs(ctypes.Structure):
-    _fields_ = [
-        ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32), ("L", _i64),
-        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32), ("bc_groups", _i32),
-        ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
-        ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
-        ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
-        ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
-        ("x0", _vp),
-        ("dy", _vp), ("dy_stride_b", _i64), ("dy_stride_d", _i64),
-        ("ckpt", _vp),
-        ("du", _vp), ("du_stride_b", _i64), ("du_stride_d", _i64),
-        ("ddelta", _vp), ("ddelta_stride_b", _i64), ("ddelta_stride_d", _i64),
-        ("dz", _vp), ("dz_stride_b", _i64), ("dz_stride_d", _i64),
-        ("dA", _vp), ("dBm", _vp), ("dCm", _vp), ("dD", _vp), ("dbias", _vp), ("dx0", _vp),
-        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp), ("cu_seqlens", _vp),
-        ("path", _i32), ("reserved", _i32),
-    ]
+class BwdArgs(ctypes.Structure):                  # lrnnx_ss_bwd_args
+    _fields_ = _SEL_HEAD + _SEL_INPUTS + _SEL_BWD_TAIL
+
+
+class BwdComplexArgs(ctypes.Structure):           # lrnnx_ss_bwd_complex_args
+    _fields_ = _SEL_HEAD + _SEL_INPUTS + _SEL_BWD_TAIL
 
 
 class LtiArgs(ctypes.Structure):
     _fields_ = [
-        ("struct_size", _sz), ("B", _i32), ("P", _i32), ("L", _i64),
-        ("lambda_", _vp), ("v", _vp), ("x0", _vp), ("x", _vp), ("x_last", _vp),
+        ("struct_size", _sz), ("B", _i32), ("P", _i32), ("L", _i64), ("path", _i32), ("reserved", _i32),
+        ("lambda_", _vp), ("v", _vp), ("x0", _vp), ("x", _vp), ("x_last", _vp), ("chain_status", _vp),
         ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
-        ("path", _i32), ("reserved", _i32),
     ]
 
 
@@ -110,14 +71,14 @@ class LtiBwdArgs(ctypes.Structure):
     _fields_ = [
         ("struct_size", _sz), ("B", _i32), ("P", _i32), ("L", _i64),
         ("lambda_", _vp), ("x", _vp), ("x0", _vp), ("gx", _vp), ("dv", _vp), ("dlambda", _vp), ("dx0", _vp),
-        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
+        ("chain_status", _vp), ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
     ]
 
 
 class DiagScanArgs(ctypes.Structure):
     _fields_ = [
         ("struct_size", _sz), ("B", _i32), ("P", _i32), ("L", _i64), ("dtype", _i32), ("reserved", _i32),
-        ("a", _vp), ("b", _vp), ("x0", _vp), ("x", _vp), ("x_last", _vp),
+        ("a", _vp), ("b", _vp), ("x0", _vp), ("x", _vp), ("x_last", _vp), ("chain_status", _vp),
         ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
     ]
 
@@ -126,36 +87,29 @@ class DiagScanBwdArgs(ctypes.Structure):
     _fields_ = [
         ("struct_size", _sz), ("B", _i32), ("P", _i32), ("L", _i64), ("dtype", _i32), ("reserved", _i32),
         ("a", _vp), ("x", _vp), ("x0", _vp), ("gx", _vp), ("da", _vp), ("db", _vp), ("dx0", _vp),
-        ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
+        ("chain_status", _vp), ("workspace", _vp), ("workspace_bytes", _sz), ("stream", _vp),
     ]
 
 
-class StepArgs(ctypes.Structure):
-    _fields_ = [
-        ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32),
-        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32),
-        ("x", _vp),
-        ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
-        ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
-        ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
-        ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
-        ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
-        ("stream", _vp), ("bc_groups", _i32), ("reserved", _i32),
-    ]
+_STEP_FIELDS = [
+    ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32), ("bc_groups", _i32),
+    ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32), ("reserved", _i32),
+    ("x", _vp),
+    ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
+    ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
+    ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
+    ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
+    ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
+    ("stream", _vp),
+]
 
 
-class StepComplexArgs(ctypes.Structure):
-    _fields_ = [
-        ("struct_size", _sz), ("B", _i32), ("D", _i32), ("N", _i32),
-        ("io_dtype", _i32), ("disc", _i32), ("delta_softplus", _i32),
-        ("x", _vp),
-        ("u", _vp), ("u_stride_b", _i64), ("u_stride_d", _i64),
-        ("delta", _vp), ("delta_stride_b", _i64), ("delta_stride_d", _i64),
-        ("A", _vp), ("Bm", _vp), ("Cm", _vp), ("Dskip", _vp), ("delta_bias", _vp),
-        ("z", _vp), ("z_stride_b", _i64), ("z_stride_d", _i64),
-        ("y", _vp), ("y_stride_b", _i64), ("y_stride_d", _i64),
-        ("stream", _vp), ("bc_groups", _i32), ("reserved", _i32),
-    ]
+class StepArgs(ctypes.Structure):                 # lrnnx_ss_step_args
+    _fields_ = _STEP_FIELDS
+
+
+class StepComplexArgs(ctypes.Structure):          # lrnnx_ss_step_complex_args
+    _fields_ = _STEP_FIELDS
 
 
 class LtiStepArgs(ctypes.Structure):
@@ -197,7 +151,7 @@ def lib():
         L.lrnnx_lti_step.restype = ctypes.c_int
         for f in (L.lrnnx_selective_scan_fwd, L.lrnnx_selective_scan_bwd, L.lrnnx_lti_diag_scan, L.lrnnx_version):
             f.restype = ctypes.c_int
-        L.lrnnx_workspace_bytes.argtypes = [ctypes.c_int, _i64, _i64, _i64, _i64, ctypes.c_int]
+        L.lrnnx_workspace_bytes.argtypes = [ctypes.c_int, _i64, _i64, _i64, _i64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.lrnnx_workspace_bytes.restype = _sz
         L.lrnnx_selective_scan_bwd_chunks.argtypes = [_i64, _i64, _i64, _i64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.lrnnx_selective_scan_bwd_chunks.restype = ctypes.c_int
@@ -233,12 +187,18 @@ def _io_dtype(t):
     raise TypeError(f"I/O dtype must be float32 or bfloat16, got {t.dtype}")
 
 
-def _bdl(t, name, io=None):
-    """(ptr, stride_b, stride_d) of a [B,D,L] tensor whose last axis is contiguous."""
+def _bdl(t, name, io=None, shape=None, out=False):
+    """(ptr, stride_b, stride_d) of a [B,D,L] tensor whose last axis is contiguous.  `shape`: the (B, D, L) every
+    per-channel tensor of the call must have (the kernels index all of them with the same b, d, l; only a stride of
+    0 may broadcast an input).  `out`: an output, whose rows must not overlap."""
     if t is None:
         return None, 0, 0
     if t.dim() != 3 or (t.shape[2] > 1 and t.stride(2) != 1):
         raise ValueError(f"{name}: expected [B,D,L] with contiguous time axis")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    if out and (t.stride(1) < t.shape[2] or (t.shape[0] > 1 and t.stride(0) < t.shape[1] * t.shape[2])):
+        raise ValueError(f"{name}: output rows overlap")
     if io is not None and t.dtype != io:
         raise TypeError(f"{name}: dtype {t.dtype} differs from the I/O dtype {io}")
     return t.data_ptr(), t.stride(0), t.stride(1)
@@ -252,6 +212,15 @@ def _f32c(t, name, shape=None):
     if shape is not None and tuple(t.shape) != tuple(shape):
         raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
     return t
+
+
+def _status_word(t):
+    """Device pointer of an optional int32 status word (a one-element tensor the caller has cleared)."""
+    if t is None:
+        return None
+    if t.dtype != torch.int32 or t.numel() != 1 or not t.is_cuda:
+        raise ValueError("chain_status: expected a one-element int32 device tensor")
+    return t.data_ptr()
 
 
 def _stream():
@@ -294,8 +263,8 @@ def lrnnx_ckpt_interval() -> int:
     return int(lib().lrnnx_ckpt_interval())
 
 
-def lrnnx_workspace_bytes(which, B, D, N, L, io_dtype) -> int:
-    return int(lib().lrnnx_workspace_bytes(which, B, D, N, L, io_dtype))
+def lrnnx_workspace_bytes(which, B, D, N, L, io_dtype, bc_groups=1, packed=False) -> int:
+    return int(lib().lrnnx_workspace_bytes(which, B, D, N, L, io_dtype, bc_groups, int(bool(packed))))
 
 
 def _check_cu(cu):
@@ -347,9 +316,10 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
     a.delta_softplus = int(bool(delta_softplus))
     a.path = PATH[path] if isinstance(path, str) else int(path)
-    a.u, a.u_stride_b, a.u_stride_d = _bdl(u, "u", io)
-    a.delta, a.delta_stride_b, a.delta_stride_d = _bdl(delta, "delta", io)
-    a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io)
+    bdl = (Bio, D, L)
+    a.u, a.u_stride_b, a.u_stride_d = _bdl(u, "u", io, bdl)
+    a.delta, a.delta_stride_b, a.delta_stride_d = _bdl(delta, "delta", io, bdl)
+    a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io, bdl)
     a.A = _ptr(_f32c(A, "A", (D, N)))
     a.bc_groups = _bc_groups(Bm, Cm, io, Bio, D, L, N)
     a.Bm, a.Cm = Bm.data_ptr(), Cm.data_ptr()
@@ -357,7 +327,7 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
     a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
     a.x0 = _ptr(_f32c(x0, "x0", (Bsz, D, N)))
     y = out if out is not None else torch.empty((Bio, D, L), dtype=io, device=u.device)
-    a.y, a.y_stride_b, a.y_stride_d = _bdl(y, "y", io)
+    a.y, a.y_stride_b, a.y_stride_d = _bdl(y, "y", io, bdl, out=True)
     x_last = torch.empty((Bsz, D, N), dtype=torch.float32, device=u.device) if return_last_state else None
     a.x_last = _ptr(x_last)
     ckpt = ckpt_out
@@ -370,9 +340,10 @@ def lrnnx_selective_scan_fwd(u, delta, A, Bm, Cm, Dskip=None, delta_bias=None, z
         _f32c(ckpt, "ckpt_out", ck_shape)
     a.ckpt = _ptr(ckpt)
     if workspace is None:
-        nbytes = lrnnx_workspace_bytes(WS_FWD, Bsz, D, N, L, a.io_dtype)
-        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=u.device)
-    a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
+        nbytes = lrnnx_workspace_bytes(WS_FWD, Bsz, D, N, L, a.io_dtype, a.bc_groups, packed)
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=u.device) if nbytes else None
+    if workspace is not None:
+        a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
     a.stream = _stream()
     _check(lib().lrnnx_selective_scan_fwd(ctypes.byref(a)))
     res = (y[0] if packed else y,)
@@ -415,9 +386,10 @@ def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias
     a.io_dtype = _io_dtype(u)
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
     a.delta_softplus = int(bool(delta_softplus))
-    a.u, a.u_stride_b, a.u_stride_d = _bdl(u, "u", io)
-    a.delta, a.delta_stride_b, a.delta_stride_d = _bdl(delta, "delta", io)
-    a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io)
+    bdl = (Bio, D, L)
+    a.u, a.u_stride_b, a.u_stride_d = _bdl(u, "u", io, bdl)
+    a.delta, a.delta_stride_b, a.delta_stride_d = _bdl(delta, "delta", io, bdl)
+    a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io, bdl)
     a.A, a.Bm, a.Cm = A.data_ptr(), Bm.data_ptr(), Cm.data_ptr()
     a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
     a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
@@ -426,7 +398,7 @@ def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias
             raise ValueError("x0: expected contiguous complex64 [B,D,N]")
         a.x0 = x0.data_ptr()
     y = out if out is not None else torch.empty((Bio, D, L), dtype=io, device=u.device)
-    a.y, a.y_stride_b, a.y_stride_d = _bdl(y, "y", io)
+    a.y, a.y_stride_b, a.y_stride_d = _bdl(y, "y", io, bdl, out=True)
     x_last = torch.empty((Bsz, D, N), dtype=torch.complex64, device=u.device) if return_last_state else None
     a.x_last = _ptr(x_last)
     ckpt = None
@@ -439,10 +411,10 @@ def lrnnx_selective_scan_fwd_complex(u, delta, A, Bm, Cm, Dskip=None, delta_bias
         a.ckpt = ckpt.data_ptr()
         return_ckpt = True
     a.path = PATH[path] if isinstance(path, str) else int(path)
-    if workspace is None and not packed:
-        nch = int(lib().lrnnx_selective_scan_fwd_complex_chunks(Bsz, D, N, L, G, a.path))
-        if nch > 1:
-            workspace = torch.empty(2 * Bsz * D * nch * N * 8, dtype=torch.uint8, device=u.device)
+    if workspace is None:
+        nbytes = lrnnx_workspace_bytes(WS_FWD_COMPLEX, Bsz, D, N, L, a.io_dtype, G, packed)
+        if nbytes:
+            workspace = torch.empty(nbytes, dtype=torch.uint8, device=u.device)
     if workspace is not None:
         a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
     a.stream = _stream()
@@ -505,8 +477,9 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
         if name not in outs:
             outs[name] = torch.empty(shape, dtype=dtype, device=dev)
         t = outs[name]
-        if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous():
-            raise ValueError(f"{name}: expected contiguous {dtype} {tuple(shape)}")
+        strided_ok = name in ("du", "ddelta", "dz")          # [B,D,L] outputs are passed with their strides
+        if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not (strided_ok or t.is_contiguous()):
+            raise ValueError(f"{name}: expected {dtype} {tuple(shape)}" + ("" if strided_ok else ", contiguous"))
         return t
 
     a = BwdComplexArgs()
@@ -518,10 +491,11 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
     a.io_dtype = _io_dtype(u)
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
     a.delta_softplus = int(bool(delta_softplus))
-    a.u, a.u_stride_b, a.u_stride_d = _bdl(u, "u", io)
-    a.delta, a.delta_stride_b, a.delta_stride_d = _bdl(delta, "delta", io)
-    a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io)
-    a.dy, a.dy_stride_b, a.dy_stride_d = _bdl(dy, "dy", io)
+    bdl = (Bio, D, L)
+    a.u, a.u_stride_b, a.u_stride_d = _bdl(u, "u", io, bdl)
+    a.delta, a.delta_stride_b, a.delta_stride_d = _bdl(delta, "delta", io, bdl)
+    a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io, bdl)
+    a.dy, a.dy_stride_b, a.dy_stride_d = _bdl(dy, "dy", io, bdl)
     a.A, a.Bm, a.Cm = A.data_ptr(), Bm.data_ptr(), Cm.data_ptr()
     a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
     a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
@@ -532,10 +506,10 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
             if t.dtype != torch.complex64 or not t.is_contiguous() or tuple(t.shape) != shape:
                 raise ValueError(f"{name}: expected contiguous complex64 {shape}")
             setattr(a, name, t.data_ptr())
-    a.du, a.du_stride_b, a.du_stride_d = _bdl(new("du", (Bio, D, L), io), "du", io)
-    a.ddelta, a.ddelta_stride_b, a.ddelta_stride_d = _bdl(new("ddelta", (Bio, D, L), io), "ddelta", io)
+    a.du, a.du_stride_b, a.du_stride_d = _bdl(new("du", bdl, io), "du", io, bdl, out=True)
+    a.ddelta, a.ddelta_stride_b, a.ddelta_stride_d = _bdl(new("ddelta", bdl, io), "ddelta", io, bdl, out=True)
     if z is not None:
-        a.dz, a.dz_stride_b, a.dz_stride_d = _bdl(new("dz", (Bio, D, L), io), "dz", io)
+        a.dz, a.dz_stride_b, a.dz_stride_d = _bdl(new("dz", bdl, io), "dz", io, bdl, out=True)
     c64 = torch.complex64
     a.dA = new("dA", (D, N), c64).data_ptr()
     map_shape = (Bio, L, N) if (Bm.dim() == 3 + (io == torch.bfloat16)) else (Bio, G, L, N)
@@ -548,14 +522,10 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
     if want_dx0:
         a.dx0 = new("dx0", (Bsz, D, N), c64).data_ptr()
     if workspace is None:
-        if packed:                                     # checkpoints of the recompute sweep, then the launch order
-            nbytes = (D * (L // I + Bsz) * N * 8 + 255) // 256 * 256 if ckpt is None else 0
-            nbytes += 4 * Bsz
-        else:                                          # checkpoints of the recompute sweep, then the chunk aggregates
-            nch = int(lib().lrnnx_selective_scan_bwd_chunks(Bsz, D, N, L, G, a.path, 1))
-            nbytes = 2 * Bsz * D * nch * N * 8 if nch > 1 else 0
-            if ckpt is None:
-                nbytes += (Bsz * D * -(-L // I) * N * 8 + 255) // 256 * 256
+        # with the forward's checkpoints only the chunk aggregates (or the launch order of a packed batch) are needed
+        nbytes = lrnnx_workspace_bytes(WS_BWD_COMPLEX, Bsz, D, N, L, a.io_dtype, G, packed)
+        if ckpt is not None:
+            nbytes -= (ckpt.numel() * 8 + 255) // 256 * 256
         if nbytes:
             workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     if workspace is not None:
@@ -593,7 +563,11 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
     def new(name, shape, dtype):
         if name not in outs:
             outs[name] = torch.empty(shape, dtype=dtype, device=dev)
-        return outs[name]
+        t = outs[name]
+        strided_ok = name in ("du", "ddelta", "dz")          # [B,D,L] outputs are passed with their strides
+        if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not (strided_ok or t.is_contiguous()):
+            raise ValueError(f"{name}: expected {dtype} {tuple(shape)}" + ("" if strided_ok else ", contiguous"))
+        return t
 
     a = BwdArgs()
     a.struct_size = ctypes.sizeof(BwdArgs)
@@ -603,21 +577,23 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
     a.io_dtype = _io_dtype(u)
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
     a.delta_softplus = int(bool(delta_softplus))
-    a.u, a.u_stride_b, a.u_stride_d = _bdl(u, "u", io)
-    a.delta, a.delta_stride_b, a.delta_stride_d = _bdl(delta, "delta", io)
-    a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io)
-    a.dy, a.dy_stride_b, a.dy_stride_d = _bdl(dy, "dy", io)
+    bdl = (Bio, D, L)
+    a.u, a.u_stride_b, a.u_stride_d = _bdl(u, "u", io, bdl)
+    a.delta, a.delta_stride_b, a.delta_stride_d = _bdl(delta, "delta", io, bdl)
+    a.z, a.z_stride_b, a.z_stride_d = _bdl(z, "z", io, bdl)
+    a.dy, a.dy_stride_b, a.dy_stride_d = _bdl(dy, "dy", io, bdl)
     a.A = _ptr(_f32c(A, "A", (D, N)))
     a.bc_groups = _bc_groups(Bm, Cm, io, Bio, D, L, N)
     a.Bm, a.Cm = Bm.data_ptr(), Cm.data_ptr()
     a.Dskip = _ptr(_f32c(Dskip, "Dskip", (D,)))
     a.delta_bias = _ptr(_f32c(delta_bias, "delta_bias", (D,)))
     a.x0 = _ptr(_f32c(x0, "x0", (Bsz, D, N)))
-    a.ckpt = _ptr(_f32c(ckpt, "ckpt"))
-    a.du, a.du_stride_b, a.du_stride_d = _bdl(new("du", (Bio, D, L), io), "du", io)
-    a.ddelta, a.ddelta_stride_b, a.ddelta_stride_d = _bdl(new("ddelta", (Bio, D, L), io), "ddelta", io)
+    I = lrnnx_ckpt_interval()
+    a.ckpt = _ptr(_f32c(ckpt, "ckpt", (D, L // I + Bsz, N) if packed else (Bsz, D, -(-L // I), N)))
+    a.du, a.du_stride_b, a.du_stride_d = _bdl(new("du", bdl, io), "du", io, bdl, out=True)
+    a.ddelta, a.ddelta_stride_b, a.ddelta_stride_d = _bdl(new("ddelta", bdl, io), "ddelta", io, bdl, out=True)
     if z is not None:
-        a.dz, a.dz_stride_b, a.dz_stride_d = _bdl(new("dz", (Bio, D, L), io), "dz", io)
+        a.dz, a.dz_stride_b, a.dz_stride_d = _bdl(new("dz", bdl, io), "dz", io, bdl, out=True)
     a.dA = new("dA", (D, N), torch.float32).data_ptr()
     a.dBm = new("dBm", tuple(Bm.shape), torch.float32).data_ptr()
     a.dCm = new("dCm", tuple(Cm.shape), torch.float32).data_ptr()
@@ -628,14 +604,8 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
     if want_dx0:
         a.dx0 = new("dx0", (Bsz, D, N), torch.float32).data_ptr()
     if workspace is None:
-        if packed:                                     # checkpoints of the recompute sweep, then the launch order
-            nbytes = (D * (L // lrnnx_ckpt_interval() + Bsz) * N * 4 + 255) // 256 * 256 if ckpt is None else 0
-            nbytes += 4 * Bsz
-        else:                                          # checkpoints of the recompute sweep, then the chunk aggregates
-            nch = int(lib().lrnnx_selective_scan_bwd_chunks(Bsz, D, N, L, a.bc_groups, a.path, 0))
-            nbytes = 2 * Bsz * D * nch * N * 4 if nch > 1 else 0
-            if ckpt is None:
-                nbytes += (Bsz * D * -(-L // lrnnx_ckpt_interval()) * N * 4 + 255) // 256 * 256
+        kind = WS_BWD if ckpt is None else WS_BWD_CARRY
+        nbytes = lrnnx_workspace_bytes(kind, Bsz, D, N, L, a.io_dtype, a.bc_groups, packed)
         if nbytes:
             workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     if workspace is not None:
@@ -648,13 +618,19 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
 
 
 @_device_checked
-def lrnnx_lti_diag_scan(lam, v, x0=None, return_last_state=False, out=None, workspace=None, path="auto"):
-    """x [B,L,P] complex64 of x_k = lam * x_{k-1} + v_k; see lrnnx_lti_args."""
+def lrnnx_lti_diag_scan(lam, v, x0=None, return_last_state=False, out=None, workspace=None, path="auto",
+                        chain_status=None):
+    """x [B,L,P] complex64 of x_k = lam * x_{k-1} + v_k; see lrnnx_lti_args.  `chain_status`: an int32 device word the
+    library sets to 1 should a bounded wait between workgroups ever run out (clear it first)."""
     if v.dtype != torch.complex64 or lam.dtype != torch.complex64:
         raise TypeError("lam and v must be complex64")
     if not v.is_contiguous() or not lam.is_contiguous():
         raise ValueError("lam and v must be contiguous")
     Bsz, L, P = v.shape
+    if tuple(lam.shape) != (P,):
+        raise ValueError(f"lam: expected shape ({P},), got {tuple(lam.shape)}")
+    if out is not None and (out.dtype != torch.complex64 or not out.is_contiguous() or out.shape != v.shape):
+        raise ValueError("out: expected a contiguous complex64 tensor of the shape of v")
     a = LtiArgs()
     a.struct_size = ctypes.sizeof(LtiArgs)
     a.B, a.P, a.L = Bsz, P, L
@@ -668,6 +644,7 @@ def lrnnx_lti_diag_scan(lam, v, x0=None, return_last_state=False, out=None, work
     a.x = x.data_ptr()
     x_last = torch.empty((Bsz, P), dtype=torch.complex64, device=v.device) if return_last_state else None
     a.x_last = _ptr(x_last)
+    a.chain_status = _status_word(chain_status)
     if workspace is None:
         nbytes = lrnnx_workspace_bytes(WS_LTI, Bsz, P, 0, L, 0)
         workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=v.device)
@@ -703,7 +680,7 @@ def lrnnx_lti_diag_scan_static(lam, v, out, x0=None, x_last_out=None):
 
 
 @_device_checked
-def lrnnx_lti_diag_scan_bwd(lam, x, gx, x0=None, want_dx0=True, out=None, workspace=None):
+def lrnnx_lti_diag_scan_bwd(lam, x, gx, x0=None, want_dx0=True, out=None, workspace=None, chain_status=None):
     """(dv [B,L,P], dlam [P], dx0 [B,P] or None) from the saved states x and the incoming gradient gx;
     see lrnnx_lti_bwd_args."""
     for t, name in ((lam, "lam"), (x, "x"), (gx, "gx")):
@@ -720,10 +697,13 @@ def lrnnx_lti_diag_scan_bwd(lam, x, gx, x0=None, want_dx0=True, out=None, worksp
         if x0.dtype != torch.complex64 or not x0.is_contiguous() or tuple(x0.shape) != (Bsz, P):
             raise ValueError("x0: expected contiguous complex64 [B,P]")
         a.x0 = x0.data_ptr()
+    if out is not None and (out.dtype != torch.complex64 or not out.is_contiguous() or out.shape != gx.shape):
+        raise ValueError("out: expected a contiguous complex64 tensor of the shape of gx")
     dv = out if out is not None else torch.empty_like(gx)
     dlam = torch.empty(P, dtype=torch.complex64, device=x.device)
     dx0 = torch.empty((Bsz, P), dtype=torch.complex64, device=x.device) if want_dx0 else None
     a.dv, a.dlambda, a.dx0 = dv.data_ptr(), dlam.data_ptr(), _ptr(dx0)
+    a.chain_status = _status_word(chain_status)
     if workspace is None:
         nbytes = lrnnx_workspace_bytes(WS_LTI_BWD, Bsz, P, 0, L, 0)
         workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
@@ -734,7 +714,7 @@ def lrnnx_lti_diag_scan_bwd(lam, x, gx, x0=None, want_dx0=True, out=None, worksp
 
 
 @_device_checked
-def lrnnx_diag_scan(a, b, x0=None, return_last_state=False, out=None, workspace=None):
+def lrnnx_diag_scan(a, b, x0=None, return_last_state=False, out=None, workspace=None, chain_status=None):
     """x [B,L,P] of x_k = a_k * x_{k-1} + b_k for float32 or complex64 a, b; see lrnnx_diag_scan_args."""
     if a.dtype not in (torch.float32, torch.complex64) or b.dtype != a.dtype:
         raise TypeError("a and b must both be float32 or both complex64")
@@ -750,10 +730,13 @@ def lrnnx_diag_scan(a, b, x0=None, return_last_state=False, out=None, workspace=
         if x0.dtype != a.dtype or not x0.is_contiguous() or tuple(x0.shape) != (Bsz, P):
             raise ValueError("x0: expected a contiguous [B,P] tensor of the dtype of a")
         g.x0 = x0.data_ptr()
+    if out is not None and (out.dtype != b.dtype or not out.is_contiguous() or out.shape != b.shape):
+        raise ValueError("out: expected a contiguous tensor of the dtype and shape of b")
     x = out if out is not None else torch.empty_like(b)
     g.x = x.data_ptr()
     x_last = torch.empty((Bsz, P), dtype=a.dtype, device=b.device) if return_last_state else None
     g.x_last = _ptr(x_last)
+    g.chain_status = _status_word(chain_status)
     if workspace is None:
         nbytes = lrnnx_workspace_bytes(WS_DIAG, Bsz, P, 0, L, dt)
         workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=b.device)
@@ -764,7 +747,7 @@ def lrnnx_diag_scan(a, b, x0=None, return_last_state=False, out=None, workspace=
 
 
 @_device_checked
-def lrnnx_diag_scan_bwd(a, x, gx, x0=None, want_dx0=True, workspace=None):
+def lrnnx_diag_scan_bwd(a, x, gx, x0=None, want_dx0=True, workspace=None, chain_status=None):
     """(da, db [B,L,P], dx0 [B,P] or None) from the forward call's a, saved states x and the incoming gradient gx;
     see lrnnx_diag_scan_bwd_args."""
     for t, name in ((a, "a"), (x, "x"), (gx, "gx")):
@@ -785,6 +768,7 @@ def lrnnx_diag_scan_bwd(a, x, gx, x0=None, want_dx0=True, workspace=None):
     da, db = torch.empty_like(a), torch.empty_like(a)
     dx0 = torch.empty((Bsz, P), dtype=a.dtype, device=a.device) if want_dx0 else None
     g.da, g.db, g.dx0 = da.data_ptr(), db.data_ptr(), _ptr(dx0)
+    g.chain_status = _status_word(chain_status)
     if workspace is None:
         nbytes = lrnnx_workspace_bytes(WS_DIAG_BWD, Bsz, P, 0, L, dt)
         workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=a.device)

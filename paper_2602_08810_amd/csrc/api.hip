@@ -155,7 +155,7 @@ extern "C" {
 
 int64_t lrnnx_ckpt_interval(void) { return kCkptInterval; }
 int64_t lrnnx_packed_ckpt_slots(int64_t L, int64_t B) { return (L < 0 || B < 0) ? 0 : L / kCkptInterval + B; }
-int lrnnx_version(void) { return 137; }   // major * 100 + minor; bumped whenever an entry point or a struct field is added
+int lrnnx_version(void) { return 200; }   // major * 100 + minor; the major number changes with any struct layout
 
 int lrnnx_selective_scan_bwd_chunks(int64_t B, int64_t D, int64_t N, int64_t L, int bc_groups, int path, int complex_a) {
     const int bcg = bc_groups > 1 ? bc_groups : 1;
@@ -188,25 +188,26 @@ const char *lrnnx_status_string(int status) {
     return "unknown status";
 }
 
-size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t L, int io_dtype) {
-    if (B < 1 || D < 1 || L < 1) return 0;
-    if (which == LRNNX_WS_FWD) {
-        if (!supported_n((int)N)) return 0;
-        const int nch = fwd_chunks(B, D, L, io_dtype, true);
-        return (size_t)2 * B * D * nch * N * sizeof(float);
-    }
-    if (which == LRNNX_WS_BWD) {                    // checkpoints of the recompute sweep, then the chunk aggregates
-        if (!supported_n((int)N)) return 0;
-        return align256((size_t)B * D * cdiv(L, kCkptInterval) * N * sizeof(float)) + bwd_carry_bytes(B, D, N, L);
-    }
-    if (which == LRNNX_WS_BWD_CARRY) return supported_n((int)N) ? bwd_carry_bytes(B, D, N, L) : 0;
-    if (which == LRNNX_WS_FWD_COMPLEX) {
-        if (!supported_n_complex((int)N)) return 0;
-        return (size_t)2 * B * D * cfwd_chunks(B * cdiv(D, 8), L, true) * N * sizeof(float2);
-    }
-    if (which == LRNNX_WS_BWD_COMPLEX) {            // checkpoints of the recompute sweep, then the chunk aggregates
-        if (!supported_n_complex((int)N)) return 0;
-        return align256((size_t)B * D * cdiv(L, kCkptInterval) * N * sizeof(float2)) + cbwd_carry_bytes(B, D, N, L);
+size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t L, int io_dtype, int bc_groups,
+                             int packed) {
+    if (B < 1 || D < 1 || L < 1 || bc_groups < 0 || B > 65535 || D > INT32_MAX) return 0;
+    const int64_t bcg = bc_groups > 1 ? bc_groups : 1;
+    const bool selective = which == LRNNX_WS_FWD || which == LRNNX_WS_BWD || which == LRNNX_WS_BWD_CARRY ||
+                           which == LRNNX_WS_FWD_COMPLEX || which == LRNNX_WS_BWD_COMPLEX;
+    if (selective) {
+        const bool cplx = which == LRNNX_WS_FWD_COMPLEX || which == LRNNX_WS_BWD_COMPLEX;
+        if (!(cplx ? supported_n_complex((int)N) : supported_n((int)N)) || D % bcg) return 0;
+        const size_t es = cplx ? sizeof(float2) : sizeof(float);
+        if (which == LRNNX_WS_FWD) return packed ? 0 : (size_t)2 * B * D * fwd_chunks(B, D, L, io_dtype, true) * N * es;
+        if (which == LRNNX_WS_FWD_COMPLEX)
+            return packed ? 0 : (size_t)2 * B * D * cfwd_chunks(B * bcg * cdiv(D / bcg, 8), L, true) * N * es;
+        // backward: the checkpoints of the recompute sweep (not LRNNX_WS_BWD_CARRY: the caller has the forward's), then
+        // the chunk aggregates, or for a packed batch the launch order
+        size_t ck = 0;
+        if (which != LRNNX_WS_BWD_CARRY)
+            ck = align256((size_t)(packed ? D * lrnnx_packed_ckpt_slots(L, B) : B * D * cdiv(L, kCkptInterval)) * N * es);
+        if (packed) return ck + sizeof(int) * (size_t)B;
+        return ck + (cplx ? cbwd_carry_bytes(B * bcg, D / bcg, N, L) : bwd_carry_bytes(B * bcg, D / bcg, N, L));
     }
     if (which == LRNNX_WS_LTI) {
         const int nch = lti_chunks(B, D, L);
@@ -224,13 +225,10 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
 }
 
 int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *a) {
-    constexpr size_t kOldSize = offsetof(lrnnx_ss_fwd_args, bc_groups);  // struct before `bc_groups` was appended
-    if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
-    constexpr size_t kSizeWithGroups = offsetof(lrnnx_ss_fwd_args, cu_seqlens);   // ... and before `cu_seqlens`
-    const bool has_groups = a->struct_size >= kSizeWithGroups;
-    const int bcg = (has_groups && a->bc_groups > 1) ? a->bc_groups : 1;
-    if (has_groups && a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
-    const int64_t *cu = a->struct_size >= sizeof(lrnnx_ss_fwd_args) ? a->cu_seqlens : nullptr;
+    if (!a || a->struct_size != sizeof(lrnnx_ss_fwd_args)) return LRNNX_ERR_INVALID_ARG;
+    if (a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
+    const int bcg = a->bc_groups > 1 ? a->bc_groups : 1;
+    const int64_t *cu = a->cu_seqlens;
     if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
     if (cu && a->path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_UNSUPPORTED;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
@@ -296,21 +294,15 @@ int lrnnx_selective_scan_fwd(const lrnnx_ss_fwd_args *a) {
 }
 
 int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *a) {
-    constexpr size_t kOldSize = offsetof(lrnnx_ss_fwd_complex_args, ckpt);   // struct before `ckpt` was appended
-    constexpr size_t kSizeCkpt = offsetof(lrnnx_ss_fwd_complex_args, bc_groups);   // ... and before `bc_groups` was
-    if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
-    void *ckpt = a->struct_size >= kSizeCkpt ? a->ckpt : nullptr;
-    constexpr size_t kSizeGroups = offsetof(lrnnx_ss_fwd_complex_args, cu_seqlens);   // ... and before `cu_seqlens`
-    constexpr size_t kSizeCu = offsetof(lrnnx_ss_fwd_complex_args, workspace);        // ... and before `workspace`, `path`
-    const bool has_groups = a->struct_size >= kSizeGroups;
-    if (has_groups && a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
-    const int bcg = (has_groups && a->bc_groups > 1) ? a->bc_groups : 1;
-    const int64_t *cu = a->struct_size >= kSizeCu ? a->cu_seqlens : nullptr;
+    if (!a || a->struct_size != sizeof(lrnnx_ss_fwd_complex_args)) return LRNNX_ERR_INVALID_ARG;
+    void *ckpt = a->ckpt;
+    if (a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
+    const int bcg = a->bc_groups > 1 ? a->bc_groups : 1;
+    const int64_t *cu = a->cu_seqlens;
     if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
-    const bool has_path = a->struct_size >= sizeof(lrnnx_ss_fwd_complex_args);
-    const int path = has_path ? a->path : LRNNX_PATH_SINGLE_PASS;
-    void *ws = has_path ? a->workspace : nullptr;
-    const size_t ws_bytes = has_path ? a->workspace_bytes : 0;
+    const int path = a->path;
+    void *ws = a->workspace;
+    const size_t ws_bytes = a->workspace_bytes;
     if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
     if (cu && path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_UNSUPPORTED;
     if (reinterpret_cast<uintptr_t>(ws) & 7u) return LRNNX_ERR_INVALID_ARG;
@@ -375,11 +367,9 @@ int lrnnx_selective_scan_fwd_complex(const lrnnx_ss_fwd_complex_args *a) {
 }
 
 int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
-    constexpr size_t kOldSize = offsetof(lrnnx_ss_bwd_complex_args, cu_seqlens);  // struct before `cu_seqlens` was appended
-    constexpr size_t kSizeCu = offsetof(lrnnx_ss_bwd_complex_args, path);         // ... and before `path` was
-    if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
-    const int64_t *cu = a->struct_size >= kSizeCu ? a->cu_seqlens : nullptr;
-    const int path = a->struct_size >= sizeof(lrnnx_ss_bwd_complex_args) ? a->path : LRNNX_PATH_AUTO;
+    if (!a || a->struct_size != sizeof(lrnnx_ss_bwd_complex_args)) return LRNNX_ERR_INVALID_ARG;
+    const int64_t *cu = a->cu_seqlens;
+    const int path = a->path;
     if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
     if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
     if (cu && path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_UNSUPPORTED;
@@ -468,11 +458,9 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
 }
 
 int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
-    constexpr size_t kOldSize = offsetof(lrnnx_ss_bwd_args, cu_seqlens);  // struct before `cu_seqlens` was appended
-    constexpr size_t kSizeCu = offsetof(lrnnx_ss_bwd_args, path);         // ... and before `path` was
-    if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
-    const int64_t *cu = a->struct_size >= kSizeCu ? a->cu_seqlens : nullptr;
-    const int path = a->struct_size >= sizeof(lrnnx_ss_bwd_args) ? a->path : LRNNX_PATH_AUTO;
+    if (!a || a->struct_size != sizeof(lrnnx_ss_bwd_args)) return LRNNX_ERR_INVALID_ARG;
+    const int64_t *cu = a->cu_seqlens;
+    const int path = a->path;
     if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
     if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
     if (cu && path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_UNSUPPORTED;
@@ -572,6 +560,7 @@ static int lti_onepass_run(const lrnnx_lti_args *a, void *ws, hipStream_t s) {
     p.x = reinterpret_cast<float2 *>(a->x);
     p.x_last = reinterpret_cast<float2 *>(a->x_last);
     p.ngroups = (int)ng;
+    p.status = a->chain_status;
     set_onepass_workspace(p, ws);
     if (launch_fill(onepass_fill(p), s) != hipSuccess) return LRNNX_ERR_LAUNCH;
     return launch_lti_onepass(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
@@ -582,14 +571,14 @@ static int lti_args_valid(const lrnnx_lti_args *a) {
     if (!a->lambda || !a->v || !a->x) return LRNNX_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(a->v) & 7u) || (reinterpret_cast<uintptr_t>(a->x) & 7u) ||
         (reinterpret_cast<uintptr_t>(a->lambda) & 7u) || (reinterpret_cast<uintptr_t>(a->x0) & 7u) ||
-        (reinterpret_cast<uintptr_t>(a->x_last) & 7u))
+        (reinterpret_cast<uintptr_t>(a->x_last) & 7u) || (reinterpret_cast<uintptr_t>(a->chain_status) & 3u))
         return LRNNX_ERR_INVALID_ARG;
     if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
     return LRNNX_OK;
 }
 
 int lrnnx_lti_diag_scan(const lrnnx_lti_args *a) {
-    if (!a || a->struct_size < sizeof(lrnnx_lti_args)) return LRNNX_ERR_INVALID_ARG;
+    if (!a || a->struct_size != sizeof(lrnnx_lti_args)) return LRNNX_ERR_INVALID_ARG;
     const int path = a->path;
     if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
     if (const int st = lti_args_valid(a)) return st;
@@ -647,7 +636,7 @@ static void *static_scratch_ptr() {
 size_t lrnnx_static_scratch_bytes(void) { return LRNNX_STATIC_SCRATCH_BYTES; }
 
 int lrnnx_lti_diag_scan_static(const lrnnx_lti_args *a) {
-    if (!a || a->struct_size < sizeof(lrnnx_lti_args)) return LRNNX_ERR_INVALID_ARG;
+    if (!a || a->struct_size != sizeof(lrnnx_lti_args)) return LRNNX_ERR_INVALID_ARG;
     if (a->path != LRNNX_PATH_AUTO && a->path != LRNNX_PATH_SINGLE_PASS) return LRNNX_ERR_INVALID_ARG;
     if (const int st = lti_args_valid(a)) return st;
     if (lti_onepass_bytes(a->B, a->P, a->L) > LRNNX_STATIC_SCRATCH_BYTES) return LRNNX_ERR_WORKSPACE;
@@ -657,7 +646,7 @@ int lrnnx_lti_diag_scan_static(const lrnnx_lti_args *a) {
 }
 
 int lrnnx_lti_diag_scan_bwd(const lrnnx_lti_bwd_args *a) {
-    if (!a || a->struct_size < sizeof(lrnnx_lti_bwd_args)) return LRNNX_ERR_INVALID_ARG;
+    if (!a || a->struct_size != sizeof(lrnnx_lti_bwd_args)) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->P < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (!a->lambda || !a->x || !a->gx || !a->dv || !a->dlambda) return LRNNX_ERR_INVALID_ARG;
     for (const void *q : {a->lambda, a->x, a->x0, a->gx, (const void *)a->dv, (const void *)a->dlambda,
@@ -665,7 +654,7 @@ int lrnnx_lti_diag_scan_bwd(const lrnnx_lti_bwd_args *a) {
         if (reinterpret_cast<uintptr_t>(q) & 7u) return LRNNX_ERR_INVALID_ARG;
     const int64_t ng = cdiv(a->L, lti_onepass_bwd_group_steps());
     const int64_t wgx = (int64_t)a->B * cdiv(a->P, 64);
-    if (ng > 65535 || wgx > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;
+    if (a->B > 65535 || ng > 65535 || wgx > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;
     if (!a->workspace || a->workspace_bytes < lti_onepass_bwd_bytes(a->B, a->P, a->L) ||
         (reinterpret_cast<uintptr_t>(a->workspace) & 7u))
         return LRNNX_ERR_WORKSPACE;
@@ -680,6 +669,7 @@ int lrnnx_lti_diag_scan_bwd(const lrnnx_lti_bwd_args *a) {
     p.x_last = reinterpret_cast<float2 *>(a->dx0);
     p.dlambda = reinterpret_cast<float *>(a->dlambda);
     p.ngroups = (int)ng;
+    p.status = a->chain_status;
     set_onepass_workspace(p, a->workspace);
     FillList z = onepass_fill(p);
     z.ptr[2] = p.dlambda; z.count[2] = 2 * (int64_t)a->P;
@@ -688,7 +678,7 @@ int lrnnx_lti_diag_scan_bwd(const lrnnx_lti_bwd_args *a) {
 }
 
 int lrnnx_diag_scan(const lrnnx_diag_scan_args *a) {
-    if (!a || a->struct_size < sizeof(lrnnx_diag_scan_args)) return LRNNX_ERR_INVALID_ARG;
+    if (!a || a->struct_size != sizeof(lrnnx_diag_scan_args)) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->P < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->dtype != LRNNX_F32 && a->dtype != LRNNX_C64) return LRNNX_ERR_INVALID_ARG;
     if (!a->a || !a->b || !a->x) return LRNNX_ERR_INVALID_ARG;
@@ -699,7 +689,7 @@ int lrnnx_diag_scan(const lrnnx_diag_scan_args *a) {
     if ((int64_t)a->P * (cplx ? 8 : 4) > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;   // 32-bit byte offsets in a row
     const int64_t ng = cdiv(a->L, diag_scan_group_steps(a->B, a->P, cplx));
     const int64_t wgx = (int64_t)a->B * cdiv(a->P, 64);
-    if (ng > 65535 || wgx > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;
+    if (a->B > 65535 || ng > 65535 || wgx > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;
     if (!a->workspace || a->workspace_bytes < diag_scan_bytes(a->B, a->P, a->L, cplx) ||
         (reinterpret_cast<uintptr_t>(a->workspace) & 7u))
         return LRNNX_ERR_WORKSPACE;
@@ -708,13 +698,14 @@ int lrnnx_diag_scan(const lrnnx_diag_scan_args *a) {
     p.B = a->B; p.P = a->P; p.L = a->L;
     p.is_complex = cplx; p.ngroups = (int)ng;
     p.a = a->a; p.b = a->b; p.x0 = a->x0; p.x = a->x; p.x_last = a->x_last;
+    p.status = a->chain_status;
     const FillList z = set_diag_workspace(p, a->workspace);
     if (launch_fill(z, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
     return launch_diag_scan(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }
 
 int lrnnx_diag_scan_bwd(const lrnnx_diag_scan_bwd_args *a) {
-    if (!a || a->struct_size < sizeof(lrnnx_diag_scan_bwd_args)) return LRNNX_ERR_INVALID_ARG;
+    if (!a || a->struct_size != sizeof(lrnnx_diag_scan_bwd_args)) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->P < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->dtype != LRNNX_F32 && a->dtype != LRNNX_C64) return LRNNX_ERR_INVALID_ARG;
     if (!a->a || !a->x || !a->gx || !a->da || !a->db) return LRNNX_ERR_INVALID_ARG;
@@ -726,7 +717,7 @@ int lrnnx_diag_scan_bwd(const lrnnx_diag_scan_bwd_args *a) {
     if ((int64_t)a->P * (cplx ? 8 : 4) > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;   // 32-bit byte offsets in a row
     const int64_t ng = cdiv(a->L, diag_scan_bwd_group_steps(cplx));
     const int64_t wgx = (int64_t)a->B * cdiv(a->P, 64);
-    if (ng > 65535 || wgx > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;
+    if (a->B > 65535 || ng > 65535 || wgx > 0x7fffffff) return LRNNX_ERR_UNSUPPORTED;
     if (!a->workspace || a->workspace_bytes < diag_scan_bwd_bytes(a->B, a->P, a->L, cplx) ||
         (reinterpret_cast<uintptr_t>(a->workspace) & 7u))
         return LRNNX_ERR_WORKSPACE;
@@ -736,17 +727,16 @@ int lrnnx_diag_scan_bwd(const lrnnx_diag_scan_bwd_args *a) {
     p.is_complex = cplx; p.ngroups = (int)ng;
     p.a = a->a; p.b = a->gx; p.xs = a->x; p.x0 = a->x0;
     p.x = a->db; p.da = a->da; p.x_last = a->dx0;
+    p.status = a->chain_status;
     const FillList z = set_diag_workspace(p, a->workspace);
     if (launch_fill(z, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
     return launch_diag_scan_bwd(p, s) == hipSuccess ? LRNNX_OK : LRNNX_ERR_LAUNCH;
 }
 
 int lrnnx_selective_step(const lrnnx_ss_step_args *a) {
-    constexpr size_t kOldSize = offsetof(lrnnx_ss_step_args, bc_groups);  // struct before `bc_groups` was appended
-    if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
-    const bool has_groups = a->struct_size >= sizeof(lrnnx_ss_step_args);
-    if (has_groups && a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
-    const int bcg = (has_groups && a->bc_groups > 1) ? a->bc_groups : 1;
+    if (!a || a->struct_size != sizeof(lrnnx_ss_step_args)) return LRNNX_ERR_INVALID_ARG;
+    if (a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
+    const int bcg = a->bc_groups > 1 ? a->bc_groups : 1;
     if (a->D % bcg) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->D < 1 || a->N < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
@@ -767,11 +757,9 @@ int lrnnx_selective_step(const lrnnx_ss_step_args *a) {
 }
 
 int lrnnx_selective_step_complex(const lrnnx_ss_step_complex_args *a) {
-    constexpr size_t kOldSize = offsetof(lrnnx_ss_step_complex_args, bc_groups);  // struct before `bc_groups` was appended
-    if (!a || a->struct_size < kOldSize) return LRNNX_ERR_INVALID_ARG;
-    const bool has_groups = a->struct_size >= sizeof(lrnnx_ss_step_complex_args);
-    if (has_groups && a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
-    const int bcg = (has_groups && a->bc_groups > 1) ? a->bc_groups : 1;
+    if (!a || a->struct_size != sizeof(lrnnx_ss_step_complex_args)) return LRNNX_ERR_INVALID_ARG;
+    if (a->bc_groups < 0) return LRNNX_ERR_INVALID_ARG;
+    const int bcg = a->bc_groups > 1 ? a->bc_groups : 1;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->D % bcg) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
@@ -791,8 +779,9 @@ int lrnnx_selective_step_complex(const lrnnx_ss_step_complex_args *a) {
 }
 
 int lrnnx_lti_step(const lrnnx_lti_step_args *a) {
-    if (!a || a->struct_size < sizeof(lrnnx_lti_step_args)) return LRNNX_ERR_INVALID_ARG;
+    if (!a || a->struct_size != sizeof(lrnnx_lti_step_args)) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->P < 1 || !a->lambda || !a->x || !a->v) return LRNNX_ERR_INVALID_ARG;
+    if (a->B > 65535) return LRNNX_ERR_UNSUPPORTED;
     if ((reinterpret_cast<uintptr_t>(a->v) & 7u) || (reinterpret_cast<uintptr_t>(a->x) & 7u) ||
         (reinterpret_cast<uintptr_t>(a->lambda) & 7u))
         return LRNNX_ERR_INVALID_ARG;

@@ -166,7 +166,7 @@ __global__ __launch_bounds__(GW * 64) void k_diag_scan(const DiagParams p) {
                 else { const float2 f = from_bits(tb[i]); acc = __builtin_fmaf(f.x, acc, f.y); }
             }
         if (!ok) {                                             // never hand back a plausible but wrong state
-            if (lane == 0) *p.err = 1;
+            if (lane == 0) { *p.err = 1; if (p.status) *p.status = 1; }
             acc = EL::nan();
         }
         if (g % ANCH == ANCH - 1 && okp) {

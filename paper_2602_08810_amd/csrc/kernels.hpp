@@ -119,6 +119,7 @@ struct LtiParams {
     float2 *ws_T;            // [B,ngroups,P] group end state from zero; all-ones words = not published yet
     float2 *ws_X;            // [B,ngroups/16+1,P] true end state of every 16th group; all-ones = not published
     int *err;                // set to 1 if a bounded wait ran out
+    int *status;             // the caller's word for the same, or null
     // adjoint (single-pass only): v = gx, x = dv, x_last = dx0, x0 = the forward pass's x0
     const float2 *xs;        // [B,L,P] states saved by the forward scan
     float *dlambda;          // [P] complex as float pairs, accumulated with atomics (zero it first)
@@ -134,6 +135,7 @@ struct DiagParams {
     float2 *ws_T;            // [B,ngroups,slots,P] group aggregates (slots: 1 real = (A,S); 2 complex = A, S)
     float2 *ws_X;            // [B,ngroups/anchor+1,P] true end state of every anchor group
     int *err;
+    int *status;             // the caller's word for a bounded wait that ran out, or null
     // adjoint only: b = gx, x = db, x_last = dx0, x0 = the forward pass's x0
     const void *xs;          // [B,L,P] states saved by the forward scan
     void *da;                // [B,L,P] out

@@ -197,7 +197,7 @@ __global__ __launch_bounds__(kOneGW * 64) void k_lti_onepass(const LtiParams p) 
         for (int i = 0; i < kAnchor - 1; ++i)
             if (i < need) acc = cfma(lg, acc, from_bits(tb[i]));
         if (!ok) {                                             // never hand back a plausible but wrong state
-            if (lane == 0) *p.err = 1;
+            if (lane == 0) { *p.err = 1; if (p.status) *p.status = 1; }
             acc = make_float2(__builtin_nanf(""), __builtin_nanf(""));
         }
         if (g % kAnchor == kAnchor - 1 && okp) publish(wsX + (int64_t)(g / kAnchor) * P, cfma(lg, acc, T));

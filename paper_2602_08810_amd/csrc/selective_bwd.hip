@@ -25,12 +25,6 @@
 namespace lrnnx {
 
 constexpr int kMaxG = 128;
-#ifndef LRNNX_BWD_NK16
-#define LRNNX_BWD_NK16 4
-#endif
-#ifndef LRNNX_BWD_T16
-#define LRNNX_BWD_T16 4
-#endif
 
 template <typename IO, int N, int NK, int T, int DISC>
 __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) {
@@ -447,8 +441,6 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     }
 }
 
-
-#ifndef LRNNX_KERNEL_ONLY
 // ---------------------------------------------------------------- launchers
 // channels per workgroup: D here is the number of channels that share one pair of Bm/Cm maps.  `balanced` says
 // that all batch entries have the same length; otherwise (packed variable-length batches) four times as many,
@@ -501,7 +493,7 @@ static hipError_t launch_bwd_disc(const BwdParams &p, hipStream_t s) {
         case 2: return launch_bwd_n<IO, 2, 2, DISC, 4>(p, s);
         case 4: return launch_bwd_n<IO, 4, 2, DISC, 4>(p, s);
         case 8: return launch_bwd_n<IO, 8, 4, DISC, 4>(p, s);
-        case 16: return launch_bwd_n<IO, 16, LRNNX_BWD_NK16, DISC, LRNNX_BWD_T16>(p, s);
+        case 16: return launch_bwd_n<IO, 16, 4, DISC, 4>(p, s);
         case 32: return launch_bwd_n<IO, 32, 4, DISC, 4>(p, s);    // eight wavefronts: one workgroup per compute unit
     }
     return hipErrorInvalidValue;
@@ -521,6 +513,5 @@ static hipError_t launch_bwd_io(const BwdParams &p, int disc, hipStream_t s) {
 hipError_t launch_ss_bwd(const BwdParams &p, int io_dtype, int disc, hipStream_t s) {
     return io_dtype == 1 ? launch_bwd_io<bf16_t>(p, disc, s) : launch_bwd_io<float>(p, disc, s);
 }
-#endif  // LRNNX_KERNEL_ONLY
 
 }  // namespace lrnnx

@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_host_queries(lib):
-    lib.lrnnx_workspace_bytes.argtypes = [ctypes.c_int] + [ctypes.c_int64] * 4 + [ctypes.c_int]
+    lib.lrnnx_workspace_bytes.argtypes = [ctypes.c_int] + [ctypes.c_int64] * 4 + [ctypes.c_int] * 3
     lib.lrnnx_workspace_bytes.restype = ctypes.c_size_t
     lib.lrnnx_ckpt_interval.restype = ctypes.c_int64
     lib.lrnnx_status_string.restype = ctypes.c_char_p
@@ -38,10 +38,10 @@ def test_host_queries(lib):
     assert I > 0
     # backward: the checkpoints of the recompute sweep (rounded up to 256 bytes), then the chunk aggregates
     ck = 2 * 3 * ((1000 + I - 1) // I) * 16 * 4
-    carry = lib.lrnnx_workspace_bytes(7, 2, 3, 16, 1000, 1)
+    carry = lib.lrnnx_workspace_bytes(7, 2, 3, 16, 1000, 1, 1, 0)
     assert carry > 0 and carry % (2 * 2 * 3 * 16 * 4) == 0            # two arrays [B,D,chunks,N] of floats
-    assert lib.lrnnx_workspace_bytes(1, 2, 3, 16, 1000, 1) == (ck + 255) // 256 * 256 + carry
-    assert lib.lrnnx_workspace_bytes(7, 1, 8, 16, 200, 1) == 0        # a single tile: nothing to cut
+    assert lib.lrnnx_workspace_bytes(1, 2, 3, 16, 1000, 1, 1, 0) == (ck + 255) // 256 * 256 + carry
+    assert lib.lrnnx_workspace_bytes(7, 1, 8, 16, 200, 1, 1, 0) == 0        # a single tile: nothing to cut
     chunks = lib.lrnnx_selective_scan_bwd_chunks
     chunks.argtypes = [ctypes.c_int64] * 4 + [ctypes.c_int] * 3
     assert chunks(16, 2560, 16, 4096, 1, 0, 0) == 1                   # enough rows to fill the chip: one pass
@@ -52,19 +52,31 @@ def test_host_queries(lib):
     assert chunks(1, 8, 3, 200, 1, 0, 0) == 0 and chunks(1, 9, 16, 200, 2, 0, 0) == 0
     assert chunks(1, 512, 16, 65536, 1, 0, 1) > 1 and chunks(8, 1536, 16, 2048, 1, 0, 1) == 1    # the complex-A scan
     assert chunks(1, 64, 32, 4096, 1, 0, 1) == 0                      # ... takes N <= 16
-    assert lib.lrnnx_workspace_bytes(0, 1, 2048, 16, 65536, 1) > 0
-    assert lib.lrnnx_workspace_bytes(0, 1, 8, 3, 64, 1) == 0          # unsupported N
-    assert lib.lrnnx_workspace_bytes(2, 4, 256, 0, 4096, 0) > 0
-    assert lib.lrnnx_workspace_bytes(3, 4, 256, 0, 4096, 0) > 0
-    assert lib.lrnnx_workspace_bytes(4, 4, 256, 0, 4096, 2) > lib.lrnnx_workspace_bytes(4, 4, 256, 0, 4096, 0) > 0
-    assert lib.lrnnx_workspace_bytes(4, 4, 256, 0, 4096, 1) == 0      # bf16 is not a dtype of the raw scan
-    assert lib.lrnnx_workspace_bytes(5, 4, 256, 0, 4096, 2) > lib.lrnnx_workspace_bytes(5, 4, 256, 0, 4096, 0) > 0
+    assert lib.lrnnx_workspace_bytes(0, 1, 2048, 16, 65536, 1, 1, 0) > 0
+    assert lib.lrnnx_workspace_bytes(0, 1, 8, 3, 64, 1, 1, 0) == 0          # unsupported N
+    assert lib.lrnnx_workspace_bytes(2, 4, 256, 0, 4096, 0, 1, 0) > 0
+    assert lib.lrnnx_workspace_bytes(3, 4, 256, 0, 4096, 0, 1, 0) > 0
+    assert lib.lrnnx_workspace_bytes(4, 4, 256, 0, 4096, 2, 1, 0) > lib.lrnnx_workspace_bytes(4, 4, 256, 0, 4096, 0, 1, 0) > 0
+    assert lib.lrnnx_workspace_bytes(4, 4, 256, 0, 4096, 1, 1, 0) == 0      # bf16 is not a dtype of the raw scan
+    assert lib.lrnnx_workspace_bytes(5, 4, 256, 0, 4096, 2, 1, 0) > lib.lrnnx_workspace_bytes(5, 4, 256, 0, 4096, 0, 1, 0) > 0
     ckc = 2 * 3 * ((1000 + I - 1) // I) * 16 * 8                      # the complex backward: float pairs
-    wsc = lib.lrnnx_workspace_bytes(6, 2, 3, 16, 1000, 1)
+    wsc = lib.lrnnx_workspace_bytes(6, 2, 3, 16, 1000, 1, 1, 0)
     assert wsc > (ckc + 255) // 256 * 256 and (wsc - (ckc + 255) // 256 * 256) % (2 * 2 * 3 * 16 * 8) == 0
-    assert lib.lrnnx_workspace_bytes(8, 1, 64, 16, 8192, 1) > 0 and lib.lrnnx_workspace_bytes(8, 1, 64, 32, 8192, 1) == 0
+    assert lib.lrnnx_workspace_bytes(8, 1, 64, 16, 8192, 1, 1, 0) > 0 and lib.lrnnx_workspace_bytes(8, 1, 64, 32, 8192, 1, 1, 0) == 0
     assert lib.lrnnx_status_string(0) == b"ok" and lib.lrnnx_status_string(3).startswith(b"workspace")
-    assert lib.lrnnx_version() >= 100
+    assert lib.lrnnx_version() >= 200
+    # grouped maps plan with (B * groups) row groups of D / groups channels: the aggregates of the chunked backward
+    # are sized for that plan (a multiple of two arrays [B,D,chunks,N]), and D must be a multiple of the groups
+    g4 = lib.lrnnx_workspace_bytes(7, 1, 512, 16, 16384, 1, 4, 0)
+    assert g4 > 0 and g4 % (2 * 512 * 16 * 4) == 0 and lib.lrnnx_workspace_bytes(7, 1, 510, 16, 16384, 1, 4, 0) == 0
+    # packed batches: checkpoints [D, L / interval + B, N] of the recompute sweep, then B ints of launch order; the
+    # forward call needs none (single pass only)
+    slots = 1024 // I + 3
+    assert lib.lrnnx_workspace_bytes(1, 3, 8, 16, 1024, 1, 1, 1) == (8 * slots * 16 * 4 + 255) // 256 * 256 + 4 * 3
+    assert lib.lrnnx_workspace_bytes(7, 3, 8, 16, 1024, 1, 1, 1) == 4 * 3
+    assert lib.lrnnx_workspace_bytes(6, 3, 8, 16, 1024, 1, 1, 1) == (8 * slots * 16 * 8 + 255) // 256 * 256 + 4 * 3
+    assert lib.lrnnx_workspace_bytes(0, 3, 8, 16, 1024, 1, 1, 1) == 0
+    assert lib.lrnnx_static_scratch_bytes() == 4 << 20
 
 
 def test_null_and_bad_struct_are_rejected_without_a_gpu(lib):
@@ -90,6 +102,8 @@ def test_null_and_bad_struct_are_rejected_without_a_gpu(lib):
     buf = (ctypes.c_char * 512)()                                       # struct_size = 0
     assert lib.lrnnx_selective_scan_fwd(ctypes.addressof(buf)) == 1
     assert lib.lrnnx_lti_diag_scan(ctypes.addressof(buf)) == 1
+    lib.lrnnx_lti_diag_scan_static.argtypes = [ctypes.c_void_p]
+    assert lib.lrnnx_lti_diag_scan_static(None) == 1 and lib.lrnnx_lti_diag_scan_static(ctypes.addressof(buf)) == 1
 
 
 def test_bench_refuses_more_than_one_gpu():
@@ -156,6 +170,7 @@ def test_host_side_validation_of_the_forward_call(lib):
     assert call(y_stride_d=50) == 1                # output rows would overlap
     assert call(bc_groups=3) == 1                  # D = 8 is not a multiple of 3 groups
     assert call(path=2) == 3                       # the chunk-carry path needs a workspace
+    assert call(struct_size=ctypes.sizeof(api.FwdArgs) - 8) == 1 and call(struct_size=ctypes.sizeof(api.FwdArgs) + 8) == 1
 
 
 def test_host_side_validation_of_the_backward_and_lti_calls(lib):
@@ -205,11 +220,20 @@ def test_host_side_validation_of_the_backward_and_lti_calls(lib):
     assert lti(v=0x10004) == 1 and lti(x=0) == 1 and lti(path=7) == 1
     assert lti(B=70000) == 2
     assert lti() == 3                                         # every path of this call needs its workspace
+    assert lti(chain_status=0x10002) == 1                     # a 4-byte word
+    lib.lrnnx_lti_diag_scan_static.argtypes = [ctypes.POINTER(api.LtiArgs)]
+    a = api.LtiArgs()
+    a.struct_size = ctypes.sizeof(api.LtiArgs)
+    a.B, a.P, a.L = 8, 1024, 8192
+    a.lambda_ = a.v = a.x = fake
+    assert lib.lrnnx_lti_diag_scan_static(ctypes.byref(a)) == 3   # needs more chain slots than the static array has
+    a.path = 2
+    assert lib.lrnnx_lti_diag_scan_static(ctypes.byref(a)) == 1   # the two-launch path is not offered there
 
 
 def test_host_side_validation_of_the_complex_calls(lib):
-    """As above for the complex-A forward and backward entry points, including the shorter argument blocks of callers
-    built before fields were appended (fake pointers, no GPU: only refusals are exercised)."""
+    """As above for the complex-A forward and backward entry points (fake pointers, no GPU: only refusals are
+    exercised)."""
     torch = pytest.importorskip("torch")
     if torch.cuda.device_count() > 0:
         pytest.skip("host-only test: not run on a machine with a GPU")
@@ -237,10 +261,7 @@ def test_host_side_validation_of_the_complex_calls(lib):
     assert fwd(path=5) == 1 and fwd(path=2, cu_seqlens=fake) == 2
     assert fwd(path=2, L=4000, y_stride_d=4000) == 3                   # the chunk-carry path needs its workspace
     assert fwd(path=2, L=4000, y_stride_d=4000, workspace=0x10004, workspace_bytes=1 << 30) == 1
-    assert fwd(size=api.FwdComplexArgs.ckpt.offset - 8) == 1           # shorter than the first published block
-    # a block that ends before `cu_seqlens` is still read (its later fields are then ignored): the refusal
-    # comes from the fields it does have
-    assert fwd(size=api.FwdComplexArgs.cu_seqlens.offset, N=3, cu_seqlens=0x10004) == 2
+    assert fwd(size=ctypes.sizeof(api.FwdComplexArgs) - 8) == 1        # any size but the struct's own is refused
 
     def bwd(size=None, **over):
         a = api.BwdComplexArgs()
@@ -263,7 +284,7 @@ def test_host_side_validation_of_the_complex_calls(lib):
     assert bwd(cu_seqlens=0x10004) == 1 and bwd(bc_groups=5) == 1
     assert bwd(path=4) == 1 and bwd(path=2, cu_seqlens=fake) == 2
     assert bwd(path=2, L=2000, du_stride_d=2000, ddelta_stride_d=2000) == 3
-    assert bwd(size=api.BwdComplexArgs.cu_seqlens.offset - 8) == 1
+    assert bwd(size=ctypes.sizeof(api.BwdComplexArgs) + 16) == 1
     # packed mode sizes the recompute workspace by D * (L / interval + B) * N float pairs
     need = 8 * (100 // int(lib.lrnnx_ckpt_interval()) + 2) * 16 * 8
     assert bwd(ckpt=0, cu_seqlens=fake, workspace=fake, workspace_bytes=need - 1) == 3

@@ -75,3 +75,25 @@ def test_error_codes(api):
     with pytest.raises(api.LrnnxError) as e:
         api.lrnnx_lti_diag_scan(lam, v, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
     assert e.value.code == 3
+
+
+def test_chain_status_word_stays_clear(api, oracle):
+    """The optional status word reports a bounded wait between workgroups that ran out; on a healthy run of many
+    chained groups (here 512 per row, and the adjoint and the caller-coefficient scans over the same shape) the library
+    must leave it at the caller's zero."""
+    import torch
+    q = workloads.make_lti(B=2, P=70, L=65536 // 2, seed=11, with_gx=True)
+    lam, v, gx = (torch.from_numpy(q[k]).cuda() for k in ("lam", "v", "gx"))
+    st = torch.zeros(1, dtype=torch.int32, device="cuda")
+    x = api.lrnnx_lti_diag_scan(lam, v, path="single_pass", chain_status=st)
+    api.lrnnx_lti_diag_scan_bwd(lam, x, gx, chain_status=st)
+    a = torch.from_numpy(np.abs(q["v"]).astype(np.float32) * 0.5).cuda().contiguous()
+    xs = api.lrnnx_diag_scan(a, gx.real.contiguous(), chain_status=st)
+    api.lrnnx_diag_scan_bwd(a, xs, gx.imag.contiguous(), chain_status=st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    ref = oracle.lti_diag_scan(q["lam"], q["v"])
+    got = x.cpu().numpy()
+    assert rel_err(got.real, ref.real) <= 1e-4 and rel_err(got.imag, ref.imag) <= 1e-4
+    with pytest.raises(ValueError):
+        api.lrnnx_lti_diag_scan(lam, v, chain_status=torch.zeros(2, dtype=torch.int32, device="cuda"))
