@@ -232,6 +232,135 @@ __device__ __forceinline__ void wave_scan_fwd_rev(float &P, float &S, float &Pr,
     }
 }
 
+// ---------------------------------------------------------------- both scans of the backward pass, NK states at once
+// The state prefix (P,S) and the adjoint suffix (Pr,Sr) of each of NK states advance together, one Hillis-Steele
+// step of all 2 NK pairs per block of instructions.  The chains of different states are independent, so each fills
+// the others' wait states (no s_nop between DPP steps) and, above all, the one LDS round trip of the suffix scan
+// (the hand-over between rows: no DPP control moves data towards lower rows) is paid once per call instead of once
+// per state: all 2 NK lane permutes are in flight while the prefix scans take their two broadcast steps.
+// Hazards inside the blocks are kept by construction (a DPP read of a register comes at least three instructions
+// after its last write); every block starts with s_nop 1 in case the compiler placed a copy right before it.
+#define LRNNX_FR_STATE(s, p, r, q, CF, CR)                                             \
+    "v_fmac_f32_dpp %" #s ", %" #s ", %" #p " " CF "\n\t"                               \
+    "v_mul_f32_dpp %" #p ", %" #p ", %" #p " " CF "\n\t"                                \
+    "v_fmac_f32_dpp %" #r ", %" #r ", %" #q " " CR "\n\t"                               \
+    "v_mul_f32_dpp %" #q ", %" #q ", %" #q " " CR "\n\t"
+#define LRNNX_F_STATE(s, p, CF)                                                        \
+    "v_fmac_f32_dpp %" #s ", %" #s ", %" #p " " CF "\n\t"                               \
+    "v_mul_f32_dpp %" #p ", %" #p ", %" #p " " CF "\n\t"
+#define LRNNX_ALLROWS " row_mask:0xf bank_mask:0xf"
+
+#define LRNNX_DEFINE_FR_ROWSTEP(NAME, CF, CR)                                                                        \
+    template <int NK>                                                                                                \
+    __device__ __forceinline__ void NAME(float *P, float *S, float *Pr, float *Sr) {                                 \
+        static_assert(NK == 1 || NK == 2 || NK == 4, "states per wavefront");                                        \
+        if constexpr (NK == 1) {                                                                                     \
+            asm("s_nop 1\n\t" LRNNX_FR_STATE(0, 1, 2, 3, CF, CR)                                                     \
+                : "+v"(S[0]), "+v"(P[0]), "+v"(Sr[0]), "+v"(Pr[0]));                                                 \
+        } else if constexpr (NK == 2) {                                                                              \
+            asm("s_nop 1\n\t" LRNNX_FR_STATE(0, 1, 2, 3, CF, CR) LRNNX_FR_STATE(4, 5, 6, 7, CF, CR)                  \
+                : "+v"(S[0]), "+v"(P[0]), "+v"(Sr[0]), "+v"(Pr[0]), "+v"(S[1]), "+v"(P[1]), "+v"(Sr[1]), "+v"(Pr[1])); \
+        } else {                                                                                                     \
+            asm("s_nop 1\n\t" LRNNX_FR_STATE(0, 1, 2, 3, CF, CR) LRNNX_FR_STATE(4, 5, 6, 7, CF, CR)                  \
+                LRNNX_FR_STATE(8, 9, 10, 11, CF, CR) LRNNX_FR_STATE(12, 13, 14, 15, CF, CR)                          \
+                : "+v"(S[0]), "+v"(P[0]), "+v"(Sr[0]), "+v"(Pr[0]), "+v"(S[1]), "+v"(P[1]), "+v"(Sr[1]), "+v"(Pr[1]), \
+                  "+v"(S[2]), "+v"(P[2]), "+v"(Sr[2]), "+v"(Pr[2]), "+v"(S[3]), "+v"(P[3]), "+v"(Sr[3]), "+v"(Pr[3])); \
+        }                                                                                                            \
+    }
+LRNNX_DEFINE_FR_ROWSTEP(scan_fr_row1, "row_shr:1" LRNNX_ALLROWS, "row_shl:1" LRNNX_ALLROWS)
+LRNNX_DEFINE_FR_ROWSTEP(scan_fr_row2, "row_shr:2" LRNNX_ALLROWS, "row_shl:2" LRNNX_ALLROWS)
+LRNNX_DEFINE_FR_ROWSTEP(scan_fr_row4, "row_shr:4" LRNNX_ALLROWS, "row_shl:4" LRNNX_ALLROWS)
+LRNNX_DEFINE_FR_ROWSTEP(scan_fr_row8, "row_shr:8" LRNNX_ALLROWS, "row_shl:8" LRNNX_ALLROWS)
+
+// prefix scans only: the two steps that cross rows (lane 15 of rows 0,2 -> rows 1,3; lane 31 -> rows 2,3)
+#define LRNNX_DEFINE_F_STEP(NAME, CF)                                                                                \
+    template <int NK>                                                                                                \
+    __device__ __forceinline__ void NAME(float *P, float *S) {                                                       \
+        if constexpr (NK == 1) {                                                                                     \
+            asm("s_nop 1\n\t" LRNNX_F_STATE(0, 1, CF) : "+v"(S[0]), "+v"(P[0]));                                     \
+        } else if constexpr (NK == 2) {                                                                              \
+            asm("s_nop 1\n\t" LRNNX_F_STATE(0, 1, CF) LRNNX_F_STATE(2, 3, CF)                                        \
+                : "+v"(S[0]), "+v"(P[0]), "+v"(S[1]), "+v"(P[1]));                                                   \
+        } else {                                                                                                     \
+            asm("s_nop 1\n\t" LRNNX_F_STATE(0, 1, CF) LRNNX_F_STATE(2, 3, CF) LRNNX_F_STATE(4, 5, CF) LRNNX_F_STATE(6, 7, CF) \
+                : "+v"(S[0]), "+v"(P[0]), "+v"(S[1]), "+v"(P[1]), "+v"(S[2]), "+v"(P[2]), "+v"(S[3]), "+v"(P[3]));   \
+        }                                                                                                            \
+    }
+LRNNX_DEFINE_F_STEP(scan_f_bcast15, "row_bcast:15 row_mask:0xa bank_mask:0xf")
+LRNNX_DEFINE_F_STEP(scan_f_bcast31, "row_bcast:31 row_mask:0xc bank_mask:0xf")
+// the last step of a prefix scan whose products are not needed afterwards: only the S half
+template <int NK>
+__device__ __forceinline__ void scan_f_bcast31_last(const float *P, float *S) {
+#define LRNNX_F_LAST(s, p) "v_fmac_f32_dpp %" #s ", %" #s ", %" #p " row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+    if constexpr (NK == 1) {
+        asm("s_nop 1\n\t" LRNNX_F_LAST(0, 1) : "+v"(S[0]) : "v"(P[0]));
+    } else if constexpr (NK == 2) {
+        asm("s_nop 1\n\t" LRNNX_F_LAST(0, 2) LRNNX_F_LAST(1, 3) : "+v"(S[0]), "+v"(S[1]) : "v"(P[0]), "v"(P[1]));
+    } else {
+        asm("s_nop 1\n\t" LRNNX_F_LAST(0, 4) LRNNX_F_LAST(1, 5) LRNNX_F_LAST(2, 6) LRNNX_F_LAST(3, 7)
+            : "+v"(S[0]), "+v"(S[1]), "+v"(S[2]), "+v"(S[3]) : "v"(P[0]), "v"(P[1]), "v"(P[2]), "v"(P[3]));
+    }
+#undef LRNNX_F_LAST
+}
+
+// On return S holds the inclusive prefix (lane 0 first) and Sr the inclusive suffix (lane 63 first) of every state;
+// P and Pr are left in an unspecified state.
+template <int NK>
+__device__ __forceinline__ void wave_scan_fwd_rev_multi(float *P, float *S, float *Pr, float *Sr, int lane) {
+    scan_fr_row1<NK>(P, S, Pr, Sr);
+    scan_fr_row2<NK>(P, S, Pr, Sr);
+    scan_fr_row4<NK>(P, S, Pr, Sr);
+    scan_fr_row8<NK>(P, S, Pr, Sr);
+    // suffixes: rows 0 and 2 take the pair held by the first lane of the next row
+    const int src = ((lane & 0x30) + 16) & 63;
+    float Pp[NK], Sp[NK];
+#pragma unroll
+    for (int k = 0; k < NK; ++k) { Pp[k] = bpermute(src, Pr[k]); Sp[k] = bpermute(src, Sr[k]); }
+    scan_f_bcast15<NK>(P, S);
+    scan_f_bcast31_last<NK>(P, S);
+#pragma unroll
+    for (int k = 0; k < NK; ++k)      // rows 0, 2 only (row_mask 0x5); the other rows keep their pair
+        asm("s_nop 1\n\t"
+            "v_fmac_f32_dpp %0, %2, %1 quad_perm:[0,1,2,3] row_mask:0x5 bank_mask:0xf\n\t"
+            "v_mul_f32_dpp %1, %3, %1 quad_perm:[0,1,2,3] row_mask:0x5 bank_mask:0xf"
+            : "+v"(Sr[k]), "+v"(Pr[k]) : "v"(Sp[k]), "v"(Pp[k]));
+    // rows 0 and 1 take the suffix now held by lane 32: Sr += Pr * Sr[32] (the product of the multipliers is not
+    // needed any more).  The value travels through a scalar register; the update runs with the upper half of the
+    // wavefront switched off.  Wait states: one between the VALU write of Sr and its v_readlane, two between the
+    // v_readlane and the VALU read of its scalar result.
+    if constexpr (NK == 4) {
+        unsigned save;
+        float t0, t1, t2, t3;
+        asm("s_nop 1\n\t"
+            "v_readlane_b32 %4, %0, 32\n\t"
+            "v_readlane_b32 %5, %1, 32\n\t"
+            "v_readlane_b32 %6, %2, 32\n\t"
+            "v_readlane_b32 %7, %3, 32\n\t"
+            "s_mov_b32 %8, exec_hi\n\t"
+            "s_mov_b32 exec_hi, 0\n\t"
+            "v_fmac_f32 %0, %4, %9\n\t"
+            "v_fmac_f32 %1, %5, %10\n\t"
+            "v_fmac_f32 %2, %6, %11\n\t"
+            "v_fmac_f32 %3, %7, %12\n\t"
+            "s_mov_b32 exec_hi, %8"
+            : "+v"(Sr[0]), "+v"(Sr[1]), "+v"(Sr[2]), "+v"(Sr[3]), "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(save)
+            : "v"(Pr[0]), "v"(Pr[1]), "v"(Pr[2]), "v"(Pr[3]));
+    } else {
+#pragma unroll
+        for (int k = 0; k < NK; ++k) {
+            unsigned save;
+            float t0;
+            asm("s_nop 1\n\t"
+                "v_readlane_b32 %1, %0, 32\n\t"
+                "s_mov_b32 %2, exec_hi\n\t"
+                "s_mov_b32 exec_hi, 0\n\t"
+                "v_fmac_f32 %0, %1, %3\n\t"
+                "s_mov_b32 exec_hi, %2"
+                : "+v"(Sr[k]), "=&s"(t0), "=&s"(save) : "v"(Pr[k]));
+        }
+    }
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
     v += dpp<0x111>(0.0f, v);
     v += dpp<0x112>(0.0f, v);
@@ -357,7 +486,9 @@ template <typename IO, int CNT, typename IDX>
 __device__ __forceinline__ void store_few(IO *row, IDX l, IDX L, bool vec, const float *v) {
     constexpr int EPC = io_traits<IO>::EPC;
     constexpr int BYTES = CNT * (16 / EPC);
-    if (vec && l + CNT <= L && BYTES % 16 == 0) {
+    if constexpr (CNT == 1) {                                   // one element: a single predicated access either way
+        if (l < L) io_traits<IO>::put(row, l, v[0]);
+    } else if (vec && l + CNT <= L && BYTES % 16 == 0) {
 #pragma unroll
         for (int c = 0; c < BYTES / 16; ++c)
             reinterpret_cast<uint4 *>(row + l)[c] = io_traits<IO>::pack(v + c * EPC);
@@ -385,7 +516,14 @@ template <typename IO, int CNT, typename IDX>
 __device__ __forceinline__ void load_few_raw(const IO *row, IDX l, IDX L, bool vec, RawFew<IO, CNT> &r) {
     constexpr int BYTES = CNT * (16 / io_traits<IO>::EPC);
     constexpr int WORDS = RawFew<IO, CNT>::WORDS;
-    if (vec && l + CNT <= L) {
+    if constexpr (CNT == 1) {
+        // one element, read without a branch: past the end the last element is read again and dropped (L >= 1)
+        const IDX lc = l < L ? l : L - 1;
+        uint32_t v;
+        if constexpr (sizeof(IO) == 4) v = *reinterpret_cast<const uint32_t *>(row + lc);
+        else v = *reinterpret_cast<const unsigned short *>(row + lc);
+        r.w[0] = l < L ? v : 0u;
+    } else if (vec && l + CNT <= L) {
         if constexpr (BYTES % 16 == 0) {
 #pragma unroll
             for (int c = 0; c < BYTES / 16; ++c) {

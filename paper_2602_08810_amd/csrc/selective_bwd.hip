@@ -26,7 +26,7 @@ namespace lrnnx {
 
 constexpr int kMaxG = 128;
 
-template <typename IO, int N, int NK, int T, int DISC>
+template <typename IO, int N, int NK, int T, int DISC, bool DZ>
 __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) {
     constexpr int W = N / NK;
     constexpr int NT = W * 64;
@@ -35,6 +35,10 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     constexpr int NA = TILE / TPW;                   // threads that take part in them: all, or (N = 32) the first 256
     constexpr int TQ = T / 4;
     constexpr int CK_PER_TILE = TILE / (int)kCkptInterval;
+    // states whose scans advance together: all of the wavefront's, or two for the schemes that also keep the gains
+    // g of every step (more registers)
+    constexpr int JSW = (DISC == DISC_ZOH || DISC == DISC_BILINEAR) ? 2 : 4;
+    constexpr int JS = NK < JSW ? NK : JSW;
     static_assert(T % 4 == 0 && (T % W == 0 || W % T == 0) && TPW <= 8 && NA % 64 == 0 && NA <= NT, "tile shape");
     static_assert(TILE % kCkptInterval == 0, "tiles must start on checkpoints");
     static_assert(TILE == kBwdTileSteps, "the chunked launch counts its chunks in tiles of this kernel");
@@ -124,18 +128,20 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
         float Cv[NK][T], dBacc[NK][T], dCacc[NK][T];
         {
         float Bv[NK][T];
+        // every row is loaded without a branch (past the end of the tile the last valid row is read again and then
+        // discarded), so that all 2 T loads of a lane are in flight together instead of one round trip per step
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             float tb[NK], tc[NK];
-            if (lane * T + t < rem) {
-                load_row<IO, NK>(BmT + (unsigned)((lane * T + t) * N), tb);
-                load_row<IO, NK>(CmT + (unsigned)((lane * T + t) * N), tc);
-            } else {
+            const int step = lane * T + t;
+            const int row = step < rem ? step : rem - 1;                  // rem >= 1: a tile has at least one step
+            load_row<IO, NK>(BmT + (unsigned)(row * N), tb);
+            load_row<IO, NK>(CmT + (unsigned)(row * N), tc);
 #pragma unroll
-                for (int k = 0; k < NK; ++k) { tb[k] = 0.0f; tc[k] = 0.0f; }
+            for (int k = 0; k < NK; ++k) {
+                Bv[k][t] = step < rem ? tb[k] : 0.0f; Cv[k][t] = step < rem ? tc[k] : 0.0f;
+                dBacc[k][t] = 0.0f; dCacc[k][t] = 0.0f;
             }
-#pragma unroll
-            for (int k = 0; k < NK; ++k) { Bv[k][t] = tb[k]; Cv[k][t] = tc[k]; dBacc[k][t] = 0.0f; dCacc[k][t] = 0.0f; }
         }
 #pragma unroll
         for (int k = 0; k < NK; ++k)
@@ -145,47 +151,68 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                     make_float4(Bv[k][4 * q], Bv[k][4 * q + 1], Bv[k][4 * q + 2], Bv[k][4 * q + 3]);
         }
 
-        // per-channel inputs are fetched one channel ahead, so their latency hides behind the main pass
-        RawFew<IO, TPW> r_u, r_dl, r_dy, r_z;
-        float pA[NK], pck[NK], pDsk, pbias;
-        auto prefetch = [&](int g) {
-            const int d = d0 + g;
-            const int64_t row = (int64_t)b * p.D + d;
+        // Per-channel inputs are fetched one channel ahead, so that their latency hides behind the main pass.  Every
+        // memory access of the channel loop is unconditional straight-line code (rows past the end of the tile, absent
+        // optional inputs and the channel past the last one read a valid address again and the value is discarded).
+        // (Fetching two channels ahead into two register sets was tried: the doubled loop body costs more than the
+        // longer distance gains.)
+        struct Pref { RawFew<IO, TPW> u, dl, dy, z; float A[NK], ck[NK], Dsk, bias; };
+        Pref S0;
+        // Row pointers (wave-uniform) of the channel the next prefetch reads and of the channel the next epilogue
+        // writes: set once per tile and stepped by one channel stride each time, so that the channel loop carries no
+        // 64-bit multiplications.
+        const int64_t tl = toff + l0;
+        const IO *n_u = reinterpret_cast<const IO *>(p.u) + bs * p.u_sb + d0 * p.u_sd + tl;
+        const IO *n_dl = reinterpret_cast<const IO *>(p.delta) + bs * p.dl_sb + d0 * p.dl_sd + tl;
+        const IO *n_dy = reinterpret_cast<const IO *>(p.dy) + bs * p.dy_sb + d0 * p.dy_sd + tl;
+        const IO *n_z = has_z ? reinterpret_cast<const IO *>(p.z) + bs * p.z_sb + d0 * p.z_sd + tl : n_dy;
+        const int64_t z_step = has_z ? p.z_sd : p.dy_sd;
+        IO *o_du_row = reinterpret_cast<IO *>(p.du) + bs * p.du_sb + d0 * p.du_sd + tl;
+        IO *o_dd_row = reinterpret_cast<IO *>(p.ddelta) + bs * p.dd_sb + d0 * p.dd_sd + tl;
+        IO *o_dz_row = DZ ? reinterpret_cast<IO *>(p.dz) + bs * p.dz_sb + d0 * p.dz_sd + tl : nullptr;
+        const float *n_A = p.A + (int64_t)d0 * N + w * NK;
+        const int64_t ck_stride = nck * N;                              // floats between the checkpoints of two channels
+        const float *n_ck = p.ckpt + ((p.cu ? (int64_t)d0 : (int64_t)b * p.D + d0) * nck + ck0 + tile * CK_PER_TILE) * N + w * NK;
+        const bool has_D = p.Dskip != nullptr, has_bias = p.bias != nullptr;
+        const float *n_Dsk = has_D ? p.Dskip + d0 : p.A, *n_bias = has_bias ? p.bias + d0 : p.A;
+        int n_left = Gact - 1;                                           // channels after the one the pointers are on
+        auto prefetch = [&](Pref &s) {
             if (io_thread) {
-                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.u) + bs * p.u_sb + d * p.u_sd + toff + l0, f0, rem, vec, r_u);
-                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.delta) + bs * p.dl_sb + d * p.dl_sd + toff + l0, f0, rem, vec, r_dl);
-                load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.dy) + bs * p.dy_sb + d * p.dy_sd + toff + l0, f0, rem, vec, r_dy);
-                if (has_z) load_few_raw<IO, TPW>(reinterpret_cast<const IO *>(p.z) + bs * p.z_sb + d * p.z_sd + toff + l0, f0, rem, vec, r_z);
+                load_few_raw<IO, TPW>(n_u, f0, rem, vec, s.u);
+                load_few_raw<IO, TPW>(n_dl, f0, rem, vec, s.dl);
+                load_few_raw<IO, TPW>(n_dy, f0, rem, vec, s.dy);
+                load_few_raw<IO, TPW>(n_z, f0, rem, vec, s.z);
             }
 #pragma unroll
-            for (int k = 0; k < NK; ++k) {
-                pA[k] = p.A[d * N + w * NK + k];
-                pck[k] = p.ckpt[((p.cu ? (int64_t)d : row) * nck + ck0 + tile * CK_PER_TILE) * N + w * NK + k];
-            }
-            pDsk = p.Dskip ? p.Dskip[d] : 0.0f;
-            pbias = p.bias ? p.bias[d] : 0.0f;
+            for (int k = 0; k < NK; ++k) { s.A[k] = n_A[k]; s.ck[k] = n_ck[k]; }
+            s.Dsk = *n_Dsk;
+            s.bias = *n_bias;
+            const bool more = n_left > 0;                                // else stay on the last channel
+            n_left -= more ? 1 : 0;
+            n_u += more ? p.u_sd : 0; n_dl += more ? p.dl_sd : 0; n_dy += more ? p.dy_sd : 0; n_z += more ? z_step : 0;
+            n_A += more ? N : 0; n_ck += more ? ck_stride : 0;
+            n_Dsk += (more && has_D) ? 1 : 0; n_bias += (more && has_bias) ? 1 : 0;
         };
-        prefetch(0);
+        prefetch(S0);
 
-        for (int g = 0; g < Gact; ++g) {
+        auto channel = [&](const int g, Pref &pf) {
             if constexpr (ALT_PRIO) {
                 if ((unsigned)(g & 1) == hw_slot) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
             }
-            const int d = d0 + g;
-            const float Dsk = pDsk, bias = pbias;
+            const float Dsk = has_D ? pf.Dsk : 0.0f, bias = has_bias ? pf.bias : 0.0f;
             float cA[NK], cck[NK];
 #pragma unroll
-            for (int k = 0; k < NK; ++k) { cA[k] = pA[k]; cck[k] = pck[k]; }
+            for (int k = 0; k < NK; ++k) { cA[k] = pf.A[k]; cck[k] = pf.ck[k]; }
 
             // ---- prologue: each thread prepares TPW flat steps for everybody
             // kept for the epilogue: d softplus / ds, and the factor that turns ypre into dz
             float e_sg[TPW], e_zf[TPW];
             if (io_thread) {
                 float e_u[TPW], r_d[TPW], e_dy[TPW], e_z[TPW];
-                unpack_few<IO, TPW>(r_u, e_u);
-                unpack_few<IO, TPW>(r_dl, r_d);
-                unpack_few<IO, TPW>(r_dy, e_dy);
-                if (has_z) unpack_few<IO, TPW>(r_z, e_z);
+                unpack_few<IO, TPW>(pf.u, e_u);
+                unpack_few<IO, TPW>(pf.dl, r_d);
+                unpack_few<IO, TPW>(pf.dy, e_dy);
+                unpack_few<IO, TPW>(pf.z, e_z);
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) {
                     float sp, dyp;
@@ -196,7 +223,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 }
             }
             __syncthreads();
-            if (g + 1 < Gact) prefetch(g + 1);
+            prefetch(pf);                            // this set's values are consumed or copied: refill it for the next channel
 
             // ---- main: this lane's T steps, this wavefront's NK states
             float dl[T], dyp[T], dlu[T], ypre[T], pdu[T], pdd[T];
@@ -209,99 +236,111 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 dlu[4 * q] = v1.x; dlu[4 * q + 1] = v1.y; dlu[4 * q + 2] = v1.z; dlu[4 * q + 3] = v1.w;   // u for now
                 dyp[4 * q] = v2.x; dyp[4 * q + 1] = v2.y; dyp[4 * q + 2] = v2.z; dyp[4 * q + 3] = v2.w;
             }
-            float sum_dl = 0.0f;
 #pragma unroll
-            for (int t = 0; t < T; ++t) {
-                sum_dl += dl[t];
+            for (int t = 0; t < T; ++t)
                 if constexpr (DISC == DISC_ZOH_S6) dlu[t] *= dl[t];   // S6 only ever needs Delta*u; the others keep u
-                ypre[t] = 0.0f; pdu[t] = 0.0f; pdd[t] = 0.0f;
-            }
-            const float dl_next0 = dpp<DPP_WAVE_SHL1>(0.0f, dl[0]);        // first Delta of the next lane (0 past lane 63)
-            const float sum_shift = sum_dl - dl[0] + dl_next0;
 
             float dA4[NK];
 #pragma unroll
-            for (int k = 0; k < NK; ++k) {
+            for (int k0 = 0; k0 < NK; k0 += JS) {
+            // ---- phase 1: forward fold (states) and backward fold (adjoint) of this lane's T steps, JS states at a time
+            float a[NK][T + 1], gg[NK][T], x[NK][T], cdy[NK][T];
+            float P[NK], S[NK], Pr[NK], Sr[NK], hcv[NK];
+            ACoef acs[NK];
+#pragma unroll
+            for (int k = k0; k < k0 + JS; ++k) {
                 const int n = w * NK + k;
                 const ACoef ac = make_acoef<DISC>(cA[k]);
+                acs[k] = ac;
                 const float xck = cck[k];
                 const float hc = sH[g * N + n];
+                hcv[k] = hc;
                 float Bk[T];
 #pragma unroll
                 for (int q = 0; q < TQ; ++q) {
                     const float4 vb = *reinterpret_cast<const float4 *>(&sBt[((n * TQ + q) * 64 + lane) * 4]);
                     Bk[4 * q] = vb.x; Bk[4 * q + 1] = vb.y; Bk[4 * q + 2] = vb.z; Bk[4 * q + 3] = vb.w;
                 }
-
-                // forward recompute of the states of this tile
-                float a[T + 1], gg[T], x[T];
-                float P = 1.0f, S = 0.0f;
+                float sx = 0.0f;
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
-                    disc_ag<DISC>(dl[t], ac, a[t], gg[t]);
-                    if constexpr (DISC == DISC_ZOH_S6) x[t] = dlu[t] * Bk[t];
-                    else if constexpr (DISC == DISC_DIRAC) x[t] = dlu[t] * Bk[t];
-                    else x[t] = gg[t] * dlu[t] * Bk[t];
-                    S = (t == 0) ? x[0] : __builtin_fmaf(a[t], S, x[t]);     // the fold starts from zero
-                    if constexpr (DISC == DISC_BILINEAR) P *= a[t];
+                    disc_ag<DISC>(dl[t], ac, a[k][t], gg[k][t]);
+                    if constexpr (DISC == DISC_ZOH_S6) x[k][t] = dlu[t] * Bk[t];
+                    else if constexpr (DISC == DISC_DIRAC) x[k][t] = dlu[t] * Bk[t];
+                    else x[k][t] = gg[k][t] * dlu[t] * Bk[t];
+                    sx = (t == 0) ? x[k][0] : __builtin_fmaf(a[k][t], sx, x[k][t]);   // the fold starts from zero
                 }
-                if constexpr (DISC != DISC_BILINEAR) P = exp2_fast(sum_dl * ac.A2);
-                if (lane == 0) S = __builtin_fmaf(P, xck, S);               // the checkpointed state enters through lane 0
+                // products of the multipliers of this lane's steps (state prefix) and of the same steps shifted by one
+                // (adjoint suffix: H_l = c_l + a_{l+1} H_{l+1}; the multiplier after the tile's last step is 1 because
+                // the carried value is already a_{l1} H_{l1}).  The inner factors are shared.
+                a[k][T] = dpp<DPP_WAVE_SHL1>(1.0f, a[k][0]);
+                float inner = a[k][1];
+#pragma unroll
+                for (int t = 2; t < T; ++t) inner *= a[k][t];
+                const float p = a[k][0] * inner, pr = inner * a[k][T];
+                if (lane == 0) sx = __builtin_fmaf(p, xck, sx);             // the checkpointed state enters through lane 0
+                P[k] = p; S[k] = sx;
 
-                // lane aggregate of the adjoint H_l = c_l + a_{l+1} H_{l+1}; the multiplier of the tile's last step is 1
-                // because the carried value is already a_{l1} H_{l1}
-                a[T] = dpp<DPP_WAVE_SHL1>(1.0f, a[0]);
-                float Pr = 1.0f, Sr = 0.0f;
+                float sr = 0.0f;
 #pragma unroll
                 for (int t = T - 1; t >= 0; --t) {
-                    Sr = (t == T - 1) ? Cv[k][t] * dyp[t] : __builtin_fmaf(a[t + 1], Sr, Cv[k][t] * dyp[t]);
-                    if constexpr (DISC == DISC_BILINEAR) Pr *= a[t + 1];
+                    cdy[k][t] = Cv[k][t] * dyp[t];
+                    sr = (t == T - 1) ? cdy[k][t] : __builtin_fmaf(a[k][t + 1], sr, cdy[k][t]);
                 }
-                if constexpr (DISC != DISC_BILINEAR) Pr = exp2_fast(sum_shift * ac.A2);
-                if (lane == 63) Sr = __builtin_fmaf(Pr, hc, Sr);            // the carried adjoint enters through lane 63
-
-                // state prefix (forward in time) and adjoint suffix (backward in time) are independent: scanned together
-                wave_scan_fwd_rev(P, S, Pr, Sr, lane);
-                const float xin = dpp<DPP_WAVE_SHR1>(xck, S);               // x entering this lane's first step
+                if (lane == 63) sr = __builtin_fmaf(pr, hc, sr);            // the carried adjoint enters through lane 63
+                Pr[k] = pr; Sr[k] = sr;
+            }
+            // ---- phase 2: state prefixes (forward in time) and adjoint suffixes (backward in time) of these JS states
+            wave_scan_fwd_rev_multi<JS>(P + k0, S + k0, Pr + k0, Sr + k0, lane);
+            // ---- phase 3: replay of the states and of the adjoint, gradients
+#pragma unroll
+            for (int k = k0; k < k0 + JS; ++k) {
+                const int n = w * NK + k;
+                const ACoef ac = acs[k];
+                float Bk[T];
+#pragma unroll
+                for (int q = 0; q < TQ; ++q) {
+                    const float4 vb = *reinterpret_cast<const float4 *>(&sBt[((n * TQ + q) * 64 + lane) * 4]);
+                    Bk[4 * q] = vb.x; Bk[4 * q + 1] = vb.y; Bk[4 * q + 2] = vb.z; Bk[4 * q + 3] = vb.w;
+                }
+                const float xin = dpp<DPP_WAVE_SHR1>(cck[k], S[k]);         // x entering this lane's first step
                 {
                     float xp = xin;
 #pragma unroll
-                    for (int t = 0; t < T; ++t) { xp = __builtin_fmaf(a[t], xp, x[t]); x[t] = xp; }
+                    for (int t = 0; t < T; ++t) { xp = __builtin_fmaf(a[k][t], xp, x[k][t]); x[k][t] = xp; }
                 }
-                const float H0 = Sr;                                        // H of this lane's first step
-                float R = dpp<DPP_WAVE_SHL1>(hc, Sr);                       // H of the next lane's first step (the carry itself past lane 63)
-                if (lane == 0) sH[g * N + n] = a[0] * H0;                   // carried to the earlier tile
+                const float H0 = Sr[k];                                     // H of this lane's first step
+                float R = dpp<DPP_WAVE_SHL1>(hcv[k], Sr[k]);                // H of the next lane's first step (the carry itself past lane 63)
+                if (lane == 0) sH[g * N + n] = a[k][0] * H0;                // carried to the earlier tile
 
                 float dA_part = 0.0f;                                       // this lane's share of dA[d, n]
 #pragma unroll
                 for (int t = T - 1; t >= 0; --t) {
-                    R = __builtin_fmaf(a[t + 1], R, Cv[k][t] * dyp[t]);       // H_t (the product is recomputed: registers are scarcer than VALU slots here)
-                    const float xprev = (t > 0) ? x[t - 1] : xin;
-                    dCacc[k][t] = __builtin_fmaf(dyp[t], x[t], dCacc[k][t]);
-                    ypre[t] = __builtin_fmaf(Cv[k][t], x[t], ypre[t]);
-                    if constexpr (DISC == DISC_ZOH_S6) {
-                        pdu[t] = __builtin_fmaf(R, Bk[t], pdu[t]);       // sum_n H B; scaled by Delta resp. u in the epilogue
+                    R = __builtin_fmaf(a[k][t + 1], R, cdy[k][t]);            // H_t
+                    const float xprev = (t > 0) ? x[k][t - 1] : xin;
+                    dCacc[k][t] = __builtin_fmaf(dyp[t], x[k][t], dCacc[k][t]);
+                    if constexpr (DZ) ypre[t] = (k == 0) ? Cv[k][t] * x[k][t] : __builtin_fmaf(Cv[k][t], x[k][t], ypre[t]);
+                    // the first state of the wavefront starts the sums over n (pdu, pdd), the others add to them
+                    auto acc = [&](float &sum, float m1, float m2) { sum = (k == 0) ? m1 * m2 : __builtin_fmaf(m1, m2, sum); };
+                    if constexpr (DISC == DISC_ZOH_S6 || DISC == DISC_DIRAC) {
+                        // S6: g = Delta (du and dDelta share sum_n H B, scaled in the epilogue); dirac: g = 1, and only
+                        // a = e^{Delta A} depends on Delta and A
+                        acc(pdu[t], R, Bk[t]);
                         dBacc[k][t] = __builtin_fmaf(R, dlu[t], dBacc[k][t]);
-                        const float q = R * xprev * a[t];
-                        pdd[t] = __builtin_fmaf(q, ac.A, pdd[t]);
-                        dA_part = __builtin_fmaf(q, dl[t], dA_part);
-                    } else if constexpr (DISC == DISC_DIRAC) {
-                        // g = 1: only a = e^{Delta A} depends on Delta and A
-                        pdu[t] = __builtin_fmaf(R, Bk[t], pdu[t]);
-                        dBacc[k][t] = __builtin_fmaf(R, dlu[t], dBacc[k][t]);
-                        const float q = R * xprev * a[t];
-                        pdd[t] = __builtin_fmaf(q, ac.A, pdd[t]);
+                        const float q = R * xprev * a[k][t];
+                        acc(pdd[t], q, ac.A);
                         dA_part = __builtin_fmaf(q, dl[t], dA_part);
                     } else if constexpr (DISC == DISC_ZOH) {
                         // da/dDelta = A a, da/dA = Delta a, dg/dDelta = a: the common factor a is taken out
                         float a_t, a_A, g_t, g_A;
-                        disc_partials<DISC>(dl[t], ac, a[t], gg[t], a_t, a_A, g_t, g_A);
+                        disc_partials<DISC>(dl[t], ac, a[k][t], gg[k][t], a_t, a_A, g_t, g_A);
                         const float hb = R * Bk[t];
                         const float dg = hb * dlu[t];
-                        const float dax = R * a[t] * xprev;                  // H x_{l-1} a
-                        pdu[t] = __builtin_fmaf(hb, gg[t], pdu[t]);
-                        dBacc[k][t] = __builtin_fmaf(R * gg[t], dlu[t], dBacc[k][t]);
-                        pdd[t] = __builtin_fmaf(dax, ac.A, __builtin_fmaf(dg, a[t], pdd[t]));
+                        const float dax = R * a[k][t] * xprev;               // H x_{l-1} a
+                        acc(pdu[t], hb, gg[k][t]);
+                        dBacc[k][t] = __builtin_fmaf(R * gg[k][t], dlu[t], dBacc[k][t]);
+                        if (k == 0) pdd[t] = __builtin_fmaf(dax, ac.A, dg * a[k][t]);
+                        else pdd[t] = __builtin_fmaf(dax, ac.A, __builtin_fmaf(dg, a[k][t], pdd[t]));
                         dA_part = __builtin_fmaf(dax, dl[t], __builtin_fmaf(dg, g_A, dA_part));
                     } else {
                         // bilinear: with q = 1 / (1 - Delta A / 2) all four partials are multiples of q^2
@@ -310,9 +349,9 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                         const float da = R * xprev;
                         const float hb = R * Bk[t];
                         const float dg = hb * dlu[t];
-                        pdu[t] = __builtin_fmaf(hb, gg[t], pdu[t]);
-                        dBacc[k][t] = __builtin_fmaf(R * gg[t], dlu[t], dBacc[k][t]);
-                        pdd[t] = __builtin_fmaf(__builtin_fmaf(da, ac.A, dg), q2, pdd[t]);                       // A q^2 da + q^2 dg
+                        acc(pdu[t], hb, gg[k][t]);
+                        dBacc[k][t] = __builtin_fmaf(R * gg[k][t], dlu[t], dBacc[k][t]);
+                        acc(pdd[t], __builtin_fmaf(da, ac.A, dg), q2);                                            // A q^2 da + q^2 dg
                         dA_part = __builtin_fmaf(__builtin_fmaf(0.5f * dl[t], dg, da) * dl[t], q2, dA_part);     // Delta q^2 da + Delta^2 q^2 dg / 2
                     }
                 }
@@ -323,6 +362,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                     if (lane == 0) sdA[0][g * N + n] += dA_tot;
                 }
             }
+            }   // groups of JS states
             if constexpr (NK == 4) {
                 // The four per-lane partial sums are reduced together: two exchange steps leave each lane of a quad
                 // with the quad's sum of ONE state (lane%4 = 0,1,2,3 -> state 0,2,1,3), two rotations sum the quads of
@@ -352,12 +392,11 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
 #pragma unroll
             for (int q = 0; q < TQ; ++q) {
                 float *base = &sPart[(w * 3) * TILE + (q * 64 + lane) * 4];
-                *reinterpret_cast<float4 *>(base) = make_float4(ypre[4 * q], ypre[4 * q + 1], ypre[4 * q + 2], ypre[4 * q + 3]);
+                if constexpr (DZ) *reinterpret_cast<float4 *>(base) = make_float4(ypre[4 * q], ypre[4 * q + 1], ypre[4 * q + 2], ypre[4 * q + 3]);
                 *reinterpret_cast<float4 *>(base + TILE) = make_float4(pdu[4 * q], pdu[4 * q + 1], pdu[4 * q + 2], pdu[4 * q + 3]);
                 *reinterpret_cast<float4 *>(base + 2 * TILE) = make_float4(pdd[4 * q], pdd[4 * q + 1], pdd[4 * q + 2], pdd[4 * q + 3]);
             }
             __syncthreads();
-
             // ---- epilogue: the threads share the tile in flat order
             if (io_thread) {
                 float o_du[TPW], o_dd[TPW], o_dz[TPW];
@@ -368,7 +407,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                     float yp = Dsk * e_u, s_du = 0.0f, s_dd = 0.0f;
 #pragma unroll
                     for (int ww = 0; ww < W; ++ww) {
-                        yp += sPart[(ww * 3 + 0) * TILE + fslot(f0 + i)];
+                        if constexpr (DZ) yp += sPart[(ww * 3 + 0) * TILE + fslot(f0 + i)];
                         s_du += sPart[(ww * 3 + 1) * TILE + fslot(f0 + i)];
                         s_dd += sPart[(ww * 3 + 2) * TILE + fslot(f0 + i)];
                     }
@@ -383,9 +422,9 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                     dD_part = __builtin_fmaf(e_dyp, e_u, dD_part);
                     db_part += (f0 + i < rem) ? o_dd[i] : 0.0f;
                 }
-                store_few<IO, TPW>(reinterpret_cast<IO *>(p.du) + bs * p.du_sb + d * p.du_sd + toff + l0, f0, rem, vec, o_du);
-                store_few<IO, TPW>(reinterpret_cast<IO *>(p.ddelta) + bs * p.dd_sb + d * p.dd_sd + toff + l0, f0, rem, vec, o_dd);
-                if (p.dz) store_few<IO, TPW>(reinterpret_cast<IO *>(p.dz) + bs * p.dz_sb + d * p.dz_sd + toff + l0, f0, rem, vec, o_dz);
+                store_few<IO, TPW>(o_du_row, f0, rem, vec, o_du);
+                store_few<IO, TPW>(o_dd_row, f0, rem, vec, o_dd);
+                if constexpr (DZ) store_few<IO, TPW>(o_dz_row, f0, rem, vec, o_dz);
                 // joint reduction of the two per-lane sums: one exchange leaves even lanes with dD and odd lanes with
                 // dbias pair sums, then lanes of equal parity are summed over the half-wavefront (lanes 0,1 / 32,33)
                 const bool odd = lane & 1;
@@ -397,8 +436,10 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 v += i2f(__builtin_amdgcn_ds_swizzle(f2i(v), 0x401F));      // lane ^ 16
                 if ((lane & 0x1E) == 0) (odd ? sdb : sdD)[((lane >> 5) * W + w) * kMaxG + g] += v;
             }
-        }
-
+            o_du_row += p.du_sd; o_dd_row += p.dd_sd;
+            if constexpr (DZ) o_dz_row += p.dz_sd;
+        };
+        for (int g = 0; g < Gact; ++g) channel(g, S0);
         // ---- add this tile's dBm/dCm sums (over the G channels) to global memory, transposed through LDS
         // so that consecutive threads hit consecutive addresses
         float *fbB = sPart, *fbC = sPart + 16 * T * N;
@@ -425,7 +466,6 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
         }
         __syncthreads();
     }
-
     // ---- per-channel results of this workgroup
     for (int i = tid; i < Gact * N; i += NT) {
         const int g = i / N, n = i % N;
@@ -477,10 +517,12 @@ BwdPlan bwd_plan(int rowsg, int dpg, int N, int64_t L, int mode, bool balanced) 
     return plan_time_chunks(rowsg, dpg, L, balanced ? mode : 1, G, 2048 / bwd_waves_per_workgroup(N), kMaxG);
 }
 
+// DZ (the caller wants dz) is a template parameter: without it the kernel does not rebuild ypre = sum_n C x
 template <typename IO, int N, int NK, int DISC, int T = 8>
 static hipError_t launch_bwd_n(const BwdParams &p, hipStream_t s) {
     dim3 grid(p.bcg * ((p.dpg + p.G - 1) / p.G), p.B, p.nchunks > 1 ? p.nchunks : 1);
-    hipLaunchKernelGGL((k_ss_bwd<IO, N, NK, T, DISC>), grid, dim3((N / NK) * 64), 0, s, p);
+    if (p.dz) hipLaunchKernelGGL((k_ss_bwd<IO, N, NK, T, DISC, true>), grid, dim3((N / NK) * 64), 0, s, p);
+    else hipLaunchKernelGGL((k_ss_bwd<IO, N, NK, T, DISC, false>), grid, dim3((N / NK) * 64), 0, s, p);
     return hipGetLastError();
 }
 
