@@ -35,9 +35,36 @@ HBM_PEAK_GBS = 8000.0
 # fp32 vector peak counts an FMA as two flops and a packed instruction as two more
 VALU_PEAK_TLANEOPS = 39.3
 
-# measured HBM traffic of the backward kernel on config 2 (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
-# copy kernel of known size); filled from profiles/ when a counter run exists, else null
-BWD_TRAFFIC_BYTES = 509.2e6   # 223.1 MB read + 286.1 MB written (profiles/config2_fwd_bwd_hbm_traffic.md)
+# Measured HBM traffic of the backward kernel on config 2 comes from the counter summary under profiles/ (rocprofv3
+# --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size).  The summary names the sources of the kernel
+# it was taken on by a hash; if they have changed since, the figure is stale and `traffic` is null.
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "config2_fwd_bwd_hbm_traffic.md")
+KERNEL_SOURCES = [os.path.join(ROOT, "paper_2602_08810_amd", "csrc", f)
+                  for f in ("selective_bwd.hip", "scan_common.hpp", "kernels.hpp")]
+
+
+def kernel_source_hash():
+    import hashlib
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES:
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic():
+    """(bytes per launch or None, note) from the machine-readable line of the counter summary."""
+    import re
+    try:
+        text = open(TRAFFIC_SUMMARY).read()
+    except OSError:
+        return None, "no counter summary"
+    m = re.search(r"bwd_traffic_bytes_per_launch\s*=\s*(\d+)\s*;\s*kernel_source_hash\s*=\s*([0-9a-f]+)", text)
+    if not m:
+        return None, "counter summary has no traffic line"
+    if m.group(2) != kernel_source_hash():
+        return None, f"stale: counters were taken on kernel sources {m.group(2)}, this tree has {kernel_source_hash()}"
+    return int(m.group(1)), "profiles/config2_fwd_bwd_hbm_traffic.md"
 
 
 def _selective_bytes(B, D, N, L, es, gate, bwd):
@@ -54,7 +81,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=90)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--repeats", type=int, default=1, help="experiments of --steps steps (mean/std over their means)")
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="experiments of --steps steps each (the paper's protocol, Sec. 4.2: mean and std over the "
+                         "experiments' means); the timed region is --repeats x --steps steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quick", action="store_true", help="skip the other configs")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -109,6 +138,14 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # what a plain device copy reaches on this machine (1 GiB read + 1 GiB written, far beyond the Infinity Cache): the
+    # practical ceiling next to the 8 TB/s data-sheet peak
+    src = torch.zeros(256 * 1024 * 1024, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    copy_t = _time(torch, lambda: dst.copy_(src), 10)
+    copy_ceiling = 2 * src.numel() * 4 / copy_t / 1e9
+    del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -140,16 +177,24 @@ def main():
 
     fwd_bytes = _selective_bytes(B, D, N, L, 2, True, False) + ckpt.numel() * 4
     bwd_bytes = _selective_bytes(B, D, N, L, 2, True, True) + ckpt.numel() * 4
+    traffic, traffic_note = measured_traffic()
     roofline = {"bound": "hbm", "kernel": "k_ss_bwd<bf16,N=16> (config 2 backward)",
                 "achieved": bwd_bytes / bwd_t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": bwd_bytes / bwd_t / 1e9 / HBM_PEAK_GBS, "traffic": BWD_TRAFFIC_BYTES,
-                "algorithmic_bytes": bwd_bytes, "avg_launch_us": bwd_t * 1e6}
-    # algorithmic VALU work of the backward pass per element: state recompute (3 fp32 + 1 exponential = 2 issue
-    # slots), adjoint recurrence (2), gradient terms (8) = 15 issue slots; scans, softplus and gate not counted
-    bwd_ops = elements * 15.0
-    roofline_alu = {"bound": "alu", "kernel": roofline["kernel"], "achieved": bwd_ops / bwd_t / 1e12,
-                    "peak": VALU_PEAK_TLANEOPS, "unit": "T lane-instr/s",
-                    "frac": bwd_ops / bwd_t / 1e12 / VALU_PEAK_TLANEOPS, "ops_per_element": 15.0}
+                "frac": bwd_bytes / bwd_t / 1e9 / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_note,
+                "algorithmic_bytes": bwd_bytes, "avg_launch_us": bwd_t * 1e6,
+                "copy_ceiling_GBs": copy_ceiling, "frac_of_copy_ceiling": bwd_bytes / bwd_t / 1e9 / copy_ceiling}
+    # Algorithmic VALU work per element.  Backward: state recompute (3 fp32 instructions + 1 exponential = 2 issue
+    # slots), adjoint recurrence (2), gradient terms (8) = 15 issue slots, 24 flops (an FMA counts two).  Forward:
+    # multiplier (1 + exponential 2), input term (1), state update (1), projection (1) = 6 slots, 8 flops.  Scans,
+    # softplus and gate are not counted.  Peaks: 39.3e12 plain lane-instructions/s; in flops 78.6 TFLOP/s for FMA
+    # streams without the packed forms (switched off on this pool), which is half the published 157.3.
+    def alu(ops, flops, t_s, kernel):
+        return {"bound": "alu", "kernel": kernel, "achieved": elements * ops / t_s / 1e12, "peak": VALU_PEAK_TLANEOPS,
+                "unit": "T lane-instr/s", "frac": elements * ops / t_s / 1e12 / VALU_PEAK_TLANEOPS, "ops_per_element": ops,
+                "achieved_TFLOPs": elements * flops / t_s / 1e12, "peak_TFLOPs_unpacked": 78.6, "peak_TFLOPs_published": 157.3,
+                "flops_per_element": flops}
+    roofline_alu = alu(15.0, 24.0, bwd_t, roofline["kernel"])
+    roofline_alu_fwd = alu(6.0, 8.0, fwd_t, "k_ss_fwd<bf16,N=16> (config 2 forward)")
 
     result = {
         "metric": "scan elements/s (B*L*D*N) fwd & bwd", "value": value, "unit": "elements/s",
@@ -163,8 +208,11 @@ def main():
                 "hbm_frac": fwd_bytes / fwd_t / 1e9 / HBM_PEAK_GBS},
         "bwd": {"us": bwd_t * 1e6, "elements_per_s": elements / bwd_t, "hbm_GBs": bwd_bytes / bwd_t / 1e9,
                 "hbm_frac": bwd_bytes / bwd_t / 1e9 / HBM_PEAK_GBS},
-        "roofline": roofline, "roofline_alu": roofline_alu,
+        "roofline": roofline, "roofline_alu": roofline_alu, "roofline_alu_fwd": roofline_alu_fwd,
+        "copy_ceiling_GBs": copy_ceiling,
     }
+    for k in ("fwd", "bwd"):
+        result[k]["frac_of_copy_ceiling"] = result[k]["hbm_GBs"] / copy_ceiling
 
     # ------------------------------------------------------------------ the other configs (context, not `value`)
     if not args.quick:
@@ -367,8 +415,7 @@ def _other_configs(api, torch, dev):
     tb = _time(torch, lambda: api.lrnnx_selective_scan_bwd(**pk, dy=dyp, cu_seqlens=cu, ckpt=ckp, outs=outs_p), 10)
     out["packed_24seq_D1536_L16384"] = {"fwd_us": tf * 1e6, "bwd_us": tb * 1e6,
                                         "elements_per_s": 2 * Dp * Np * Lp / (tf + tb),
-                                        "note": "same total size as config 2; sequence starts are not 16-byte aligned, "
-                                                "so rows are read element by element"}
+                                        "note": "same total size as config 2"}
     del tp, pk, dyp, yp, ckp, outs_p
 
     # config 3: long-sequence forward, both paths
@@ -393,6 +440,23 @@ def _other_configs(api, torch, dev):
                                        "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS,
                                        "chunks": int(api.lib().lrnnx_selective_scan_bwd_chunks(B3, D3, N3, L3, 1, api.PATH[path], 0))}
     del t3, y3, ws3, dy3, ck3, outs3
+
+    # config 2's shape with float32 I/O (the float32 kernels differ: no Bm/Cm row prefetch in the forward pass)
+    Bf, Df, Nf, Lf = 8, 1536, 16, 2048
+    tf32 = {k: (v.float() if (v is not None and v.dtype == bf) else v) for k, v in sel(Bf, Df, Nf, Lf, True).items()}
+    dyf = torch.randn(Bf, Df, Lf, device=dev, generator=g)
+    yf = torch.empty_like(tf32["u"])
+    _, ckf = api.lrnnx_selective_scan_fwd(**tf32, out=yf, return_ckpt=True)
+    outs_f = {}
+    tt = _time(torch, lambda: api.lrnnx_selective_scan_fwd(**tf32, out=yf, ckpt_out=ckf), 10)
+    nb = _selective_bytes(Bf, Df, Nf, Lf, 4, True, False) + ckf.numel() * 4
+    out["c2_shape_f32io_fwd"] = {"us": tt * 1e6, "elements_per_s": Bf * Df * Nf * Lf / tt, "hbm_GBs": nb / tt / 1e9,
+                                 "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
+    tt = _time(torch, lambda: outs_f.update(api.lrnnx_selective_scan_bwd(**tf32, dy=dyf, ckpt=ckf, outs=outs_f)), 10)
+    nb = _selective_bytes(Bf, Df, Nf, Lf, 4, True, True) + ckf.numel() * 4
+    out["c2_shape_f32io_bwd"] = {"us": tt * 1e6, "elements_per_s": Bf * Df * Nf * Lf / tt, "hbm_GBs": nb / tt / 1e9,
+                                 "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
+    del tf32, dyf, yf, ckf, outs_f
 
     # config 4: backward only (checkpoints from one untimed forward)
     B4, D4, N4, L4 = 16, 2560, 16, 4096

@@ -97,10 +97,8 @@ int64_t lrnnx_packed_ckpt_slots(int64_t L, int64_t B);
  * nothing crosses a boundary; steps outside every sequence are not touched).  u, delta, z, y are then [D,L] (the
  * batch strides are ignored), Bm and Cm [G,L,N], x0 and x_last [B,D,N], and ckpt is
  * [D, lrnnx_packed_ckpt_slots(L,B), N].  Boundaries are clamped to [0,L] on the device; the single-pass path
- * is used (LRNNX_PATH_CHUNK_CARRY is refused).  A sequence whose first step is a multiple of 8 steps into the packed
- * axis is read and written with 16-byte accesses like an unpacked row; any other start is correct too but takes the
- * element-by-element path (forward about 30 % slower, backward a few per cent), so pad sequences to multiples of 8
- * steps where the rate matters.
+ * is used (LRNNX_PATH_CHUNK_CARRY is refused).  Sequences may start anywhere: rows are read and written with vector
+ * accesses at element alignment.
  * workspace is needed only by LRNNX_PATH_CHUNK_CARRY (AUTO falls back to the single
  * pass when it is missing or too small).                                              */
 typedef struct lrnnx_ss_fwd_args {

@@ -17,9 +17,10 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t elem_size(int io) { return io == LRNNX_BF16 ? 2 : 4; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// 16-byte vector access to a [B,D,L] tensor is possible when every row start is 16-byte aligned.
-inline bool row_vec_ok(const void *p, int64_t sb, int64_t sd, size_t es) {
-    return aligned16(p) && (sb * (int64_t)es) % 16 == 0 && (sd * (int64_t)es) % 16 == 0;
+// Vector access to the time axis of a [B,D,L] tensor needs element alignment only (the kernels tell the compiler so
+// and global memory takes unaligned vector accesses); strides are counted in elements, so the base decides.
+inline bool row_vec_ok(const void *p, int64_t, int64_t, size_t es) {
+    return (reinterpret_cast<uintptr_t>(p) & (es - 1)) == 0;
 }
 
 // Number of time chunks of the chunk-carry forward path.

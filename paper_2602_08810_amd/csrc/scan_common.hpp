@@ -408,8 +408,23 @@ template <> struct io_traits<bf16_t> {
     }
 };
 
-// A lane's CNT consecutive elements row[l .. l+CNT), zero where l+i >= L.  `vec` says that
-// row + l is 16-byte aligned whenever l is a multiple of EPC (checked on the host).
+// 16-, 8- and 4-byte accesses to the time axis of a [B,D,L] tensor are made at ELEMENT alignment: rows of packed
+// variable-length batches start anywhere, and global memory takes unaligned vector accesses (the compiler is told
+// the true alignment and still emits one instruction).  IO selects the alignment (2 or 4 bytes).
+template <typename IO> struct ua;
+template <> struct ua<float> {
+    typedef uint4 __attribute__((aligned(4))) v4;
+    typedef uint2 __attribute__((aligned(4))) v2;
+    typedef uint32_t __attribute__((aligned(4))) v1;
+};
+template <> struct ua<bf16_t> {
+    typedef uint4 __attribute__((aligned(2))) v4;
+    typedef uint2 __attribute__((aligned(2))) v2;
+    typedef uint32_t __attribute__((aligned(2))) v1;
+};
+
+// A lane's CNT consecutive elements row[l .. l+CNT), zero where l+i >= L.  `vec` allows vector accesses (the host
+// sets it when every row pointer is element-aligned).
 template <typename IO, int CNT>
 __device__ __forceinline__ void load_seg(const IO *row, int64_t l, int64_t L, bool vec, float *out) {
     constexpr int EPC = io_traits<IO>::EPC;
@@ -418,7 +433,7 @@ __device__ __forceinline__ void load_seg(const IO *row, int64_t l, int64_t L, bo
     for (int c = 0; c < CNT / EPC; ++c) {
         int64_t lc = l + c * EPC;
         if (vec && lc + EPC <= L) {
-            uint4 r = *reinterpret_cast<const uint4 *>(row + lc);
+            uint4 r = *reinterpret_cast<const typename ua<IO>::v4 *>(row + lc);
             io_traits<IO>::unpack(r, out + c * EPC);
         } else {
 #pragma unroll
@@ -433,7 +448,7 @@ __device__ __forceinline__ void store_seg(IO *row, int64_t l, int64_t L, bool ve
     for (int c = 0; c < CNT / EPC; ++c) {
         int64_t lc = l + c * EPC;
         if (vec && lc + EPC <= L) {
-            *reinterpret_cast<uint4 *>(row + lc) = io_traits<IO>::pack(v + c * EPC);
+            *reinterpret_cast<typename ua<IO>::v4 *>(row + lc) = io_traits<IO>::pack(v + c * EPC);
         } else {
 #pragma unroll
             for (int i = 0; i < EPC; ++i) if (lc + i < L) io_traits<IO>::put(row, lc + i, v[c * EPC + i]);
@@ -471,17 +486,6 @@ __device__ __forceinline__ void load_row(const IO *p, float *out) {
     }
 }
 
-// CNT (1, 2, 4 or 8) consecutive elements row[l .. l+CNT) with zero fill past L; `vec` as in load_seg
-// (then row + l is aligned to CNT*sizeof(IO) bytes whenever l is a multiple of CNT).
-template <typename IO, int CNT>
-__device__ __forceinline__ void load_few(const IO *row, int64_t l, int64_t L, bool vec, float *out) {
-    if (vec && l + CNT <= L) {
-        load_row<IO, CNT>(row + l, out);
-    } else {
-#pragma unroll
-        for (int i = 0; i < CNT; ++i) out[i] = (l + i < L) ? io_traits<IO>::get(row, l + i) : 0.0f;
-    }
-}
 template <typename IO, int CNT, typename IDX>
 __device__ __forceinline__ void store_few(IO *row, IDX l, IDX L, bool vec, const float *v) {
     constexpr int EPC = io_traits<IO>::EPC;
@@ -491,14 +495,14 @@ __device__ __forceinline__ void store_few(IO *row, IDX l, IDX L, bool vec, const
     } else if (vec && l + CNT <= L && BYTES % 16 == 0) {
 #pragma unroll
         for (int c = 0; c < BYTES / 16; ++c)
-            reinterpret_cast<uint4 *>(row + l)[c] = io_traits<IO>::pack(v + c * EPC);
+            reinterpret_cast<typename ua<IO>::v4 *>(row + l)[c] = io_traits<IO>::pack(v + c * EPC);
     } else if (vec && l + CNT <= L && (BYTES == 8 || BYTES == 4)) {
         float tmp[EPC];
 #pragma unroll
         for (int i = 0; i < EPC; ++i) tmp[i] = i < CNT ? v[i] : 0.0f;
         uint4 r = io_traits<IO>::pack(tmp);
-        if constexpr (BYTES == 8) *reinterpret_cast<uint2 *>(row + l) = make_uint2(r.x, r.y);
-        else *reinterpret_cast<uint32_t *>(row + l) = r.x;
+        if constexpr (BYTES == 8) *reinterpret_cast<typename ua<IO>::v2 *>(row + l) = make_uint2(r.x, r.y);
+        else *reinterpret_cast<typename ua<IO>::v1 *>(row + l) = r.x;
     } else {
 #pragma unroll
         for (int i = 0; i < CNT; ++i) if (l + i < L) io_traits<IO>::put(row, l + i, v[i]);
@@ -527,14 +531,14 @@ __device__ __forceinline__ void load_few_raw(const IO *row, IDX l, IDX L, bool v
         if constexpr (BYTES % 16 == 0) {
 #pragma unroll
             for (int c = 0; c < BYTES / 16; ++c) {
-                const uint4 v = reinterpret_cast<const uint4 *>(row + l)[c];
+                const uint4 v = reinterpret_cast<const typename ua<IO>::v4 *>(row + l)[c];
                 r.w[4 * c] = v.x; r.w[4 * c + 1] = v.y; r.w[4 * c + 2] = v.z; r.w[4 * c + 3] = v.w;
             }
         } else if constexpr (BYTES == 8) {
-            const uint2 v = *reinterpret_cast<const uint2 *>(row + l);
+            const uint2 v = *reinterpret_cast<const typename ua<IO>::v2 *>(row + l);
             r.w[0] = v.x; r.w[1] = v.y;
         } else if constexpr (BYTES == 4) {
-            r.w[0] = *reinterpret_cast<const uint32_t *>(row + l);
+            r.w[0] = *reinterpret_cast<const typename ua<IO>::v1 *>(row + l);
         } else {
             r.w[0] = *reinterpret_cast<const unsigned short *>(row + l);
         }
@@ -556,6 +560,20 @@ __device__ __forceinline__ void unpack_few(const RawFew<IO, CNT> &r, float *out)
     for (int i = 0; i < CNT; ++i) {
         if constexpr (sizeof(IO) == 4) out[i] = i2f((int)r.w[i]);
         else out[i] = (i % 2) ? i2f((int)(r.w[i / 2] & 0xFFFF0000u)) : i2f((int)(r.w[i / 2] << 16));
+    }
+}
+
+// CNT (1, 2, 4 or 8) consecutive elements row[l .. l+CNT) with zero fill past L; `vec` as in load_seg
+// (then row + l is aligned to CNT*sizeof(IO) bytes whenever l is a multiple of CNT).
+template <typename IO, int CNT>
+__device__ __forceinline__ void load_few(const IO *row, int64_t l, int64_t L, bool vec, float *out) {
+    if (vec && l + CNT <= L) {
+        RawFew<IO, CNT> r;
+        load_few_raw<IO, CNT>(row, l, L, vec, r);
+        unpack_few<IO, CNT>(r, out);
+    } else {
+#pragma unroll
+        for (int i = 0; i < CNT; ++i) out[i] = (l + i < L) ? io_traits<IO>::get(row, l + i) : 0.0f;
     }
 }
 

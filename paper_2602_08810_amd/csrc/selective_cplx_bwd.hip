@@ -113,7 +113,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     // checkpoints of this workgroup's rows: [B,D,nck,N], or packed [D,nslots,N] with sequence b at slot toff/interval + b
     const int64_t nck = p.cu ? p.nslots : (p.L + kCkptInterval - 1) / kCkptInterval;
     const int64_t ck0 = p.cu ? toff / kCkptInterval + b : toff / kCkptInterval;
-    const bool vec = p.vec != 0 && (toff % 8) == 0;
+    const bool vec = p.vec != 0;
     const bool has_z = p.z != nullptr;
 
     for (int i = tid; i < kMaxGc * N; i += NT) {

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
     const int64_t tile0 = (int64_t)chunk * p.tiles_per_chunk;
     const int64_t tile1 = (tile0 + p.tiles_per_chunk < ntiles) ? tile0 + p.tiles_per_chunk : ntiles;
     const int64_t row = (int64_t)b * p.D + d;
-    const bool vec = p.vec != 0 && (toff % 8) == 0;
+    const bool vec = p.vec != 0;
 
     const IO *urow = reinterpret_cast<const IO *>(p.u) + bs * p.u_sb + d * p.u_sd + toff;
     const IO *drow = reinterpret_cast<const IO *>(p.delta) + bs * p.dl_sb + d * p.dl_sd + toff;

@@ -61,7 +61,7 @@ __global__ __launch_bounds__(W * 64, (N <= 16) ? 4 : 2) void k_ss_fwd(const FwdP
     const int64_t tile0 = (int64_t)chunk * p.tiles_per_chunk;
     const int64_t tile1 = (tile0 + p.tiles_per_chunk < ntiles) ? tile0 + p.tiles_per_chunk : ntiles;
     const int64_t row = (int64_t)b * p.D + d;
-    const bool vec = p.vec != 0 && (toff % 8) == 0;
+    const bool vec = p.vec != 0;
     const int mode = p.mode;
 
     const IO *urow = reinterpret_cast<const IO *>(p.u) + bs * p.u_sb + d * p.u_sd + toff;
