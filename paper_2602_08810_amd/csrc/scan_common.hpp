@@ -48,14 +48,19 @@ __device__ __forceinline__ float log2_fast(float x) { return __builtin_amdgcn_lo
 __device__ __forceinline__ float rcp_fast(float x) { return __builtin_amdgcn_rcpf(x); }     // v_rcp_f32
 
 // softplus(s) = log(1 + e^s) and its derivative sigmoid(s) = e^s / (1 + e^s).
-// For s > 20 both saturate (softplus = s to 2e-9); for small e^s the logarithm is taken
-// by its series so that the result keeps full relative accuracy.
+// For s > 20 both saturate (softplus = s to 2e-9).  The logarithm of 1 + w rounds its argument, which leaves an
+// ABSOLUTE error of 2^-24 in the step size: for float32 I/O (PRECISE) small w take the series of log(1 + w) instead,
+// which keeps full relative accuracy; with bfloat16 I/O, whose inputs and outputs carry relative errors of 2^-9, the
+// absolute 6e-8 is far below anything the step size is multiplied into, and the series is left out.
+template <bool PRECISE = true>
 __device__ __forceinline__ void softplus_sigmoid(float s, float &sp, float &sg) {
     float w = exp2_fast(fminf(s, 20.0f) * kLog2e);
     float r = rcp_fast(1.0f + w);
-    float series = w * (1.0f - w * (0.5f - w * (0.33333334f - w * 0.25f)));
-    float lg = log2_fast(1.0f + w) * kLn2;
-    float v = w < 0.015625f ? series : lg;
+    float v = log2_fast(1.0f + w) * kLn2;
+    if constexpr (PRECISE) {
+        const float series = w * (1.0f - w * (0.5f - w * (0.33333334f - w * 0.25f)));
+        v = w < 0.015625f ? series : v;
+    }
     sp = s > 20.0f ? s : v;
     sg = s > 20.0f ? 1.0f : w * r;
 }
@@ -132,9 +137,10 @@ __device__ __forceinline__ void disc_partials(float dt, const ACoef &c, float a,
 // From the raw step input s = delta + bias, the upstream gradient dy and the gate input z of one time step:
 // Delta and d Delta / d s, the gradient reaching ypre (y = ypre z sigmoid(z)) and the factor that turns ypre into dz
 // (dz = dy ypre sigmoid(z) (1 + z (1 - sigmoid(z)))).
+template <bool PRECISE = true>
 __device__ __forceinline__ void bwd_step_inputs(float s, float dy, float z, bool softplus, bool has_z,
                                                 float &sp, float &sg, float &dyp, float &zf) {
-    if (softplus) softplus_sigmoid(s, sp, sg); else { sp = s; sg = 1.0f; }
+    if (softplus) softplus_sigmoid<PRECISE>(s, sp, sg); else { sp = s; sg = 1.0f; }
     if (has_z) {
         const float sz = sigmoid_fast(z);
         const float dsz = dy * sz;

@@ -216,7 +216,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) {
                     float sp, dyp;
-                    bwd_step_inputs(r_d[i] + bias, e_dy[i], has_z ? e_z[i] : 0.0f, p.softplus != 0, has_z, sp, e_sg[i], dyp, e_zf[i]);
+                    bwd_step_inputs<sizeof(IO) == 4>(r_d[i] + bias, e_dy[i], has_z ? e_z[i] : 0.0f, p.softplus != 0, has_z, sp, e_sg[i], dyp, e_zf[i]);
                     sIn[0 * TILE + fslot(f0 + i)] = (f0 + i < rem) ? sp : 0.0f;
                     sIn[1 * TILE + fslot(f0 + i)] = e_u[i];
                     sIn[2 * TILE + fslot(f0 + i)] = dyp;

@@ -90,7 +90,7 @@ __global__ __launch_bounds__(512, 2) void k_ss_bwd_agg(const BwdParams p) {
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             float sp, sg, gp, zf;
-            bwd_step_inputs(dl[t] + bias, dyp[t], has_z ? zv[t] : 0.0f, p.softplus != 0, has_z, sp, sg, gp, zf);
+            bwd_step_inputs<sizeof(IO) == 4>(dl[t] + bias, dyp[t], has_z ? zv[t] : 0.0f, p.softplus != 0, has_z, sp, sg, gp, zf);
             dl[t] = (ll + t < Lc) ? sp : 0.0f;        // steps past the end are the identity (a = 1, no source term)
             dyp[t] = (ll + t < Lc) ? gp : 0.0f;
             sum_dl += dl[t];
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(512, 2) void k_ss_cbwd_agg(const CBwdParams p) {
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             float sp, sg, gp, zf;
-            bwd_step_inputs(dl[t] + bias, dyp[t], has_z ? zv[t] : 0.0f, p.softplus != 0, has_z, sp, sg, gp, zf);
+            bwd_step_inputs<sizeof(IO) == 4>(dl[t] + bias, dyp[t], has_z ? zv[t] : 0.0f, p.softplus != 0, has_z, sp, sg, gp, zf);
             dl[t] = (ll + t < Lc) ? sp : 0.0f;        // steps past the end are the identity (a = 1, no source term)
             dyp[t] = (ll + t < Lc) ? gp : 0.0f;
             sum_dl += dl[t];

@@ -204,7 +204,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
                 float sp, sg, dyp, zf;
-                bwd_step_inputs(r_d[i] + bias, e_dy[i], has_z ? e_z[i] : 0.0f, p.softplus != 0, has_z, sp, sg, dyp, zf);
+                bwd_step_inputs<sizeof(IO) == 4>(r_d[i] + bias, e_dy[i], has_z ? e_z[i] : 0.0f, p.softplus != 0, has_z, sp, sg, dyp, zf);
                 in[0 * TILE + fslot(f0 + i)] = (f0 + i < rem) ? sp : 0.0f;
                 in[1 * TILE + fslot(f0 + i)] = e_u[i];
                 in[2 * TILE + fslot(f0 + i)] = dyp;

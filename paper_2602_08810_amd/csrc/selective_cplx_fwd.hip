@@ -111,7 +111,7 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             float s = dl[t] + bias, sp, sg;
-            if (p.softplus) softplus_sigmoid(s, sp, sg); else sp = s;
+            if (p.softplus) softplus_sigmoid<sizeof(IO) == 4>(s, sp, sg); else sp = s;
             dl[t] = (ll + t < L) ? sp : 0.0f;         // steps past the end are the identity map (a = 1, b = 0)
             uv[t] = (ll + t < L) ? uv[t] : 0.0f;
             sum_dl += dl[t];

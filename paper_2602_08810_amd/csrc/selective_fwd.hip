@@ -91,9 +91,16 @@ __global__ __launch_bounds__(W * 64, (N <= 16) ? 4 : 2) void k_ss_fwd(const FwdP
     RawFew<IO, T> r_u, r_dl, r_z;
     auto fetch = [&](int64_t tile) {
         const int64_t lf = tile * TILE + lane * T;
-        load_few_raw<IO, T>(urow, lf, L, vec, r_u);
-        load_few_raw<IO, T>(drow, lf, L, vec, r_dl);
-        if constexpr (WANT_Y) { if (zrow) load_few_raw<IO, T>(zrow, lf, L, vec, r_z); }
+        if (vec && (tile + 1) * TILE <= L) {
+            // a tile wholly inside the sequence (wave-uniform): plain vector loads, nothing to check per element
+            load_few_raw<IO, T>(urow + lf, 0, T, true, r_u);
+            load_few_raw<IO, T>(drow + lf, 0, T, true, r_dl);
+            if constexpr (WANT_Y) { if (zrow) load_few_raw<IO, T>(zrow + lf, 0, T, true, r_z); }
+        } else {
+            load_few_raw<IO, T>(urow, lf, L, vec, r_u);
+            load_few_raw<IO, T>(drow, lf, L, vec, r_dl);
+            if constexpr (WANT_Y) { if (zrow) load_few_raw<IO, T>(zrow, lf, L, vec, r_z); }
+        }
     };
     if (active && tile0 < tile1) fetch(tile0);
     // likewise the row of Bm and Cm this thread stages (one step of the tile per thread when the tile has as many
@@ -112,6 +119,8 @@ __global__ __launch_bounds__(W * 64, (N <= 16) ? 4 : 2) void k_ss_fwd(const FwdP
     for (int64_t tile = tile0; tile < tile1; ++tile) {
         const int64_t l0 = tile * TILE;
         const int64_t ll = l0 + lane * T;
+        static_assert(TILE % kCkptInterval == 0 && kCkptInterval % T == 0, "checkpoints fall on lane boundaries");
+        const bool ck_lane = (lane % ((int)kCkptInterval / T)) == 0;     // ll is a multiple of the checkpoint interval
 
         // ---- stage the Bm/Cm tile (all wavefronts), fp32, layout [n][t/4][lane][t%4]; the rows were fetched (raw) one
         // tile ahead
@@ -151,11 +160,19 @@ __global__ __launch_bounds__(W * 64, (N <= 16) ? 4 : 2) void k_ss_fwd(const FwdP
         const RawFew<IO, T> c_z = r_z;                // this tile's gate values, needed after the state loop
         if (tile + 1 < tile1) fetch(tile + 1);
         float sum_dl = 0.0f;
+        const int rem = (L - l0 < TILE) ? (int)(L - l0) : TILE;   // valid steps of this tile (wave-uniform)
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             float s = dl[t] + bias, sp, sg;
-            if (p.softplus) softplus_sigmoid(s, sp, sg); else sp = s;
-            dl[t] = (ll + t < L) ? sp : 0.0f;         // steps past the end are the identity map (a = 1, b = 0)
+            if (p.softplus) softplus_sigmoid<sizeof(IO) == 4>(s, sp, sg); else sp = s;
+            dl[t] = sp;
+        }
+        if (rem < TILE) {                             // steps past the end are the identity map (a = 1, b = 0)
+#pragma unroll
+            for (int t = 0; t < T; ++t) dl[t] = (lane * T + t < rem) ? dl[t] : 0.0f;
+        }
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
             sum_dl += dl[t];
             du[t] = dl[t] * uv[t];
             yv[t] = Dsk * uv[t];
@@ -199,7 +216,7 @@ __global__ __launch_bounds__(W * 64, (N <= 16) ? 4 : 2) void k_ss_fwd(const FwdP
             wave_scan_fwd(P, S);
             float x = dpp<DPP_WAVE_SHR1>(xc, S);                     // state entering this lane's first step
             if constexpr (CKPT) {
-                if ((ll % kCkptInterval) == 0 && ll < L) p.ckpt[(ck0 + ll / kCkptInterval) * N + n] = x;
+                if (ck_lane && ll < L) p.ckpt[(ck0 + ll / kCkptInterval) * N + n] = x;
             }
             if constexpr (!WANT_Y) {
                 xcv = writelane(xcv, readlane(S, 63), n);            // inclusive prefix at lane 63 = state after the tile
@@ -265,7 +282,7 @@ __global__ __launch_bounds__(W * 64, (N <= 16) ? 4 : 2) void k_ss_fwd(const FwdP
             float x0 = dpp<DPP_WAVE_SHR1>(xc0, S0);                  // states entering this lane's first step
             float x1 = dpp<DPP_WAVE_SHR1>(xc1, S1);
             if constexpr (CKPT) {
-                if ((ll % kCkptInterval) == 0 && ll < L) {
+                if (ck_lane && ll < L) {
                     float *ck = p.ckpt + (ck0 + ll / kCkptInterval) * N + n;
                     ck[0] = x0; ck[1] = x1;
                 }
@@ -307,7 +324,8 @@ __global__ __launch_bounds__(W * 64, (N <= 16) ? 4 : 2) void k_ss_fwd(const FwdP
 #pragma unroll
                 for (int t = 0; t < T; ++t) yv[t] *= zv[t] * sigmoid_fast(zv[t]);
             }
-            store_seg<IO, T>(yrow, ll, L, vec, yv);
+            if (vec && rem == TILE) store_seg<IO, T>(yrow + ll, 0, T, true, yv);   // whole tile inside the sequence
+            else store_seg<IO, T>(yrow, ll, L, vec, yv);
         }
     }
 

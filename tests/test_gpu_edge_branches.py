@@ -49,19 +49,21 @@ def _base(B, D, N, L, seed, gate=True):
     return workloads.make_selective(B=B, D=D, N=N, L=L, io="f32", gate=gate, bias=None, seed=seed, with_x0=True)
 
 
-@pytest.mark.parametrize("disc", ["zoh_s6", "zoh"])
-def test_softplus_series_log_and_saturation_branches(api, oracle, disc):
+@pytest.mark.parametrize("disc,io", [("zoh_s6", "f32"), ("zoh", "f32"), ("zoh_s6", "bf16")])
+def test_softplus_series_log_and_saturation_branches(api, oracle, disc, io):
     """s = delta + bias placed at -30 and -4.2 (series of log1p), -4.1 and 19.9 (logarithm), 20.1 and 40 (saturated:
-    softplus(s) = s, derivative 1); the switch points are e^s = 1/64 (s = -4.1589) and s = 20."""
-    p = _base(2, 6, 16, 700, seed=501)
+    softplus(s) = s, derivative 1); the switch points are e^s = 1/64 (s = -4.1589) and s = 20.  With bfloat16 I/O the
+    kernels take the logarithm throughout (absolute error 2^-24 in the step size) and the values are the nearest
+    bfloat16 numbers, still on both sides of the switch points."""
+    p = workloads.make_selective(B=2, D=6, N=16, L=700, io=io, gate=True, bias=None, seed=501, with_x0=True)
     s_values = np.array([-30.0, -4.2, -4.1, 19.9, 20.1, 40.0, -4.1589, 20.0, 0.3, -1.0], dtype=np.float32)
     L = p["delta"].shape[2]
     pattern = s_values[(np.arange(L)[None, None, :] + np.arange(6)[None, :, None] * 3) % len(s_values)]
-    p["delta"] = np.ascontiguousarray(np.broadcast_to(pattern, p["delta"].shape)).astype(np.float32)
+    p["delta"] = workloads._io_round(np.ascontiguousarray(np.broadcast_to(pattern, p["delta"].shape)), io)
     p["delta_bias"] = np.zeros(6, dtype=np.float32)
     # steps of size 20-40 with A of order -1 wipe the state; keep A small so that the large steps still matter
     p["A"] = (p["A"] * 0.02).astype(np.float32)
-    _fwd_bwd(api, oracle, p, disc, True, f"softplus branches, {disc}")
+    _fwd_bwd(api, oracle, p, disc, True, f"softplus branches, {disc}, {io}", io=io)
 
 
 def test_softplus_bias_moves_values_across_the_switch_points(api, oracle):
