@@ -41,6 +41,16 @@ __device__ __forceinline__ float writelane(float old, float v, int lane) {
     return i2f(lrnnx_llvm_writelane_i32(f2i(v), lane, f2i(old)));
 }
 __device__ __forceinline__ float bpermute(int src_lane, float x) { return i2f(__builtin_amdgcn_ds_bpermute(src_lane << 2, f2i(x))); }
+// v[lane] + v[lane ^ 16]: the row-pair swap of gfx950 exchanges the odd rows of one copy with the even rows of the
+// other, all in the vector ALU (a swizzle through the LDS crossbar would cost a round trip of a hundred cycles)
+__device__ __forceinline__ float sum_xor16(float v) {
+    const auto r = __builtin_amdgcn_permlane16_swap((unsigned)f2i(v), (unsigned)f2i(v), false, false);
+    return i2f((int)r[0]) + i2f((int)r[1]);
+}
+// LDS accumulate without a returned value: the wavefront does not wait for it
+__device__ __forceinline__ void lds_add(float *p, float v) {
+    (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
 
 // ---------------------------------------------------------------- transcendentals (fp32, ~1 ulp hardware ops)
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32
@@ -309,27 +319,91 @@ __device__ __forceinline__ void scan_f_bcast31_last(const float *P, float *S) {
 #undef LRNNX_F_LAST
 }
 
+// All steps of the NK suffix scans inside their rows, and all steps of the NK prefix scans, as one block of
+// instructions each (NK = 2 or 4).  Every leading s_nop and every boundary between blocks costs the wavefront an issue
+// slot of its own, and a wavefront of the backward kernel is bound by the length of its own instruction stream.
+// A step touches every state once, so a DPP read of a register comes at least two instructions after its last write.
+#define LRNNX_STEP2(CTRL) LRNNX_F_STATE(0, 1, CTRL) LRNNX_F_STATE(2, 3, CTRL)
+#define LRNNX_STEP4(CTRL) LRNNX_STEP2(CTRL) LRNNX_F_STATE(4, 5, CTRL) LRNNX_F_STATE(6, 7, CTRL)
+#define LRNNX_S_ONLY(s, p, CTRL) "v_fmac_f32_dpp %" #s ", %" #s ", %" #p " " CTRL "\n\t"
+template <int NK>
+__device__ __forceinline__ void scan_r_rows(float *Pr, float *Sr) {
+    static_assert(NK == 2 || NK == 4, "states per block");
+    if constexpr (NK == 2) {
+        asm("s_nop 1\n\t" LRNNX_STEP2("row_shl:1" LRNNX_ALLROWS) LRNNX_STEP2("row_shl:2" LRNNX_ALLROWS)
+            LRNNX_STEP2("row_shl:4" LRNNX_ALLROWS) LRNNX_STEP2("row_shl:8" LRNNX_ALLROWS)
+            : "+v"(Sr[0]), "+v"(Pr[0]), "+v"(Sr[1]), "+v"(Pr[1]));
+    } else {
+        asm("s_nop 1\n\t" LRNNX_STEP4("row_shl:1" LRNNX_ALLROWS) LRNNX_STEP4("row_shl:2" LRNNX_ALLROWS)
+            LRNNX_STEP4("row_shl:4" LRNNX_ALLROWS) LRNNX_STEP4("row_shl:8" LRNNX_ALLROWS)
+            : "+v"(Sr[0]), "+v"(Pr[0]), "+v"(Sr[1]), "+v"(Pr[1]), "+v"(Sr[2]), "+v"(Pr[2]), "+v"(Sr[3]), "+v"(Pr[3]));
+    }
+}
+// inclusive prefixes of NK states, complete (lane 15 of rows 0,2 -> rows 1,3, then lane 31 -> rows 2,3; the last
+// step leaves the products alone, nobody needs them afterwards)
+template <int NK>
+__device__ __forceinline__ void scan_f_all(float *P, float *S) {
+    static_assert(NK == 2 || NK == 4, "states per block");
+    if constexpr (NK == 2) {
+        asm("s_nop 1\n\t" LRNNX_STEP2("row_shr:1" LRNNX_ALLROWS) LRNNX_STEP2("row_shr:2" LRNNX_ALLROWS)
+            LRNNX_STEP2("row_shr:4" LRNNX_ALLROWS) LRNNX_STEP2("row_shr:8" LRNNX_ALLROWS)
+            LRNNX_STEP2("row_bcast:15 row_mask:0xa bank_mask:0xf")
+            LRNNX_S_ONLY(0, 1, "row_bcast:31 row_mask:0xc bank_mask:0xf") LRNNX_S_ONLY(2, 3, "row_bcast:31 row_mask:0xc bank_mask:0xf")
+            : "+v"(S[0]), "+v"(P[0]), "+v"(S[1]), "+v"(P[1]));
+    } else {
+        asm("s_nop 1\n\t" LRNNX_STEP4("row_shr:1" LRNNX_ALLROWS) LRNNX_STEP4("row_shr:2" LRNNX_ALLROWS)
+            LRNNX_STEP4("row_shr:4" LRNNX_ALLROWS) LRNNX_STEP4("row_shr:8" LRNNX_ALLROWS)
+            LRNNX_STEP4("row_bcast:15 row_mask:0xa bank_mask:0xf")
+            LRNNX_S_ONLY(0, 1, "row_bcast:31 row_mask:0xc bank_mask:0xf") LRNNX_S_ONLY(2, 3, "row_bcast:31 row_mask:0xc bank_mask:0xf")
+            LRNNX_S_ONLY(4, 5, "row_bcast:31 row_mask:0xc bank_mask:0xf") LRNNX_S_ONLY(6, 7, "row_bcast:31 row_mask:0xc bank_mask:0xf")
+            : "+v"(S[0]), "+v"(P[0]), "+v"(S[1]), "+v"(P[1]), "+v"(S[2]), "+v"(P[2]), "+v"(S[3]), "+v"(P[3]));
+    }
+}
+
 // On return S holds the inclusive prefix (lane 0 first) and Sr the inclusive suffix (lane 63 first) of every state;
 // P and Pr are left in an unspecified state.
 template <int NK>
 __device__ __forceinline__ void wave_scan_fwd_rev_multi(float *P, float *S, float *Pr, float *Sr, int lane) {
-    scan_fr_row1<NK>(P, S, Pr, Sr);
-    scan_fr_row2<NK>(P, S, Pr, Sr);
-    scan_fr_row4<NK>(P, S, Pr, Sr);
-    scan_fr_row8<NK>(P, S, Pr, Sr);
     // suffixes: rows 0 and 2 take the pair held by the first lane of the next row
     const int src = ((lane & 0x30) + 16) & 63;
     float Pp[NK], Sp[NK];
+    if constexpr (NK == 1) {
+        scan_fr_row1<NK>(P, S, Pr, Sr);
+        scan_fr_row2<NK>(P, S, Pr, Sr);
+        scan_fr_row4<NK>(P, S, Pr, Sr);
+        scan_fr_row8<NK>(P, S, Pr, Sr);
+        Pp[0] = bpermute(src, Pr[0]); Sp[0] = bpermute(src, Sr[0]);
+        scan_f_bcast15<NK>(P, S);
+        scan_f_bcast31_last<NK>(P, S);
+    } else {
+        // the suffixes go first, so that the lane permutes of their hand-over between rows (one round trip through
+        // the LDS crossbar) are in flight during all of the prefix scans
+        scan_r_rows<NK>(Pr, Sr);
 #pragma unroll
-    for (int k = 0; k < NK; ++k) { Pp[k] = bpermute(src, Pr[k]); Sp[k] = bpermute(src, Sr[k]); }
-    scan_f_bcast15<NK>(P, S);
-    scan_f_bcast31_last<NK>(P, S);
-#pragma unroll
-    for (int k = 0; k < NK; ++k)      // rows 0, 2 only (row_mask 0x5); the other rows keep their pair
+        for (int k = 0; k < NK; ++k) { Pp[k] = bpermute(src, Pr[k]); Sp[k] = bpermute(src, Sr[k]); }
+        scan_f_all<NK>(P, S);
+    }
+    // rows 0, 2 only (row_mask 0x5); the other rows keep their pair
+    if constexpr (NK == 4) {
         asm("s_nop 1\n\t"
-            "v_fmac_f32_dpp %0, %2, %1 quad_perm:[0,1,2,3] row_mask:0x5 bank_mask:0xf\n\t"
-            "v_mul_f32_dpp %1, %3, %1 quad_perm:[0,1,2,3] row_mask:0x5 bank_mask:0xf"
-            : "+v"(Sr[k]), "+v"(Pr[k]) : "v"(Sp[k]), "v"(Pp[k]));
+            "v_fmac_f32_dpp %0, %8, %4 quad_perm:[0,1,2,3] row_mask:0x5 bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %1, %9, %5 quad_perm:[0,1,2,3] row_mask:0x5 bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %2, %10, %6 quad_perm:[0,1,2,3] row_mask:0x5 bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %3, %11, %7 quad_perm:[0,1,2,3] row_mask:0x5 bank_mask:0xf\n\t"
+            "v_mul_f32_dpp %4, %12, %4 quad_perm:[0,1,2,3] row_mask:0x5 bank_mask:0xf\n\t"
+            "v_mul_f32_dpp %5, %13, %5 quad_perm:[0,1,2,3] row_mask:0x5 bank_mask:0xf\n\t"
+            "v_mul_f32_dpp %6, %14, %6 quad_perm:[0,1,2,3] row_mask:0x5 bank_mask:0xf\n\t"
+            "v_mul_f32_dpp %7, %15, %7 quad_perm:[0,1,2,3] row_mask:0x5 bank_mask:0xf"
+            : "+v"(Sr[0]), "+v"(Sr[1]), "+v"(Sr[2]), "+v"(Sr[3]), "+v"(Pr[0]), "+v"(Pr[1]), "+v"(Pr[2]), "+v"(Pr[3])
+            : "v"(Sp[0]), "v"(Sp[1]), "v"(Sp[2]), "v"(Sp[3]), "v"(Pp[0]), "v"(Pp[1]), "v"(Pp[2]), "v"(Pp[3]));
+    } else {
+#pragma unroll
+        for (int k = 0; k < NK; ++k)
+            asm("s_nop 1\n\t"
+                "v_fmac_f32_dpp %0, %2, %1 quad_perm:[0,1,2,3] row_mask:0x5 bank_mask:0xf\n\t"
+                "v_mul_f32_dpp %1, %3, %1 quad_perm:[0,1,2,3] row_mask:0x5 bank_mask:0xf"
+                : "+v"(Sr[k]), "+v"(Pr[k]) : "v"(Sp[k]), "v"(Pp[k]));
+    }
     // rows 0 and 1 take the suffix now held by lane 32: Sr += Pr * Sr[32] (the product of the multipliers is not
     // needed any more).  The value travels through a scalar register; the update runs with the upper half of the
     // wavefront switched off.  Wait states: one between the VALU write of Sr and its v_readlane, two between the

@@ -193,7 +193,19 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
             n_A += more ? N : 0; n_ck += more ? ck_stride : 0;
             n_Dsk += (more && has_D) ? 1 : 0; n_bias += (more && has_bias) ? 1 : 0;
         };
+        // The prefetched registers are claimed ("settled") at a point of the program where their loads have long
+        // arrived and no store is in flight behind them: the memory counter is in order, so a wait for a load that
+        // comes after younger stores (the epilogue's, issued under a branch) would wait for those stores as well.
+        auto settle = [&](Pref &s) {
+#pragma unroll
+            for (int i = 0; i < RawFew<IO, TPW>::WORDS; ++i)
+                asm volatile("" : "+v"(s.u.w[i]), "+v"(s.dl.w[i]), "+v"(s.dy.w[i]), "+v"(s.z.w[i]) : : "memory");
+#pragma unroll
+            for (int k = 0; k < NK; ++k) asm volatile("" : "+v"(s.A[k]), "+v"(s.ck[k]) : : "memory");
+            asm volatile("" : "+v"(s.Dsk), "+v"(s.bias) : : "memory");
+        };
         prefetch(S0);
+        settle(S0);
 
         auto channel = [&](const int g, Pref &pf) {
             if constexpr (ALT_PRIO) {
@@ -247,27 +259,35 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
             float a[NK][T + 1], gg[NK][T], x[NK][T], cdy[NK][T];
             float P[NK], S[NK], Pr[NK], Sr[NK], hcv[NK];
             ACoef acs[NK];
+            // The Bm columns of all JS states are read from LDS in one batch (one round trip instead of one per state;
+            // the scheduler is kept from moving the reads down to their uses)
+            float Bk[NK][T];
+            auto read_Bk = [&]() {
+#pragma unroll
+                for (int k = k0; k < k0 + JS; ++k)
+#pragma unroll
+                    for (int q = 0; q < TQ; ++q) {
+                        const float4 vb = *reinterpret_cast<const float4 *>(&sBt[(((w * NK + k) * TQ + q) * 64 + lane) * 4]);
+                        Bk[k][4 * q] = vb.x; Bk[k][4 * q + 1] = vb.y; Bk[k][4 * q + 2] = vb.z; Bk[k][4 * q + 3] = vb.w;
+                    }
+            };
+            read_Bk();
+#pragma unroll
+            for (int k = k0; k < k0 + JS; ++k) hcv[k] = sH[g * N + w * NK + k];
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int k = k0; k < k0 + JS; ++k) {
-                const int n = w * NK + k;
                 const ACoef ac = make_acoef<DISC>(cA[k]);
                 acs[k] = ac;
                 const float xck = cck[k];
-                const float hc = sH[g * N + n];
-                hcv[k] = hc;
-                float Bk[T];
-#pragma unroll
-                for (int q = 0; q < TQ; ++q) {
-                    const float4 vb = *reinterpret_cast<const float4 *>(&sBt[((n * TQ + q) * 64 + lane) * 4]);
-                    Bk[4 * q] = vb.x; Bk[4 * q + 1] = vb.y; Bk[4 * q + 2] = vb.z; Bk[4 * q + 3] = vb.w;
-                }
+                const float hc = hcv[k];
                 float sx = 0.0f;
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
                     disc_ag<DISC>(dl[t], ac, a[k][t], gg[k][t]);
-                    if constexpr (DISC == DISC_ZOH_S6) x[k][t] = dlu[t] * Bk[t];
-                    else if constexpr (DISC == DISC_DIRAC) x[k][t] = dlu[t] * Bk[t];
-                    else x[k][t] = gg[k][t] * dlu[t] * Bk[t];
+                    if constexpr (DISC == DISC_ZOH_S6) x[k][t] = dlu[t] * Bk[k][t];
+                    else if constexpr (DISC == DISC_DIRAC) x[k][t] = dlu[t] * Bk[k][t];
+                    else x[k][t] = gg[k][t] * dlu[t] * Bk[k][t];
                     sx = (t == 0) ? x[k][0] : __builtin_fmaf(a[k][t], sx, x[k][t]);   // the fold starts from zero
                 }
                 // products of the multipliers of this lane's steps (state prefix) and of the same steps shifted by one
@@ -290,19 +310,17 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 if (lane == 63) sr = __builtin_fmaf(pr, hc, sr);            // the carried adjoint enters through lane 63
                 Pr[k] = pr; Sr[k] = sr;
             }
-            // ---- phase 2: state prefixes (forward in time) and adjoint suffixes (backward in time) of these JS states
+            // ---- phase 2: state prefixes (forward in time) and adjoint suffixes (backward in time) of these JS states;
+            // the Bm columns are read again meanwhile (the fold has consumed the first copy)
+            __builtin_amdgcn_sched_barrier(0);
+            read_Bk();
+            __builtin_amdgcn_sched_barrier(0);
             wave_scan_fwd_rev_multi<JS>(P + k0, S + k0, Pr + k0, Sr + k0, lane);
             // ---- phase 3: replay of the states and of the adjoint, gradients
 #pragma unroll
             for (int k = k0; k < k0 + JS; ++k) {
                 const int n = w * NK + k;
                 const ACoef ac = acs[k];
-                float Bk[T];
-#pragma unroll
-                for (int q = 0; q < TQ; ++q) {
-                    const float4 vb = *reinterpret_cast<const float4 *>(&sBt[((n * TQ + q) * 64 + lane) * 4]);
-                    Bk[4 * q] = vb.x; Bk[4 * q + 1] = vb.y; Bk[4 * q + 2] = vb.z; Bk[4 * q + 3] = vb.w;
-                }
                 const float xin = dpp<DPP_WAVE_SHR1>(cck[k], S[k]);         // x entering this lane's first step
                 {
                     float xp = xin;
@@ -325,7 +343,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                     if constexpr (DISC == DISC_ZOH_S6 || DISC == DISC_DIRAC) {
                         // S6: g = Delta (du and dDelta share sum_n H B, scaled in the epilogue); dirac: g = 1, and only
                         // a = e^{Delta A} depends on Delta and A
-                        acc(pdu[t], R, Bk[t]);
+                        acc(pdu[t], R, Bk[k][t]);
                         dBacc[k][t] = __builtin_fmaf(R, dlu[t], dBacc[k][t]);
                         const float q = R * xprev * a[k][t];
                         acc(pdd[t], q, ac.A);
@@ -334,7 +352,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                         // da/dDelta = A a, da/dA = Delta a, dg/dDelta = a: the common factor a is taken out
                         float a_t, a_A, g_t, g_A;
                         disc_partials<DISC>(dl[t], ac, a[k][t], gg[k][t], a_t, a_A, g_t, g_A);
-                        const float hb = R * Bk[t];
+                        const float hb = R * Bk[k][t];
                         const float dg = hb * dlu[t];
                         const float dax = R * a[k][t] * xprev;               // H x_{l-1} a
                         acc(pdu[t], hb, gg[k][t]);
@@ -347,7 +365,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                         const float q = rcp_fast(__builtin_fmaf(-dl[t], ac.hA, 1.0f));
                         const float q2 = q * q;
                         const float da = R * xprev;
-                        const float hb = R * Bk[t];
+                        const float hb = R * Bk[k][t];
                         const float dg = hb * dlu[t];
                         acc(pdu[t], hb, gg[k][t]);
                         dBacc[k][t] = __builtin_fmaf(R * gg[k][t], dlu[t], dBacc[k][t]);
@@ -359,14 +377,14 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                     dA4[k] = dA_part;
                 } else {
                     const float dA_tot = wave_sum(dA_part);
-                    if (lane == 0) sdA[0][g * N + n] += dA_tot;
+                    if (lane == 0) lds_add(&sdA[0][g * N + n], dA_tot);
                 }
             }
             }   // groups of JS states
             if constexpr (NK == 4) {
                 // The four per-lane partial sums are reduced together: two exchange steps leave each lane of a quad
                 // with the quad's sum of ONE state (lane%4 = 0,1,2,3 -> state 0,2,1,3), two rotations sum the quads of
-                // a row, one swizzle sums the two rows of a half-wavefront; lanes 0-3 and 32-35 own the results.
+                // a row, one row-pair swap sums the two rows of a half-wavefront; lanes 0-3 and 32-35 own the results.
                 const bool b0 = lane & 1, b1 = lane & 2;
                 float kA = b0 ? dA4[2] : dA4[0], kB = b0 ? dA4[3] : dA4[1];
                 const float sA = b0 ? dA4[0] : dA4[2], sB = b0 ? dA4[1] : dA4[3];
@@ -376,8 +394,8 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 v += dpp<0x4E>(0.0f, b1 ? kA : kB);                         // quad_perm [2,3,0,1]
                 v += dpp<0x124>(0.0f, v);                                   // row_ror:4
                 v += dpp<0x128>(0.0f, v);                                   // row_ror:8
-                v += i2f(__builtin_amdgcn_ds_swizzle(f2i(v), 0x401F));      // lane ^ 16
-                if ((lane & 0x1C) == 0) sdA[lane >> 5][g * N + w * NK + ((lane & 1) << 1) + ((lane >> 1) & 1)] += v;
+                v = sum_xor16(v);
+                if ((lane & 0x1C) == 0) lds_add(&sdA[lane >> 5][g * N + w * NK + ((lane & 1) << 1) + ((lane >> 1) & 1)], v);
             } else if constexpr (NK == 2) {
                 // the same with two partial sums: even lanes end up with state 0, odd lanes with state 1
                 const bool odd = lane & 1;
@@ -386,8 +404,8 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 v += dpp<0x4E>(0.0f, v);                                    // quad_perm [2,3,0,1]
                 v += dpp<0x124>(0.0f, v);                                   // row_ror:4
                 v += dpp<0x128>(0.0f, v);                                   // row_ror:8
-                v += i2f(__builtin_amdgcn_ds_swizzle(f2i(v), 0x401F));      // lane ^ 16
-                if ((lane & 0x1E) == 0) sdA[lane >> 5][g * N + w * NK + (lane & 1)] += v;
+                v = sum_xor16(v);
+                if ((lane & 0x1E) == 0) lds_add(&sdA[lane >> 5][g * N + w * NK + (lane & 1)], v);
             }
 #pragma unroll
             for (int q = 0; q < TQ; ++q) {
@@ -401,27 +419,42 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
             if (io_thread) {
                 float o_du[TPW], o_dd[TPW], o_dz[TPW];
                 float dD_part = 0.0f, db_part = 0.0f;
+                // every LDS value of the epilogue is read up front, in one round trip (left alone, the compiler moves
+                // the reads that only feed the stores into the stores' own branch, one round trip after the other)
+                float e_in[TPW][3], e_part[TPW][W][3];
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) {
-                    const float e_u = sIn[1 * TILE + fslot(f0 + i)], e_dyp = sIn[2 * TILE + fslot(f0 + i)];
+#pragma unroll
+                    for (int j = 0; j < 3; ++j) e_in[i][j] = sIn[j * TILE + fslot(f0 + i)];
+#pragma unroll
+                    for (int ww = 0; ww < W; ++ww)
+#pragma unroll
+                        for (int j = DZ ? 0 : 1; j < 3; ++j) e_part[i][ww][j] = sPart[(ww * 3 + j) * TILE + fslot(f0 + i)];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) {
+                    const float e_u = e_in[i][1], e_dyp = e_in[i][2];
                     float yp = Dsk * e_u, s_du = 0.0f, s_dd = 0.0f;
 #pragma unroll
                     for (int ww = 0; ww < W; ++ww) {
-                        if constexpr (DZ) yp += sPart[(ww * 3 + 0) * TILE + fslot(f0 + i)];
-                        s_du += sPart[(ww * 3 + 1) * TILE + fslot(f0 + i)];
-                        s_dd += sPart[(ww * 3 + 2) * TILE + fslot(f0 + i)];
+                        if constexpr (DZ) yp += e_part[i][ww][0];
+                        s_du += e_part[i][ww][1];
+                        s_dd += e_part[i][ww][2];
                     }
                     if constexpr (DISC == DISC_ZOH_S6) {
                         // the wavefronts' sums are sum_n H B: dDelta += u sum_n H B, du = Delta sum_n H B
                         s_dd = __builtin_fmaf(e_u, s_du, s_dd);
-                        s_du *= sIn[0 * TILE + fslot(f0 + i)];
+                        s_du *= e_in[i][0];
                     }
                     o_du[i] = __builtin_fmaf(e_dyp, Dsk, s_du);
                     o_dd[i] = s_dd * e_sg[i];
                     o_dz[i] = yp * e_zf[i];
                     dD_part = __builtin_fmaf(e_dyp, e_u, dD_part);
                     db_part += (f0 + i < rem) ? o_dd[i] : 0.0f;
+                    asm volatile("" : "+v"(o_du[i]), "+v"(o_dd[i]), "+v"(o_dz[i]));   // computed here, not inside the stores' branch
                 }
+                settle(pf);                          // the next channel's inputs, before this channel's stores
                 store_few<IO, TPW>(o_du_row, f0, rem, vec, o_du);
                 store_few<IO, TPW>(o_dd_row, f0, rem, vec, o_dd);
                 if constexpr (DZ) store_few<IO, TPW>(o_dz_row, f0, rem, vec, o_dz);
@@ -433,8 +466,8 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 v += dpp<0x4E>(0.0f, v);                                    // quad_perm [2,3,0,1]
                 v += dpp<0x124>(0.0f, v);                                   // row_ror:4
                 v += dpp<0x128>(0.0f, v);                                   // row_ror:8
-                v += i2f(__builtin_amdgcn_ds_swizzle(f2i(v), 0x401F));      // lane ^ 16
-                if ((lane & 0x1E) == 0) (odd ? sdb : sdD)[((lane >> 5) * W + w) * kMaxG + g] += v;
+                v = sum_xor16(v);
+                if ((lane & 0x1E) == 0) lds_add(&(odd ? sdb : sdD)[((lane >> 5) * W + w) * kMaxG + g], v);
             }
             o_du_row += p.du_sd; o_dd_row += p.dd_sd;
             if constexpr (DZ) o_dz_row += p.dz_sd;
