@@ -596,6 +596,14 @@ struct RawFew {
     static constexpr int WORDS = (CNT * (16 / io_traits<IO>::EPC) + 3) / 4;
     uint32_t w[WORDS];
 };
+// One element, read without a branch and without touching the loaded register afterwards (so nothing waits for the
+// load before its real use): past the end the last element is read again (L >= 1) and the CALLER discards it.
+template <typename IO, typename IDX>
+__device__ __forceinline__ void load_one_raw_clamped(const IO *row, IDX l, IDX L, RawFew<IO, 1> &r) {
+    const IDX lc = l < L ? l : L - 1;
+    if constexpr (sizeof(IO) == 4) r.w[0] = *reinterpret_cast<const uint32_t *>(row + lc);
+    else r.w[0] = *reinterpret_cast<const unsigned short *>(row + lc);
+}
 template <typename IO, int CNT, typename IDX>
 __device__ __forceinline__ void load_few_raw(const IO *row, IDX l, IDX L, bool vec, RawFew<IO, CNT> &r) {
     constexpr int BYTES = CNT * (16 / io_traits<IO>::EPC);

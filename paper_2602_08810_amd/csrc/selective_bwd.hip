@@ -178,10 +178,18 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
         int n_left = Gact - 1;                                           // channels after the one the pointers are on
         auto prefetch = [&](Pref &s) {
             if (io_thread) {
-                load_few_raw<IO, TPW>(n_u, f0, rem, vec, s.u);
-                load_few_raw<IO, TPW>(n_dl, f0, rem, vec, s.dl);
-                load_few_raw<IO, TPW>(n_dy, f0, rem, vec, s.dy);
-                load_few_raw<IO, TPW>(n_z, f0, rem, vec, s.z);
+                if constexpr (TPW == 1) {
+                    // steps past the end of the tile read the last valid one again; the prologue discards them
+                    load_one_raw_clamped<IO>(n_u, f0, rem, s.u);
+                    load_one_raw_clamped<IO>(n_dl, f0, rem, s.dl);
+                    load_one_raw_clamped<IO>(n_dy, f0, rem, s.dy);
+                    load_one_raw_clamped<IO>(n_z, f0, rem, s.z);
+                } else {
+                    load_few_raw<IO, TPW>(n_u, f0, rem, vec, s.u);
+                    load_few_raw<IO, TPW>(n_dl, f0, rem, vec, s.dl);
+                    load_few_raw<IO, TPW>(n_dy, f0, rem, vec, s.dy);
+                    load_few_raw<IO, TPW>(n_z, f0, rem, vec, s.z);
+                }
             }
 #pragma unroll
             for (int k = 0; k < NK; ++k) { s.A[k] = n_A[k]; s.ck[k] = n_ck[k]; }
@@ -207,35 +215,61 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
         prefetch(S0);
         settle(S0);
 
-        auto channel = [&](const int g, Pref &pf) {
-            if constexpr (ALT_PRIO) {
-                if ((unsigned)(g & 1) == hw_slot) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
-            }
-            const float Dsk = has_D ? pf.Dsk : 0.0f, bias = has_bias ? pf.bias : 0.0f;
-            float cA[NK], cck[NK];
-#pragma unroll
-            for (int k = 0; k < NK; ++k) { cA[k] = pf.A[k]; cck[k] = pf.ck[k]; }
+        // Order of a channel's work between the workgroup's two barriers per channel.  After the first barrier (the
+        // step inputs of channel g are in LDS): the main pass, which leaves the wavefronts' partial sums in LDS.
+        // After the second: the LDS reads of the epilogue of channel g are issued, the prologue of channel g+1 runs
+        // while they are in flight (softplus, gate, staging of the step inputs; its inputs were fetched during the
+        // main pass), then the epilogue's arithmetic and stores.  Kept in registers from a channel's prologue to its
+        // epilogue: d softplus / ds, the factor that turns ypre into dz, and Dskip (n_*: of the channel after).
+        float e_sg[TPW], e_zf[TPW], n_sg[TPW], n_zf[TPW];
+        float Dsk = 0.0f, nDsk = 0.0f;
+        float cA[NK], cck[NK];                       // A and the checkpointed state of the main pass's channel
 
-            // ---- prologue: each thread prepares TPW flat steps for everybody
-            // kept for the epilogue: d softplus / ds, and the factor that turns ypre into dz
-            float e_sg[TPW], e_zf[TPW];
+        // ---- prologue of the channel whose inputs S0 holds: each thread prepares TPW flat steps for everybody
+        auto prologue = [&]() {
+            const float bias = has_bias ? S0.bias : 0.0f;
+            // The values are moved out of S0 here and now (real moves, which the compiler may not turn into a renaming):
+            // the fetch that follows then loads into the very registers S0 has at the top of the loop.  Left to the
+            // compiler, the fetch gets fresh registers and the copies land at the end of the loop body, where they
+            // wait for the loads that have just been issued.
+            nDsk = has_D ? S0.Dsk : 0.0f;
+            asm volatile("" : "+v"(nDsk));
+#pragma unroll
+            for (int k = 0; k < NK; ++k) {
+                asm volatile("v_mov_b32 %0, %1" : "=v"(cA[k]) : "v"(S0.A[k]));
+                asm volatile("v_mov_b32 %0, %1" : "=v"(cck[k]) : "v"(S0.ck[k]));
+            }
             if (io_thread) {
                 float e_u[TPW], r_d[TPW], e_dy[TPW], e_z[TPW];
-                unpack_few<IO, TPW>(pf.u, e_u);
-                unpack_few<IO, TPW>(pf.dl, r_d);
-                unpack_few<IO, TPW>(pf.dy, e_dy);
-                unpack_few<IO, TPW>(pf.z, e_z);
+                unpack_few<IO, TPW>(S0.u, e_u);
+                unpack_few<IO, TPW>(S0.dl, r_d);
+                unpack_few<IO, TPW>(S0.dy, e_dy);
+                unpack_few<IO, TPW>(S0.z, e_z);
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) {
                     float sp, dyp;
-                    bwd_step_inputs<sizeof(IO) == 4>(r_d[i] + bias, e_dy[i], has_z ? e_z[i] : 0.0f, p.softplus != 0, has_z, sp, e_sg[i], dyp, e_zf[i]);
-                    sIn[0 * TILE + fslot(f0 + i)] = (f0 + i < rem) ? sp : 0.0f;
-                    sIn[1 * TILE + fslot(f0 + i)] = e_u[i];
-                    sIn[2 * TILE + fslot(f0 + i)] = dyp;
+                    bwd_step_inputs<sizeof(IO) == 4>(r_d[i] + bias, e_dy[i], has_z ? e_z[i] : 0.0f, p.softplus != 0, has_z, sp, n_sg[i], dyp, n_zf[i]);
+                    const bool valid = f0 + i < rem;     // steps past the end: Delta = 0 (a = 1), no input, no gradient
+                    sIn[0 * TILE + fslot(f0 + i)] = valid ? sp : 0.0f;
+                    sIn[1 * TILE + fslot(f0 + i)] = valid ? e_u[i] : 0.0f;
+                    sIn[2 * TILE + fslot(f0 + i)] = valid ? dyp : 0.0f;
                 }
             }
+        };
+        auto rotate = [&]() {
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) { e_sg[i] = n_sg[i]; e_zf[i] = n_zf[i]; }
+            Dsk = nDsk;
+        };
+        prologue();                                  // channel 0
+        rotate();
+        prefetch(S0);                                // channel 1 (where there is none, the last channel again)
+
+        auto channel = [&](const int g) {
+            if constexpr (ALT_PRIO) {
+                if ((unsigned)(g & 1) == hw_slot) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
+            }
             __syncthreads();
-            prefetch(pf);                            // this set's values are consumed or copied: refill it for the next channel
 
             // ---- main: this lane's T steps, this wavefront's NK states
             float dl[T], dyp[T], dlu[T], ypre[T], pdu[T], pdd[T];
@@ -415,13 +449,11 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 *reinterpret_cast<float4 *>(base + 2 * TILE) = make_float4(pdd[4 * q], pdd[4 * q + 1], pdd[4 * q + 2], pdd[4 * q + 3]);
             }
             __syncthreads();
-            // ---- epilogue: the threads share the tile in flat order
+            // ---- epilogue of this channel, with the prologue of the next one in its shadow
+            float e_in[TPW][3], e_part[TPW][W][3];
             if (io_thread) {
-                float o_du[TPW], o_dd[TPW], o_dz[TPW];
-                float dD_part = 0.0f, db_part = 0.0f;
                 // every LDS value of the epilogue is read up front, in one round trip (left alone, the compiler moves
                 // the reads that only feed the stores into the stores' own branch, one round trip after the other)
-                float e_in[TPW][3], e_part[TPW][W][3];
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) {
 #pragma unroll
@@ -431,7 +463,15 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
 #pragma unroll
                         for (int j = DZ ? 0 : 1; j < 3; ++j) e_part[i][ww][j] = sPart[(ww * 3 + j) * TILE + fslot(f0 + i)];
                 }
-                __builtin_amdgcn_sched_barrier(0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            settle(S0);                              // the next channel's inputs: claimed before this channel's stores
+            prologue();                              // (past the last channel: the last one again, unused)
+            prefetch(S0);                            // the channel after the next
+            __builtin_amdgcn_sched_barrier(0);
+            if (io_thread) {
+                float o_du[TPW], o_dd[TPW], o_dz[TPW];
+                float dD_part = 0.0f, db_part = 0.0f;
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) {
                     const float e_u = e_in[i][1], e_dyp = e_in[i][2];
@@ -454,7 +494,6 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                     db_part += (f0 + i < rem) ? o_dd[i] : 0.0f;
                     asm volatile("" : "+v"(o_du[i]), "+v"(o_dd[i]), "+v"(o_dz[i]));   // computed here, not inside the stores' branch
                 }
-                settle(pf);                          // the next channel's inputs, before this channel's stores
                 store_few<IO, TPW>(o_du_row, f0, rem, vec, o_du);
                 store_few<IO, TPW>(o_dd_row, f0, rem, vec, o_dd);
                 if constexpr (DZ) store_few<IO, TPW>(o_dz_row, f0, rem, vec, o_dz);
@@ -469,10 +508,11 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                 v = sum_xor16(v);
                 if ((lane & 0x1E) == 0) lds_add(&(odd ? sdb : sdD)[((lane >> 5) * W + w) * kMaxG + g], v);
             }
+            rotate();
             o_du_row += p.du_sd; o_dd_row += p.dd_sd;
             if constexpr (DZ) o_dz_row += p.dz_sd;
         };
-        for (int g = 0; g < Gact; ++g) channel(g, S0);
+        for (int g = 0; g < Gact; ++g) channel(g);
         // ---- add this tile's dBm/dCm sums (over the G channels) to global memory, transposed through LDS
         // so that consecutive threads hit consecutive addresses
         float *fbB = sPart, *fbC = sPart + 16 * T * N;
