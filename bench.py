@@ -8,13 +8,13 @@ The same run also times the other single-kernel workloads (config 1 LTI scan, co
 long-sequence forward on both paths, config 4 backward) and reports them under
 "other_configs"; they are not part of `value`.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--quick]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--quick] [--alu-probe]
 
 Prints ONE JSON line.  `roofline` is for the dominant kernel of the step (the backward
 kernel): algorithmic HBM bytes per launch / average launch time measured with HIP
 events on the launch stream, against the 8 TB/s HBM peak.  `roofline_alu` prices the
-same launch against the plain (non-packed) fp32 VALU issue rate, which is the tighter
-bound for this path (N exponentials per loaded element).  `cpu_baseline` is the fp64
+same launch against the fp32 vector-ALU issue rate, which is the tighter bound for this
+path (N exponentials per loaded element).  `cpu_baseline` is the fp64
 oracle timed on the host cores on the same workload.
 """
 from __future__ import annotations
@@ -31,9 +31,13 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# 256 CUs x 4 SIMD16 x 2.4 GHz = 39.3e12 plain (non-packed) fp32 lane-instructions/s; the vendor's 157.3 TFLOP/s
-# fp32 vector peak counts an FMA as two flops and a packed instruction as two more
-VALU_PEAK_TLANEOPS = 39.3
+# 256 CUs x 4 SIMDs x 32 lanes per clock x 2.4 GHz = 78.6e12 plain fp32 lane-instructions/s: the published
+# 157.3 TFLOP/s fp32 vector peak counts an FMA as two flops and needs no packed form.  Measured with the probe
+# (`--alu-probe`, csrc/valu_probe.hip): a plain FMA/MUL/ADD issues every 2.6 nominal cycles per SIMD (60e12 lanes/s),
+# an instruction with a DPP or scalar-register operand, a select, a conversion or a min/max every 4.4 (35e12), a
+# transcendental every 8.4 (18e12); one wavefront alone issues at most every 5.5 cycles.
+VALU_PEAK_TLANEOPS = 78.6
+PROBE = os.path.join(ROOT, "paper_2602_08810_amd", "valu_probe")
 
 # Measured HBM traffic of the backward kernel on config 2 comes from the counter summary under profiles/ (rocprofv3
 # --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size).  The summary names the sources of the kernel
@@ -41,6 +45,22 @@ VALU_PEAK_TLANEOPS = 39.3
 TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "config2_fwd_bwd_hbm_traffic.md")
 KERNEL_SOURCES = [os.path.join(ROOT, "paper_2602_08810_amd", "csrc", f)
                   for f in ("selective_bwd.hip", "scan_common.hpp", "kernels.hpp")]
+
+
+def _alu_probe():
+    """Runs the stand-alone probe (its own process: it shares nothing with the library) and returns
+    {instruction: {"chains c, w waves/SIMD": cycles per instruction and SIMD at the nominal 2.4 GHz}}."""
+    import re
+    import subprocess
+    if not os.path.exists(PROBE):
+        raise SystemExit(f"bench.py: {PROBE} is not built (python -m paper_2602_08810_amd.build)")
+    r = subprocess.run([PROBE], capture_output=True, text=True, timeout=120)
+    if r.returncode != 0:
+        raise SystemExit(f"bench.py: the ALU probe failed:\n{r.stderr}")
+    out = {}
+    for m in re.finditer(r"^(.*?)\s+chains (\d+)\s+waves/SIMD (\d+)\s+([0-9.]+) cycles", r.stdout, re.M):
+        out.setdefault(m.group(1).strip(), {})[f"chains {m.group(2)}, {m.group(3)} waves/SIMD"] = float(m.group(4))
+    return out
 
 
 def kernel_source_hash():
@@ -86,6 +106,8 @@ def main():
                          "experiments' means); the timed region is --repeats x --steps steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quick", action="store_true", help="skip the other configs")
+    ap.add_argument("--alu-probe", action="store_true",
+                    help="also run the vector-ALU issue-rate probe (paper_2602_08810_amd/valu_probe) and report it")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of 256 MiB (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -183,18 +205,19 @@ def main():
                 "frac": bwd_bytes / bwd_t / 1e9 / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_note,
                 "algorithmic_bytes": bwd_bytes, "avg_launch_us": bwd_t * 1e6,
                 "copy_ceiling_GBs": copy_ceiling, "frac_of_copy_ceiling": bwd_bytes / bwd_t / 1e9 / copy_ceiling}
-    # Algorithmic VALU work per element.  Backward: state recompute (3 fp32 instructions + 1 exponential = 2 issue
-    # slots), adjoint recurrence (2), gradient terms (8) = 15 issue slots, 24 flops (an FMA counts two).  Forward:
-    # multiplier (1 + exponential 2), input term (1), state update (1), projection (1) = 6 slots, 8 flops.  Scans,
-    # softplus and gate are not counted.  Peaks: 39.3e12 plain lane-instructions/s; in flops 78.6 TFLOP/s for FMA
-    # streams without the packed forms (switched off on this pool), which is half the published 157.3.
-    def alu(ops, flops, t_s, kernel):
-        return {"bound": "alu", "kernel": kernel, "achieved": elements * ops / t_s / 1e12, "peak": VALU_PEAK_TLANEOPS,
-                "unit": "T lane-instr/s", "frac": elements * ops / t_s / 1e12 / VALU_PEAK_TLANEOPS, "ops_per_element": ops,
-                "achieved_TFLOPs": elements * flops / t_s / 1e12, "peak_TFLOPs_unpacked": 78.6, "peak_TFLOPs_published": 157.3,
+    # Algorithmic VALU work per element, in issue slots of a plain fp32 instruction (the exponential runs at a quarter
+    # of that rate: 4 slots).  Backward: multiplier (1 + 4), state recompute (2), adjoint recurrence (2), gradient
+    # terms (9) = 18 slots, 15 instructions, 24 flops (an FMA counts two).  Forward: multiplier (1 + 4), input term
+    # (1), fold, state update and projection (3) = 9 slots, 6 instructions, 8 flops.  Scans, softplus and gate are not
+    # counted.  Peak: 78.6e12 slots/s = the published 157.3 TFLOP/s at two flops per FMA.
+    def alu(slots, instrs, flops, t_s, kernel):
+        return {"bound": "alu", "kernel": kernel, "achieved": elements * slots / t_s / 1e12, "peak": VALU_PEAK_TLANEOPS,
+                "unit": "T issue slots/s", "frac": elements * slots / t_s / 1e12 / VALU_PEAK_TLANEOPS,
+                "slots_per_element": slots, "instructions_per_element": instrs,
+                "achieved_TFLOPs": elements * flops / t_s / 1e12, "peak_TFLOPs_published": 157.3,
                 "flops_per_element": flops}
-    roofline_alu = alu(15.0, 24.0, bwd_t, roofline["kernel"])
-    roofline_alu_fwd = alu(6.0, 8.0, fwd_t, "k_ss_fwd<bf16,N=16> (config 2 forward)")
+    roofline_alu = alu(18.0, 15.0, 24.0, bwd_t, roofline["kernel"])
+    roofline_alu_fwd = alu(9.0, 6.0, 8.0, fwd_t, "k_ss_fwd<bf16,N=16> (config 2 forward)")
 
     result = {
         "metric": "scan elements/s (B*L*D*N) fwd & bwd", "value": value, "unit": "elements/s",
@@ -217,6 +240,10 @@ def main():
     # ------------------------------------------------------------------ the other configs (context, not `value`)
     if not args.quick:
         result["other_configs"] = _other_configs(api, torch, dev)
+
+    # ------------------------------------------------------------------ vector-ALU issue rates (on request)
+    if args.alu_probe:
+        result["alu_probe"] = _alu_probe()
 
     # ------------------------------------------------------------------ CPU baseline: the oracle as it stands
     if not args.no_cpu_baseline:

@@ -3,7 +3,8 @@
     python -m paper_2602_08810_amd.build
 
 Each .hip file under csrc/ is compiled to an object in parallel, then linked into
-paper_2602_08810_amd/liblrnnx.so.  hipcc cross-compiles: no GPU is needed to build.
+paper_2602_08810_amd/liblrnnx.so; csrc/valu_probe.hip becomes the stand-alone program
+paper_2602_08810_amd/valu_probe.  hipcc cross-compiles: no GPU is needed to build.
 """
 from __future__ import annotations
 
@@ -16,6 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblrnnx.so")
+PROBE = os.path.join(HERE, "valu_probe")
 SOURCES = ["api.hip", "selective_fwd.hip", "selective_bwd.hip", "selective_bwd_carry.hip", "selective_cplx_fwd.hip", "selective_cplx_bwd.hip", "lti_scan.hip", "diag_scan.hip", "step.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -46,6 +48,12 @@ def build(verbose: bool = True) -> str:
         raise RuntimeError(f"link failed:\n{r.stderr}")
     if verbose:
         print(f"built {LIB}")
+    # the stand-alone issue-rate probe of the vector ALU (bench.py --alu-probe runs it)
+    r = subprocess.run([HIPCC, *FLAGS, os.path.join(CSRC, "valu_probe.hip"), "-o", PROBE], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on valu_probe.hip:\n{r.stderr}")
+    if verbose:
+        print(f"built {PROBE}")
     return LIB
 
 
