@@ -29,7 +29,7 @@ namespace {
 
 // Sum over the 32 lanes of each half-wavefront of four per-lane values at once: two exchange steps leave each lane
 // of a quad with the quad's sum of ONE value (lane%4 = 0,1,2,3 -> value 0,2,1,3), two rotations sum the quads of a
-// row, one swizzle sums the two rows.  Lanes 0-3 and 32-35 own the results.
+// row, one row-pair swap sums the two rows.  Lanes 0-3 and 32-35 own the results.
 __device__ __forceinline__ float half_sum4(const float *v4, int lane) {
     const bool b0 = lane & 1, b1 = lane & 2;
     float kA = b0 ? v4[2] : v4[0], kB = b0 ? v4[3] : v4[1];
@@ -40,16 +40,14 @@ __device__ __forceinline__ float half_sum4(const float *v4, int lane) {
     v += dpp<0x4E>(0.0f, b1 ? kA : kB);                         // quad_perm [2,3,0,1]
     v += dpp<0x124>(0.0f, v);                                   // row_ror:4
     v += dpp<0x128>(0.0f, v);                                   // row_ror:8
-    v += i2f(__builtin_amdgcn_ds_swizzle(f2i(v), 0x401F));      // lane ^ 16
-    return v;
+    return sum_xor16(v);
 }
 __device__ __forceinline__ float half_sum(float v) {
     v += dpp<0xB1>(0.0f, v);
     v += dpp<0x4E>(0.0f, v);
     v += dpp<0x124>(0.0f, v);
     v += dpp<0x128>(0.0f, v);
-    v += i2f(__builtin_amdgcn_ds_swizzle(f2i(v), 0x401F));
-    return v;
+    return sum_xor16(v);
 }
 
 }  // namespace
@@ -376,11 +374,11 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
                     const float v4[4] = {dAr4[k2], dAr4[k2 + 1], dAi4[k2], dAi4[k2 + 1]};
                     const float v = half_sum4(v4, lane);       // lane % 4 = 0,1,2,3 holds value 0,2,1,3
                     if ((lane & 0x1C) == 0)
-                        sdA[lane >> 5][((g * N + w * NK + k2 + ((lane >> 1) & 1)) << 1) + (lane & 1)] += v;
+                        lds_add(&sdA[lane >> 5][((g * N + w * NK + k2 + ((lane >> 1) & 1)) << 1) + (lane & 1)], v);
                 }
             } else {
                 const float vr = half_sum(dAr4[0]), vi = half_sum(dAi4[0]);
-                if ((lane & 31) == 0) { sdA[lane >> 5][(g * N + w) << 1] += vr; sdA[lane >> 5][((g * N + w) << 1) + 1] += vi; }
+                if ((lane & 31) == 0) { lds_add(&sdA[lane >> 5][(g * N + w) << 1], vr); lds_add(&sdA[lane >> 5][((g * N + w) << 1) + 1], vi); }
             }
 #pragma unroll
             for (int q = 0; q < TQ; ++q) {
@@ -395,35 +393,49 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
             if (epi_thread) {
                 float o_du[TPW], o_dd[TPW], o_dz[TPW];
                 float dD_part = 0.0f, db_part = 0.0f;
+                // every LDS value of the epilogue is read up front, in one round trip (left alone, the compiler moves
+                // the reads that only feed the stores into the stores' own branch, one round trip after the other)
+                float e_in[TPW][5], e_part[TPW][W][3];
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) {
                     const int fs = fslot(f0e + i);
-                    const float e_u = in[1 * TILE + fs], e_dyp = in[2 * TILE + fs];
+#pragma unroll
+                    for (int j = 0; j < 5; ++j) e_in[i][j] = in[j * TILE + fs];
+#pragma unroll
+                    for (int ww = 0; ww < W; ++ww)
+#pragma unroll
+                        for (int j = 0; j < 3; ++j) e_part[i][ww][j] = sPart[(ww * 3 + j) * TILE + fs];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) {
+                    const float e_u = e_in[i][1], e_dyp = e_in[i][2];
                     float yp = Dsk * e_u, s_du = 0.0f, s_dd = 0.0f;
 #pragma unroll
                     for (int ww = 0; ww < W; ++ww) {
-                        yp += sPart[(ww * 3 + 0) * TILE + fs];
-                        s_du += sPart[(ww * 3 + 1) * TILE + fs];
-                        s_dd += sPart[(ww * 3 + 2) * TILE + fs];
+                        yp += e_part[i][ww][0];
+                        s_du += e_part[i][ww][1];
+                        s_dd += e_part[i][ww][2];
                     }
                     if constexpr (DISC == DISC_ZOH_S6) {
                         // the wavefronts' sums are sum_n Re(H conj(B)): dDelta += u times it, du = Delta times it
                         s_dd = __builtin_fmaf(e_u, s_du, s_dd);
-                        s_du *= in[0 * TILE + fs];
+                        s_du *= e_in[i][0];
                     }
                     o_du[i] = __builtin_fmaf(e_dyp, Dsk, s_du);
-                    o_dd[i] = s_dd * in[3 * TILE + fs];
-                    o_dz[i] = yp * in[4 * TILE + fs];
+                    o_dd[i] = s_dd * e_in[i][3];
+                    o_dz[i] = yp * e_in[i][4];
                     dD_part = __builtin_fmaf(e_dyp, e_u, dD_part);
                     db_part += (f0e + i < rem) ? o_dd[i] : 0.0f;
+                    asm volatile("" : "+v"(o_du[i]), "+v"(o_dd[i]), "+v"(o_dz[i]));   // computed here, not inside the stores' branch
                 }
                 store_few<IO, TPW>(reinterpret_cast<IO *>(p.du) + bs * p.du_sb + d * p.du_sd + toff + l0, f0e, rem, vec, o_du);
                 store_few<IO, TPW>(reinterpret_cast<IO *>(p.ddelta) + bs * p.dd_sb + d * p.dd_sd + toff + l0, f0e, rem, vec, o_dd);
                 if (p.dz) store_few<IO, TPW>(reinterpret_cast<IO *>(p.dz) + bs * p.dz_sb + d * p.dz_sd + toff + l0, f0e, rem, vec, o_dz);
                 const float vD = half_sum(dD_part), vb = half_sum(db_part);
                 if ((lane & 31) == 0) {
-                    sdD[((lane >> 5) * W + w) * kMaxGc + g] += vD;
-                    sdb[((lane >> 5) * W + w) * kMaxGc + g] += vb;
+                    lds_add(&sdD[((lane >> 5) * W + w) * kMaxGc + g], vD);
+                    lds_add(&sdb[((lane >> 5) * W + w) * kMaxGc + g], vb);
                 }
             }
             // the next channel's prologue fills the other half of sIn (the prefetch that feeds it was issued before
