@@ -201,53 +201,6 @@ __device__ __forceinline__ void wave_scan_fwd2(float &P, float &S, float &Q, flo
     LRNNX_PAIR_STEP2("", P, S, "row_bcast:31 row_mask:0xc bank_mask:0xf", Q, R, "row_bcast:31 row_mask:0xc bank_mask:0xf");
 }
 
-// Inclusive suffix over the 64 lanes, lane 63 first (time runs right to left):
-//   (P,S)_i <- (P,S)_i o (P,S)_{i+1} o ... o (P,S)_63.
-__device__ __forceinline__ void wave_scan_rev(float &P, float &S, int lane) {
-    LRNNX_PAIR_STEP(P, S, "row_shl:1 row_mask:0xf bank_mask:0xf");
-    LRNNX_PAIR_STEP(P, S, "row_shl:2 row_mask:0xf bank_mask:0xf");
-    LRNNX_PAIR_STEP(P, S, "row_shl:4 row_mask:0xf bank_mask:0xf");
-    LRNNX_PAIR_STEP(P, S, "row_shl:8 row_mask:0xf bank_mask:0xf");
-    {   // rows 0 and 2 take the suffix held by the first lane of the next row
-        const int src = ((lane & 0x30) + 16) & 63;
-        float Pp = bpermute(src, P), Sp = bpermute(src, S);
-        const bool take = ((lane >> 4) & 1) == 0;
-        Pp = take ? Pp : 1.0f; Sp = take ? Sp : 0.0f;
-        S = __builtin_fmaf(P, Sp, S); P = P * Pp;
-    }
-    {   // rows 0 and 1 take the suffix held by lane 32
-        float Pp = bpermute(32, P), Sp = bpermute(32, S);
-        const bool take = lane < 32;
-        Pp = take ? Pp : 1.0f; Sp = take ? Sp : 0.0f;
-        S = __builtin_fmaf(P, Sp, S); P = P * Pp;
-    }
-}
-
-// Both scans of the backward pass at once: inclusive prefix of (P,S) and inclusive suffix of (Pr,Sr).  The four
-// in-row steps are interleaved pairwise; the suffix's hand-over between rows (two lane permutes) overlaps the
-// prefix's two broadcast steps.
-__device__ __forceinline__ void wave_scan_fwd_rev(float &P, float &S, float &Pr, float &Sr, int lane) {
-    LRNNX_PAIR_STEP2("s_nop 1\n\t", P, S, "row_shr:1 row_mask:0xf bank_mask:0xf", Pr, Sr, "row_shl:1 row_mask:0xf bank_mask:0xf");
-    LRNNX_PAIR_STEP2("", P, S, "row_shr:2 row_mask:0xf bank_mask:0xf", Pr, Sr, "row_shl:2 row_mask:0xf bank_mask:0xf");
-    LRNNX_PAIR_STEP2("", P, S, "row_shr:4 row_mask:0xf bank_mask:0xf", Pr, Sr, "row_shl:4 row_mask:0xf bank_mask:0xf");
-    LRNNX_PAIR_STEP2("", P, S, "row_shr:8 row_mask:0xf bank_mask:0xf", Pr, Sr, "row_shl:8 row_mask:0xf bank_mask:0xf");
-    const int src = ((lane & 0x30) + 16) & 63;                          // first lane of the next row
-    float Pp = bpermute(src, Pr), Sp = bpermute(src, Sr);
-    LRNNX_PAIR_STEP(P, S, "row_bcast:15 row_mask:0xa bank_mask:0xf");   // lane 15 of rows 0,2 -> rows 1,3
-    LRNNX_PAIR_STEP(P, S, "row_bcast:31 row_mask:0xc bank_mask:0xf");   // lane 31 -> rows 2,3
-    {   // rows 0 and 2 take the suffix held by the first lane of the next row
-        const bool take = ((lane >> 4) & 1) == 0;
-        Pp = take ? Pp : 1.0f; Sp = take ? Sp : 0.0f;
-        Sr = __builtin_fmaf(Pr, Sp, Sr); Pr = Pr * Pp;
-    }
-    {   // rows 0 and 1 take the suffix held by lane 32
-        float Pq = bpermute(32, Pr), Sq = bpermute(32, Sr);
-        const bool take = lane < 32;
-        Pq = take ? Pq : 1.0f; Sq = take ? Sq : 0.0f;
-        Sr = __builtin_fmaf(Pr, Sq, Sr); Pr = Pr * Pq;
-    }
-}
-
 // ---------------------------------------------------------------- both scans of the backward pass, NK states at once
 // The state prefix (P,S) and the adjoint suffix (Pr,Sr) of each of NK states advance together, one Hillis-Steele
 // step of all 2 NK pairs per block of instructions.  The chains of different states are independent, so each fills
@@ -266,57 +219,23 @@ __device__ __forceinline__ void wave_scan_fwd_rev(float &P, float &S, float &Pr,
     "v_mul_f32_dpp %" #p ", %" #p ", %" #p " " CF "\n\t"
 #define LRNNX_ALLROWS " row_mask:0xf bank_mask:0xf"
 
-#define LRNNX_DEFINE_FR_ROWSTEP(NAME, CF, CR)                                                                        \
-    template <int NK>                                                                                                \
-    __device__ __forceinline__ void NAME(float *P, float *S, float *Pr, float *Sr) {                                 \
-        static_assert(NK == 1 || NK == 2 || NK == 4, "states per wavefront");                                        \
-        if constexpr (NK == 1) {                                                                                     \
-            asm("s_nop 1\n\t" LRNNX_FR_STATE(0, 1, 2, 3, CF, CR)                                                     \
-                : "+v"(S[0]), "+v"(P[0]), "+v"(Sr[0]), "+v"(Pr[0]));                                                 \
-        } else if constexpr (NK == 2) {                                                                              \
-            asm("s_nop 1\n\t" LRNNX_FR_STATE(0, 1, 2, 3, CF, CR) LRNNX_FR_STATE(4, 5, 6, 7, CF, CR)                  \
-                : "+v"(S[0]), "+v"(P[0]), "+v"(Sr[0]), "+v"(Pr[0]), "+v"(S[1]), "+v"(P[1]), "+v"(Sr[1]), "+v"(Pr[1])); \
-        } else {                                                                                                     \
-            asm("s_nop 1\n\t" LRNNX_FR_STATE(0, 1, 2, 3, CF, CR) LRNNX_FR_STATE(4, 5, 6, 7, CF, CR)                  \
-                LRNNX_FR_STATE(8, 9, 10, 11, CF, CR) LRNNX_FR_STATE(12, 13, 14, 15, CF, CR)                          \
-                : "+v"(S[0]), "+v"(P[0]), "+v"(Sr[0]), "+v"(Pr[0]), "+v"(S[1]), "+v"(P[1]), "+v"(Sr[1]), "+v"(Pr[1]), \
-                  "+v"(S[2]), "+v"(P[2]), "+v"(Sr[2]), "+v"(Pr[2]), "+v"(S[3]), "+v"(P[3]), "+v"(Sr[3]), "+v"(Pr[3])); \
-        }                                                                                                            \
-    }
-LRNNX_DEFINE_FR_ROWSTEP(scan_fr_row1, "row_shr:1" LRNNX_ALLROWS, "row_shl:1" LRNNX_ALLROWS)
-LRNNX_DEFINE_FR_ROWSTEP(scan_fr_row2, "row_shr:2" LRNNX_ALLROWS, "row_shl:2" LRNNX_ALLROWS)
-LRNNX_DEFINE_FR_ROWSTEP(scan_fr_row4, "row_shr:4" LRNNX_ALLROWS, "row_shl:4" LRNNX_ALLROWS)
-LRNNX_DEFINE_FR_ROWSTEP(scan_fr_row8, "row_shr:8" LRNNX_ALLROWS, "row_shl:8" LRNNX_ALLROWS)
-
-// prefix scans only: the two steps that cross rows (lane 15 of rows 0,2 -> rows 1,3; lane 31 -> rows 2,3)
-#define LRNNX_DEFINE_F_STEP(NAME, CF)                                                                                \
-    template <int NK>                                                                                                \
-    __device__ __forceinline__ void NAME(float *P, float *S) {                                                       \
-        if constexpr (NK == 1) {                                                                                     \
-            asm("s_nop 1\n\t" LRNNX_F_STATE(0, 1, CF) : "+v"(S[0]), "+v"(P[0]));                                     \
-        } else if constexpr (NK == 2) {                                                                              \
-            asm("s_nop 1\n\t" LRNNX_F_STATE(0, 1, CF) LRNNX_F_STATE(2, 3, CF)                                        \
-                : "+v"(S[0]), "+v"(P[0]), "+v"(S[1]), "+v"(P[1]));                                                   \
-        } else {                                                                                                     \
-            asm("s_nop 1\n\t" LRNNX_F_STATE(0, 1, CF) LRNNX_F_STATE(2, 3, CF) LRNNX_F_STATE(4, 5, CF) LRNNX_F_STATE(6, 7, CF) \
-                : "+v"(S[0]), "+v"(P[0]), "+v"(S[1]), "+v"(P[1]), "+v"(S[2]), "+v"(P[2]), "+v"(S[3]), "+v"(P[3]));   \
-        }                                                                                                            \
-    }
-LRNNX_DEFINE_F_STEP(scan_f_bcast15, "row_bcast:15 row_mask:0xa bank_mask:0xf")
-LRNNX_DEFINE_F_STEP(scan_f_bcast31, "row_bcast:31 row_mask:0xc bank_mask:0xf")
-// the last step of a prefix scan whose products are not needed afterwards: only the S half
-template <int NK>
-__device__ __forceinline__ void scan_f_bcast31_last(const float *P, float *S) {
-#define LRNNX_F_LAST(s, p) "v_fmac_f32_dpp %" #s ", %" #s ", %" #p " row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
-    if constexpr (NK == 1) {
-        asm("s_nop 1\n\t" LRNNX_F_LAST(0, 1) : "+v"(S[0]) : "v"(P[0]));
-    } else if constexpr (NK == 2) {
-        asm("s_nop 1\n\t" LRNNX_F_LAST(0, 2) LRNNX_F_LAST(1, 3) : "+v"(S[0]), "+v"(S[1]) : "v"(P[0]), "v"(P[1]));
-    } else {
-        asm("s_nop 1\n\t" LRNNX_F_LAST(0, 4) LRNNX_F_LAST(1, 5) LRNNX_F_LAST(2, 6) LRNNX_F_LAST(3, 7)
-            : "+v"(S[0]), "+v"(S[1]), "+v"(S[2]), "+v"(S[3]) : "v"(P[0]), "v"(P[1]), "v"(P[2]), "v"(P[3]));
-    }
-#undef LRNNX_F_LAST
+// One state only (NK = 1): the four in-row steps of its prefix and of its suffix in one block (four instructions per
+// step, so a DPP read comes at least two instructions after the last write of its register) ...
+__device__ __forceinline__ void scan_fr_rows_one(float &P, float &S, float &Pr, float &Sr) {
+    asm("s_nop 1\n\t"
+        LRNNX_FR_STATE(0, 1, 2, 3, "row_shr:1" LRNNX_ALLROWS, "row_shl:1" LRNNX_ALLROWS)
+        LRNNX_FR_STATE(0, 1, 2, 3, "row_shr:2" LRNNX_ALLROWS, "row_shl:2" LRNNX_ALLROWS)
+        LRNNX_FR_STATE(0, 1, 2, 3, "row_shr:4" LRNNX_ALLROWS, "row_shl:4" LRNNX_ALLROWS)
+        LRNNX_FR_STATE(0, 1, 2, 3, "row_shr:8" LRNNX_ALLROWS, "row_shl:8" LRNNX_ALLROWS)
+        : "+v"(S), "+v"(P), "+v"(Sr), "+v"(Pr));
+}
+// ... and the two steps of its prefix that cross rows (lane 15 of rows 0,2 -> rows 1,3; lane 31 -> rows 2,3; the
+// last one leaves the product alone, nobody needs it afterwards)
+__device__ __forceinline__ void scan_f_cross_one(float &P, float &S) {
+    asm("s_nop 1\n\t" LRNNX_F_STATE(0, 1, "row_bcast:15 row_mask:0xa bank_mask:0xf")
+        "s_nop 0\n\t"
+        "v_fmac_f32_dpp %0, %0, %1 row_bcast:31 row_mask:0xc bank_mask:0xf"
+        : "+v"(S), "+v"(P));
 }
 
 // All steps of the NK suffix scans inside their rows, and all steps of the NK prefix scans, as one block of
@@ -368,13 +287,9 @@ __device__ __forceinline__ void wave_scan_fwd_rev_multi(float *P, float *S, floa
     const int src = ((lane & 0x30) + 16) & 63;
     float Pp[NK], Sp[NK];
     if constexpr (NK == 1) {
-        scan_fr_row1<NK>(P, S, Pr, Sr);
-        scan_fr_row2<NK>(P, S, Pr, Sr);
-        scan_fr_row4<NK>(P, S, Pr, Sr);
-        scan_fr_row8<NK>(P, S, Pr, Sr);
+        scan_fr_rows_one(P[0], S[0], Pr[0], Sr[0]);
         Pp[0] = bpermute(src, Pr[0]); Sp[0] = bpermute(src, Sr[0]);
-        scan_f_bcast15<NK>(P, S);
-        scan_f_bcast31_last<NK>(P, S);
+        scan_f_cross_one(P[0], S[0]);
     } else {
         // the suffixes go first, so that the lane permutes of their hand-over between rows (one round trip through
         // the LDS crossbar) are in flight during all of the prefix scans
@@ -648,20 +563,6 @@ __device__ __forceinline__ void unpack_few(const RawFew<IO, CNT> &r, float *out)
     for (int i = 0; i < CNT; ++i) {
         if constexpr (sizeof(IO) == 4) out[i] = i2f((int)r.w[i]);
         else out[i] = (i % 2) ? i2f((int)(r.w[i / 2] & 0xFFFF0000u)) : i2f((int)(r.w[i / 2] << 16));
-    }
-}
-
-// CNT (1, 2, 4 or 8) consecutive elements row[l .. l+CNT) with zero fill past L; `vec` as in load_seg
-// (then row + l is aligned to CNT*sizeof(IO) bytes whenever l is a multiple of CNT).
-template <typename IO, int CNT>
-__device__ __forceinline__ void load_few(const IO *row, int64_t l, int64_t L, bool vec, float *out) {
-    if (vec && l + CNT <= L) {
-        RawFew<IO, CNT> r;
-        load_few_raw<IO, CNT>(row, l, L, vec, r);
-        unpack_few<IO, CNT>(r, out);
-    } else {
-#pragma unroll
-        for (int i = 0; i < CNT; ++i) out[i] = (l + i < L) ? io_traits<IO>::get(row, l + i) : 0.0f;
     }
 }
 

@@ -60,6 +60,17 @@ def test_packed_lengths(api, oracle, lengths, io):
     _check(api, oracle, 16, 16, lengths, io, seed=len(lengths))
 
 
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+def test_packed_starts_at_every_residue_mod_8(api, oracle, io):
+    """Sequence starts at 0, 513, 522, 532, 543, 555, 568, 582, 597: every residue mod 8, i.e. every misalignment of a
+    row against the 16-byte vector accesses (which only need element alignment), with sequences of more than one
+    vector and two of more than one tile."""
+    lengths = (513, 9, 10, 11, 12, 13, 14, 15, 600)
+    starts = np.concatenate([[0], np.cumsum(lengths)[:-1]])
+    assert set(int(v) % 8 for v in starts) == set(range(8))
+    _check(api, oracle, 12, 16, lengths, io, seed=31)
+
+
 def test_packed_with_grouped_maps_and_unused_steps_around(api, oracle):
     _check(api, oracle, 24, 16, (333, 900, 40), "bf16", seed=7, G=3, gap=5)
 
