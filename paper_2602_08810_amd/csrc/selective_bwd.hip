@@ -13,7 +13,8 @@
 // work on the same channel at the same time.  A wavefront therefore keeps its NK columns of Bm/Cm
 // for the tile, and the running sums of dBm/dCm over channels, in registers while the workgroup
 // loops over G channels: the reduction of dBm/dCm over channels costs no memory traffic and no
-// atomics inside the loop (LDS float atomics are very slow on this chip).  What is summed over n
+// per-element atomics inside the loop (LDS float atomics are very slow on this chip when every lane
+// takes part; only the few lanes that own a per-channel sum use them).  What is summed over n
 // (du, dDelta, ypre for dz) is exchanged through LDS once per (channel, tile): each wavefront
 // writes its partial sums, and after a barrier the threads share the epilogue of the 64*T steps
 // in flat order, so u/delta/dy/z are each read once and du/ddelta/dz written once, coalesced.
