@@ -43,7 +43,6 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     static_assert(T % 4 == 0 && (T % W == 0 || W % T == 0) && TPW <= 8 && NA % 64 == 0 && NA <= NT, "tile shape");
     static_assert(TILE % kCkptInterval == 0, "tiles must start on checkpoints");
     static_assert(TILE == kBwdTileSteps, "the chunked launch counts its chunks in tiles of this kernel");
-    static_assert(W * 3 * TILE >= 2 * 16 * T * N, "flush buffer must fit in the partials area");
 
     __shared__ __attribute__((aligned(16))) float sIn[3 * TILE];          // delta, u, dypre   [q][lane][4]
     __shared__ __attribute__((aligned(16))) float sPart[W * 3 * TILE];    // per wave: ypre, du, ddelta partials
@@ -514,27 +513,38 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
             if constexpr (DZ) o_dz_row += p.dz_sd;
         };
         for (int g = 0; g < Gact; ++g) channel(g);
-        // ---- add this tile's dBm/dCm sums (over the G channels) to global memory, transposed through LDS
-        // so that consecutive threads hit consecutive addresses
-        float *fbB = sPart, *fbC = sPart + 16 * T * N;
-        for (int j = 0; j < 4; ++j) {
+        // ---- add this tile's dBm/dCm sums (over the G channels) to global memory, transposed through LDS so that
+        // consecutive threads hit consecutive addresses: two rounds of 32 lanes each, in the area of the Bm columns
+        // (not needed any more: the next tile stages its own)
+        constexpr int FL = 32;                                           // lanes per round
+        float *fbB = sBt, *fbC = sBt + FL * T * N;
+        static_assert(2 * FL * T * N <= N * TILE, "flush buffer must fit in the Bm area");
+        for (int j = 0; j < 64 / FL; ++j) {
             __syncthreads();
-            if ((lane >> 4) == j) {
+            if (lane / FL == j) {
 #pragma unroll
                 for (int t = 0; t < T; ++t)
 #pragma unroll
                     for (int k = 0; k < NK; ++k) {
-                        fbB[((lane & 15) * T + t) * N + w * NK + k] = dBacc[k][t];
-                        fbC[((lane & 15) * T + t) * N + w * NK + k] = dCacc[k][t];
+                        fbB[((lane % FL) * T + t) * N + w * NK + k] = dBacc[k][t];
+                        fbC[((lane % FL) * T + t) * N + w * NK + k] = dCacc[k][t];
                     }
             }
             __syncthreads();
-            const int step0 = j * 16 * T;                                // within the tile
+            const int step0 = j * FL * T;                                // within the tile
             float *gB = p.dBm + bc0 + (l0 + step0) * N, *gC = p.dCm + bc0 + (l0 + step0) * N;
-            for (int idx = tid; idx < 16 * T * N; idx += NT) {
+            // each thread's values are read from LDS in one batch, then added (one round trip instead of one per value)
+            constexpr int PER = FL * T * N / NT;                         // = T * NK / 2
+            static_assert(PER * NT == FL * T * N, "the flush buffer is a whole number of values per thread");
+            float vB[PER], vC[PER];
+#pragma unroll
+            for (int i = 0; i < PER; ++i) { vB[i] = fbB[tid + i * NT]; vC[i] = fbC[tid + i * NT]; }
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const int idx = tid + i * NT;
                 if (step0 + idx / N < rem) {
-                    unsafeAtomicAdd(gB + (unsigned)idx, fbB[idx]);
-                    unsafeAtomicAdd(gC + (unsigned)idx, fbC[idx]);
+                    unsafeAtomicAdd(gB + (unsigned)idx, vB[i]);
+                    unsafeAtomicAdd(gC + (unsigned)idx, vC[i]);
                 }
             }
         }
