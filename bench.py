@@ -439,11 +439,21 @@ def _other_configs(api, torch, dev):
     outs_p.update(dA=torch.empty((Dp, Np), device=dev), dBm=torch.empty((Lp, Np), device=dev),
                   dCm=torch.empty((Lp, Np), device=dev), dD=torch.empty(Dp, device=dev), dbias=torch.empty(Dp, device=dev))
     tf = _time(torch, lambda: api.lrnnx_selective_scan_fwd(**pk, cu_seqlens=cu, out=yp, ckpt_out=ckp), 10)
-    tb = _time(torch, lambda: api.lrnnx_selective_scan_bwd(**pk, dy=dyp, cu_seqlens=cu, ckpt=ckp, outs=outs_p), 10)
+    tb = _time(torch, lambda: api.lrnnx_selective_scan_bwd(**pk, dy=dyp, cu_seqlens=cu, ckpt=ckp, outs=outs_p,
+                                                           max_seqlen=max(lens)), 10)
     out["packed_24seq_D1536_L16384"] = {"fwd_us": tf * 1e6, "bwd_us": tb * 1e6,
                                         "elements_per_s": 2 * Dp * Np * Lp / (tf + tb),
-                                        "note": "same total size as config 2"}
-    del tp, pk, dyp, yp, ckp, outs_p
+                                        "note": "same total size as config 2; the backward call is given max_seqlen"}
+    # the same steps as 8 sequences of 2048 (config 2 itself, packed): what the packed mode costs on equal lengths
+    cu8 = torch.arange(0, Lp + 1, 2048, dtype=torch.int64, device=dev)
+    ckp8 = torch.empty((Dp, Lp // api.lrnnx_ckpt_interval() + 8, Np), device=dev)
+    tf = _time(torch, lambda: api.lrnnx_selective_scan_fwd(**pk, cu_seqlens=cu8, out=yp, ckpt_out=ckp8), 10)
+    tb = _time(torch, lambda: api.lrnnx_selective_scan_bwd(**pk, dy=dyp, cu_seqlens=cu8, ckpt=ckp8, outs=outs_p,
+                                                           max_seqlen=2048), 10)
+    out["packed_8x2048_D1536"] = {"fwd_us": tf * 1e6, "bwd_us": tb * 1e6,
+                                  "elements_per_s": 2 * Dp * Np * Lp / (tf + tb),
+                                  "note": "config 2 as a packed batch; the backward call is given max_seqlen"}
+    del tp, pk, dyp, yp, ckp, ckp8, outs_p
 
     # config 3: long-sequence forward, both paths
     B3, D3, N3, L3 = 1, 2048, 16, 65536

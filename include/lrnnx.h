@@ -200,6 +200,8 @@ typedef struct lrnnx_ss_bwd_complex_args {
                                     ckpt == NULL */
     const int64_t *cu_seqlens;   /* packed mode as in the forward call (then du, ddelta, dz are [D,L], dBm, dCm
                                     [G,L,N], ckpt [D, lrnnx_packed_ckpt_slots(L,B), N]), or NULL */
+    int64_t max_seqlen;          /* packed mode: the longest sequence of the batch if the caller knows it, else 0; as
+                                    in lrnnx_ss_bwd_args */
     const void *u;      int64_t u_stride_b, u_stride_d;
     const void *delta;  int64_t delta_stride_b, delta_stride_d;
     const void *A;                                                 /* [D,N] complex float */
@@ -255,6 +257,12 @@ typedef struct lrnnx_ss_bwd_args {
                                     workspace also holds B ints that let the launch start the longest sequences first
                                     (batches of up to 256 sequences), which shortens its tail; a workspace without
                                     room for them is accepted and the launch keeps the caller's order. */
+    int64_t max_seqlen;          /* packed mode: the longest sequence of the batch (steps) if the caller knows it,
+                                    else 0.  A hint for the launch shape only, never for addressing: with it the
+                                    workgroups of sequences much longer than the average take fewer channels each, so
+                                    that one long sequence does not set the time of the whole launch; a value that is
+                                    too small only loses that balance, a value that is too large costs some idle
+                                    workgroups.  Ignored without cu_seqlens. */
     const void *u;      int64_t u_stride_b, u_stride_d;
     const void *delta;  int64_t delta_stride_b, delta_stride_d;
     const float *A;

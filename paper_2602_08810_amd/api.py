@@ -52,11 +52,11 @@ class FwdComplexArgs(ctypes.Structure):           # lrnnx_ss_fwd_complex_args (s
 
 
 class BwdArgs(ctypes.Structure):                  # lrnnx_ss_bwd_args
-    _fields_ = _SEL_HEAD + _SEL_INPUTS + _SEL_BWD_TAIL
+    _fields_ = _SEL_HEAD + [("max_seqlen", _i64)] + _SEL_INPUTS + _SEL_BWD_TAIL
 
 
 class BwdComplexArgs(ctypes.Structure):           # lrnnx_ss_bwd_complex_args
-    _fields_ = _SEL_HEAD + _SEL_INPUTS + _SEL_BWD_TAIL
+    _fields_ = _SEL_HEAD + [("max_seqlen", _i64)] + _SEL_INPUTS + _SEL_BWD_TAIL
 
 
 class LtiArgs(ctypes.Structure):
@@ -451,12 +451,13 @@ def _check_complex_maps(A, Bm, Cm, io, Bsz, D, L):
 @_device_checked
 def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,
                                      ckpt=None, disc="zoh_s6", delta_softplus=True, want_dx0=False, outs=None,
-                                     workspace=None, cu_seqlens=None, path="auto"):
+                                     workspace=None, cu_seqlens=None, path="auto", max_seqlen=None):
     """Gradients of sum(dy*y) of the complex-A selective scan as a dict; see lrnnx_ss_bwd_complex_args.
     dA [D,N], dBm, dCm [B,L,N], dx0 [B,D,N] are complex64 (dLoss/dRe + i dLoss/dIm); du, ddelta, dz in the I/O
     type; dD, dbias float32.  `ckpt`: the checkpoints a forward call returned (else they are recomputed).
     `cu_seqlens`: packed variable-length mode as in the forward call (du, ddelta, dz are [D,L]; dBm, dCm [L,N] or
-    [G,L,N]; dx0 [S,D,N]).  `path`: "auto", "single_pass" or "chunk_carry" as for the real scan."""
+    [G,L,N]; dx0 [S,D,N]).  `path`: "auto", "single_pass" or "chunk_carry" as for the real scan.  `max_seqlen`: as
+    for the real scan."""
     io = u.dtype
     packed = cu_seqlens is not None
     if packed:
@@ -487,6 +488,7 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
     a.B, a.D, a.N, a.L = Bsz, D, N, L
     a.bc_groups = G
     a.cu_seqlens = _ptr(cu_seqlens)
+    a.max_seqlen = 0 if max_seqlen is None else int(max_seqlen)
     a.path = PATH[path] if isinstance(path, str) else int(path)
     a.io_dtype = _io_dtype(u)
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)
@@ -540,10 +542,12 @@ def lrnnx_selective_scan_bwd_complex(u, delta, A, Bm, Cm, dy, Dskip=None, delta_
 @_device_checked
 def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=None, z=None, x0=None,
                              ckpt=None, disc="zoh_s6", delta_softplus=True, want_dx0=False,
-                             outs=None, workspace=None, cu_seqlens=None, path="auto"):
+                             outs=None, workspace=None, cu_seqlens=None, path="auto", max_seqlen=None):
     """Gradients of sum(dy*y) as a dict; see lrnnx_ss_bwd_args.  `outs` may supply preallocated outputs.
     `cu_seqlens`: packed variable-length mode as in the forward call (du, ddelta, dz are [D,L]; dBm, dCm as Bm).
-    `path`: "auto", "single_pass" or "chunk_carry" (time axis cut into chunks that run side by side)."""
+    `path`: "auto", "single_pass" or "chunk_carry" (time axis cut into chunks that run side by side).
+    `max_seqlen`: packed mode, the longest sequence of the batch if the host knows it (a hint for the launch shape
+    that keeps one long sequence from setting the time of the whole launch; the lengths themselves stay on the device)."""
     io = u.dtype
     packed = cu_seqlens is not None
     if packed:
@@ -573,6 +577,7 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
     a.struct_size = ctypes.sizeof(BwdArgs)
     a.B, a.D, a.N, a.L = Bsz, D, N, L
     a.cu_seqlens = _ptr(cu_seqlens)
+    a.max_seqlen = 0 if max_seqlen is None else int(max_seqlen)
     a.path = PATH[path] if isinstance(path, str) else int(path)
     a.io_dtype = _io_dtype(u)
     a.disc = DISC[disc] if isinstance(disc, str) else int(disc)

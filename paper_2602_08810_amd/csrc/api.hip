@@ -158,7 +158,7 @@ extern "C" {
 
 int64_t lrnnx_ckpt_interval(void) { return kCkptInterval; }
 int64_t lrnnx_packed_ckpt_slots(int64_t L, int64_t B) { return (L < 0 || B < 0) ? 0 : L / kCkptInterval + B; }
-int lrnnx_version(void) { return 200; }   // major * 100 + minor; the major number changes with any struct layout
+int lrnnx_version(void) { return 300; }   // major * 100 + minor; the major number changes with any struct layout
 
 int lrnnx_selective_scan_bwd_chunks(int64_t B, int64_t D, int64_t N, int64_t L, int bc_groups, int path, int complex_a) {
     const int bcg = bc_groups > 1 ? bc_groups : 1;
@@ -376,6 +376,7 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
     if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
     if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
     if (cu && path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_UNSUPPORTED;
+    if (a->max_seqlen < 0) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
@@ -435,6 +436,9 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
     p.G = pl.G;
     p.nchunks = pl.nchunks;
     p.tiles_per_chunk = pl.tiles_per_chunk;
+    if (cu && pl.nchunks == 1)
+        bwd_packed_shape(a->B, a->D, a->L, a->max_seqlen, cbwd_channels_per_group(a->B * bcg, a->D / bcg, a->N, true),
+                         a->N >= 16 ? 256 : 512, &p.G, &p.wcap, &p.gmin);
     if (pl.nchunks > 1) {
         p.ws_P = reinterpret_cast<float2 *>(static_cast<char *>(a->workspace) + carry_off);
         p.ws_Q = p.ws_P + (size_t)a->B * a->D * p.nchunks * a->N;
@@ -467,6 +471,7 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
     if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
     if (cu && path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_UNSUPPORTED;
+    if (a->max_seqlen < 0) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
     if (a->disc < 0 || a->disc > LRNNX_DISC_DIRAC) return LRNNX_ERR_INVALID_ARG;
@@ -523,6 +528,9 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     p.G = pl.G;
     p.nchunks = pl.nchunks;
     p.tiles_per_chunk = pl.tiles_per_chunk;
+    if (cu && pl.nchunks == 1)
+        bwd_packed_shape(a->B, a->D, a->L, a->max_seqlen, bwd_channels_per_group(a->B * bcg, a->D / bcg, a->N, a->L, true),
+                         2048 / bwd_waves_per_workgroup(a->N), &p.G, &p.wcap, &p.gmin);
     if (pl.nchunks > 1) {
         p.ws_P = reinterpret_cast<float *>(static_cast<char *>(a->workspace) + carry_off);
         p.ws_Q = p.ws_P + (size_t)a->B * a->D * p.nchunks * a->N;

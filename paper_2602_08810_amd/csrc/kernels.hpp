@@ -75,6 +75,7 @@ struct CBwdParams {
     float2 *ws_P, *ws_Q;
     const float2 *hc;
     const int *order;        // packed mode: sequences in the order the launch should start them, or null
+    int wcap, gmin;          // packed mode with a known longest sequence: as in BwdParams
 };
 
 struct BwdParams {
@@ -101,8 +102,19 @@ struct BwdParams {
     const float *hc;
     // packed mode: sequences in the order the launch should start them (longest first), or null for 0, 1, 2, ...
     const int *order;
+    // packed mode with a known longest sequence: cap on the channel-tiles (channels x 256-step tiles) one workgroup
+    // walks, and the fewest channels a workgroup may take (the grid is sized for that; 0: no cap, always G).  A
+    // workgroup of a long sequence then takes wcap / tiles channels, between gmin and G, and the workgroups of the
+    // launch that its sequence does not need leave at once.
+    int wcap, gmin;
 };
 constexpr int kBwdTileSteps = 256;
+constexpr int kBwdMinG = 4;
+// launch shape of a packed batch of B sequences on L steps, D channels, whose longest has max_seqlen steps (0: not
+// known, nothing changes): *G comes in as the channels per workgroup of a batch of unknown lengths and may be raised
+// to Gbal, those of a batch [B,D,L] of equal lengths; else cap and fewest channels as in BwdParams.  `places` =
+// workgroups the chip holds at once.
+void bwd_packed_shape(int B, int D, int64_t L, int64_t max_seqlen, int Gbal, int places, int *G, int *wcap, int *gmin);
 constexpr int kMaxOrdered = 256;     // packed batches of more sequences than this are not reordered
 hipError_t launch_seq_order(const int64_t *cu, int B, int64_t L, int *order, hipStream_t s);
 
@@ -172,7 +184,7 @@ hipError_t launch_ss_fwd(const FwdParams &p, int io_dtype, int disc, hipStream_t
 hipError_t launch_ss_carry(const FwdParams &p, hipStream_t s);
 hipError_t launch_ss_cfwd(const CFwdParams &p, int io_dtype, int disc, hipStream_t s);
 hipError_t launch_ss_cbwd(const CBwdParams &p, int io_dtype, int disc, hipStream_t s);
-int cbwd_channels_per_group(int B, int D, int N);
+int cbwd_channels_per_group(int B, int D, int N, bool balanced);
 hipError_t launch_ss_bwd(const BwdParams &p, int io_dtype, int disc, hipStream_t s);
 hipError_t launch_ss_bwd_agg(const BwdParams &p, int io_dtype, int disc, hipStream_t s);   // chunk aggregates -> ws_P, ws_Q
 hipError_t launch_ss_bwd_carry(const BwdParams &p, hipStream_t s);                         // ws_Q -> carries, in place
@@ -259,5 +271,6 @@ int lti_chunk_group();                       // chunks (wavefronts) of one workg
 int lti_onepass_anchor();                    // every how many groups the single-launch LTI scan publishes a true state
 int fwd_tile_steps(int io_dtype);            // time steps one workgroup covers per tile
 int bwd_channels_per_group(int B, int D, int N, int64_t L, bool balanced);
+int bwd_waves_per_workgroup(int N);
 
 }  // namespace lrnnx

@@ -67,13 +67,6 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     // packed batches: workgroups start in launch order, so the longest sequences go first and the short ones fill the
     // end of the launch instead of a long one running on alone
     const int b = p.order ? p.order[blockIdx.y] : blockIdx.y;
-    // a workgroup takes up to G consecutive channels of ONE Bm/Cm group
-    const int chunks_per_grp = (p.dpg + p.G - 1) / p.G;
-    const int grp = blockIdx.x / chunks_per_grp;
-    const int din0 = (blockIdx.x % chunks_per_grp) * p.G;
-    const int d0 = grp * p.dpg + din0;
-    const int Gact = (p.dpg - din0 < p.G) ? p.dpg - din0 : p.G;
-    const int bcrow = b * p.bcg + grp;                               // row of Bm, Cm, dBm, dCm (unpacked)
     // Packed variable-length mode (p.cu != nullptr): batch entry b is the sequence of steps cu[b] .. cu[b+1]-1 of ONE
     // packed time axis of p.L steps; I/O rows have no batch stride, the maps are [G, p.L, N].  The bounds are
     // clamped to the packed axis, so no content of cu can send an access out of the buffers.
@@ -93,6 +86,21 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
         L = (p.L - toff < span) ? p.L - toff : span;
     }
     const int64_t ntiles = (L + TILE - 1) / TILE;
+    // a workgroup takes up to G consecutive channels of ONE Bm/Cm group; in a packed batch with a work cap fewer when
+    // its sequence is long, and the workgroups of the launch that its sequence then does not need leave here, all
+    // threads together and before any barrier
+    int G = p.G;
+    if (p.wcap > 0) {
+        const int64_t fit = p.wcap / (ntiles > 0 ? ntiles : 1);
+        G = fit < p.gmin ? p.gmin : (fit < G ? (int)fit : G);
+    }
+    const int chunks_per_grp = (p.dpg + G - 1) / G;
+    if ((int)blockIdx.x >= p.bcg * chunks_per_grp) return;
+    const int grp = blockIdx.x / chunks_per_grp;
+    const int din0 = (blockIdx.x % chunks_per_grp) * G;
+    const int d0 = grp * p.dpg + din0;
+    const int Gact = (p.dpg - din0 < G) ? p.dpg - din0 : G;
+    const int bcrow = b * p.bcg + grp;                               // row of Bm, Cm, dBm, dCm (unpacked)
     // checkpoints of this workgroup's rows: [B,D,nck,N], or packed [D,nslots,N] with sequence b at slot toff/interval + b
     const int64_t nck = p.cu ? p.nslots : (p.L + kCkptInterval - 1) / kCkptInterval;
     const int64_t ck0 = p.cu ? toff / kCkptInterval + b : toff / kCkptInterval;
@@ -594,6 +602,23 @@ int bwd_channels_per_group(int B, int D, int N, int64_t, bool balanced) {
     return (int)G;
 }
 
+void bwd_packed_shape(int B, int D, int64_t L, int64_t max_seqlen, int Gbal, int places, int *G, int *wcap, int *gmin) {
+    *wcap = 0; *gmin = *G;
+    if (max_seqlen <= 0) return;
+    // what each place of the chip gets at perfect balance, in channel-tiles: D channels x the tiles of all sequences
+    // (each sequence rounded up by half a tile on average), and the channels of the longest sequence that come to that
+    const double tiles = (double)L / kBwdTileSteps + 0.5 * B;
+    const double cap = (double)D * tiles / places;
+    const int64_t longest = (max_seqlen + kBwdTileSteps - 1) / kBwdTileSteps;
+    const double fit = cap / (double)longest;
+    // sequences of about one length: the launch shape of a batch [B,D,L] (whole rounds of equal workgroups, as many
+    // channels each as that allows) is within a tenth of perfect balance and pays staging and flush less often
+    if (Gbal > *G && (double)Gbal <= 1.1 * fit) { *G = *gmin = Gbal; return; }
+    if (fit >= (double)*G || *G <= kBwdMinG) return;    // the longest sequence is no longer than a fair share: no cap
+    *wcap = cap < 1.0 ? 1 : (cap > 1e9 ? 1000000000 : (int)cap);
+    *gmin = fit < (double)kBwdMinG ? kBwdMinG : (int)fit;
+}
+
 // launch shape incl. the chunked path for few rows and long sequences (selective_bwd_carry.hip)
 BwdPlan bwd_plan(int rowsg, int dpg, int N, int64_t L, int mode, bool balanced) {
     const int G = bwd_channels_per_group(rowsg, dpg, N, L, balanced);
@@ -604,7 +629,8 @@ BwdPlan bwd_plan(int rowsg, int dpg, int N, int64_t L, int mode, bool balanced) 
 // DZ (the caller wants dz) is a template parameter: without it the kernel does not rebuild ypre = sum_n C x
 template <typename IO, int N, int NK, int DISC, int T = 8>
 static hipError_t launch_bwd_n(const BwdParams &p, hipStream_t s) {
-    dim3 grid(p.bcg * ((p.dpg + p.G - 1) / p.G), p.B, p.nchunks > 1 ? p.nchunks : 1);
+    const int gmin = p.wcap > 0 ? p.gmin : p.G;                       // fewest channels a workgroup may take
+    dim3 grid(p.bcg * ((p.dpg + gmin - 1) / gmin), p.B, p.nchunks > 1 ? p.nchunks : 1);
     if (p.dz) hipLaunchKernelGGL((k_ss_bwd<IO, N, NK, T, DISC, true>), grid, dim3((N / NK) * 64), 0, s, p);
     else hipLaunchKernelGGL((k_ss_bwd<IO, N, NK, T, DISC, false>), grid, dim3((N / NK) * 64), 0, s, p);
     return hipGetLastError();

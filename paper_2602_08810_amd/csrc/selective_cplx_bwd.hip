@@ -83,12 +83,6 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b = p.order ? p.order[blockIdx.y] : blockIdx.y;   // packed batches: the longest sequences start first
-    // a workgroup takes up to G consecutive channels of ONE Bm/Cm group
-    const int chunks_per_grp = (p.dpg + p.G - 1) / p.G;
-    const int grp = blockIdx.x / chunks_per_grp;
-    const int din0 = (blockIdx.x % chunks_per_grp) * p.G;
-    const int d0 = grp * p.dpg + din0;
-    const int Gact = (p.dpg - din0 < p.G) ? p.dpg - din0 : p.G;
     // Packed variable-length mode (p.cu != nullptr): batch entry b is the sequence of steps cu[b] .. cu[b+1]-1 of ONE
     // packed time axis of p.L steps; I/O rows have no batch stride, the maps and their gradients are [G, p.L, N].
     // The bounds are clamped to the packed axis, so no content of cu can send an access out of the buffers.
@@ -108,6 +102,20 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
         L = (p.L - toff < span) ? p.L - toff : span;
     }
     const int64_t ntiles = (L + TILE - 1) / TILE;
+    // a workgroup takes up to G consecutive channels of ONE Bm/Cm group; in a packed batch with a work cap fewer when
+    // its sequence is long, and the workgroups of the launch that its sequence then does not need leave here, all
+    // threads together and before any barrier
+    int G = p.G;
+    if (p.wcap > 0) {
+        const int64_t fit = p.wcap / (ntiles > 0 ? ntiles : 1);
+        G = fit < p.gmin ? p.gmin : (fit < G ? (int)fit : G);
+    }
+    const int chunks_per_grp = (p.dpg + G - 1) / G;
+    if ((int)blockIdx.x >= p.bcg * chunks_per_grp) return;
+    const int grp = blockIdx.x / chunks_per_grp;
+    const int din0 = (blockIdx.x % chunks_per_grp) * G;
+    const int d0 = grp * p.dpg + din0;
+    const int Gact = (p.dpg - din0 < G) ? p.dpg - din0 : G;
     // checkpoints of this workgroup's rows: [B,D,nck,N], or packed [D,nslots,N] with sequence b at slot toff/interval + b
     const int64_t nck = p.cu ? p.nslots : (p.L + kCkptInterval - 1) / kCkptInterval;
     const int64_t ck0 = p.cu ? toff / kCkptInterval + b : toff / kCkptInterval;
@@ -493,13 +501,16 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
 // channels per workgroup: aim at one workgroup per CU (256), as many channels each as fit: the staging of the maps
 // and the flush of dBm/dCm are paid once per (workgroup, tile).  Measured on B=8, D=1536, N=16, L=2048: 1.69 ms with
 // 256 workgroups, 1.76 ms with 512, 1.90 ms with 1024.
-int cbwd_channels_per_group(int B, int D, int) {
-    int64_t G = ((int64_t)B * D) / 256;
-    // never a few workgroups more than a whole number of rounds of 256 (see bwd_channels_per_group)
-    int64_t rounds = 1;
-    while ((int64_t)B * ((D + kMaxGc - 1) / kMaxGc) > rounds * 256 && rounds < 64) ++rounds;
-    const int64_t nb = rounds * 256 / B;
-    if (nb >= 1) G = (D + nb - 1) / nb;
+int cbwd_channels_per_group(int B, int D, int, bool balanced) {
+    // packed sequences of unknown lengths: four times as many workgroups, so that the short ones fill in beside the long
+    int64_t G = ((int64_t)B * D) / (balanced ? 256 : 1024);
+    if (balanced) {
+        // never a few workgroups more than a whole number of rounds of 256 (see bwd_channels_per_group)
+        int64_t rounds = 1;
+        while ((int64_t)B * ((D + kMaxGc - 1) / kMaxGc) > rounds * 256 && rounds < 64) ++rounds;
+        const int64_t nb = rounds * 256 / B;
+        if (nb >= 1) G = (D + nb - 1) / nb;
+    }
     if (G < 8) G = 8;
     if (G > kMaxGc) G = kMaxGc;
     if (G > D) G = D;
@@ -511,13 +522,14 @@ int cbwd_channels_per_group(int B, int D, int) {
 // launch shape incl. the chunked path for few rows and long sequences (selective_bwd_carry.hip): the chip holds one
 // 512-thread workgroup per CU for N = 16, two smaller ones below
 BwdPlan cbwd_plan(int rowsg, int dpg, int N, int64_t L, int mode, bool balanced) {
-    const int G = cbwd_channels_per_group(rowsg, dpg, N);
+    const int G = cbwd_channels_per_group(rowsg, dpg, N, balanced);
     return plan_time_chunks(rowsg, dpg, L, balanced ? mode : 1, G, N >= 16 ? 256 : 512, kMaxGc);
 }
 
 template <typename IO, int N, int NK, int DISC>
 static hipError_t launch_cbwd_n(const CBwdParams &p, hipStream_t s) {
-    dim3 grid(p.bcg * ((p.dpg + p.G - 1) / p.G), p.B, p.nchunks > 1 ? p.nchunks : 1);
+    const int gmin = p.wcap > 0 ? p.gmin : p.G;                       // fewest channels a workgroup may take
+    dim3 grid(p.bcg * ((p.dpg + gmin - 1) / gmin), p.B, p.nchunks > 1 ? p.nchunks : 1);
     hipLaunchKernelGGL((k_ss_cbwd<IO, N, NK, 4, DISC>), grid, dim3((N / NK) * 64), 0, s, p);
     return hipGetLastError();
 }

@@ -64,7 +64,7 @@ def test_host_queries(lib):
     assert wsc > (ckc + 255) // 256 * 256 and (wsc - (ckc + 255) // 256 * 256) % (2 * 2 * 3 * 16 * 8) == 0
     assert lib.lrnnx_workspace_bytes(8, 1, 64, 16, 8192, 1, 1, 0) > 0 and lib.lrnnx_workspace_bytes(8, 1, 64, 32, 8192, 1, 1, 0) == 0
     assert lib.lrnnx_status_string(0) == b"ok" and lib.lrnnx_status_string(3).startswith(b"workspace")
-    assert lib.lrnnx_version() >= 200
+    assert lib.lrnnx_version() >= 300
     # grouped maps plan with (B * groups) row groups of D / groups channels: the aggregates of the chunked backward
     # are sized for that plan (a multiple of two arrays [B,D,chunks,N]), and D must be a multiple of the groups
     g4 = lib.lrnnx_workspace_bytes(7, 1, 512, 16, 16384, 1, 4, 0)

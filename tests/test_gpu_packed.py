@@ -18,7 +18,7 @@ def api():
     return _api
 
 
-def _check(api, oracle, D, N, lengths, io, seed, G=1, gap=0, with_ckpt=True, disc="zoh_s6"):
+def _check(api, oracle, D, N, lengths, io, seed, G=1, gap=0, with_ckpt=True, disc="zoh_s6", max_seqlen=None):
     import torch
     p = workloads.make_packed(D=D, N=N, lengths=lengths, io=io, seed=seed, bc_groups=G, gap=gap)
     cu = torch.from_numpy(p["cu_seqlens"]).cuda()
@@ -29,7 +29,12 @@ def _check(api, oracle, D, N, lengths, io, seed, G=1, gap=0, with_ckpt=True, dis
     y, x_last, ckpt = api.lrnnx_selective_scan_fwd(**t, disc=disc, cu_seqlens=cu, return_last_state=True,
                                                    return_ckpt=True, out=y0)
     g = api.lrnnx_selective_scan_bwd(**t, dy=dev(p["dy"], io), disc=disc, cu_seqlens=cu, want_dx0=True,
-                                     ckpt=ckpt if with_ckpt else None)
+                                     ckpt=ckpt if with_ckpt else None, max_seqlen=max_seqlen)
+    if max_seqlen is not None:
+        # the hint only moves channels between workgroups: what one channel computes on its own is bit for bit the same
+        g0 = api.lrnnx_selective_scan_bwd(**t, dy=dev(p["dy"], io), disc=disc, cu_seqlens=cu, want_dx0=True, ckpt=ckpt)
+        for k in ("du", "ddelta", "dz", "dx0"):
+            assert torch.equal(g[k], g0[k]), k
     ref = {k: p[k] for k in ("u", "delta", "A", "Bm", "Cm", "Dskip", "delta_bias", "z", "x0")}
     yr, xr = oracle.selective_scan_fwd_packed(cu_seqlens=p["cu_seqlens"], disc=disc, **ref)
     r = oracle.selective_scan_bwd_packed(dy=p["dy"], cu_seqlens=p["cu_seqlens"], disc=disc, **ref)
@@ -86,6 +91,31 @@ def test_packed_other_discretisations(api, oracle, disc):
 
 def test_packed_backward_without_checkpoints(api, oracle):
     _check(api, oracle, 16, 16, (700, 300, 1500), "bf16", seed=10, with_ckpt=False)
+
+
+@pytest.mark.parametrize("hint", [1500, 1000, 100, 10**9])
+def test_packed_one_long_sequence_with_max_seqlen(api, oracle, hint):
+    """One sequence of six tiles among 32 of one tile each, on enough channels that a workgroup takes 16 of them: with
+    the longest length known (1500) the workgroups of the long sequence take 8 channels, those of the short ones 16,
+    and the workgroups of the launch the short ones do not need leave at once.  A hint that is too small (1000: the
+    long sequence still gets fewer channels than the others; 100: no effect) or far too large is as correct."""
+    lengths = (20,) * 11 + (1500,) + (20,) * 21
+    _check(api, oracle, 1024, 16, lengths, "bf16", seed=41, max_seqlen=hint)
+
+
+def test_packed_max_seqlen_is_validated(api):
+    p = workloads.make_packed(D=8, N=16, lengths=(100, 200), io="f32", seed=11)
+    import torch
+    t = dict(u=dev(p["u"]), delta=dev(p["delta"]), A=dev(p["A"]), Bm=dev(p["Bm"]), Cm=dev(p["Cm"]))
+    cu = torch.from_numpy(p["cu_seqlens"]).cuda()
+    with pytest.raises(api.LrnnxError):
+        api.lrnnx_selective_scan_bwd(**t, dy=dev(p["dy"]), cu_seqlens=cu, max_seqlen=-1)
+    # without cu_seqlens the hint is ignored
+    b = workloads.make_selective(B=2, D=8, N=16, L=300, io="f32", seed=12)
+    tb = dict(u=dev(b["u"]), delta=dev(b["delta"]), A=dev(b["A"]), Bm=dev(b["Bm"]), Cm=dev(b["Cm"]))
+    g0 = api.lrnnx_selective_scan_bwd(**tb, dy=dev(b["dy"]))
+    g1 = api.lrnnx_selective_scan_bwd(**tb, dy=dev(b["dy"]), max_seqlen=5)
+    assert torch.equal(g0["du"], g1["du"]) and torch.equal(g0["ddelta"], g1["ddelta"])
 
 
 def test_packed_boundaries_are_clamped_and_chunk_carry_is_refused(api):

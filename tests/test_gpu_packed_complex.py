@@ -34,7 +34,7 @@ def _crel(got, ref):
     return float(np.abs(np.asarray(got, dtype=np.complex128) - ref).max() / (den if den > 0 else 1.0))
 
 
-def _check(api, oracle, D, N, lengths, io, seed, G=1, gap=0, with_ckpt=True, disc="zoh_s6"):
+def _check(api, oracle, D, N, lengths, io, seed, G=1, gap=0, with_ckpt=True, disc="zoh_s6", max_seqlen=None):
     import torch
     p = workloads.make_packed_complex(D=D, N=N, lengths=lengths, io=io, seed=seed, bc_groups=G, gap=gap)
     cu = torch.from_numpy(p["cu_seqlens"]).cuda()
@@ -46,7 +46,13 @@ def _check(api, oracle, D, N, lengths, io, seed, G=1, gap=0, with_ckpt=True, dis
     y, x_last, ckpt = api.lrnnx_selective_scan_fwd_complex(**t, disc=disc, cu_seqlens=cu, return_last_state=True,
                                                            return_ckpt=True, out=y0)
     g = api.lrnnx_selective_scan_bwd_complex(**t, dy=dev(p["dy"], io), disc=disc, cu_seqlens=cu, want_dx0=True,
-                                             ckpt=ckpt if with_ckpt else None)
+                                             ckpt=ckpt if with_ckpt else None, max_seqlen=max_seqlen)
+    if max_seqlen is not None:
+        # the hint only moves channels between workgroups: what one channel computes on its own is bit for bit the same
+        g0 = api.lrnnx_selective_scan_bwd_complex(**t, dy=dev(p["dy"], io), disc=disc, cu_seqlens=cu, want_dx0=True,
+                                                  ckpt=ckpt)
+        for k in ("du", "ddelta", "dz"):
+            assert torch.equal(g[k], g0[k]), k
     torch.cuda.synchronize()
     ref = dict(u=p["u"], delta=p["delta"], A=p["A"], Bm=_cplx(p["Bm"]), Cm=_cplx(p["Cm"]), Dskip=p["Dskip"],
                delta_bias=p["delta_bias"], z=p["z"], x0=p["x0"])
@@ -94,6 +100,14 @@ def test_packed_complex_other_discretisations(api, oracle, disc):
 
 def test_packed_complex_backward_without_checkpoints(api, oracle):
     _check(api, oracle, 16, 16, (700, 300, 1500), "bf16", seed=10, with_ckpt=False)
+
+
+@pytest.mark.parametrize("hint", [1500, 10**9])
+def test_packed_complex_one_long_sequence_with_max_seqlen(api, oracle, hint):
+    """One sequence of six tiles among 32 of one tile each: with the longest length known its workgroups take 8
+    channels and those of the short sequences 24, instead of 33 each."""
+    lengths = (20,) * 11 + (1500,) + (20,) * 21
+    _check(api, oracle, 256, 16, lengths, "bf16", seed=42, max_seqlen=hint)
 
 
 def test_packed_complex_boundaries_are_clamped(api):
