@@ -252,7 +252,11 @@ typedef struct lrnnx_ss_bwd_args {
                                     (three launches: adjoint aggregate per chunk, chain, backward per chunk), for long
                                     sequences with few rows; needs the workspace.  SINGLE_PASS: one workgroup walks a
                                     whole row.  AUTO picks CHUNK_CARRY when a single pass would leave most of the chip
-                                    idle and the workspace allows it.  Not with cu_seqlens (single pass). */
+                                    idle and the workspace allows it.  With cu_seqlens every sequence is cut into
+                                    chunks of one size counted from its own start (the last chunk of a sequence takes
+                                    what is left), planned for B sequences of max_seqlen steps (of L steps if that is
+                                    0) and for no more chunks than the workspace holds; AUTO then picks CHUNK_CARRY
+                                    only when max_seqlen is given. */
     const int64_t *cu_seqlens;   /* as in the forward call (then dBm, dCm are [G,L,N]), or NULL.  In packed mode the
                                     workspace also holds B ints that let the launch start the longest sequences first
                                     (batches of up to 256 sequences), which shortens its tail; a workspace without
@@ -262,7 +266,8 @@ typedef struct lrnnx_ss_bwd_args {
                                     workgroups of sequences much longer than the average take fewer channels each, so
                                     that one long sequence does not set the time of the whole launch; a value that is
                                     too small only loses that balance, a value that is too large costs some idle
-                                    workgroups.  Ignored without cu_seqlens. */
+                                    workgroups.  The chunks of CHUNK_CARRY are planned from it as well (see path).
+                                    Ignored without cu_seqlens. */
     const void *u;      int64_t u_stride_b, u_stride_d;
     const void *delta;  int64_t delta_stride_b, delta_stride_d;
     const float *A;
@@ -492,7 +497,8 @@ typedef enum { LRNNX_WS_FWD = 0, LRNNX_WS_BWD = 1, LRNNX_WS_LTI = 2, LRNNX_WS_LT
 
 /* Bytes of device scratch the call may need (the largest over its paths).  bc_groups as in the call's struct (0 or 1:
  * none); packed != 0: the call will be given cu_seqlens (B sequences on one time axis of L steps; the backward kinds
- * then cover the checkpoints of the recompute sweep in the packed layout and the B ints of the launch order).
+ * then cover the checkpoints of the recompute sweep in the packed layout, and the larger of the B ints of the launch
+ * order and the chunk aggregates as planned for sequences of L steps).
  * For LRNNX_WS_LTI, LRNNX_WS_LTI_BWD, LRNNX_WS_DIAG and LRNNX_WS_DIAG_BWD pass P as D and 0 for N, bc_groups and packed
  * (the DIAG kinds: io_dtype is LRNNX_F32 or LRNNX_C64).  Returns 0 for invalid sizes and for calls that need none.   */
 size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t L, int io_dtype, int bc_groups,

@@ -547,7 +547,8 @@ def lrnnx_selective_scan_bwd(u, delta, A, Bm, Cm, dy, Dskip=None, delta_bias=Non
     `cu_seqlens`: packed variable-length mode as in the forward call (du, ddelta, dz are [D,L]; dBm, dCm as Bm).
     `path`: "auto", "single_pass" or "chunk_carry" (time axis cut into chunks that run side by side).
     `max_seqlen`: packed mode, the longest sequence of the batch if the host knows it (a hint for the launch shape
-    that keeps one long sequence from setting the time of the whole launch; the lengths themselves stay on the device)."""
+    that keeps one long sequence from setting the time of the whole launch, and lets "auto" cut a few long sequences
+    into chunks; the lengths themselves stay on the device)."""
     io = u.dtype
     packed = cu_seqlens is not None
     if packed:

@@ -120,6 +120,30 @@ size_t cbwd_carry_bytes(int64_t B, int64_t D, int64_t N, int64_t L) {    // the 
 }
 size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 
+// Launch plan of a backward call.  A batch [B,D,L] is planned as it is.  Of a packed batch the host knows the number of
+// sequences and the length of the time axis, and max_seqlen if the caller gave it (else 0): the single pass is planned
+// for sequences of unknown, unequal lengths; chunks of the time axis are planned for B sequences of max_seqlen steps
+// (of the whole axis without it) when the caller asks for them, and on its own account only when max_seqlen is known.
+// Every chunk but the last of a sequence has the planned number of steps and the last takes what is left, so a
+// max_seqlen that is too small costs balance, never steps.
+template <typename Plan>
+BwdPlan packed_bwd_plan(Plan plan, int rowsg, int dpg, int N, int64_t L, int path, bool packed, int64_t max_seqlen) {
+    if (!packed) return plan(rowsg, dpg, N, L, path, true);
+    const bool known = max_seqlen > 0;
+    if (path == LRNNX_PATH_CHUNK_CARRY || (path == LRNNX_PATH_AUTO && known)) {
+        const BwdPlan pc = plan(rowsg, dpg, N, known && max_seqlen < L ? max_seqlen : L, path, true);
+        if (pc.nchunks > 1) return pc;
+    }
+    return plan(rowsg, dpg, N, L, LRNNX_PATH_SINGLE_PASS, false);
+}
+// at most `nfit` chunks (what the workspace holds): fewer, longer chunks of whole tiles
+void fit_chunks(BwdPlan &pl, size_t nfit) {
+    if (nfit >= (size_t)pl.nchunks || nfit < 2) return;
+    const int64_t ntiles = pl.tiles_per_chunk * pl.nchunks;          // an upper bound of the planned tiles
+    pl.tiles_per_chunk = (ntiles + (int64_t)nfit - 1) / (int64_t)nfit;
+    pl.nchunks = (int)nfit;
+}
+
 // The real and the complex backward entry points take the same per-row tensors (same field names in both argument
 // structs and both parameter blocks): checks and marshalling are written once.
 template <typename Args>
@@ -209,8 +233,9 @@ size_t lrnnx_workspace_bytes(int which, int64_t B, int64_t D, int64_t N, int64_t
         size_t ck = 0;
         if (which != LRNNX_WS_BWD_CARRY)
             ck = align256((size_t)(packed ? D * lrnnx_packed_ckpt_slots(L, B) : B * D * cdiv(L, kCkptInterval)) * N * es);
-        if (packed) return ck + sizeof(int) * (size_t)B;
-        return ck + (cplx ? cbwd_carry_bytes(B * bcg, D / bcg, N, L) : bwd_carry_bytes(B * bcg, D / bcg, N, L));
+        const size_t carry = cplx ? cbwd_carry_bytes(B * bcg, D / bcg, N, L) : bwd_carry_bytes(B * bcg, D / bcg, N, L);
+        const size_t order = packed ? sizeof(int) * (size_t)B : 0;
+        return ck + (carry > order ? carry : order);
     }
     if (which == LRNNX_WS_LTI) {
         const int nch = lti_chunks(B, D, L);
@@ -375,7 +400,6 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
     const int path = a->path;
     if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
     if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
-    if (cu && path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_UNSUPPORTED;
     if (a->max_seqlen < 0) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
@@ -397,13 +421,15 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
     hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
 
     // chunked path: the aggregates live in the workspace, after the checkpoints of the recompute sweep if there are any
-    BwdPlan pl = cbwd_plan(a->B * bcg, a->D / bcg, a->N, a->L, path, cu == nullptr);
+    BwdPlan pl = packed_bwd_plan(cbwd_plan, a->B * bcg, a->D / bcg, a->N, a->L, path, cu != nullptr, a->max_seqlen);
     const size_t carry_off = a->ckpt ? 0 : align256(ck_bytes);
     if (pl.nchunks > 1) {
-        const size_t need = carry_off + (size_t)2 * a->B * a->D * pl.nchunks * a->N * sizeof(float2);
-        if (!a->workspace || a->workspace_bytes < need) {
+        const size_t per_chunk = (size_t)2 * a->B * a->D * a->N * sizeof(float2);
+        const size_t room = (a->workspace && a->workspace_bytes > carry_off) ? a->workspace_bytes - carry_off : 0;
+        if (cu) fit_chunks(pl, room / per_chunk);
+        if (pl.nchunks > 1 && room < per_chunk * pl.nchunks) {
             if (path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_WORKSPACE;
-            pl = cbwd_plan(a->B * bcg, a->D / bcg, a->N, a->L, LRNNX_PATH_SINGLE_PASS, true);
+            pl = cbwd_plan(a->B * bcg, a->D / bcg, a->N, a->L, LRNNX_PATH_SINGLE_PASS, cu == nullptr);
         }
     }
 
@@ -447,7 +473,8 @@ int lrnnx_selective_scan_bwd_complex(const lrnnx_ss_bwd_complex_args *a) {
         if (launch_ss_cbwd_carry(p, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
     }
     // packed batches: longest sequences first, if the workspace has room for the order (as in the real backward)
-    if (cu && a->B > 1 && a->B <= kMaxOrdered && a->workspace && a->workspace_bytes >= carry_off + sizeof(int) * (size_t)a->B) {
+    if (cu && pl.nchunks == 1 && a->B > 1 && a->B <= kMaxOrdered && a->workspace &&
+        a->workspace_bytes >= carry_off + sizeof(int) * (size_t)a->B) {
         int *order = reinterpret_cast<int *>(static_cast<char *>(a->workspace) + carry_off);
         if (launch_seq_order(cu, a->B, a->L, order, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
         p.order = order;
@@ -470,7 +497,6 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     const int path = a->path;
     if (cu && (reinterpret_cast<uintptr_t>(cu) & 7u)) return LRNNX_ERR_INVALID_ARG;
     if (path < LRNNX_PATH_AUTO || path > LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_INVALID_ARG;
-    if (cu && path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_UNSUPPORTED;
     if (a->max_seqlen < 0) return LRNNX_ERR_INVALID_ARG;
     if (a->B < 1 || a->D < 1 || a->N < 1 || a->L < 1) return LRNNX_ERR_INVALID_ARG;
     if (a->io_dtype != LRNNX_F32 && a->io_dtype != LRNNX_BF16) return LRNNX_ERR_INVALID_ARG;
@@ -492,13 +518,15 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     hipStream_t s = reinterpret_cast<hipStream_t>(a->stream);
 
     // chunked path: the aggregates live in the workspace, after the checkpoints of the recompute sweep if there are any
-    BwdPlan pl = bwd_plan(a->B * bcg, a->D / bcg, a->N, a->L, path, cu == nullptr);
+    BwdPlan pl = packed_bwd_plan(bwd_plan, a->B * bcg, a->D / bcg, a->N, a->L, path, cu != nullptr, a->max_seqlen);
     const size_t carry_off = a->ckpt ? 0 : align256(ck_bytes);
     if (pl.nchunks > 1) {
-        const size_t need = carry_off + (size_t)2 * a->B * a->D * pl.nchunks * a->N * sizeof(float);
-        if (!a->workspace || a->workspace_bytes < need) {
+        const size_t per_chunk = (size_t)2 * a->B * a->D * a->N * sizeof(float);
+        const size_t room = (a->workspace && a->workspace_bytes > carry_off) ? a->workspace_bytes - carry_off : 0;
+        if (cu) fit_chunks(pl, room / per_chunk);
+        if (pl.nchunks > 1 && room < per_chunk * pl.nchunks) {
             if (path == LRNNX_PATH_CHUNK_CARRY) return LRNNX_ERR_WORKSPACE;
-            pl = bwd_plan(a->B * bcg, a->D / bcg, a->N, a->L, LRNNX_PATH_SINGLE_PASS, true);
+            pl = bwd_plan(a->B * bcg, a->D / bcg, a->N, a->L, LRNNX_PATH_SINGLE_PASS, cu == nullptr);
         }
     }
 
@@ -540,7 +568,8 @@ int lrnnx_selective_scan_bwd(const lrnnx_ss_bwd_args *a) {
     }
     // packed batches: longest sequences first, if the workspace has room for the order (B ints, after the checkpoints
     // of the recompute sweep if there are any)
-    if (cu && a->B > 1 && a->B <= kMaxOrdered && a->workspace && a->workspace_bytes >= carry_off + sizeof(int) * (size_t)a->B) {
+    if (cu && pl.nchunks == 1 && a->B > 1 && a->B <= kMaxOrdered && a->workspace &&
+        a->workspace_bytes >= carry_off + sizeof(int) * (size_t)a->B) {
         int *order = reinterpret_cast<int *>(static_cast<char *>(a->workspace) + carry_off);
         if (launch_seq_order(cu, a->B, a->L, order, s) != hipSuccess) return LRNNX_ERR_LAUNCH;
         p.order = order;

@@ -21,6 +21,28 @@
 
 namespace lrnnx {
 
+// Steps of chunk `chunk` of batch entry b: Lc steps from step s0 of the time axis on, in row bs of the [B,D,L] tensors.
+// Chunks are counted from the start of the sequence, `span` steps each; the last one takes whatever is left, so a
+// chunk count planned for a shorter longest sequence than the batch really has (packed mode: the lengths are on the
+// device) still covers every step.  Packed mode (cu != nullptr): sequence b lies at cu[b] .. cu[b+1]-1 of ONE time
+// axis of L steps (bounds clamped to it), the rows have no batch stride (bs = 0), and a sequence that ends before
+// the chunk starts has Lc = 0.
+__device__ __forceinline__ void chunk_span(const int64_t *cu, int b, int64_t L, int chunk, int nchunks, int64_t span,
+                                           int64_t &s0, int64_t &Lc, int64_t &bs) {
+    int64_t o = 0, e = L;
+    bs = b;
+    if (cu) {
+        o = cu[b]; e = cu[b + 1];
+        o = o < 0 ? 0 : (o > L ? L : o);
+        e = e < o ? o : (e > L ? L : e);
+        bs = 0;
+    }
+    const int64_t c0 = (int64_t)chunk * span;
+    const int64_t left = e - o - c0;
+    s0 = o + (left > 0 ? c0 : 0);
+    Lc = left <= 0 ? 0 : ((chunk == nchunks - 1 || left < span) ? left : span);
+}
+
 template <typename IO, int N, int DISC>
 __global__ __launch_bounds__(512, 2) void k_ss_bwd_agg(const BwdParams p) {
     constexpr int T = 8, W = 8;
@@ -41,18 +63,18 @@ __global__ __launch_bounds__(512, 2) void k_ss_bwd_agg(const BwdParams p) {
     const int d_in = (blockIdx.x % blk_per_grp) * W + w;
     const bool active = d_in < p.dpg;
     const int d = grp * p.dpg + (active ? d_in : p.dpg - 1);
-    // the chunk's steps [s0, s1) of the sequence; s0 is a multiple of the backward tile (256 steps)
-    const int64_t s0 = (int64_t)chunk * p.tiles_per_chunk * kBwdTileSteps;
-    const int64_t s1 = (s0 + p.tiles_per_chunk * kBwdTileSteps < p.L) ? s0 + p.tiles_per_chunk * kBwdTileSteps : p.L;
-    const int64_t Lc = s1 - s0;
-    const int64_t ntiles = (Lc + TILE - 1) / TILE;
+    // the chunk's Lc steps of the sequence, from step s0 of the time axis on; the chunk starts a multiple of the
+    // backward tile (256 steps) after the start of its sequence
+    int64_t s0, Lc, bs;
+    chunk_span(p.cu, b, p.L, chunk, p.nchunks, p.tiles_per_chunk * kBwdTileSteps, s0, Lc, bs);
+    const int64_t ntiles = (Lc + TILE - 1) / TILE;     // none for a packed sequence that ends before this chunk: the pair stays (1, 0)
     const bool vec = p.vec != 0;
     const bool has_z = p.z != nullptr;
 
-    const IO *drow = reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd + s0;
-    const IO *gyrow = reinterpret_cast<const IO *>(p.dy) + b * p.dy_sb + d * p.dy_sd + s0;
-    const IO *zrow = has_z ? reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd + s0 : nullptr;
-    const IO *Cm = reinterpret_cast<const IO *>(p.Cm) + (((int64_t)b * p.bcg + grp) * p.L + s0) * N;
+    const IO *drow = reinterpret_cast<const IO *>(p.delta) + bs * p.dl_sb + d * p.dl_sd + s0;
+    const IO *gyrow = reinterpret_cast<const IO *>(p.dy) + bs * p.dy_sb + d * p.dy_sd + s0;
+    const IO *zrow = has_z ? reinterpret_cast<const IO *>(p.z) + bs * p.z_sb + d * p.z_sd + s0 : nullptr;
+    const IO *Cm = reinterpret_cast<const IO *>(p.Cm) + ((bs * p.bcg + grp) * p.L + s0) * N;
 
     // lane n holds A[d,n] and the chunk's pair of state n
     const float Av = (lane < N) ? p.A[d * N + lane] : 0.0f;
@@ -171,17 +193,16 @@ __global__ __launch_bounds__(512, 2) void k_ss_cbwd_agg(const CBwdParams p) {
     const int d_in = (blockIdx.x % blk_per_grp) * W + w;
     const bool active = d_in < p.dpg;
     const int d = grp * p.dpg + (active ? d_in : p.dpg - 1);
-    const int64_t s0 = (int64_t)chunk * p.tiles_per_chunk * kBwdTileSteps;
-    const int64_t s1 = (s0 + p.tiles_per_chunk * kBwdTileSteps < p.L) ? s0 + p.tiles_per_chunk * kBwdTileSteps : p.L;
-    const int64_t Lc = s1 - s0;
+    int64_t s0, Lc, bs;                                // as in k_ss_bwd_agg
+    chunk_span(p.cu, b, p.L, chunk, p.nchunks, p.tiles_per_chunk * kBwdTileSteps, s0, Lc, bs);
     const int64_t ntiles = (Lc + TILE - 1) / TILE;
     const bool vec = p.vec != 0;
     const bool has_z = p.z != nullptr;
 
-    const IO *drow = reinterpret_cast<const IO *>(p.delta) + b * p.dl_sb + d * p.dl_sd + s0;
-    const IO *gyrow = reinterpret_cast<const IO *>(p.dy) + b * p.dy_sb + d * p.dy_sd + s0;
-    const IO *zrow = has_z ? reinterpret_cast<const IO *>(p.z) + b * p.z_sb + d * p.z_sd + s0 : nullptr;
-    const CW *Cm = reinterpret_cast<const CW *>(p.Cm) + (((int64_t)b * p.bcg + grp) * p.L + s0) * N;
+    const IO *drow = reinterpret_cast<const IO *>(p.delta) + bs * p.dl_sb + d * p.dl_sd + s0;
+    const IO *gyrow = reinterpret_cast<const IO *>(p.dy) + bs * p.dy_sb + d * p.dy_sd + s0;
+    const IO *zrow = has_z ? reinterpret_cast<const IO *>(p.z) + bs * p.z_sb + d * p.z_sd + s0 : nullptr;
+    const CW *Cm = reinterpret_cast<const CW *>(p.Cm) + ((bs * p.bcg + grp) * p.L + s0) * N;
 
     // lane n holds A[d,n] and the chunk's pair of state n
     float Arv = 0.0f, Aiv = 0.0f;

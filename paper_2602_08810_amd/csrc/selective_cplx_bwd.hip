@@ -94,12 +94,16 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
         toff = o; L = e - o; bs = 0;
     }
     // Chunked launch: this workgroup walks chunk blockIdx.z of its rows only, i.e. the steps toff .. toff + L - 1 of
-    // the sequence, starting from that chunk's carried adjoint.
+    // the time axis, starting from that chunk's carried adjoint.  Chunks are counted from the start of the sequence;
+    // the last one takes whatever is left (see chunk_span in selective_bwd_carry.hip), and the workgroups of a packed
+    // sequence that ends before their chunk leave here, all threads together and before any barrier.
     const int chunk = blockIdx.z;
     if (p.nchunks > 1) {
         const int64_t span = p.tiles_per_chunk * TILE;
-        toff = chunk * span;
-        L = (p.L - toff < span) ? p.L - toff : span;
+        const int64_t left = L - chunk * span;
+        if (left <= 0) return;
+        toff += chunk * span;
+        L = (chunk == p.nchunks - 1 || left < span) ? left : span;
     }
     const int64_t ntiles = (L + TILE - 1) / TILE;
     // a workgroup takes up to G consecutive channels of ONE Bm/Cm group; in a packed batch with a work cap fewer when

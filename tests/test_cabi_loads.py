@@ -69,12 +69,17 @@ def test_host_queries(lib):
     # are sized for that plan (a multiple of two arrays [B,D,chunks,N]), and D must be a multiple of the groups
     g4 = lib.lrnnx_workspace_bytes(7, 1, 512, 16, 16384, 1, 4, 0)
     assert g4 > 0 and g4 % (2 * 512 * 16 * 4) == 0 and lib.lrnnx_workspace_bytes(7, 1, 510, 16, 16384, 1, 4, 0) == 0
-    # packed batches: checkpoints [D, L / interval + B, N] of the recompute sweep, then B ints of launch order; the
-    # forward call needs none (single pass only)
+    # packed batches: checkpoints [D, L / interval + B, N] of the recompute sweep, then the larger of the B ints of
+    # launch order and the chunk aggregates [B,D,chunks,N] x 2 as planned for sequences of L steps; the forward call
+    # needs none (single pass only)
     slots = 1024 // I + 3
-    assert lib.lrnnx_workspace_bytes(1, 3, 8, 16, 1024, 1, 1, 1) == (8 * slots * 16 * 4 + 255) // 256 * 256 + 4 * 3
-    assert lib.lrnnx_workspace_bytes(7, 3, 8, 16, 1024, 1, 1, 1) == 4 * 3
-    assert lib.lrnnx_workspace_bytes(6, 3, 8, 16, 1024, 1, 1, 1) == (8 * slots * 16 * 8 + 255) // 256 * 256 + 4 * 3
+    nch = chunks(3, 8, 16, 1024, 1, 2, 0)
+    assert nch > 1 and chunks(3, 8, 16, 1024, 1, 0, 0) <= nch
+    assert lib.lrnnx_workspace_bytes(1, 3, 8, 16, 1024, 1, 1, 1) == (8 * slots * 16 * 4 + 255) // 256 * 256 + 2 * 3 * 8 * nch * 16 * 4
+    assert lib.lrnnx_workspace_bytes(7, 3, 8, 16, 1024, 1, 1, 1) == 2 * 3 * 8 * nch * 16 * 4
+    nchc = chunks(3, 8, 16, 1024, 1, 2, 1)
+    assert lib.lrnnx_workspace_bytes(6, 3, 8, 16, 1024, 1, 1, 1) == (8 * slots * 16 * 8 + 255) // 256 * 256 + 2 * 3 * 8 * nchc * 16 * 8
+    assert lib.lrnnx_workspace_bytes(7, 300, 8, 16, 256, 1, 1, 1) == 4 * 300     # one tile: no chunks, the launch order
     assert lib.lrnnx_workspace_bytes(0, 3, 8, 16, 1024, 1, 1, 1) == 0
     assert lib.lrnnx_static_scratch_bytes() == 4 << 20
 
@@ -205,7 +210,9 @@ def test_host_side_validation_of_the_backward_and_lti_calls(lib):
     assert bwd(bc_groups=3) == 1 and bwd(bc_groups=-1) == 1
     assert bwd(path=9) == 1 and bwd(path=-1) == 1
     assert bwd(path=2, L=2000, du_stride_d=2000, ddelta_stride_d=2000) == 3   # the chunked path keeps its aggregates in the workspace
-    assert bwd(path=2, cu_seqlens=fake) == 2                  # ... and is not offered for packed batches
+    # ... also for a packed batch (du, ddelta [D,L]), where max_seqlen is a hint that must not be negative
+    assert bwd(path=2, cu_seqlens=fake, L=2000, du_stride_d=2000, ddelta_stride_d=2000) == 3
+    assert bwd(cu_seqlens=fake, max_seqlen=-1) == 1
 
     def lti(**over):
         a = api.LtiArgs()
@@ -282,7 +289,8 @@ def test_host_side_validation_of_the_complex_calls(lib):
     assert bwd(dz=fake) == 1 and bwd(dD=fake) == 1 and bwd(dbias=fake) == 1
     assert bwd(dA=0x10004) == 1 and bwd(dx0=0x10004) == 1 and bwd(dCm=0x10008) == 1
     assert bwd(cu_seqlens=0x10004) == 1 and bwd(bc_groups=5) == 1
-    assert bwd(path=4) == 1 and bwd(path=2, cu_seqlens=fake) == 2
+    assert bwd(path=4) == 1 and bwd(cu_seqlens=fake, max_seqlen=-1) == 1
+    assert bwd(path=2, cu_seqlens=fake, L=2000, du_stride_d=2000, ddelta_stride_d=2000) == 3
     assert bwd(path=2, L=2000, du_stride_d=2000, ddelta_stride_d=2000) == 3
     assert bwd(size=ctypes.sizeof(api.BwdComplexArgs) + 16) == 1
     # packed mode sizes the recompute workspace by D * (L / interval + B) * N float pairs

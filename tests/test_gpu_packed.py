@@ -18,7 +18,8 @@ def api():
     return _api
 
 
-def _check(api, oracle, D, N, lengths, io, seed, G=1, gap=0, with_ckpt=True, disc="zoh_s6", max_seqlen=None):
+def _check(api, oracle, D, N, lengths, io, seed, G=1, gap=0, with_ckpt=True, disc="zoh_s6", max_seqlen=None,
+           path="auto", same_bits=True):
     import torch
     p = workloads.make_packed(D=D, N=N, lengths=lengths, io=io, seed=seed, bc_groups=G, gap=gap)
     cu = torch.from_numpy(p["cu_seqlens"]).cuda()
@@ -29,8 +30,8 @@ def _check(api, oracle, D, N, lengths, io, seed, G=1, gap=0, with_ckpt=True, dis
     y, x_last, ckpt = api.lrnnx_selective_scan_fwd(**t, disc=disc, cu_seqlens=cu, return_last_state=True,
                                                    return_ckpt=True, out=y0)
     g = api.lrnnx_selective_scan_bwd(**t, dy=dev(p["dy"], io), disc=disc, cu_seqlens=cu, want_dx0=True,
-                                     ckpt=ckpt if with_ckpt else None, max_seqlen=max_seqlen)
-    if max_seqlen is not None:
+                                     ckpt=ckpt if with_ckpt else None, max_seqlen=max_seqlen, path=path)
+    if max_seqlen is not None and path == "auto" and same_bits:
         # the hint only moves channels between workgroups: what one channel computes on its own is bit for bit the same
         g0 = api.lrnnx_selective_scan_bwd(**t, dy=dev(p["dy"], io), disc=disc, cu_seqlens=cu, want_dx0=True, ckpt=ckpt)
         for k in ("du", "ddelta", "dz", "dx0"):
@@ -101,6 +102,29 @@ def test_packed_one_long_sequence_with_max_seqlen(api, oracle, hint):
     long sequence still gets fewer channels than the others; 100: no effect) or far too large is as correct."""
     lengths = (20,) * 11 + (1500,) + (20,) * 21
     _check(api, oracle, 1024, 16, lengths, "bf16", seed=41, max_seqlen=hint)
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("hint", [None, 5000, 1000])
+def test_packed_backward_in_chunks(api, oracle, hint, io):
+    """The chunked backward on a packed batch: every sequence cut into chunks counted from its own start, planned for
+    the longest length the caller names (5000), for the whole axis (no hint), or for a length that is too small (1000:
+    the last chunk of the longer sequences then takes what is left).  Sequences of 10 and 700 steps end before most
+    chunks start; 3000 and 5000 are not multiples of the chunk."""
+    lengths = (3000, 700, 5000, 10)
+    planned = min(hint or sum(lengths), sum(lengths))
+    assert api.lib().lrnnx_selective_scan_bwd_chunks(len(lengths), 16, 16, planned, 1, 2, 0) > 1
+    _check(api, oracle, 16, 16, lengths, io, seed=51, max_seqlen=hint, path="chunk_carry")
+
+
+def test_packed_backward_in_chunks_variants(api, oracle):
+    """Grouped maps with unused steps around the sequences, no checkpoints from the forward call, a small state, and
+    the automatic choice (which cuts a packed batch into chunks only when it is told the longest length)."""
+    _check(api, oracle, 24, 16, (2100, 900, 40), "bf16", seed=52, G=3, gap=5, path="chunk_carry")
+    _check(api, oracle, 16, 16, (700, 300, 1500), "bf16", seed=53, with_ckpt=False, path="chunk_carry", max_seqlen=1500)
+    _check(api, oracle, 13, 4, (100, 2600, 257), "f32", seed=54, path="chunk_carry")
+    assert api.lib().lrnnx_selective_scan_bwd_chunks(2, 32, 16, 6000, 1, 0, 0) > 1
+    _check(api, oracle, 32, 16, (6000, 5000), "bf16", seed=55, max_seqlen=6000, same_bits=False)
 
 
 def test_packed_max_seqlen_is_validated(api):

@@ -34,7 +34,8 @@ def _crel(got, ref):
     return float(np.abs(np.asarray(got, dtype=np.complex128) - ref).max() / (den if den > 0 else 1.0))
 
 
-def _check(api, oracle, D, N, lengths, io, seed, G=1, gap=0, with_ckpt=True, disc="zoh_s6", max_seqlen=None):
+def _check(api, oracle, D, N, lengths, io, seed, G=1, gap=0, with_ckpt=True, disc="zoh_s6", max_seqlen=None,
+           path="auto"):
     import torch
     p = workloads.make_packed_complex(D=D, N=N, lengths=lengths, io=io, seed=seed, bc_groups=G, gap=gap)
     cu = torch.from_numpy(p["cu_seqlens"]).cuda()
@@ -46,8 +47,8 @@ def _check(api, oracle, D, N, lengths, io, seed, G=1, gap=0, with_ckpt=True, dis
     y, x_last, ckpt = api.lrnnx_selective_scan_fwd_complex(**t, disc=disc, cu_seqlens=cu, return_last_state=True,
                                                            return_ckpt=True, out=y0)
     g = api.lrnnx_selective_scan_bwd_complex(**t, dy=dev(p["dy"], io), disc=disc, cu_seqlens=cu, want_dx0=True,
-                                             ckpt=ckpt if with_ckpt else None, max_seqlen=max_seqlen)
-    if max_seqlen is not None:
+                                             ckpt=ckpt if with_ckpt else None, max_seqlen=max_seqlen, path=path)
+    if max_seqlen is not None and path == "auto":
         # the hint only moves channels between workgroups: what one channel computes on its own is bit for bit the same
         g0 = api.lrnnx_selective_scan_bwd_complex(**t, dy=dev(p["dy"], io), disc=disc, cu_seqlens=cu, want_dx0=True,
                                                   ckpt=ckpt)
@@ -108,6 +109,21 @@ def test_packed_complex_one_long_sequence_with_max_seqlen(api, oracle, hint):
     channels and those of the short sequences 24, instead of 33 each."""
     lengths = (20,) * 11 + (1500,) + (20,) * 21
     _check(api, oracle, 256, 16, lengths, "bf16", seed=42, max_seqlen=hint)
+
+
+@pytest.mark.parametrize("hint", [None, 5000, 1000])
+def test_packed_complex_backward_in_chunks(api, oracle, hint):
+    """The chunked backward on a packed batch, chunks planned for the longest length the caller names, for the whole
+    axis, or for a length that is too small (the last chunk of a longer sequence takes what is left)."""
+    lengths = (3000, 700, 5000, 10)
+    planned = min(hint or sum(lengths), sum(lengths))
+    assert api.lib().lrnnx_selective_scan_bwd_chunks(len(lengths), 16, 16, planned, 1, 2, 1) > 1
+    _check(api, oracle, 16, 16, lengths, "bf16", seed=61, max_seqlen=hint, path="chunk_carry")
+
+
+def test_packed_complex_backward_in_chunks_variants(api, oracle):
+    _check(api, oracle, 24, 8, (2100, 900, 40), "f32", seed=62, G=3, gap=5, path="chunk_carry")
+    _check(api, oracle, 16, 16, (700, 300, 1500), "bf16", seed=63, with_ckpt=False, path="chunk_carry", max_seqlen=1500)
 
 
 def test_packed_complex_boundaries_are_clamped(api):
