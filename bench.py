@@ -495,6 +495,20 @@ def _other_configs(api, torch, dev):
                                  "hbm_frac": nb / tt / 1e9 / HBM_PEAK_GBS}
     del tf32, dyf, yf, ckf, outs_f
 
+    # config 2's shape under the other discretisation schemes (Sec. 3): exact zero-order hold, bilinear, dirac
+    td = sel(Bf, Df, Nf, Lf, True)
+    dyd = torch.randn(Bf, Df, Lf, device=dev, generator=g).to(bf)
+    yd = torch.empty_like(td["u"])
+    for disc in ("zoh", "bilinear", "dirac"):
+        _, ckd = api.lrnnx_selective_scan_fwd(**td, out=yd, return_ckpt=True, disc=disc)
+        outs_d = {}
+        tf_ = _time(torch, lambda: api.lrnnx_selective_scan_fwd(**td, out=yd, ckpt_out=ckd, disc=disc), 10)
+        tb_ = _time(torch, lambda: outs_d.update(api.lrnnx_selective_scan_bwd(**td, dy=dyd, ckpt=ckd, outs=outs_d, disc=disc)), 10)
+        out[f"c2_shape_{disc}"] = {"fwd_us": tf_ * 1e6, "bwd_us": tb_ * 1e6,
+                                   "elements_per_s": 2 * Bf * Df * Nf * Lf / (tf_ + tb_)}
+        del ckd, outs_d
+    del td, dyd, yd
+
     # config 4: backward only (checkpoints from one untimed forward)
     B4, D4, N4, L4 = 16, 2560, 16, 4096
     t4 = sel(B4, D4, N4, L4, True)

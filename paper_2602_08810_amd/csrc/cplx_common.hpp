@@ -130,8 +130,7 @@ __device__ __forceinline__ void cdisc_partials(float dt, const CCoef &c, float2 
                                                float2 &a_t, float2 &a_A, float2 &g_t, float2 &g_A) {
     const float2 Ac = make_float2(c.Ar, c.Ai);
     if constexpr (DISC == DISC_BILINEAR) {
-        const float r = (dt != 0.0f) ? rcp_fast(dt) : 0.0f;
-        const float2 q = (dt != 0.0f) ? make_float2(g.x * r, g.y * r) : make_float2(1.0f, 0.0f);   // 1 / (1 - dt A / 2)
+        const float2 q = make_float2(__builtin_fmaf(a.x, 0.5f, 0.5f), 0.5f * a.y);   // 1 / (1 - dt A / 2) = (a + 1) / 2
         const float2 q2 = cxmul(q, q);
         a_t = cxmul(Ac, q2);
         a_A = make_float2(dt * q2.x, dt * q2.y);

@@ -124,7 +124,7 @@ template <int DISC>
 __device__ __forceinline__ void disc_partials(float dt, const ACoef &c, float a, float g,
                                               float &a_t, float &a_A, float &g_t, float &g_A) {
     if constexpr (DISC == DISC_BILINEAR) {
-        const float q = rcp_fast(__builtin_fmaf(-dt, c.hA, 1.0f));   // 1 / (1 - dt A / 2), as in disc_ag
+        const float q = __builtin_fmaf(a, 0.5f, 0.5f);               // 1 / (1 - dt A / 2) = (a + 1) / 2
         const float q2 = q * q;
         a_t = c.A * q2; a_A = dt * q2; g_t = q2; g_A = 0.5f * dt * dt * q2;
     } else {

@@ -407,8 +407,9 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
                         else pdd[t] = __builtin_fmaf(dax, ac.A, __builtin_fmaf(dg, a[k][t], pdd[t]));
                         dA_part = __builtin_fmaf(dax, dl[t], __builtin_fmaf(dg, g_A, dA_part));
                     } else {
-                        // bilinear: with q = 1 / (1 - Delta A / 2) all four partials are multiples of q^2
-                        const float q = rcp_fast(__builtin_fmaf(-dl[t], ac.hA, 1.0f));
+                        // bilinear: with q = 1 / (1 - Delta A / 2) all four partials are multiples of q^2, and
+                        // a = (1 + Delta A / 2) q gives q = (a + 1) / 2 without a second reciprocal
+                        const float q = __builtin_fmaf(a[k][t], 0.5f, 0.5f);
                         const float q2 = q * q;
                         const float da = R * xprev;
                         const float hb = R * Bk[k][t];
