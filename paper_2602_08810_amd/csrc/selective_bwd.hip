@@ -80,12 +80,13 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     // Chunked launch: this workgroup walks chunk blockIdx.z of its rows only, i.e. the steps toff .. toff + L - 1 of
     // the time axis, starting from that chunk's carried adjoint.  Chunks are counted from the start of the sequence;
     // the last one takes whatever is left (see chunk_span in selective_bwd_carry.hip), and the workgroups of a packed
-    // sequence that ends before their chunk leave here, all threads together and before any barrier.
+    // sequence that ends before their chunk leave here, all threads together and before any barrier (chunk 0 stays
+    // even for an empty sequence: it writes that sequence's dx0).
     const int chunk = blockIdx.z;
     if (p.nchunks > 1) {
         const int64_t span = p.tiles_per_chunk * TILE;
         const int64_t left = L - chunk * span;
-        if (left <= 0) return;
+        if (chunk > 0 && left <= 0) return;
         toff += chunk * span;
         L = (chunk == p.nchunks - 1 || left < span) ? left : span;
     }

@@ -123,6 +123,7 @@ def test_packed_backward_in_chunks_variants(api, oracle):
     _check(api, oracle, 24, 16, (2100, 900, 40), "bf16", seed=52, G=3, gap=5, path="chunk_carry")
     _check(api, oracle, 16, 16, (700, 300, 1500), "bf16", seed=53, with_ckpt=False, path="chunk_carry", max_seqlen=1500)
     _check(api, oracle, 13, 4, (100, 2600, 257), "f32", seed=54, path="chunk_carry")
+    _check(api, oracle, 16, 16, (1030, 0, 77), "f32", seed=56, path="chunk_carry")      # an empty sequence: its dx0 is zero
     assert api.lib().lrnnx_selective_scan_bwd_chunks(2, 32, 16, 6000, 1, 0, 0) > 1
     _check(api, oracle, 32, 16, (6000, 5000), "bf16", seed=55, max_seqlen=6000, same_bits=False)
 

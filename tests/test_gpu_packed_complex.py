@@ -124,6 +124,7 @@ def test_packed_complex_backward_in_chunks(api, oracle, hint):
 def test_packed_complex_backward_in_chunks_variants(api, oracle):
     _check(api, oracle, 24, 8, (2100, 900, 40), "f32", seed=62, G=3, gap=5, path="chunk_carry")
     _check(api, oracle, 16, 16, (700, 300, 1500), "bf16", seed=63, with_ckpt=False, path="chunk_carry", max_seqlen=1500)
+    _check(api, oracle, 16, 16, (1030, 0, 77), "f32", seed=64, path="chunk_carry")      # an empty sequence: its dx0 is zero
 
 
 def test_packed_complex_boundaries_are_clamped(api):
