@@ -128,6 +128,17 @@ def test_packed_backward_in_chunks_variants(api, oracle):
     _check(api, oracle, 32, 16, (6000, 5000), "bf16", seed=55, max_seqlen=6000, same_bits=False)
 
 
+@pytest.mark.parametrize("lengths", [
+    (3000, 1500, 1000, 2048, 512, 512, 700, 324, 100, 100, 60, 40, 2200, 1800, 32, 8, 448, 900, 300, 300, 200, 100, 100, 100),
+    (2048,) * 8], ids=["24_mixed", "8x2048"])
+def test_packed_batches_of_the_benchmark_at_full_size(api, oracle, lengths):
+    """The two packed batches bench.py times (16384 steps on 1536 channels, N = 16, bf16; the backward call with
+    max_seqlen), every output against the oracle.  The second is config 2 itself as a packed batch: its launch takes
+    the shape of the batch [8,1536,2048]."""
+    assert sum(lengths) == 16384
+    _check(api, oracle, 1536, 16, lengths, "bf16", seed=71, max_seqlen=max(lengths))
+
+
 def test_packed_max_seqlen_is_validated(api):
     p = workloads.make_packed(D=8, N=16, lengths=(100, 200), io="f32", seed=11)
     import torch
