@@ -65,7 +65,7 @@ __device__ __forceinline__ void cdisc_ag(float dt, const CCoef &c, float2 &a, fl
         const float wr = 1.0f - hr, wi = -hi;                               // 1 - dt A / 2
         const float r = rcp_fast(wr * wr + wi * wi);
         const float ir = wr * r, ii = -wi * r;                              // 1 / (1 - dt A / 2)
-        a = make_float2((1.0f + hr) * ir - hi * ii, (1.0f + hr) * ii + hi * ir);
+        a = make_float2(__builtin_fmaf(2.0f, ir, -1.0f), 2.0f * ii);        // (1 + dt A / 2) / (1 - dt A / 2) = 2 / (1 - dt A / 2) - 1
         g = make_float2(dt * ir, dt * ii);
     } else {
         a = cexp_dt(dt, c.A2r, c.Arev);

@@ -107,9 +107,10 @@ __device__ __forceinline__ ACoef make_acoef(float A) {
 template <int DISC>
 __device__ __forceinline__ void disc_ag(float dt, const ACoef &c, float &a, float &g) {
     if constexpr (DISC == DISC_BILINEAR) {
-        const float h = dt * c.hA;
-        const float q = rcp_fast(1.0f - h);           // v_rcp_f32 is accurate to 1 ulp, like the exponential of the other schemes
-        a = (1.0f + h) * q;
+        // q = 1 / (1 - dt A / 2); a = (1 + dt A / 2) q = 2 q - 1.  v_rcp_f32 is accurate to 1 ulp, like the
+        // exponential of the other schemes
+        const float q = rcp_fast(__builtin_fmaf(-dt, c.hA, 1.0f));
+        a = __builtin_fmaf(2.0f, q, -1.0f);
         g = dt * q;
     } else {
         a = exp2_fast(dt * c.A2);
