@@ -197,8 +197,15 @@ def _bdl(t, name, io=None, shape=None, out=False):
         raise ValueError(f"{name}: expected [B,D,L] with contiguous time axis")
     if shape is not None and tuple(t.shape) != tuple(shape):
         raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
-    if out and (t.stride(1) < t.shape[2] or (t.shape[0] > 1 and t.stride(0) < t.shape[1] * t.shape[2])):
-        raise ValueError(f"{name}: output rows overlap")
+    if out:
+        # rows (b, d) of L elements at b * stride_b + d * stride_d: the axis with the smaller stride must step over a
+        # whole row, the other one over all rows of the first (either axis may be the inner one)
+        axes = sorted((t.stride(i), t.shape[i]) for i in (0, 1) if t.shape[i] > 1)
+        need = t.shape[2]
+        for stride, count in axes:
+            if stride < need:
+                raise ValueError(f"{name}: output rows overlap")
+            need = stride * count
     if io is not None and t.dtype != io:
         raise TypeError(f"{name}: dtype {t.dtype} differs from the I/O dtype {io}")
     return t.data_ptr(), t.stride(0), t.stride(1)

@@ -99,6 +99,12 @@ def test_strided_and_broadcast_inputs(api, oracle):
                                       delta_bias=p["delta_bias"], z=p["z"])
     assert rel_err(host(y), yr) <= 1e-4
     assert float(out[:, :, L:].abs().max()) == 0.0            # nothing written past the rows
+    # an output whose channel axis is the outer one in memory ([B,D,L] view of a [D,B,L] buffer): rows do not overlap
+    out2 = torch.zeros((D, B, L), device="cuda").transpose(0, 1)
+    y2 = api.lrnnx_selective_scan_fwd(**t, out=out2)
+    assert torch.equal(y2, y)
+    with pytest.raises(ValueError):                           # rows of different batch entries on top of each other
+        api.lrnnx_selective_scan_fwd(**t, out=torch.zeros((1, D, L), device="cuda").expand(B, D, L))
 
 
 def test_deterministic_and_chaining(api, oracle):
