@@ -104,6 +104,13 @@ def test_packed_one_long_sequence_with_max_seqlen(api, oracle, hint):
     _check(api, oracle, 1024, 16, lengths, "bf16", seed=41, max_seqlen=hint)
 
 
+def test_packed_one_long_sequence_with_max_seqlen_and_grouped_maps(api, oracle):
+    """The same batch with four groups of maps (256 channels each): the channel blocks of a workgroup stay within one
+    group whatever number of channels its sequence's length gives it."""
+    lengths = (20,) * 11 + (1500,) + (20,) * 21
+    _check(api, oracle, 1024, 16, lengths, "f32", seed=43, G=4, max_seqlen=1500)
+
+
 @pytest.mark.parametrize("io", ["f32", "bf16"])
 @pytest.mark.parametrize("hint", [None, 5000, 1000])
 def test_packed_backward_in_chunks(api, oracle, hint, io):
