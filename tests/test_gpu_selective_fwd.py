@@ -60,6 +60,16 @@ def test_state_sizes_multi_tile_ragged(api, oracle, io, N):
               bias=("uniform", -4.0, -2.0), check_ckpt=True)
 
 
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("N", [1, 2, 4, 8, 16, 32])
+def test_state_sizes_on_short_tiles(api, oracle, io, N):
+    """Row lengths the launch walks in 256-step tiles (four channels per workgroup): three tiles with a ragged tail,
+    and one tile not even half full; D not a multiple of four."""
+    _run_case(api, oracle, io, "zoh_s6", True, B=2, D=13, N=N, L=700, gate=True, with_x0=True, seed=60 + N,
+              bias=("uniform", -4.0, -2.0), check_ckpt=True)
+    _run_case(api, oracle, io, "zoh", True, B=3, D=6, N=N, L=100, gate=False, seed=80 + N, check_ckpt=True)
+
+
 @pytest.mark.parametrize("disc", ["zoh_s6", "zoh", "bilinear", "dirac"])
 @pytest.mark.parametrize("softplus", [True, False])
 def test_discretisations(api, oracle, disc, softplus):
