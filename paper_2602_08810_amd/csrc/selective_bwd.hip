@@ -129,6 +129,78 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
     const bool io_thread = NA == NT || tid < NA;                     // wave-uniform: NA is a multiple of 64
     auto fslot = [](int f) { return (((f % T) / 4) * 64 + f / T) * 4 + (f % 4); };
 
+    // ---- The dBm/dCm sums of a tile (over the workgroup's channels) are added to global memory one tile late: after
+    // the next tile's loads have been issued, so that those round trips run while the flush goes through LDS, and so
+    // that nothing has to wait for the atomics (the memory counter is in order: a load issued after them cannot be
+    // claimed before they are done, and all workgroups flush at about the same time).  The sums are transposed
+    // through LDS so that consecutive threads hit consecutive addresses: two rounds of 32 lanes each, in the area of
+    // the Bm columns (the tile they belonged to is finished, the next tile stages its own after the flush).
+    // `mid` runs after the first round's trip through LDS, before the first atomic.
+    float dBacc[NK][T], dCacc[NK][T];
+    int64_t fl_l0 = 0;                                               // first step of the tile the sums belong to
+    int fl_rem = 0;                                                  // its valid steps; 0: nothing to flush
+    auto flush = [&](auto &&mid) {
+        constexpr int FL = 32;                                           // lanes per round
+        float *fbB = sBt, *fbC = sBt + FL * T * N;
+        static_assert(2 * FL * T * N <= N * TILE, "flush buffer must fit in the Bm area");
+#pragma unroll
+        for (int j = 0; j < 64 / FL; ++j) {
+            __syncthreads();
+            // A lane's values of one step are NK consecutive floats of that step's row.  With NK = 4 they go out as one
+            // 16-byte write; lanes are T * N floats apart, which would put all of them on the same banks (measured:
+            // the 32-way conflicts of the plain layout made the flush 11 % of the kernel), so the 16-byte chunk index
+            // is XORed with the lane's low bits: eight consecutive lanes then cover all banks, and a reader's 64
+            // consecutive floats stay a permutation of whole chunks within the same 8-chunk block.
+            constexpr bool SWZ = NK == 4;
+            constexpr int CPL = T * N / 4;                               // 16-byte chunks per lane
+            if (lane / FL == j) {
+                // (the addresses are formed here and now: hoisted out of the tile loop they would sit in registers
+                // all through the channel loop, which has none to spare)
+                int lr = lane % FL;
+                asm volatile("" : "+v"(lr));
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    if constexpr (SWZ) {
+                        const int c4 = ((lr * T + t) * (N / 4) + w) ^ (lr & 7);
+                        *reinterpret_cast<float4 *>(&fbB[c4 * 4]) = make_float4(dBacc[0][t], dBacc[1][t], dBacc[2][t], dBacc[3][t]);
+                        *reinterpret_cast<float4 *>(&fbC[c4 * 4]) = make_float4(dCacc[0][t], dCacc[1][t], dCacc[2][t], dCacc[3][t]);
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < NK; ++k) {
+                            fbB[(lr * T + t) * N + w * NK + k] = dBacc[k][t];
+                            fbC[(lr * T + t) * N + w * NK + k] = dCacc[k][t];
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+            const int step0 = j * FL * T;                                // within the tile
+            float *gB = p.dBm + bc0 + (fl_l0 + step0) * N, *gC = p.dCm + bc0 + (fl_l0 + step0) * N;
+            // each thread's values are read from LDS in one batch, then added (one round trip instead of one per value)
+            constexpr int PER = FL * T * N / NT;                         // = T * NK / 2
+            static_assert(PER * NT == FL * T * N, "the flush buffer is a whole number of values per thread");
+            float vB[PER], vC[PER];
+            int tf = tid;
+            asm volatile("" : "+v"(tf));
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const int idx = tf + i * NT;
+                const int at = SWZ ? ((((idx >> 2) ^ (((idx >> 2) / CPL) & 7)) << 2) | (idx & 3)) : idx;
+                vB[i] = fbB[at]; vC[i] = fbC[at];
+            }
+            if (j == 0) mid();
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const int idx = tid + i * NT;
+                if (step0 + idx / N < fl_rem) {
+                    unsafeAtomicAdd(gB + (unsigned)idx, vB[i]);
+                    unsafeAtomicAdd(gC + (unsigned)idx, vC[i]);
+                }
+            }
+        }
+        __syncthreads();
+    };
+
     for (int64_t tile = ntiles - 1; tile >= 0; --tile) {
         const int64_t l0 = tile * TILE;
         const int rem = (L - l0 < TILE) ? (int)(L - l0) : TILE;      // valid steps of this tile
@@ -136,32 +208,17 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
         // they need one 32-bit register per lane instead of a 64-bit induction variable each
         const IO *BmT = Bm + l0 * N + w * NK, *CmT = Cm + l0 * N + w * NK;
 
-        // ---- this wavefront's NK columns of Bm/Cm for the tile, and zeroed dBm/dCm sums.  Cm and both sums stay in
-        // registers; the Bm columns go to this wavefront's own slice of LDS (read back as ds_read_b128 in each pass)
-        float Cv[NK][T], dBacc[NK][T], dCacc[NK][T];
-        {
-        float Bv[NK][T];
-        // every row is loaded without a branch (past the end of the tile the last valid row is read again and then
-        // discarded), so that all 2 T loads of a lane are in flight together instead of one round trip per step
+        // ---- this wavefront's NK columns of Bm/Cm for the tile: fetched here (raw), used after the flush of the
+        // tile before (below), so that the round trip runs while that flush goes through LDS.  Every row is loaded
+        // without a branch (past the end of the tile the last valid row is read again and then discarded), so that
+        // all 2 T loads of a lane are in flight together instead of one round trip per step.
+        RawFew<IO, NK> rB[T], rC[T];
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            float tb[NK], tc[NK];
             const int step = lane * T + t;
             const int row = step < rem ? step : rem - 1;                  // rem >= 1: a tile has at least one step
-            load_row<IO, NK>(BmT + (unsigned)(row * N), tb);
-            load_row<IO, NK>(CmT + (unsigned)(row * N), tc);
-#pragma unroll
-            for (int k = 0; k < NK; ++k) {
-                Bv[k][t] = step < rem ? tb[k] : 0.0f; Cv[k][t] = step < rem ? tc[k] : 0.0f;
-                dBacc[k][t] = 0.0f; dCacc[k][t] = 0.0f;
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < NK; ++k)
-#pragma unroll
-            for (int q = 0; q < TQ; ++q)
-                *reinterpret_cast<float4 *>(&sBt[(((w * NK + k) * TQ + q) * 64 + lane) * 4]) =
-                    make_float4(Bv[k][4 * q], Bv[k][4 * q + 1], Bv[k][4 * q + 2], Bv[k][4 * q + 3]);
+            load_few_raw<IO, NK>(BmT + (unsigned)(row * N), 0, NK, true, rB[t]);
+            load_few_raw<IO, NK>(CmT + (unsigned)(row * N), 0, NK, true, rC[t]);
         }
 
         // Per-channel inputs are fetched one channel ahead, so that their latency hides behind the main pass.  Every
@@ -226,7 +283,43 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
             asm volatile("" : "+v"(s.Dsk), "+v"(s.bias) : : "memory");
         };
         prefetch(S0);
-        settle(S0);
+        // The loads above are claimed before the first atomic of the flush is issued (the memory counter is in
+        // order and the atomics sit under a branch: a wait placed after them would wait for them as well), i.e. after
+        // the flush's first trip through LDS.
+        auto settle_tile = [&]() {
+            settle(S0);
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int i = 0; i < RawFew<IO, NK>::WORDS; ++i)
+                    asm volatile("" : "+v"(rB[t].w[i]), "+v"(rC[t].w[i]) : : "memory");
+        };
+        if (fl_rem > 0) flush(settle_tile);          // the sums of the tile before (later in time); same branch for the whole workgroup
+        settle_tile();
+        // Cm and both sums stay in registers; the Bm columns go to this wavefront's own slice of LDS (read back as
+        // ds_read_b128 in each pass)
+        float Cv[NK][T];
+        {
+        float Bv[NK][T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            float tb[NK], tc[NK];
+            unpack_few<IO, NK>(rB[t], tb);
+            unpack_few<IO, NK>(rC[t], tc);
+            const int step = lane * T + t;
+#pragma unroll
+            for (int k = 0; k < NK; ++k) {
+                Bv[k][t] = step < rem ? tb[k] : 0.0f; Cv[k][t] = step < rem ? tc[k] : 0.0f;
+                dBacc[k][t] = 0.0f; dCacc[k][t] = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < NK; ++k)
+#pragma unroll
+            for (int q = 0; q < TQ; ++q)
+                *reinterpret_cast<float4 *>(&sBt[(((w * NK + k) * TQ + q) * 64 + lane) * 4]) =
+                    make_float4(Bv[k][4 * q], Bv[k][4 * q + 1], Bv[k][4 * q + 2], Bv[k][4 * q + 3]);
+        }
 
         // Order of a channel's work between the workgroup's two barriers per channel.  After the first barrier (the
         // step inputs of channel g are in LDS): the main pass, which leaves the wavefronts' partial sums in LDS.
@@ -527,43 +620,9 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_bwd(const BwdParams p) 
             if constexpr (DZ) o_dz_row += p.dz_sd;
         };
         for (int g = 0; g < Gact; ++g) channel(g);
-        // ---- add this tile's dBm/dCm sums (over the G channels) to global memory, transposed through LDS so that
-        // consecutive threads hit consecutive addresses: two rounds of 32 lanes each, in the area of the Bm columns
-        // (not needed any more: the next tile stages its own)
-        constexpr int FL = 32;                                           // lanes per round
-        float *fbB = sBt, *fbC = sBt + FL * T * N;
-        static_assert(2 * FL * T * N <= N * TILE, "flush buffer must fit in the Bm area");
-        for (int j = 0; j < 64 / FL; ++j) {
-            __syncthreads();
-            if (lane / FL == j) {
-#pragma unroll
-                for (int t = 0; t < T; ++t)
-#pragma unroll
-                    for (int k = 0; k < NK; ++k) {
-                        fbB[((lane % FL) * T + t) * N + w * NK + k] = dBacc[k][t];
-                        fbC[((lane % FL) * T + t) * N + w * NK + k] = dCacc[k][t];
-                    }
-            }
-            __syncthreads();
-            const int step0 = j * FL * T;                                // within the tile
-            float *gB = p.dBm + bc0 + (l0 + step0) * N, *gC = p.dCm + bc0 + (l0 + step0) * N;
-            // each thread's values are read from LDS in one batch, then added (one round trip instead of one per value)
-            constexpr int PER = FL * T * N / NT;                         // = T * NK / 2
-            static_assert(PER * NT == FL * T * N, "the flush buffer is a whole number of values per thread");
-            float vB[PER], vC[PER];
-#pragma unroll
-            for (int i = 0; i < PER; ++i) { vB[i] = fbB[tid + i * NT]; vC[i] = fbC[tid + i * NT]; }
-#pragma unroll
-            for (int i = 0; i < PER; ++i) {
-                const int idx = tid + i * NT;
-                if (step0 + idx / N < rem) {
-                    unsafeAtomicAdd(gB + (unsigned)idx, vB[i]);
-                    unsafeAtomicAdd(gC + (unsigned)idx, vC[i]);
-                }
-            }
-        }
-        __syncthreads();
+        fl_l0 = l0; fl_rem = rem;                    // flushed while the next tile's maps are on their way
     }
+    if (fl_rem > 0) flush([]() {});
     // ---- per-channel results of this workgroup
     for (int i = tid; i < Gact * N; i += NT) {
         const int g = i / N, n = i % N;
