@@ -62,7 +62,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
     constexpr int NA = TILE / TPW;                   // threads that take part in them (all, or the first wavefronts)
     constexpr int TQ = T / 4;
     constexpr int CK_PER_TILE = TILE / (int)kCkptInterval;
-    constexpr int FL = 8;                            // lanes whose dBm/dCm sums are flushed together
+    constexpr int FL = 16;                           // lanes whose dBm/dCm sums are flushed together
     static_assert(T % 4 == 0 && (T % W == 0 || W % T == 0) && TPW <= 8 && NA % 64 == 0 && NA <= NT, "tile shape");
     static_assert(TILE % kCkptInterval == 0, "tiles must start on checkpoints");
     static_assert(TILE == kBwdTileSteps, "the chunked launch counts its chunks in tiles of this kernel");
@@ -458,27 +458,57 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
 
         // ---- add this tile's dBm/dCm sums (over the G channels) to global memory, transposed through LDS so that
         // consecutive threads hit consecutive addresses; FL lanes (FL * T time steps) at a time
+        // A lane's two states of a step are one 16-byte chunk of that step's row; lanes are T * N pairs apart, which
+        // would put all of them on the same banks, so the chunk index is XORed with the lane's low bits (eight
+        // consecutive lanes then cover all banks; a reader's consecutive floats stay a permutation of whole chunks
+        // within one 8-chunk block).  A thread reads all its values in one batch before it issues its atomics.
         float2 *fbB = reinterpret_cast<float2 *>(sPart), *fbC = fbB + FL * T * N;
+        constexpr int CPL = T * N / 2;                                   // 16-byte chunks per lane
+        constexpr bool SWZ = NK == 2 && CPL >= 8;
         for (int j = 0; j < 64 / FL; ++j) {
             __syncthreads();
             if (lane / FL == j) {
+                // (addresses formed here and now: hoisted out of the tile loop they would cost the channel loop registers)
+                int lr = lane % FL;
+                asm volatile("" : "+v"(lr));
 #pragma unroll
-                for (int t = 0; t < T; ++t)
+                for (int t = 0; t < T; ++t) {
+                    if constexpr (SWZ) {
+                        const int c4 = ((lr * T + t) * (N / 2) + w) ^ (lr & 7);
+                        *reinterpret_cast<float4 *>(&fbB[c4 * 2]) = make_float4(dBacc[0][t].x, dBacc[0][t].y, dBacc[1][t].x, dBacc[1][t].y);
+                        *reinterpret_cast<float4 *>(&fbC[c4 * 2]) = make_float4(dCacc[0][t].x, dCacc[0][t].y, dCacc[1][t].x, dCacc[1][t].y);
+                    } else {
 #pragma unroll
-                    for (int k = 0; k < NK; ++k) {
-                        fbB[((lane % FL) * T + t) * N + w * NK + k] = dBacc[k][t];
-                        fbC[((lane % FL) * T + t) * N + w * NK + k] = dCacc[k][t];
+                        for (int k = 0; k < NK; ++k) {
+                            fbB[(lr * T + t) * N + w * NK + k] = dBacc[k][t];
+                            fbC[(lr * T + t) * N + w * NK + k] = dCacc[k][t];
+                        }
                     }
+                }
             }
             __syncthreads();
             const int step0 = j * FL * T;                                // within the tile
             float *gB = reinterpret_cast<float *>(p.dBm + bc0 + (l0 + step0) * N);
             float *gC = reinterpret_cast<float *>(p.dCm + bc0 + (l0 + step0) * N);
             const float *lB = reinterpret_cast<const float *>(fbB), *lC = reinterpret_cast<const float *>(fbC);
-            for (int idx = tid; idx < FL * T * N * 2; idx += NT) {
-                if (step0 + idx / (2 * N) < rem) {
-                    unsafeAtomicAdd(gB + (unsigned)idx, lB[idx]);
-                    unsafeAtomicAdd(gC + (unsigned)idx, lC[idx]);
+            constexpr int TOTAL = FL * T * N * 2;                        // floats per array and round
+            constexpr int PER = (TOTAL + NT - 1) / NT;
+            float vB[PER], vC[PER];
+            int tf = tid;
+            asm volatile("" : "+v"(tf));
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const int idx = tf + i * NT;
+                const int at = SWZ ? ((((idx >> 2) ^ (((idx >> 2) / CPL) & 7)) << 2) | (idx & 3)) : idx;
+                const bool in = TOTAL % NT == 0 || idx < TOTAL;
+                vB[i] = in ? lB[at] : 0.0f; vC[i] = in ? lC[at] : 0.0f;
+            }
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const int idx = tf + i * NT;
+                if ((TOTAL % NT == 0 || idx < TOTAL) && step0 + idx / (2 * N) < rem) {
+                    unsafeAtomicAdd(gB + (unsigned)idx, vB[i]);
+                    unsafeAtomicAdd(gC + (unsigned)idx, vC[i]);
                 }
             }
         }
