@@ -70,7 +70,7 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
 
     __shared__ __attribute__((aligned(16))) float sIn[2][5 * TILE];       // two channels in flight: delta, u, dypre, d softplus, dz factor; [q][lane][4]
     __shared__ __attribute__((aligned(16))) float sPart[W * 3 * TILE];    // per wave: ypre, du, ddelta partials
-    // maps of the tile as fp32 pairs: [n][q][lane][4], wave-private slices (converted once per tile; every channel
+    // maps of the tile as fp32 pairs: [n][t/2][lane][t%2], wave-private slices (converted once per tile; every channel
     // of the workgroup then reads them five times)
     __shared__ __attribute__((aligned(16))) float2 sB[N * TILE];
     __shared__ __attribute__((aligned(16))) float2 sC[N * TILE];
@@ -175,8 +175,8 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
             for (int k = 0; k < NK; ++k)
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
-                    sB[(((w * NK + k) * TQ + t / 4) * 64 + lane) * 4 + (t % 4)] = cword<IO>::unpack(tb[t][k]);
-                    sC[(((w * NK + k) * TQ + t / 4) * 64 + lane) * 4 + (t % 4)] = cword<IO>::unpack(tc[t][k]);
+                    sB[(((w * NK + k) * (T / 2) + t / 2) * 64 + lane) * 2 + (t % 2)] = cword<IO>::unpack(tb[t][k]);
+                    sC[(((w * NK + k) * (T / 2) + t / 2) * 64 + lane) * 2 + (t % 2)] = cword<IO>::unpack(tc[t][k]);
                 }
         }
 
@@ -260,9 +260,12 @@ __global__ __launch_bounds__((N / NK) * 64, 2) void k_ss_cbwd(const CBwdParams p
                 const CCoef cc = make_ccoef(cA[k].x, cA[k].y);
                 const float2 xck = cck[k];
                 const float2 hc = sH[g * N + n];
-                const float2 *sBn = &sB[(n * TQ * 64 + lane) * 4], *sCn = &sC[(n * TQ * 64 + lane) * 4];
-                auto mapB = [&](int t) { return sBn[(t / 4) * 256 + (t % 4)]; };
-                auto mapC = [&](int t) { return sCn[(t / 4) * 256 + (t % 4)]; };
+                // [n][t/2][lane][t%2]: two steps of a lane are one 16-byte chunk and neighbouring lanes neighbouring
+                // chunks, so a ds_read_b128 touches every bank once (with the lane's four steps side by side, 32 bytes
+                // per lane, each such read hit half the banks twice: a quarter of this kernel's LDS cycles)
+                const float2 *sBn = &sB[(n * (T / 2) * 64 + lane) * 2], *sCn = &sC[(n * (T / 2) * 64 + lane) * 2];
+                auto mapB = [&](int t) { return sBn[(t / 2) * 128 + (t % 2)]; };
+                auto mapC = [&](int t) { return sCn[(t / 2) * 128 + (t % 2)]; };
 
                 // forward recompute of the states of this tile
                 float2 a[T + 1], gg[T], x[T];
