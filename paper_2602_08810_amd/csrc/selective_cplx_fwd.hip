@@ -105,8 +105,18 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
 
         // ---- this lane's T steps of u and Delta
         float uv[T], dl[T], yv[T];
-        load_seg<IO, T>(urow, ll, L, vec, uv);
-        load_seg<IO, T>(drow, ll, L, vec, dl);
+        // (with T = 4 a lane's bfloat16 steps are less than a 16-byte chunk: one 8-byte access)
+        auto load_steps = [&](const IO *r, float *out) {
+            if constexpr (T % io_traits<IO>::EPC == 0) {
+                load_seg<IO, T>(r, ll, L, vec, out);
+            } else {
+                RawFew<IO, T> raw;
+                load_few_raw<IO, T>(r, ll, L, vec, raw);
+                unpack_few<IO, T>(raw, out);
+            }
+        };
+        load_steps(urow, uv);
+        load_steps(drow, dl);
         float sum_dl = 0.0f;
 #pragma unroll
         for (int t = 0; t < T; ++t) {
@@ -169,11 +179,12 @@ __global__ __launch_bounds__(W * 64, 2) void k_ss_cfwd(const CFwdParams p) {
         if (!want_y) continue;
         if (zrow) {
             float zv[T];
-            load_seg<IO, T>(zrow, ll, L, vec, zv);
+            load_steps(zrow, zv);
 #pragma unroll
             for (int t = 0; t < T; ++t) yv[t] *= zv[t] * sigmoid_fast(zv[t]);
         }
-        store_seg<IO, T>(yrow, ll, L, vec, yv);
+        if constexpr (T % io_traits<IO>::EPC == 0) store_seg<IO, T>(yrow, ll, L, vec, yv);
+        else store_few<IO, T>(yrow, ll, L, vec, yv);
     }
 
     if constexpr (AGG) {
@@ -206,8 +217,24 @@ __global__ void k_ss_ccarry(const CFwdParams p) {
 }
 
 // ---------------------------------------------------------------- launchers
+// Short tiles (4 steps per lane, 4 channels per workgroup: tiles of 256 steps) for the single pass over short rows,
+// by the rule of the real forward pass (selective_fwd.hip): a tile is walked whole, so the smaller one pays when it
+// wastes enough fewer steps to make up for its higher cost per step.
+static bool cfwd_short_tiles(const CFwdParams &p) {
+    if (p.nchunks != 1 || p.mode != MODE_FULL) return false;
+    if (p.cu) return p.L < (int64_t)360 * p.B;
+    const int64_t walked8 = (p.L + 511) / 512 * 512, walked4 = (p.L + 255) / 256 * 256;
+    return walked4 * 125 < walked8 * 100;
+}
+
 template <typename IO, int N, int DISC>
 static hipError_t launch_cfwd_n(const CFwdParams &p, hipStream_t s) {
+    if (cfwd_short_tiles(p)) {
+        constexpr int W = 4, T = 4;
+        dim3 grid(p.bcg * ((p.dpg + W - 1) / W), p.B, 1);
+        hipLaunchKernelGGL((k_ss_cfwd<IO, N, T, W, DISC, false>), grid, dim3(W * 64), 0, s, p);
+        return hipGetLastError();
+    }
     constexpr int W = 8, T = 8;
     // the aggregate launch skips the last chunk: nobody needs its pair
     dim3 grid(p.bcg * ((p.dpg + W - 1) / W), p.B, p.nchunks > 1 ? (p.mode == MODE_AGG ? p.nchunks - 1 : p.nchunks) : 1);

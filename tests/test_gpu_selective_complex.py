@@ -63,6 +63,15 @@ def test_shapes(api, oracle, io, B, D, N, L):
     _run(api, oracle, B, D, N, L, io, "zoh_s6", gate=bool(L % 2), x0=bool(D % 2), seed=B + D + N + L)
 
 
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("N", [1, 2, 4, 8, 16])
+def test_state_sizes_on_short_tiles(api, oracle, io, N):
+    """Row lengths the launch walks in 256-step tiles (four channels per workgroup): three tiles with a ragged tail,
+    and one tile not even half full; D not a multiple of four."""
+    _run(api, oracle, 2, 13, N, 700, io, "zoh_s6", gate=True, x0=True, seed=70 + N)
+    _run(api, oracle, 3, 6, N, 100, io, "bilinear", gate=False, x0=False, seed=90 + N)
+
+
 def test_caller_supplied_step_sizes(api, oracle):
     _run(api, oracle, 2, 6, 16, 700, "f32", "zoh", gate=False, x0=True, seed=5, softplus=False)
 
