@@ -146,6 +146,29 @@ def test_packed_batches_of_the_benchmark_at_full_size(api, oracle, lengths):
     _check(api, oracle, 1536, 16, lengths, "bf16", seed=71, max_seqlen=max(lengths))
 
 
+def test_packed_backward_in_chunks_with_a_small_workspace(api, oracle):
+    """A workspace with room for fewer chunks than planned: the call cuts the sequences into fewer, longer chunks
+    (same results); with room for less than two chunks an explicit request is refused."""
+    import torch
+    lengths = (3000, 700, 5000, 10)
+    B, D, N = len(lengths), 16, 16
+    nch = api.lib().lrnnx_selective_scan_bwd_chunks(B, D, N, 5000, 1, 2, 0)
+    assert nch >= 4
+    per_chunk = 2 * B * D * N * 4
+    p = workloads.make_packed(D=D, N=N, lengths=lengths, io="f32", seed=57)
+    cu = torch.from_numpy(p["cu_seqlens"]).cuda()
+    t = dict(u=dev(p["u"]), delta=dev(p["delta"]), A=dev(p["A"]), Bm=dev(p["Bm"]), Cm=dev(p["Cm"]),
+             Dskip=dev(p["Dskip"]), delta_bias=dev(p["delta_bias"]), z=dev(p["z"]), x0=dev(p["x0"]))
+    _, ckpt = api.lrnnx_selective_scan_fwd(**t, cu_seqlens=cu, return_ckpt=True)
+    kw = dict(dy=dev(p["dy"]), cu_seqlens=cu, want_dx0=True, ckpt=ckpt, path="chunk_carry", max_seqlen=5000)
+    full = api.lrnnx_selective_scan_bwd(**t, **kw)
+    small = api.lrnnx_selective_scan_bwd(**t, **kw, workspace=torch.empty(per_chunk * 2 + 100, dtype=torch.uint8, device="cuda"))
+    for k in ("du", "ddelta", "dz", "dA", "dBm", "dCm", "dD", "dbias", "dx0"):
+        assert rel_err(host(small[k]), host(full[k])) <= 1e-5, k
+    with pytest.raises(api.LrnnxError):
+        api.lrnnx_selective_scan_bwd(**t, **kw, workspace=torch.empty(per_chunk + 100, dtype=torch.uint8, device="cuda"))
+
+
 def test_packed_max_seqlen_is_validated(api):
     p = workloads.make_packed(D=8, N=16, lengths=(100, 200), io="f32", seed=11)
     import torch
