@@ -264,10 +264,19 @@ def main():
     print(json.dumps(result))
 
 
-def _time(torch, fn, reps, warm=3):
+def _time(torch, fn, reps, warm=3, warm_ms=25.0):
+    """Average time of one call of fn over `reps` calls, after `warm` untimed calls and at least `warm_ms` of untimed
+    work (a timing loop of a millisecond or two right after the host prepared inputs would otherwise be measured
+    while the GPU's clocks are still coming up: 10 % slower on the shapes of this file)."""
+    import time
     for _ in range(warm):
         fn()
     torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < warm_ms:
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
